@@ -1,0 +1,231 @@
+"""fp64 CPU oracle for the PolarQuant hot path -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper around ``pq_oracle.c`` (plain C, double precision).  Only
+tests, ``__graft_entry__.smoke()`` and ``bench.py``'s ``cpu_baseline`` leg may
+import this package.  It shares no code with the HIP library and never
+imports it.
+
+All array arguments are numpy arrays; inputs are widened to float64 by the
+caller (bf16/fp32 widen exactly).
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pq_oracle.c")
+_LIB = os.path.join(_HERE, "libpq_oracle.so")
+
+D = 128
+NANG = 120
+NBLK = 8
+REC = 62
+CB_LEN = 28
+CB_OFF = {1: 0, 2: 16, 3: 20, 4: 24}
+CB_K = {1: 16, 2: 4, 3: 4, 4: 4}
+
+
+def build(force=False):
+    """Compile the oracle with gcc -O2 (OpenMP over independent units)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        c_dp = ctypes.POINTER(ctypes.c_double)
+        L.orc_angle_pdf.restype = ctypes.c_double
+        L.orc_angle_pdf.argtypes = [ctypes.c_int, ctypes.c_double]
+        L.orc_codebook_distortion.restype = ctypes.c_double
+        L.orc_codebook_distortion.argtypes = [ctypes.c_int, ctypes.c_int, c_dp]
+        L.orc_f64_to_f16.restype = ctypes.c_uint16
+        L.orc_f64_to_f16.argtypes = [ctypes.c_double]
+        L.orc_f16_to_f64.restype = ctypes.c_double
+        L.orc_f16_to_f64.argtypes = [ctypes.c_uint16]
+        L.orc_quant.restype = ctypes.c_int
+        L.orc_quant.argtypes = [ctypes.c_double, c_dp, ctypes.c_int]
+        L.orc_num_threads.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a, ty=ctypes.c_double):
+    return a.ctypes.data_as(ctypes.POINTER(ty))
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def num_threads():
+    return int(lib().orc_num_threads())
+
+
+def gaussian_matrix(seed, d=D):
+    G = np.empty((d, d), dtype=np.float64)
+    lib().orc_gaussian_matrix(ctypes.c_uint64(seed), ctypes.c_int(d), _p(G))
+    return G
+
+
+def rotation_from_gaussian(G):
+    G = _f64(G)
+    d = G.shape[0]
+    S = np.empty((d, d), dtype=np.float64)
+    rc = lib().orc_rotation_from_gaussian(_p(G), ctypes.c_int(d), _p(S))
+    assert rc == 0
+    return S
+
+
+def preconditioner(seed, d=D):
+    """S of Section 4.1: rotation from the QR of the seeded Gaussian matrix."""
+    return rotation_from_gaussian(gaussian_matrix(seed, d))
+
+
+def angle_pdf(level, psi):
+    return float(lib().orc_angle_pdf(int(level), float(psi)))
+
+
+def codebook(level, K):
+    c = np.empty(K, dtype=np.float64)
+    b = np.empty(K + 1, dtype=np.float64)
+    rc = lib().orc_codebook(ctypes.c_int(level), ctypes.c_int(K), _p(c), _p(b))
+    assert rc == 0
+    return c, b
+
+
+def codebook_distortion(level, centroids):
+    c = _f64(centroids)
+    return float(lib().orc_codebook_distortion(int(level), int(c.size), _p(c)))
+
+
+def default_codebooks():
+    cb = np.empty(CB_LEN, dtype=np.float64)
+    rc = lib().orc_default_codebooks(_p(cb))
+    assert rc == 0
+    return cb
+
+
+def polar(y, L):
+    y = _f64(y)
+    d = y.size
+    nang = sum(d >> l for l in range(1, L + 1))
+    psi = np.empty(nang, dtype=np.float64)
+    r = np.empty(d >> L, dtype=np.float64)
+    lib().orc_polar(_p(y), ctypes.c_int(d), ctypes.c_int(L), _p(psi), _p(r))
+    return psi, r
+
+
+def polar_inverse(psi, r, d, L):
+    psi = _f64(psi)
+    r = _f64(r)
+    y = np.empty(d, dtype=np.float64)
+    lib().orc_polar_inverse(_p(psi), _p(r), ctypes.c_int(d), ctypes.c_int(L), _p(y))
+    return y
+
+
+def quant(psi, theta):
+    theta = _f64(theta)
+    return int(lib().orc_quant(float(psi), _p(theta), int(theta.size)))
+
+
+def f64_to_f16(x):
+    return int(lib().orc_f64_to_f16(float(x)))
+
+
+def f16_to_f64(h):
+    return float(lib().orc_f16_to_f64(int(h)))
+
+
+def pack(J, rad):
+    J = np.ascontiguousarray(J, dtype=np.int32)
+    rad = np.ascontiguousarray(rad, dtype=np.uint16)
+    n = J.shape[0]
+    rec = np.empty((n, REC), dtype=np.uint8)
+    lib().orc_pack(_p(J, ctypes.c_int32), _p(rad, ctypes.c_uint16), ctypes.c_int64(n), _p(rec, ctypes.c_uint8))
+    return rec
+
+
+def unpack(rec):
+    rec = np.ascontiguousarray(rec, dtype=np.uint8)
+    n = rec.shape[0]
+    J = np.empty((n, NANG), dtype=np.int32)
+    rad = np.empty((n, NBLK), dtype=np.uint16)
+    lib().orc_unpack(_p(rec, ctypes.c_uint8), ctypes.c_int64(n), _p(J, ctypes.c_int32), _p(rad, ctypes.c_uint16))
+    return J, rad
+
+
+def encode(x, S, cb, want_psi=False, want_y=False):
+    """x[n,128] -> canonical records [n,62] (+ exact angles / rotated vectors)."""
+    x = _f64(x).reshape(-1, D)
+    S = _f64(S)
+    cb = _f64(cb)
+    n = x.shape[0]
+    rec = np.empty((n, REC), dtype=np.uint8)
+    psi = np.empty((n, NANG), dtype=np.float64) if want_psi else None
+    y = np.empty((n, D), dtype=np.float64) if want_y else None
+    lib().orc_encode(
+        _p(x), ctypes.c_int64(n), _p(S), _p(cb), _p(rec, ctypes.c_uint8),
+        _p(psi) if want_psi else None, _p(y) if want_y else None,
+    )
+    out = [rec]
+    if want_psi:
+        out.append(psi)
+    if want_y:
+        out.append(y)
+    return out[0] if len(out) == 1 else tuple(out)
+
+
+def decode(rec, S, cb, rotated=False):
+    rec = np.ascontiguousarray(rec, dtype=np.uint8).reshape(-1, REC)
+    S = _f64(S)
+    cb = _f64(cb)
+    n = rec.shape[0]
+    out = np.empty((n, D), dtype=np.float64)
+    lib().orc_decode(_p(rec, ctypes.c_uint8), ctypes.c_int64(n), _p(S), _p(cb), ctypes.c_int(1 if rotated else 0), _p(out))
+    return out
+
+
+def attention(q, k_rec, v_rec, seq_start, ctx_len, S, cb, scale, rotated=False):
+    """q[B,Hq,128]; k_rec/v_rec [Hkv, plane_tokens, 62] -> out[B,Hq,128] (float64)."""
+    q = _f64(q)
+    B, Hq, _ = q.shape
+    k_rec = np.ascontiguousarray(k_rec, dtype=np.uint8)
+    v_rec = np.ascontiguousarray(v_rec, dtype=np.uint8)
+    Hkv, plane, _ = k_rec.shape
+    assert v_rec.shape == k_rec.shape and Hq % Hkv == 0
+    seq_start = np.ascontiguousarray(seq_start, dtype=np.int64)
+    ctx_len = np.ascontiguousarray(ctx_len, dtype=np.int32)
+    assert seq_start.size == B and ctx_len.size == B
+    assert np.all(seq_start + ctx_len <= plane)
+    S = _f64(S)
+    cb = _f64(cb)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lib().orc_attention(
+        _p(q), ctypes.c_int(B), ctypes.c_int(Hq), ctypes.c_int(Hkv),
+        _p(k_rec, ctypes.c_uint8), _p(v_rec, ctypes.c_uint8),
+        _p(seq_start, ctypes.c_int64), _p(ctx_len, ctypes.c_int32),
+        ctypes.c_int64(plane), _p(S), _p(cb), ctypes.c_double(scale),
+        ctypes.c_int(1 if rotated else 0), _p(out),
+    )
+    return out
+
+
+def attention_exact(q, K, V, scale):
+    """Plain softmax attention on unquantised K,V[T,128] for q[G,128] (reporting only)."""
+    q = _f64(q).reshape(-1, D)
+    K = _f64(K)
+    V = _f64(V)
+    out = np.empty_like(q)
+    lib().orc_attention_exact(_p(q), _p(K), _p(V), ctypes.c_int64(K.shape[0]), ctypes.c_int(q.shape[0]), ctypes.c_double(scale), _p(out))
+    return out

@@ -1,0 +1,471 @@
+"""Pins of the fp64 oracle against what the paper and the mathematics fix.
+
+Nothing here touches the GPU library.  Every check compares the oracle with
+something other than itself: a closed form, an invariant, a library routine
+used on a special case, a brute force on tiny inputs, or a hand-built fixture.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.integrate
+import scipy.special
+import scipy.stats
+
+import oracle
+from paper_2502_02617_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def S():
+    return oracle.preconditioner(0)
+
+
+@pytest.fixture(scope="module")
+def cb():
+    return oracle.default_codebooks()
+
+
+@pytest.fixture(scope="module")
+def X0():
+    # config 0: 1024 vectors, d=128, fp32 N(0,1), seed 0
+    return synth.gaussian_vectors(1024, seed=0).numpy().astype(np.float64)
+
+
+# ----------------------------------------------------------------------------
+# Preconditioner (Section 3.2 footnote: P^T P = I)
+# ----------------------------------------------------------------------------
+def test_S_is_orthogonal(S):
+    assert np.linalg.norm(S.T @ S - np.eye(128)) <= 1e-12
+    assert np.linalg.norm(S @ S.T - np.eye(128)) <= 1e-12
+    assert abs(abs(np.linalg.det(S)) - 1.0) <= 1e-10
+
+
+def test_S_matches_lapack_qr():
+    # QR with positive diagonal of R is unique: LAPACK's factor, sign-fixed, must agree.
+    G = oracle.gaussian_matrix(5)
+    S = oracle.rotation_from_gaussian(G)
+    Q, R = np.linalg.qr(G)
+    Qs = Q * np.sign(np.diag(R))[None, :]
+    assert np.max(np.abs(S - Qs)) <= 1e-11
+    # S^T G is upper triangular with positive diagonal
+    Rm = S.T @ G
+    assert np.max(np.abs(np.tril(Rm, -1))) <= 1e-11
+    assert np.all(np.diag(Rm) > 0)
+
+
+def test_S_preserves_inner_products(S):
+    rng = np.random.default_rng(1)
+    a, b = rng.standard_normal((2, 128))
+    assert abs((a @ S) @ (b @ S) - a @ b) <= 1e-12 * 128
+    assert abs(np.linalg.norm(a @ S) - np.linalg.norm(a)) <= 1e-12
+
+
+def test_gaussian_matrix_is_standard_normal():
+    G = oracle.gaussian_matrix(0)
+    assert G.shape == (128, 128)
+    # KS against N(0,1): 16384 samples
+    d, p = scipy.stats.kstest(G.ravel(), "norm")
+    assert p > 1e-3, (d, p)
+    assert not np.array_equal(G, oracle.gaussian_matrix(1))
+    assert np.array_equal(G, oracle.gaussian_matrix(0))
+
+
+# ----------------------------------------------------------------------------
+# Polar transform (Definition 1, Algorithm 1 procedure Polar)
+# ----------------------------------------------------------------------------
+def test_polar_d2_is_textbook():
+    for a, b in [(3.0, 4.0), (-1.0, 2.0), (-2.0, -0.5), (0.7, -0.1), (1.0, 0.0), (0.0, 0.0)]:
+        psi, r = oracle.polar([a, b], 1)
+        assert abs(r[0] - math.hypot(a, b)) <= 1e-15
+        ref = math.atan2(b, a) % (2 * math.pi)
+        assert abs(psi[0] - ref) <= 1e-15
+        assert 0.0 <= psi[0] < 2 * math.pi + 1e-15
+
+
+def test_polar_round_trip_exact(S, X0):
+    # quantisation disabled: x -> xS -> Polar -> inverse -> S^T
+    Y = X0[:64] @ S
+    for y in Y:
+        psi, r = oracle.polar(y, 4)
+        assert psi.size == 120 and r.size == 8
+        y2 = oracle.polar_inverse(psi, r, 128, 4)
+        assert np.max(np.abs(y2 - y)) <= 1e-12
+        x2 = y2 @ S.T
+        assert np.max(np.abs(x2 - y @ S.T)) <= 1e-12
+    # full depth too (Definition 1: log2 d levels, one radius)
+    psi, r = oracle.polar(Y[0], 7)
+    assert psi.size == 127 and r.size == 1
+    assert abs(r[0] - np.linalg.norm(Y[0])) <= 1e-12
+    assert np.max(np.abs(oracle.polar_inverse(psi, r, 128, 7) - Y[0])) <= 1e-12
+
+
+def test_final_radius_is_block_norm(S, X0):
+    Y = X0[:64] @ S
+    for y in Y:
+        _, r = oracle.polar(y, 4)
+        ref = np.linalg.norm(y.reshape(8, 16), axis=1)
+        assert np.max(np.abs(r - ref)) <= 1e-12
+
+
+def test_angle_ranges_and_definition(S, X0):
+    y = (X0[:1] @ S)[0]
+    psi, _ = oracle.polar(y, 4)
+    l1, l2, l3, l4 = psi[:64], psi[64:96], psi[96:112], psi[112:120]
+    assert np.all((l1 >= 0) & (l1 < 2 * np.pi))
+    for lv in (l2, l3, l4):
+        assert np.all((lv >= 0) & (lv <= np.pi / 2))
+    # Definition 1, level l >= 2: tan psi = norm of the upper half / norm of the lower half
+    for lev, ang in ((2, l2), (3, l3), (4, l4)):
+        w = 2 ** lev
+        seg = y.reshape(-1, w)
+        lo = np.linalg.norm(seg[:, : w // 2], axis=1)
+        hi = np.linalg.norm(seg[:, w // 2 :], axis=1)
+        assert np.max(np.abs(np.arctan2(hi, lo) - ang)) <= 1e-13
+    assert np.max(np.abs(np.mod(np.arctan2(y[1::2], y[0::2]), 2 * np.pi) - l1)) <= 1e-13
+
+
+def test_inverse_matches_closed_product_form(S, X0):
+    # Definition 1's reverse map, 0-based: x_i = r * prod_l (cos if (i mod 2^l) < 2^(l-1) else sin)(psi^(l)_{i >> l})
+    y = (X0[3:4] @ S)[0]
+    psi, r = oracle.polar(y, 4)
+    off = {1: 0, 2: 64, 3: 96, 4: 112}
+    for i in range(128):
+        v = r[i >> 4]
+        for l in range(1, 5):
+            a = psi[off[l] + (i >> l)]
+            v *= math.cos(a) if (i % (1 << l)) < (1 << (l - 1)) else math.sin(a)
+        assert abs(v - y[i]) <= 1e-12
+
+
+# ----------------------------------------------------------------------------
+# Angle densities (Lemma 2)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("level", [2, 3, 4, 5])
+def test_pdf_normalised_symmetric(level):
+    f = lambda t: oracle.angle_pdf(level, t)
+    total, _ = scipy.integrate.quad(f, 0, np.pi / 2, epsabs=1e-13, epsrel=1e-13)
+    assert abs(total - 1.0) <= 1e-11
+    for t in (0.1, 0.3, 0.7):
+        assert abs(f(t) - f(np.pi / 2 - t)) <= 1e-13
+    mean, _ = scipy.integrate.quad(lambda t: t * f(t), 0, np.pi / 2, epsabs=1e-13, epsrel=1e-13)
+    assert abs(mean - np.pi / 4) <= 1e-11
+    # the printed constant: Gamma(2^(l-1)) / (2^(2^(l-1)-2) Gamma(2^(l-2))^2) at psi = pi/4
+    n = 2 ** (level - 1)
+    const = math.gamma(n) / (2 ** (n - 2) * math.gamma(n / 2) ** 2)
+    assert abs(f(np.pi / 4) - const) <= 1e-12 * const
+
+
+def test_empirical_angles_follow_lemma2(S, X0):
+    # Gaussian vectors, rotated: level 1 uniform on [0, 2pi); level l >= 2 has
+    # sin^2(psi) ~ Beta(2^(l-2), 2^(l-2)), i.e. CDF = regularised incomplete beta.
+    Y = X0 @ S
+    psi = np.stack([oracle.polar(y, 4)[0] for y in Y])
+    lv = {1: psi[:, :64].ravel(), 2: psi[:, 64:96].ravel(), 3: psi[:, 96:112].ravel(), 4: psi[:, 112:].ravel()}
+    assert lv[1].size == 65536 and lv[4].size == 8192
+    d, p = scipy.stats.kstest(lv[1], lambda t: t / (2 * np.pi))
+    assert p > 1e-3, ("level 1", d, p)
+    for l in (2, 3, 4):
+        a = 2.0 ** (l - 2)
+        d, p = scipy.stats.kstest(lv[l], lambda t: scipy.special.betainc(a, a, np.sin(t) ** 2))
+        assert p > 1e-3, (l, d, p)
+    # the oracle's pdf integrates to that same CDF
+    for l in (2, 3, 4):
+        a = 2.0 ** (l - 2)
+        for t in (0.4, 0.9, 1.3):
+            F, _ = scipy.integrate.quad(lambda u: oracle.angle_pdf(l, u), 0, t, epsabs=1e-13)
+            assert abs(F - scipy.special.betainc(a, a, math.sin(t) ** 2)) <= 1e-10
+
+
+# ----------------------------------------------------------------------------
+# Codebooks (Eq. 3)
+# ----------------------------------------------------------------------------
+def test_level1_codebook_closed_form():
+    c, b = oracle.codebook(1, 16)
+    assert np.max(np.abs(c - (np.arange(16) + 0.5) * np.pi / 8)) <= 1e-15
+    assert np.max(np.abs(b - np.arange(17) * np.pi / 8)) <= 1e-15
+    # distortion of a uniform density on bins of width pi/8
+    assert abs(oracle.codebook_distortion(1, c) - (np.pi / 8) ** 2 / 12) <= 1e-12
+
+
+@pytest.mark.parametrize("level", [2, 3, 4])
+def test_lloyd_max_fixed_point(level):
+    c, b = oracle.codebook(level, 4)
+    assert b[0] == 0.0 and abs(b[4] - np.pi / 2) <= 1e-15
+    # symmetry of the density about pi/4
+    assert np.max(np.abs(c + c[::-1] - np.pi / 2)) <= 1e-12
+    assert abs(b[2] - np.pi / 4) <= 1e-12
+    # midpoint condition
+    assert np.max(np.abs(b[1:4] - 0.5 * (c[:-1] + c[1:]))) <= 1e-14
+    # centroid condition with an independent adaptive quadrature and the beta form of the density
+    a = 2.0 ** (level - 2)
+    m = 2 ** (level - 1) - 1
+    pdf = lambda t: math.sin(2 * t) ** m
+    for k in range(4):
+        num, _ = scipy.integrate.quad(lambda t: t * pdf(t), b[k], b[k + 1], epsabs=1e-14, epsrel=1e-14)
+        den, _ = scipy.integrate.quad(pdf, b[k], b[k + 1], epsabs=1e-14, epsrel=1e-14)
+        assert abs(num / den - c[k]) <= 1e-11
+    # bin probabilities from the closed-form CDF sum to one and are symmetric
+    F = scipy.special.betainc(a, a, np.sin(b) ** 2)
+    pr = np.diff(F)
+    assert abs(pr.sum() - 1.0) <= 1e-12 and abs(pr[0] - pr[3]) <= 1e-11 and abs(pr[1] - pr[2]) <= 1e-11
+
+
+@pytest.mark.parametrize("level", [2, 3, 4])
+def test_codebook_is_a_local_minimum_of_eq3(level):
+    c, _ = oracle.codebook(level, 4)
+    base = oracle.codebook_distortion(level, c)
+    # independent evaluation of Eq. 3 for the same centroids
+    m = 2 ** (level - 1) - 1
+    norm, _ = scipy.integrate.quad(lambda t: math.sin(2 * t) ** m, 0, np.pi / 2)
+    edges = np.concatenate([[0.0], 0.5 * (c[:-1] + c[1:]), [np.pi / 2]])
+    ref = sum(
+        scipy.integrate.quad(lambda t, k=k: (t - c[k]) ** 2 * math.sin(2 * t) ** m / norm, edges[k], edges[k + 1], epsabs=1e-14)[0]
+        for k in range(4)
+    )
+    assert abs(base - ref) <= 1e-11
+    rng = np.random.default_rng(level)
+    for _ in range(20):
+        c2 = np.sort(c + 1e-3 * rng.standard_normal(4))
+        assert oracle.codebook_distortion(level, c2) > base
+    # and far better than a uniform grid on [0, pi/2]
+    assert base < oracle.codebook_distortion(level, (np.arange(4) + 0.5) * np.pi / 8)
+
+
+def test_codebook_regression_values():
+    # values derived independently during the survey of the paper (Lloyd-Max of Lemma 2's densities)
+    rows = np.loadtxt(os.path.join(GOLDEN, "codebook_lloyd_max.txt"))
+    for row in rows:
+        level = int(row[0])
+        c, _ = oracle.codebook(level, 4)
+        assert np.max(np.abs(c - row[1:5])) <= 2e-9
+        assert abs(oracle.codebook_distortion(level, c) - row[5]) <= 2e-7
+
+
+def test_sampled_kmeans_converges_to_codebook():
+    # the paper's own recipe: 1-D k-means on sampled angles approaches the same centroids
+    rng = np.random.default_rng(7)
+    for level in (2, 3, 4):
+        a = 2.0 ** (level - 2)
+        t = np.arcsin(np.sqrt(rng.beta(a, a, size=400000)))
+        c, _ = oracle.codebook(level, 4)
+        km = (np.arange(4) + 0.5) * np.pi / 8
+        for _ in range(200):
+            edges = 0.5 * (km[:-1] + km[1:])
+            idx = np.searchsorted(edges, t)
+            km = np.array([t[idx == k].mean() for k in range(4)])
+        assert np.max(np.abs(km - c)) <= 4e-3
+
+
+# ----------------------------------------------------------------------------
+# Quant (nearest centroid)
+# ----------------------------------------------------------------------------
+def test_quant_is_brute_force_nearest(cb):
+    rng = np.random.default_rng(3)
+    for level in (1, 2, 3, 4):
+        K = oracle.CB_K[level]
+        theta = cb[oracle.CB_OFF[level] : oracle.CB_OFF[level] + K]
+        hi = 2 * np.pi if level == 1 else np.pi / 2
+        for psi in np.concatenate([rng.uniform(0, hi, 500), [0.0, hi]]):
+            assert oracle.quant(psi, theta) == int(np.argmin(np.abs(theta - psi)))
+    # ties go to the lower index
+    assert oracle.quant(1.0, np.array([0.5, 1.5])) == 0
+
+
+def test_quant_equals_interval_lookup(cb):
+    # Eq. 3's partition: the intervals between midpoints are the nearest-centroid cells
+    for level in (1, 2, 3, 4):
+        K = oracle.CB_K[level]
+        theta, bnd = oracle.codebook(level, K)
+        hi = 2 * np.pi if level == 1 else np.pi / 2
+        grid = np.linspace(0, hi, 20001)[1:-1]
+        grid = grid[np.min(np.abs(grid[:, None] - bnd[None, 1:-1]), axis=1) > 1e-9]
+        ref = np.searchsorted(bnd[1:-1], grid)
+        got = np.array([oracle.quant(t, theta) for t in grid])
+        assert np.array_equal(ref, got)
+
+
+def test_code_frequencies_match_bin_probabilities(S, cb, X0):
+    rec = oracle.encode(X0, S, cb)
+    J, _ = oracle.unpack(rec)
+    spans = {1: (0, 64), 2: (64, 96), 3: (96, 112), 4: (112, 120)}
+    for level, (a0, a1) in spans.items():
+        K = oracle.CB_K[level]
+        codes = J[:, a0:a1].ravel()
+        n = codes.size
+        freq = np.bincount(codes, minlength=K) / n
+        if level == 1:
+            prob = np.full(16, 1 / 16)
+        else:
+            _, bnd = oracle.codebook(level, 4)
+            a = 2.0 ** (level - 2)
+            prob = np.diff(scipy.special.betainc(a, a, np.sin(bnd) ** 2))
+        sigma = np.sqrt(prob * (1 - prob) / n)
+        assert np.all(np.abs(freq - prob) <= 4.5 * sigma), (level, freq, prob)
+
+
+# ----------------------------------------------------------------------------
+# binary16 conversion
+# ----------------------------------------------------------------------------
+def test_f16_conversion_matches_numpy():
+    rng = np.random.default_rng(11)
+    vals = np.concatenate([
+        rng.standard_normal(2000) * 10.0 ** rng.uniform(-8, 5, 2000),
+        [0.0, 1.0, 65504.0, 65519.9, 65520.0, 1e6, 2.0 ** -14, 2.0 ** -24, 2.0 ** -25, 1.5 * 2.0 ** -24,
+         2.0 ** -25 * 1.0000001, 1.00048828125, 1.0009765625 + 2.0 ** -11, 1023.5 * 2.0 ** -24, -3.3],
+    ])
+    for v in vals:
+        with np.errstate(over="ignore"):
+            ref = int(np.float64(v).astype(np.float16).view(np.uint16))
+        assert oracle.f64_to_f16(v) == ref, v
+    for h in list(range(0, 0x7C00, 7)) + [0x7BFF, 0x0001, 0x03FF, 0x0400]:
+        assert oracle.f16_to_f64(h) == float(np.uint16(h).view(np.float16))
+
+
+# ----------------------------------------------------------------------------
+# Record layout (Section 4.1: 46 code bits + 16 radius bits per 16 coordinates)
+# ----------------------------------------------------------------------------
+def test_record_size_and_bit_budget():
+    assert oracle.REC == 62
+    assert 62 * 8 / 128 == 3.875
+    assert abs(16 * 128 / (62 * 8) - 4.129) < 1e-3
+
+
+def test_pack_hand_built_record():
+    # fixture written by hand from the documented canonical order
+    lines = [l.split("#")[0].strip() for l in open(os.path.join(GOLDEN, "record_hand_built.txt"))]
+    lines = [l for l in lines if l]
+    codes = np.array([int(t) for t in lines[0].split()], dtype=np.int32)
+    radii = np.array([int(t, 16) for t in lines[1].split()], dtype=np.uint16)
+    expect = np.array([int(t, 16) for t in " ".join(lines[2:]).split()], dtype=np.uint8)
+    assert codes.size == 120 and radii.size == 8 and expect.size == 62
+    rec = oracle.pack(codes[None, :], radii[None, :])
+    assert np.array_equal(rec[0], expect)
+    J, r = oracle.unpack(rec)
+    assert np.array_equal(J[0], codes) and np.array_equal(r[0], radii)
+
+
+def test_pack_unpack_identity():
+    rng = np.random.default_rng(5)
+    J = np.concatenate([rng.integers(0, 16, (50, 64)), rng.integers(0, 4, (50, 56))], axis=1).astype(np.int32)
+    rad = rng.integers(0, 0x7C00, (50, 8)).astype(np.uint16)
+    rec = oracle.pack(J, rad)
+    assert rec.shape == (50, 62)
+    J2, rad2 = oracle.unpack(rec)
+    assert np.array_equal(J, J2) and np.array_equal(rad, rad2)
+
+
+# ----------------------------------------------------------------------------
+# Encode / DeQuant
+# ----------------------------------------------------------------------------
+def test_encode_is_polar_plus_quant(S, cb, X0):
+    rec, psi, Y = oracle.encode(X0[:32], S, cb, want_psi=True, want_y=True)
+    assert np.max(np.abs(Y - X0[:32] @ S)) <= 1e-12
+    J, rad = oracle.unpack(rec)
+    for i in range(32):
+        p, r = oracle.polar(Y[i], 4)
+        assert np.max(np.abs(p - psi[i])) == 0.0
+        spans = {1: (0, 64), 2: (64, 96), 3: (96, 112), 4: (112, 120)}
+        for level, (a0, a1) in spans.items():
+            theta = cb[oracle.CB_OFF[level] : oracle.CB_OFF[level] + oracle.CB_K[level]]
+            ref = np.argmin(np.abs(theta[None, :] - p[a0:a1, None]), axis=1)
+            assert np.array_equal(ref, J[i, a0:a1])
+        assert np.array_equal(rad[i], r.astype(np.float16).view(np.uint16))
+
+
+def test_dequant_block_lies_on_stored_sphere(S, cb, X0):
+    rec = oracle.encode(X0[:64], S, cb)
+    yhat = oracle.decode(rec, S, cb, rotated=True)
+    _, rad = oracle.unpack(rec)
+    r = rad.view(np.float16).astype(np.float64)
+    assert np.max(np.abs(np.linalg.norm(yhat.reshape(64, 8, 16), axis=2) - r)) <= 1e-12
+    xhat = oracle.decode(rec, S, cb, rotated=False)
+    assert np.max(np.abs(xhat - yhat @ S.T)) <= 1e-12
+    assert np.max(np.abs(np.linalg.norm(xhat, axis=1) - np.linalg.norm(r, axis=1))) <= 1e-12
+
+
+def test_zero_vector_encodes_to_zero_radius(S, cb):
+    rec = oracle.encode(np.zeros((1, 128)), S, cb)
+    J, rad = oracle.unpack(rec)
+    assert np.all(rad == 0) and np.all(J == 0)
+    assert np.all(oracle.decode(rec, S, cb) == 0.0)
+
+
+def test_reconstruction_error_matches_per_level_prediction(S, cb, X0):
+    # For Gaussian data the angle errors of different levels are independent, so
+    # E<x, xhat>/|x|^2 = prod_l E[cos(delta_l)] and |xhat| = |x| up to fp16:
+    # relative L2 error = sqrt(2 (1 - prod_l E cos delta_l)).
+    prod = 1.0
+    for level in (1, 2, 3, 4):
+        K = oracle.CB_K[level]
+        c, b = oracle.codebook(level, K)
+        m = 0 if level == 1 else 2 ** (level - 1) - 1
+        pdf = lambda t: math.sin(2 * t) ** m if level > 1 else 1.0
+        norm, _ = scipy.integrate.quad(pdf, b[0], b[-1])
+        e = sum(
+            scipy.integrate.quad(lambda t, k=k: math.cos(t - c[k]) * pdf(t), b[k], b[k + 1])[0] for k in range(K)
+        ) / norm
+        prod *= e
+    predicted = math.sqrt(2 * (1 - prod))
+    rec = oracle.encode(X0, S, cb)
+    xhat = oracle.decode(rec, S, cb)
+    rel = np.linalg.norm(xhat - X0) / np.linalg.norm(X0)
+    assert abs(rel - predicted) <= 0.004, (rel, predicted)
+    assert 0.17 < rel < 0.19
+
+
+# ----------------------------------------------------------------------------
+# Attention (Eq. 5)
+# ----------------------------------------------------------------------------
+def _small_cache(S, cb, T=37, Hkv=2, B=2, seed=21):
+    k = synth.kv_stream(T * B, Hkv, seed).float().numpy().astype(np.float64)
+    v = synth.kv_stream(T * B, Hkv, seed + 1).float().numpy().astype(np.float64)
+    k_rec = oracle.encode(k.reshape(-1, 128), S, cb).reshape(Hkv, T * B, 62)
+    v_rec = oracle.encode(v.reshape(-1, 128), S, cb).reshape(Hkv, T * B, 62)
+    q = synth.queries(B, 4 * Hkv, seed).float().numpy().astype(np.float64)
+    return q, k_rec, v_rec
+
+
+def test_attention_is_textbook_softmax_on_dequantised_cache(S, cb):
+    T, Hkv, B = 37, 2, 2
+    q, k_rec, v_rec = _small_cache(S, cb, T, Hkv, B)
+    seq_start = np.array([0, T], dtype=np.int64)
+    ctx_len = np.array([T, T - 5], dtype=np.int32)
+    scale = 1 / math.sqrt(128)
+    out = oracle.attention(q, k_rec, v_rec, seq_start, ctx_len, S, cb, scale)
+    for b in range(B):
+        for h in range(4 * Hkv):
+            hk = h // 4
+            sl = slice(seq_start[b], seq_start[b] + ctx_len[b])
+            Kh = oracle.decode(k_rec[hk, sl], S, cb)
+            Vh = oracle.decode(v_rec[hk, sl], S, cb)
+            p = scipy.special.softmax(Kh @ q[b, h] * scale)
+            assert np.max(np.abs(p @ Vh - out[b, h])) <= 1e-12
+    # rotated-domain evaluation (query rotated once, output un-rotated once) is the same number
+    out_r = oracle.attention(q, k_rec, v_rec, seq_start, ctx_len, S, cb, scale, rotated=True)
+    assert np.max(np.abs(out_r - out)) <= 1e-12
+
+
+def test_attention_degenerate_cases(S, cb):
+    T, Hkv, B = 9, 1, 2
+    q, k_rec, v_rec = _small_cache(S, cb, T, Hkv, B, seed=33)
+    scale = 1 / math.sqrt(128)
+    # one cached token: the output is that token's dequantised value; empty context: zeros
+    out = oracle.attention(q, k_rec, v_rec, np.array([3, 0]), np.array([1, 0], dtype=np.int32), S, cb, scale)
+    assert np.max(np.abs(out[0] - oracle.decode(v_rec[0, 3:4], S, cb))) <= 1e-12
+    assert np.all(out[1] == 0.0)
+    # zero query: all scores equal, output = mean of the dequantised values
+    out = oracle.attention(np.zeros_like(q), k_rec, v_rec, np.array([0, T]), np.array([T, T], dtype=np.int32), S, cb, scale)
+    assert np.max(np.abs(out[0, 0] - oracle.decode(v_rec[0, :T], S, cb).mean(axis=0))) <= 1e-12
+
+
+def test_exact_attention_helper_is_plain_softmax():
+    rng = np.random.default_rng(2)
+    K, V = rng.standard_normal((2, 50, 128))
+    q = rng.standard_normal((4, 128))
+    out = oracle.attention_exact(q, K, V, 0.1)
+    ref = scipy.special.softmax(q @ K.T * 0.1, axis=1) @ V
+    assert np.max(np.abs(out - ref)) <= 1e-12
