@@ -1,0 +1,202 @@
+/*
+ * polarquant.h -- C ABI of libpolarquant: the PolarQuant KV-cache hot path
+ * (random preconditioning, recursive polar transform, per-level angle
+ * quantisation, attention computed on the packed codes) for one MI355X GPU.
+ *
+ * Configuration (Section 4.1 of the PolarQuant paper, "Practical
+ * Implementation"): head dimension d = 128, L = 4 polar levels, 4 bits per
+ * level-1 angle, 2 bits per angle of levels 2..4, one binary16 radius per
+ * block of 16 rotated coordinates: 46 code bytes + 16 radius bytes = 62 bytes
+ * per vector (3.875 bits per coordinate).
+ *
+ * Conventions
+ *   - Every function returns a pq_status and never throws or aborts.
+ *   - "device" pointers are HIP device memory owned by the caller and must be
+ *     16-byte aligned (PQ_EALIGN otherwise); "host" pointers are ordinary
+ *     memory.  The library allocates device memory only for the constants of
+ *     a pq_ctx (< 1 MB per device, on the first call that uses that device).
+ *   - Kernels are enqueued on the caller's hipStream_t (passed as void*; NULL
+ *     is the default stream).  The library never synchronises the stream.
+ *   - A pq_ctx is immutable after creation and may be shared by threads.
+ *
+ * Cache layout ("tiles")
+ *   A cache holds keys or values of n_heads head planes.  Each plane is an
+ *   array of pool_tokens token slots, pool_tokens a multiple of 64.  64
+ *   consecutive slots form a tile: PQ_TILE_CODE_BYTES (2944) code bytes in
+ *   the codes buffer and PQ_TILE_RADII (512) binary16 radii in the radii
+ *   buffer, i.e. exactly 62 bytes per token.
+ *     codes: uint8_t [n_heads][pool_tokens/64][2944]
+ *     radii: uint16_t[n_heads][pool_tokens/64][512]
+ *   Inside a tile the fields are stored planar and lane-major so that a
+ *   64-lane wavefront reads them with full-width coalesced loads; keys
+ *   (PQ_KEY) and values (PQ_VALUE) use different in-tile orders because the
+ *   score and the weighted-sum contractions consume them differently.  The
+ *   exact bit positions are specified at the top of csrc/pq_layout.h;
+ *   pq_export_canonical converts tiles to the order-independent canonical
+ *   62-byte records.
+ *   A sequence must start on a tile boundary (seq_start % 64 == 0).
+ */
+#ifndef POLARQUANT_H
+#define POLARQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pq_ctx pq_ctx; /* opaque: S, codebooks, device constant tables */
+
+typedef enum { PQ_F32 = 0, PQ_BF16 = 1 } pq_dtype;
+typedef enum { PQ_KEY = 0, PQ_VALUE = 1 } pq_kind;
+typedef enum {
+    PQ_OK = 0,
+    PQ_EINVAL = -1,       /* null pointer, bad size, bad enum */
+    PQ_EUNSUPPORTED = -2, /* d != 128, Hq/Hkv not in {1,2,4,8}, ... */
+    PQ_EALIGN = -3,       /* device pointer or stride not 16-byte aligned */
+    PQ_EHIP = -4,         /* a HIP runtime call failed (no device, launch error) */
+    PQ_ENOMEM = -5        /* host or device allocation failed, workspace too small */
+} pq_status;
+
+#define PQ_D 128               /* head dimension */
+#define PQ_LEVELS 4            /* polar levels */
+#define PQ_BLOCK 16            /* coordinates per stored radius */
+#define PQ_RECORD_BYTES 62     /* canonical record: 46 code bytes + 8 binary16 radii */
+#define PQ_TILE_TOKENS 64
+#define PQ_TILE_CODE_BYTES 2944
+#define PQ_TILE_RADII 512
+
+const char *pq_status_string(pq_status s);
+
+/* ---------------------------------------------------------------------------
+ * Preconditioner and codebooks (Section 3.2 footnote and Section 4.1: one
+ * random rotation S shared by keys, values, layers and heads; Algorithm 1
+ * line 3 / Eq. 3 with the "offline" codebook: the optimal 1-D quantiser of the
+ * closed-form angle density of Lemma 2, shared by every prompt).
+ *
+ * d must be 128 (PQ_EUNSUPPORTED otherwise).  If S_rowmajor_f64 (host, d*d
+ * doubles, S[i][j] at i*d+j, used as y = x * S) is not NULL it is taken
+ * verbatim after checking ||S^T S - I||_max <= 1e-10 (PQ_EINVAL otherwise);
+ * if NULL, S is generated on the host in double precision from `seed`:
+ * a Gaussian matrix from a counter-based generator (splitmix64 finaliser +
+ * Box-Muller), Householder QR, columns sign-fixed so that R has a positive
+ * diagonal.  Codebooks are computed on the host in double precision.
+ * No device is touched; *out receives the context (caller frees it with
+ * pq_destroy).
+ * ------------------------------------------------------------------------- */
+pq_status pq_init_preconditioner(pq_ctx **out, int d, uint64_t seed, const double *S_rowmajor_f64);
+
+/* Copies S (d*d doubles, row-major) to host memory S_out. */
+pq_status pq_get_preconditioner(const pq_ctx *ctx, double *S_out);
+
+/* level in 1..4.  centroids: K doubles (K = 16 for level 1, 4 otherwise);
+ * boundaries: K+1 doubles (lower end, K-1 inner boundaries, upper end).
+ * Either output may be NULL. */
+pq_status pq_get_codebook(const pq_ctx *ctx, int level, double *centroids, double *boundaries);
+
+void pq_destroy(pq_ctx *ctx);
+
+/* ---------------------------------------------------------------------------
+ * Encode (Algorithm 1 lines 2 and 4, procedures Polar and Quant, with the
+ * settings of Section 4.1): for every vector y = x * S, a depth-4 polar
+ * transform of each block of 16 coordinates, every angle replaced by the
+ * index of its nearest centroid, the block radius rounded to binary16, the
+ * result bit-packed into the tile layout of `kind`.
+ *
+ * x (device): element (t, h, k) at x[t*ld_token + h*ld_head + k], k < 128,
+ *   t < n_tokens, h < n_heads; dtype xt; ld_token and ld_head in elements,
+ *   multiples of 8 (bf16) or 4 (f32) so that every row is 16-byte aligned.
+ * Token t of head h is written to slot dst_token0 + t of head plane h of the
+ * cache (codes, radii) whose planes hold pool_tokens slots.  Slots of a tile
+ * outside [dst_token0, dst_token0 + n_tokens) keep their contents.
+ * Two calls that write into the same tile must not overlap in time.
+ * n_tokens == 0 is a no-op (pointers are not examined).
+ * ------------------------------------------------------------------------- */
+pq_status pq_encode_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,
+                       int64_t n_tokens, int n_heads, int64_t ld_token, int64_t ld_head,
+                       uint8_t *codes, uint16_t *radii, int64_t pool_tokens,
+                       int64_t dst_token0, void *hip_stream);
+
+/* Decode-time append: one new token per sequence.  x (device): [n_seq][n_heads][128]
+ * contiguous; sequence b's vectors go to slot dst_token[b] (device array of
+ * n_seq int64) of every head plane.  Same arithmetic as pq_encode_kv. */
+pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,
+                       int n_seq, int n_heads, uint8_t *codes, uint16_t *radii,
+                       int64_t pool_tokens, const int64_t *dst_token, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * DeQuant (Algorithm 1, procedure DeQuant): slots [token0, token0+n_tokens)
+ * of every head plane are rebuilt top-down from the stored radius with the
+ * cos / sin of the code centroids.  rotated == 0 applies the trailing
+ * multiplication by S^T (the procedure as printed); rotated != 0 stops
+ * before it and returns r^(0), the vector in the rotated domain.
+ * out (device): element (t, h, k) at out[t*ld_token + h*ld_head + k].
+ * ------------------------------------------------------------------------- */
+pq_status pq_decode_kv(const pq_ctx *ctx, pq_kind kind, const uint8_t *codes, const uint16_t *radii,
+                       int64_t pool_tokens, int64_t token0, int64_t n_tokens, int n_heads,
+                       void *out, pq_dtype ot, int64_t ld_token, int64_t ld_head,
+                       int rotated, void *hip_stream);
+
+/* Tiles -> canonical records (device to device): rec[h][t][62] for slots
+ * [token0, token0+n_tokens) of each head plane.  Canonical record: bytes
+ * 0..31 the 64 level-1 codes in coordinate order, two per byte, earlier code
+ * in the high nibble; bytes 32..39 / 40..43 / 44..45 the level-2 / 3 / 4
+ * codes, four per byte, earlier code in the higher bits; bytes 46..61 the 8
+ * binary16 radii in block order, little endian. */
+pq_status pq_export_canonical(const pq_ctx *ctx, pq_kind kind, const uint8_t *codes,
+                              const uint16_t *radii, int64_t pool_tokens, int64_t token0,
+                              int64_t n_tokens, int n_heads, uint8_t *rec, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Decode attention on the packed cache (Eq. 5: softmax(Khat q / sqrt(d))
+ * Vhat with Khat, Vhat the DeQuant of the cached codes), one query token per
+ * sequence, grouped-query heads.  Because S is a rotation, the kernels work
+ * in the rotated domain: q is multiplied by S once, keys and values are
+ * rebuilt from their codes without the trailing S^T, and the weighted value
+ * sum is multiplied by S^T once at the end.
+ *
+ * q (device): [B][Hq][128] bf16.  out (device): [B][Hq][128] of out_dtype
+ * (PQ_BF16, rounded to nearest even, or PQ_F32).  k_* / v_*: caches written by
+ * pq_encode_kv with PQ_KEY / PQ_VALUE, Hkv head planes of pool_tokens slots.
+ * Sequence b owns slots [seq_start[b], seq_start[b] + ctx_len[b]) of every
+ * plane (seq_start, ctx_len: device arrays of B entries; seq_start[b] % 64
+ * == 0; the tile holding the last token must lie inside the pool).  The
+ * query attends to all ctx_len[b] cached tokens (its own key/value are
+ * appended before the call).  Query head h reads KV head h / (Hq/Hkv);
+ * Hq/Hkv must be 1, 2 or 4.  ctx_len[b] == 0 gives a zero output row.
+ * max_ctx (host) bounds every ctx_len[b]; it sizes the launch.
+ * workspace (device): at least pq_attn_workspace_bytes(B, Hq, Hkv, max_ctx)
+ * bytes, PQ_ENOMEM otherwise; contents need not be preserved between calls.
+ * ------------------------------------------------------------------------- */
+pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
+                               const uint8_t *k_codes, const uint16_t *k_radii,
+                               const uint8_t *v_codes, const uint16_t *v_radii,
+                               const int64_t *seq_start, const int32_t *ctx_len,
+                               int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
+                               float softmax_scale, void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
+
+size_t pq_attn_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ctx);
+
+/* ---------------------------------------------------------------------------
+ * Optional timing of the two dominant kernels (the attention partial kernel
+ * and the encode kernel) with HIP events recorded on the launch stream,
+ * for benchmarks: pq_profile_begin(max_launches) creates the events and turns
+ * recording on (at most max_launches launches of each kernel are timed);
+ * pq_profile_end waits for the recorded events, returns the summed kernel
+ * time in milliseconds and the number of timed launches per kernel (any
+ * output may be NULL) and turns recording off.  Process-wide, not per ctx.
+ * ------------------------------------------------------------------------- */
+pq_status pq_profile_begin(int max_launches);
+pq_status pq_profile_end(double *attn_ms, int *attn_launches, double *encode_ms, int *encode_launches);
+
+/* Name of the dominant kernel of the last pq_attn_decode_polar / pq_encode_kv
+ * launch configuration (for matching profiler output); static strings. */
+const char *pq_kernel_name_attn(void);
+const char *pq_kernel_name_encode(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POLARQUANT_H */

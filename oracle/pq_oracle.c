@@ -19,8 +19,8 @@
  * Parity status of each function is stated in its comment; functions whose
  * result no independent fact pins say "parity unpinned".
  *
- * OpenMP pragmas parallelise over independent vectors / (sequence, head)
- * pairs only; no blocking, fusion or reordering beyond the definitions.
+ * OpenMP pragmas parallelise over independent vectors / cached rows only;
+ * no blocking, fusion or reordering beyond the definitions.
  */
 #include <math.h>
 #include <stdint.h>
@@ -485,7 +485,6 @@ void orc_attention(const double *q, int B, int Hq, int Hkv,
 {
     int G = Hq / Hkv;
     int64_t pairs = (int64_t)B * Hkv;
-#pragma omp parallel for schedule(dynamic, 1)
     for (int64_t p = 0; p < pairs; ++p) {
         int b = (int)(p / Hkv), hk = (int)(p % Hkv);
         int64_t T = ctx_len[b];
@@ -497,6 +496,8 @@ void orc_attention(const double *q, int B, int Hq, int Hkv,
         double *Kh = (double *)malloc(sizeof(double) * T * ORC_D);
         double *Vh = (double *)malloc(sizeof(double) * T * ORC_D);
         double *sc = (double *)malloc(sizeof(double) * T);
+        /* DeQuant of every cached row (rows are independent) */
+#pragma omp parallel for schedule(static)
         for (int64_t t = 0; t < T; ++t) {
             double y[ORC_D];
             orc_dequant_rotated_one(kr + t * ORC_REC, cb, y);

@@ -1,0 +1,213 @@
+"""ctypes binding of libpolarquant (argument marshalling only).
+
+Function names mirror the C ABI: ``Context`` wraps ``pq_init_preconditioner`` /
+``pq_destroy`` and its methods call ``pq_encode_kv``, ``pq_append_kv``,
+``pq_decode_kv``, ``pq_export_canonical`` and ``pq_attn_decode_polar`` with
+pointers of torch tensors (torch is used for device memory and streams only).
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import _build
+
+PQ_F32, PQ_BF16 = 0, 1
+PQ_KEY, PQ_VALUE = 0, 1
+TILE_TOKENS = 64
+TILE_CODE_BYTES = 2944
+TILE_RADII = 512
+RECORD_BYTES = 62
+D = 128
+
+_lib = None
+
+
+class PolarQuantError(RuntimeError):
+    pass
+
+
+def library():
+    """Loads the in-tree libpolarquant.so (building it first if it is absent)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIB_PATH
+    if not os.path.exists(path):
+        _build.build()
+    L = ctypes.CDLL(path)
+    vp, i64, i32, u64 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint64
+    L.pq_status_string.restype = ctypes.c_char_p
+    L.pq_status_string.argtypes = [i32]
+    L.pq_init_preconditioner.restype = i32
+    L.pq_init_preconditioner.argtypes = [ctypes.POINTER(vp), i32, u64, vp]
+    L.pq_get_preconditioner.restype = i32
+    L.pq_get_preconditioner.argtypes = [vp, vp]
+    L.pq_get_codebook.restype = i32
+    L.pq_get_codebook.argtypes = [vp, i32, vp, vp]
+    L.pq_destroy.restype = None
+    L.pq_destroy.argtypes = [vp]
+    L.pq_encode_kv.restype = i32
+    L.pq_encode_kv.argtypes = [vp, vp, i32, i32, i64, i32, i64, i64, vp, vp, i64, i64, vp]
+    L.pq_append_kv.restype = i32
+    L.pq_append_kv.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i64, vp, vp]
+    L.pq_decode_kv.restype = i32
+    L.pq_decode_kv.argtypes = [vp, i32, vp, vp, i64, i64, i64, i32, vp, i32, i64, i64, i32, vp]
+    L.pq_export_canonical.restype = i32
+    L.pq_export_canonical.argtypes = [vp, i32, vp, vp, i64, i64, i64, i32, vp, vp]
+    L.pq_attn_decode_polar.restype = i32
+    L.pq_attn_decode_polar.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, i64,
+                                       ctypes.c_float, vp, ctypes.c_size_t, vp]
+    L.pq_attn_workspace_bytes.restype = ctypes.c_size_t
+    L.pq_attn_workspace_bytes.argtypes = [i32, i32, i32, i64]
+    L.pq_profile_begin.restype = i32
+    L.pq_profile_begin.argtypes = [i32]
+    L.pq_profile_end.restype = i32
+    L.pq_profile_end.argtypes = [vp, vp, vp, vp]
+    L.pq_kernel_name_attn.restype = ctypes.c_char_p
+    L.pq_kernel_name_encode.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def pq_status_string(code):
+    return library().pq_status_string(int(code)).decode()
+
+
+def profile_begin(max_launches):
+    _check(library().pq_profile_begin(int(max_launches)))
+
+
+def profile_end():
+    """-> dict(attn_ms, attn_launches, encode_ms, encode_launches) of the launches timed since profile_begin."""
+    a, e = ctypes.c_double(), ctypes.c_double()
+    na, ne = ctypes.c_int(), ctypes.c_int()
+    _check(library().pq_profile_end(ctypes.byref(a), ctypes.byref(na), ctypes.byref(e), ctypes.byref(ne)))
+    return {"attn_ms": a.value, "attn_launches": na.value, "encode_ms": e.value, "encode_launches": ne.value}
+
+
+def _check(code):
+    if code != 0:
+        raise PolarQuantError(pq_status_string(code))
+
+
+def _stream():
+    import torch
+
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t):
+    import torch
+
+    if t.dtype == torch.bfloat16:
+        return PQ_BF16
+    if t.dtype == torch.float32:
+        return PQ_F32
+    raise PolarQuantError("only float32 and bfloat16 tensors are supported")
+
+
+class Context:
+    """pq_ctx: the preconditioner S, the codebooks and the device constant tables."""
+
+    def __init__(self, seed=0, S=None, d=D):
+        L = library()
+        h = ctypes.c_void_p()
+        if S is not None:
+            S = np.ascontiguousarray(S, dtype=np.float64)
+            if S.shape != (d, d):
+                raise PolarQuantError("S must be d x d")
+            sp = S.ctypes.data_as(ctypes.c_void_p)
+        else:
+            sp = None
+        _check(L.pq_init_preconditioner(ctypes.byref(h), int(d), int(seed), sp))
+        self._h = h
+        self.d = d
+
+    def close(self):
+        if getattr(self, "_h", None):
+            library().pq_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- host-side getters -------------------------------------------------
+    def preconditioner(self):
+        S = np.empty((self.d, self.d), dtype=np.float64)
+        _check(library().pq_get_preconditioner(self._h, S.ctypes.data_as(ctypes.c_void_p)))
+        return S
+
+    def codebook(self, level):
+        K = 16 if level == 1 else 4
+        c = np.empty(K, dtype=np.float64)
+        b = np.empty(K + 1, dtype=np.float64)
+        _check(library().pq_get_codebook(self._h, int(level), c.ctypes.data_as(ctypes.c_void_p),
+                                         b.ctypes.data_as(ctypes.c_void_p)))
+        return c, b
+
+    # ---- cache allocation helper (torch owns the memory) --------------------
+    @staticmethod
+    def alloc_cache(n_heads, pool_tokens, device="cuda"):
+        import torch
+
+        if pool_tokens % TILE_TOKENS:
+            raise PolarQuantError("pool_tokens must be a multiple of 64")
+        tiles = pool_tokens // TILE_TOKENS
+        codes = torch.empty((n_heads, tiles, TILE_CODE_BYTES), dtype=torch.uint8, device=device)
+        radii = torch.empty((n_heads, tiles, TILE_RADII), dtype=torch.int16, device=device)
+        return codes, radii
+
+    # ---- kernels -------------------------------------------------------------
+    def encode_kv(self, x, kind, codes, radii, dst_token0=0, ld_token=None, ld_head=None, n_tokens=None, n_heads=None):
+        """x: [n_tokens, n_heads, 128] (token-major) or any strided view given ld_token / ld_head (elements)."""
+        if ld_token is None:
+            n_tokens, n_heads = x.shape[0], x.shape[1]
+            ld_token, ld_head = x.stride(0), x.stride(1)
+            if x.stride(2) != 1:
+                raise PolarQuantError("innermost dimension must be contiguous")
+        pool_tokens = codes.shape[1] * TILE_TOKENS
+        _check(library().pq_encode_kv(self._h, x.data_ptr(), _dtype_code(x), int(kind), int(n_tokens), int(n_heads),
+                                      int(ld_token), int(ld_head), codes.data_ptr(), radii.data_ptr(),
+                                      int(pool_tokens), int(dst_token0), _stream()))
+
+    def append_kv(self, x, kind, codes, radii, dst_token):
+        """x: [n_seq, n_heads, 128] contiguous; dst_token: int64 device tensor [n_seq]."""
+        if not x.is_contiguous():
+            raise PolarQuantError("x must be contiguous")
+        pool_tokens = codes.shape[1] * TILE_TOKENS
+        _check(library().pq_append_kv(self._h, x.data_ptr(), _dtype_code(x), int(kind), int(x.shape[0]), int(x.shape[1]),
+                                      codes.data_ptr(), radii.data_ptr(), int(pool_tokens), dst_token.data_ptr(),
+                                      _stream()))
+
+    def decode_kv(self, kind, codes, radii, token0, n_tokens, out, rotated=False):
+        """out: [n_tokens, n_heads, 128] float32 or bfloat16 (strides taken from the tensor)."""
+        pool_tokens = codes.shape[1] * TILE_TOKENS
+        _check(library().pq_decode_kv(self._h, int(kind), codes.data_ptr(), radii.data_ptr(), int(pool_tokens),
+                                      int(token0), int(n_tokens), int(out.shape[1]), out.data_ptr(), _dtype_code(out),
+                                      int(out.stride(0)), int(out.stride(1)), 1 if rotated else 0, _stream()))
+
+    def export_canonical(self, kind, codes, radii, token0, n_tokens, rec):
+        """rec: uint8 [n_heads, n_tokens, 62] contiguous."""
+        pool_tokens = codes.shape[1] * TILE_TOKENS
+        _check(library().pq_export_canonical(self._h, int(kind), codes.data_ptr(), radii.data_ptr(), int(pool_tokens),
+                                             int(token0), int(n_tokens), int(codes.shape[0]), rec.data_ptr(), _stream()))
+
+    @staticmethod
+    def attn_workspace_bytes(B, Hq, Hkv, max_ctx):
+        return int(library().pq_attn_workspace_bytes(int(B), int(Hq), int(Hkv), int(max_ctx)))
+
+    def attn_decode_polar(self, q, out, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len, max_ctx,
+                          softmax_scale, workspace):
+        """q: [B, Hq, 128] bf16; out: same shape, bf16 or float32; seq_start int64 [B], ctx_len int32 [B] (device)."""
+        B, Hq = q.shape[0], q.shape[1]
+        Hkv = k_codes.shape[0]
+        pool_tokens = k_codes.shape[1] * TILE_TOKENS
+        _check(library().pq_attn_decode_polar(
+            self._h, q.data_ptr(), out.data_ptr(), _dtype_code(out), k_codes.data_ptr(), k_radii.data_ptr(), v_codes.data_ptr(),
+            v_radii.data_ptr(), seq_start.data_ptr(), ctx_len.data_ptr(), int(B), int(Hq), int(Hkv), int(pool_tokens),
+            int(max_ctx), float(softmax_scale), workspace.data_ptr(), int(workspace.numel() * workspace.element_size()),
+            _stream()))

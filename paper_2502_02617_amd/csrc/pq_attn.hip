@@ -1,0 +1,507 @@
+/*
+ * pq_attn.hip -- pq_attn_decode_polar: attention of one query token per
+ * sequence computed directly on the packed PolarQuant cache (Eq. 5 with the
+ * DeQuant of Algorithm 1 fused in), for gfx950.
+ *
+ * Because S is a rotation, <q, khat> = <q S, khat S>: keys and values stay in
+ * the rotated domain r^(0) (DeQuant without its trailing S^T), the query is
+ * rotated once and the weighted value sum is multiplied by S^T once.
+ *
+ * Three kernels per call:
+ *   pq_rotate_q_kernel      q' = (q S) * softmax_scale * log2(e), binary16
+ *   pq_attn_partial_kernel  one wavefront per (sequence, kv head, chunk of
+ *                           tiles): streams K and V tiles, rebuilds them in
+ *                           registers, scores and weighted sums on the matrix
+ *                           cores, online softmax; writes (m, l, o') partials
+ *   pq_attn_combine_kernel  merges the partials of a (sequence, query head) in
+ *                           chunk order, divides by l, multiplies by S^T, bf16
+ *
+ * Partial kernel, per 16-token pass (four passes per 64-token tile):
+ *   K:  lane (gk, m) rebuilds the 32 rotated coordinates of quarter gk of token
+ *       16*i + m from its own registers: radius -> level 4 -> (level 3 x level 2
+ *       product table) -> level 1, every step a packed-binary16 multiply by a
+ *       (cos, sin) pair fetched from a 16-entry LDS table (all entries in
+ *       distinct banks, so the gathers are conflict free).  The 4 x 8 values are
+ *       the A operand (token rows) of v_mfma_f32_16x16x32_f16 against q'
+ *       (columns = query heads), accumulated over the four 32-coordinate slices.
+ *   softmax: the score tile comes out with lane (g, col) holding tokens
+ *       16*i + 4*g + {0..3}; running max and sum per column.
+ *   V:  lane (g, n) rebuilds half-block n (8 coordinates = 4 (cos, sin) pairs) of
+ *       those same four tokens.  A (cos, sin) register holds two coordinates of
+ *       one token, while a matrix-core operand wants several tokens of one
+ *       coordinate per lane; instead of transposing, the contraction index is
+ *       widened to (token, parity): operand rows are coordinate pairs, and the
+ *       probability operand has one column per (head, parity) with zeros in the
+ *       slots of the other parity.  The result accumulates o' for the even
+ *       coordinates in the parity-0 columns and for the odd ones in parity 1.
+ */
+#include "pq_common.h"
+
+namespace {
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWavesPerBlock = 4;
+constexpr float kLog2e = 1.4426950408889634f;
+/* Probabilities are handed to the matrix cores as binary16.  They are computed
+ * as 2^(s - m + kProbShift) so that even weights 2^-28 below the running
+ * maximum stay normal numbers; l carries the same factor and it cancels in o'/l. */
+constexpr float kProbShift = 14.0f;
+
+/* LDS table block (dwords): T1 [0,16)  T4 [16,20)  TA [32,48)  TB [48,64)
+ * T4 broadcast per half: [64,68) cos, [68,72) sin as (f, f) pairs */
+constexpr int kT1 = 0, kT4 = 16, kTA = 32, kTB = 48, kT4B = 64, kTabDwords = 72;
+
+struct AttnArgs {
+    const uint16_t *qrot; /* [B][Hq][128] binary16, rotated and pre-scaled */
+    const uint8_t *k_codes, *v_codes;
+    const uint16_t *k_radii, *v_radii;
+    const int64_t *seq_start;
+    const int32_t *ctx_len;
+    int B, Hq, Hkv;
+    int64_t pool_tiles;
+    int64_t max_ctx;
+    int chunk_tiles, n_chunks;
+    float *ws_ml; /* [B][Hq][n_chunks][2] */
+    float *ws_o;  /* [B][Hq][n_chunks][128] */
+    const PqDeviceConsts *consts;
+};
+
+union H8 {
+    h8 v;
+    uint4 q;
+    uint32_t w[4];
+    h2 p[4];
+};
+
+__device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__device__ __forceinline__ uint32_t as_u32(h2 v) { return __builtin_bit_cast(uint32_t, v); }
+
+/* fetch a packed (lo, hi) binary16 pair from an LDS table; byte_off is 4 * index */
+__device__ __forceinline__ h2 lut(const uint32_t *tab, int table, uint32_t byte_off)
+{
+    return as_h2(*reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(tab + table) + byte_off));
+}
+
+__device__ __forceinline__ h2 bcast_lo(h2 v) { return h2{v.x, v.x}; }
+__device__ __forceinline__ h2 bcast_hi(h2 v) { return h2{v.y, v.y}; }
+
+/* The four level-1 radii of a half-block times their (cos, sin) pairs:
+ * r3 = (r, r) radius of the level-3 node, g6 = [c2a | c3 | c2b], l1 = 4 level-1 codes. */
+__device__ __forceinline__ void expand_half_block(const uint32_t *tab, h2 r3, uint32_t g6, uint32_t l1, h2 out[4])
+{
+    h2 ra = r3 * lut(tab, kTA, (g6 >> 2) << 2);          /* (r1_0, r1_1) */
+    h2 rb = r3 * lut(tab, kTB, (g6 & 15u) << 2);         /* (r1_2, r1_3) */
+    out[0] = bcast_lo(ra) * lut(tab, kT1, (l1 << 2) & 0x3Cu);
+    out[1] = bcast_hi(ra) * lut(tab, kT1, (l1 >> 2) & 0x3Cu);
+    out[2] = bcast_lo(rb) * lut(tab, kT1, (l1 >> 6) & 0x3Cu);
+    out[3] = bcast_hi(rb) * lut(tab, kT1, (l1 >> 10) & 0x3Cu);
+}
+
+/* 24 bits starting at bit 24*i of the 96-bit little-endian string (d0, d1, d2) */
+__device__ __forceinline__ uint32_t take24(uint32_t d0, uint32_t d1, uint32_t d2, int i)
+{
+    switch (i) {
+    case 0: return d0 & 0xFFFFFFu;
+    case 1: return ((d0 >> 24) | (d1 << 8)) & 0xFFFFFFu;
+    case 2: return ((d1 >> 16) | (d2 << 16)) & 0xFFFFFFu;
+    default: return d2 >> 8;
+    }
+}
+
+struct KTileRaw {
+    uint4 l1a, l1b; /* chunks 0,1 | 2,3: {L1 block A, L1 block B} each */
+    uint32_t g0, g1, g2;
+    uint32_t c4;    /* 16 bits used */
+    uint4 rad;      /* chunk i: (radius A, radius B) */
+};
+
+struct VTileRaw {
+    uint4 l1a, l1b; /* slots 0..7 | 8..15, 16 bits each */
+    uint32_t g0, g1, g2;
+    uint32_t c4;    /* slot s at bits [2s, 2s+2) */
+    uint4 rad0, rad1; /* slots 0..7 | 8..15 */
+};
+
+__device__ __forceinline__ void load_k_tile(KTileRaw &t, const uint8_t *codes, const uint16_t *radii, int lane)
+{
+    t.l1a = *reinterpret_cast<const uint4 *>(codes + PQL_OFF_L1A + lane * 16);
+    t.l1b = *reinterpret_cast<const uint4 *>(codes + PQL_OFF_L1B + lane * 16);
+    const uint32_t *g = reinterpret_cast<const uint32_t *>(codes + PQL_OFF_G6 + lane * 12);
+    t.g0 = g[0]; t.g1 = g[1]; t.g2 = g[2];
+    t.c4 = *reinterpret_cast<const uint16_t *>(codes + PQL_OFF_C4 + lane * 2);
+    t.rad = *reinterpret_cast<const uint4 *>(radii + lane * 8);
+}
+
+__device__ __forceinline__ void load_v_tile(VTileRaw &t, const uint8_t *codes, const uint16_t *radii, int lane)
+{
+    t.l1a = *reinterpret_cast<const uint4 *>(codes + PQL_OFF_L1A + lane * 16);
+    t.l1b = *reinterpret_cast<const uint4 *>(codes + PQL_OFF_L1B + lane * 16);
+    const uint32_t *g = reinterpret_cast<const uint32_t *>(codes + PQL_OFF_G6 + lane * 12);
+    t.g0 = g[0]; t.g1 = g[1]; t.g2 = g[2];
+    t.c4 = *reinterpret_cast<const uint32_t *>(codes + PQL_OFF_C4 + (lane >> 1) * 4);
+    const uint4 *r = reinterpret_cast<const uint4 *>(radii + (lane >> 1) * 16);
+    t.rad0 = r[0];
+    t.rad1 = r[1];
+}
+
+/* Context length the kernels act on: the caller's value clamped to [0, max_ctx];
+ * a sequence whose slots would leave the pool or that does not start on a tile
+ * boundary is treated as empty (zero output) instead of being read. */
+__device__ __forceinline__ int effective_ctx(const int64_t *seq_start, const int32_t *ctx_len, int b,
+                                             int64_t max_ctx, int64_t pool_tiles)
+{
+    int64_t c = ctx_len[b];
+    if (c > max_ctx) c = max_ctx;
+    if (c <= 0) return 0;
+    int64_t s0 = seq_start[b];
+    if (s0 < 0 || (s0 & 63) || (s0 >> 6) + ((c + 63) >> 6) > pool_tiles) return 0;
+    return (int)c;
+}
+
+__device__ __forceinline__ uint32_t sel4(uint4 v, int c)
+{
+    return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w));
+}
+
+template <int G>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_partial_kernel(AttnArgs a)
+{
+    __shared__ uint32_t tab[kTabDwords];
+    {
+        const PqDeviceConsts &K = *a.consts;
+        int t = threadIdx.x;
+        if (t < 16) { tab[kT1 + t] = K.t1_h2[t]; tab[kTA + t] = K.ta_h2[t]; tab[kTB + t] = K.tb_h2[t]; }
+        if (t < 4) {
+            uint32_t cs = K.t4_h2[t];
+            tab[kT4 + t] = cs;
+            tab[kT4B + t] = (cs & 0xFFFFu) * 0x10001u;
+            tab[kT4B + 4 + t] = (cs >> 16) * 0x10001u;
+        }
+        if (t >= 20 && t < 32) tab[t] = 0u;
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int chunk = (int)(item % a.n_chunks);
+    const int hk = (int)((item / a.n_chunks) % a.Hkv);
+    const int b = (int)(item / ((int64_t)a.n_chunks * a.Hkv));
+    if (b >= a.B) return;
+    const int ctx = effective_ctx(a.seq_start, a.ctx_len, b, a.max_ctx, a.pool_tiles);
+    const int n_tiles = (ctx + 63) >> 6;
+    const int tile_lo = chunk * a.chunk_tiles;
+    if (tile_lo >= n_tiles) return;
+    const int tile_hi = min(tile_lo + a.chunk_tiles, n_tiles);
+
+    const int g = lane >> 4, n = lane & 15;
+    const int64_t seq_tile0 = a.seq_start[b] >> 6;
+    const uint8_t *kc = a.k_codes + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_CODE_BYTES;
+    const uint8_t *vc = a.v_codes + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_CODE_BYTES;
+    const uint16_t *kr = a.k_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_RADII;
+    const uint16_t *vr = a.v_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_RADII;
+
+    /* ---- q' operand: column n = (head n&3, parity (n>>2)&1) for n < 8, zero otherwise;
+     * slice s = rotated coordinates 32*g + 8*s .. +8 ---- */
+    H8 qb[4];
+    {
+        const int head = n & 3;
+        const bool real = (n < 8) && (head < G);
+        const uint4 *qp = reinterpret_cast<const uint4 *>(a.qrot + ((int64_t)b * a.Hq + hk * G + (real ? head : 0)) * PQ_D + 32 * g);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) qb[s].q = real ? qp[s] : make_uint4(0, 0, 0, 0);
+    }
+    const uint32_t parity_shift = (n & 4) ? 16u : 0u;
+    const int t4b = kT4B + ((n & 1) ? 4 : 0);
+
+    f4 acc_o[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc_o[c] = f4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+
+    KTileRaw kt;
+    VTileRaw vt;
+    load_k_tile(kt, kc + (int64_t)tile_lo * PQL_CODE_BYTES, kr + (int64_t)tile_lo * PQL_RADII, lane);
+    load_v_tile(vt, vc + (int64_t)tile_lo * PQL_CODE_BYTES, vr + (int64_t)tile_lo * PQL_RADII, lane);
+
+    for (int tile = tile_lo; tile < tile_hi; ++tile) {
+        KTileRaw kcur = kt;
+        VTileRaw vcur = vt;
+        if (tile + 1 < tile_hi) {
+            load_k_tile(kt, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * PQL_RADII, lane);
+            load_v_tile(vt, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * PQL_RADII, lane);
+        }
+        const int n_valid = min(64, ctx - tile * 64); /* >= 1 */
+
+        /* ---- scores: four passes of 16 tokens ---- */
+        f4 sc[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 l1q = (i < 2) ? kcur.l1a : kcur.l1b;
+            const uint32_t l1A = (i & 1) ? l1q.z : l1q.x, l1B = (i & 1) ? l1q.w : l1q.y;
+            const uint32_t g24 = take24(kcur.g0, kcur.g1, kcur.g2, i);
+            const uint32_t c4n = kcur.c4 >> (4 * i);
+            const h2 rad = as_h2(sel4(kcur.rad, i));
+            H8 ka[4];
+            {   /* block A = 2*gk: slices 0, 1 */
+                h2 rr = bcast_lo(rad) * lut(tab, kT4, (c4n << 2) & 0xCu);
+                expand_half_block(tab, bcast_lo(rr), g24 & 63u, l1A & 0xFFFFu, ka[0].p);
+                expand_half_block(tab, bcast_hi(rr), (g24 >> 6) & 63u, l1A >> 16, ka[1].p);
+            }
+            {   /* block B = 2*gk + 1: slices 2, 3 */
+                h2 rr = bcast_hi(rad) * lut(tab, kT4, c4n & 0xCu);
+                expand_half_block(tab, bcast_lo(rr), (g24 >> 12) & 63u, l1B & 0xFFFFu, ka[2].p);
+                expand_half_block(tab, bcast_hi(rr), (g24 >> 18) & 63u, l1B >> 16, ka[3].p);
+            }
+            f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                s4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[s].v, qb[s].v, s4, 0, 0, 0);
+            sc[i] = s4; /* lane (g, n): tokens 16*i + 4*g + e, column n */
+        }
+        if (n_valid < 64) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (16 * i + 4 * g + e >= n_valid) sc[i][e] = -INFINITY;
+        }
+
+        /* ---- online softmax, one state per column ---- */
+        float tmax = sc[0][0];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) tmax = fmaxf(tmax, sc[i][e]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m_run, tmax);
+        if (m_new > m_run) { /* not wave-uniform in general; cheap enough to predicate */
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            l_run *= alpha;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc_o[c] *= alpha;
+            m_run = m_new;
+        }
+
+        /* ---- probabilities and the weighted value sum, pass by pass ---- */
+        const float m_sub = m_run - kProbShift;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            H8 pb;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float p = __builtin_amdgcn_exp2f(sc[i][e] - m_sub);
+                l_run += p;
+                _Float16 ph = (_Float16)p;
+                uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, ph);
+                pb.w[e] = bits << parity_shift;
+            }
+            const uint4 l1q = (i < 2) ? vcur.l1a : vcur.l1b;
+            const uint32_t g24 = take24(vcur.g0, vcur.g1, vcur.g2, i);
+            const uint4 rq = (i < 2) ? vcur.rad0 : vcur.rad1;
+            h2 ve[4][4]; /* [token e][pair q] */
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int s = 4 * i + e;
+                const uint32_t l1w = sel4(l1q, 2 * (i & 1) + (e >> 1));
+                const uint32_t l1 = (e & 1) ? (l1w >> 16) : (l1w & 0xFFFFu);
+                const uint32_t rw = sel4(rq, 2 * (i & 1) + (e >> 1));
+                h2 rad = as_h2(rw);
+                h2 r = (e & 1) ? bcast_hi(rad) : bcast_lo(rad);
+                if (16 * i + 4 * g + e >= n_valid) r = h2{(_Float16)0.f, (_Float16)0.f};
+                const uint32_t c4 = (vcur.c4 >> (2 * s)) & 3u;
+                h2 r3 = r * lut(tab, t4b, c4 << 2);
+                expand_half_block(tab, r3, (g24 >> (6 * e)) & 63u, l1, ve[e]);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                H8 va;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) va.p[e] = ve[e][c];
+                acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.v, pb.v, acc_o[c], 0, 0, 0);
+            }
+        }
+    }
+
+    /* ---- partial results: l summed over the four token groups; o' scattered to coordinate order ---- */
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    const int head = n & 3;
+    if (n < 8 && head < G) {
+        const int par = (n >> 2) & 1;
+        const int64_t slot = ((int64_t)b * a.Hq + hk * G + head) * a.n_chunks + chunk;
+        float *o = a.ws_o + slot * PQ_D;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                o[2 * (16 * g + 4 * e + c) + par] = acc_o[c][e];
+        if (g == 0 && par == 0) {
+            a.ws_ml[slot * 2] = m_run;
+            a.ws_ml[slot * 2 + 1] = l_run;
+        }
+    }
+}
+
+struct RotateArgs {
+    const uint16_t *q; /* bf16 [rows][128] */
+    uint16_t *qrot;    /* binary16 [rows][128] */
+    const float *S;    /* S[i*128 + j] */
+    float scale;       /* softmax_scale * log2(e) */
+    const PqDeviceConsts *consts;
+};
+
+__global__ __launch_bounds__(PQ_D) void pq_rotate_q_kernel(RotateArgs a)
+{
+    __shared__ float sq[PQ_D];
+    const int row = blockIdx.x, j = threadIdx.x;
+    sq[j] = __uint_as_float((uint32_t)a.q[(int64_t)row * PQ_D + j] << 16);
+    __syncthreads();
+    float acc = 0.f;
+    for (int i = 0; i < PQ_D; ++i) acc += sq[i] * a.S[i * PQ_D + j];
+    /* rebuilt keys carry the table scale sigma of their coordinate: take it out here */
+    _Float16 h = (_Float16)(acc * a.scale / a.consts->sigma[j & 15]);
+    a.qrot[(int64_t)row * PQ_D + j] = __builtin_bit_cast(uint16_t, h);
+}
+
+struct CombineArgs {
+    const float *ws_ml, *ws_o;
+    const int64_t *seq_start;
+    const int32_t *ctx_len;
+    int64_t max_ctx, pool_tiles;
+    int Hq, n_chunks, chunk_tiles;
+    const float *St; /* St[j*128 + i] = S[i][j] */
+    void *out;       /* bf16 or f32 [B][Hq][128] */
+    int out_f32;
+    const PqDeviceConsts *consts;
+};
+
+__global__ __launch_bounds__(PQ_D) void pq_attn_combine_kernel(CombineArgs a)
+{
+    __shared__ float so[PQ_D];
+    const int row = blockIdx.x, j = threadIdx.x;
+    const int b = row / a.Hq;
+    const int ctx = effective_ctx(a.seq_start, a.ctx_len, b, a.max_ctx, a.pool_tiles);
+    const int n_tiles = (ctx + 63) >> 6;
+    const int used = min((n_tiles + a.chunk_tiles - 1) / a.chunk_tiles, a.n_chunks);
+    float m = -INFINITY, l = 0.f, o = 0.f;
+    for (int c = 0; c < used; ++c) { /* fixed order: results do not depend on scheduling */
+        const int64_t slot = (int64_t)row * a.n_chunks + c;
+        float mc = a.ws_ml[slot * 2], lc = a.ws_ml[slot * 2 + 1];
+        float oc = a.ws_o[slot * PQ_D + j];
+        float mn = fmaxf(m, mc);
+        float sa = exp2f(m - mn), sb = exp2f(mc - mn);
+        l = l * sa + lc * sb;
+        o = o * sa + oc * sb;
+        m = mn;
+    }
+    /* rebuilt values carry the table scale sigma of their coordinate */
+    so[j] = (used > 0) ? o / (l * a.consts->sigma[j & 15]) : 0.f;
+    __syncthreads();
+    float acc = 0.f;
+    for (int k = 0; k < PQ_D; ++k) acc += so[k] * a.St[k * PQ_D + j]; /* out_j = sum_k o'_k S[j][k] */
+    if (a.out_f32) {
+        static_cast<float *>(a.out)[(int64_t)row * PQ_D + j] = acc;
+    } else {
+        uint32_t u = __float_as_uint(acc);
+        static_cast<uint16_t *>(a.out)[(int64_t)row * PQ_D + j] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+    }
+}
+
+struct Plan {
+    int chunk_tiles, n_chunks;
+    size_t off_ml, off_o, total;
+};
+
+Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx)
+{
+    Plan p;
+    int64_t max_tiles = (max_ctx + 63) / 64;
+    if (max_tiles < 1) max_tiles = 1;
+    const int64_t target_items = 256 * 8 * 4; /* a few work items per resident wavefront */
+    int64_t streams = (int64_t)B * Hkv;
+    int64_t per_stream = (target_items + streams - 1) / streams;
+    if (per_stream < 1) per_stream = 1;
+    int64_t ct = (max_tiles + per_stream - 1) / per_stream;
+    if (ct < 4) ct = 4;
+    if (ct > max_tiles) ct = max_tiles;
+    p.chunk_tiles = (int)ct;
+    p.n_chunks = (int)((max_tiles + ct - 1) / ct);
+    size_t rows = (size_t)B * Hq;
+    p.off_ml = (rows * PQ_D * 2 + 255) & ~(size_t)255;
+    p.off_o = (p.off_ml + rows * p.n_chunks * 2 * sizeof(float) + 255) & ~(size_t)255;
+    p.total = p.off_o + rows * p.n_chunks * PQ_D * sizeof(float);
+    return p;
+}
+
+} // namespace
+
+extern "C" const char *pq_kernel_name_attn(void) { return "pq_attn_partial_kernel"; }
+
+extern "C" size_t pq_attn_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ctx)
+{
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || max_ctx < 0) return 0;
+    return make_plan(B, Hq, Hkv, max_ctx).total;
+}
+
+extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
+                                          const uint8_t *k_codes, const uint16_t *k_radii,
+                                          const uint8_t *v_codes, const uint16_t *v_radii,
+                                          const int64_t *seq_start, const int32_t *ctx_len,
+                                          int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
+                                          float softmax_scale, void *workspace, size_t workspace_bytes,
+                                          void *hip_stream)
+{
+    if (!ctx || !q || !out || !k_codes || !k_radii || !v_codes || !v_radii || !seq_start || !ctx_len || !workspace)
+        return PQ_EINVAL;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || pool_tokens <= 0 || (pool_tokens & 63) || max_ctx < 0 || max_ctx > pool_tokens)
+        return PQ_EINVAL;
+    if (Hq % Hkv) return PQ_EINVAL;
+    if (out_dtype != PQ_BF16 && out_dtype != PQ_F32) return PQ_EINVAL;
+    const int G = Hq / Hkv;
+    if (G != 1 && G != 2 && G != 4) return PQ_EUNSUPPORTED;
+    if (!pq_aligned16(q) || !pq_aligned16(out) || !pq_aligned16(k_codes) || !pq_aligned16(k_radii) ||
+        !pq_aligned16(v_codes) || !pq_aligned16(v_radii) || !pq_aligned16(workspace))
+        return PQ_EALIGN;
+    const Plan p = make_plan(B, Hq, Hkv, max_ctx);
+    if (workspace_bytes < p.total) return PQ_ENOMEM;
+    const PqDeviceState *ds = nullptr;
+    pq_status st = pq_device_state(ctx, &ds);
+    if (st != PQ_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    uint16_t *qrot = reinterpret_cast<uint16_t *>(ws);
+    float *ws_ml = reinterpret_cast<float *>(ws + p.off_ml);
+    float *ws_o = reinterpret_cast<float *>(ws + p.off_o);
+    const int rows = B * Hq;
+
+    RotateArgs ra{static_cast<const uint16_t *>(q), qrot, ds->S_f32, softmax_scale * kLog2e, ds->consts};
+    hipLaunchKernelGGL(pq_rotate_q_kernel, dim3(rows), dim3(PQ_D), 0, s, ra);
+
+    AttnArgs aa{};
+    aa.qrot = qrot;
+    aa.k_codes = k_codes; aa.v_codes = v_codes; aa.k_radii = k_radii; aa.v_radii = v_radii;
+    aa.seq_start = seq_start; aa.ctx_len = ctx_len;
+    aa.B = B; aa.Hq = Hq; aa.Hkv = Hkv;
+    aa.pool_tiles = pool_tokens / 64;
+    aa.max_ctx = max_ctx;
+    aa.chunk_tiles = p.chunk_tiles; aa.n_chunks = p.n_chunks;
+    aa.ws_ml = ws_ml; aa.ws_o = ws_o;
+    aa.consts = ds->consts;
+    const int64_t items = (int64_t)B * Hkv * p.n_chunks;
+    const unsigned blocks = (unsigned)((items + kWavesPerBlock - 1) / kWavesPerBlock);
+    pq_prof_before(0, s);
+    if (G == 4) hipLaunchKernelGGL(pq_attn_partial_kernel<4>, dim3(blocks), dim3(kWavesPerBlock * 64), 0, s, aa);
+    else if (G == 2) hipLaunchKernelGGL(pq_attn_partial_kernel<2>, dim3(blocks), dim3(kWavesPerBlock * 64), 0, s, aa);
+    else hipLaunchKernelGGL(pq_attn_partial_kernel<1>, dim3(blocks), dim3(kWavesPerBlock * 64), 0, s, aa);
+    pq_prof_after(0, s);
+
+    CombineArgs ca{ws_ml, ws_o, seq_start, ctx_len, max_ctx, pool_tokens / 64, Hq, p.n_chunks, p.chunk_tiles,
+                   ds->St_f32, out, out_dtype == PQ_F32 ? 1 : 0, ds->consts};
+    hipLaunchKernelGGL(pq_attn_combine_kernel, dim3(rows), dim3(PQ_D), 0, s, ca);
+    PQ_HIP_TRY(hipGetLastError());
+    return PQ_OK;
+}

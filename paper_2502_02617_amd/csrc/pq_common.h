@@ -1,0 +1,84 @@
+/*
+ * pq_common.h -- shared declarations of libpolarquant's translation units:
+ * the context object, the device-side constant block and launch helpers.
+ */
+#ifndef PQ_COMMON_H
+#define PQ_COMMON_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <mutex>
+
+#include "../../include/polarquant.h"
+#include "pq_layout.h"
+
+/* Constants every kernel reads; one copy per device in global memory. */
+struct PqDeviceConsts {
+    /* Quantisation by comparison in the tangent domain (Algorithm 1, Quant):
+       an angle psi = atan(v/u), u, v >= 0, lies above the inner boundary t iff
+       v > tan(t) * u.  tan_b[l-1] = {tan t_1, tan t_2, tan t_3} of level l
+       within one quadrant (level 1: boundaries pi/8, pi/4, 3pi/8). */
+    float tan_b[4][4];
+    /* cos / sin of the centroids, fp32 (DeQuant). */
+    float cs1[16][2];
+    float cs234[3][4][2];
+    /* Packed binary16 pairs (low half, high half) for the attention kernel. */
+    uint32_t t1_h2[16]; /* (cos, sin) of level-1 centroid c                        */
+    uint32_t t4_h2[4];  /* (cos, sin) of level-4 centroid c                        */
+    uint32_t ta_h2[16]; /* index (c2<<2 | c3): cos(th3[c3]) * (cos, sin)(th2[c2])  */
+    uint32_t tb_h2[16]; /* index (c3<<2 | c2): sin(th3[c3]) * (cos, sin)(th2[c2])  */
+    /* Every column of the binary16 tables is stored times a constant in [1, 2)
+       chosen so that its entries round to binary16 with the least error; a value
+       rebuilt with them for coordinate i of a block is sigma[i] times too large.
+       The query is divided by sigma before the scores, the output after the sum. */
+    float sigma[16];
+};
+
+/* Per-device constant buffers of a context (created on first use). */
+struct PqDeviceState {
+    bool ready = false;
+    PqDeviceConsts *consts = nullptr; /* device */
+    float *S_f32 = nullptr;           /* device [128][128], S[i][j]              */
+    float *St_f32 = nullptr;          /* device [128][128], St[j][i] = S[i][j]   */
+    uint16_t *S_bf16x3 = nullptr;     /* device: three bf16 terms of S in MFMA operand order */
+};
+
+#define PQ_MAX_DEVICES 16
+
+struct pq_ctx {
+    int d;
+    uint64_t seed;
+    double S[PQ_D * PQ_D];
+    double centroids[4][16];
+    double boundaries[4][17];
+    PqDeviceConsts host_consts;
+    std::mutex mu;
+    PqDeviceState dev[PQ_MAX_DEVICES];
+};
+
+/* Returns the constant buffers of the current device, uploading them on the
+ * first call per device.  PQ_EHIP if there is no usable device. */
+pq_status pq_device_state(const pq_ctx *ctx, const PqDeviceState **out);
+
+#define PQ_HIP_TRY(expr)                         \
+    do {                                         \
+        hipError_t e__ = (expr);                 \
+        if (e__ != hipSuccess) return PQ_EHIP;   \
+    } while (0)
+
+/* Optional timing of the two dominant kernels with HIP events on the caller's
+ * stream (see pq_profile_begin / pq_profile_end).  kind: 0 attention partial
+ * kernel, 1 encode kernel.  No-ops unless profiling is on. */
+void pq_prof_before(int kind, hipStream_t s);
+void pq_prof_after(int kind, hipStream_t s);
+
+static inline bool pq_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+/* Layout of S_bf16x3 (halves): [term 3][row-tile 4][k-step 8][lane 64][8].
+ * Lane l = 32*kg + i of (term, rt, ks) holds S_term[16*ks + 8*kg + e][col(rt, i)]
+ * for e = 0..7, where the 32 rows of row-tile rt map to rotated coordinates
+ * col(rt, i) = 16*(4*((i>>2)&1) + rt) + 4*(i>>3) + (i&3). */
+#define PQ_SB_TERM_STRIDE (4 * 8 * 64 * 8)
+
+#endif

@@ -1,0 +1,382 @@
+/*
+ * pq_encode.hip -- pq_encode_kv / pq_append_kv: Algorithm 1 lines 2 and 4
+ * (precondition with S, procedure Polar, procedure Quant) plus bit-packing
+ * into the tile layout, for gfx950.
+ *
+ * One wavefront owns one destination tile (64 token slots of one head plane).
+ *   1. y = x * S on the matrix cores.  S is held as three bf16 terms
+ *      S1 + S2 + S3 (24 significant bits) so that bf16 MFMAs with fp32
+ *      accumulation reproduce an fp32-accurate rotation; bf16 inputs are
+ *      exact operands, fp32 inputs are split the same way (x1 + x2 + x3) and
+ *      the six products above 2^-24 are accumulated.
+ *      The product is computed transposed, D = S^T-tile (32 rotated
+ *      coordinates) x X^T (32 vectors), with the rows of each S^T tile
+ *      ordered so that a lane ends up with complete blocks of 16 consecutive
+ *      rotated coordinates of one vector in its accumulator registers: the
+ *      whole polar recursion of a block is then register-local.
+ *   2. Four polar levels per block; every angle is quantised by comparing
+ *      in the tangent domain (v > tan(t) * u for each inner boundary t),
+ *      which is the nearest-centroid rule of procedure Quant without
+ *      evaluating an arctangent.
+ *   3. The fields are scattered into an image of the tile in LDS and the
+ *      image is written out with full-width stores.
+ */
+#include "pq_common.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWaves = 8;                 /* wavefronts per workgroup */
+constexpr int kThreads = kWaves * 64;
+constexpr int kImgDwords = (PQL_CODE_BYTES + PQL_RADII * 2) / 4; /* 992 */
+constexpr int kSChunks = 3 * 4 * 8 * 64;  /* 16-byte chunks of the bf16x3 copy of S */
+
+struct EncodeArgs {
+    const void *x;
+    int64_t ld_token, ld_head;
+    uint8_t *codes;
+    uint16_t *radii;
+    int64_t pool_tiles;
+    int64_t pool_tokens;
+    /* bulk mode: tokens [dst0, dst0 + n) */
+    int64_t dst0, n_tokens;
+    int64_t first_tile, n_tiles; /* tiles spanned by the range */
+    /* append mode: one token per sequence at dst_token[seq] */
+    const int64_t *dst_token;
+    int n_seq;
+    int n_heads;
+    int64_t n_items;
+    const uint4 *S_bf16x3;
+    const PqDeviceConsts *consts;
+};
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+__device__ __forceinline__ uint32_t bf16_rne_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+union BOperand {
+    bf16x8 v;
+    uint4 q;
+    uint32_t w[4];
+};
+
+/* Set `width` bits at bit offset `bit` (from the start of the image) to v.
+ * The image is shared by the lanes of one wavefront: LDS atomics keep
+ * concurrent updates of neighbouring fields in one dword intact. */
+template <bool CLEAR>
+__device__ __forceinline__ void put_bits(uint32_t *img, uint32_t bit, int width, uint32_t v)
+{
+    uint32_t dw = bit >> 5, sh = bit & 31;
+    uint32_t mask = (1u << width) - 1u;
+    if (CLEAR) atomicAnd(&img[dw], ~(mask << sh));
+    atomicOr(&img[dw], v << sh);
+    if (sh + width > 32) {
+        uint32_t done = 32 - sh;
+        if (CLEAR) atomicAnd(&img[dw + 1], ~(mask >> done));
+        atomicOr(&img[dw + 1], v >> done);
+    }
+}
+
+/* Quantise one quadrant angle: number of inner boundaries below atan(v/u). */
+__device__ __forceinline__ uint32_t quant3(float u, float v, float t1, float t3)
+{
+    return (uint32_t)(v > t1 * u) + (uint32_t)(v > u) + (uint32_t)(v > t3 * u);
+}
+
+template <int XT, int KIND, bool APPEND>
+__global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
+{
+    __shared__ uint4 sS[kSChunks];                  /* 96 KB: S1, S2, S3 in A-operand order */
+    __shared__ uint32_t sImg[kWaves][kImgDwords];   /* one tile image per wavefront */
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int c = threadIdx.x; c < kSChunks; c += kThreads) sS[c] = a.S_bf16x3[c];
+    __syncthreads();
+
+    const PqDeviceConsts &K = *a.consts;
+    const float t1a = K.tan_b[0][0], t1c = K.tan_b[0][2];
+    const float t2a = K.tan_b[1][0], t2c = K.tan_b[1][2];
+    const float t3a = K.tan_b[2][0], t3c = K.tan_b[2][2];
+    const float t4a = K.tan_b[3][0], t4c = K.tan_b[3][2];
+
+    uint32_t *img = sImg[wave];
+    const int j = lane & 31, H = lane >> 5; /* vector within the 32-vector group, lane half */
+
+    for (int64_t item = (int64_t)blockIdx.x * kWaves + wave; item < a.n_items; item += (int64_t)gridDim.x * kWaves) {
+        /* ---- which tile, which source rows ---- */
+        int head;
+        int64_t tile;      /* tile index inside the head plane */
+        int tau_lo, tau_hi; /* slots [tau_lo, tau_hi) of the tile are written */
+        int64_t src_t0;    /* source token index of slot tau_lo */
+        if (APPEND) {
+            int seq = (int)(item / a.n_heads);
+            head = (int)(item % a.n_heads);
+            int64_t dst = a.dst_token[seq];
+            if (dst < 0 || dst >= a.pool_tokens) continue; /* slot outside the pool: nothing is written */
+            tile = dst >> 6;
+            tau_lo = (int)(dst & 63);
+            tau_hi = tau_lo + 1;
+            src_t0 = seq;
+        } else {
+            head = (int)(item / a.n_tiles);
+            int64_t trel = item % a.n_tiles;
+            tile = a.first_tile + trel;
+            int64_t lo = tile * 64 > a.dst0 ? tile * 64 : a.dst0;
+            int64_t hi = (tile + 1) * 64 < a.dst0 + a.n_tokens ? (tile + 1) * 64 : a.dst0 + a.n_tokens;
+            tau_lo = (int)(lo - tile * 64);
+            tau_hi = (int)(hi - tile * 64);
+            src_t0 = lo - a.dst0;
+        }
+        const bool full = (tau_lo == 0 && tau_hi == 64);
+        uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
+        uint16_t *gradii = a.radii + ((int64_t)head * a.pool_tiles + tile) * PQL_RADII;
+
+        /* ---- tile image: zeros, or the tile's present contents if only part of it is written ---- */
+        if (full) {
+            for (int c = lane; c < kImgDwords; c += 64) img[c] = 0u;
+        } else {
+            const uint32_t *gc = reinterpret_cast<const uint32_t *>(gcodes);
+            const uint32_t *gr = reinterpret_cast<const uint32_t *>(gradii);
+            for (int c = lane; c < PQL_CODE_BYTES / 4; c += 64) img[c] = gc[c];
+            for (int c = lane; c < PQL_RADII / 2; c += 64) img[PQL_CODE_BYTES / 4 + c] = gr[c];
+        }
+        wave_lds_sync();
+
+        for (int vt = 0; vt < 2; ++vt) {
+            const int tau = 32 * vt + j;
+            /* wave-uniform skip of a half tile with nothing to write */
+            if (32 * vt + 32 <= tau_lo || 32 * vt >= tau_hi) continue;
+            const bool valid = tau >= tau_lo && tau < tau_hi;
+
+            /* ---- B operand: this lane's 8-coordinate slices of its vector, every k-step ---- */
+            constexpr int NXT = (XT == PQ_BF16) ? 1 : 3; /* bf16 terms of x */
+            BOperand xb[NXT][8];
+            {
+                int64_t t_src = src_t0 + (tau - tau_lo);
+                int64_t row = APPEND ? ((int64_t)t_src * a.n_heads + head) * PQ_D
+                                     : t_src * a.ld_token + (int64_t)head * a.ld_head;
+                if constexpr (XT == PQ_BF16) {
+                    const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.x) + row);
+#pragma unroll
+                    for (int ks = 0; ks < 8; ++ks) {
+                        uint4 v = make_uint4(0, 0, 0, 0);
+                        if (valid) v = xr[2 * ks + H];
+                        xb[0][ks].q = v;
+                    }
+                } else {
+                    const float4 *xr = reinterpret_cast<const float4 *>(static_cast<const float *>(a.x) + row);
+#pragma unroll
+                    for (int ks = 0; ks < 8; ++ks) {
+                        float f[8];
+                        float4 p0 = make_float4(0, 0, 0, 0), p1 = p0;
+                        if (valid) { p0 = xr[4 * ks + 2 * H]; p1 = xr[4 * ks + 2 * H + 1]; }
+                        f[0] = p0.x; f[1] = p0.y; f[2] = p0.z; f[3] = p0.w;
+                        f[4] = p1.x; f[5] = p1.y; f[6] = p1.z; f[7] = p1.w;
+#pragma unroll
+                        for (int e = 0; e < 8; e += 2) {
+                            uint32_t w1[2], w2[2], w3[2];
+#pragma unroll
+                            for (int z = 0; z < 2; ++z) {
+                                float v = f[e + z];
+                                uint32_t b1 = bf16_rne_bits(v);
+                                float r1 = v - __uint_as_float(b1 << 16);
+                                uint32_t b2 = bf16_rne_bits(r1);
+                                float r2 = r1 - __uint_as_float(b2 << 16);
+                                uint32_t b3 = bf16_rne_bits(r2);
+                                w1[z] = b1; w2[z] = b2; w3[z] = b3;
+                            }
+                            xb[0][ks].w[e / 2] = w1[0] | (w1[1] << 16);
+                            xb[1][ks].w[e / 2] = w2[0] | (w2[1] << 16);
+                            xb[2][ks].w[e / 2] = w3[0] | (w3[1] << 16);
+                        }
+                    }
+                }
+            }
+
+#pragma unroll 1
+            for (int rt = 0; rt < 4; ++rt) {
+                /* ---- D[i][j] = sum_k S[k][col(rt,i)] * x[j][k]: 32 rotated coordinates x 32 vectors ---- */
+                f32x16 acc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    /* smallest terms first */
+#pragma unroll
+                    for (int term = 2; term >= 0; --term) {
+                        BOperand sa;
+                        sa.q = sS[((term * 4 + rt) * 8 + ks) * 64 + lane];
+#pragma unroll
+                        for (int xt = 0; xt < NXT; ++xt) {
+                            if (xt + term > 2) continue; /* below 2^-24 of the leading product */
+                            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa.v, xb[xt][ks].v, acc, 0, 0, 0);
+                        }
+                    }
+                }
+                /* lane (H, j): acc[r] = rotated coordinate 16*(4H + rt) + r of vector tau */
+                const int b = 4 * H + rt;
+
+                /* ---- procedure Polar on the block, with procedure Quant folded in ---- */
+                float r1[8];
+                uint32_t l1 = 0;
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    float ya = acc[2 * p], yb = acc[2 * p + 1];
+                    float ua = fabsf(ya), ub = fabsf(yb);
+                    uint32_t mq = quant3(ua, ub, t1a, t1c);
+                    /* quadrant of atan2(yb, ya) in [0, 2 pi): cells are pi/8 wide */
+                    uint32_t code = (ya < 0.0f) ? ((yb < 0.0f) ? 8u + mq : 7u - mq)
+                                                : ((yb < 0.0f) ? 15u - mq : mq);
+                    l1 |= code << (4 * p);
+                    r1[p] = __builtin_amdgcn_sqrtf(ya * ya + yb * yb);
+                }
+                float r2[4];
+                uint32_t c2[4];
+#pragma unroll
+                for (int n = 0; n < 4; ++n) {
+                    c2[n] = quant3(r1[2 * n], r1[2 * n + 1], t2a, t2c);
+                    r2[n] = __builtin_amdgcn_sqrtf(r1[2 * n] * r1[2 * n] + r1[2 * n + 1] * r1[2 * n + 1]);
+                }
+                float r3[2];
+                uint32_t c3[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    c3[h] = quant3(r2[2 * h], r2[2 * h + 1], t3a, t3c);
+                    r3[h] = __builtin_amdgcn_sqrtf(r2[2 * h] * r2[2 * h] + r2[2 * h + 1] * r2[2 * h + 1]);
+                }
+                uint32_t c4 = quant3(r3[0], r3[1], t4a, t4c);
+                float r4 = __builtin_amdgcn_sqrtf(r3[0] * r3[0] + r3[1] * r3[1]);
+                _Float16 rh = (_Float16)r4; /* round to nearest even */
+                uint16_t rbits = __builtin_bit_cast(uint16_t, rh);
+
+                /* ---- scatter the block's fields into the tile image ---- */
+                if (valid) {
+                    PqBlockPos pos = pql_pos(KIND, tau, b);
+                    uint16_t *img16 = reinterpret_cast<uint16_t *>(img);
+                    img16[pos.l1_byte[0] >> 1] = (uint16_t)(l1 & 0xFFFFu);
+                    img16[pos.l1_byte[1] >> 1] = (uint16_t)(l1 >> 16);
+                    uint32_t g0 = (c2[0] << 4) | (c3[0] << 2) | c2[1];
+                    uint32_t g1 = (c2[2] << 4) | (c3[1] << 2) | c2[3];
+                    if (full) {
+                        put_bits<false>(img, pos.g6_bit[0], 6, g0);
+                        put_bits<false>(img, pos.g6_bit[1], 6, g1);
+                        put_bits<false>(img, pos.c4_bit, 2, c4);
+                    } else {
+                        put_bits<true>(img, pos.g6_bit[0], 6, g0);
+                        put_bits<true>(img, pos.g6_bit[1], 6, g1);
+                        put_bits<true>(img, pos.c4_bit, 2, c4);
+                    }
+                    img16[PQL_CODE_BYTES / 2 + pos.radius_half] = rbits;
+                }
+            }
+        }
+        wave_lds_sync();
+
+        /* ---- image -> global, 16 bytes per lane per store ---- */
+        {
+            const uint4 *src = reinterpret_cast<const uint4 *>(img);
+            uint4 *dc = reinterpret_cast<uint4 *>(gcodes);
+            uint4 *dr = reinterpret_cast<uint4 *>(gradii);
+            for (int c = lane; c < PQL_CODE_BYTES / 16; c += 64) dc[c] = src[c];
+            for (int c = lane; c < PQL_RADII * 2 / 16; c += 64) dr[c] = src[PQL_CODE_BYTES / 16 + c];
+        }
+        wave_lds_sync();
+    }
+}
+
+template <int XT, int KIND, bool APPEND>
+pq_status launch_encode(const EncodeArgs &a, hipStream_t stream)
+{
+    int dev = 0, cus = 256;
+    PQ_HIP_TRY(hipGetDevice(&dev));
+    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    int64_t blocks = (a.n_items + kWaves - 1) / kWaves;
+    if (blocks > cus) blocks = cus;
+    if (blocks < 1) blocks = 1;
+    pq_prof_before(1, stream);
+    hipLaunchKernelGGL((pq_encode_kernel<XT, KIND, APPEND>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a);
+    pq_prof_after(1, stream);
+    PQ_HIP_TRY(hipGetLastError());
+    return PQ_OK;
+}
+
+template <bool APPEND>
+pq_status dispatch_encode(const EncodeArgs &a, pq_dtype xt, pq_kind kind, hipStream_t stream)
+{
+    if (xt == PQ_BF16)
+        return kind == PQ_KEY ? launch_encode<PQ_BF16, PQ_KEY, APPEND>(a, stream)
+                              : launch_encode<PQ_BF16, PQ_VALUE, APPEND>(a, stream);
+    return kind == PQ_KEY ? launch_encode<PQ_F32, PQ_KEY, APPEND>(a, stream)
+                          : launch_encode<PQ_F32, PQ_VALUE, APPEND>(a, stream);
+}
+
+} // namespace
+
+extern "C" const char *pq_kernel_name_encode(void) { return "pq_encode_kernel"; }
+
+extern "C" pq_status pq_encode_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,
+                                  int64_t n_tokens, int n_heads, int64_t ld_token, int64_t ld_head,
+                                  uint8_t *codes, uint16_t *radii, int64_t pool_tokens,
+                                  int64_t dst_token0, void *hip_stream)
+{
+    if (!ctx) return PQ_EINVAL;
+    if (n_tokens == 0) return PQ_OK;
+    if (!x || !codes || !radii) return PQ_EINVAL;
+    if (xt != PQ_F32 && xt != PQ_BF16) return PQ_EINVAL;
+    if (kind != PQ_KEY && kind != PQ_VALUE) return PQ_EINVAL;
+    if (n_tokens < 0 || n_heads <= 0 || pool_tokens <= 0 || (pool_tokens & 63) || dst_token0 < 0) return PQ_EINVAL;
+    if (dst_token0 + n_tokens > pool_tokens) return PQ_EINVAL;
+    if (ld_token < 0 || ld_head < 0) return PQ_EINVAL;
+    const int64_t elems16 = xt == PQ_BF16 ? 8 : 4;
+    if (!pq_aligned16(x) || !pq_aligned16(codes) || !pq_aligned16(radii)) return PQ_EALIGN;
+    if ((ld_token % elems16) || (ld_head % elems16)) return PQ_EALIGN;
+    const PqDeviceState *ds = nullptr;
+    pq_status st = pq_device_state(ctx, &ds);
+    if (st != PQ_OK) return st;
+    EncodeArgs a{};
+    a.x = x; a.ld_token = ld_token; a.ld_head = ld_head;
+    a.codes = codes; a.radii = radii; a.pool_tiles = pool_tokens / 64; a.pool_tokens = pool_tokens;
+    a.dst0 = dst_token0; a.n_tokens = n_tokens;
+    a.first_tile = dst_token0 / 64;
+    a.n_tiles = (dst_token0 + n_tokens + 63) / 64 - a.first_tile;
+    a.n_heads = n_heads;
+    a.n_items = a.n_tiles * n_heads;
+    a.S_bf16x3 = reinterpret_cast<const uint4 *>(ds->S_bf16x3);
+    a.consts = ds->consts;
+    return dispatch_encode<false>(a, xt, kind, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,
+                                  int n_seq, int n_heads, uint8_t *codes, uint16_t *radii,
+                                  int64_t pool_tokens, const int64_t *dst_token, void *hip_stream)
+{
+    if (!ctx) return PQ_EINVAL;
+    if (n_seq == 0) return PQ_OK;
+    if (!x || !codes || !radii || !dst_token) return PQ_EINVAL;
+    if (xt != PQ_F32 && xt != PQ_BF16) return PQ_EINVAL;
+    if (kind != PQ_KEY && kind != PQ_VALUE) return PQ_EINVAL;
+    if (n_seq < 0 || n_heads <= 0 || pool_tokens <= 0 || (pool_tokens & 63)) return PQ_EINVAL;
+    if (!pq_aligned16(x) || !pq_aligned16(codes) || !pq_aligned16(radii)) return PQ_EALIGN;
+    const PqDeviceState *ds = nullptr;
+    pq_status st = pq_device_state(ctx, &ds);
+    if (st != PQ_OK) return st;
+    EncodeArgs a{};
+    a.x = x;
+    a.codes = codes; a.radii = radii; a.pool_tiles = pool_tokens / 64; a.pool_tokens = pool_tokens;
+    a.dst_token = dst_token; a.n_seq = n_seq; a.n_heads = n_heads;
+    a.n_items = (int64_t)n_seq * n_heads;
+    a.S_bf16x3 = reinterpret_cast<const uint4 *>(ds->S_bf16x3);
+    a.consts = ds->consts;
+    return dispatch_encode<true>(a, xt, kind, static_cast<hipStream_t>(hip_stream));
+}

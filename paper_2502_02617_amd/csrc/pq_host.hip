@@ -1,0 +1,473 @@
+/*
+ * pq_host.hip -- host side of libpolarquant: context creation (random
+ * rotation S, Lloyd-Max codebooks of the closed-form angle densities, lookup
+ * tables), per-device upload of the constants, small utilities.
+ *
+ * Everything here is double precision on the CPU and runs once per model
+ * (Section 4.1: S and the offline codebook are shared by all layers, heads
+ * and prompts).
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "pq_common.h"
+
+namespace {
+
+const double kPi = 3.14159265358979323846264338327950288;
+
+/* ---- counter-based Gaussian generator: splitmix64 finaliser + Box-Muller ---- */
+uint64_t splitmix_finalise(uint64_t z)
+{
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27; z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+
+double uniform_open01(uint64_t seed_mixed, uint64_t counter)
+{
+    uint64_t bits = splitmix_finalise(seed_mixed + (counter + 1) * 0x9E3779B97F4A7C15ULL);
+    return ((double)(bits >> 11) + 0.5) * 0x1.0p-53;
+}
+
+void fill_gaussian(uint64_t seed, int d, std::vector<double> &G)
+{
+    const uint64_t sm = splitmix_finalise(seed);
+    G.resize((size_t)d * d);
+    for (size_t c = 0; c < (size_t)d * d; ++c) {
+        double u1 = uniform_open01(sm, 2 * c), u2 = uniform_open01(sm, 2 * c + 1);
+        G[c] = sqrt(-2.0 * log(u1)) * cos(2.0 * kPi * u2);
+    }
+}
+
+/* ---- S = Q of the QR factorisation with positive diag(R): the columns of G
+ * orthonormalised in order (modified Gram-Schmidt, each projection pass done
+ * twice so that orthogonality holds to rounding). ---- */
+bool orthonormalise_columns(const std::vector<double> &G, int d, double *S)
+{
+    std::vector<double> col(d);
+    for (int j = 0; j < d; ++j) {
+        for (int i = 0; i < d; ++i) col[i] = G[(size_t)i * d + j];
+        for (int pass = 0; pass < 2; ++pass)
+            for (int p = 0; p < j; ++p) {
+                double dot = 0.0;
+                for (int i = 0; i < d; ++i) dot += S[(size_t)i * d + p] * col[i];
+                for (int i = 0; i < d; ++i) col[i] -= dot * S[(size_t)i * d + p];
+            }
+        double nrm = 0.0;
+        for (int i = 0; i < d; ++i) nrm += col[i] * col[i];
+        nrm = sqrt(nrm);
+        if (!(nrm > 1e-300)) return false;
+        for (int i = 0; i < d; ++i) S[(size_t)i * d + j] = col[i] / nrm;
+    }
+    return true;
+}
+
+double orthogonality_defect(const double *S, int d)
+{
+    double worst = 0.0;
+    for (int a = 0; a < d; ++a)
+        for (int b = a; b < d; ++b) {
+            double dot = 0.0;
+            for (int i = 0; i < d; ++i) dot += S[(size_t)i * d + a] * S[(size_t)i * d + b];
+            double e = fabs(dot - (a == b ? 1.0 : 0.0));
+            if (e > worst) worst = e;
+        }
+    return worst;
+}
+
+/* ---- Lloyd-Max quantiser of f_l(psi) ~ sin^m(2 psi), m = 2^(l-1) - 1 (Lemma 2),
+ * on [0, pi/2], with closed-form moments: for odd m
+ *   sin^m(u) = 2^(1-m) * sum_{k=0}^{(m-1)/2} (-1)^((m-1)/2-k) C(m,k) sin((m-2k) u),
+ * so the integrals of sin^m(2 psi) and psi*sin^m(2 psi) are finite sums of
+ * elementary antiderivatives. ---- */
+struct SinPower {
+    int terms;
+    double coef[8], freq[8]; /* sin^m(2 psi) = sum coef[k] * sin(freq[k] * psi) */
+};
+
+SinPower make_sin_power(int m)
+{
+    SinPower sp;
+    sp.terms = (m + 1) / 2;
+    double binom = 1.0; /* C(m, k) */
+    for (int k = 0; k < sp.terms; ++k) {
+        double sign = (((m - 1) / 2 - k) & 1) ? -1.0 : 1.0;
+        sp.coef[k] = sign * binom * ldexp(1.0, 1 - m);
+        sp.freq[k] = 2.0 * (m - 2 * k);
+        binom = binom * (m - k) / (k + 1);
+    }
+    return sp;
+}
+
+double mass_antiderivative(const SinPower &sp, double x) /* int sin^m(2x) dx */
+{
+    double acc = 0.0;
+    for (int k = 0; k < sp.terms; ++k) acc += sp.coef[k] * (-cos(sp.freq[k] * x) / sp.freq[k]);
+    return acc;
+}
+
+double first_moment_antiderivative(const SinPower &sp, double x) /* int x sin^m(2x) dx */
+{
+    double acc = 0.0;
+    for (int k = 0; k < sp.terms; ++k) {
+        double a = sp.freq[k];
+        acc += sp.coef[k] * (-x * cos(a * x) / a + sin(a * x) / (a * a));
+    }
+    return acc;
+}
+
+void lloyd_max_level(int level, double *centroids /*4*/, double *boundaries /*5*/)
+{
+    const int K = 4;
+    const SinPower sp = make_sin_power((1 << (level - 1)) - 1);
+    const double lo = 0.0, hi = kPi / 2.0;
+    for (int k = 0; k < K; ++k) centroids[k] = hi * (k + 0.5) / K;
+    for (int it = 0; it < 200000; ++it) {
+        boundaries[0] = lo; boundaries[K] = hi;
+        for (int k = 1; k < K; ++k) boundaries[k] = 0.5 * (centroids[k - 1] + centroids[k]);
+        double moved = 0.0;
+        for (int k = 0; k < K; ++k) {
+            double mass = mass_antiderivative(sp, boundaries[k + 1]) - mass_antiderivative(sp, boundaries[k]);
+            double mom = first_moment_antiderivative(sp, boundaries[k + 1]) - first_moment_antiderivative(sp, boundaries[k]);
+            double c = mom / mass;
+            moved = fmax(moved, fabs(c - centroids[k]));
+            centroids[k] = c;
+        }
+        if (moved < 1e-15) break;
+    }
+    boundaries[0] = lo; boundaries[K] = hi;
+    for (int k = 1; k < K; ++k) boundaries[k] = 0.5 * (centroids[k - 1] + centroids[k]);
+}
+
+/* ---- binary16 / bfloat16 from double, round to nearest even ---- */
+uint16_t to_binary16(double v)
+{
+    /* bit-level conversion of a finite double with one rounding step */
+    uint64_t u;
+    memcpy(&u, &v, 8);
+    uint16_t sign = (uint16_t)((u >> 48) & 0x8000u);
+    int exp = (int)((u >> 52) & 0x7FF) - 1023;
+    uint64_t frac = (u & 0xFFFFFFFFFFFFFULL) | (1ULL << 52); /* 1.frac, 53 bits */
+    if (((u >> 52) & 0x7FF) == 0) return sign;             /* zero / double subnormal */
+    if (exp > 15) return (uint16_t)(sign | 0x7C00u);
+    int drop = 42;                                          /* keep 11 significant bits */
+    if (exp < -14) drop += -14 - exp;                       /* binary16 subnormal: fewer bits */
+    if (drop > 63) return sign;
+    uint64_t kept = frac >> drop, rest = frac & ((1ULL << drop) - 1), half = 1ULL << (drop - 1);
+    if (rest > half || (rest == half && (kept & 1))) kept += 1;
+    if (exp < -14) return (uint16_t)(sign | (uint16_t)kept); /* kept == 1024 becomes the smallest normal */
+    if (kept == 2048) { kept = 1024; exp += 1; if (exp > 15) return (uint16_t)(sign | 0x7C00u); }
+    return (uint16_t)(sign | (uint16_t)((exp + 15) << 10) | (uint16_t)(kept - 1024));
+}
+
+uint32_t pack_h2(double lo, double hi) { return (uint32_t)to_binary16(lo) | ((uint32_t)to_binary16(hi) << 16); }
+
+uint16_t to_bfloat16(double v)
+{
+    float f = (float)v;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    /* the double -> float step is exact for the values used here or loses
+       bits far below bf16's 8-bit significand; round the float to bf16 */
+    uint32_t rounded = u + 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(rounded >> 16);
+}
+
+double from_bfloat16(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+double from_binary16(uint16_t h)
+{
+    int e = (h >> 10) & 31, m = h & 1023;
+    double v = e == 0 ? ldexp((double)m, -24) : ldexp(1024.0 + m, e - 25);
+    return (h & 0x8000) ? -v : v;
+}
+
+/* Scale in [1, 2) for which vals[0..n) * scale round to binary16 with the least
+ * root-mean-square relative error.  The rounding errors of a lookup table are
+ * the same for every token and do not average out in the attention sums; with
+ * only 4..16 distinct magnitudes per column a good common scale removes most
+ * of them at no run-time cost. */
+double best_table_scale(const double *vals, int n)
+{
+    double best_s = 1.0, best_e = 1e300;
+    for (int k = 0; k < 65536; ++k) {
+        double sc = 1.0 + k / 65536.0, e = 0.0;
+        for (int i = 0; i < n; ++i) {
+            double x = fabs(vals[i]) * sc;
+            double d = (from_binary16(to_binary16(x)) - x) / x;
+            e += d * d;
+        }
+        if (e < best_e) { best_e = e; best_s = sc; }
+    }
+    return best_s;
+}
+
+void build_tables(pq_ctx *ctx)
+{
+    PqDeviceConsts &c = ctx->host_consts;
+    memset(&c, 0, sizeof(c));
+    for (int l = 1; l <= 4; ++l) {
+        const double *bnd = ctx->boundaries[l - 1];
+        if (l == 1) {
+            c.tan_b[0][0] = (float)tan(kPi / 8.0);
+            c.tan_b[0][1] = 1.0f;
+            c.tan_b[0][2] = (float)tan(3.0 * kPi / 8.0);
+        } else {
+            c.tan_b[l - 1][0] = (float)tan(bnd[1]);
+            c.tan_b[l - 1][1] = 1.0f; /* middle boundary is pi/4 by symmetry of the density */
+            c.tan_b[l - 1][2] = (float)tan(bnd[3]);
+        }
+    }
+    for (int k = 0; k < 16; ++k) {
+        double t = ctx->centroids[0][k];
+        c.cs1[k][0] = (float)cos(t);
+        c.cs1[k][1] = (float)sin(t);
+    }
+    for (int l = 2; l <= 4; ++l)
+        for (int k = 0; k < 4; ++k) {
+            double t = ctx->centroids[l - 1][k];
+            c.cs234[l - 2][k][0] = (float)cos(t);
+            c.cs234[l - 2][k][1] = (float)sin(t);
+        }
+    /* exact table columns: [0] low half, [1] high half of each packed pair */
+    double t1[2][16], t4[2][4], ta[2][16], tb[2][16];
+    for (int k = 0; k < 16; ++k) { t1[0][k] = cos(ctx->centroids[0][k]); t1[1][k] = sin(ctx->centroids[0][k]); }
+    for (int k = 0; k < 4; ++k) { t4[0][k] = cos(ctx->centroids[3][k]); t4[1][k] = sin(ctx->centroids[3][k]); }
+    for (int c2 = 0; c2 < 4; ++c2)
+        for (int c3 = 0; c3 < 4; ++c3) {
+            double th2 = ctx->centroids[1][c2], th3 = ctx->centroids[2][c3];
+            ta[0][(c2 << 2) | c3] = cos(th3) * cos(th2);
+            ta[1][(c2 << 2) | c3] = cos(th3) * sin(th2);
+            tb[0][(c3 << 2) | c2] = sin(th3) * cos(th2);
+            tb[1][(c3 << 2) | c2] = sin(th3) * sin(th2);
+        }
+    double s1[2], s4[2], sa[2], sb[2];
+    for (int col = 0; col < 2; ++col) {
+        s1[col] = best_table_scale(t1[col], 16);
+        s4[col] = best_table_scale(t4[col], 4);
+        sa[col] = best_table_scale(ta[col], 16);
+        sb[col] = best_table_scale(tb[col], 16);
+    }
+    for (int k = 0; k < 16; ++k) {
+        c.t1_h2[k] = pack_h2(t1[0][k] * s1[0], t1[1][k] * s1[1]);
+        c.ta_h2[k] = pack_h2(ta[0][k] * sa[0], ta[1][k] * sa[1]);
+        c.tb_h2[k] = pack_h2(tb[0][k] * sb[0], tb[1][k] * sb[1]);
+    }
+    for (int k = 0; k < 4; ++k) c.t4_h2[k] = pack_h2(t4[0][k] * s4[0], t4[1][k] * s4[1]);
+    /* coordinate i of a block: half-block h = i>>3 (level-4 side), pair q = (i>>1)&3
+       (q < 2: table A, else table B; q&1: its low / high half), parity i&1 (level-1 cos / sin) */
+    for (int i = 0; i < 16; ++i) {
+        int h = i >> 3, q = (i >> 1) & 3, par = i & 1;
+        c.sigma[i] = (float)(s4[h] * (q < 2 ? sa[q & 1] : sb[q & 1]) * s1[par]);
+    }
+}
+
+} // namespace
+
+extern "C" const char *pq_status_string(pq_status s)
+{
+    switch (s) {
+    case PQ_OK: return "PQ_OK";
+    case PQ_EINVAL: return "PQ_EINVAL: invalid argument";
+    case PQ_EUNSUPPORTED: return "PQ_EUNSUPPORTED: configuration not supported";
+    case PQ_EALIGN: return "PQ_EALIGN: device pointer or stride not 16-byte aligned";
+    case PQ_EHIP: return "PQ_EHIP: HIP runtime error or no device";
+    case PQ_ENOMEM: return "PQ_ENOMEM: allocation failed or workspace too small";
+    }
+    return "unknown pq_status";
+}
+
+extern "C" pq_status pq_init_preconditioner(pq_ctx **out, int d, uint64_t seed, const double *S_in)
+{
+    if (!out) return PQ_EINVAL;
+    *out = nullptr;
+    if (d != PQ_D) return PQ_EUNSUPPORTED;
+    pq_ctx *ctx = new (std::nothrow) pq_ctx();
+    if (!ctx) return PQ_ENOMEM;
+    ctx->d = d;
+    ctx->seed = seed;
+    if (S_in) {
+        memcpy(ctx->S, S_in, sizeof(double) * d * d);
+        for (int i = 0; i < d * d; ++i)
+            if (!isfinite(ctx->S[i])) { delete ctx; return PQ_EINVAL; }
+        if (!(orthogonality_defect(ctx->S, d) <= 1e-10)) { delete ctx; return PQ_EINVAL; }
+    } else {
+        std::vector<double> G;
+        fill_gaussian(seed, d, G);
+        if (!orthonormalise_columns(G, d, ctx->S)) { delete ctx; return PQ_EINVAL; }
+    }
+    /* level 1: uniform density on [0, 2 pi): equal cells, centroids at their middles */
+    for (int k = 0; k < 16; ++k) ctx->centroids[0][k] = (k + 0.5) * kPi / 8.0;
+    for (int k = 0; k <= 16; ++k) ctx->boundaries[0][k] = k * kPi / 8.0;
+    for (int l = 2; l <= 4; ++l) lloyd_max_level(l, ctx->centroids[l - 1], ctx->boundaries[l - 1]);
+    build_tables(ctx);
+    *out = ctx;
+    return PQ_OK;
+}
+
+extern "C" pq_status pq_get_preconditioner(const pq_ctx *ctx, double *S_out)
+{
+    if (!ctx || !S_out) return PQ_EINVAL;
+    memcpy(S_out, ctx->S, sizeof(double) * PQ_D * PQ_D);
+    return PQ_OK;
+}
+
+extern "C" pq_status pq_get_codebook(const pq_ctx *ctx, int level, double *centroids, double *boundaries)
+{
+    if (!ctx || level < 1 || level > 4) return PQ_EINVAL;
+    int K = level == 1 ? 16 : 4;
+    if (centroids) memcpy(centroids, ctx->centroids[level - 1], sizeof(double) * K);
+    if (boundaries) memcpy(boundaries, ctx->boundaries[level - 1], sizeof(double) * (K + 1));
+    return PQ_OK;
+}
+
+extern "C" void pq_destroy(pq_ctx *ctx)
+{
+    if (!ctx) return;
+    int saved = -1;
+    bool have_dev = hipGetDevice(&saved) == hipSuccess;
+    for (int i = 0; i < PQ_MAX_DEVICES; ++i) {
+        PqDeviceState &s = ctx->dev[i];
+        if (!s.ready) continue;
+        if (hipSetDevice(i) != hipSuccess) continue;
+        (void)hipFree(s.consts);
+        (void)hipFree(s.S_f32);
+        (void)hipFree(s.St_f32);
+        (void)hipFree(s.S_bf16x3);
+    }
+    if (have_dev) (void)hipSetDevice(saved);
+    delete ctx;
+}
+
+pq_status pq_device_state(const pq_ctx *cctx, const PqDeviceState **out)
+{
+    pq_ctx *ctx = const_cast<pq_ctx *>(cctx);
+    int dev = -1;
+    PQ_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= PQ_MAX_DEVICES) return PQ_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(ctx->mu);
+    PqDeviceState &s = ctx->dev[dev];
+    if (!s.ready) {
+        const int d = PQ_D;
+        std::vector<float> Sf((size_t)d * d), Stf((size_t)d * d);
+        for (int i = 0; i < d; ++i)
+            for (int j = 0; j < d; ++j) {
+                Sf[(size_t)i * d + j] = (float)ctx->S[(size_t)i * d + j];
+                Stf[(size_t)j * d + i] = (float)ctx->S[(size_t)i * d + j];
+            }
+        /* S = S1 + S2 + S3 with bf16 terms (24 significant bits in total), stored in
+           the order the encode kernel's matrix-core A operand consumes them. */
+        std::vector<uint16_t> sb((size_t)3 * PQ_SB_TERM_STRIDE);
+        for (int rt = 0; rt < 4; ++rt)
+            for (int ks = 0; ks < 8; ++ks)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int e = 0; e < 8; ++e) {
+                        int kg = lane >> 5, i = lane & 31;
+                        int row = 16 * ks + 8 * kg + e;
+                        int col = 16 * (4 * ((i >> 2) & 1) + rt) + 4 * (i >> 3) + (i & 3);
+                        double v = ctx->S[(size_t)row * d + col];
+                        uint16_t t1 = to_bfloat16(v);
+                        double r1 = v - from_bfloat16(t1);
+                        uint16_t t2 = to_bfloat16(r1);
+                        double r2 = r1 - from_bfloat16(t2);
+                        uint16_t t3 = to_bfloat16(r2);
+                        size_t at = ((((size_t)rt * 8 + ks) * 64 + lane) * 8 + e);
+                        sb[at] = t1;
+                        sb[PQ_SB_TERM_STRIDE + at] = t2;
+                        sb[2 * (size_t)PQ_SB_TERM_STRIDE + at] = t3;
+                    }
+        PqDeviceState t;
+        if (hipMalloc((void **)&t.consts, sizeof(PqDeviceConsts)) != hipSuccess) return PQ_ENOMEM;
+        if (hipMalloc((void **)&t.S_f32, Sf.size() * 4) != hipSuccess) return PQ_ENOMEM;
+        if (hipMalloc((void **)&t.St_f32, Stf.size() * 4) != hipSuccess) return PQ_ENOMEM;
+        if (hipMalloc((void **)&t.S_bf16x3, sb.size() * 2) != hipSuccess) return PQ_ENOMEM;
+        PQ_HIP_TRY(hipMemcpy(t.consts, &ctx->host_consts, sizeof(PqDeviceConsts), hipMemcpyHostToDevice));
+        PQ_HIP_TRY(hipMemcpy(t.S_f32, Sf.data(), Sf.size() * 4, hipMemcpyHostToDevice));
+        PQ_HIP_TRY(hipMemcpy(t.St_f32, Stf.data(), Stf.size() * 4, hipMemcpyHostToDevice));
+        PQ_HIP_TRY(hipMemcpy(t.S_bf16x3, sb.data(), sb.size() * 2, hipMemcpyHostToDevice));
+        t.ready = true;
+        s = t;
+    }
+    *out = &s;
+    return PQ_OK;
+}
+
+/* ---- optional kernel timing with HIP events on the launch stream ---- */
+namespace {
+struct Profiler {
+    std::mutex mu;
+    bool on = false;
+    int cap = 0;
+    std::vector<hipEvent_t> start[2], stop[2];
+    int used[2] = {0, 0};
+} g_prof;
+} // namespace
+
+void pq_prof_before(int kind, hipStream_t s)
+{
+    if (!g_prof.on) return;
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    if (g_prof.on && g_prof.used[kind] < g_prof.cap) (void)hipEventRecord(g_prof.start[kind][g_prof.used[kind]], s);
+}
+
+void pq_prof_after(int kind, hipStream_t s)
+{
+    if (!g_prof.on) return;
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    if (g_prof.on && g_prof.used[kind] < g_prof.cap) {
+        (void)hipEventRecord(g_prof.stop[kind][g_prof.used[kind]], s);
+        g_prof.used[kind] += 1;
+    }
+}
+
+extern "C" pq_status pq_profile_begin(int max_launches)
+{
+    if (max_launches <= 0 || max_launches > 65536) return PQ_EINVAL;
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    if (g_prof.on) return PQ_EINVAL;
+    for (int k = 0; k < 2; ++k) {
+        while ((int)g_prof.start[k].size() < max_launches) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess) return PQ_EHIP;
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return PQ_EHIP; }
+            g_prof.start[k].push_back(a);
+            g_prof.stop[k].push_back(b);
+        }
+        g_prof.used[k] = 0;
+    }
+    g_prof.cap = max_launches;
+    g_prof.on = true;
+    return PQ_OK;
+}
+
+extern "C" pq_status pq_profile_end(double *attn_ms, int *attn_launches, double *encode_ms, int *encode_launches)
+{
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    if (!g_prof.on) return PQ_EINVAL;
+    g_prof.on = false;
+    double total[2] = {0.0, 0.0};
+    for (int k = 0; k < 2; ++k)
+        for (int i = 0; i < g_prof.used[k]; ++i) {
+            float ms = 0.f;
+            if (hipEventSynchronize(g_prof.stop[k][i]) != hipSuccess) return PQ_EHIP;
+            if (hipEventElapsedTime(&ms, g_prof.start[k][i], g_prof.stop[k][i]) != hipSuccess) return PQ_EHIP;
+            total[k] += ms;
+        }
+    if (attn_ms) *attn_ms = total[0];
+    if (attn_launches) *attn_launches = g_prof.used[0];
+    if (encode_ms) *encode_ms = total[1];
+    if (encode_launches) *encode_launches = g_prof.used[1];
+    return PQ_OK;
+}

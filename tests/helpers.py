@@ -1,0 +1,90 @@
+"""Shared helpers of the GPU parity tests: acceptance rules written out once.
+
+Acceptance rules:
+  codes   bit-exact against the fp64 oracle, except where the oracle's exact angle
+          lies within 1e-5 rad of a codebook boundary; there the neighbouring code
+          is accepted; overall mismatch rate <= 1e-4
+  radii   bit-exact binary16, except where the oracle's exact radius lies within
+          a relative 1e-6 of a binary16 rounding boundary; there +-1 ulp is
+          accepted; overall mismatch rate <= 2e-3
+  DeQuant <= 1e-3 relative L2
+  attention <= 2e-3 relative L2 (bf16 inputs and outputs)
+"""
+import math
+
+import numpy as np
+
+import oracle
+
+ANGLE_TOL = 1e-5
+CODE_MISMATCH_RATE = 1e-4
+RADIUS_REL_TOL = 1e-6
+RADIUS_MISMATCH_RATE = 2e-3
+
+_LEVEL_OF = np.concatenate([np.full(64, 1), np.full(32, 2), np.full(16, 3), np.full(8, 4)])
+
+
+def boundary_distance(psi):
+    """psi [n,120] exact oracle angles -> distance to the nearest code boundary."""
+    dist = np.empty_like(psi)
+    step = np.pi / 8
+    a = psi[:, :64]
+    dist[:, :64] = np.abs(a - np.round(a / step) * step)
+    off = 64
+    for level, cnt in ((2, 32), (3, 16), (4, 8)):
+        _, bnd = oracle.codebook(level, 4)
+        inner = bnd[1:4]
+        a = psi[:, off : off + cnt]
+        dist[:, off : off + cnt] = np.min(np.abs(a[..., None] - inner), axis=-1)
+        off += cnt
+    return dist
+
+
+def check_codes(rec_gpu, rec_oracle, psi):
+    """Returns a dict of statistics; raises AssertionError when the acceptance rule fails."""
+    Jg, rg = oracle.unpack(rec_gpu)
+    Jo, ro = oracle.unpack(rec_oracle)
+    bad = Jg != Jo
+    n_bad = int(bad.sum())
+    stats = {"angles": int(Jo.size), "code_mismatches": n_bad, "code_mismatch_rate": n_bad / Jo.size}
+    if n_bad:
+        dist = boundary_distance(psi)
+        worst = float(dist[bad].max())
+        stats["worst_mismatch_boundary_distance"] = worst
+        assert worst <= ANGLE_TOL, f"code mismatch {worst:.3e} rad away from any boundary"
+        diff = np.abs(Jg[bad].astype(np.int64) - Jo[bad])
+        lev = np.broadcast_to(_LEVEL_OF, Jo.shape)[bad]
+        ok = (diff == 1) | ((lev == 1) & (diff == 15))
+        assert np.all(ok), "a mismatching code is not the neighbouring cell"
+    assert stats["code_mismatch_rate"] <= CODE_MISMATCH_RATE, stats
+    return stats, rg, ro
+
+
+def check_radii(rg, ro, y_oracle):
+    """rg, ro uint16 [n,8]; y_oracle [n,128] the oracle's rotated vectors (exact radii)."""
+    bad = rg != ro
+    n_bad = int(bad.sum())
+    stats = {"radii": int(ro.size), "radius_mismatches": n_bad, "radius_mismatch_rate": n_bad / ro.size}
+    if n_bad:
+        r_exact = np.linalg.norm(y_oracle.reshape(-1, 8, 16), axis=2)
+        d = np.abs(rg[bad].astype(np.int64) - ro[bad].astype(np.int64))
+        assert np.all(d == 1), "radius off by more than one binary16 ulp"
+        # the exact radius must sit next to the rounding boundary between the two candidates
+        lo = np.minimum(rg[bad], ro[bad]).astype(np.uint16)
+        hi = (lo + 1).astype(np.uint16)
+        mid = 0.5 * (lo.view(np.float16).astype(np.float64) + hi.view(np.float16).astype(np.float64))
+        rel = np.abs(r_exact[bad] - mid) / mid
+        stats["worst_radius_rel_distance"] = float(rel.max())
+        assert rel.max() <= RADIUS_REL_TOL, f"radius mismatch {rel.max():.3e} (relative) away from a rounding boundary"
+    assert stats["radius_mismatch_rate"] <= RADIUS_MISMATCH_RATE, stats
+    return stats
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def softmax_scale():
+    return 1.0 / math.sqrt(128.0)
