@@ -88,16 +88,86 @@ __device__ __forceinline__ h2 lut(const uint32_t *tab, int table, uint32_t byte_
 __device__ __forceinline__ h2 bcast_lo(h2 v) { return h2{v.x, v.x}; }
 __device__ __forceinline__ h2 bcast_hi(h2 v) { return h2{v.y, v.y}; }
 
-/* The four level-1 radii of a half-block times their (cos, sin) pairs:
- * r3 = (r, r) radius of the level-3 node, g6 = [c2a | c3 | c2b], l1 = 4 level-1 codes. */
-__device__ __forceinline__ void expand_half_block(const uint32_t *tab, h2 r3, uint32_t g6, uint32_t l1, h2 out[4])
+/* Byte offsets (4 * code) of eight 4-bit codes packed in one dword, with 12
+ * operations instead of 16: two masked copies hold the even and the odd codes
+ * already multiplied by four, one per byte, and each offset is then a single
+ * byte extraction.  The empty asm statements keep the compiler from folding
+ * the masks back into per-code shift-and-mask pairs. */
+struct NibbleOffsets {
+    uint32_t even, odd; /* byte k of even: 4 * code 2k; of odd: 4 * code 2k+1 */
+};
+
+__device__ __forceinline__ NibbleOffsets nibble_offsets(uint32_t w)
 {
-    h2 ra = r3 * lut(tab, kTA, (g6 >> 2) << 2);          /* (r1_0, r1_1) */
-    h2 rb = r3 * lut(tab, kTB, (g6 & 15u) << 2);         /* (r1_2, r1_3) */
-    out[0] = bcast_lo(ra) * lut(tab, kT1, (l1 << 2) & 0x3Cu);
-    out[1] = bcast_hi(ra) * lut(tab, kT1, (l1 >> 2) & 0x3Cu);
-    out[2] = bcast_lo(rb) * lut(tab, kT1, (l1 >> 6) & 0x3Cu);
-    out[3] = bcast_hi(rb) * lut(tab, kT1, (l1 >> 10) & 0x3Cu);
+    NibbleOffsets r;
+    r.even = (w << 2) & 0x3C3C3C3Cu;
+    r.odd = (w >> 2) & 0x3C3C3C3Cu;
+    asm("" : "+v"(r.even));
+    asm("" : "+v"(r.odd));
+    return r;
+}
+
+template <int CODE>
+__device__ __forceinline__ uint32_t nibble_offset(const NibbleOffsets &n)
+{
+    const uint32_t src = (CODE & 1) ? n.odd : n.even;
+    constexpr int k = CODE >> 1;
+    if (k == 0) return src & 0xFFu;
+    if (k == 3) return src >> 24;
+    return __builtin_amdgcn_ubfe(src, 8 * k, 8);
+}
+
+/* The same idea for the four 6-bit groups [c2a | c3 | c2b] of a 24-bit string:
+ * offA holds 4*(c2a<<2|c3) and offB holds 4*(c3<<2|c2b) of group k at bits [6k, 6k+6). */
+struct GroupOffsets {
+    uint32_t offA, offB;
+};
+
+__device__ __forceinline__ GroupOffsets group_offsets(uint32_t g24)
+{
+    GroupOffsets r;
+    r.offA = g24 & 0xF3CF3Cu;
+    r.offB = (g24 << 2) & 0xF3CF3Cu;
+    asm("" : "+v"(r.offA));
+    asm("" : "+v"(r.offB));
+    return r;
+}
+
+template <int K>
+__device__ __forceinline__ uint32_t group_offset(uint32_t packed)
+{
+    if (K == 0) return packed & 0x3Fu;
+    if (K == 3) return packed >> 18;
+    return __builtin_amdgcn_ubfe(packed, 6 * K, 6);
+}
+
+/* Table entries of one half-block, fetched before any arithmetic so that the LDS
+ * gathers of a whole block are in flight together. */
+struct HalfBlockLut {
+    h2 ta, tb, t1[4];
+};
+
+__device__ __forceinline__ void gather_half_block(const uint32_t *tab, uint32_t offA, uint32_t offB,
+                                                  uint32_t o0, uint32_t o1, uint32_t o2, uint32_t o3, HalfBlockLut &l)
+{
+    l.ta = lut(tab, kTA, offA);
+    l.tb = lut(tab, kTB, offB);
+    l.t1[0] = lut(tab, kT1, o0);
+    l.t1[1] = lut(tab, kT1, o1);
+    l.t1[2] = lut(tab, kT1, o2);
+    l.t1[3] = lut(tab, kT1, o3);
+}
+
+/* The four level-1 radii of a half-block times their (cos, sin) pairs:
+ * r3 = (r, r) radius of the level-3 node. */
+__device__ __forceinline__ void expand_half_block(h2 r3, const HalfBlockLut &l, h2 out[4])
+{
+    h2 ra = r3 * l.ta; /* (r1_0, r1_1) */
+    h2 rb = r3 * l.tb; /* (r1_2, r1_3) */
+    out[0] = bcast_lo(ra) * l.t1[0];
+    out[1] = bcast_hi(ra) * l.t1[1];
+    out[2] = bcast_lo(rb) * l.t1[2];
+    out[3] = bcast_hi(rb) * l.t1[3];
 }
 
 /* 24 bits starting at bit 24*i of the 96-bit little-endian string (d0, d1, d2) */
@@ -166,8 +236,131 @@ __device__ __forceinline__ uint32_t sel4(uint4 v, int c)
     return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w));
 }
 
+/* Scores of one 64-token tile: four passes of 16 tokens.  Lane (g, n) ends up with
+ * sc[i][e] = score of token 16*i + 4*g + e against column n. */
+__device__ __forceinline__ void score_tile(const uint32_t *tab, const KTileRaw &kcur, const H8 (&qb)[4], f4 (&sc)[4])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint4 l1q = (i < 2) ? kcur.l1a : kcur.l1b;
+        const uint32_t l1A = (i & 1) ? l1q.z : l1q.x, l1B = (i & 1) ? l1q.w : l1q.y;
+        const GroupOffsets go = group_offsets(take24(kcur.g0, kcur.g1, kcur.g2, i));
+        const uint32_t c4n = kcur.c4 >> (4 * i);
+        const h2 rad = as_h2(sel4(kcur.rad, i));
+        H8 ka[4];
+        HalfBlockLut la0, la1, lb0, lb1;
+        const NibbleOffsets noA = nibble_offsets(l1A), noB = nibble_offsets(l1B);
+        const h2 t4A = lut(tab, kT4, (c4n << 2) & 0xCu), t4B = lut(tab, kT4, c4n & 0xCu);
+        gather_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(noA),
+                          nibble_offset<1>(noA), nibble_offset<2>(noA), nibble_offset<3>(noA), la0);
+        gather_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(noA),
+                          nibble_offset<5>(noA), nibble_offset<6>(noA), nibble_offset<7>(noA), la1);
+        gather_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(noB),
+                          nibble_offset<1>(noB), nibble_offset<2>(noB), nibble_offset<3>(noB), lb0);
+        gather_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(noB),
+                          nibble_offset<5>(noB), nibble_offset<6>(noB), nibble_offset<7>(noB), lb1);
+        {   /* block A = 2*gk: slices 0, 1;  block B = 2*gk + 1: slices 2, 3 */
+            h2 rrA = bcast_lo(rad) * t4A, rrB = bcast_hi(rad) * t4B;
+            expand_half_block(bcast_lo(rrA), la0, ka[0].p);
+            expand_half_block(bcast_hi(rrA), la1, ka[1].p);
+            expand_half_block(bcast_lo(rrB), lb0, ka[2].p);
+            expand_half_block(bcast_hi(rrB), lb1, ka[3].p);
+        }
+        f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            s4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[s].v, qb[s].v, s4, 0, 0, 0);
+        sc[i] = s4;
+    }
+}
+
+/* Online-softmax update with the scores of one tile (one state per column), then
+ * the probabilities and the weighted value sum pass by pass.  MASKED handles a
+ * tile whose last slots lie beyond the context (the final tile of a sequence). */
+template <bool MASKED>
+__device__ __forceinline__ void softmax_pv_tile(const uint32_t *tab, f4 (&sc)[4], const VTileRaw &vcur,
+                                                f4 (&acc_o)[4], float &m_run, float &l_run,
+                                                int n_valid, int g, uint32_t parity_shift, int t4b)
+{
+    if (MASKED) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (16 * i + 4 * g + e >= n_valid) sc[i][e] = -INFINITY;
+    }
+    float tmax = sc[0][0];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tmax = fmaxf(tmax, sc[i][e]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float m_new = fmaxf(m_run, tmax);
+    if (__ballot(m_new > m_run) != 0ull) { /* wave-uniform: after the first tiles the maximum rarely moves */
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc_o[c] *= alpha;
+        m_run = m_new;
+    }
+    const float m_sub = m_run - kProbShift;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        H8 pb;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float p = __builtin_amdgcn_exp2f(sc[i][e] - m_sub);
+            l_run += p;
+            _Float16 ph = (_Float16)p;
+            uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, ph);
+            pb.w[e] = bits << parity_shift;
+        }
+        const uint4 l1q = (i < 2) ? vcur.l1a : vcur.l1b;
+        const GroupOffsets go = group_offsets(take24(vcur.g0, vcur.g1, vcur.g2, i));
+        const uint4 rq = (i < 2) ? vcur.rad0 : vcur.rad1;
+        const uint32_t c4x = vcur.c4 >> (8 * i); /* slots 4i..4i+3: 2 bits each */
+        h2 ve[4][4]; /* [token e][pair q] */
+#pragma unroll
+        for (int ep = 0; ep < 2; ++ep) { /* tokens 2ep, 2ep+1 share one L1 dword and one radius dword */
+            const NibbleOffsets no = nibble_offsets(sel4(l1q, 2 * (i & 1) + ep));
+            h2 rad = as_h2(sel4(rq, 2 * (i & 1) + ep));
+            h2 r0 = bcast_lo(rad), r1 = bcast_hi(rad);
+            if (MASKED) {
+                const h2 zero = h2{(_Float16)0.f, (_Float16)0.f};
+                if (16 * i + 4 * g + 2 * ep >= n_valid) r0 = zero;
+                if (16 * i + 4 * g + 2 * ep + 1 >= n_valid) r1 = zero;
+            }
+            const uint32_t c4a = ep == 0 ? ((c4x << 2) & 0xCu) : ((c4x >> 2) & 0xCu);
+            const uint32_t c4b = ep == 0 ? (c4x & 0xCu) : ((c4x >> 4) & 0xCu);
+            const h2 t4a = lut(tab, t4b, c4a), t4bb = lut(tab, t4b, c4b);
+            HalfBlockLut l0, l1;
+            if (ep == 0) {
+                gather_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(no),
+                                  nibble_offset<1>(no), nibble_offset<2>(no), nibble_offset<3>(no), l0);
+                gather_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(no),
+                                  nibble_offset<5>(no), nibble_offset<6>(no), nibble_offset<7>(no), l1);
+            } else {
+                gather_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(no),
+                                  nibble_offset<1>(no), nibble_offset<2>(no), nibble_offset<3>(no), l0);
+                gather_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(no),
+                                  nibble_offset<5>(no), nibble_offset<6>(no), nibble_offset<7>(no), l1);
+            }
+            expand_half_block(r0 * t4a, l0, ve[2 * ep]);
+            expand_half_block(r1 * t4bb, l1, ve[2 * ep + 1]);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            H8 va;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) va.p[e] = ve[e][c];
+            acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.v, pb.v, acc_o[c], 0, 0, 0);
+        }
+    }
+}
+
 template <int G>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_partial_kernel(AttnArgs a)
+__global__ __launch_bounds__(kWavesPerBlock * 64, 3) void pq_attn_partial_kernel(AttnArgs a)
 {
     __shared__ uint32_t tab[kTabDwords];
     {
@@ -221,109 +414,29 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_partial_kernel(At
     for (int c = 0; c < 4; ++c) acc_o[c] = f4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
 
-    KTileRaw kt;
-    VTileRaw vt;
-    load_k_tile(kt, kc + (int64_t)tile_lo * PQL_CODE_BYTES, kr + (int64_t)tile_lo * PQL_RADII, lane);
-    load_v_tile(vt, vc + (int64_t)tile_lo * PQL_CODE_BYTES, vr + (int64_t)tile_lo * PQL_RADII, lane);
-
-    for (int tile = tile_lo; tile < tile_hi; ++tile) {
-        KTileRaw kcur = kt;
-        VTileRaw vcur = vt;
-        if (tile + 1 < tile_hi) {
-            load_k_tile(kt, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * PQL_RADII, lane);
-            load_v_tile(vt, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * PQL_RADII, lane);
-        }
-        const int n_valid = min(64, ctx - tile * 64); /* >= 1 */
-
-        /* ---- scores: four passes of 16 tokens ---- */
+    /* Tiles tile_lo .. tile_hi-1; all but possibly the last one of the sequence are full.
+     * The raw tile registers are single buffered and refilled as soon as their phase is
+     * over: the next key tile is fetched while the values of this tile are consumed, the
+     * next value tile while the next keys are scored. */
+    const int n_full = min(tile_hi, ctx >> 6); /* tiles below this index are full */
+    KTileRaw kraw;
+    VTileRaw vraw;
+    load_k_tile(kraw, kc + (int64_t)tile_lo * PQL_CODE_BYTES, kr + (int64_t)tile_lo * PQL_RADII, lane);
+    load_v_tile(vraw, vc + (int64_t)tile_lo * PQL_CODE_BYTES, vr + (int64_t)tile_lo * PQL_RADII, lane);
+    int tile = tile_lo;
+    for (; tile < n_full; ++tile) {
         f4 sc[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint4 l1q = (i < 2) ? kcur.l1a : kcur.l1b;
-            const uint32_t l1A = (i & 1) ? l1q.z : l1q.x, l1B = (i & 1) ? l1q.w : l1q.y;
-            const uint32_t g24 = take24(kcur.g0, kcur.g1, kcur.g2, i);
-            const uint32_t c4n = kcur.c4 >> (4 * i);
-            const h2 rad = as_h2(sel4(kcur.rad, i));
-            H8 ka[4];
-            {   /* block A = 2*gk: slices 0, 1 */
-                h2 rr = bcast_lo(rad) * lut(tab, kT4, (c4n << 2) & 0xCu);
-                expand_half_block(tab, bcast_lo(rr), g24 & 63u, l1A & 0xFFFFu, ka[0].p);
-                expand_half_block(tab, bcast_hi(rr), (g24 >> 6) & 63u, l1A >> 16, ka[1].p);
-            }
-            {   /* block B = 2*gk + 1: slices 2, 3 */
-                h2 rr = bcast_hi(rad) * lut(tab, kT4, c4n & 0xCu);
-                expand_half_block(tab, bcast_lo(rr), (g24 >> 12) & 63u, l1B & 0xFFFFu, ka[2].p);
-                expand_half_block(tab, bcast_hi(rr), (g24 >> 18) & 63u, l1B >> 16, ka[3].p);
-            }
-            f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-                s4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[s].v, qb[s].v, s4, 0, 0, 0);
-            sc[i] = s4; /* lane (g, n): tokens 16*i + 4*g + e, column n */
-        }
-        if (n_valid < 64) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (16 * i + 4 * g + e >= n_valid) sc[i][e] = -INFINITY;
-        }
-
-        /* ---- online softmax, one state per column ---- */
-        float tmax = sc[0][0];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) tmax = fmaxf(tmax, sc[i][e]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m_run, tmax);
-        if (m_new > m_run) { /* not wave-uniform in general; cheap enough to predicate */
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            l_run *= alpha;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc_o[c] *= alpha;
-            m_run = m_new;
-        }
-
-        /* ---- probabilities and the weighted value sum, pass by pass ---- */
-        const float m_sub = m_run - kProbShift;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            H8 pb;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float p = __builtin_amdgcn_exp2f(sc[i][e] - m_sub);
-                l_run += p;
-                _Float16 ph = (_Float16)p;
-                uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, ph);
-                pb.w[e] = bits << parity_shift;
-            }
-            const uint4 l1q = (i < 2) ? vcur.l1a : vcur.l1b;
-            const uint32_t g24 = take24(vcur.g0, vcur.g1, vcur.g2, i);
-            const uint4 rq = (i < 2) ? vcur.rad0 : vcur.rad1;
-            h2 ve[4][4]; /* [token e][pair q] */
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int s = 4 * i + e;
-                const uint32_t l1w = sel4(l1q, 2 * (i & 1) + (e >> 1));
-                const uint32_t l1 = (e & 1) ? (l1w >> 16) : (l1w & 0xFFFFu);
-                const uint32_t rw = sel4(rq, 2 * (i & 1) + (e >> 1));
-                h2 rad = as_h2(rw);
-                h2 r = (e & 1) ? bcast_hi(rad) : bcast_lo(rad);
-                if (16 * i + 4 * g + e >= n_valid) r = h2{(_Float16)0.f, (_Float16)0.f};
-                const uint32_t c4 = (vcur.c4 >> (2 * s)) & 3u;
-                h2 r3 = r * lut(tab, t4b, c4 << 2);
-                expand_half_block(tab, r3, (g24 >> (6 * e)) & 63u, l1, ve[e]);
-            }
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                H8 va;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) va.p[e] = ve[e][c];
-                acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.v, pb.v, acc_o[c], 0, 0, 0);
-            }
-        }
+        score_tile(tab, kraw, qb, sc);
+        if (tile + 1 < tile_hi)
+            load_k_tile(kraw, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * PQL_RADII, lane);
+        softmax_pv_tile<false>(tab, sc, vraw, acc_o, m_run, l_run, 64, g, parity_shift, t4b);
+        if (tile + 1 < tile_hi)
+            load_v_tile(vraw, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * PQL_RADII, lane);
+    }
+    if (tile < tile_hi) { /* the partial last tile of the sequence */
+        f4 sc[4];
+        score_tile(tab, kraw, qb, sc);
+        softmax_pv_tile<true>(tab, sc, vraw, acc_o, m_run, l_run, ctx - tile * 64, g, parity_shift, t4b);
     }
 
     /* ---- partial results: l summed over the four token groups; o' scattered to coordinate order ---- */
