@@ -170,6 +170,53 @@ __device__ __forceinline__ void expand_half_block(h2 r3, const HalfBlockLut &l, 
     out[3] = bcast_hi(rb) * l.t1[3];
 }
 
+/* Mixed-precision multiplies (v_fma_mix*): operands are binary16 halves or fp32
+ * registers, the product is formed exactly in fp32 and rounded once. */
+template <int SA, int SB>
+__device__ __forceinline__ float mix_mul_hh(h2 a, h2 b) /* half SA of a times half SB of b, exact */
+{
+    float d;
+    if (SA == 0 && SB == 0) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b));
+    else if (SA == 1 && SB == 0) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b));
+    else if (SA == 0 && SB == 1) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b));
+    else asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+
+template <int SB>
+__device__ __forceinline__ float mix_mul_fh(float a, h2 b) /* fp32 a times half SB of b */
+{
+    float d;
+    if (SB == 0) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(d) : "v"(a), "v"(b));
+    else asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+
+/* (a_lo * b.lo, a_hi * b.hi) rounded once each to binary16 */
+__device__ __forceinline__ h2 mix_mul_pair(float a_lo, float a_hi, h2 b)
+{
+    uint32_t d;
+    asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(d) : "v"(a_lo), "v"(b));
+    asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "+v"(d) : "v"(a_hi), "v"(b));
+    return as_h2(d);
+}
+
+/* Key-side half-block expansion with every product formed in fp32 and each of
+ * the 8 results rounded to binary16 exactly once.  r3 is the exact product radius x
+ * level-4 entry.  The scores are the precision-critical contraction (an error of a
+ * key element moves a softmax weight, and those errors do not average out over the
+ * context), so the keys pay for the extra instructions; the values use the packed
+ * binary16 chain. */
+__device__ __forceinline__ void expand_half_block_mixed(float r3, const HalfBlockLut &l, h2 out[4])
+{
+    float r10 = mix_mul_fh<0>(r3, l.ta), r11 = mix_mul_fh<1>(r3, l.ta);
+    float r12 = mix_mul_fh<0>(r3, l.tb), r13 = mix_mul_fh<1>(r3, l.tb);
+    out[0] = mix_mul_pair(r10, r10, l.t1[0]);
+    out[1] = mix_mul_pair(r11, r11, l.t1[1]);
+    out[2] = mix_mul_pair(r12, r12, l.t1[2]);
+    out[3] = mix_mul_pair(r13, r13, l.t1[3]);
+}
+
 /* 24 bits starting at bit 24*i of the 96-bit little-endian string (d0, d1, d2) */
 __device__ __forceinline__ uint32_t take24(uint32_t d0, uint32_t d1, uint32_t d2, int i)
 {
@@ -260,11 +307,10 @@ __device__ __forceinline__ void score_tile(const uint32_t *tab, const KTileRaw &
         gather_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(noB),
                           nibble_offset<5>(noB), nibble_offset<6>(noB), nibble_offset<7>(noB), lb1);
         {   /* block A = 2*gk: slices 0, 1;  block B = 2*gk + 1: slices 2, 3 */
-            h2 rrA = bcast_lo(rad) * t4A, rrB = bcast_hi(rad) * t4B;
-            expand_half_block(bcast_lo(rrA), la0, ka[0].p);
-            expand_half_block(bcast_hi(rrA), la1, ka[1].p);
-            expand_half_block(bcast_lo(rrB), lb0, ka[2].p);
-            expand_half_block(bcast_hi(rrB), lb1, ka[3].p);
+            expand_half_block_mixed(mix_mul_hh<0, 0>(rad, t4A), la0, ka[0].p);
+            expand_half_block_mixed(mix_mul_hh<0, 1>(rad, t4A), la1, ka[1].p);
+            expand_half_block_mixed(mix_mul_hh<1, 0>(rad, t4B), lb0, ka[2].p);
+            expand_half_block_mixed(mix_mul_hh<1, 1>(rad, t4B), lb1, ka[3].p);
         }
         f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -467,17 +513,20 @@ struct RotateArgs {
     const PqDeviceConsts *consts;
 };
 
-__global__ __launch_bounds__(PQ_D) void pq_rotate_q_kernel(RotateArgs a)
+__global__ __launch_bounds__(512) void pq_rotate_q_kernel(RotateArgs a)
 {
     __shared__ float sq[PQ_D];
-    const int row = blockIdx.x, j = threadIdx.x;
-    sq[j] = __uint_as_float((uint32_t)a.q[(int64_t)row * PQ_D + j] << 16);
+    __shared__ float spart[4][PQ_D];
+    const int tid = threadIdx.x, j = tid & 127;
+    const int row = blockIdx.x;
+    if (tid < PQ_D) sq[j] = __uint_as_float((uint32_t)a.q[(int64_t)row * PQ_D + j] << 16);
     __syncthreads();
-    float acc = 0.f;
-    for (int i = 0; i < PQ_D; ++i) acc += sq[i] * a.S[i * PQ_D + j];
-    /* rebuilt keys carry the table scale sigma of their coordinate: take it out here */
-    _Float16 h = (_Float16)(acc * a.scale / a.consts->sigma[j & 15]);
-    a.qrot[(int64_t)row * PQ_D + j] = __builtin_bit_cast(uint16_t, h);
+    const float acc = vector_times_matrix(sq, a.S, spart, tid); /* q'_j = sum_i q_i S[i][j] */
+    if (tid < PQ_D) {
+        /* rebuilt keys carry the table scale sigma of their coordinate: take it out here */
+        _Float16 h = (_Float16)(acc * a.scale / a.consts->sigma[j & 15]);
+        a.qrot[(int64_t)row * PQ_D + j] = __builtin_bit_cast(uint16_t, h);
+    }
 }
 
 struct CombineArgs {
@@ -492,35 +541,48 @@ struct CombineArgs {
     const PqDeviceConsts *consts;
 };
 
-__global__ __launch_bounds__(PQ_D) void pq_attn_combine_kernel(CombineArgs a)
+__global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
 {
     __shared__ float so[PQ_D];
-    const int row = blockIdx.x, j = threadIdx.x;
+    __shared__ float spart[4][PQ_D];
+    __shared__ float sl[4][PQ_D];
+    const int tid = threadIdx.x, cq = tid >> 7, j = tid & 127;
+    const int row = blockIdx.x;
     const int b = row / a.Hq;
     const int ctx = effective_ctx(a.seq_start, a.ctx_len, b, a.max_ctx, a.pool_tiles);
     const int n_tiles = (ctx + 63) >> 6;
     const int used = min((n_tiles + a.chunk_tiles - 1) / a.chunk_tiles, a.n_chunks);
-    float m = -INFINITY, l = 0.f, o = 0.f;
-    for (int c = 0; c < used; ++c) { /* fixed order: results do not depend on scheduling */
-        const int64_t slot = (int64_t)row * a.n_chunks + c;
-        float mc = a.ws_ml[slot * 2], lc = a.ws_ml[slot * 2 + 1];
-        float oc = a.ws_o[slot * PQ_D + j];
-        float mn = fmaxf(m, mc);
-        float sa = exp2f(m - mn), sb = exp2f(mc - mn);
-        l = l * sa + lc * sb;
-        o = o * sa + oc * sb;
-        m = mn;
+    const float *ml = a.ws_ml + (int64_t)row * a.n_chunks * 2;
+    const float *op = a.ws_o + (int64_t)row * a.n_chunks * PQ_D + j;
+    /* overall maximum first, then the weighted sums; thread group cq takes chunks cq, cq+4, ...
+       and the four group sums are added in a fixed order: the result does not depend on scheduling */
+    float m = -INFINITY;
+    for (int c = 0; c < used; ++c) m = fmaxf(m, ml[2 * c]);
+    float l = 0.f, o = 0.f;
+#pragma unroll 4
+    for (int c = cq; c < used; c += 4) {
+        const float w = exp2f(ml[2 * c] - m);
+        l = fmaf(ml[2 * c + 1], w, l);
+        o = fmaf(op[(int64_t)c * PQ_D], w, o);
     }
-    /* rebuilt values carry the table scale sigma of their coordinate */
-    so[j] = (used > 0) ? o / (l * a.consts->sigma[j & 15]) : 0.f;
+    spart[cq][j] = o;
+    sl[cq][j] = l;
     __syncthreads();
-    float acc = 0.f;
-    for (int k = 0; k < PQ_D; ++k) acc += so[k] * a.St[k * PQ_D + j]; /* out_j = sum_k o'_k S[j][k] */
-    if (a.out_f32) {
-        static_cast<float *>(a.out)[(int64_t)row * PQ_D + j] = acc;
-    } else {
-        uint32_t u = __float_as_uint(acc);
-        static_cast<uint16_t *>(a.out)[(int64_t)row * PQ_D + j] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+    if (tid < PQ_D) {
+        const float ot = ((spart[0][j] + spart[1][j]) + spart[2][j]) + spart[3][j];
+        const float lt = ((sl[0][j] + sl[1][j]) + sl[2][j]) + sl[3][j];
+        /* rebuilt values carry the table scale sigma of their coordinate */
+        so[j] = used > 0 ? ot / (lt * a.consts->sigma[j & 15]) : 0.f;
+    }
+    __syncthreads();
+    const float acc = vector_times_matrix(so, a.St, spart, tid); /* out_j = sum_k o'_k S[j][k] */
+    if (tid < PQ_D) {
+        if (a.out_f32) {
+            static_cast<float *>(a.out)[(int64_t)row * PQ_D + j] = acc;
+        } else {
+            uint32_t u = __float_as_uint(acc);
+            static_cast<uint16_t *>(a.out)[(int64_t)row * PQ_D + j] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+        }
     }
 }
 
@@ -534,7 +596,9 @@ Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx)
     Plan p;
     int64_t max_tiles = (max_ctx + 63) / 64;
     if (max_tiles < 1) max_tiles = 1;
-    const int64_t target_items = 256 * 8 * 4; /* a few work items per resident wavefront */
+    /* 256 CUs x 12 resident wavefronts (3 per SIMD); two rounds of equal work items keep
+       the tail short without writing many partial results */
+    const int64_t target_items = 256 * 12 * 2;
     int64_t streams = (int64_t)B * Hkv;
     int64_t per_stream = (target_items + streams - 1) / streams;
     if (per_stream < 1) per_stream = 1;
@@ -592,7 +656,7 @@ extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void
     const int rows = B * Hq;
 
     RotateArgs ra{static_cast<const uint16_t *>(q), qrot, ds->S_f32, softmax_scale * kLog2e, ds->consts};
-    hipLaunchKernelGGL(pq_rotate_q_kernel, dim3(rows), dim3(PQ_D), 0, s, ra);
+    hipLaunchKernelGGL(pq_rotate_q_kernel, dim3(rows), dim3(512), 0, s, ra);
 
     AttnArgs aa{};
     aa.qrot = qrot;
@@ -607,14 +671,15 @@ extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void
     const int64_t items = (int64_t)B * Hkv * p.n_chunks;
     const unsigned blocks = (unsigned)((items + kWavesPerBlock - 1) / kWavesPerBlock);
     pq_prof_before(0, s);
-    if (G == 4) hipLaunchKernelGGL(pq_attn_partial_kernel<4>, dim3(blocks), dim3(kWavesPerBlock * 64), 0, s, aa);
-    else if (G == 2) hipLaunchKernelGGL(pq_attn_partial_kernel<2>, dim3(blocks), dim3(kWavesPerBlock * 64), 0, s, aa);
-    else hipLaunchKernelGGL(pq_attn_partial_kernel<1>, dim3(blocks), dim3(kWavesPerBlock * 64), 0, s, aa);
+    const dim3 grid(blocks), blk(kWavesPerBlock * 64);
+    if (G == 4) hipLaunchKernelGGL(pq_attn_partial_kernel<4>, grid, blk, 0, s, aa);
+    else if (G == 2) hipLaunchKernelGGL(pq_attn_partial_kernel<2>, grid, blk, 0, s, aa);
+    else hipLaunchKernelGGL(pq_attn_partial_kernel<1>, grid, blk, 0, s, aa);
     pq_prof_after(0, s);
 
     CombineArgs ca{ws_ml, ws_o, seq_start, ctx_len, max_ctx, pool_tokens / 64, Hq, p.n_chunks, p.chunk_tiles,
                    ds->St_f32, out, out_dtype == PQ_F32 ? 1 : 0, ds->consts};
-    hipLaunchKernelGGL(pq_attn_combine_kernel, dim3(rows), dim3(PQ_D), 0, s, ca);
+    hipLaunchKernelGGL(pq_attn_combine_kernel, dim3(rows), dim3(512), 0, s, ca);
     PQ_HIP_TRY(hipGetLastError());
     return PQ_OK;
 }

@@ -75,6 +75,25 @@ void pq_prof_after(int kind, hipStream_t s);
 
 static inline bool pq_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+/* ---- small dense products with S: one vector per 512-thread workgroup ----
+ * out[j] = sum_k in[k] * M[k*128 + j].  Thread (kq, j) accumulates the k-quarter kq with
+ * all 32 loads in flight at once (these kernels are latency bound, not bandwidth bound);
+ * the four quarter sums are added in a fixed order by the threads of quarter 0. */
+static __device__ __forceinline__ float vector_times_matrix(const float (&sin)[PQ_D], const float *M,
+                                                     float (&spart)[4][PQ_D], int tid)
+{
+    const int kq = tid >> 7, j = tid & 127;
+    float m[32];
+#pragma unroll
+    for (int k = 0; k < 32; ++k) m[k] = M[(32 * kq + k) * PQ_D + j];
+    float acc = 0.f;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) acc = fmaf(sin[32 * kq + k], m[k], acc);
+    spart[kq][j] = acc;
+    __syncthreads();
+    return ((spart[0][j] + spart[1][j]) + spart[2][j]) + spart[3][j];
+}
+
 /* Layout of S_bf16x3 (halves): [term 3][row-tile 4][k-step 8][lane 64][8].
  * Lane l = 32*kg + i of (term, rt, ks) holds S_term[16*ks + 8*kg + e][col(rt, i)]
  * for e = 0..7, where the 32 rows of row-tile rt map to rotated coordinates

@@ -3,7 +3,8 @@
  * (precondition with S, procedure Polar, procedure Quant) plus bit-packing
  * into the tile layout, for gfx950.
  *
- * One wavefront owns one destination tile (64 token slots of one head plane).
+ * Bulk kernel (pq_encode_kv; the append kernel is described further down):
+ * one wavefront owns one destination tile (64 token slots of one head plane).
  *   1. y = x * S on the matrix cores.  S is held as three bf16 terms
  *      S1 + S2 + S3 (24 significant bits) so that bf16 MFMAs with fp32
  *      accumulation reproduce an fp32-accurate rotation; bf16 inputs are
@@ -40,12 +41,9 @@ struct EncodeArgs {
     uint16_t *radii;
     int64_t pool_tiles;
     int64_t pool_tokens;
-    /* bulk mode: tokens [dst0, dst0 + n) */
+    /* tokens [dst0, dst0 + n) of every head plane */
     int64_t dst0, n_tokens;
     int64_t first_tile, n_tiles; /* tiles spanned by the range */
-    /* append mode: one token per sequence at dst_token[seq] */
-    const int64_t *dst_token;
-    int n_seq;
     int n_heads;
     int64_t n_items;
     const uint4 *S_bf16x3;
@@ -94,7 +92,72 @@ __device__ __forceinline__ uint32_t quant3(float u, float v, float t1, float t3)
     return (uint32_t)(v > t1 * u) + (uint32_t)(v > u) + (uint32_t)(v > t3 * u);
 }
 
-template <int XT, int KIND, bool APPEND>
+/* tan of the first and third inner boundary of each level (the middle one is pi/4) */
+struct Thresholds {
+    float t1a, t1c, t2a, t2c, t3a, t3c, t4a, t4c;
+};
+
+__device__ __forceinline__ Thresholds load_thresholds(const PqDeviceConsts &K)
+{
+    Thresholds t;
+    t.t1a = K.tan_b[0][0]; t.t1c = K.tan_b[0][2];
+    t.t2a = K.tan_b[1][0]; t.t2c = K.tan_b[1][2];
+    t.t3a = K.tan_b[2][0]; t.t3c = K.tan_b[2][2];
+    t.t4a = K.tan_b[3][0]; t.t4c = K.tan_b[3][2];
+    return t;
+}
+
+struct BlockCodes {
+    uint32_t l1;     /* 8 level-1 codes, pair p at bits [4p, 4p+4) */
+    uint32_t g0, g1; /* [c2(2h) | c3(h) | c2(2h+1)] of half-block 0 / 1 */
+    uint32_t c4;
+    uint16_t radius; /* binary16 bits */
+};
+
+/* Procedure Polar on one block of 16 rotated coordinates with procedure Quant
+ * folded in: four levels of (angle code, radius) pairs, all in registers. */
+template <typename Y16>
+__device__ __forceinline__ BlockCodes polar_quant_block(const Y16 &y, const Thresholds &th)
+{
+    BlockCodes out;
+    float r1[8];
+    uint32_t l1 = 0;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        float ya = y[2 * p], yb = y[2 * p + 1];
+        float ua = fabsf(ya), ub = fabsf(yb);
+        uint32_t mq = quant3(ua, ub, th.t1a, th.t1c);
+        /* quadrant of atan2(yb, ya) in [0, 2 pi): cells are pi/8 wide */
+        uint32_t code = (ya < 0.0f) ? ((yb < 0.0f) ? 8u + mq : 7u - mq)
+                                    : ((yb < 0.0f) ? 15u - mq : mq);
+        l1 |= code << (4 * p);
+        r1[p] = __builtin_amdgcn_sqrtf(ya * ya + yb * yb);
+    }
+    float r2[4];
+    uint32_t c2[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        c2[n] = quant3(r1[2 * n], r1[2 * n + 1], th.t2a, th.t2c);
+        r2[n] = __builtin_amdgcn_sqrtf(r1[2 * n] * r1[2 * n] + r1[2 * n + 1] * r1[2 * n + 1]);
+    }
+    float r3[2];
+    uint32_t c3[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        c3[h] = quant3(r2[2 * h], r2[2 * h + 1], th.t3a, th.t3c);
+        r3[h] = __builtin_amdgcn_sqrtf(r2[2 * h] * r2[2 * h] + r2[2 * h + 1] * r2[2 * h + 1]);
+    }
+    out.c4 = quant3(r3[0], r3[1], th.t4a, th.t4c);
+    float r4 = __builtin_amdgcn_sqrtf(r3[0] * r3[0] + r3[1] * r3[1]);
+    _Float16 rh = (_Float16)r4; /* round to nearest even */
+    out.radius = __builtin_bit_cast(uint16_t, rh);
+    out.l1 = l1;
+    out.g0 = (c2[0] << 4) | (c3[0] << 2) | c2[1];
+    out.g1 = (c2[2] << 4) | (c3[1] << 2) | c2[3];
+    return out;
+}
+
+template <int XT, int KIND>
 __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
 {
     __shared__ uint4 sS[kSChunks];                  /* 96 KB: S1, S2, S3 in A-operand order */
@@ -104,11 +167,7 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
     for (int c = threadIdx.x; c < kSChunks; c += kThreads) sS[c] = a.S_bf16x3[c];
     __syncthreads();
 
-    const PqDeviceConsts &K = *a.consts;
-    const float t1a = K.tan_b[0][0], t1c = K.tan_b[0][2];
-    const float t2a = K.tan_b[1][0], t2c = K.tan_b[1][2];
-    const float t3a = K.tan_b[2][0], t3c = K.tan_b[2][2];
-    const float t4a = K.tan_b[3][0], t4c = K.tan_b[3][2];
+    const Thresholds th = load_thresholds(*a.consts);
 
     uint32_t *img = sImg[wave];
     const int j = lane & 31, H = lane >> 5; /* vector within the 32-vector group, lane half */
@@ -119,25 +178,14 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
         int64_t tile;      /* tile index inside the head plane */
         int tau_lo, tau_hi; /* slots [tau_lo, tau_hi) of the tile are written */
         int64_t src_t0;    /* source token index of slot tau_lo */
-        if (APPEND) {
-            int seq = (int)(item / a.n_heads);
-            head = (int)(item % a.n_heads);
-            int64_t dst = a.dst_token[seq];
-            if (dst < 0 || dst >= a.pool_tokens) continue; /* slot outside the pool: nothing is written */
-            tile = dst >> 6;
-            tau_lo = (int)(dst & 63);
-            tau_hi = tau_lo + 1;
-            src_t0 = seq;
-        } else {
-            head = (int)(item / a.n_tiles);
-            int64_t trel = item % a.n_tiles;
-            tile = a.first_tile + trel;
-            int64_t lo = tile * 64 > a.dst0 ? tile * 64 : a.dst0;
-            int64_t hi = (tile + 1) * 64 < a.dst0 + a.n_tokens ? (tile + 1) * 64 : a.dst0 + a.n_tokens;
-            tau_lo = (int)(lo - tile * 64);
-            tau_hi = (int)(hi - tile * 64);
-            src_t0 = lo - a.dst0;
-        }
+        head = (int)(item / a.n_tiles);
+        int64_t trel = item % a.n_tiles;
+        tile = a.first_tile + trel;
+        int64_t lo = tile * 64 > a.dst0 ? tile * 64 : a.dst0;
+        int64_t hi = (tile + 1) * 64 < a.dst0 + a.n_tokens ? (tile + 1) * 64 : a.dst0 + a.n_tokens;
+        tau_lo = (int)(lo - tile * 64);
+        tau_hi = (int)(hi - tile * 64);
+        src_t0 = lo - a.dst0;
         const bool full = (tau_lo == 0 && tau_hi == 64);
         uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
         uint16_t *gradii = a.radii + ((int64_t)head * a.pool_tiles + tile) * PQL_RADII;
@@ -164,8 +212,7 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
             BOperand xb[NXT][8];
             {
                 int64_t t_src = src_t0 + (tau - tau_lo);
-                int64_t row = APPEND ? ((int64_t)t_src * a.n_heads + head) * PQ_D
-                                     : t_src * a.ld_token + (int64_t)head * a.ld_head;
+                int64_t row = t_src * a.ld_token + (int64_t)head * a.ld_head;
                 if constexpr (XT == PQ_BF16) {
                     const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.x) + row);
 #pragma unroll
@@ -227,38 +274,9 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
                 /* lane (H, j): acc[r] = rotated coordinate 16*(4H + rt) + r of vector tau */
                 const int b = 4 * H + rt;
 
-                /* ---- procedure Polar on the block, with procedure Quant folded in ---- */
-                float r1[8];
-                uint32_t l1 = 0;
-#pragma unroll
-                for (int p = 0; p < 8; ++p) {
-                    float ya = acc[2 * p], yb = acc[2 * p + 1];
-                    float ua = fabsf(ya), ub = fabsf(yb);
-                    uint32_t mq = quant3(ua, ub, t1a, t1c);
-                    /* quadrant of atan2(yb, ya) in [0, 2 pi): cells are pi/8 wide */
-                    uint32_t code = (ya < 0.0f) ? ((yb < 0.0f) ? 8u + mq : 7u - mq)
-                                                : ((yb < 0.0f) ? 15u - mq : mq);
-                    l1 |= code << (4 * p);
-                    r1[p] = __builtin_amdgcn_sqrtf(ya * ya + yb * yb);
-                }
-                float r2[4];
-                uint32_t c2[4];
-#pragma unroll
-                for (int n = 0; n < 4; ++n) {
-                    c2[n] = quant3(r1[2 * n], r1[2 * n + 1], t2a, t2c);
-                    r2[n] = __builtin_amdgcn_sqrtf(r1[2 * n] * r1[2 * n] + r1[2 * n + 1] * r1[2 * n + 1]);
-                }
-                float r3[2];
-                uint32_t c3[2];
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    c3[h] = quant3(r2[2 * h], r2[2 * h + 1], t3a, t3c);
-                    r3[h] = __builtin_amdgcn_sqrtf(r2[2 * h] * r2[2 * h] + r2[2 * h + 1] * r2[2 * h + 1]);
-                }
-                uint32_t c4 = quant3(r3[0], r3[1], t4a, t4c);
-                float r4 = __builtin_amdgcn_sqrtf(r3[0] * r3[0] + r3[1] * r3[1]);
-                _Float16 rh = (_Float16)r4; /* round to nearest even */
-                uint16_t rbits = __builtin_bit_cast(uint16_t, rh);
+                BlockCodes bc = polar_quant_block(acc, th);
+                const uint32_t l1 = bc.l1, g0 = bc.g0, g1 = bc.g1, c4 = bc.c4;
+                const uint16_t rbits = bc.radius;
 
                 /* ---- scatter the block's fields into the tile image ---- */
                 if (valid) {
@@ -266,8 +284,6 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
                     uint16_t *img16 = reinterpret_cast<uint16_t *>(img);
                     img16[pos.l1_byte[0] >> 1] = (uint16_t)(l1 & 0xFFFFu);
                     img16[pos.l1_byte[1] >> 1] = (uint16_t)(l1 >> 16);
-                    uint32_t g0 = (c2[0] << 4) | (c3[0] << 2) | c2[1];
-                    uint32_t g1 = (c2[2] << 4) | (c3[1] << 2) | c2[3];
                     if (full) {
                         put_bits<false>(img, pos.g6_bit[0], 6, g0);
                         put_bits<false>(img, pos.g6_bit[1], 6, g1);
@@ -295,30 +311,106 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
     }
 }
 
-template <int XT, int KIND, bool APPEND>
+
+/* ---- decode-time append: one vector per (sequence, head) ----
+ * Too little work for the matrix cores: one workgroup per vector computes
+ * y_j = sum_i x_i S[i][j] in fp32 (S read from L2, four partial sums per
+ * coordinate added in a fixed order), eight threads then run the polar recursion of one block each and patch the fields
+ * into the tile in place.  Fields narrower than a byte share dwords with other
+ * slots of the tile, so they are updated with dword atomics. */
+struct AppendArgs {
+    const void *x;
+    uint8_t *codes;
+    uint16_t *radii;
+    int64_t pool_tiles, pool_tokens;
+    const int64_t *dst_token;
+    int n_heads;
+    const float *S; /* S[i*128 + j] */
+    const PqDeviceConsts *consts;
+};
+
+__device__ __forceinline__ void put_bits_global(uint8_t *codes, uint32_t bit, int width, uint32_t v)
+{
+    uint32_t *w = reinterpret_cast<uint32_t *>(codes) + (bit >> 5);
+    const uint32_t sh = bit & 31, mask = (1u << width) - 1u;
+    atomicAnd(w, ~(mask << sh));
+    atomicOr(w, v << sh);
+    if (sh + width > 32) {
+        const uint32_t done = 32 - sh;
+        atomicAnd(w + 1, ~(mask >> done));
+        atomicOr(w + 1, v >> done);
+    }
+}
+
+template <int XT, int KIND>
+__global__ __launch_bounds__(512) void pq_append_kernel(AppendArgs a)
+{
+    __shared__ float sx[PQ_D];
+    __shared__ float sy[PQ_D];
+    __shared__ float spart[4][PQ_D];
+    const int seq = blockIdx.x / a.n_heads, head = blockIdx.x % a.n_heads, tid = threadIdx.x, j = tid & 127;
+    const int64_t dst = a.dst_token[seq];
+    if (dst < 0 || dst >= a.pool_tokens) return; /* slot outside the pool: nothing is written */
+    const int64_t row = ((int64_t)seq * a.n_heads + head) * PQ_D;
+    if (tid < PQ_D) {
+        if (XT == PQ_BF16) sx[j] = __uint_as_float((uint32_t)static_cast<const uint16_t *>(a.x)[row + j] << 16);
+        else sx[j] = static_cast<const float *>(a.x)[row + j];
+    }
+    __syncthreads();
+    const float acc = vector_times_matrix(sx, a.S, spart, tid); /* y_j = sum_i x_i S[i][j] */
+    if (tid < PQ_D) sy[j] = acc;
+    __syncthreads();
+    if (tid < 8) {
+        const int b = tid;
+        float y[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) y[r] = sy[16 * b + r];
+        const Thresholds th = load_thresholds(*a.consts);
+        BlockCodes bc = polar_quant_block(y, th);
+        const int64_t tile = dst >> 6;
+        const int tau = (int)(dst & 63);
+        uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
+        uint16_t *gradii = a.radii + ((int64_t)head * a.pool_tiles + tile) * PQL_RADII;
+        PqBlockPos pos = pql_pos(KIND, tau, b);
+        *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[0]) = (uint16_t)(bc.l1 & 0xFFFFu);
+        *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[1]) = (uint16_t)(bc.l1 >> 16);
+        put_bits_global(gcodes, pos.g6_bit[0], 6, bc.g0);
+        put_bits_global(gcodes, pos.g6_bit[1], 6, bc.g1);
+        put_bits_global(gcodes, pos.c4_bit, 2, bc.c4);
+        gradii[pos.radius_half] = bc.radius;
+    }
+}
+
+template <int XT, int KIND>
 pq_status launch_encode(const EncodeArgs &a, hipStream_t stream)
 {
-    int dev = 0, cus = 256;
+    static int cached_cus[PQ_MAX_DEVICES] = {0};
+    int dev = 0;
     PQ_HIP_TRY(hipGetDevice(&dev));
-    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (dev < 0 || dev >= PQ_MAX_DEVICES) return PQ_EUNSUPPORTED;
+    if (cached_cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached_cus[dev] = n;
+    }
+    const int cus = cached_cus[dev];
     int64_t blocks = (a.n_items + kWaves - 1) / kWaves;
     if (blocks > cus) blocks = cus;
     if (blocks < 1) blocks = 1;
     pq_prof_before(1, stream);
-    hipLaunchKernelGGL((pq_encode_kernel<XT, KIND, APPEND>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((pq_encode_kernel<XT, KIND>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a);
     pq_prof_after(1, stream);
     PQ_HIP_TRY(hipGetLastError());
     return PQ_OK;
 }
 
-template <bool APPEND>
 pq_status dispatch_encode(const EncodeArgs &a, pq_dtype xt, pq_kind kind, hipStream_t stream)
 {
     if (xt == PQ_BF16)
-        return kind == PQ_KEY ? launch_encode<PQ_BF16, PQ_KEY, APPEND>(a, stream)
-                              : launch_encode<PQ_BF16, PQ_VALUE, APPEND>(a, stream);
-    return kind == PQ_KEY ? launch_encode<PQ_F32, PQ_KEY, APPEND>(a, stream)
-                          : launch_encode<PQ_F32, PQ_VALUE, APPEND>(a, stream);
+        return kind == PQ_KEY ? launch_encode<PQ_BF16, PQ_KEY>(a, stream)
+                              : launch_encode<PQ_BF16, PQ_VALUE>(a, stream);
+    return kind == PQ_KEY ? launch_encode<PQ_F32, PQ_KEY>(a, stream)
+                          : launch_encode<PQ_F32, PQ_VALUE>(a, stream);
 }
 
 } // namespace
@@ -354,7 +446,7 @@ extern "C" pq_status pq_encode_kv(const pq_ctx *ctx, const void *x, pq_dtype xt,
     a.n_items = a.n_tiles * n_heads;
     a.S_bf16x3 = reinterpret_cast<const uint4 *>(ds->S_bf16x3);
     a.consts = ds->consts;
-    return dispatch_encode<false>(a, xt, kind, static_cast<hipStream_t>(hip_stream));
+    return dispatch_encode(a, xt, kind, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,
@@ -367,16 +459,21 @@ extern "C" pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt,
     if (xt != PQ_F32 && xt != PQ_BF16) return PQ_EINVAL;
     if (kind != PQ_KEY && kind != PQ_VALUE) return PQ_EINVAL;
     if (n_seq < 0 || n_heads <= 0 || pool_tokens <= 0 || (pool_tokens & 63)) return PQ_EINVAL;
+    if ((int64_t)n_seq * n_heads > 0x7FFFFFFF) return PQ_EINVAL;
     if (!pq_aligned16(x) || !pq_aligned16(codes) || !pq_aligned16(radii)) return PQ_EALIGN;
     const PqDeviceState *ds = nullptr;
     pq_status st = pq_device_state(ctx, &ds);
     if (st != PQ_OK) return st;
-    EncodeArgs a{};
-    a.x = x;
-    a.codes = codes; a.radii = radii; a.pool_tiles = pool_tokens / 64; a.pool_tokens = pool_tokens;
-    a.dst_token = dst_token; a.n_seq = n_seq; a.n_heads = n_heads;
-    a.n_items = (int64_t)n_seq * n_heads;
-    a.S_bf16x3 = reinterpret_cast<const uint4 *>(ds->S_bf16x3);
-    a.consts = ds->consts;
-    return dispatch_encode<true>(a, xt, kind, static_cast<hipStream_t>(hip_stream));
+    AppendArgs a{x, codes, radii, pool_tokens / 64, pool_tokens, dst_token, n_heads, ds->S_f32, ds->consts};
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    dim3 grid((unsigned)(n_seq * n_heads)), block(512);
+    if (xt == PQ_BF16) {
+        if (kind == PQ_KEY) hipLaunchKernelGGL((pq_append_kernel<PQ_BF16, PQ_KEY>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((pq_append_kernel<PQ_BF16, PQ_VALUE>), grid, block, 0, s, a);
+    } else {
+        if (kind == PQ_KEY) hipLaunchKernelGGL((pq_append_kernel<PQ_F32, PQ_KEY>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((pq_append_kernel<PQ_F32, PQ_VALUE>), grid, block, 0, s, a);
+    }
+    PQ_HIP_TRY(hipGetLastError());
+    return PQ_OK;
 }
