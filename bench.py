@@ -35,6 +35,9 @@ HBM_PEAK_GBS = 8000.0
 B, HQ, HKV, CTX, D = 16, 32, 8, 32768, 128
 N_CACHES = 3
 BYTES_PER_TOKEN_HEAD = 124  # 62-byte key record + 62-byte value record
+# HBM bytes per launch of pq_attn_partial_kernel on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled
+# by a plain copy of known size (profiles/attn_partial_cfg2_counters.txt): 521.4 MB read + 12.7 MB written.
+MEASURED_TRAFFIC_BYTES = 521.4e6 + 12.7e6
 
 
 def main():
@@ -159,7 +162,8 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES,
+            "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated; separate profiling run)",
             "kernel_avg_ms": round(kern_ms, 5),
             "launches_timed": prof["attn_launches"],
         },

@@ -25,5 +25,20 @@ def build(verbose=False):
     return LIB_PATH
 
 
+MEMBENCH_PATH = os.path.join(LIB_DIR, "pq_membench")
+
+
+def build_membench():
+    """Stand-alone HBM read-ceiling / counter-calibration probe (see csrc/pq_membench.hip)."""
+    os.makedirs(LIB_DIR, exist_ok=True)
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(CSRC, "pq_membench.hip"), "-o", MEMBENCH_PATH]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    return MEMBENCH_PATH
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_membench())

@@ -19,15 +19,16 @@
  * Partial kernel, per 16-token pass (four passes per 64-token tile):
  *   K:  lane (gk, m) rebuilds the 32 rotated coordinates of quarter gk of token
  *       16*i + m from its own registers: radius -> level 4 -> (level 3 x level 2
- *       product table) -> level 1, every step a packed-binary16 multiply by a
- *       (cos, sin) pair fetched from a 16-entry LDS table (all entries in
- *       distinct banks, so the gathers are conflict free).  The 4 x 8 values are
+ *       product table) -> level 1, every factor a (cos, sin) pair fetched from a
+ *       16-entry LDS table (all entries in distinct banks, so the gathers are
+ *       conflict free), the products formed in fp32 by mixed-precision
+ *       multiplies and rounded to binary16 once.  The 4 x 8 values are
  *       the A operand (token rows) of v_mfma_f32_16x16x32_f16 against q'
  *       (columns = query heads), accumulated over the four 32-coordinate slices.
  *   softmax: the score tile comes out with lane (g, col) holding tokens
  *       16*i + 4*g + {0..3}; running max and sum per column.
  *   V:  lane (g, n) rebuilds half-block n (8 coordinates = 4 (cos, sin) pairs) of
- *       those same four tokens.  A (cos, sin) register holds two coordinates of
+ *       those same four tokens with packed binary16 multiplies.  A (cos, sin) register holds two coordinates of
  *       one token, while a matrix-core operand wants several tokens of one
  *       coordinate per lane; instead of transposing, the contraction index is
  *       widened to (token, parity): operand rows are coordinate pairs, and the
