@@ -52,8 +52,9 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kProbShift = 14.0f;
 
 /* LDS table block (dwords): T1 [0,16)  T4 [16,20)  TA [32,48)  TB [48,64)
- * T4 broadcast per half: [64,68) cos, [68,72) sin as (f, f) pairs */
-constexpr int kT1 = 0, kT4 = 16, kTA = 32, kTB = 48, kT4B = 64, kTabDwords = 72;
+ * T4 broadcast per half: [64,68) cos, [68,72) sin as (f, f) pairs
+ * T1 in fp32 [96,128): 16 (cos, sin) float pairs, one pair per two banks */
+constexpr int kT1 = 0, kT4 = 16, kTA = 32, kTB = 48, kT4B = 64, kT1F = 96, kTabDwords = 128;
 
 struct AttnArgs {
     const uint16_t *qrot; /* [B][Hq][128] binary16, rotated and pre-scaled */
@@ -98,11 +99,33 @@ struct NibbleOffsets {
     uint32_t even, odd; /* byte k of even: 4 * code 2k; of odd: 4 * code 2k+1 */
 };
 
+/* A 32-bit literal doubles the size of a vector instruction; masks used hundreds of times
+ * per tile are kept in scalar registers instead (the empty asm hides their value from
+ * constant propagation). */
+__device__ __forceinline__ uint32_t scalar_const(uint32_t v)
+{
+    asm("" : "+s"(v));
+    return v;
+}
+
 __device__ __forceinline__ NibbleOffsets nibble_offsets(uint32_t w)
 {
     NibbleOffsets r;
-    r.even = (w << 2) & 0x3C3C3C3Cu;
-    r.odd = (w >> 2) & 0x3C3C3C3Cu;
+    const uint32_t m = scalar_const(0x3C3C3C3Cu);
+    r.even = (w << 2) & m;
+    r.odd = (w >> 2) & m;
+    asm("" : "+v"(r.even));
+    asm("" : "+v"(r.odd));
+    return r;
+}
+
+/* the same with 8 * code (8-byte table entries) */
+__device__ __forceinline__ NibbleOffsets nibble_offsets8(uint32_t w)
+{
+    NibbleOffsets r;
+    const uint32_t m = scalar_const(0x78787878u);
+    r.even = (w << 3) & m;
+    r.odd = (w >> 1) & m;
     asm("" : "+v"(r.even));
     asm("" : "+v"(r.odd));
     return r;
@@ -127,8 +150,9 @@ struct GroupOffsets {
 __device__ __forceinline__ GroupOffsets group_offsets(uint32_t g24)
 {
     GroupOffsets r;
-    r.offA = g24 & 0xF3CF3Cu;
-    r.offB = (g24 << 2) & 0xF3CF3Cu;
+    const uint32_t m = scalar_const(0xF3CF3Cu);
+    r.offA = g24 & m;
+    r.offB = (g24 << 2) & m;
     asm("" : "+v"(r.offA));
     asm("" : "+v"(r.offB));
     return r;
@@ -193,29 +217,47 @@ __device__ __forceinline__ float mix_mul_fh(float a, h2 b) /* fp32 a times half 
     return d;
 }
 
-/* (a_lo * b.lo, a_hi * b.hi) rounded once each to binary16 */
-__device__ __forceinline__ h2 mix_mul_pair(float a_lo, float a_hi, h2 b)
+/* Key-side tables of one half-block: level-3 x level-2 products as binary16 pairs,
+ * level-1 (cos, sin) as fp32 pairs. */
+struct KeyHalfBlockLut {
+    h2 ta, tb;
+    float2 t1[4];
+};
+
+__device__ __forceinline__ float2 lut_f2(const uint32_t *tab, uint32_t byte_off) /* byte_off = 8 * index */
 {
-    uint32_t d;
-    asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(d) : "v"(a_lo), "v"(b));
-    asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "+v"(d) : "v"(a_hi), "v"(b));
-    return as_h2(d);
+    return *reinterpret_cast<const float2 *>(reinterpret_cast<const char *>(tab + kT1F) + byte_off);
 }
 
-/* Key-side half-block expansion with every product formed in fp32 and each of
- * the 8 results rounded to binary16 exactly once.  r3 is the exact product radius x
- * level-4 entry.  The scores are the precision-critical contraction (an error of a
- * key element moves a softmax weight, and those errors do not average out over the
- * context), so the keys pay for the extra instructions; the values use the packed
- * binary16 chain. */
-__device__ __forceinline__ void expand_half_block_mixed(float r3, const HalfBlockLut &l, h2 out[4])
+__device__ __forceinline__ void gather_key_half_block(const uint32_t *tab, uint32_t offA, uint32_t offB,
+                                                      uint32_t o0, uint32_t o1, uint32_t o2, uint32_t o3,
+                                                      KeyHalfBlockLut &l)
+{
+    l.ta = lut(tab, kTA, offA);
+    l.tb = lut(tab, kTB, offB);
+    l.t1[0] = lut_f2(tab, o0);
+    l.t1[1] = lut_f2(tab, o1);
+    l.t1[2] = lut_f2(tab, o2);
+    l.t1[3] = lut_f2(tab, o3);
+}
+
+/* Key-side half-block expansion with every product formed in fp32 and each of the 8
+ * results rounded to binary16 exactly once.  r3 is the exact product radius x level-4
+ * entry.  The scores are the precision-critical contraction (an error of a key element
+ * moves a softmax weight, and those errors do not average out over the context), so the
+ * keys pay for the extra instructions; the values use the packed binary16 chain.
+ * Plain fp32 multiplies plus one packed conversion per pair issue faster than the
+ * mixed-precision multiply with a binary16 destination. */
+__device__ __forceinline__ h2 round_pair(float a, float b) { return h2{(_Float16)a, (_Float16)b}; }
+
+__device__ __forceinline__ void expand_key_half_block(float r3, const KeyHalfBlockLut &l, h2 out[4])
 {
     float r10 = mix_mul_fh<0>(r3, l.ta), r11 = mix_mul_fh<1>(r3, l.ta);
     float r12 = mix_mul_fh<0>(r3, l.tb), r13 = mix_mul_fh<1>(r3, l.tb);
-    out[0] = mix_mul_pair(r10, r10, l.t1[0]);
-    out[1] = mix_mul_pair(r11, r11, l.t1[1]);
-    out[2] = mix_mul_pair(r12, r12, l.t1[2]);
-    out[3] = mix_mul_pair(r13, r13, l.t1[3]);
+    out[0] = round_pair(r10 * l.t1[0].x, r10 * l.t1[0].y);
+    out[1] = round_pair(r11 * l.t1[1].x, r11 * l.t1[1].y);
+    out[2] = round_pair(r12 * l.t1[2].x, r12 * l.t1[2].y);
+    out[3] = round_pair(r13 * l.t1[3].x, r13 * l.t1[3].y);
 }
 
 /* 24 bits starting at bit 24*i of the 96-bit little-endian string (d0, d1, d2) */
@@ -296,22 +338,22 @@ __device__ __forceinline__ void score_tile(const uint32_t *tab, const KTileRaw &
         const uint32_t c4n = kcur.c4 >> (4 * i);
         const h2 rad = as_h2(sel4(kcur.rad, i));
         H8 ka[4];
-        HalfBlockLut la0, la1, lb0, lb1;
-        const NibbleOffsets noA = nibble_offsets(l1A), noB = nibble_offsets(l1B);
+        KeyHalfBlockLut la0, la1, lb0, lb1;
+        const NibbleOffsets noA = nibble_offsets8(l1A), noB = nibble_offsets8(l1B);
         const h2 t4A = lut(tab, kT4, (c4n << 2) & 0xCu), t4B = lut(tab, kT4, c4n & 0xCu);
-        gather_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(noA),
+        gather_key_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(noA),
                           nibble_offset<1>(noA), nibble_offset<2>(noA), nibble_offset<3>(noA), la0);
-        gather_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(noA),
+        gather_key_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(noA),
                           nibble_offset<5>(noA), nibble_offset<6>(noA), nibble_offset<7>(noA), la1);
-        gather_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(noB),
+        gather_key_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(noB),
                           nibble_offset<1>(noB), nibble_offset<2>(noB), nibble_offset<3>(noB), lb0);
-        gather_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(noB),
+        gather_key_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(noB),
                           nibble_offset<5>(noB), nibble_offset<6>(noB), nibble_offset<7>(noB), lb1);
         {   /* block A = 2*gk: slices 0, 1;  block B = 2*gk + 1: slices 2, 3 */
-            expand_half_block_mixed(mix_mul_hh<0, 0>(rad, t4A), la0, ka[0].p);
-            expand_half_block_mixed(mix_mul_hh<0, 1>(rad, t4A), la1, ka[1].p);
-            expand_half_block_mixed(mix_mul_hh<1, 0>(rad, t4B), lb0, ka[2].p);
-            expand_half_block_mixed(mix_mul_hh<1, 1>(rad, t4B), lb1, ka[3].p);
+            expand_key_half_block(mix_mul_hh<0, 0>(rad, t4A), la0, ka[0].p);
+            expand_key_half_block(mix_mul_hh<0, 1>(rad, t4A), la1, ka[1].p);
+            expand_key_half_block(mix_mul_hh<1, 0>(rad, t4B), lb0, ka[2].p);
+            expand_key_half_block(mix_mul_hh<1, 1>(rad, t4B), lb1, ka[3].p);
         }
         f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -421,6 +463,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 3) void pq_attn_partial_kernel
             tab[kT4B + 4 + t] = (cs >> 16) * 0x10001u;
         }
         if (t >= 20 && t < 32) tab[t] = 0u;
+        if (t >= 72 && t < 96) tab[t] = 0u;
+        if (t >= 96 && t < 128) tab[t] = __float_as_uint(K.t1_f32[(t - 96) >> 1][t & 1]);
     }
     __syncthreads();
 
@@ -597,9 +641,10 @@ Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx)
     Plan p;
     int64_t max_tiles = (max_ctx + 63) / 64;
     if (max_tiles < 1) max_tiles = 1;
-    /* 256 CUs x 12 resident wavefronts (3 per SIMD); two rounds of equal work items keep
-       the tail short without writing many partial results */
-    const int64_t target_items = 256 * 12 * 2;
+    /* 256 CUs x 12 resident wavefronts (3 per SIMD): one work item per resident wavefront
+       measured fastest (140 us against 145-150 us for 2..8 rounds on the 32k-context batch)
+       and writes the fewest partial results */
+    const int64_t target_items = 256 * 12;
     int64_t streams = (int64_t)B * Hkv;
     int64_t per_stream = (target_items + streams - 1) / streams;
     if (per_stream < 1) per_stream = 1;

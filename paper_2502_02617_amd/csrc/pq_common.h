@@ -25,6 +25,7 @@ struct PqDeviceConsts {
     float cs234[3][4][2];
     /* Packed binary16 pairs (low half, high half) for the attention kernel. */
     uint32_t t1_h2[16]; /* (cos, sin) of level-1 centroid c                        */
+    float t1_f32[16][2]; /* the same (scaled) pairs in fp32, for the key path        */
     uint32_t t4_h2[4];  /* (cos, sin) of level-4 centroid c                        */
     uint32_t ta_h2[16]; /* index (c2<<2 | c3): cos(th3[c3]) * (cos, sin)(th2[c2])  */
     uint32_t tb_h2[16]; /* index (c3<<2 | c2): sin(th3[c3]) * (cos, sin)(th2[c2])  */

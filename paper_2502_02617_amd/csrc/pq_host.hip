@@ -262,6 +262,8 @@ void build_tables(pq_ctx *ctx)
     }
     for (int k = 0; k < 16; ++k) {
         c.t1_h2[k] = pack_h2(t1[0][k] * s1[0], t1[1][k] * s1[1]);
+        c.t1_f32[k][0] = (float)(t1[0][k] * s1[0]);
+        c.t1_f32[k][1] = (float)(t1[1][k] * s1[1]);
         c.ta_h2[k] = pack_h2(ta[0][k] * sa[0], ta[1][k] * sa[1]);
         c.tb_h2[k] = pack_h2(tb[0][k] * sb[0], tb[1][k] * sb[1]);
     }
