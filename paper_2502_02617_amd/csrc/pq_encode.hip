@@ -69,21 +69,23 @@ union BOperand {
     uint32_t w[4];
 };
 
-/* Set `width` bits at bit offset `bit` (from the start of the image) to v.
- * The image is shared by the lanes of one wavefront: LDS atomics keep
- * concurrent updates of neighbouring fields in one dword intact. */
-template <bool CLEAR>
+/* Set `width` bits at bit offset `bit` (from the start of the image) to v.  The image is
+ * shared by the lanes of one wavefront: LDS atomics keep concurrent updates of neighbouring
+ * fields in one dword intact.  The second dword is always touched (with zeros when the field
+ * does not straddle): no divergent branch, and every field that can straddle lies in the
+ * G6 plane, whose following dword is still inside the image. */
+template <bool CLEAR, bool MAY_STRADDLE>
 __device__ __forceinline__ void put_bits(uint32_t *img, uint32_t bit, int width, uint32_t v)
 {
-    uint32_t dw = bit >> 5, sh = bit & 31;
-    uint32_t mask = (1u << width) - 1u;
-    if (CLEAR) atomicAnd(&img[dw], ~(mask << sh));
-    atomicOr(&img[dw], v << sh);
-    if (sh + width > 32) {
-        uint32_t done = 32 - sh;
-        if (CLEAR) atomicAnd(&img[dw + 1], ~(mask >> done));
-        atomicOr(&img[dw + 1], v >> done);
+    const uint32_t dw = bit >> 5, sh = bit & 31;
+    const uint64_t vv = (uint64_t)v << sh;
+    if (CLEAR) {
+        const uint64_t mm = (uint64_t)((1u << width) - 1u) << sh;
+        atomicAnd(&img[dw], ~(uint32_t)mm);
+        if (MAY_STRADDLE) atomicAnd(&img[dw + 1], ~(uint32_t)(mm >> 32));
     }
+    atomicOr(&img[dw], (uint32_t)vv);
+    if (MAY_STRADDLE) atomicOr(&img[dw + 1], (uint32_t)(vv >> 32));
 }
 
 /* Quantise one quadrant angle: number of inner boundaries below atan(v/u). */
@@ -157,6 +159,26 @@ __device__ __forceinline__ BlockCodes polar_quant_block(const Y16 &y, const Thre
     return out;
 }
 
+/* Scatter the fields of block b of slot tau into the tile image (codes, then radii). */
+template <int KIND, bool CLEAR>
+__device__ __forceinline__ void emit_block(uint32_t *img, int tau, int b, const BlockCodes &bc)
+{
+    const PqBlockPos pos = pql_pos(KIND, tau, b);
+    uint16_t *img16 = reinterpret_cast<uint16_t *>(img);
+    if (KIND == PQ_KEY) {
+        /* the two L1 halves are one aligned dword, the two G6 groups 12 consecutive bits */
+        img[pos.l1_byte[0] >> 2] = bc.l1;
+        put_bits<CLEAR, true>(img, pos.g6_bit[0], 12, bc.g0 | (bc.g1 << 6));
+    } else {
+        img16[pos.l1_byte[0] >> 1] = (uint16_t)(bc.l1 & 0xFFFFu);
+        img16[pos.l1_byte[1] >> 1] = (uint16_t)(bc.l1 >> 16);
+        put_bits<CLEAR, true>(img, pos.g6_bit[0], 6, bc.g0);
+        put_bits<CLEAR, true>(img, pos.g6_bit[1], 6, bc.g1);
+    }
+    put_bits<CLEAR, false>(img, pos.c4_bit, 2, bc.c4); /* even bit offset: never straddles */
+    img16[PQL_CODE_BYTES / 2 + pos.radius_half] = bc.radius;
+}
+
 template <int XT, int KIND>
 __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
 {
@@ -201,25 +223,31 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
         }
         wave_lds_sync();
 
-        for (int vt = 0; vt < 2; ++vt) {
-            const int tau = 32 * vt + j;
-            /* wave-uniform skip of a half tile with nothing to write */
-            if (32 * vt + 32 <= tau_lo || 32 * vt >= tau_hi) continue;
-            const bool valid = tau >= tau_lo && tau < tau_hi;
+        /* bf16 input: both 32-vector halves of the tile share every A-operand fetch (halves the
+           LDS traffic); fp32 input carries three bf16 terms per value and goes one half at a time */
+        constexpr int NXT = (XT == PQ_BF16) ? 1 : 3; /* bf16 terms of x */
+        constexpr int NVT = (XT == PQ_BF16) ? 2 : 1; /* 32-vector halves per pass */
+        for (int vt0 = 0; vt0 < 2; vt0 += NVT) {
+            /* wave-uniform skip of a pass with nothing to write */
+            if (32 * (vt0 + NVT) <= tau_lo || 32 * vt0 >= tau_hi) continue;
 
-            /* ---- B operand: this lane's 8-coordinate slices of its vector, every k-step ---- */
-            constexpr int NXT = (XT == PQ_BF16) ? 1 : 3; /* bf16 terms of x */
-            BOperand xb[NXT][8];
-            {
-                int64_t t_src = src_t0 + (tau - tau_lo);
+            /* ---- B operands: this lane's 8-coordinate slices of its vectors, every k-step ---- */
+            BOperand xb[NVT][NXT][8];
+            bool valid[NVT];
+            int tau[NVT];
+#pragma unroll
+            for (int v = 0; v < NVT; ++v) {
+                tau[v] = 32 * (vt0 + v) + j;
+                valid[v] = tau[v] >= tau_lo && tau[v] < tau_hi;
+                int64_t t_src = src_t0 + (tau[v] - tau_lo);
                 int64_t row = t_src * a.ld_token + (int64_t)head * a.ld_head;
                 if constexpr (XT == PQ_BF16) {
                     const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.x) + row);
 #pragma unroll
                     for (int ks = 0; ks < 8; ++ks) {
-                        uint4 v = make_uint4(0, 0, 0, 0);
-                        if (valid) v = xr[2 * ks + H];
-                        xb[0][ks].q = v;
+                        uint4 q = make_uint4(0, 0, 0, 0);
+                        if (valid[v]) q = xr[2 * ks + H];
+                        xb[v][0][ks].q = q;
                     }
                 } else {
                     const float4 *xr = reinterpret_cast<const float4 *>(static_cast<const float *>(a.x) + row);
@@ -227,7 +255,7 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
                     for (int ks = 0; ks < 8; ++ks) {
                         float f[8];
                         float4 p0 = make_float4(0, 0, 0, 0), p1 = p0;
-                        if (valid) { p0 = xr[4 * ks + 2 * H]; p1 = xr[4 * ks + 2 * H + 1]; }
+                        if (valid[v]) { p0 = xr[4 * ks + 2 * H]; p1 = xr[4 * ks + 2 * H + 1]; }
                         f[0] = p0.x; f[1] = p0.y; f[2] = p0.z; f[3] = p0.w;
                         f[4] = p1.x; f[5] = p1.y; f[6] = p1.z; f[7] = p1.w;
 #pragma unroll
@@ -235,17 +263,17 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
                             uint32_t w1[2], w2[2], w3[2];
 #pragma unroll
                             for (int z = 0; z < 2; ++z) {
-                                float v = f[e + z];
-                                uint32_t b1 = bf16_rne_bits(v);
-                                float r1 = v - __uint_as_float(b1 << 16);
+                                float val = f[e + z];
+                                uint32_t b1 = bf16_rne_bits(val);
+                                float r1 = val - __uint_as_float(b1 << 16);
                                 uint32_t b2 = bf16_rne_bits(r1);
                                 float r2 = r1 - __uint_as_float(b2 << 16);
                                 uint32_t b3 = bf16_rne_bits(r2);
                                 w1[z] = b1; w2[z] = b2; w3[z] = b3;
                             }
-                            xb[0][ks].w[e / 2] = w1[0] | (w1[1] << 16);
-                            xb[1][ks].w[e / 2] = w2[0] | (w2[1] << 16);
-                            xb[2][ks].w[e / 2] = w3[0] | (w3[1] << 16);
+                            xb[v][0][ks].w[e / 2] = w1[0] | (w1[1] << 16);
+                            xb[v][NXT > 1 ? 1 : 0][ks].w[e / 2] = w2[0] | (w2[1] << 16);
+                            xb[v][NXT > 2 ? 2 : 0][ks].w[e / 2] = w3[0] | (w3[1] << 16);
                         }
                     }
                 }
@@ -254,9 +282,11 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
 #pragma unroll 1
             for (int rt = 0; rt < 4; ++rt) {
                 /* ---- D[i][j] = sum_k S[k][col(rt,i)] * x[j][k]: 32 rotated coordinates x 32 vectors ---- */
-                f32x16 acc;
+                f32x16 acc[NVT];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+                for (int v = 0; v < NVT; ++v)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[v][r] = 0.0f;
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks) {
                     /* smallest terms first */
@@ -265,35 +295,23 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
                         BOperand sa;
                         sa.q = sS[((term * 4 + rt) * 8 + ks) * 64 + lane];
 #pragma unroll
-                        for (int xt = 0; xt < NXT; ++xt) {
-                            if (xt + term > 2) continue; /* below 2^-24 of the leading product */
-                            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa.v, xb[xt][ks].v, acc, 0, 0, 0);
-                        }
+                        for (int v = 0; v < NVT; ++v)
+#pragma unroll
+                            for (int xt = 0; xt < NXT; ++xt) {
+                                if (xt + term > 2) continue; /* below 2^-24 of the leading product */
+                                acc[v] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa.v, xb[v][xt][ks].v, acc[v], 0, 0, 0);
+                            }
                     }
                 }
-                /* lane (H, j): acc[r] = rotated coordinate 16*(4H + rt) + r of vector tau */
+                /* lane (H, j): acc[v][r] = rotated coordinate 16*(4H + rt) + r of vector tau[v] */
                 const int b = 4 * H + rt;
-
-                BlockCodes bc = polar_quant_block(acc, th);
-                const uint32_t l1 = bc.l1, g0 = bc.g0, g1 = bc.g1, c4 = bc.c4;
-                const uint16_t rbits = bc.radius;
-
-                /* ---- scatter the block's fields into the tile image ---- */
-                if (valid) {
-                    PqBlockPos pos = pql_pos(KIND, tau, b);
-                    uint16_t *img16 = reinterpret_cast<uint16_t *>(img);
-                    img16[pos.l1_byte[0] >> 1] = (uint16_t)(l1 & 0xFFFFu);
-                    img16[pos.l1_byte[1] >> 1] = (uint16_t)(l1 >> 16);
-                    if (full) {
-                        put_bits<false>(img, pos.g6_bit[0], 6, g0);
-                        put_bits<false>(img, pos.g6_bit[1], 6, g1);
-                        put_bits<false>(img, pos.c4_bit, 2, c4);
-                    } else {
-                        put_bits<true>(img, pos.g6_bit[0], 6, g0);
-                        put_bits<true>(img, pos.g6_bit[1], 6, g1);
-                        put_bits<true>(img, pos.c4_bit, 2, c4);
+#pragma unroll
+                for (int v = 0; v < NVT; ++v) {
+                    const BlockCodes bc = polar_quant_block(acc[v], th);
+                    if (valid[v]) {
+                        if (full) emit_block<KIND, false>(img, tau[v], b, bc);
+                        else emit_block<KIND, true>(img, tau[v], b, bc);
                     }
-                    img16[PQL_CODE_BYTES / 2 + pos.radius_half] = rbits;
                 }
             }
         }
