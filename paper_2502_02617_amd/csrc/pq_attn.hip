@@ -47,9 +47,11 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 constexpr int kWavesPerBlock = 4;
 constexpr float kLog2e = 1.4426950408889634f;
 /* Probabilities are handed to the matrix cores as binary16.  They are computed
- * as 2^(s - m + kProbShift) so that even weights 2^-28 below the running
- * maximum stay normal numbers; l carries the same factor and it cancels in o'/l. */
-constexpr float kProbShift = 14.0f;
+ * as 2^(s - m + kProbShift) against an exponent reference m that may lag the true
+ * maximum by up to kRefSlack, so that weights from 2^-23 below the reference (normal
+ * numbers) to 2^kRefSlack above it fit; l carries the same factor and it cancels in o'/l. */
+constexpr float kProbShift = 9.0f;
+constexpr float kRefSlack = 6.0f;
 
 /* LDS table block (dwords): T1 [0,16)  T4 [16,20)  TA [32,48)  TB [48,64)
  * T4 broadcast per half: [64,68) cos, [68,72) sin as (f, f) pairs
@@ -57,7 +59,7 @@ constexpr float kProbShift = 14.0f;
 constexpr int kT1 = 0, kT4 = 16, kTA = 32, kTB = 48, kT4B = 64, kT1F = 96, kTabDwords = 128;
 
 struct AttnArgs {
-    const uint16_t *qrot; /* [B][Hq][128] binary16, rotated and pre-scaled */
+    const uint16_t *qrot; /* [B][Hq][2][128] binary16: rotated, pre-scaled q' as a leading part and its remainder */
     const uint8_t *k_codes, *v_codes;
     const uint16_t *k_radii, *v_radii;
     const int64_t *seq_start;
@@ -326,130 +328,137 @@ __device__ __forceinline__ uint32_t sel4(uint4 v, int c)
     return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w));
 }
 
-/* Scores of one 64-token tile: four passes of 16 tokens.  Lane (g, n) ends up with
- * sc[i][e] = score of token 16*i + 4*g + e against column n. */
-__device__ __forceinline__ void score_tile(const uint32_t *tab, const KTileRaw &kcur, const H8 (&qb)[4], f4 (&sc)[4])
+/* Scores of pass i of a 64-token tile: lane (g, n) gets s[e] = score of token
+ * 16*i + 4*g + e against column n. */
+template <int i>
+__device__ __forceinline__ f4 score_pass(const uint32_t *tab, const KTileRaw &kcur, const H8 (&qb)[4])
 {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint4 l1q = (i < 2) ? kcur.l1a : kcur.l1b;
-        const uint32_t l1A = (i & 1) ? l1q.z : l1q.x, l1B = (i & 1) ? l1q.w : l1q.y;
-        const GroupOffsets go = group_offsets(take24(kcur.g0, kcur.g1, kcur.g2, i));
-        const uint32_t c4n = kcur.c4 >> (4 * i);
-        const h2 rad = as_h2(sel4(kcur.rad, i));
-        H8 ka[4];
-        KeyHalfBlockLut la0, la1, lb0, lb1;
-        const NibbleOffsets noA = nibble_offsets8(l1A), noB = nibble_offsets8(l1B);
-        const h2 t4A = lut(tab, kT4, (c4n << 2) & 0xCu), t4B = lut(tab, kT4, c4n & 0xCu);
-        gather_key_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(noA),
+    const uint4 l1q = (i < 2) ? kcur.l1a : kcur.l1b;
+    const uint32_t l1A = (i & 1) ? l1q.z : l1q.x, l1B = (i & 1) ? l1q.w : l1q.y;
+    const GroupOffsets go = group_offsets(take24(kcur.g0, kcur.g1, kcur.g2, i));
+    const uint32_t c4n = kcur.c4 >> (4 * i);
+    const h2 rad = as_h2(sel4(kcur.rad, i));
+    H8 ka[4];
+    KeyHalfBlockLut la0, la1, lb0, lb1;
+    const NibbleOffsets noA = nibble_offsets8(l1A), noB = nibble_offsets8(l1B);
+    const h2 t4A = lut(tab, kT4, (c4n << 2) & 0xCu), t4B = lut(tab, kT4, c4n & 0xCu);
+    gather_key_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(noA),
                           nibble_offset<1>(noA), nibble_offset<2>(noA), nibble_offset<3>(noA), la0);
-        gather_key_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(noA),
+    gather_key_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(noA),
                           nibble_offset<5>(noA), nibble_offset<6>(noA), nibble_offset<7>(noA), la1);
-        gather_key_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(noB),
+    gather_key_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(noB),
                           nibble_offset<1>(noB), nibble_offset<2>(noB), nibble_offset<3>(noB), lb0);
-        gather_key_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(noB),
+    gather_key_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(noB),
                           nibble_offset<5>(noB), nibble_offset<6>(noB), nibble_offset<7>(noB), lb1);
-        {   /* block A = 2*gk: slices 0, 1;  block B = 2*gk + 1: slices 2, 3 */
-            expand_key_half_block(mix_mul_hh<0, 0>(rad, t4A), la0, ka[0].p);
-            expand_key_half_block(mix_mul_hh<0, 1>(rad, t4A), la1, ka[1].p);
-            expand_key_half_block(mix_mul_hh<1, 0>(rad, t4B), lb0, ka[2].p);
-            expand_key_half_block(mix_mul_hh<1, 1>(rad, t4B), lb1, ka[3].p);
-        }
-        f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
+    /* block A = 2*gk: slices 0, 1;  block B = 2*gk + 1: slices 2, 3 */
+    expand_key_half_block(mix_mul_hh<0, 0>(rad, t4A), la0, ka[0].p);
+    expand_key_half_block(mix_mul_hh<0, 1>(rad, t4A), la1, ka[1].p);
+    expand_key_half_block(mix_mul_hh<1, 0>(rad, t4B), lb0, ka[2].p);
+    expand_key_half_block(mix_mul_hh<1, 1>(rad, t4B), lb1, ka[3].p);
+    f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-            s4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[s].v, qb[s].v, s4, 0, 0, 0);
-        sc[i] = s4;
+    for (int s = 0; s < 4; ++s)
+        s4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[s].v, qb[s].v, s4, 0, 0, 0);
+    return s4;
+}
+
+/* Weighted value sum of pass i: acc_o += V(tokens 16*i + 4*g + e) * pb.  MASKED
+ * zeroes the radii of slots beyond the context so that stale cache bytes there
+ * cannot reach the sum. */
+template <int i, bool MASKED>
+__device__ __forceinline__ void pv_pass(const uint32_t *tab, const VTileRaw &vcur, const H8 &pb, f4 (&acc_o)[4],
+                                        int n_valid, int g, int t4b)
+{
+    const uint4 l1q = (i < 2) ? vcur.l1a : vcur.l1b;
+    const GroupOffsets go = group_offsets(take24(vcur.g0, vcur.g1, vcur.g2, i));
+    const uint4 rq = (i < 2) ? vcur.rad0 : vcur.rad1;
+    const uint32_t c4x = vcur.c4 >> (8 * i); /* slots 4i..4i+3: 2 bits each */
+    h2 ve[4][4]; /* [token e][pair q] */
+#pragma unroll
+    for (int ep = 0; ep < 2; ++ep) { /* tokens 2ep, 2ep+1 share one L1 dword and one radius dword */
+        const NibbleOffsets no = nibble_offsets(sel4(l1q, 2 * (i & 1) + ep));
+        h2 rad = as_h2(sel4(rq, 2 * (i & 1) + ep));
+        h2 r0 = bcast_lo(rad), r1 = bcast_hi(rad);
+        if (MASKED) {
+            const h2 zero = h2{(_Float16)0.f, (_Float16)0.f};
+            if (16 * i + 4 * g + 2 * ep >= n_valid) r0 = zero;
+            if (16 * i + 4 * g + 2 * ep + 1 >= n_valid) r1 = zero;
+        }
+        const uint32_t c4a = ep == 0 ? ((c4x << 2) & 0xCu) : ((c4x >> 2) & 0xCu);
+        const uint32_t c4b = ep == 0 ? (c4x & 0xCu) : ((c4x >> 4) & 0xCu);
+        const h2 t4a = lut(tab, t4b, c4a), t4bb = lut(tab, t4b, c4b);
+        HalfBlockLut l0, l1;
+        if (ep == 0) {
+            gather_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(no),
+                              nibble_offset<1>(no), nibble_offset<2>(no), nibble_offset<3>(no), l0);
+            gather_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(no),
+                              nibble_offset<5>(no), nibble_offset<6>(no), nibble_offset<7>(no), l1);
+        } else {
+            gather_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(no),
+                              nibble_offset<1>(no), nibble_offset<2>(no), nibble_offset<3>(no), l0);
+            gather_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(no),
+                              nibble_offset<5>(no), nibble_offset<6>(no), nibble_offset<7>(no), l1);
+        }
+        expand_half_block(r0 * t4a, l0, ve[2 * ep]);
+        expand_half_block(r1 * t4bb, l1, ve[2 * ep + 1]);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        H8 va;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) va.p[e] = ve[e][c];
+        acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.v, pb.v, acc_o[c], 0, 0, 0);
     }
 }
 
-/* Online-softmax update with the scores of one tile (one state per column), then
- * the probabilities and the weighted value sum pass by pass.  MASKED handles a
- * tile whose last slots lie beyond the context (the final tile of a sequence). */
-template <bool MASKED>
-__device__ __forceinline__ void softmax_pv_tile(const uint32_t *tab, f4 (&sc)[4], const VTileRaw &vcur,
-                                                f4 (&acc_o)[4], float &m_run, float &l_run,
-                                                int n_valid, int g, uint32_t parity_shift, int t4b)
+/* Softmax state of a column: the exponent reference m_ref is shared by the four
+ * token groups of the column and only moves when a score exceeds it by more than
+ * kRefSlack, which after the first pass of a chunk is rare.  Probabilities are
+ * exp2(s - m_ref + kProbShift): below 2^(kRefSlack + kProbShift), inside binary16,
+ * and the partial result (m_ref, l, o) is consistent for any reference. */
+/* One pass: scores, reference check, probabilities, weighted values. */
+template <int i, bool MASKED>
+__device__ __forceinline__ void attend_pass(const uint32_t *tab, const KTileRaw &kcur, const VTileRaw &vcur,
+                                            const H8 (&qb)[4], f4 (&acc_o)[4], float &m_ref, float &l_run,
+                                            int n_valid, int g, uint32_t parity_shift, int t4b)
 {
+    f4 s4 = score_pass<i>(tab, kcur, qb);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) /* leading part + remainder: columns n and n+8 (mod 16) of the same row of lanes */
+        s4[e] += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s4[e]), 0x128 /* row_ror:8 */, 0xF, 0xF, false));
     if (MASKED) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (16 * i + 4 * g + e >= n_valid) sc[i][e] = -INFINITY;
+        for (int e = 0; e < 4; ++e)
+            if (16 * i + 4 * g + e >= n_valid) s4[e] = -INFINITY;
     }
-    float tmax = sc[0][0];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) tmax = fmaxf(tmax, sc[i][e]);
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    const float m_new = fmaxf(m_run, tmax);
-    if (__ballot(m_new > m_run) != 0ull) { /* wave-uniform: after the first tiles the maximum rarely moves */
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const float pmax = fmaxf(fmaxf(fmaxf(s4[0], s4[1]), s4[2]), s4[3]);
+    if (__ballot(pmax > m_ref + kRefSlack) != 0ull) { /* wave-uniform */
+        float cmax = fmaxf(pmax, __shfl_xor(pmax, 16));
+        cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
+        const float m_new = fmaxf(m_ref, cmax);
+        /* m_new is finite here for every column that has seen a valid token; a column
+         * with none yet keeps -inf and contributes exact zeros below */
+        const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
         l_run *= alpha;
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc_o[c] *= alpha;
-        m_run = m_new;
+        m_ref = m_new;
     }
-    const float m_sub = m_run - kProbShift;
+    const float m_sub = m_ref - kProbShift;
+    H8 pb;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        H8 pb;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float p = __builtin_amdgcn_exp2f(sc[i][e] - m_sub);
-            l_run += p;
-            _Float16 ph = (_Float16)p;
-            uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, ph);
-            pb.w[e] = bits << parity_shift;
-        }
-        const uint4 l1q = (i < 2) ? vcur.l1a : vcur.l1b;
-        const GroupOffsets go = group_offsets(take24(vcur.g0, vcur.g1, vcur.g2, i));
-        const uint4 rq = (i < 2) ? vcur.rad0 : vcur.rad1;
-        const uint32_t c4x = vcur.c4 >> (8 * i); /* slots 4i..4i+3: 2 bits each */
-        h2 ve[4][4]; /* [token e][pair q] */
-#pragma unroll
-        for (int ep = 0; ep < 2; ++ep) { /* tokens 2ep, 2ep+1 share one L1 dword and one radius dword */
-            const NibbleOffsets no = nibble_offsets(sel4(l1q, 2 * (i & 1) + ep));
-            h2 rad = as_h2(sel4(rq, 2 * (i & 1) + ep));
-            h2 r0 = bcast_lo(rad), r1 = bcast_hi(rad);
-            if (MASKED) {
-                const h2 zero = h2{(_Float16)0.f, (_Float16)0.f};
-                if (16 * i + 4 * g + 2 * ep >= n_valid) r0 = zero;
-                if (16 * i + 4 * g + 2 * ep + 1 >= n_valid) r1 = zero;
-            }
-            const uint32_t c4a = ep == 0 ? ((c4x << 2) & 0xCu) : ((c4x >> 2) & 0xCu);
-            const uint32_t c4b = ep == 0 ? (c4x & 0xCu) : ((c4x >> 4) & 0xCu);
-            const h2 t4a = lut(tab, t4b, c4a), t4bb = lut(tab, t4b, c4b);
-            HalfBlockLut l0, l1;
-            if (ep == 0) {
-                gather_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(no),
-                                  nibble_offset<1>(no), nibble_offset<2>(no), nibble_offset<3>(no), l0);
-                gather_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(no),
-                                  nibble_offset<5>(no), nibble_offset<6>(no), nibble_offset<7>(no), l1);
-            } else {
-                gather_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(no),
-                                  nibble_offset<1>(no), nibble_offset<2>(no), nibble_offset<3>(no), l0);
-                gather_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(no),
-                                  nibble_offset<5>(no), nibble_offset<6>(no), nibble_offset<7>(no), l1);
-            }
-            expand_half_block(r0 * t4a, l0, ve[2 * ep]);
-            expand_half_block(r1 * t4bb, l1, ve[2 * ep + 1]);
-        }
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            H8 va;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) va.p[e] = ve[e][c];
-            acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.v, pb.v, acc_o[c], 0, 0, 0);
-        }
+    for (int e = 0; e < 4; ++e) {
+        float p = (MASKED && s4[e] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s4[e] - m_sub);
+        l_run += p;
+        _Float16 ph = (_Float16)p;
+        uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, ph);
+        pb.w[e] = bits << parity_shift;
     }
+    pv_pass<i, MASKED>(tab, vcur, pb, acc_o, n_valid, g, t4b);
 }
 
 template <int G>
-__global__ __launch_bounds__(kWavesPerBlock * 64, 3) void pq_attn_partial_kernel(AttnArgs a)
+__global__ __launch_bounds__(kWavesPerBlock * 64, 4) void pq_attn_partial_kernel(AttnArgs a)
 {
     __shared__ uint32_t tab[kTabDwords];
     {
@@ -487,13 +496,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 3) void pq_attn_partial_kernel
     const uint16_t *kr = a.k_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_RADII;
     const uint16_t *vr = a.v_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_RADII;
 
-    /* ---- q' operand: column n = (head n&3, parity (n>>2)&1) for n < 8, zero otherwise;
-     * slice s = rotated coordinates 32*g + 8*s .. +8 ---- */
+    /* ---- q' operand: columns n < 8 = (head n&3, parity (n>>2)&1) hold the leading binary16
+     * part of q', columns n + 8 its binary16 remainder, so that q' enters the scores to
+     * ~22 bits at no extra matrix instruction; slice s = rotated coordinates 32*g + 8*s .. +8 ---- */
     H8 qb[4];
     {
         const int head = n & 3;
-        const bool real = (n < 8) && (head < G);
-        const uint4 *qp = reinterpret_cast<const uint4 *>(a.qrot + ((int64_t)b * a.Hq + hk * G + (real ? head : 0)) * PQ_D + 32 * g);
+        const bool real = head < G;
+        const uint4 *qp = reinterpret_cast<const uint4 *>(
+            a.qrot + (((int64_t)b * a.Hq + hk * G + (real ? head : 0)) * 2 + (n >> 3)) * PQ_D + 32 * g);
 #pragma unroll
         for (int s = 0; s < 4; ++s) qb[s].q = real ? qp[s] : make_uint4(0, 0, 0, 0);
     }
@@ -506,9 +517,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 3) void pq_attn_partial_kernel
     float m_run = -INFINITY, l_run = 0.f;
 
     /* Tiles tile_lo .. tile_hi-1; all but possibly the last one of the sequence are full.
-     * The raw tile registers are single buffered and refilled as soon as their phase is
-     * over: the next key tile is fetched while the values of this tile are consumed, the
-     * next value tile while the next keys are scored. */
+     * The raw tile registers are single buffered: the next key tile is requested once the
+     * last pass has scored, the next value tile once it has been consumed; the other
+     * wavefronts resident on the SIMD cover the latency. */
     const int n_full = min(tile_hi, ctx >> 6); /* tiles below this index are full */
     KTileRaw kraw;
     VTileRaw vraw;
@@ -516,18 +527,21 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 3) void pq_attn_partial_kernel
     load_v_tile(vraw, vc + (int64_t)tile_lo * PQL_CODE_BYTES, vr + (int64_t)tile_lo * PQL_RADII, lane);
     int tile = tile_lo;
     for (; tile < n_full; ++tile) {
-        f4 sc[4];
-        score_tile(tab, kraw, qb, sc);
-        if (tile + 1 < tile_hi)
+        attend_pass<0, false>(tab, kraw, vraw, qb, acc_o, m_run, l_run, 64, g, parity_shift, t4b);
+        attend_pass<1, false>(tab, kraw, vraw, qb, acc_o, m_run, l_run, 64, g, parity_shift, t4b);
+        attend_pass<2, false>(tab, kraw, vraw, qb, acc_o, m_run, l_run, 64, g, parity_shift, t4b);
+        attend_pass<3, false>(tab, kraw, vraw, qb, acc_o, m_run, l_run, 64, g, parity_shift, t4b);
+        if (tile + 1 < tile_hi) {
             load_k_tile(kraw, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * PQL_RADII, lane);
-        softmax_pv_tile<false>(tab, sc, vraw, acc_o, m_run, l_run, 64, g, parity_shift, t4b);
-        if (tile + 1 < tile_hi)
             load_v_tile(vraw, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * PQL_RADII, lane);
+        }
     }
     if (tile < tile_hi) { /* the partial last tile of the sequence */
-        f4 sc[4];
-        score_tile(tab, kraw, qb, sc);
-        softmax_pv_tile<true>(tab, sc, vraw, acc_o, m_run, l_run, ctx - tile * 64, g, parity_shift, t4b);
+        const int nv = ctx - tile * 64;
+        attend_pass<0, true>(tab, kraw, vraw, qb, acc_o, m_run, l_run, nv, g, parity_shift, t4b);
+        attend_pass<1, true>(tab, kraw, vraw, qb, acc_o, m_run, l_run, nv, g, parity_shift, t4b);
+        attend_pass<2, true>(tab, kraw, vraw, qb, acc_o, m_run, l_run, nv, g, parity_shift, t4b);
+        attend_pass<3, true>(tab, kraw, vraw, qb, acc_o, m_run, l_run, nv, g, parity_shift, t4b);
     }
 
     /* ---- partial results: l summed over the four token groups; o' scattered to coordinate order ---- */
@@ -552,7 +566,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 3) void pq_attn_partial_kernel
 
 struct RotateArgs {
     const uint16_t *q; /* bf16 [rows][128] */
-    uint16_t *qrot;    /* binary16 [rows][128] */
+    uint16_t *qrot;    /* binary16 [rows][2][128]: leading part, remainder */
     const float *S;    /* S[i*128 + j] */
     float scale;       /* softmax_scale * log2(e) */
     const PqDeviceConsts *consts;
@@ -569,8 +583,11 @@ __global__ __launch_bounds__(512) void pq_rotate_q_kernel(RotateArgs a)
     const float acc = vector_times_matrix(sq, a.S, spart, tid); /* q'_j = sum_i q_i S[i][j] */
     if (tid < PQ_D) {
         /* rebuilt keys carry the table scale sigma of their coordinate: take it out here */
-        _Float16 h = (_Float16)(acc * a.scale / a.consts->sigma[j & 15]);
-        a.qrot[(int64_t)row * PQ_D + j] = __builtin_bit_cast(uint16_t, h);
+        const float v = acc * a.scale / a.consts->sigma[j & 15];
+        const _Float16 h = (_Float16)v;
+        const _Float16 r = (_Float16)(v - (float)h);
+        a.qrot[(int64_t)row * 2 * PQ_D + j] = __builtin_bit_cast(uint16_t, h);
+        a.qrot[(int64_t)row * 2 * PQ_D + PQ_D + j] = __builtin_bit_cast(uint16_t, r);
     }
 }
 
@@ -641,10 +658,10 @@ Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx)
     Plan p;
     int64_t max_tiles = (max_ctx + 63) / 64;
     if (max_tiles < 1) max_tiles = 1;
-    /* 256 CUs x 12 resident wavefronts (3 per SIMD): one work item per resident wavefront
-       measured fastest (140 us against 145-150 us for 2..8 rounds on the 32k-context batch)
-       and writes the fewest partial results */
-    const int64_t target_items = 256 * 12;
+    /* 256 CUs x 16 resident wavefronts (4 per SIMD): one work item per resident wavefront
+       measured fastest on the 32k-context batch (143 us against 149-156 us for 3/4 or 3/2
+       of that) and writes few partial results */
+    const int64_t target_items = 256 * 16;
     int64_t streams = (int64_t)B * Hkv;
     int64_t per_stream = (target_items + streams - 1) / streams;
     if (per_stream < 1) per_stream = 1;
@@ -654,7 +671,7 @@ Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx)
     p.chunk_tiles = (int)ct;
     p.n_chunks = (int)((max_tiles + ct - 1) / ct);
     size_t rows = (size_t)B * Hq;
-    p.off_ml = (rows * PQ_D * 2 + 255) & ~(size_t)255;
+    p.off_ml = (rows * 2 * PQ_D * sizeof(uint16_t) + 255) & ~(size_t)255;
     p.off_o = (p.off_ml + rows * p.n_chunks * 2 * sizeof(float) + 255) & ~(size_t)255;
     p.total = p.off_o + rows * p.n_chunks * PQ_D * sizeof(float);
     return p;
