@@ -16,9 +16,10 @@
  *      rotated coordinates of one vector in its accumulator registers: the
  *      whole polar recursion of a block is then register-local.
  *   2. Four polar levels per block; every angle is quantised by comparing
- *      in the tangent domain (v > tan(t) * u for each inner boundary t),
- *      which is the nearest-centroid rule of procedure Quant without
- *      evaluating an arctangent.
+ *      in the tangent domain (v > tan(t) * u for each inner boundary t, on
+ *      squared radii above level 1), which is the nearest-centroid rule of
+ *      procedure Quant without evaluating an arctangent or, but for the
+ *      block radius, a square root.
  *   3. The fields are scattered into an image of the tile in LDS and the
  *      image is written out with full-width stores.
  */
@@ -29,8 +30,10 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kWaves = 8;                 /* wavefronts per workgroup */
-constexpr int kThreads = kWaves * 64;
+/* wavefronts per workgroup (two per SIMD: the kernel uses the whole register file).  Sixteen
+   wavefronts working on one 32-vector half at a time in 128 registers measured slower: every
+   A-operand fetch then feeds one matrix instruction instead of two. */
+template <int XT> struct EncodeShape { static constexpr int waves = 8; };
 constexpr int kImgDwords = (PQL_CODE_BYTES + PQL_RADII * 2) / 4; /* 992 */
 constexpr int kSChunks = 3 * 4 * 8 * 64;  /* 16-byte chunks of the bf16x3 copy of S */
 
@@ -88,13 +91,19 @@ __device__ __forceinline__ void put_bits(uint32_t *img, uint32_t bit, int width,
     if (MAY_STRADDLE) atomicOr(&img[dw + 1], (uint32_t)(vv >> 32));
 }
 
-/* Quantise one quadrant angle: number of inner boundaries below atan(v/u). */
+/* Quantise one quadrant angle: number of inner boundaries below atan(v/u), for
+ * u, v >= 0.  Boundary k is passed when v > t_k * u, that is when the fused
+ * t_k * u - v (one rounding, so its sign is the exact one) is negative; the sign
+ * bits are added up.  The middle boundary is pi/4 (t = 1). */
 __device__ __forceinline__ uint32_t quant3(float u, float v, float t1, float t3)
 {
-    return (uint32_t)(v > t1 * u) + (uint32_t)(v > u) + (uint32_t)(v > t3 * u);
+    const float d1 = __builtin_fmaf(t1, u, -v), d2 = u - v, d3 = __builtin_fmaf(t3, u, -v);
+    return (__float_as_uint(d1) >> 31) + (__float_as_uint(d2) >> 31) + (__float_as_uint(d3) >> 31);
 }
 
-/* tan of the first and third inner boundary of each level (the middle one is pi/4) */
+/* First and third inner boundary of each level (the middle one is pi/4): their
+ * tangents for level 1, the squares of their tangents above it, where the
+ * recursion carries squared radii (v > t u  <=>  v^2 > t^2 u^2 for u, v >= 0). */
 struct Thresholds {
     float t1a, t1c, t2a, t2c, t3a, t3c, t4a, t4c;
 };
@@ -103,9 +112,9 @@ __device__ __forceinline__ Thresholds load_thresholds(const PqDeviceConsts &K)
 {
     Thresholds t;
     t.t1a = K.tan_b[0][0]; t.t1c = K.tan_b[0][2];
-    t.t2a = K.tan_b[1][0]; t.t2c = K.tan_b[1][2];
-    t.t3a = K.tan_b[2][0]; t.t3c = K.tan_b[2][2];
-    t.t4a = K.tan_b[3][0]; t.t4c = K.tan_b[3][2];
+    t.t2a = K.tan_b[1][0] * K.tan_b[1][0]; t.t2c = K.tan_b[1][2] * K.tan_b[1][2];
+    t.t3a = K.tan_b[2][0] * K.tan_b[2][0]; t.t3c = K.tan_b[2][2] * K.tan_b[2][2];
+    t.t4a = K.tan_b[3][0] * K.tan_b[3][0]; t.t4c = K.tan_b[3][2] * K.tan_b[3][2];
     return t;
 }
 
@@ -117,46 +126,75 @@ struct BlockCodes {
 };
 
 /* Procedure Polar on one block of 16 rotated coordinates with procedure Quant
- * folded in: four levels of (angle code, radius) pairs, all in registers. */
+ * folded in: four levels of (angle code, radius) pairs, all in registers.  Only
+ * the squares of the intermediate radii are kept (the angle of a node depends on
+ * the ratio of its children's radii alone); the root radius takes the one square
+ * root.  The recursion is cut into eight steps (one level-1 pair each, plus the
+ * nodes of the upper levels that the pair completes) so that a caller can spread
+ * it between other work. */
+struct PolarState {
+    float q1[8], q2[4], q3[2]; /* squared radii */
+    uint32_t mq, l1, c2[4], c3[2];
+    BlockCodes out;
+};
+
+/* level-1 pair p, first part: position inside the quadrant */
+template <typename Y16>
+__device__ __forceinline__ void polar_level1_a(PolarState &s, const Y16 &y, int p, const Thresholds &th)
+{
+    s.mq = quant3(fabsf(y[2 * p]), fabsf(y[2 * p + 1]), th.t1a, th.t1c);
+}
+
+/* level-1 pair p, second part: quadrant, code, squared radius */
+template <typename Y16>
+__device__ __forceinline__ void polar_level1_b(PolarState &s, const Y16 &y, int p)
+{
+    const float ya = y[2 * p], yb = y[2 * p + 1];
+    /* cell of atan2(yb, ya) in [0, 2 pi), cells pi/8 wide: quadrant Q = 0..3 from the signs,
+       code = 4Q + mq in quadrants 0 and 2, 4Q + 3 - mq in 1 and 3 (angle measured from the
+       other axis), which is (mq xor 7f) + 8 sb with f = sa xor sb */
+    const uint32_t ba = __float_as_uint(ya), bb = __float_as_uint(yb);
+    const uint32_t f7 = (uint32_t)((int32_t)(ba ^ bb) >> 31) & 7u;
+    const uint32_t code = (s.mq ^ f7) + ((bb >> 28) & 8u);
+    s.l1 = (p == 0) ? code : (s.l1 | (code << (4 * p)));
+    s.q1[p] = __builtin_fmaf(ya, ya, yb * yb);
+}
+
+/* the upper-level nodes whose children are complete once level-1 pair p is done */
+__device__ __forceinline__ void polar_upper(PolarState &s, int p, const Thresholds &th)
+{
+    if (p & 1) {
+        const int n = p >> 1;
+        s.c2[n] = quant3(s.q1[2 * n], s.q1[2 * n + 1], th.t2a, th.t2c);
+        s.q2[n] = s.q1[2 * n] + s.q1[2 * n + 1];
+    }
+    if ((p & 3) == 3) {
+        const int h = p >> 2;
+        s.c3[h] = quant3(s.q2[2 * h], s.q2[2 * h + 1], th.t3a, th.t3c);
+        s.q3[h] = s.q2[2 * h] + s.q2[2 * h + 1];
+    }
+    if (p == 7) {
+        s.out.c4 = quant3(s.q3[0], s.q3[1], th.t4a, th.t4c);
+        const float r4 = __builtin_amdgcn_sqrtf(s.q3[0] + s.q3[1]);
+        const _Float16 rh = (_Float16)r4; /* round to nearest even */
+        s.out.radius = __builtin_bit_cast(uint16_t, rh);
+        s.out.l1 = s.l1;
+        s.out.g0 = (s.c2[0] << 4) | (s.c3[0] << 2) | s.c2[1];
+        s.out.g1 = (s.c2[2] << 4) | (s.c3[1] << 2) | s.c2[3];
+    }
+}
+
 template <typename Y16>
 __device__ __forceinline__ BlockCodes polar_quant_block(const Y16 &y, const Thresholds &th)
 {
-    BlockCodes out;
-    float r1[8];
-    uint32_t l1 = 0;
+    PolarState s;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-        float ya = y[2 * p], yb = y[2 * p + 1];
-        float ua = fabsf(ya), ub = fabsf(yb);
-        uint32_t mq = quant3(ua, ub, th.t1a, th.t1c);
-        /* quadrant of atan2(yb, ya) in [0, 2 pi): cells are pi/8 wide */
-        uint32_t code = (ya < 0.0f) ? ((yb < 0.0f) ? 8u + mq : 7u - mq)
-                                    : ((yb < 0.0f) ? 15u - mq : mq);
-        l1 |= code << (4 * p);
-        r1[p] = __builtin_amdgcn_sqrtf(ya * ya + yb * yb);
+        polar_level1_a(s, y, p, th);
+        polar_level1_b(s, y, p);
+        polar_upper(s, p, th);
     }
-    float r2[4];
-    uint32_t c2[4];
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-        c2[n] = quant3(r1[2 * n], r1[2 * n + 1], th.t2a, th.t2c);
-        r2[n] = __builtin_amdgcn_sqrtf(r1[2 * n] * r1[2 * n] + r1[2 * n + 1] * r1[2 * n + 1]);
-    }
-    float r3[2];
-    uint32_t c3[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        c3[h] = quant3(r2[2 * h], r2[2 * h + 1], th.t3a, th.t3c);
-        r3[h] = __builtin_amdgcn_sqrtf(r2[2 * h] * r2[2 * h] + r2[2 * h + 1] * r2[2 * h + 1]);
-    }
-    out.c4 = quant3(r3[0], r3[1], th.t4a, th.t4c);
-    float r4 = __builtin_amdgcn_sqrtf(r3[0] * r3[0] + r3[1] * r3[1]);
-    _Float16 rh = (_Float16)r4; /* round to nearest even */
-    out.radius = __builtin_bit_cast(uint16_t, rh);
-    out.l1 = l1;
-    out.g0 = (c2[0] << 4) | (c3[0] << 2) | c2[1];
-    out.g1 = (c2[2] << 4) | (c3[1] << 2) | c2[3];
-    return out;
+    return s.out;
 }
 
 /* Scatter the fields of block b of slot tau into the tile image (codes, then radii). */
@@ -179,9 +217,99 @@ __device__ __forceinline__ void emit_block(uint32_t *img, int tau, int b, const 
     img16[PQL_CODE_BYTES / 2 + pos.radius_half] = bc.radius;
 }
 
-template <int XT, int KIND>
-__global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
+/* ---- full tiles: whole dwords assembled in registers, no atomics ----
+ * In the bulk kernel lane (H, j) holds, at row tile st, block b = 4H + st of tokens
+ * tau = j (v = 0) and 32 + j (v = 1).  The fields narrower than a dword that share
+ * dwords with other tokens (G6, C4) are collected across lanes with DPP and one
+ * lane-exchange, so that each dword of the image is written once by one lane. */
+__device__ __forceinline__ uint32_t quad_or(uint32_t x)
 {
+    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false);
+    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, false);
+    return x;
+}
+
+__device__ __forceinline__ uint32_t from_odd_even_neighbour(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false);
+}
+
+/* four 24-bit chunks -> the three dwords of a lane's 96-bit G6 string */
+__device__ __forceinline__ void store_chunks96(uint32_t *dst, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3)
+{
+    dst[0] = (c0 & 0xFFFFFFu) | (c1 << 24);
+    dst[1] = ((c1 >> 8) & 0xFFFFu) | (c2 << 16);
+    dst[2] = ((c2 >> 16) & 0xFFu) | (c3 << 8);
+}
+
+/* Key tile, fields of two consecutive row tiles (blocks 2gk and 2gk+1 of the same
+ * tokens): lane lambda = 16 gk + m of the tile owns chunk i of token 16 i + m;
+ * here lane j holds chunks i = j>>4 (v = 0) and 2 + (j>>4) (v = 1). */
+struct KeyHeld { uint32_t g12[2], c4[2], rad[2]; };
+
+__device__ __forceinline__ void emit_key_l1(uint32_t *img, int j, int H, int st, int v, uint32_t l1)
+{
+    const int lam = 16 * (2 * H + (st >> 1)) + (j & 15);
+    img[((v ? PQL_OFF_L1B : PQL_OFF_L1A) + lam * 16 + (j >> 4) * 8 + (st & 1) * 4) >> 2] = l1;
+}
+
+__device__ __forceinline__ void emit_key_pair(uint32_t *img, int j, int H, int st, const KeyHeld &even,
+                                              const BlockCodes (&odd)[2])
+{
+    const int lam = 16 * (2 * H + (st >> 1)) + (j & 15);
+    uint32_t P[2], Q[2];
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+        const int i = 2 * v + (j >> 4);
+        img[PQL_CODE_BYTES / 4 + lam * 4 + i] = even.rad[v] | ((uint32_t)odd[v].radius << 16);
+        const uint32_t chunk = even.g12[v] | ((odd[v].g0 | (odd[v].g1 << 6)) << 12);
+        P[v] = chunk | ((even.c4[v] | (odd[v].c4 << 2)) << 24);
+        Q[v] = (uint32_t)__shfl_xor((int)P[v], 16);
+    }
+    if ((j >> 4) == 0) { /* chunks 0 and 2 are this lane's, 1 and 3 the partner's */
+        store_chunks96(img + (PQL_OFF_G6 >> 2) + 3 * lam, P[0], Q[0], P[1], Q[1]);
+        reinterpret_cast<uint16_t *>(img)[(PQL_OFF_C4 >> 1) + lam] =
+            (uint16_t)((P[0] >> 24) | ((Q[0] >> 24) << 4) | ((P[1] >> 24) << 8) | ((Q[1] >> 24) << 12));
+    }
+}
+
+/* Value tile, one row tile: the 16 slots of a (token group g, block b) pair sit in the
+ * quads of lanes 4g..4g+3 and 16+4g..16+4g+3, both halves v. */
+__device__ __forceinline__ void emit_value_full(uint32_t *img, int j, int b, const BlockCodes (&bc)[2])
+{
+    const int g = (j >> 2) & 3, e = j & 3, jhi = j >> 4;
+    const int lam0 = 16 * g + 2 * b, gb = g * 8 + b;
+    uint32_t P0[2], P1[2], Q0[2], Q1[2];
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+        const int s = 8 * v + 4 * jhi + e;
+        /* level-1 halves and radii: lanes e, e+1 (e even) fill one dword together */
+        const uint32_t nl1 = from_odd_even_neighbour(bc[v].l1);
+        const uint32_t nrad = from_odd_even_neighbour(bc[v].radius);
+        const int l1_base = ((v ? PQL_OFF_L1B : PQL_OFF_L1A) + (4 * jhi + (e & 2)) * 2) >> 2;
+        if ((e & 1) == 0) {
+            img[l1_base + lam0 * 4] = (bc[v].l1 & 0xFFFFu) | (nl1 << 16);
+            img[PQL_CODE_BYTES / 4 + ((gb * 16 + s) >> 1)] = (uint32_t)bc[v].radius | (nrad << 16);
+        } else {
+            img[l1_base + (lam0 + 1) * 4] = (nl1 >> 16) | (bc[v].l1 & 0xFFFF0000u);
+        }
+        P0[v] = quad_or((bc[v].g0 << (6 * e)) | (bc[v].c4 << (24 + 2 * e)));
+        P1[v] = quad_or(bc[v].g1 << (6 * e));
+        Q0[v] = (uint32_t)__shfl_xor((int)P0[v], 16);
+        Q1[v] = (uint32_t)__shfl_xor((int)P1[v], 16);
+    }
+    if (jhi == 0) { /* this quad holds chunks 0 and 2, the other one chunks 1 and 3 */
+        if (e == 0) store_chunks96(img + (PQL_OFF_G6 >> 2) + 3 * lam0, P0[0], Q0[0], P0[1], Q0[1]);
+        if (e == 1) store_chunks96(img + (PQL_OFF_G6 >> 2) + 3 * (lam0 + 1), P1[0], Q1[0], P1[1], Q1[1]);
+        if (e == 2)
+            img[(PQL_OFF_C4 >> 2) + gb] = (P0[0] >> 24) | ((Q0[0] >> 24) << 8) | ((P0[1] >> 24) << 16) | ((Q0[1] >> 24) << 24);
+    }
+}
+
+template <int XT, int KIND>
+__global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(EncodeArgs a)
+{
+    constexpr int kWaves = EncodeShape<XT>::waves, kThreads = kWaves * 64;
     __shared__ uint4 sS[kSChunks];                  /* 96 KB: S1, S2, S3 in A-operand order */
     __shared__ uint32_t sImg[kWaves][kImgDwords];   /* one tile image per wavefront */
 
@@ -194,27 +322,54 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
     uint32_t *img = sImg[wave];
     const int j = lane & 31, H = lane >> 5; /* vector within the 32-vector group, lane half */
 
-    for (int64_t item = (int64_t)blockIdx.x * kWaves + wave; item < a.n_items; item += (int64_t)gridDim.x * kWaves) {
-        /* ---- which tile, which source rows ---- */
+    /* bf16 input: both 32-vector halves of the tile share every A-operand fetch (halves the
+       LDS traffic); fp32 input carries three bf16 terms per value and goes one half at a time */
+    constexpr int NXT = (XT == PQ_BF16) ? 1 : 3; /* bf16 terms of x */
+    constexpr int NVT = (XT == PQ_BF16) ? 2 : 1; /* 32-vector halves per pass */
+    BOperand xb[NVT][NXT][8];
+
+    /* which tile and which source rows an item covers */
+    struct Geometry {
         int head;
-        int64_t tile;      /* tile index inside the head plane */
+        int64_t tile;       /* tile index inside the head plane */
         int tau_lo, tau_hi; /* slots [tau_lo, tau_hi) of the tile are written */
-        int64_t src_t0;    /* source token index of slot tau_lo */
-        head = (int)(item / a.n_tiles);
-        int64_t trel = item % a.n_tiles;
-        tile = a.first_tile + trel;
-        int64_t lo = tile * 64 > a.dst0 ? tile * 64 : a.dst0;
-        int64_t hi = (tile + 1) * 64 < a.dst0 + a.n_tokens ? (tile + 1) * 64 : a.dst0 + a.n_tokens;
-        tau_lo = (int)(lo - tile * 64);
-        tau_hi = (int)(hi - tile * 64);
-        src_t0 = lo - a.dst0;
+        int64_t src_t0;     /* source token index of slot tau_lo */
+    };
+    auto geometry = [&](int64_t item) {
+        Geometry g;
+        g.head = (int)(item / a.n_tiles);
+        g.tile = a.first_tile + item % a.n_tiles;
+        const int64_t lo = g.tile * 64 > a.dst0 ? g.tile * 64 : a.dst0;
+        const int64_t hi = (g.tile + 1) * 64 < a.dst0 + a.n_tokens ? (g.tile + 1) * 64 : a.dst0 + a.n_tokens;
+        g.tau_lo = (int)(lo - g.tile * 64);
+        g.tau_hi = (int)(hi - g.tile * 64);
+        g.src_t0 = lo - a.dst0;
+        return g;
+    };
+    /* element offset of the input row that feeds slot tau_ of the item; a lane without a slot
+       to write reads the first row of the range again: its results are never emitted, and
+       every address stays inside the input */
+    auto source_row = [&](const Geometry &g, int tau_) {
+        const bool ok = tau_ >= g.tau_lo && tau_ < g.tau_hi;
+        const int64_t t_src = g.src_t0 + (ok ? tau_ - g.tau_lo : 0);
+        return t_src * a.ld_token + (int64_t)g.head * a.ld_head;
+    };
+    const int64_t item_stride = (int64_t)gridDim.x * kWaves;
+    const int64_t item0 = (int64_t)blockIdx.x * kWaves + wave;
+
+    for (int64_t item = item0; item < a.n_items; item += item_stride) {
+        const Geometry geo = geometry(item);
+        const int head = geo.head, tau_lo = geo.tau_lo, tau_hi = geo.tau_hi;
+        const int64_t tile = geo.tile;
         const bool full = (tau_lo == 0 && tau_hi == 64);
         uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
         uint16_t *gradii = a.radii + ((int64_t)head * a.pool_tiles + tile) * PQL_RADII;
 
         /* ---- tile image: zeros, or the tile's present contents if only part of it is written ---- */
+        constexpr bool kAssembled = (XT == PQ_BF16); /* full tiles written as whole dwords from registers */
         if (full) {
-            for (int c = lane; c < kImgDwords; c += 64) img[c] = 0u;
+            if (!kAssembled)
+                for (int c = lane; c < kImgDwords; c += 64) img[c] = 0u;
         } else {
             const uint32_t *gc = reinterpret_cast<const uint32_t *>(gcodes);
             const uint32_t *gr = reinterpret_cast<const uint32_t *>(gradii);
@@ -223,39 +378,29 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
         }
         wave_lds_sync();
 
-        /* bf16 input: both 32-vector halves of the tile share every A-operand fetch (halves the
-           LDS traffic); fp32 input carries three bf16 terms per value and goes one half at a time */
-        constexpr int NXT = (XT == PQ_BF16) ? 1 : 3; /* bf16 terms of x */
-        constexpr int NVT = (XT == PQ_BF16) ? 2 : 1; /* 32-vector halves per pass */
         for (int vt0 = 0; vt0 < 2; vt0 += NVT) {
             /* wave-uniform skip of a pass with nothing to write */
             if (32 * (vt0 + NVT) <= tau_lo || 32 * vt0 >= tau_hi) continue;
 
-            /* ---- B operands: this lane's 8-coordinate slices of its vectors, every k-step ---- */
-            BOperand xb[NVT][NXT][8];
             bool valid[NVT];
             int tau[NVT];
 #pragma unroll
             for (int v = 0; v < NVT; ++v) {
                 tau[v] = 32 * (vt0 + v) + j;
                 valid[v] = tau[v] >= tau_lo && tau[v] < tau_hi;
-                int64_t t_src = src_t0 + (tau[v] - tau_lo);
-                int64_t row = t_src * a.ld_token + (int64_t)head * a.ld_head;
+                /* ---- B operands: this lane's 8-coordinate slices of its vector, every k-step
+                   (coordinates 64 H + 8 ks .. + 7: one contiguous half row per lane) ---- */
+                const int64_t row = source_row(geo, tau[v]);
                 if constexpr (XT == PQ_BF16) {
                     const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.x) + row);
 #pragma unroll
-                    for (int ks = 0; ks < 8; ++ks) {
-                        uint4 q = make_uint4(0, 0, 0, 0);
-                        if (valid[v]) q = xr[2 * ks + H];
-                        xb[v][0][ks].q = q;
-                    }
+                    for (int ks = 0; ks < 8; ++ks) xb[v][0][ks].q = xr[8 * H + ks];
                 } else {
                     const float4 *xr = reinterpret_cast<const float4 *>(static_cast<const float *>(a.x) + row);
 #pragma unroll
                     for (int ks = 0; ks < 8; ++ks) {
                         float f[8];
-                        float4 p0 = make_float4(0, 0, 0, 0), p1 = p0;
-                        if (valid[v]) { p0 = xr[4 * ks + 2 * H]; p1 = xr[4 * ks + 2 * H + 1]; }
+                        const float4 p0 = xr[16 * H + 2 * ks], p1 = xr[16 * H + 2 * ks + 1]; /* coordinates 64 H + 8 ks .. + 7 */
                         f[0] = p0.x; f[1] = p0.y; f[2] = p0.z; f[3] = p0.w;
                         f[4] = p1.x; f[5] = p1.y; f[6] = p1.z; f[7] = p1.w;
 #pragma unroll
@@ -279,38 +424,104 @@ __global__ __launch_bounds__(kThreads) void pq_encode_kernel(EncodeArgs a)
                 }
             }
 
-#pragma unroll 1
-            for (int rt = 0; rt < 4; ++rt) {
-                /* ---- D[i][j] = sum_k S[k][col(rt,i)] * x[j][k]: 32 rotated coordinates x 32 vectors ---- */
-                f32x16 acc[NVT];
+            /* D[i][j] = sum_k S[k][col(rt,i)] * x[j][k]: 32 rotated coordinates x 32 vectors per row
+               tile rt.  The products of row tile rt+1 are issued between the steps of the polar
+               recursion of row tile rt, in a fixed interleaving: each pair of matrix instructions
+               is followed by a slice of vector work that does not depend on them, so the matrix
+               cores run while the vector ALU quantises.  Stage -1 only multiplies, stage 3 only
+               quantises. */
+            f32x16 acc_even[NVT], acc_odd[NVT];
+            KeyHeld held = {};
 #pragma unroll
-                for (int v = 0; v < NVT; ++v)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[v][r] = 0.0f;
+            for (int st = -1; st < 4; ++st) {
+                f32x16 (&cur)[NVT] = (st & 1) ? acc_odd : acc_even;   /* row tile st: quantised now */
+                f32x16 (&nxt)[NVT] = (st & 1) ? acc_even : acc_odd;   /* row tile st+1: accumulated now */
+                const bool mul = st < 3, quant = st >= 0;
+                PolarState ps[NVT];
+                BOperand sa_next;
+                if (mul) sa_next.q = sS[((2 * 4 + (st + 1)) * 8 + 0) * 64 + lane];
+                /* slice m of the vector work that goes with k-step ks: six slices, one after each
+                   of the six matrix instructions of the k-step */
+                constexpr int NM = NVT * (NXT == 1 ? 3 : 6); /* matrix instructions per k-step */
+                auto slice = [&](int ks, int m) {
+                    if (NVT == 2) {
+                        if (m == 0) polar_level1_a(ps[0], cur[0], ks, th);
+                        if (m == 1) polar_level1_b(ps[0], cur[0], ks);
+                        if (m == 2) polar_level1_a(ps[NVT - 1], cur[NVT - 1], ks, th);
+                        if (m == 3) polar_level1_b(ps[NVT - 1], cur[NVT - 1], ks);
+                        if (m == 4) polar_upper(ps[0], ks, th);
+                        if (m == 5) polar_upper(ps[NVT - 1], ks, th);
+                    } else {
+                        if (m == 0) polar_level1_a(ps[0], cur[0], ks, th);
+                        if (m == NM / 3) polar_level1_b(ps[0], cur[0], ks);
+                        if (m == 2 * NM / 3) polar_upper(ps[0], ks, th);
+                    }
+                };
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks) {
-                    /* smallest terms first */
+                    int m = 0;
 #pragma unroll
-                    for (int term = 2; term >= 0; --term) {
-                        BOperand sa;
-                        sa.q = sS[((term * 4 + rt) * 8 + ks) * 64 + lane];
+                    for (int term = 2; term >= 0; --term) { /* smallest terms first */
+                        if (mul) {
+                            /* A operand of this step; the next one is requested from LDS right away */
+                            const BOperand sa = sa_next;
+                            const int nterm = term > 0 ? term - 1 : 2, nks = term > 0 ? ks : ks + 1;
+                            if (nks < 8) sa_next.q = sS[((nterm * 4 + (st + 1)) * 8 + nks) * 64 + lane];
 #pragma unroll
-                        for (int v = 0; v < NVT; ++v)
+                            for (int v = 0; v < NVT; ++v)
 #pragma unroll
-                            for (int xt = 0; xt < NXT; ++xt) {
-                                if (xt + term > 2) continue; /* below 2^-24 of the leading product */
-                                acc[v] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa.v, xb[v][xt][ks].v, acc[v], 0, 0, 0);
-                            }
+                                for (int xt = 0; xt < NXT; ++xt) {
+                                    if (xt + term > 2) continue; /* below 2^-24 of the leading product */
+                                    /* the first product of a row tile starts from a zero accumulator operand */
+                                    const bool first = (ks == 0 && term == 2 && xt == 0);
+                                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                                    nxt[v] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa.v, xb[v][xt][ks].v, first ? zero : nxt[v], 0, 0, 0);
+                                    if (quant) {
+                                        slice(ks, m);
+                                        __builtin_amdgcn_sched_barrier(0);
+                                    }
+                                    ++m;
+                                }
+                        }
+                    }
+                    if (!mul) {
+#pragma unroll
+                        for (int mm = 0; mm < NM; ++mm) slice(ks, mm);
                     }
                 }
-                /* lane (H, j): acc[v][r] = rotated coordinate 16*(4H + rt) + r of vector tau[v] */
-                const int b = 4 * H + rt;
+                if (quant) {
+                    /* lane (H, j): cur[v][r] = rotated coordinate 16*(4H + st) + r of vector tau[v] */
+                    const int b = 4 * H + st;
+                    /* a full tile has a slot for every lane: no per-lane branch there.  (Around a
+                       single vector's fields it would let the optimiser move that vector's whole
+                       recursion behind the branch and undo the interleaving above.) */
+                    if (full) {
+                        if constexpr (kAssembled && NVT == 2) {
+                            BlockCodes bc[2] = {ps[0].out, ps[1].out};
+                            if (KIND == PQ_KEY) {
 #pragma unroll
-                for (int v = 0; v < NVT; ++v) {
-                    const BlockCodes bc = polar_quant_block(acc[v], th);
-                    if (valid[v]) {
-                        if (full) emit_block<KIND, false>(img, tau[v], b, bc);
-                        else emit_block<KIND, true>(img, tau[v], b, bc);
+                                for (int v = 0; v < 2; ++v) emit_key_l1(img, j, H, st, v, bc[v].l1);
+                                if ((st & 1) == 0) {
+#pragma unroll
+                                    for (int v = 0; v < 2; ++v) {
+                                        held.g12[v] = bc[v].g0 | (bc[v].g1 << 6);
+                                        held.c4[v] = bc[v].c4;
+                                        held.rad[v] = bc[v].radius;
+                                    }
+                                } else {
+                                    emit_key_pair(img, j, H, st, held, bc);
+                                }
+                            } else {
+                                emit_value_full(img, j, b, bc);
+                            }
+                        } else {
+#pragma unroll
+                            for (int v = 0; v < NVT; ++v) emit_block<KIND, false>(img, tau[v], b, ps[v].out);
+                        }
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < NVT; ++v)
+                            if (valid[v]) emit_block<KIND, true>(img, tau[v], b, ps[v].out);
                     }
                 }
             }
@@ -412,6 +623,7 @@ pq_status launch_encode(const EncodeArgs &a, hipStream_t stream)
         cached_cus[dev] = n;
     }
     const int cus = cached_cus[dev];
+    constexpr int kWaves = EncodeShape<XT>::waves, kThreads = kWaves * 64;
     int64_t blocks = (a.n_items + kWaves - 1) / kWaves;
     if (blocks > cus) blocks = cus;
     if (blocks < 1) blocks = 1;

@@ -377,7 +377,10 @@ pq_status pq_device_state(const pq_ctx *cctx, const PqDeviceState **out)
                 for (int lane = 0; lane < 64; ++lane)
                     for (int e = 0; e < 8; ++e) {
                         int kg = lane >> 5, i = lane & 31;
-                        int row = 16 * ks + 8 * kg + e;
+                        /* k-step ks contracts input coordinates 8 ks .. 8 ks + 7 (lane half 0) and
+                           64 + 8 ks .. (lane half 1): a lane of the kernel then reads one contiguous
+                           half of its input row over the eight k-steps */
+                        int row = 64 * kg + 8 * ks + e;
                         int col = 16 * (4 * ((i >> 2) & 1) + rt) + 4 * (i >> 3) + (i & 3);
                         double v = ctx->S[(size_t)row * d + col];
                         uint16_t t1 = to_bfloat16(v);
