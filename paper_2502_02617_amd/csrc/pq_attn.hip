@@ -477,7 +477,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 4) void pq_attn_partial_kernel
     }
     __syncthreads();
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    /* the wavefront index is the same in all lanes: telling the compiler so keeps everything
+       derived from it (work item, pointers, loop bounds) in scalar registers */
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
     const int chunk = (int)(item % a.n_chunks);
     const int hk = (int)((item / a.n_chunks) % a.Hkv);

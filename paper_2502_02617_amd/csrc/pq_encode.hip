@@ -313,7 +313,9 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
     __shared__ uint4 sS[kSChunks];                  /* 96 KB: S1, S2, S3 in A-operand order */
     __shared__ uint32_t sImg[kWaves][kImgDwords];   /* one tile image per wavefront */
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    /* same value in all lanes: keeps the item geometry and the tile pointers in scalar registers */
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     for (int c = threadIdx.x; c < kSChunks; c += kThreads) sS[c] = a.S_bf16x3[c];
     __syncthreads();
 
