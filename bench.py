@@ -36,8 +36,8 @@ B, HQ, HKV, CTX, D = 16, 32, 8, 32768, 128
 N_CACHES = 3
 BYTES_PER_TOKEN_HEAD = 124  # 62-byte key record + 62-byte value record
 # HBM bytes per launch of pq_attn_partial_kernel on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled
-# by a plain copy of known size (profiles/attn_partial_cfg2_counters.txt): 521.4 MB read + 12.7 MB written.
-MEASURED_TRAFFIC_BYTES = 521.4e6 + 12.7e6
+# by a plain copy of known size (profiles/attn_partial_cfg2_counters.txt): 522.4 MB read + 8.5 MB written.
+MEASURED_TRAFFIC_BYTES = 522.4e6 + 8.5e6
 
 
 def main():
