@@ -38,6 +38,11 @@ BYTES_PER_TOKEN_HEAD = 124  # 62-byte key record + 62-byte value record
 # HBM bytes per launch of pq_attn_partial_kernel on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled
 # by a plain copy of known size (profiles/attn_partial_cfg2_counters.txt): 522.4 MB read + 8.5 MB written.
 MEASURED_TRAFFIC_BYTES = 522.4e6 + 8.5e6
+# Secondary bound of the same kernel: vector-ALU issue.  Its tile loop holds 1004 vector instructions per 64-token
+# tile of one kv head (compiled code, counted in the assembly listing); one SIMD issues one 64-lane vector
+# instruction per 4 cycles: 256 CUs x 4 SIMDs x 2.4 GHz / 4 = 614.4 G wavefront instructions/s at most.
+VALU_INSTR_PER_TILE = 1004
+VALU_PEAK_GINSTR = 256 * 4 * 2.4 / 4.0
 
 
 def main():
@@ -180,6 +185,14 @@ def main():
             "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated; separate profiling run)",
             "kernel_avg_ms": round(kern_ms, 5),
             "launches_timed": prof["attn_launches"],
+        },
+        "roofline_alu": {
+            "bound": "alu",
+            "kernel": "pq_attn_partial_kernel",
+            "achieved": round(VALU_INSTR_PER_TILE * B * HKV * (CTX // 64) / (kern_ms * 1e-3) / 1e9, 1) if kern_ms > 0 else 0.0,
+            "peak": VALU_PEAK_GINSTR,
+            "unit": "G wavefront vector instructions/s",
+            "frac": round(VALU_INSTR_PER_TILE * B * HKV * (CTX // 64) / (kern_ms * 1e-3) / 1e9 / VALU_PEAK_GINSTR, 4) if kern_ms > 0 else 0.0,
         },
         "encode": {
             "workload": "configs[1]: 8 kv heads x 32768 tokens, bf16 keys and values with outlier channels",

@@ -301,6 +301,59 @@ def test_attention_medium_against_oracle(env):
     assert err <= 2e-3
 
 
+@pytest.mark.parametrize("shape", ["rising", "falling", "spike"])
+def test_attention_moving_maximum(env, shape):
+    """Scores that climb (or fall) steadily along the context, or jump by a large amount at one token:
+    the running exponent reference of the softmax has to follow without losing small or large weights."""
+    ctx, S, cb = env
+    lens = [300, 1000, 3000]
+    say(f"attention with {shape} scores, lens={lens}")
+    B, Hq, Hkv = len(lens), 4, 1
+    g = torch.Generator().manual_seed(900)
+    u = torch.randn(128, generator=g, dtype=torch.float64)
+    u = u / u.norm()
+    # the four heads of the group see the ramp with different slopes and signs
+    gains = torch.tensor([1.0, 2.5, -1.0, 0.25], dtype=torch.float64)
+    q = (gains[None, :, None] * u[None, None, :] * math.sqrt(128.0)).repeat(B, 1, 1)
+    q = (q + 0.05 * torch.randn(q.shape, generator=g, dtype=torch.float64)).to(torch.bfloat16)
+    starts, pool = [], 0
+    for n in lens:
+        starts.append(pool)
+        pool += ((n + 63) // 64) * 64
+    kc, kr = Context.alloc_cache(Hkv, pool, DEV)
+    vc, vr = Context.alloc_cache(Hkv, pool, DEV)
+    for t in (kc, kr, vc, vr):
+        t.zero_()
+    k_rec = np.zeros((Hkv, pool, 62), dtype=np.uint8)
+    v_rec = np.zeros((Hkv, pool, 62), dtype=np.uint8)
+    for b, n in enumerate(lens):
+        t = torch.arange(n, dtype=torch.float64) / n
+        if shape == "rising":
+            c = 40.0 * t
+        elif shape == "falling":
+            c = 40.0 * (1.0 - t)
+        else:
+            c = torch.zeros(n, dtype=torch.float64)
+            c[(2 * n) // 3] = 30.0
+        k = c[:, None] * u[None, :] + torch.randn((n, 128), generator=g, dtype=torch.float64)
+        k = k.to(torch.bfloat16)[:, None, :].contiguous()             # [n, 1, 128]
+        v = synth.kv_stream(n, Hkv, 901 + b).permute(1, 0, 2).contiguous()
+        ctx.encode_kv(k.to(DEV), PQ_KEY, kc, kr, dst_token0=starts[b])
+        ctx.encode_kv(v.to(DEV), PQ_VALUE, vc, vr, dst_token0=starts[b])
+        k_rec[:, starts[b]:starts[b] + n] = oracle_records(k, S, cb)[0]
+        v_rec[:, starts[b]:starts[b] + n] = oracle_records(v, S, cb)[0]
+    torch.cuda.synchronize()
+    starts = np.array(starts, dtype=np.int64)
+    got = gpu_attention(ctx, q, (kc, kr, vc, vr), starts, lens)
+    ref = oracle.attention(q.to(torch.float64).numpy(), k_rec, v_rec, starts, np.array(lens, np.int32), S, cb,
+                           helpers.softmax_scale())
+    assert np.all(np.isfinite(got))
+    err = helpers.rel_l2(got, ref)
+    per_row = [helpers.rel_l2(got[b, h], ref[b, h]) for b in range(B) for h in range(Hq)]
+    say(f"  rel L2 {err:.2e}; worst row {max(per_row):.2e}")
+    assert err <= 2e-3
+
+
 def test_attention_rejects_bad_sequences_gracefully(env):
     ctx, S, cb = env
     say("attention with an unaligned / out-of-pool sequence")
