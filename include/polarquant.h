@@ -125,6 +125,16 @@ pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind ki
                        int n_seq, int n_heads, uint8_t *codes, uint16_t *radii,
                        int64_t pool_tokens, const int64_t *dst_token, void *hip_stream);
 
+/* The same for the key and the value vectors of the new tokens in one launch
+ * (a decode step appends both): xk, xv (device) [n_seq][n_heads][128] contiguous,
+ * same dtype; both caches have pool_tokens slots per head plane and the vectors
+ * of sequence b go to slot dst_token[b] of either.  Results are identical to two
+ * pq_append_kv calls. */
+pq_status pq_append_kv_pair(const pq_ctx *ctx, const void *xk, const void *xv, pq_dtype xt,
+                            int n_seq, int n_heads, uint8_t *k_codes, uint16_t *k_radii,
+                            uint8_t *v_codes, uint16_t *v_radii, int64_t pool_tokens,
+                            const int64_t *dst_token, void *hip_stream);
+
 /* ---------------------------------------------------------------------------
  * DeQuant (Algorithm 1, procedure DeQuant): slots [token0, token0+n_tokens)
  * of every head plane are rebuilt top-down from the stored radius with the

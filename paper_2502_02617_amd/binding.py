@@ -1,7 +1,7 @@
 """ctypes binding of libpolarquant (argument marshalling only).
 
 Function names mirror the C ABI: ``Context`` wraps ``pq_init_preconditioner`` /
-``pq_destroy`` and its methods call ``pq_encode_kv``, ``pq_append_kv``,
+``pq_destroy`` and its methods call ``pq_encode_kv``, ``pq_append_kv``, ``pq_append_kv_pair``,
 ``pq_decode_kv``, ``pq_export_canonical`` and ``pq_attn_decode_polar`` with
 pointers of torch tensors (torch is used for device memory and streams only).
 """
@@ -51,6 +51,8 @@ def library():
     L.pq_encode_kv.argtypes = [vp, vp, i32, i32, i64, i32, i64, i64, vp, vp, i64, i64, vp]
     L.pq_append_kv.restype = i32
     L.pq_append_kv.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i64, vp, vp]
+    L.pq_append_kv_pair.restype = i32
+    L.pq_append_kv_pair.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, i64, vp, vp]
     L.pq_decode_kv.restype = i32
     L.pq_decode_kv.argtypes = [vp, i32, vp, vp, i64, i64, i64, i32, vp, i32, i64, i64, i32, vp]
     L.pq_export_canonical.restype = i32
@@ -182,6 +184,20 @@ class Context:
         _check(library().pq_append_kv(self._h, x.data_ptr(), _dtype_code(x), int(kind), int(x.shape[0]), int(x.shape[1]),
                                       codes.data_ptr(), radii.data_ptr(), int(pool_tokens), dst_token.data_ptr(),
                                       _stream()))
+
+    def append_kv_pair(self, xk, xv, k_codes, k_radii, v_codes, v_radii, dst_token):
+        """xk, xv: [n_seq, n_heads, 128] contiguous, same dtype; dst_token: int64 device tensor [n_seq]."""
+        if not (xk.is_contiguous() and xv.is_contiguous()):
+            raise PolarQuantError("xk and xv must be contiguous")
+        if xk.shape != xv.shape or xk.dtype != xv.dtype:
+            raise PolarQuantError("xk and xv must have the same shape and dtype")
+        if k_codes.shape != v_codes.shape:
+            raise PolarQuantError("key and value caches must have the same pool size")
+        pool_tokens = k_codes.shape[1] * TILE_TOKENS
+        _check(library().pq_append_kv_pair(self._h, xk.data_ptr(), xv.data_ptr(), _dtype_code(xk), int(xk.shape[0]),
+                                           int(xk.shape[1]), k_codes.data_ptr(), k_radii.data_ptr(),
+                                           v_codes.data_ptr(), v_radii.data_ptr(), int(pool_tokens),
+                                           dst_token.data_ptr(), _stream()))
 
     def decode_kv(self, kind, codes, radii, token0, n_tokens, out, rotated=False):
         """out: [n_tokens, n_heads, 128] float32 or bfloat16 (strides taken from the tensor)."""

@@ -573,13 +573,14 @@ __device__ __forceinline__ void put_bits_global(uint8_t *codes, uint32_t bit, in
     }
 }
 
-template <int XT, int KIND>
-__global__ __launch_bounds__(512) void pq_append_kernel(AppendArgs a)
+/* one (sequence, head) vector of kind `kind`, by one workgroup */
+template <int XT>
+__device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int vec)
 {
     __shared__ float sx[PQ_D];
     __shared__ float sy[PQ_D];
     __shared__ float spart[4][PQ_D];
-    const int seq = blockIdx.x / a.n_heads, head = blockIdx.x % a.n_heads, tid = threadIdx.x, j = tid & 127;
+    const int seq = vec / a.n_heads, head = vec % a.n_heads, tid = threadIdx.x, j = tid & 127;
     const int64_t dst = a.dst_token[seq];
     if (dst < 0 || dst >= a.pool_tokens) return; /* slot outside the pool: nothing is written */
     const int64_t row = ((int64_t)seq * a.n_heads + head) * PQ_D;
@@ -602,7 +603,7 @@ __global__ __launch_bounds__(512) void pq_append_kernel(AppendArgs a)
         const int tau = (int)(dst & 63);
         uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
         uint16_t *gradii = a.radii + ((int64_t)head * a.pool_tiles + tile) * PQL_RADII;
-        PqBlockPos pos = pql_pos(KIND, tau, b);
+        PqBlockPos pos = pql_pos(kind, tau, b);
         *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[0]) = (uint16_t)(bc.l1 & 0xFFFFu);
         *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[1]) = (uint16_t)(bc.l1 >> 16);
         put_bits_global(gcodes, pos.g6_bit[0], 6, bc.g0);
@@ -610,6 +611,21 @@ __global__ __launch_bounds__(512) void pq_append_kernel(AppendArgs a)
         put_bits_global(gcodes, pos.c4_bit, 2, bc.c4);
         gradii[pos.radius_half] = bc.radius;
     }
+}
+
+template <int XT, int KIND>
+__global__ __launch_bounds__(512) void pq_append_kernel(AppendArgs a)
+{
+    append_vector<XT>(a, KIND, (int)blockIdx.x);
+}
+
+/* keys and values of the same tokens in one launch: workgroups [0, n) take the key vectors,
+   [n, 2n) the value vectors (a decode step appends both; one launch saves a dispatch) */
+template <int XT>
+__global__ __launch_bounds__(512) void pq_append_pair_kernel(AppendArgs k, AppendArgs v, int n)
+{
+    if ((int)blockIdx.x < n) append_vector<XT>(k, PQ_KEY, (int)blockIdx.x);
+    else append_vector<XT>(v, PQ_VALUE, (int)blockIdx.x - n);
 }
 
 template <int XT, int KIND>
@@ -706,6 +722,33 @@ extern "C" pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt,
         if (kind == PQ_KEY) hipLaunchKernelGGL((pq_append_kernel<PQ_F32, PQ_KEY>), grid, block, 0, s, a);
         else hipLaunchKernelGGL((pq_append_kernel<PQ_F32, PQ_VALUE>), grid, block, 0, s, a);
     }
+    PQ_HIP_TRY(hipGetLastError());
+    return PQ_OK;
+}
+
+extern "C" pq_status pq_append_kv_pair(const pq_ctx *ctx, const void *xk, const void *xv, pq_dtype xt,
+                                       int n_seq, int n_heads, uint8_t *k_codes, uint16_t *k_radii,
+                                       uint8_t *v_codes, uint16_t *v_radii, int64_t pool_tokens,
+                                       const int64_t *dst_token, void *hip_stream)
+{
+    if (!ctx) return PQ_EINVAL;
+    if (n_seq == 0) return PQ_OK;
+    if (!xk || !xv || !k_codes || !k_radii || !v_codes || !v_radii || !dst_token) return PQ_EINVAL;
+    if (xt != PQ_F32 && xt != PQ_BF16) return PQ_EINVAL;
+    if (n_seq < 0 || n_heads <= 0 || pool_tokens <= 0 || (pool_tokens & 63)) return PQ_EINVAL;
+    if (2 * (int64_t)n_seq * n_heads > 0x7FFFFFFF) return PQ_EINVAL;
+    if (!pq_aligned16(xk) || !pq_aligned16(xv) || !pq_aligned16(k_codes) || !pq_aligned16(k_radii) ||
+        !pq_aligned16(v_codes) || !pq_aligned16(v_radii)) return PQ_EALIGN;
+    const PqDeviceState *ds = nullptr;
+    pq_status st = pq_device_state(ctx, &ds);
+    if (st != PQ_OK) return st;
+    AppendArgs ak{xk, k_codes, k_radii, pool_tokens / 64, pool_tokens, dst_token, n_heads, ds->S_f32, ds->consts};
+    AppendArgs av{xv, v_codes, v_radii, pool_tokens / 64, pool_tokens, dst_token, n_heads, ds->S_f32, ds->consts};
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int n = n_seq * n_heads;
+    dim3 grid((unsigned)(2 * n)), block(512);
+    if (xt == PQ_BF16) hipLaunchKernelGGL((pq_append_pair_kernel<PQ_BF16>), grid, block, 0, s, ak, av, n);
+    else hipLaunchKernelGGL((pq_append_pair_kernel<PQ_F32>), grid, block, 0, s, ak, av, n);
     PQ_HIP_TRY(hipGetLastError());
     return PQ_OK;
 }

@@ -176,6 +176,43 @@ def test_append_one_token_per_sequence(env):
             helpers.check_radii(rg, ro, y.reshape(-1, 128))
 
 
+def test_append_pair_equals_two_appends(env):
+    """pq_append_kv_pair writes what pq_append_kv(keys) + pq_append_kv(values) write, bit for bit."""
+    ctx, S, cb = env
+    say("append pair vs two single appends")
+    H, B, pool = 3, 5, 64 * 5
+    dst = torch.tensor([0, 64 + 63, 128 + 1, 192 + 30, 256 + 17], dtype=torch.int64, device=DEV)
+    caches = []
+    for _ in range(2):
+        kc, kr = Context.alloc_cache(H, pool, DEV)
+        vc, vr = Context.alloc_cache(H, pool, DEV)
+        old_k = synth.kv_stream(pool, H, seed=60).permute(1, 0, 2).contiguous().to(DEV)
+        old_v = synth.kv_stream(pool, H, seed=61).permute(1, 0, 2).contiguous().to(DEV)
+        ctx.encode_kv(old_k, PQ_KEY, kc, kr)      # neighbours of the patched slots must survive
+        ctx.encode_kv(old_v, PQ_VALUE, vc, vr)
+        caches.append((kc, kr, vc, vr))
+    for dtype in (torch.bfloat16, torch.float32):
+        nk = synth.kv_stream(B, H, seed=62).permute(1, 0, 2).contiguous().to(dtype).to(DEV)
+        nv = synth.kv_stream(B, H, seed=63).permute(1, 0, 2).contiguous().to(dtype).to(DEV)
+        kc, kr, vc, vr = caches[0]
+        ctx.append_kv(nk, PQ_KEY, kc, kr, dst)
+        ctx.append_kv(nv, PQ_VALUE, vc, vr, dst)
+        kc2, kr2, vc2, vr2 = caches[1]
+        ctx.append_kv_pair(nk, nv, kc2, kr2, vc2, vr2, dst)
+        torch.cuda.synchronize()
+        for a, b in zip(caches[0], caches[1]):
+            assert torch.equal(a, b)
+    # and against the oracle on the patched slots
+    kc2, kr2, vc2, vr2 = caches[1]
+    for kind, codes, radii, x in ((PQ_KEY, kc2, kr2, nk), (PQ_VALUE, vc2, vr2, nv)):
+        for b in range(B):
+            slot = int(dst[b])
+            rec = canonical_both_ways(ctx, kind, codes, radii, slot - slot % 64, 64)[:, slot % 64]
+            rec_or, psi, y = oracle_records(x[b:b + 1].cpu(), S, cb)
+            st, rg, ro = helpers.check_codes(rec.reshape(-1, 62), rec_or.reshape(-1, 62), psi.reshape(-1, 120))
+            helpers.check_radii(rg, ro, y.reshape(-1, 128))
+
+
 def test_encode_degenerate_inputs(env):
     ctx, S, cb = env
     say("degenerate encode inputs")
