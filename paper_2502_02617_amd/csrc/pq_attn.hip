@@ -581,9 +581,11 @@ __global__ __launch_bounds__(512) void pq_rotate_q_kernel(RotateArgs a)
     __shared__ float spart[4][PQ_D];
     const int tid = threadIdx.x, j = tid & 127;
     const int row = blockIdx.x;
+    MatrixSlice ms;
+    matrix_slice_load(ms, a.S, tid);
     if (tid < PQ_D) sq[j] = __uint_as_float((uint32_t)a.q[(int64_t)row * PQ_D + j] << 16);
     __syncthreads();
-    const float acc = vector_times_matrix(sq, a.S, spart, tid); /* q'_j = sum_i q_i S[i][j] */
+    const float acc = vector_times_slice(sq, ms, spart, tid); /* q'_j = sum_i q_i S[i][j] */
     if (tid < PQ_D) {
         /* rebuilt keys carry the table scale sigma of their coordinate: take it out here */
         const float v = acc * a.scale / a.consts->sigma[j & 15];
@@ -613,6 +615,8 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
     __shared__ float sl[4][PQ_D];
     const int tid = threadIdx.x, cq = tid >> 7, j = tid & 127;
     const int row = blockIdx.x;
+    MatrixSlice ms; /* requested first: its latency overlaps the reads of the partial results */
+    matrix_slice_load(ms, a.St, tid);
     const int b = row / a.Hq;
     const int ctx = effective_ctx(a.seq_start, a.ctx_len, b, a.max_ctx, a.pool_tiles);
     const int n_tiles = (ctx + 63) >> 6;
@@ -640,7 +644,7 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
         so[j] = used > 0 ? ot / (lt * a.consts->sigma[j & 15]) : 0.f;
     }
     __syncthreads();
-    const float acc = vector_times_matrix(so, a.St, spart, tid); /* out_j = sum_k o'_k S[j][k] */
+    const float acc = vector_times_slice(so, ms, spart, tid); /* out_j = sum_k o'_k S[j][k] */
     if (tid < PQ_D) {
         if (a.out_f32) {
             static_cast<float *>(a.out)[(int64_t)row * PQ_D + j] = acc;

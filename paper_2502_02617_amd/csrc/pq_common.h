@@ -79,24 +79,34 @@ static inline bool pq_aligned16(const void *p) { return (reinterpret_cast<uintpt
 /* ---- small dense products with S: one vector per 512-thread workgroup ----
  * out[j] = sum_k in[k] * M[k*128 + j].  Thread (kq, j) accumulates the k-quarter kq with
  * all 32 loads in flight at once (these kernels are latency bound, not bandwidth bound);
- * the four quarter sums are added in a fixed order by the threads of quarter 0. */
-static __device__ __forceinline__ float vector_times_matrix(const float (&sin)[PQ_D], const float *M,
-                                                     float (&spart)[4][PQ_D], int tid)
+ * the four quarter sums are added in a fixed order by the threads of quarter 0.
+ * The matrix part does not depend on the vector: a kernel requests it first
+ * (matrix_slice_load) and overlaps its latency with fetching the vector. */
+struct MatrixSlice {
+    float m[32];
+};
+
+static __device__ __forceinline__ void matrix_slice_load(MatrixSlice &s, const float *M, int tid)
 {
     const int kq = tid >> 7, j = tid & 127;
-    float m[32];
 #pragma unroll
-    for (int k = 0; k < 32; ++k) m[k] = M[(32 * kq + k) * PQ_D + j];
+    for (int k = 0; k < 32; ++k) s.m[k] = M[(32 * kq + k) * PQ_D + j];
+}
+
+static __device__ __forceinline__ float vector_times_slice(const float (&sin)[PQ_D], const MatrixSlice &s,
+                                                           float (&spart)[4][PQ_D], int tid)
+{
+    const int kq = tid >> 7, j = tid & 127;
     float acc = 0.f;
 #pragma unroll
-    for (int k = 0; k < 32; ++k) acc = fmaf(sin[32 * kq + k], m[k], acc);
+    for (int k = 0; k < 32; ++k) acc = fmaf(sin[32 * kq + k], s.m[k], acc);
     spart[kq][j] = acc;
     __syncthreads();
     return ((spart[0][j] + spart[1][j]) + spart[2][j]) + spart[3][j];
 }
 
 /* Layout of S_bf16x3 (halves): [term 3][row-tile 4][k-step 8][lane 64][8].
- * Lane l = 32*kg + i of (term, rt, ks) holds S_term[16*ks + 8*kg + e][col(rt, i)]
+ * Lane l = 32*kg + i of (term, rt, ks) holds S_term[64*kg + 8*ks + e][col(rt, i)]
  * for e = 0..7, where the 32 rows of row-tile rt map to rotated coordinates
  * col(rt, i) = 16*(4*((i>>2)&1) + rt) + 4*(i>>3) + (i&3). */
 #define PQ_SB_TERM_STRIDE (4 * 8 * 64 * 8)

@@ -581,6 +581,8 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
     __shared__ float sy[PQ_D];
     __shared__ float spart[4][PQ_D];
     const int seq = vec / a.n_heads, head = vec % a.n_heads, tid = threadIdx.x, j = tid & 127;
+    MatrixSlice ms;
+    matrix_slice_load(ms, a.S, tid);
     const int64_t dst = a.dst_token[seq];
     if (dst < 0 || dst >= a.pool_tokens) return; /* slot outside the pool: nothing is written */
     const int64_t row = ((int64_t)seq * a.n_heads + head) * PQ_D;
@@ -589,7 +591,7 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
         else sx[j] = static_cast<const float *>(a.x)[row + j];
     }
     __syncthreads();
-    const float acc = vector_times_matrix(sx, a.S, spart, tid); /* y_j = sum_i x_i S[i][j] */
+    const float acc = vector_times_slice(sx, ms, spart, tid); /* y_j = sum_i x_i S[i][j] */
     if (tid < PQ_D) sy[j] = acc;
     __syncthreads();
     if (tid < 8) {
