@@ -53,10 +53,13 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kProbShift = 9.0f;
 constexpr float kRefSlack = 6.0f;
 
-/* LDS table block (dwords): T1 [0,16)  T4 [16,20)  TA [32,48)  TB [48,64)
- * T4 broadcast per half: [64,68) cos, [68,72) sin as (f, f) pairs
- * T1 in fp32 [96,128): 16 (cos, sin) float pairs, one pair per two banks */
-constexpr int kT1 = 0, kT4 = 16, kTA = 32, kTB = 48, kT4B = 64, kT1F = 96, kTabDwords = 128;
+/* LDS table block (dwords).  Binary16 pairs for the value path: T1 [0,16)  T4 [16,20)
+ * TA [32,48)  TB [48,64); T4 broadcast per half: [64,68) cos, [68,72) sin as (f, f) pairs.
+ * fp32 for the key path: T1 [96,128) as 16 (cos, sin) pairs, one pair per two banks;
+ * TA [128,160), TB [160,192), T4 [192,200): the low halves of all entries, then the high
+ * halves (two 16-entry dword tables, one entry per bank, read with one two-address load). */
+constexpr int kT1 = 0, kT4 = 16, kTA = 32, kTB = 48, kT4B = 64, kT1F = 96;
+constexpr int kTAF = 128, kTBF = 160, kT4F = 192, kTabDwords = 208;
 
 struct AttnArgs {
     const uint16_t *qrot; /* [B][Hq][2][128] binary16: rotated, pre-scaled q' as a leading part and its remainder */
@@ -197,32 +200,10 @@ __device__ __forceinline__ void expand_half_block(h2 r3, const HalfBlockLut &l, 
     out[3] = bcast_hi(rb) * l.t1[3];
 }
 
-/* Mixed-precision multiplies (v_fma_mix*): operands are binary16 halves or fp32
- * registers, the product is formed exactly in fp32 and rounded once. */
-template <int SA, int SB>
-__device__ __forceinline__ float mix_mul_hh(h2 a, h2 b) /* half SA of a times half SB of b, exact */
-{
-    float d;
-    if (SA == 0 && SB == 0) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b));
-    else if (SA == 1 && SB == 0) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b));
-    else if (SA == 0 && SB == 1) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b));
-    else asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b));
-    return d;
-}
-
-template <int SB>
-__device__ __forceinline__ float mix_mul_fh(float a, h2 b) /* fp32 a times half SB of b */
-{
-    float d;
-    if (SB == 0) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(d) : "v"(a), "v"(b));
-    else asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "=v"(d) : "v"(a), "v"(b));
-    return d;
-}
-
-/* Key-side tables of one half-block: level-3 x level-2 products as binary16 pairs,
- * level-1 (cos, sin) as fp32 pairs. */
+/* Key-side tables of one half-block, all fp32: level-3 x level-2 products (low and high
+ * half of the packed entry the value path uses), level-1 (cos, sin) pairs. */
 struct KeyHalfBlockLut {
-    h2 ta, tb;
+    float ta0, ta1, tb0, tb1;
     float2 t1[4];
 };
 
@@ -231,31 +212,38 @@ __device__ __forceinline__ float2 lut_f2(const uint32_t *tab, uint32_t byte_off)
     return *reinterpret_cast<const float2 *>(reinterpret_cast<const char *>(tab + kT1F) + byte_off);
 }
 
+/* fp32 entry `index` of a dword table; byte_off is 4 * index */
+__device__ __forceinline__ float lut_f(const uint32_t *tab, int table, uint32_t byte_off)
+{
+    return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(tab + table) + byte_off);
+}
+
 __device__ __forceinline__ void gather_key_half_block(const uint32_t *tab, uint32_t offA, uint32_t offB,
                                                       uint32_t o0, uint32_t o1, uint32_t o2, uint32_t o3,
                                                       KeyHalfBlockLut &l)
 {
-    l.ta = lut(tab, kTA, offA);
-    l.tb = lut(tab, kTB, offB);
+    l.ta0 = lut_f(tab, kTAF, offA);
+    l.ta1 = lut_f(tab, kTAF + 16, offA);
+    l.tb0 = lut_f(tab, kTBF, offB);
+    l.tb1 = lut_f(tab, kTBF + 16, offB);
     l.t1[0] = lut_f2(tab, o0);
     l.t1[1] = lut_f2(tab, o1);
     l.t1[2] = lut_f2(tab, o2);
     l.t1[3] = lut_f2(tab, o3);
 }
 
-/* Key-side half-block expansion with every product formed in fp32 and each of the 8
- * results rounded to binary16 exactly once.  r3 is the exact product radius x level-4
- * entry.  The scores are the precision-critical contraction (an error of a key element
- * moves a softmax weight, and those errors do not average out over the context), so the
- * keys pay for the extra instructions; the values use the packed binary16 chain.
- * Plain fp32 multiplies plus one packed conversion per pair issue faster than the
- * mixed-precision multiply with a binary16 destination. */
+/* Key-side half-block expansion with every product formed in fp32 from fp32 tables and
+ * each of the 8 results rounded to binary16 exactly once.  r3 is the radius times the
+ * level-4 entry.  The scores are the precision-critical contraction (an error of a key
+ * element moves a softmax weight, and those errors do not average out over the context),
+ * so the keys pay for the extra instructions; the values use the packed binary16 chain.
+ * Plain fp32 multiplies plus one packed conversion per pair issue faster than mixed-
+ * precision multiplies on binary16 table entries. */
 __device__ __forceinline__ h2 round_pair(float a, float b) { return h2{(_Float16)a, (_Float16)b}; }
 
 __device__ __forceinline__ void expand_key_half_block(float r3, const KeyHalfBlockLut &l, h2 out[4])
 {
-    float r10 = mix_mul_fh<0>(r3, l.ta), r11 = mix_mul_fh<1>(r3, l.ta);
-    float r12 = mix_mul_fh<0>(r3, l.tb), r13 = mix_mul_fh<1>(r3, l.tb);
+    const float r10 = r3 * l.ta0, r11 = r3 * l.ta1, r12 = r3 * l.tb0, r13 = r3 * l.tb1;
     out[0] = round_pair(r10 * l.t1[0].x, r10 * l.t1[0].y);
     out[1] = round_pair(r11 * l.t1[1].x, r11 * l.t1[1].y);
     out[2] = round_pair(r12 * l.t1[2].x, r12 * l.t1[2].y);
@@ -339,22 +327,29 @@ __device__ __forceinline__ f4 score_pass(const uint32_t *tab, const KTileRaw &kc
     const uint32_t c4n = kcur.c4 >> (4 * i);
     const h2 rad = as_h2(sel4(kcur.rad, i));
     H8 ka[4];
-    KeyHalfBlockLut la0, la1, lb0, lb1;
     const NibbleOffsets noA = nibble_offsets8(l1A), noB = nibble_offsets8(l1B);
-    const h2 t4A = lut(tab, kT4, (c4n << 2) & 0xCu), t4B = lut(tab, kT4, c4n & 0xCu);
-    gather_key_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(noA),
-                          nibble_offset<1>(noA), nibble_offset<2>(noA), nibble_offset<3>(noA), la0);
-    gather_key_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(noA),
-                          nibble_offset<5>(noA), nibble_offset<6>(noA), nibble_offset<7>(noA), la1);
-    gather_key_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(noB),
-                          nibble_offset<1>(noB), nibble_offset<2>(noB), nibble_offset<3>(noB), lb0);
-    gather_key_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(noB),
-                          nibble_offset<5>(noB), nibble_offset<6>(noB), nibble_offset<7>(noB), lb1);
-    /* block A = 2*gk: slices 0, 1;  block B = 2*gk + 1: slices 2, 3 */
-    expand_key_half_block(mix_mul_hh<0, 0>(rad, t4A), la0, ka[0].p);
-    expand_key_half_block(mix_mul_hh<0, 1>(rad, t4A), la1, ka[1].p);
-    expand_key_half_block(mix_mul_hh<1, 0>(rad, t4B), lb0, ka[2].p);
-    expand_key_half_block(mix_mul_hh<1, 1>(rad, t4B), lb1, ka[3].p);
+    const uint32_t o4A = (c4n << 2) & 0xCu, o4B = c4n & 0xCu;
+    const float t4Ac = lut_f(tab, kT4F, o4A), t4As = lut_f(tab, kT4F + 4, o4A);
+    const float t4Bc = lut_f(tab, kT4F, o4B), t4Bs = lut_f(tab, kT4F + 4, o4B);
+    const float radA = (float)rad.x, radB = (float)rad.y; /* binary16 radii of blocks 2gk, 2gk+1 */
+    {   /* block A = 2*gk: slices 0, 1 */
+        KeyHalfBlockLut l0, l1;
+        gather_key_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(noA),
+                              nibble_offset<1>(noA), nibble_offset<2>(noA), nibble_offset<3>(noA), l0);
+        gather_key_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(noA),
+                              nibble_offset<5>(noA), nibble_offset<6>(noA), nibble_offset<7>(noA), l1);
+        expand_key_half_block(radA * t4Ac, l0, ka[0].p);
+        expand_key_half_block(radA * t4As, l1, ka[1].p);
+    }
+    {   /* block B = 2*gk + 1: slices 2, 3 */
+        KeyHalfBlockLut l0, l1;
+        gather_key_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(noB),
+                              nibble_offset<1>(noB), nibble_offset<2>(noB), nibble_offset<3>(noB), l0);
+        gather_key_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(noB),
+                              nibble_offset<5>(noB), nibble_offset<6>(noB), nibble_offset<7>(noB), l1);
+        expand_key_half_block(radB * t4Bc, l0, ka[2].p);
+        expand_key_half_block(radB * t4Bs, l1, ka[3].p);
+    }
     f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < 4; ++s)
@@ -474,6 +469,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 4) void pq_attn_partial_kernel
         if (t >= 20 && t < 32) tab[t] = 0u;
         if (t >= 72 && t < 96) tab[t] = 0u;
         if (t >= 96 && t < 128) tab[t] = __float_as_uint(K.t1_f32[(t - 96) >> 1][t & 1]);
+        if (t >= 128 && t < 160) tab[t] = __float_as_uint(K.ta_f32[(t - 128) >> 4][t & 15]);
+        if (t >= 160 && t < 192) tab[t] = __float_as_uint(K.tb_f32[(t - 160) >> 4][t & 15]);
+        if (t >= 192 && t < 200) tab[t] = __float_as_uint(K.t4_f32[(t - 192) >> 2][t & 3]);
+        if (t >= 200 && t < 208) tab[t] = 0u;
     }
     __syncthreads();
 

@@ -29,6 +29,11 @@ struct PqDeviceConsts {
     uint32_t t4_h2[4];  /* (cos, sin) of level-4 centroid c                        */
     uint32_t ta_h2[16]; /* index (c2<<2 | c3): cos(th3[c3]) * (cos, sin)(th2[c2])  */
     uint32_t tb_h2[16]; /* index (c3<<2 | c2): sin(th3[c3]) * (cos, sin)(th2[c2])  */
+    /* The level-2..4 tables once more in fp32 (same scaling), one array per half, for the
+       key path, whose radius chain runs in fp32: [0] the low halves, [1] the high halves. */
+    float ta_f32[2][16];
+    float tb_f32[2][16];
+    float t4_f32[2][4];
     /* Every column of the binary16 tables is stored times a constant in [1, 2)
        chosen so that its entries round to binary16 with the least error; a value
        rebuilt with them for coordinate i of a block is sigma[i] times too large.

@@ -268,6 +268,13 @@ void build_tables(pq_ctx *ctx)
         c.tb_h2[k] = pack_h2(tb[0][k] * sb[0], tb[1][k] * sb[1]);
     }
     for (int k = 0; k < 4; ++k) c.t4_h2[k] = pack_h2(t4[0][k] * s4[0], t4[1][k] * s4[1]);
+    for (int col = 0; col < 2; ++col) {
+        for (int k = 0; k < 16; ++k) {
+            c.ta_f32[col][k] = (float)(ta[col][k] * sa[col]);
+            c.tb_f32[col][k] = (float)(tb[col][k] * sb[col]);
+        }
+        for (int k = 0; k < 4; ++k) c.t4_f32[col][k] = (float)(t4[col][k] * s4[col]);
+    }
     /* coordinate i of a block: half-block h = i>>3 (level-4 side), pair q = (i>>1)&3
        (q < 2: table A, else table B; q&1: its low / high half), parity i&1 (level-1 cos / sin) */
     for (int i = 0; i < 16; ++i) {
