@@ -6,9 +6,9 @@ GQA decode attention on a polar-quantised KV cache, batch 16, 32 query heads /
 8 KV heads, 32768-token context, d = 128, one bf16 query per sequence.
 
 One step = one pass of the whole hot path for one decode iteration:
-  pq_append_kv_pair     encode the newest key and value of every sequence (rotate, polar, quantise, pack;
-                        one launch, same results as pq_append_kv on the keys and then on the values)
-  pq_attn_decode_polar  rotate q, attention on the packed codes, combine, un-rotate
+  pq_decode_step_polar  = pq_append_kv_pair + pq_attn_decode_polar (same results, one launch fewer):
+     append             encode the newest key and value of every sequence (rotate, polar, quantise, pack)
+     attention          rotate q, attention on the packed codes, combine, un-rotate
 The value is the cache bandwidth the whole step sustains: 124 bytes per cached
 (token, kv head) -- one 62-byte key record and one 62-byte value record --
 divided by the step time.  Three distinct caches are used in rotation so that
@@ -108,8 +108,7 @@ def main():
 
     def step(i):
         kc, kr, vc, vr = caches[i % N_CACHES]
-        ctx.append_kv_pair(new_k, new_v, kc, kr, vc, vr, newest_slot)
-        ctx.attn_decode_polar(q, out, kc, kr, vc, vr, seq_start, ctx_len, CTX, scale, ws)
+        ctx.decode_step_polar(new_k, new_v, newest_slot, q, out, kc, kr, vc, vr, seq_start, ctx_len, CTX, scale, ws)
 
     for i in range(args.warmup):
         step(i)
@@ -168,7 +167,7 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": "configs[2]: GQA decode attention, batch 16, 32 q heads / 8 kv heads, 32768-token context, d=128; "
-                        "step = append newest K and V token per sequence (one launch) + attention on the packed cache",
+                        "step = pq_decode_step_polar: append newest K and V token per sequence, then attention on the packed cache",
             "batch": B, "q_heads": HQ, "kv_heads": HKV, "context": CTX, "rotating_caches": N_CACHES,
             "algorithmic_bytes_per_step": step_bytes,
         },

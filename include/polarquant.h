@@ -189,6 +189,21 @@ pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void *out, pq_d
 
 size_t pq_attn_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ctx);
 
+/* One whole decode step (Algorithm 1 on the newest token of every sequence, then
+ * Eq. 5 on the cache that now holds it): pq_append_kv_pair(xk, xv -> dst_token)
+ * followed by pq_attn_decode_polar, with identical results; the appends and the
+ * rotation of q share one launch.  xk, xv (device): [B][Hkv][128] contiguous of
+ * dtype xt; dst_token (device): B slots, normally seq_start[b] + ctx_len[b] - 1
+ * with ctx_len already counting the new token.  The caches are written (the
+ * appended slots) and read.  All other arguments as for pq_attn_decode_polar. */
+pq_status pq_decode_step_polar(const pq_ctx *ctx, const void *xk, const void *xv, pq_dtype xt,
+                               const int64_t *dst_token, const void *q, void *out, pq_dtype out_dtype,
+                               uint8_t *k_codes, uint16_t *k_radii, uint8_t *v_codes, uint16_t *v_radii,
+                               const int64_t *seq_start, const int32_t *ctx_len,
+                               int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
+                               float softmax_scale, void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
+
 /* ---------------------------------------------------------------------------
  * Optional timing of the two dominant kernels (the attention partial kernel
  * and the encode kernel) with HIP events recorded on the launch stream,

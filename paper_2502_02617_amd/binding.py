@@ -2,7 +2,7 @@
 
 Function names mirror the C ABI: ``Context`` wraps ``pq_init_preconditioner`` /
 ``pq_destroy`` and its methods call ``pq_encode_kv``, ``pq_append_kv``, ``pq_append_kv_pair``,
-``pq_decode_kv``, ``pq_export_canonical`` and ``pq_attn_decode_polar`` with
+``pq_decode_kv``, ``pq_export_canonical``, ``pq_attn_decode_polar`` and ``pq_decode_step_polar`` with
 pointers of torch tensors (torch is used for device memory and streams only).
 """
 import ctypes
@@ -59,6 +59,9 @@ def library():
     L.pq_export_canonical.argtypes = [vp, i32, vp, vp, i64, i64, i64, i32, vp, vp]
     L.pq_attn_decode_polar.restype = i32
     L.pq_attn_decode_polar.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, i64,
+                                       ctypes.c_float, vp, ctypes.c_size_t, vp]
+    L.pq_decode_step_polar.restype = i32
+    L.pq_decode_step_polar.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, i64,
                                        ctypes.c_float, vp, ctypes.c_size_t, vp]
     L.pq_attn_workspace_bytes.restype = ctypes.c_size_t
     L.pq_attn_workspace_bytes.argtypes = [i32, i32, i32, i64]
@@ -215,6 +218,22 @@ class Context:
     @staticmethod
     def attn_workspace_bytes(B, Hq, Hkv, max_ctx):
         return int(library().pq_attn_workspace_bytes(int(B), int(Hq), int(Hkv), int(max_ctx)))
+
+    def decode_step_polar(self, xk, xv, dst_token, q, out, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len,
+                          max_ctx, softmax_scale, workspace):
+        """append_kv_pair(xk, xv -> dst_token) + attn_decode_polar in one call; xk, xv: [B, Hkv, 128] contiguous."""
+        if not (xk.is_contiguous() and xv.is_contiguous()):
+            raise PolarQuantError("xk and xv must be contiguous")
+        B, Hq = q.shape[0], q.shape[1]
+        Hkv = k_codes.shape[0]
+        if tuple(xk.shape) != (B, Hkv, 128) or xk.shape != xv.shape or xk.dtype != xv.dtype:
+            raise PolarQuantError("xk and xv must both be [B, Hkv, 128] of one dtype")
+        pool_tokens = k_codes.shape[1] * TILE_TOKENS
+        _check(library().pq_decode_step_polar(
+            self._h, xk.data_ptr(), xv.data_ptr(), _dtype_code(xk), dst_token.data_ptr(), q.data_ptr(), out.data_ptr(),
+            _dtype_code(out), k_codes.data_ptr(), k_radii.data_ptr(), v_codes.data_ptr(), v_radii.data_ptr(),
+            seq_start.data_ptr(), ctx_len.data_ptr(), int(B), int(Hq), int(Hkv), int(pool_tokens), int(max_ctx),
+            float(softmax_scale), workspace.data_ptr(), int(workspace.numel() * workspace.element_size()), _stream()))
 
     def attn_decode_polar(self, q, out, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len, max_ctx,
                           softmax_scale, workspace):

@@ -37,6 +37,7 @@
  *       coordinates in the parity-0 columns and for the odd ones in parity 1.
  */
 #include "pq_common.h"
+#include "pq_polar.h"
 
 namespace {
 
@@ -574,12 +575,11 @@ struct RotateArgs {
     const PqDeviceConsts *consts;
 };
 
-__global__ __launch_bounds__(512) void pq_rotate_q_kernel(RotateArgs a)
+__device__ __forceinline__ void rotate_query_row(const RotateArgs &a, int row)
 {
     __shared__ float sq[PQ_D];
     __shared__ float spart[4][PQ_D];
     const int tid = threadIdx.x, j = tid & 127;
-    const int row = blockIdx.x;
     MatrixSlice ms;
     matrix_slice_load(ms, a.S, tid);
     if (tid < PQ_D) sq[j] = __uint_as_float((uint32_t)a.q[(int64_t)row * PQ_D + j] << 16);
@@ -593,6 +593,23 @@ __global__ __launch_bounds__(512) void pq_rotate_q_kernel(RotateArgs a)
         a.qrot[(int64_t)row * 2 * PQ_D + j] = __builtin_bit_cast(uint16_t, h);
         a.qrot[(int64_t)row * 2 * PQ_D + PQ_D + j] = __builtin_bit_cast(uint16_t, r);
     }
+}
+
+__global__ __launch_bounds__(512) void pq_rotate_q_kernel(RotateArgs a)
+{
+    rotate_query_row(a, (int)blockIdx.x);
+}
+
+/* First launch of a whole decode step: workgroups [0, n) append the new key vectors,
+   [n, 2n) the new value vectors, the rest rotate one query row each; the three jobs are
+   independent of each other and all of them precede the attention proper. */
+template <int XT>
+__global__ __launch_bounds__(512) void pq_step_prologue_kernel(RotateArgs r, AppendArgs k, AppendArgs v, int n)
+{
+    const int blk = (int)blockIdx.x;
+    if (blk < n) append_vector<XT>(k, PQ_KEY, blk);
+    else if (blk < 2 * n) append_vector<XT>(v, PQ_VALUE, blk - n);
+    else rotate_query_row(r, blk - 2 * n);
 }
 
 struct CombineArgs {
@@ -693,13 +710,21 @@ extern "C" size_t pq_attn_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ct
     return make_plan(B, Hq, Hkv, max_ctx).total;
 }
 
-extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
-                                          const uint8_t *k_codes, const uint16_t *k_radii,
-                                          const uint8_t *v_codes, const uint16_t *v_radii,
-                                          const int64_t *seq_start, const int32_t *ctx_len,
-                                          int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
-                                          float softmax_scale, void *workspace, size_t workspace_bytes,
-                                          void *hip_stream)
+namespace {
+
+/* the new key / value vectors of a decode step, appended by the first launch (optional) */
+struct StepAppend {
+    const void *xk, *xv;
+    pq_dtype xt;
+    const int64_t *dst_token;
+    int n_heads;
+};
+
+pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const void *q, void *out, pq_dtype out_dtype,
+                             uint8_t *k_codes, uint16_t *k_radii, uint8_t *v_codes, uint16_t *v_radii,
+                             const int64_t *seq_start, const int32_t *ctx_len,
+                             int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
+                             float softmax_scale, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!ctx || !q || !out || !k_codes || !k_radii || !v_codes || !v_radii || !seq_start || !ctx_len || !workspace)
         return PQ_EINVAL;
@@ -712,6 +737,12 @@ extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void
     if (!pq_aligned16(q) || !pq_aligned16(out) || !pq_aligned16(k_codes) || !pq_aligned16(k_radii) ||
         !pq_aligned16(v_codes) || !pq_aligned16(v_radii) || !pq_aligned16(workspace))
         return PQ_EALIGN;
+    if (app) {
+        if (!app->xk || !app->xv || !app->dst_token) return PQ_EINVAL;
+        if (app->xt != PQ_F32 && app->xt != PQ_BF16) return PQ_EINVAL;
+        if (!pq_aligned16(app->xk) || !pq_aligned16(app->xv)) return PQ_EALIGN;
+        if (2 * (int64_t)B * Hkv + (int64_t)B * Hq > 0x7FFFFFFF) return PQ_EINVAL;
+    }
     const Plan p = make_plan(B, Hq, Hkv, max_ctx);
     if (workspace_bytes < p.total) return PQ_ENOMEM;
     const PqDeviceState *ds = nullptr;
@@ -725,8 +756,16 @@ extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void
     const int rows = B * Hq;
 
     RotateArgs ra{static_cast<const uint16_t *>(q), qrot, ds->S_f32, softmax_scale * kLog2e, ds->consts};
-    hipLaunchKernelGGL(pq_rotate_q_kernel, dim3(rows), dim3(512), 0, s, ra);
-
+    if (app) {
+        AppendArgs ak{app->xk, k_codes, k_radii, pool_tokens / 64, pool_tokens, app->dst_token, Hkv, ds->S_f32, ds->consts};
+        AppendArgs av{app->xv, v_codes, v_radii, pool_tokens / 64, pool_tokens, app->dst_token, Hkv, ds->S_f32, ds->consts};
+        const int n = B * Hkv;
+        const dim3 grid((unsigned)(2 * n + rows)), blk(512);
+        if (app->xt == PQ_BF16) hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_BF16>), grid, blk, 0, s, ra, ak, av, n);
+        else hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_F32>), grid, blk, 0, s, ra, ak, av, n);
+    } else {
+        hipLaunchKernelGGL(pq_rotate_q_kernel, dim3(rows), dim3(512), 0, s, ra);
+    }
     AttnArgs aa{};
     aa.qrot = qrot;
     aa.k_codes = k_codes; aa.v_codes = v_codes; aa.k_radii = k_radii; aa.v_radii = v_radii;
@@ -752,3 +791,34 @@ extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void
     PQ_HIP_TRY(hipGetLastError());
     return PQ_OK;
 }
+
+} // namespace
+
+extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
+                                          const uint8_t *k_codes, const uint16_t *k_radii,
+                                          const uint8_t *v_codes, const uint16_t *v_radii,
+                                          const int64_t *seq_start, const int32_t *ctx_len,
+                                          int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
+                                          float softmax_scale, void *workspace, size_t workspace_bytes,
+                                          void *hip_stream)
+{
+    /* the caches are only read on this path */
+    return attention_launches(ctx, nullptr, q, out, out_dtype, const_cast<uint8_t *>(k_codes),
+                              const_cast<uint16_t *>(k_radii), const_cast<uint8_t *>(v_codes),
+                              const_cast<uint16_t *>(v_radii), seq_start, ctx_len, B, Hq, Hkv, pool_tokens, max_ctx,
+                              softmax_scale, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" pq_status pq_decode_step_polar(const pq_ctx *ctx, const void *xk, const void *xv, pq_dtype xt,
+                                          const int64_t *dst_token, const void *q, void *out, pq_dtype out_dtype,
+                                          uint8_t *k_codes, uint16_t *k_radii, uint8_t *v_codes, uint16_t *v_radii,
+                                          const int64_t *seq_start, const int32_t *ctx_len,
+                                          int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
+                                          float softmax_scale, void *workspace, size_t workspace_bytes,
+                                          void *hip_stream)
+{
+    const StepAppend app{xk, xv, xt, dst_token, Hkv};
+    return attention_launches(ctx, &app, q, out, out_dtype, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len,
+                              B, Hq, Hkv, pool_tokens, max_ctx, softmax_scale, workspace, workspace_bytes, hip_stream);
+}
+

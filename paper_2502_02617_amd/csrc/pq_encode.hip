@@ -24,6 +24,7 @@
  *      image is written out with full-width stores.
  */
 #include "pq_common.h"
+#include "pq_polar.h"
 
 namespace {
 
@@ -89,112 +90,6 @@ __device__ __forceinline__ void put_bits(uint32_t *img, uint32_t bit, int width,
     }
     atomicOr(&img[dw], (uint32_t)vv);
     if (MAY_STRADDLE) atomicOr(&img[dw + 1], (uint32_t)(vv >> 32));
-}
-
-/* Quantise one quadrant angle: number of inner boundaries below atan(v/u), for
- * u, v >= 0.  Boundary k is passed when v > t_k * u, that is when the fused
- * t_k * u - v (one rounding, so its sign is the exact one) is negative; the sign
- * bits are added up.  The middle boundary is pi/4 (t = 1). */
-__device__ __forceinline__ uint32_t quant3(float u, float v, float t1, float t3)
-{
-    const float d1 = __builtin_fmaf(t1, u, -v), d2 = u - v, d3 = __builtin_fmaf(t3, u, -v);
-    return (__float_as_uint(d1) >> 31) + (__float_as_uint(d2) >> 31) + (__float_as_uint(d3) >> 31);
-}
-
-/* First and third inner boundary of each level (the middle one is pi/4): their
- * tangents for level 1, the squares of their tangents above it, where the
- * recursion carries squared radii (v > t u  <=>  v^2 > t^2 u^2 for u, v >= 0). */
-struct Thresholds {
-    float t1a, t1c, t2a, t2c, t3a, t3c, t4a, t4c;
-};
-
-__device__ __forceinline__ Thresholds load_thresholds(const PqDeviceConsts &K)
-{
-    Thresholds t;
-    t.t1a = K.tan_b[0][0]; t.t1c = K.tan_b[0][2];
-    t.t2a = K.tan_b[1][0] * K.tan_b[1][0]; t.t2c = K.tan_b[1][2] * K.tan_b[1][2];
-    t.t3a = K.tan_b[2][0] * K.tan_b[2][0]; t.t3c = K.tan_b[2][2] * K.tan_b[2][2];
-    t.t4a = K.tan_b[3][0] * K.tan_b[3][0]; t.t4c = K.tan_b[3][2] * K.tan_b[3][2];
-    return t;
-}
-
-struct BlockCodes {
-    uint32_t l1;     /* 8 level-1 codes, pair p at bits [4p, 4p+4) */
-    uint32_t g0, g1; /* [c2(2h) | c3(h) | c2(2h+1)] of half-block 0 / 1 */
-    uint32_t c4;
-    uint16_t radius; /* binary16 bits */
-};
-
-/* Procedure Polar on one block of 16 rotated coordinates with procedure Quant
- * folded in: four levels of (angle code, radius) pairs, all in registers.  Only
- * the squares of the intermediate radii are kept (the angle of a node depends on
- * the ratio of its children's radii alone); the root radius takes the one square
- * root.  The recursion is cut into eight steps (one level-1 pair each, plus the
- * nodes of the upper levels that the pair completes) so that a caller can spread
- * it between other work. */
-struct PolarState {
-    float q1[8], q2[4], q3[2]; /* squared radii */
-    uint32_t mq, l1, c2[4], c3[2];
-    BlockCodes out;
-};
-
-/* level-1 pair p, first part: position inside the quadrant */
-template <typename Y16>
-__device__ __forceinline__ void polar_level1_a(PolarState &s, const Y16 &y, int p, const Thresholds &th)
-{
-    s.mq = quant3(fabsf(y[2 * p]), fabsf(y[2 * p + 1]), th.t1a, th.t1c);
-}
-
-/* level-1 pair p, second part: quadrant, code, squared radius */
-template <typename Y16>
-__device__ __forceinline__ void polar_level1_b(PolarState &s, const Y16 &y, int p)
-{
-    const float ya = y[2 * p], yb = y[2 * p + 1];
-    /* cell of atan2(yb, ya) in [0, 2 pi), cells pi/8 wide: quadrant Q = 0..3 from the signs,
-       code = 4Q + mq in quadrants 0 and 2, 4Q + 3 - mq in 1 and 3 (angle measured from the
-       other axis), which is (mq xor 7f) + 8 sb with f = sa xor sb */
-    const uint32_t ba = __float_as_uint(ya), bb = __float_as_uint(yb);
-    const uint32_t f7 = (uint32_t)((int32_t)(ba ^ bb) >> 31) & 7u;
-    const uint32_t code = (s.mq ^ f7) + ((bb >> 28) & 8u);
-    s.l1 = (p == 0) ? code : (s.l1 | (code << (4 * p)));
-    s.q1[p] = __builtin_fmaf(ya, ya, yb * yb);
-}
-
-/* the upper-level nodes whose children are complete once level-1 pair p is done */
-__device__ __forceinline__ void polar_upper(PolarState &s, int p, const Thresholds &th)
-{
-    if (p & 1) {
-        const int n = p >> 1;
-        s.c2[n] = quant3(s.q1[2 * n], s.q1[2 * n + 1], th.t2a, th.t2c);
-        s.q2[n] = s.q1[2 * n] + s.q1[2 * n + 1];
-    }
-    if ((p & 3) == 3) {
-        const int h = p >> 2;
-        s.c3[h] = quant3(s.q2[2 * h], s.q2[2 * h + 1], th.t3a, th.t3c);
-        s.q3[h] = s.q2[2 * h] + s.q2[2 * h + 1];
-    }
-    if (p == 7) {
-        s.out.c4 = quant3(s.q3[0], s.q3[1], th.t4a, th.t4c);
-        const float r4 = __builtin_amdgcn_sqrtf(s.q3[0] + s.q3[1]);
-        const _Float16 rh = (_Float16)r4; /* round to nearest even */
-        s.out.radius = __builtin_bit_cast(uint16_t, rh);
-        s.out.l1 = s.l1;
-        s.out.g0 = (s.c2[0] << 4) | (s.c3[0] << 2) | s.c2[1];
-        s.out.g1 = (s.c2[2] << 4) | (s.c3[1] << 2) | s.c2[3];
-    }
-}
-
-template <typename Y16>
-__device__ __forceinline__ BlockCodes polar_quant_block(const Y16 &y, const Thresholds &th)
-{
-    PolarState s;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) {
-        polar_level1_a(s, y, p, th);
-        polar_level1_b(s, y, p);
-        polar_upper(s, p, th);
-    }
-    return s.out;
 }
 
 /* Scatter the fields of block b of slot tau into the tile image (codes, then radii). */
@@ -542,78 +437,6 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
     }
 }
 
-
-/* ---- decode-time append: one vector per (sequence, head) ----
- * Too little work for the matrix cores: one workgroup per vector computes
- * y_j = sum_i x_i S[i][j] in fp32 (S read from L2, four partial sums per
- * coordinate added in a fixed order), eight threads then run the polar recursion of one block each and patch the fields
- * into the tile in place.  Fields narrower than a byte share dwords with other
- * slots of the tile, so they are updated with dword atomics. */
-struct AppendArgs {
-    const void *x;
-    uint8_t *codes;
-    uint16_t *radii;
-    int64_t pool_tiles, pool_tokens;
-    const int64_t *dst_token;
-    int n_heads;
-    const float *S; /* S[i*128 + j] */
-    const PqDeviceConsts *consts;
-};
-
-__device__ __forceinline__ void put_bits_global(uint8_t *codes, uint32_t bit, int width, uint32_t v)
-{
-    uint32_t *w = reinterpret_cast<uint32_t *>(codes) + (bit >> 5);
-    const uint32_t sh = bit & 31, mask = (1u << width) - 1u;
-    atomicAnd(w, ~(mask << sh));
-    atomicOr(w, v << sh);
-    if (sh + width > 32) {
-        const uint32_t done = 32 - sh;
-        atomicAnd(w + 1, ~(mask >> done));
-        atomicOr(w + 1, v >> done);
-    }
-}
-
-/* one (sequence, head) vector of kind `kind`, by one workgroup */
-template <int XT>
-__device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int vec)
-{
-    __shared__ float sx[PQ_D];
-    __shared__ float sy[PQ_D];
-    __shared__ float spart[4][PQ_D];
-    const int seq = vec / a.n_heads, head = vec % a.n_heads, tid = threadIdx.x, j = tid & 127;
-    MatrixSlice ms;
-    matrix_slice_load(ms, a.S, tid);
-    const int64_t dst = a.dst_token[seq];
-    if (dst < 0 || dst >= a.pool_tokens) return; /* slot outside the pool: nothing is written */
-    const int64_t row = ((int64_t)seq * a.n_heads + head) * PQ_D;
-    if (tid < PQ_D) {
-        if (XT == PQ_BF16) sx[j] = __uint_as_float((uint32_t)static_cast<const uint16_t *>(a.x)[row + j] << 16);
-        else sx[j] = static_cast<const float *>(a.x)[row + j];
-    }
-    __syncthreads();
-    const float acc = vector_times_slice(sx, ms, spart, tid); /* y_j = sum_i x_i S[i][j] */
-    if (tid < PQ_D) sy[j] = acc;
-    __syncthreads();
-    if (tid < 8) {
-        const int b = tid;
-        float y[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) y[r] = sy[16 * b + r];
-        const Thresholds th = load_thresholds(*a.consts);
-        BlockCodes bc = polar_quant_block(y, th);
-        const int64_t tile = dst >> 6;
-        const int tau = (int)(dst & 63);
-        uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
-        uint16_t *gradii = a.radii + ((int64_t)head * a.pool_tiles + tile) * PQL_RADII;
-        PqBlockPos pos = pql_pos(kind, tau, b);
-        *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[0]) = (uint16_t)(bc.l1 & 0xFFFFu);
-        *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[1]) = (uint16_t)(bc.l1 >> 16);
-        put_bits_global(gcodes, pos.g6_bit[0], 6, bc.g0);
-        put_bits_global(gcodes, pos.g6_bit[1], 6, bc.g1);
-        put_bits_global(gcodes, pos.c4_bit, 2, bc.c4);
-        gradii[pos.radius_half] = bc.radius;
-    }
-}
 
 template <int XT, int KIND>
 __global__ __launch_bounds__(512) void pq_append_kernel(AppendArgs a)

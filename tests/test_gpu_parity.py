@@ -391,6 +391,50 @@ def test_attention_moving_maximum(env, shape):
     assert err <= 2e-3
 
 
+def test_decode_step_equals_append_then_attention(env):
+    """pq_decode_step_polar gives, bit for bit, the caches and the output of pq_append_kv_pair followed by
+    pq_attn_decode_polar."""
+    ctx, S, cb = env
+    lens = [1, 64, 65, 300, 1000]      # context lengths including the token appended in the step
+    say(f"decode step vs append + attention, lens={lens}")
+    B, Hq, Hkv = len(lens), 8, 2
+    results = []
+    for fused in (False, True):
+        starts, pool = [], 0
+        for n in lens:
+            starts.append(pool)
+            pool += ((n + 63) // 64) * 64
+        kc, kr = Context.alloc_cache(Hkv, pool, DEV)
+        vc, vr = Context.alloc_cache(Hkv, pool, DEV)
+        for t in (kc, kr, vc, vr):
+            t.zero_()
+        for b, n in enumerate(lens):
+            if n > 1:
+                k = synth.kv_stream(n - 1, Hkv, 810 + 2 * b).permute(1, 0, 2).contiguous()
+                v = synth.kv_stream(n - 1, Hkv, 811 + 2 * b).permute(1, 0, 2).contiguous()
+                ctx.encode_kv(k.to(DEV), PQ_KEY, kc, kr, dst_token0=starts[b])
+                ctx.encode_kv(v.to(DEV), PQ_VALUE, vc, vr, dst_token0=starts[b])
+        nk = synth.kv_stream(B, Hkv, 830).permute(1, 0, 2).contiguous().to(DEV)
+        nv = synth.kv_stream(B, Hkv, 831).permute(1, 0, 2).contiguous().to(DEV)
+        q = synth.queries(B, Hq, seed=832).to(DEV)
+        seq_start = torch.tensor(starts, dtype=torch.int64, device=DEV)
+        ctx_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
+        dst = seq_start + ctx_len.to(torch.int64) - 1
+        out = torch.empty((B, Hq, 128), dtype=torch.float32, device=DEV)
+        ws = torch.empty(Context.attn_workspace_bytes(B, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
+        if fused:
+            ctx.decode_step_polar(nk, nv, dst, q, out, kc, kr, vc, vr, seq_start, ctx_len, max(lens),
+                                  helpers.softmax_scale(), ws)
+        else:
+            ctx.append_kv_pair(nk, nv, kc, kr, vc, vr, dst)
+            ctx.attn_decode_polar(q, out, kc, kr, vc, vr, seq_start, ctx_len, max(lens), helpers.softmax_scale(), ws)
+        torch.cuda.synchronize()
+        results.append((kc, kr, vc, vr, out))
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
+    assert torch.isfinite(results[1][4]).all()
+
+
 def test_attention_rejects_bad_sequences_gracefully(env):
     ctx, S, cb = env
     say("attention with an unaligned / out-of-pool sequence")
