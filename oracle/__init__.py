@@ -221,6 +221,37 @@ def attention(q, k_rec, v_rec, seq_start, ctx_len, S, cb, scale, rotated=False):
     return out
 
 
+def attention_hybrid(q, k_rec, v_rec, seq_start, ctx_len, win_k, win_v, win_len, S, cb, scale):
+    """Quantised prefix + unquantised window: q[B,Hq,128]; k_rec/v_rec [Hkv, plane, 62];
+    win_k/win_v [B, Hkv, win_cap, 128]; win_len [B] -> out[B,Hq,128] (float64)."""
+    q = _f64(q)
+    B, Hq, _ = q.shape
+    k_rec = np.ascontiguousarray(k_rec, dtype=np.uint8)
+    v_rec = np.ascontiguousarray(v_rec, dtype=np.uint8)
+    Hkv, plane, _ = k_rec.shape
+    assert v_rec.shape == k_rec.shape and Hq % Hkv == 0
+    seq_start = np.ascontiguousarray(seq_start, dtype=np.int64)
+    ctx_len = np.ascontiguousarray(ctx_len, dtype=np.int32)
+    win_len = np.ascontiguousarray(win_len, dtype=np.int32)
+    win_k = _f64(win_k)
+    win_v = _f64(win_v)
+    assert win_k.shape == win_v.shape and win_k.shape[:2] == (B, Hkv) and win_k.shape[3] == D
+    cap = win_k.shape[2]
+    assert seq_start.size == B and ctx_len.size == B and win_len.size == B
+    assert np.all(seq_start + ctx_len <= plane) and np.all(win_len <= cap)
+    S = _f64(S)
+    cb = _f64(cb)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lib().orc_attention_hybrid(
+        _p(q), ctypes.c_int(B), ctypes.c_int(Hq), ctypes.c_int(Hkv),
+        _p(k_rec, ctypes.c_uint8), _p(v_rec, ctypes.c_uint8),
+        _p(seq_start, ctypes.c_int64), _p(ctx_len, ctypes.c_int32), ctypes.c_int64(plane),
+        _p(win_k), _p(win_v), _p(win_len, ctypes.c_int32), ctypes.c_int64(cap),
+        _p(S), _p(cb), ctypes.c_double(scale), _p(out),
+    )
+    return out
+
+
 def attention_exact(q, K, V, scale):
     """Plain softmax attention on unquantised K,V[T,128] for q[G,128] (reporting only)."""
     q = _f64(q).reshape(-1, D)

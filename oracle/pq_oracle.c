@@ -552,6 +552,76 @@ void orc_attention(const double *q, int B, int Hq, int Hkv,
     }
 }
 
+/* ------------------------------------------------------------------ */
+/* Attention over a quantised prefix plus an unquantised recent window  */
+/* (Section 5.2: the keys and values streamed in during generation are  */
+/* kept in 16 bits, only the prompt's are quantised).  One softmax over */
+/* the concatenation: the first ctx_len[b] rows are the DeQuant of the  */
+/* cached records (Eq. 5), the next win_len[b] rows are the window's    */
+/* vectors as given.  win_k, win_v: [B][Hkv][win_cap][128].             */
+/* No rows at all gives a zero output row.                              */
+/* ------------------------------------------------------------------ */
+void orc_attention_hybrid(const double *q, int B, int Hq, int Hkv,
+                          const uint8_t *k_rec, const uint8_t *v_rec,
+                          const int64_t *seq_start, const int32_t *ctx_len,
+                          int64_t plane_tokens, const double *win_k, const double *win_v,
+                          const int32_t *win_len, int64_t win_cap,
+                          const double *S, const double *cb, double scale, double *out)
+{
+    int G = Hq / Hkv;
+    for (int b = 0; b < B; ++b)
+        for (int hk = 0; hk < Hkv; ++hk) {
+            int64_t T = ctx_len[b] > 0 ? ctx_len[b] : 0, W = win_len[b] > 0 ? win_len[b] : 0, N = T + W;
+            for (int g = 0; g < G; ++g)
+                memset(out + ((int64_t)b * Hq + hk * G + g) * ORC_D, 0, sizeof(double) * ORC_D);
+            if (N == 0) continue;
+            double *Kh = (double *)malloc(sizeof(double) * N * ORC_D);
+            double *Vh = (double *)malloc(sizeof(double) * N * ORC_D);
+            double *sc = (double *)malloc(sizeof(double) * N);
+            const uint8_t *kr = k_rec + ((int64_t)hk * plane_tokens + seq_start[b]) * ORC_REC;
+            const uint8_t *vr = v_rec + ((int64_t)hk * plane_tokens + seq_start[b]) * ORC_REC;
+#pragma omp parallel for schedule(static)
+            for (int64_t t = 0; t < T; ++t) { /* procedure DeQuant, trailing S^T included */
+                double y[ORC_D];
+                orc_dequant_rotated_one(kr + t * ORC_REC, cb, y);
+                for (int i = 0; i < ORC_D; ++i) {
+                    double acc = 0.0;
+                    for (int j = 0; j < ORC_D; ++j) acc += y[j] * S[i * ORC_D + j];
+                    Kh[t * ORC_D + i] = acc;
+                }
+                orc_dequant_rotated_one(vr + t * ORC_REC, cb, y);
+                for (int i = 0; i < ORC_D; ++i) {
+                    double acc = 0.0;
+                    for (int j = 0; j < ORC_D; ++j) acc += y[j] * S[i * ORC_D + j];
+                    Vh[t * ORC_D + i] = acc;
+                }
+            }
+            const double *wk = win_k + ((int64_t)b * Hkv + hk) * win_cap * ORC_D;
+            const double *wv = win_v + ((int64_t)b * Hkv + hk) * win_cap * ORC_D;
+            for (int64_t t = 0; t < W; ++t) {
+                memcpy(Kh + (T + t) * ORC_D, wk + t * ORC_D, sizeof(double) * ORC_D);
+                memcpy(Vh + (T + t) * ORC_D, wv + t * ORC_D, sizeof(double) * ORC_D);
+            }
+            for (int g = 0; g < G; ++g) {
+                const double *qh = q + ((int64_t)b * Hq + hk * G + g) * ORC_D;
+                double *oh = out + ((int64_t)b * Hq + hk * G + g) * ORC_D;
+                double mx = -INFINITY, den = 0.0;
+                for (int64_t t = 0; t < N; ++t) {
+                    double s = 0.0;
+                    for (int j = 0; j < ORC_D; ++j) s += Kh[t * ORC_D + j] * qh[j];
+                    sc[t] = s * scale;
+                    if (sc[t] > mx) mx = sc[t];
+                }
+                for (int64_t t = 0; t < N; ++t) { sc[t] = exp(sc[t] - mx); den += sc[t]; }
+                for (int64_t t = 0; t < N; ++t) {
+                    double w = sc[t] / den;
+                    for (int j = 0; j < ORC_D; ++j) oh[j] += w * Vh[t * ORC_D + j];
+                }
+            }
+            free(Kh); free(Vh); free(sc);
+        }
+}
+
 /* Exact attention on unquantised K, V (Eq. 4), for reporting the       */
 /* approximation error only.  parity unpinned against the paper (it     */
 /* prints no bound relating Eq. 5 to Eq. 4); it is plain softmax.       */

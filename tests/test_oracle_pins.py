@@ -462,6 +462,51 @@ def test_attention_degenerate_cases(S, cb):
     assert np.max(np.abs(out[0, 0] - oracle.decode(v_rec[0, :T], S, cb).mean(axis=0))) <= 1e-12
 
 
+def test_hybrid_attention_is_one_softmax_over_prefix_and_window(S, cb):
+    """Quantised prefix + unquantised window (Section 5.2's protocol): the textbook softmax over the
+    concatenation of the dequantised prefix rows and the window rows, from scipy; an empty window reduces
+    it to Eq. 5, an empty prefix to plain attention on the window, and it equals the log-sum-exp merge of
+    the two separate attentions."""
+    T, Hkv, B, cap = 29, 2, 3, 11
+    q, k_rec, v_rec = _small_cache(S, cb, T, Hkv, B, seed=71)
+    rng = np.random.default_rng(72)
+    win_k = rng.standard_normal((B, Hkv, cap, 128))
+    win_v = rng.standard_normal((B, Hkv, cap, 128))
+    seq_start = np.array([0, T, 2 * T], dtype=np.int64)
+    ctx_len = np.array([T, 0, T - 7], dtype=np.int32)
+    win_len = np.array([cap, 5, 0], dtype=np.int32)
+    scale = 1 / math.sqrt(128)
+    out = oracle.attention_hybrid(q, k_rec, v_rec, seq_start, ctx_len, win_k, win_v, win_len, S, cb, scale)
+    for b in range(B):
+        for h in range(4 * Hkv):
+            hk = h // 4
+            sl = slice(seq_start[b], seq_start[b] + ctx_len[b])
+            Kh = np.concatenate([oracle.decode(k_rec[hk, sl], S, cb).reshape(-1, 128), win_k[b, hk, :win_len[b]]])
+            Vh = np.concatenate([oracle.decode(v_rec[hk, sl], S, cb).reshape(-1, 128), win_v[b, hk, :win_len[b]]])
+            p = scipy.special.softmax(Kh @ q[b, h] * scale)
+            assert np.max(np.abs(p @ Vh - out[b, h])) <= 1e-12
+    # empty window: Eq. 5 on the cache alone
+    plain = oracle.attention(q, k_rec, v_rec, seq_start, ctx_len, S, cb, scale)
+    assert np.max(np.abs(out[2] - plain[2])) <= 1e-12
+    # empty prefix: plain attention on the window rows
+    for h in range(4 * Hkv):
+        ref = oracle.attention_exact(q[1, h], win_k[1, h // 4, :5], win_v[1, h // 4, :5], scale)
+        assert np.max(np.abs(out[1, h] - ref[0])) <= 1e-12
+    # merge of the two separate results with their log-sum-exp weights
+    for h in range(4 * Hkv):
+        hk = h // 4
+        Kp = oracle.decode(k_rec[hk, :T], S, cb)
+        lse_p = scipy.special.logsumexp(Kp @ q[0, h] * scale)
+        lse_w = scipy.special.logsumexp(win_k[0, hk] @ q[0, h] * scale)
+        o_w = oracle.attention_exact(q[0, h], win_k[0, hk], win_v[0, hk], scale)[0]
+        wp, ww = scipy.special.softmax([lse_p, lse_w])
+        assert np.max(np.abs(wp * plain[0, h] + ww * o_w - out[0, h])) <= 1e-12
+    # nothing at all: zeros
+    none = oracle.attention_hybrid(q, k_rec, v_rec, seq_start, np.zeros(B, np.int32), win_k, win_v,
+                                   np.zeros(B, np.int32), S, cb, scale)
+    assert np.all(none == 0.0)
+
+
 def test_exact_attention_helper_is_plain_softmax():
     rng = np.random.default_rng(2)
     K, V = rng.standard_normal((2, 50, 128))
