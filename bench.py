@@ -152,6 +152,28 @@ def main():
     enc_bytes_per_token = 16 * (256 + 62)
     enc_gbs = enc_mtok * 1e6 * enc_bytes_per_token / 1e9
 
+    # ---- hybrid line: the same quantised 32k-token prefix plus a bf16 window of 256 recent tokens per
+    # sequence (the keys and values of the generation stage kept in 16 bits), pq_attn_decode_hybrid
+    WIN = 256
+    win_k = synth.kv_stream(B * WIN, HKV, seed=11, device=dev).reshape(HKV, B, WIN, D).permute(1, 0, 2, 3).contiguous()
+    win_v = synth.kv_stream(B * WIN, HKV, seed=12, device=dev).reshape(HKV, B, WIN, D).permute(1, 0, 2, 3).contiguous()
+    win_len = torch.full((B,), WIN, dtype=torch.int32, device=dev)
+    ws_h = torch.empty(Context.attn_hybrid_workspace_bytes(B, HQ, HKV, CTX, WIN), dtype=torch.uint8, device=dev)
+
+    def hybrid_step(i):
+        kc_, kr_, vc_, vr_ = caches[i % N_CACHES]
+        ctx.attn_decode_hybrid(q, out, kc_, kr_, vc_, vr_, seq_start, ctx_len, win_k, win_v, win_len, CTX, scale, ws_h)
+
+    for i in range(args.warmup):
+        hybrid_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        hybrid_step(i)
+    torch.cuda.synchronize()
+    hybrid_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    hybrid_bytes = step_bytes + 2 * 2 * D * B * HKV * WIN   # + bf16 keys and values of the window
+
     result = {
         "metric": "decode attn HBM GB/s on polar-quantized KV @32k ctx",
         "value": round(value, 1),
@@ -199,6 +221,13 @@ def main():
             "frac_of_hbm_roofline": round(enc_gbs / HBM_PEAK_GBS, 4),
             "kernel": "pq_encode_kernel",
             "tokens_timed": encode_tokens,
+        },
+        "hybrid": {
+            "workload": "configs[2] prefix + 256 unquantised (bf16) recent tokens per sequence, pq_attn_decode_hybrid "
+                        "(attention only, no append)",
+            "ms_per_step": round(hybrid_ms, 4),
+            "gb_per_s": round(hybrid_bytes / (hybrid_ms * 1e-3) / 1e9, 1),
+            "algorithmic_bytes_per_step": hybrid_bytes,
         },
         "setup_s": round(t_setup, 1),
     }

@@ -205,6 +205,29 @@ pq_status pq_decode_step_polar(const pq_ctx *ctx, const void *xk, const void *xv
                                void *hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * Decode attention over a quantised prefix plus an unquantised recent window
+ * (Section 5.2: the keys and values streamed in during generation are kept in
+ * 16 bits, only the prompt's are quantised): one softmax over the DeQuant of
+ * sequence b's ctx_len[b] cached tokens (Eq. 5) and its win_len[b] window
+ * tokens, taken as given.  win_k, win_v (device): bf16 [B][Hkv][win_cap][128]
+ * contiguous; win_len (device): B entries, clamped to [0, win_cap]; the order
+ * of the window tokens does not matter.  All other arguments as for
+ * pq_attn_decode_polar (ctx_len counts the quantised tokens only); workspace:
+ * at least pq_attn_hybrid_workspace_bytes(B, Hq, Hkv, max_ctx, win_cap) bytes.
+ * A sequence with neither prefix nor window gives a zero output row.
+ * ------------------------------------------------------------------------- */
+pq_status pq_attn_decode_hybrid(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
+                                const uint8_t *k_codes, const uint16_t *k_radii,
+                                const uint8_t *v_codes, const uint16_t *v_radii,
+                                const int64_t *seq_start, const int32_t *ctx_len,
+                                const void *win_k, const void *win_v, const int32_t *win_len,
+                                int64_t win_cap, int B, int Hq, int Hkv, int64_t pool_tokens,
+                                int64_t max_ctx, float softmax_scale, void *workspace,
+                                size_t workspace_bytes, void *hip_stream);
+
+size_t pq_attn_hybrid_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap);
+
+/* ---------------------------------------------------------------------------
  * Optional timing of the two dominant kernels (the attention partial kernel
  * and the encode kernel) with HIP events recorded on the launch stream,
  * for benchmarks: pq_profile_begin(max_launches) creates the events and turns

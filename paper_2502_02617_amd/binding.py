@@ -2,7 +2,7 @@
 
 Function names mirror the C ABI: ``Context`` wraps ``pq_init_preconditioner`` /
 ``pq_destroy`` and its methods call ``pq_encode_kv``, ``pq_append_kv``, ``pq_append_kv_pair``,
-``pq_decode_kv``, ``pq_export_canonical``, ``pq_attn_decode_polar`` and ``pq_decode_step_polar`` with
+``pq_decode_kv``, ``pq_export_canonical``, ``pq_attn_decode_polar``, ``pq_attn_decode_hybrid`` and ``pq_decode_step_polar`` with
 pointers of torch tensors (torch is used for device memory and streams only).
 """
 import ctypes
@@ -63,6 +63,11 @@ def library():
     L.pq_decode_step_polar.restype = i32
     L.pq_decode_step_polar.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, i64,
                                        ctypes.c_float, vp, ctypes.c_size_t, vp]
+    L.pq_attn_decode_hybrid.restype = i32
+    L.pq_attn_decode_hybrid.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i64, i64,
+                                        ctypes.c_float, vp, ctypes.c_size_t, vp]
+    L.pq_attn_hybrid_workspace_bytes.restype = ctypes.c_size_t
+    L.pq_attn_hybrid_workspace_bytes.argtypes = [i32, i32, i32, i64, i64]
     L.pq_attn_workspace_bytes.restype = ctypes.c_size_t
     L.pq_attn_workspace_bytes.argtypes = [i32, i32, i32, i64]
     L.pq_profile_begin.restype = i32
@@ -218,6 +223,29 @@ class Context:
     @staticmethod
     def attn_workspace_bytes(B, Hq, Hkv, max_ctx):
         return int(library().pq_attn_workspace_bytes(int(B), int(Hq), int(Hkv), int(max_ctx)))
+
+    def attn_decode_hybrid(self, q, out, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len, win_k, win_v, win_len,
+                           max_ctx, softmax_scale, workspace):
+        """Quantised prefix + bf16 window: win_k, win_v [B, Hkv, win_cap, 128] bf16 contiguous, win_len int32 [B]."""
+        if not (win_k.is_contiguous() and win_v.is_contiguous()):
+            raise PolarQuantError("win_k and win_v must be contiguous")
+        B, Hq = q.shape[0], q.shape[1]
+        Hkv = k_codes.shape[0]
+        if win_k.shape != win_v.shape or tuple(win_k.shape[:2]) != (B, Hkv) or win_k.shape[3] != 128:
+            raise PolarQuantError("win_k and win_v must both be [B, Hkv, win_cap, 128]")
+        if _dtype_code(win_k) != PQ_BF16 or _dtype_code(win_v) != PQ_BF16:
+            raise PolarQuantError("the window is bfloat16")
+        pool_tokens = k_codes.shape[1] * TILE_TOKENS
+        _check(library().pq_attn_decode_hybrid(
+            self._h, q.data_ptr(), out.data_ptr(), _dtype_code(out), k_codes.data_ptr(), k_radii.data_ptr(),
+            v_codes.data_ptr(), v_radii.data_ptr(), seq_start.data_ptr(), ctx_len.data_ptr(), win_k.data_ptr(),
+            win_v.data_ptr(), win_len.data_ptr(), int(win_k.shape[2]), int(B), int(Hq), int(Hkv), int(pool_tokens),
+            int(max_ctx), float(softmax_scale), workspace.data_ptr(),
+            int(workspace.numel() * workspace.element_size()), _stream()))
+
+    @staticmethod
+    def attn_hybrid_workspace_bytes(B, Hq, Hkv, max_ctx, win_cap):
+        return int(library().pq_attn_hybrid_workspace_bytes(int(B), int(Hq), int(Hkv), int(max_ctx), int(win_cap)))
 
     def decode_step_polar(self, xk, xv, dst_token, q, out, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len,
                           max_ctx, softmax_scale, workspace):

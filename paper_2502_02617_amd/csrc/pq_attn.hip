@@ -622,13 +622,22 @@ struct CombineArgs {
     void *out;       /* bf16 or f32 [B][Hq][128] */
     int out_f32;
     const PqDeviceConsts *consts;
+    /* unquantised window (hybrid attention only): partial results in the original domain */
+    const float *win_ml, *win_o;
+    const int32_t *win_len;
+    int n_wchunks, win_cap;
 };
 
+/* HYBRID adds the partial results of the unquantised window.  They live in the original
+ * domain, so they join after the un-rotation of the prefix sum:
+ * out = (S^T-product of (sum_c w_c o'_c / sigma) + sum_w w_w o_w) / (sum of all w l). */
+template <bool HYBRID>
 __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
 {
     __shared__ float so[PQ_D];
     __shared__ float spart[4][PQ_D];
     __shared__ float sl[4][PQ_D];
+    __shared__ float sw[4][PQ_D];
     const int tid = threadIdx.x, cq = tid >> 7, j = tid & 127;
     const int row = blockIdx.x;
     MatrixSlice ms; /* requested first: its latency overlaps the reads of the partial results */
@@ -639,29 +648,55 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
     const int used = min((n_tiles + a.chunk_tiles - 1) / a.chunk_tiles, a.n_chunks);
     const float *ml = a.ws_ml + (int64_t)row * a.n_chunks * 2;
     const float *op = a.ws_o + (int64_t)row * a.n_chunks * PQ_D + j;
+    int used_w = 0;
+    const float *wml = nullptr, *wop = nullptr;
+    if (HYBRID) {
+        int w = a.win_len[b];
+        w = w < 0 ? 0 : (w > a.win_cap ? a.win_cap : w);
+        used_w = (w + 63) >> 6;
+        wml = a.win_ml + (int64_t)row * a.n_wchunks * 2;
+        wop = a.win_o + (int64_t)row * a.n_wchunks * PQ_D + j;
+    }
     /* overall maximum first, then the weighted sums; thread group cq takes chunks cq, cq+4, ...
        and the four group sums are added in a fixed order: the result does not depend on scheduling */
     float m = -INFINITY;
     for (int c = 0; c < used; ++c) m = fmaxf(m, ml[2 * c]);
-    float l = 0.f, o = 0.f;
+    if (HYBRID)
+        for (int c = 0; c < used_w; ++c) m = fmaxf(m, wml[2 * c]);
+    float l = 0.f, o = 0.f, ow = 0.f;
 #pragma unroll 4
     for (int c = cq; c < used; c += 4) {
         const float w = exp2f(ml[2 * c] - m);
         l = fmaf(ml[2 * c + 1], w, l);
         o = fmaf(op[(int64_t)c * PQ_D], w, o);
     }
+    if (HYBRID) {
+        for (int c = cq; c < used_w; c += 4) {
+            const float w = exp2f(wml[2 * c] - m);
+            l = fmaf(wml[2 * c + 1], w, l);
+            ow = fmaf(wop[(int64_t)c * PQ_D], w, ow);
+        }
+        sw[cq][j] = ow;
+    }
     spart[cq][j] = o;
     sl[cq][j] = l;
     __syncthreads();
+    float lt = 0.f, owt = 0.f;
     if (tid < PQ_D) {
         const float ot = ((spart[0][j] + spart[1][j]) + spart[2][j]) + spart[3][j];
-        const float lt = ((sl[0][j] + sl[1][j]) + sl[2][j]) + sl[3][j];
+        lt = ((sl[0][j] + sl[1][j]) + sl[2][j]) + sl[3][j];
         /* rebuilt values carry the table scale sigma of their coordinate */
-        so[j] = used > 0 ? ot / (lt * a.consts->sigma[j & 15]) : 0.f;
+        if (HYBRID) {
+            owt = ((sw[0][j] + sw[1][j]) + sw[2][j]) + sw[3][j];
+            so[j] = used > 0 ? ot / a.consts->sigma[j & 15] : 0.f;
+        } else {
+            so[j] = used > 0 ? ot / (lt * a.consts->sigma[j & 15]) : 0.f;
+        }
     }
     __syncthreads();
-    const float acc = vector_times_slice(so, ms, spart, tid); /* out_j = sum_k o'_k S[j][k] */
+    float acc = vector_times_slice(so, ms, spart, tid); /* out_j = sum_k o'_k S[j][k] */
     if (tid < PQ_D) {
+        if (HYBRID) acc = (used > 0 || used_w > 0) ? (acc + owt) / lt : 0.f;
         if (a.out_f32) {
             static_cast<float *>(a.out)[(int64_t)row * PQ_D + j] = acc;
         } else {
@@ -671,12 +706,144 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
     }
 }
 
+/* ---- unquantised recent window (Section 5.2: generation-stage keys and values stay in
+ * 16 bits): plain attention partials over bf16 rows, in the original domain.  One wavefront
+ * per (sequence, kv head, chunk of 64 window tokens); lane t scores token t against the G
+ * query heads of the group (q in LDS, read as broadcasts), the wavefront reduces maximum
+ * and sum, then lane c accumulates coordinates 2c, 2c+1 of the weighted value sum with the
+ * value rows read as whole 256-byte lines.  The window is short next to the quantised
+ * prefix, so this kernel is kept simple (vector ALU only). */
+struct WindowArgs {
+    const uint16_t *q;      /* bf16 [B][Hq][128] */
+    const uint16_t *win_k;  /* bf16 [B][Hkv][win_cap][128] */
+    const uint16_t *win_v;
+    const int32_t *win_len; /* [B] */
+    int B, Hq, Hkv, win_cap, n_wchunks;
+    float scale;            /* softmax_scale * log2(e) */
+    float *win_ml;          /* [B][Hq][n_wchunks][2] */
+    float *win_o;           /* [B][Hq][n_wchunks][128] */
+};
+
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) x = fmaxf(x, __shfl_xor(x, d));
+    return x;
+}
+
+__device__ __forceinline__ float wave_sum_fixed(float x)
+{
+    /* butterfly: every lane adds the same pairs in the same order, the result is reproducible */
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d);
+    return x;
+}
+
+template <int G>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_window_kernel(WindowArgs a)
+{
+    __shared__ float sq[kWavesPerBlock][G][PQ_D];
+    __shared__ float sp[kWavesPerBlock][G][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int wc = (int)(item % a.n_wchunks);
+    const int hk = (int)((item / a.n_wchunks) % a.Hkv);
+    const int b = (int)(item / ((int64_t)a.n_wchunks * a.Hkv));
+    if (b >= a.B) return;
+    int W = a.win_len[b];
+    W = W < 0 ? 0 : (W > a.win_cap ? a.win_cap : W);
+    const int t0 = 64 * wc;
+    const int n_valid = min(W - t0, 64);
+    if (n_valid <= 0) return; /* the combine kernel reads only the chunks below win_len */
+
+    /* q of the group's heads, scaled, as fp32 in LDS */
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const uint32_t two = reinterpret_cast<const uint32_t *>(a.q + ((int64_t)b * a.Hq + hk * G + h) * PQ_D)[lane];
+        sq[wave][h][2 * lane] = __uint_as_float(two << 16) * a.scale;
+        sq[wave][h][2 * lane + 1] = __uint_as_float(two & 0xFFFF0000u) * a.scale;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+    /* scores: lane t takes window token t0 + t (lanes beyond the window re-read the last row) */
+    const int64_t plane = ((int64_t)b * a.Hkv + hk) * a.win_cap;
+    const int tl = lane < n_valid ? lane : n_valid - 1;
+    const uint4 *krow = reinterpret_cast<const uint4 *>(a.win_k + (plane + t0 + tl) * PQ_D);
+    float s[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) s[h] = 0.f;
+#pragma unroll 4
+    for (int c = 0; c < 16; ++c) { /* 8 coordinates per step */
+        const uint4 kv = krow[c];
+        const uint32_t w[4] = {kv.x, kv.y, kv.z, kv.w};
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const float4 qa = *reinterpret_cast<const float4 *>(&sq[wave][h][8 * c]);
+            const float4 qb = *reinterpret_cast<const float4 *>(&sq[wave][h][8 * c + 4]);
+            float acc = s[h];
+            acc = fmaf(__uint_as_float(w[0] << 16), qa.x, acc);
+            acc = fmaf(__uint_as_float(w[0] & 0xFFFF0000u), qa.y, acc);
+            acc = fmaf(__uint_as_float(w[1] << 16), qa.z, acc);
+            acc = fmaf(__uint_as_float(w[1] & 0xFFFF0000u), qa.w, acc);
+            acc = fmaf(__uint_as_float(w[2] << 16), qb.x, acc);
+            acc = fmaf(__uint_as_float(w[2] & 0xFFFF0000u), qb.y, acc);
+            acc = fmaf(__uint_as_float(w[3] << 16), qb.z, acc);
+            acc = fmaf(__uint_as_float(w[3] & 0xFFFF0000u), qb.w, acc);
+            s[h] = acc;
+        }
+    }
+    float m[G], l[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const float sv = lane < n_valid ? s[h] : -INFINITY;
+        m[h] = wave_max(sv);
+        /* the same factor 2^kProbShift as the partial results of the quantised prefix carry */
+        const float p = lane < n_valid ? __builtin_amdgcn_exp2f(sv - m[h] + kProbShift) : 0.f;
+        l[h] = wave_sum_fixed(p);
+        sp[wave][h][lane] = p;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+    /* weighted values: lane c owns coordinates 2c, 2c+1; tokens in order */
+    const uint32_t *vbase = reinterpret_cast<const uint32_t *>(a.win_v + (plane + t0) * PQ_D) + lane;
+    float o0[G], o1[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) { o0[h] = 0.f; o1[h] = 0.f; }
+    for (int t = 0; t < n_valid; ++t) {
+        const uint32_t two = vbase[(int64_t)t * (PQ_D / 2)];
+        const float v0 = __uint_as_float(two << 16), v1 = __uint_as_float(two & 0xFFFF0000u);
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const float p = sp[wave][h][t];
+            o0[h] = fmaf(p, v0, o0[h]);
+            o1[h] = fmaf(p, v1, o1[h]);
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const int64_t slot = ((int64_t)b * a.Hq + hk * G + h) * a.n_wchunks + wc;
+        reinterpret_cast<float2 *>(a.win_o + slot * PQ_D)[lane] = make_float2(o0[h], o1[h]);
+        if (lane == 0) {
+            a.win_ml[slot * 2] = m[h];
+            a.win_ml[slot * 2 + 1] = l[h];
+        }
+    }
+}
+
 struct Plan {
     int chunk_tiles, n_chunks;
     size_t off_ml, off_o, total;
+    /* window partials (hybrid attention; n_wchunks == 0 otherwise) */
+    int n_wchunks;
+    size_t off_wml, off_wo;
 };
 
-Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx)
+Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap = 0)
 {
     Plan p;
     int64_t max_tiles = (max_ctx + 63) / 64;
@@ -701,6 +868,10 @@ Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx)
     p.off_ml = (rows * 2 * PQ_D * sizeof(uint16_t) + 255) & ~(size_t)255;
     p.off_o = (p.off_ml + rows * p.n_chunks * 2 * sizeof(float) + 255) & ~(size_t)255;
     p.total = p.off_o + rows * p.n_chunks * PQ_D * sizeof(float);
+    p.n_wchunks = (int)((win_cap + 63) / 64);
+    p.off_wml = (p.total + 255) & ~(size_t)255;
+    p.off_wo = (p.off_wml + rows * p.n_wchunks * 2 * sizeof(float) + 255) & ~(size_t)255;
+    if (p.n_wchunks > 0) p.total = p.off_wo + rows * p.n_wchunks * PQ_D * sizeof(float);
     return p;
 }
 
@@ -714,6 +885,12 @@ extern "C" size_t pq_attn_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ct
     return make_plan(B, Hq, Hkv, max_ctx).total;
 }
 
+extern "C" size_t pq_attn_hybrid_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap)
+{
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || max_ctx < 0 || win_cap < 0) return 0;
+    return make_plan(B, Hq, Hkv, max_ctx, win_cap).total;
+}
+
 namespace {
 
 /* the new key / value vectors of a decode step, appended by the first launch (optional) */
@@ -724,7 +901,15 @@ struct StepAppend {
     int n_heads;
 };
 
-pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const void *q, void *out, pq_dtype out_dtype,
+/* the unquantised recent window of hybrid attention (optional) */
+struct StepWindow {
+    const void *win_k, *win_v;
+    const int32_t *win_len;
+    int64_t win_cap;
+};
+
+pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const StepWindow *win, const void *q, void *out,
+                             pq_dtype out_dtype,
                              uint8_t *k_codes, uint16_t *k_radii, uint8_t *v_codes, uint16_t *v_radii,
                              const int64_t *seq_start, const int32_t *ctx_len,
                              int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
@@ -747,7 +932,13 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const voi
         if (!pq_aligned16(app->xk) || !pq_aligned16(app->xv)) return PQ_EALIGN;
         if (2 * (int64_t)B * Hkv + (int64_t)B * Hq > 0x7FFFFFFF) return PQ_EINVAL;
     }
-    const Plan p = make_plan(B, Hq, Hkv, max_ctx);
+    if (win) {
+        if (!win->win_k || !win->win_v || !win->win_len) return PQ_EINVAL;
+        if (win->win_cap <= 0 || win->win_cap > 0x7FFFFFFF) return PQ_EINVAL;
+        if (!pq_aligned16(win->win_k) || !pq_aligned16(win->win_v)) return PQ_EALIGN;
+    }
+    const Plan p = make_plan(B, Hq, Hkv, max_ctx, win ? win->win_cap : 0);
+    if ((int64_t)B * Hkv * p.n_wchunks > 0x7FFFFFFF) return PQ_EINVAL;
     if (workspace_bytes < p.total) return PQ_ENOMEM;
     const PqDeviceState *ds = nullptr;
     pq_status st = pq_device_state(ctx, &ds);
@@ -758,6 +949,18 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const voi
     float *ws_ml = reinterpret_cast<float *>(ws + p.off_ml);
     float *ws_o = reinterpret_cast<float *>(ws + p.off_o);
     const int rows = B * Hq;
+
+    if (win) {
+        WindowArgs wa{static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(win->win_k),
+                      static_cast<const uint16_t *>(win->win_v), win->win_len, B, Hq, Hkv, (int)win->win_cap,
+                      p.n_wchunks, softmax_scale * kLog2e, reinterpret_cast<float *>(ws + p.off_wml),
+                      reinterpret_cast<float *>(ws + p.off_wo)};
+        const int64_t witems = (int64_t)B * Hkv * p.n_wchunks;
+        const dim3 wgrid((unsigned)((witems + kWavesPerBlock - 1) / kWavesPerBlock)), wblk(kWavesPerBlock * 64);
+        if (G == 4) hipLaunchKernelGGL(pq_attn_window_kernel<4>, wgrid, wblk, 0, s, wa);
+        else if (G == 2) hipLaunchKernelGGL(pq_attn_window_kernel<2>, wgrid, wblk, 0, s, wa);
+        else hipLaunchKernelGGL(pq_attn_window_kernel<1>, wgrid, wblk, 0, s, wa);
+    }
 
     RotateArgs ra{static_cast<const uint16_t *>(q), qrot, ds->S_f32, softmax_scale * kLog2e, ds->consts};
     if (app) {
@@ -790,8 +993,11 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const voi
     pq_prof_after(0, s);
 
     CombineArgs ca{ws_ml, ws_o, seq_start, ctx_len, max_ctx, pool_tokens / 64, Hq, p.n_chunks, p.chunk_tiles,
-                   ds->St_f32, out, out_dtype == PQ_F32 ? 1 : 0, ds->consts};
-    hipLaunchKernelGGL(pq_attn_combine_kernel, dim3(rows), dim3(512), 0, s, ca);
+                   ds->St_f32, out, out_dtype == PQ_F32 ? 1 : 0, ds->consts,
+                   reinterpret_cast<const float *>(ws + p.off_wml), reinterpret_cast<const float *>(ws + p.off_wo),
+                   win ? win->win_len : nullptr, p.n_wchunks, win ? (int)win->win_cap : 0};
+    if (win) hipLaunchKernelGGL(pq_attn_combine_kernel<true>, dim3(rows), dim3(512), 0, s, ca);
+    else hipLaunchKernelGGL(pq_attn_combine_kernel<false>, dim3(rows), dim3(512), 0, s, ca);
     PQ_HIP_TRY(hipGetLastError());
     return PQ_OK;
 }
@@ -807,7 +1013,7 @@ extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void
                                           void *hip_stream)
 {
     /* the caches are only read on this path */
-    return attention_launches(ctx, nullptr, q, out, out_dtype, const_cast<uint8_t *>(k_codes),
+    return attention_launches(ctx, nullptr, nullptr, q, out, out_dtype, const_cast<uint8_t *>(k_codes),
                               const_cast<uint16_t *>(k_radii), const_cast<uint8_t *>(v_codes),
                               const_cast<uint16_t *>(v_radii), seq_start, ctx_len, B, Hq, Hkv, pool_tokens, max_ctx,
                               softmax_scale, workspace, workspace_bytes, hip_stream);
@@ -822,7 +1028,22 @@ extern "C" pq_status pq_decode_step_polar(const pq_ctx *ctx, const void *xk, con
                                           void *hip_stream)
 {
     const StepAppend app{xk, xv, xt, dst_token, Hkv};
-    return attention_launches(ctx, &app, q, out, out_dtype, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len,
+    return attention_launches(ctx, &app, nullptr, q, out, out_dtype, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len,
                               B, Hq, Hkv, pool_tokens, max_ctx, softmax_scale, workspace, workspace_bytes, hip_stream);
 }
 
+extern "C" pq_status pq_attn_decode_hybrid(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
+                                           const uint8_t *k_codes, const uint16_t *k_radii,
+                                           const uint8_t *v_codes, const uint16_t *v_radii,
+                                           const int64_t *seq_start, const int32_t *ctx_len,
+                                           const void *win_k, const void *win_v, const int32_t *win_len,
+                                           int64_t win_cap, int B, int Hq, int Hkv, int64_t pool_tokens,
+                                           int64_t max_ctx, float softmax_scale, void *workspace,
+                                           size_t workspace_bytes, void *hip_stream)
+{
+    const StepWindow win{win_k, win_v, win_len, win_cap};
+    return attention_launches(ctx, nullptr, &win, q, out, out_dtype, const_cast<uint8_t *>(k_codes),
+                              const_cast<uint16_t *>(k_radii), const_cast<uint8_t *>(v_codes),
+                              const_cast<uint16_t *>(v_radii), seq_start, ctx_len, B, Hq, Hkv, pool_tokens, max_ctx,
+                              softmax_scale, workspace, workspace_bytes, hip_stream);
+}

@@ -435,6 +435,52 @@ def test_decode_step_equals_append_then_attention(env):
     assert torch.isfinite(results[1][4]).all()
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (2, 2)])
+def test_hybrid_attention_prefix_plus_window(env, Hq, Hkv):
+    """Quantised prefix + bf16 window against the oracle: every mix of empty / one-tile / ragged prefix and
+    empty / partial / several-chunk window."""
+    ctx, S, cb = env
+    lens = [0, 1, 0, 100, 1000, 64, 300, 2000]
+    wins = [0, 0, 5, 1, 63, 64, 65, 200]
+    cap = 200
+    say(f"hybrid attention Hq={Hq} Hkv={Hkv} prefix={lens} window={wins}")
+    B = len(lens)
+    caches, starts, pool, k_rec, v_rec = build_cache(ctx, S, cb, lens, Hkv, seed=950)
+    g = torch.Generator().manual_seed(951)
+    win_k = torch.randn((B, Hkv, cap, 128), generator=g).to(torch.bfloat16)
+    win_v = torch.randn((B, Hkv, cap, 128), generator=g).to(torch.bfloat16)
+    win_k[:, :, :, 7] *= 6.0   # an outlier channel, as in the cached streams
+    q = synth.queries(B, Hq, seed=952)
+    kc, kr, vc, vr = caches
+    out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(Context.attn_hybrid_workspace_bytes(B, Hq, Hkv, max(lens), cap), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)
+    ctx.attn_decode_hybrid(q.to(DEV), out, kc, kr, vc, vr, torch.from_numpy(starts).to(DEV),
+                           torch.tensor(lens, dtype=torch.int32, device=DEV), win_k.to(DEV), win_v.to(DEV),
+                           torch.tensor(wins, dtype=torch.int32, device=DEV), max(lens), helpers.softmax_scale(), ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    ref = oracle.attention_hybrid(q.to(torch.float64).numpy(), k_rec, v_rec, starts, np.array(lens, np.int32),
+                                  win_k.to(torch.float64).numpy(), win_v.to(torch.float64).numpy(),
+                                  np.array(wins, np.int32), S, cb, helpers.softmax_scale())
+    assert np.all(np.isfinite(got))
+    assert np.all(got[0] == 0.0)                      # neither prefix nor window
+    per_seq = [helpers.rel_l2(got[b], ref[b]) for b in range(1, B)]
+    err = helpers.rel_l2(got[1:], ref[1:])
+    say(f"  rel L2 {err:.2e}; per sequence {['%.1e' % e for e in per_seq]}")
+    assert err <= 2e-3 and max(per_seq) <= 4e-3
+    # window only (sequence 2): no quantisation in the way, fp32 accuracy
+    assert per_seq[1] <= 1e-5
+    # the window path with an empty window equals plain attention on the prefix, bit for bit
+    out2 = torch.empty_like(out)
+    ctx.attn_decode_hybrid(q.to(DEV), out2, kc, kr, vc, vr, torch.from_numpy(starts).to(DEV),
+                           torch.tensor(lens, dtype=torch.int32, device=DEV), win_k.to(DEV), win_v.to(DEV),
+                           torch.zeros(B, dtype=torch.int32, device=DEV), max(lens), helpers.softmax_scale(), ws)
+    plain = gpu_attention(ctx, q, caches, starts, lens)
+    torch.cuda.synchronize()
+    assert helpers.rel_l2(out2.cpu().numpy()[1:], plain[1:]) <= 1e-6
+
+
 def test_attention_rejects_bad_sequences_gracefully(env):
     ctx, S, cb = env
     say("attention with an unaligned / out-of-pool sequence")
