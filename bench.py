@@ -152,6 +152,31 @@ def main():
     enc_bytes_per_token = 16 * (256 + 62)
     enc_gbs = enc_mtok * 1e6 * enc_bytes_per_token / 1e9
 
+    # ---- the same encode loop with a randomised Hadamard preconditioner (one exact bf16 term of S
+    # instead of three in the rotation), into a scratch cache
+    ctx_h = Context(seed=0, hadamard=True)
+    hk_c, hk_r = Context.alloc_cache(HKV, len(enc_inputs) * pool_per_seq, dev)
+    hv_c, hv_r = Context.alloc_cache(HKV, len(enc_inputs) * pool_per_seq, dev)
+
+    def encode_step_h(i):
+        k, v, _ = enc_inputs[i % len(enc_inputs)]
+        slot0 = (i % len(enc_inputs)) * pool_per_seq
+        ctx_h.encode_kv(k, PQ_KEY, hk_c, hk_r, dst_token0=slot0, ld_token=k.stride(1), ld_head=k.stride(0),
+                        n_tokens=CTX, n_heads=HKV)
+        ctx_h.encode_kv(v, PQ_VALUE, hv_c, hv_r, dst_token0=slot0, ld_token=v.stride(1), ld_head=v.stride(0),
+                        n_tokens=CTX, n_heads=HKV)
+
+    for i in range(args.warmup):
+        encode_step_h(i)
+    torch.cuda.synchronize()
+    profile_begin(2 * args.encode_steps + 2)
+    for i in range(args.encode_steps):
+        encode_step_h(i)
+    torch.cuda.synchronize()
+    pr_h = profile_end()
+    enc_h_mtok = CTX * args.encode_steps / (pr_h["encode_ms"] * 1e-3) / 1e6 if pr_h["encode_ms"] > 0 else 0.0
+    del hk_c, hk_r, hv_c, hv_r
+
     # ---- hybrid line: the same quantised 32k-token prefix plus a bf16 window of 256 recent tokens per
     # sequence (the keys and values of the generation stage kept in 16 bits), pq_attn_decode_hybrid
     WIN = 256
@@ -221,6 +246,12 @@ def main():
             "frac_of_hbm_roofline": round(enc_gbs / HBM_PEAK_GBS, 4),
             "kernel": "pq_encode_kernel",
             "tokens_timed": encode_tokens,
+        },
+        "encode_hadamard": {
+            "workload": "configs[1] with S = randomised Hadamard matrix (pq_init_preconditioner_hadamard)",
+            "mtok_per_s": round(enc_h_mtok, 2),
+            "gb_per_s": round(enc_h_mtok * 1e6 * enc_bytes_per_token / 1e9, 1),
+            "frac_of_hbm_roofline": round(enc_h_mtok * 1e6 * enc_bytes_per_token / 1e9 / HBM_PEAK_GBS, 4),
         },
         "hybrid": {
             "workload": "configs[2] prefix + 256 unquantised (bf16) recent tokens per sequence, pq_attn_decode_hybrid "

@@ -87,6 +87,15 @@ const char *pq_status_string(pq_status s);
  * ------------------------------------------------------------------------- */
 pq_status pq_init_preconditioner(pq_ctx **out, int d, uint64_t seed, const double *S_rowmajor_f64);
 
+/* The same with a structured preconditioner: S = D H / sqrt(d), H the Sylvester
+ * Hadamard matrix H[i][j] = (-1)^popcount(i & j), D a diagonal of random signs
+ * drawn from seed (Section 1 names random Hadamard matrices as preconditioners
+ * of this kind).  Everything else (codebooks, layout, kernels) is unchanged;
+ * because all entries of such an S are +-1/sqrt(d), pq_encode_kv rotates with
+ * one exact bf16 term instead of three.  Any S passed to pq_init_preconditioner
+ * whose entries all have that magnitude takes the same path. */
+pq_status pq_init_preconditioner_hadamard(pq_ctx **out, int d, uint64_t seed);
+
 /* Copies S (d*d doubles, row-major) to host memory S_out. */
 pq_status pq_get_preconditioner(const pq_ctx *ctx, double *S_out);
 

@@ -41,6 +41,8 @@ def library():
     L.pq_status_string.argtypes = [i32]
     L.pq_init_preconditioner.restype = i32
     L.pq_init_preconditioner.argtypes = [ctypes.POINTER(vp), i32, u64, vp]
+    L.pq_init_preconditioner_hadamard.restype = i32
+    L.pq_init_preconditioner_hadamard.argtypes = [ctypes.POINTER(vp), i32, u64]
     L.pq_get_preconditioner.restype = i32
     L.pq_get_preconditioner.argtypes = [vp, vp]
     L.pq_get_codebook.restype = i32
@@ -120,9 +122,18 @@ def _dtype_code(t):
 class Context:
     """pq_ctx: the preconditioner S, the codebooks and the device constant tables."""
 
-    def __init__(self, seed=0, S=None, d=D):
+    def __init__(self, seed=0, S=None, d=D, hadamard=False):
+        """S: explicit d x d orthogonal matrix; hadamard=True: randomised Hadamard matrix from seed
+        (pq_init_preconditioner_hadamard); otherwise the QR factor of a seeded Gaussian matrix."""
         L = library()
         h = ctypes.c_void_p()
+        if hadamard:
+            if S is not None:
+                raise PolarQuantError("give either S or hadamard=True")
+            _check(L.pq_init_preconditioner_hadamard(ctypes.byref(h), int(d), int(seed)))
+            self._h = h
+            self.d = d
+            return
         if S is not None:
             S = np.ascontiguousarray(S, dtype=np.float64)
             if S.shape != (d, d):

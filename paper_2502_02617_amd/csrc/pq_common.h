@@ -47,7 +47,8 @@ struct PqDeviceState {
     PqDeviceConsts *consts = nullptr; /* device */
     float *S_f32 = nullptr;           /* device [128][128], S[i][j]              */
     float *St_f32 = nullptr;          /* device [128][128], St[j][i] = S[i][j]   */
-    uint16_t *S_bf16x3 = nullptr;     /* device: three bf16 terms of S in MFMA operand order */
+    uint16_t *S_bf16x3 = nullptr;     /* device: three bf16 terms of S (of sqrt(d) * S if its entries are all
+                                         +-1/sqrt(d): one term, the others zero) in MFMA operand order */
 };
 
 #define PQ_MAX_DEVICES 16
@@ -56,6 +57,9 @@ struct pq_ctx {
     int d;
     uint64_t seed;
     double S[PQ_D * PQ_D];
+    /* every entry of S is +-1/sqrt(d) (a sign-flipped Hadamard matrix, say): sqrt(d) * S is then
+       exact in bf16 and the encode kernel multiplies by one term instead of three */
+    bool unit_entries;
     double centroids[4][16];
     double boundaries[4][17];
     PqDeviceConsts host_consts;

@@ -36,7 +36,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
    A-operand fetch then feeds one matrix instruction instead of two. */
 template <int XT> struct EncodeShape { static constexpr int waves = 8; };
 constexpr int kImgDwords = (PQL_CODE_BYTES + PQL_RADII * 2) / 4; /* 992 */
-constexpr int kSChunks = 3 * 4 * 8 * 64;  /* 16-byte chunks of the bf16x3 copy of S */
 
 struct EncodeArgs {
     const void *x;
@@ -201,11 +200,15 @@ __device__ __forceinline__ void emit_value_full(uint32_t *img, int j, int b, con
     }
 }
 
-template <int XT, int KIND>
+/* NTERMS = 3: S as three bf16 terms.  NTERMS = 1: every entry of S is +-1/sqrt(128), the
+   operand is sqrt(128) * S (exactly +-1 in bf16), one product per k-step replaces three and
+   the common factor is taken out of the block radius (the angles do not see it). */
+template <int XT, int KIND, int NTERMS>
 __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(EncodeArgs a)
 {
     constexpr int kWaves = EncodeShape<XT>::waves, kThreads = kWaves * 64;
-    __shared__ uint4 sS[kSChunks];                  /* 96 KB: S1, S2, S3 in A-operand order */
+    constexpr int kSChunks = NTERMS * 4 * 8 * 64;   /* 16-byte chunks of the copy of S that is used */
+    __shared__ uint4 sS[kSChunks];                  /* 32 KB per term, in A-operand order */
     __shared__ uint32_t sImg[kWaves][kImgDwords];   /* one tile image per wavefront */
 
     const int lane = threadIdx.x & 63;
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
     for (int c = threadIdx.x; c < kSChunks; c += kThreads) sS[c] = a.S_bf16x3[c];
     __syncthreads();
 
-    const Thresholds th = load_thresholds(*a.consts);
+    const Thresholds th = load_thresholds(*a.consts, NTERMS == 1 ? 0.08838834764831845f /* 1/sqrt(128) */ : 1.0f);
 
     uint32_t *img = sImg[wave];
     const int j = lane & 31, H = lane >> 5; /* vector within the 32-vector group, lane half */
@@ -336,33 +339,28 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
                 const bool mul = st < 3, quant = st >= 0;
                 PolarState ps[NVT];
                 BOperand sa_next;
-                if (mul) sa_next.q = sS[((2 * 4 + (st + 1)) * 8 + 0) * 64 + lane];
-                /* slice m of the vector work that goes with k-step ks: six slices, one after each
-                   of the six matrix instructions of the k-step */
-                constexpr int NM = NVT * (NXT == 1 ? 3 : 6); /* matrix instructions per k-step */
-                auto slice = [&](int ks, int m) {
-                    if (NVT == 2) {
-                        if (m == 0) polar_level1_a(ps[0], cur[0], ks, th);
-                        if (m == 1) polar_level1_b(ps[0], cur[0], ks);
-                        if (m == 2) polar_level1_a(ps[NVT - 1], cur[NVT - 1], ks, th);
-                        if (m == 3) polar_level1_b(ps[NVT - 1], cur[NVT - 1], ks);
-                        if (m == 4) polar_upper(ps[0], ks, th);
-                        if (m == 5) polar_upper(ps[NVT - 1], ks, th);
-                    } else {
-                        if (m == 0) polar_level1_a(ps[0], cur[0], ks, th);
-                        if (m == NM / 3) polar_level1_b(ps[0], cur[0], ks);
-                        if (m == 2 * NM / 3) polar_upper(ps[0], ks, th);
-                    }
+                if (mul) sa_next.q = sS[(((NTERMS - 1) * 4 + (st + 1)) * 8 + 0) * 64 + lane];
+                /* The vector work that goes with k-step ks comes in U units (level-1 pair ks in two parts
+                   and the upper-level nodes it completes, per vector); they are spread evenly behind the
+                   NM matrix instructions of the k-step. */
+                constexpr int NM = NXT == 1 ? NVT * NTERMS : NVT * (NTERMS == 3 ? 6 : 3);
+                constexpr int U = 3 * NVT;
+                auto unit = [&](int ks, int u) {
+                    const int v = NVT == 2 ? (u < 4 ? u >> 1 : u - 4) : 0;
+                    const int part = NVT == 2 ? (u < 4 ? (u & 1) : 2) : u;
+                    if (part == 0) polar_level1_a(ps[v], cur[v], ks, th);
+                    if (part == 1) polar_level1_b(ps[v], cur[v], ks);
+                    if (part == 2) polar_upper(ps[v], ks, th);
                 };
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks) {
                     int m = 0;
 #pragma unroll
-                    for (int term = 2; term >= 0; --term) { /* smallest terms first */
+                    for (int term = NTERMS - 1; term >= 0; --term) { /* smallest terms first */
                         if (mul) {
                             /* A operand of this step; the next one is requested from LDS right away */
                             const BOperand sa = sa_next;
-                            const int nterm = term > 0 ? term - 1 : 2, nks = term > 0 ? ks : ks + 1;
+                            const int nterm = term > 0 ? term - 1 : NTERMS - 1, nks = term > 0 ? ks : ks + 1;
                             if (nks < 8) sa_next.q = sS[((nterm * 4 + (st + 1)) * 8 + nks) * 64 + lane];
 #pragma unroll
                             for (int v = 0; v < NVT; ++v)
@@ -370,11 +368,12 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
                                 for (int xt = 0; xt < NXT; ++xt) {
                                     if (xt + term > 2) continue; /* below 2^-24 of the leading product */
                                     /* the first product of a row tile starts from a zero accumulator operand */
-                                    const bool first = (ks == 0 && term == 2 && xt == 0);
+                                    const bool first = (ks == 0 && term == NTERMS - 1 && xt == 0);
                                     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                                     nxt[v] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa.v, xb[v][xt][ks].v, first ? zero : nxt[v], 0, 0, 0);
                                     if (quant) {
-                                        slice(ks, m);
+#pragma unroll
+                                        for (int u = m * U / NM; u < (m + 1) * U / NM; ++u) unit(ks, u);
                                         __builtin_amdgcn_sched_barrier(0);
                                     }
                                     ++m;
@@ -383,7 +382,7 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
                     }
                     if (!mul) {
 #pragma unroll
-                        for (int mm = 0; mm < NM; ++mm) slice(ks, mm);
+                        for (int u = 0; u < U; ++u) unit(ks, u);
                     }
                 }
                 if (quant) {
@@ -453,7 +452,7 @@ __global__ __launch_bounds__(512) void pq_append_pair_kernel(AppendArgs k, Appen
     else append_vector<XT>(v, PQ_VALUE, (int)blockIdx.x - n);
 }
 
-template <int XT, int KIND>
+template <int XT, int KIND, int NTERMS>
 pq_status launch_encode(const EncodeArgs &a, hipStream_t stream)
 {
     static int cached_cus[PQ_MAX_DEVICES] = {0};
@@ -471,19 +470,25 @@ pq_status launch_encode(const EncodeArgs &a, hipStream_t stream)
     if (blocks > cus) blocks = cus;
     if (blocks < 1) blocks = 1;
     pq_prof_before(1, stream);
-    hipLaunchKernelGGL((pq_encode_kernel<XT, KIND>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((pq_encode_kernel<XT, KIND, NTERMS>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a);
     pq_prof_after(1, stream);
     PQ_HIP_TRY(hipGetLastError());
     return PQ_OK;
 }
 
-pq_status dispatch_encode(const EncodeArgs &a, pq_dtype xt, pq_kind kind, hipStream_t stream)
+template <int NTERMS>
+pq_status dispatch_encode_terms(const EncodeArgs &a, pq_dtype xt, pq_kind kind, hipStream_t stream)
 {
     if (xt == PQ_BF16)
-        return kind == PQ_KEY ? launch_encode<PQ_BF16, PQ_KEY>(a, stream)
-                              : launch_encode<PQ_BF16, PQ_VALUE>(a, stream);
-    return kind == PQ_KEY ? launch_encode<PQ_F32, PQ_KEY>(a, stream)
-                          : launch_encode<PQ_F32, PQ_VALUE>(a, stream);
+        return kind == PQ_KEY ? launch_encode<PQ_BF16, PQ_KEY, NTERMS>(a, stream)
+                              : launch_encode<PQ_BF16, PQ_VALUE, NTERMS>(a, stream);
+    return kind == PQ_KEY ? launch_encode<PQ_F32, PQ_KEY, NTERMS>(a, stream)
+                          : launch_encode<PQ_F32, PQ_VALUE, NTERMS>(a, stream);
+}
+
+pq_status dispatch_encode(const EncodeArgs &a, pq_dtype xt, pq_kind kind, bool unit_entries, hipStream_t stream)
+{
+    return unit_entries ? dispatch_encode_terms<1>(a, xt, kind, stream) : dispatch_encode_terms<3>(a, xt, kind, stream);
 }
 
 } // namespace
@@ -519,7 +524,7 @@ extern "C" pq_status pq_encode_kv(const pq_ctx *ctx, const void *x, pq_dtype xt,
     a.n_items = a.n_tiles * n_heads;
     a.S_bf16x3 = reinterpret_cast<const uint4 *>(ds->S_bf16x3);
     a.consts = ds->consts;
-    return dispatch_encode(a, xt, kind, static_cast<hipStream_t>(hip_stream));
+    return dispatch_encode(a, xt, kind, ctx->unit_entries, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,

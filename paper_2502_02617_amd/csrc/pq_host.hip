@@ -298,7 +298,37 @@ extern "C" const char *pq_status_string(pq_status s)
     return "unknown pq_status";
 }
 
+namespace {
+
+/* S = D H / sqrt(d): H the Sylvester Hadamard matrix H[i][j] = (-1)^popcount(i & j), D a diagonal of
+   random signs (bit 63 of the counter-based generator at counter i), so y = x S flips the sign of
+   coordinate i by D_i and then applies the Hadamard transform. */
+void fill_randomised_hadamard(uint64_t seed, int d, double *S)
+{
+    const uint64_t sm = splitmix_finalise(seed ^ 0x48414441ULL);
+    const double inv = 1.0 / sqrt((double)d);
+    for (int i = 0; i < d; ++i) {
+        const uint64_t bits = splitmix_finalise(sm + ((uint64_t)i + 1) * 0x9E3779B97F4A7C15ULL);
+        const double di = (bits >> 63) ? -1.0 : 1.0;
+        for (int j = 0; j < d; ++j) S[(size_t)i * d + j] = (__builtin_popcount((unsigned)(i & j)) & 1) ? -di * inv : di * inv;
+    }
+}
+
+} // namespace
+
+static pq_status init_context(pq_ctx **out, int d, uint64_t seed, const double *S_in, bool hadamard);
+
 extern "C" pq_status pq_init_preconditioner(pq_ctx **out, int d, uint64_t seed, const double *S_in)
+{
+    return init_context(out, d, seed, S_in, false);
+}
+
+extern "C" pq_status pq_init_preconditioner_hadamard(pq_ctx **out, int d, uint64_t seed)
+{
+    return init_context(out, d, seed, nullptr, true);
+}
+
+static pq_status init_context(pq_ctx **out, int d, uint64_t seed, const double *S_in, bool hadamard)
 {
     if (!out) return PQ_EINVAL;
     *out = nullptr;
@@ -312,11 +342,16 @@ extern "C" pq_status pq_init_preconditioner(pq_ctx **out, int d, uint64_t seed, 
         for (int i = 0; i < d * d; ++i)
             if (!isfinite(ctx->S[i])) { delete ctx; return PQ_EINVAL; }
         if (!(orthogonality_defect(ctx->S, d) <= 1e-10)) { delete ctx; return PQ_EINVAL; }
+    } else if (hadamard) {
+        fill_randomised_hadamard(seed, d, ctx->S);
     } else {
         std::vector<double> G;
         fill_gaussian(seed, d, G);
         if (!orthonormalise_columns(G, d, ctx->S)) { delete ctx; return PQ_EINVAL; }
     }
+    ctx->unit_entries = true;
+    for (int i = 0; i < d * d; ++i)
+        if (fabs(fabs(ctx->S[i]) * sqrt((double)d) - 1.0) > 1e-12) { ctx->unit_entries = false; break; }
     /* level 1: uniform density on [0, 2 pi): equal cells, centroids at their middles */
     for (int k = 0; k < 16; ++k) ctx->centroids[0][k] = (k + 0.5) * kPi / 8.0;
     for (int k = 0; k <= 16; ++k) ctx->boundaries[0][k] = k * kPi / 8.0;
@@ -390,6 +425,7 @@ pq_status pq_device_state(const pq_ctx *cctx, const PqDeviceState **out)
                         int row = 64 * kg + 8 * ks + e;
                         int col = 16 * (4 * ((i >> 2) & 1) + rt) + 4 * (i >> 3) + (i & 3);
                         double v = ctx->S[(size_t)row * d + col];
+                        if (ctx->unit_entries) v = v < 0 ? -1.0 : 1.0; /* sqrt(d) * S, exact */
                         uint16_t t1 = to_bfloat16(v);
                         double r1 = v - from_bfloat16(t1);
                         uint16_t t2 = to_bfloat16(r1);

@@ -25,11 +25,14 @@ __device__ __forceinline__ uint32_t quant3(float u, float v, float t1, float t3)
  * recursion carries squared radii (v > t u  <=>  v^2 > t^2 u^2 for u, v >= 0). */
 struct Thresholds {
     float t1a, t1c, t2a, t2c, t3a, t3c, t4a, t4c;
+    float radius_scale; /* the block radius is multiplied by this (1 unless the rotated coordinates
+                           come in scaled; the angles do not depend on a common scale) */
 };
 
-__device__ __forceinline__ Thresholds load_thresholds(const PqDeviceConsts &K)
+__device__ __forceinline__ Thresholds load_thresholds(const PqDeviceConsts &K, float radius_scale = 1.0f)
 {
     Thresholds t;
+    t.radius_scale = radius_scale;
     t.t1a = K.tan_b[0][0]; t.t1c = K.tan_b[0][2];
     t.t2a = K.tan_b[1][0] * K.tan_b[1][0]; t.t2c = K.tan_b[1][2] * K.tan_b[1][2];
     t.t3a = K.tan_b[2][0] * K.tan_b[2][0]; t.t3c = K.tan_b[2][2] * K.tan_b[2][2];
@@ -94,7 +97,7 @@ __device__ __forceinline__ void polar_upper(PolarState &s, int p, const Threshol
     }
     if (p == 7) {
         s.out.c4 = quant3(s.q3[0], s.q3[1], th.t4a, th.t4c);
-        const float r4 = __builtin_amdgcn_sqrtf(s.q3[0] + s.q3[1]);
+        const float r4 = __builtin_amdgcn_sqrtf(s.q3[0] + s.q3[1]) * th.radius_scale;
         const _Float16 rh = (_Float16)r4; /* round to nearest even */
         s.out.radius = __builtin_bit_cast(uint16_t, rh);
         s.out.l1 = s.l1;

@@ -2,6 +2,7 @@
 symbol the header declares, and its host logic (preconditioner, codebooks,
 argument validation) behaves -- no kernel is launched here."""
 import ctypes
+import math
 import os
 import re
 
@@ -119,3 +120,22 @@ def test_layout_positions_are_a_bijection():
                     owner[c4 : c4 + 2] += 1
                     rad_owner[(g_ * 8 + b) * 16 + s] += 1
         assert np.all(owner == 1) and np.all(rad_owner == 1), kind
+
+
+def test_hadamard_preconditioner_structure():
+    """pq_init_preconditioner_hadamard: S = D H / sqrt(d) with the Sylvester H and a sign diagonal D that
+    depends on the seed; orthogonal, symmetric up to D, and H itself for its first row and column signs."""
+    import scipy.linalg
+
+    H = scipy.linalg.hadamard(128).astype(np.float64)
+    seen = set()
+    for seed in (0, 1, 7):
+        S = binding.Context(seed=seed, hadamard=True).preconditioner()
+        assert np.max(np.abs(S @ S.T - np.eye(128))) <= 1e-12
+        M = S * math.sqrt(128.0)
+        assert np.max(np.abs(np.abs(M) - 1.0)) <= 1e-12
+        D = np.sign(M[:, 0])                       # H[i][0] = +1
+        assert np.array_equal(np.sign(M), D[:, None] * H)
+        assert 30 <= int((D < 0).sum()) <= 98      # the signs look random
+        seen.add(tuple(D))
+    assert len(seen) == 3

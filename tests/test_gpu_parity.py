@@ -481,6 +481,62 @@ def test_hybrid_attention_prefix_plus_window(env, Hq, Hkv):
     assert helpers.rel_l2(out2.cpu().numpy()[1:], plain[1:]) <= 1e-6
 
 
+@pytest.mark.parametrize("which", ["hadamard", "identity"])
+def test_other_preconditioners_encode_and_attend(which):
+    """A randomised Hadamard S (one exact bf16 term in the encode kernel) and S = I (no preconditioning):
+    the library's S is handed to the oracle as data; encode, DeQuant and attention against it."""
+    cb = oracle.default_codebooks()
+    if which == "hadamard":
+        ctx = Context(seed=5, hadamard=True)
+    else:
+        ctx = Context(S=np.eye(128))
+    S = ctx.preconditioner()
+    assert np.max(np.abs(S @ S.T - np.eye(128))) <= 1e-12
+    for kind in (PQ_KEY, PQ_VALUE):
+        if which == "hadamard":
+            for dtype in (torch.bfloat16, torch.float32):
+                x = synth.kv_stream(700, 3, seed=970 + kind).permute(1, 0, 2).contiguous().to(dtype)
+                check_encode(ctx, S, cb, x, kind, f"{which} S")
+        else:
+            # without a rotation, 8-bit mantissas would put 0.25 % of the level-1 pairs exactly on the pi/4
+            # boundaries (|y_2j| == |y_2j+1|), where either neighbour is a correct code: full fp32 data here
+            x = synth.gaussian_vectors(700 * 3, seed=972 + kind).reshape(700, 3, 128)
+            check_encode(ctx, S, cb, x, kind, f"{which} S")
+    lens = [1, 200, 1500]
+    if which == "hadamard":
+        caches, starts, pool, k_rec, v_rec = build_cache(ctx, S, cb, lens, 2, seed=980)
+    else:
+        # plain N(0,1) keys and values: without the rotation the outlier channels of the usual streams
+        # make the scores several times larger and the softmax correspondingly more sensitive, which is
+        # the regime the preconditioner exists to avoid, not the one the 2e-3 bound is stated for
+        Hkv, starts, pool = 2, [], 0
+        for n in lens:
+            starts.append(pool)
+            pool += ((n + 63) // 64) * 64
+        kc, kr = Context.alloc_cache(Hkv, pool, DEV)
+        vc, vr = Context.alloc_cache(Hkv, pool, DEV)
+        for t in (kc, kr, vc, vr):
+            t.zero_()
+        k_rec = np.zeros((Hkv, pool, 62), dtype=np.uint8)
+        v_rec = np.zeros((Hkv, pool, 62), dtype=np.uint8)
+        for b, n in enumerate(lens):
+            k = synth.gaussian_vectors(n * Hkv, seed=982 + 2 * b).reshape(n, Hkv, 128)
+            v = synth.gaussian_vectors(n * Hkv, seed=983 + 2 * b).reshape(n, Hkv, 128)
+            ctx.encode_kv(k.to(DEV), PQ_KEY, kc, kr, dst_token0=starts[b])
+            ctx.encode_kv(v.to(DEV), PQ_VALUE, vc, vr, dst_token0=starts[b])
+            k_rec[:, starts[b]:starts[b] + n] = oracle_records(k, S, cb)[0]
+            v_rec[:, starts[b]:starts[b] + n] = oracle_records(v, S, cb)[0]
+        torch.cuda.synchronize()
+        caches, starts = (kc, kr, vc, vr), np.array(starts, dtype=np.int64)
+    q = synth.queries(len(lens), 8, seed=981)
+    got = gpu_attention(ctx, q, caches, starts, lens)
+    ref = oracle.attention(q.to(torch.float64).numpy(), k_rec, v_rec, starts, np.array(lens, np.int32), S, cb,
+                           helpers.softmax_scale())
+    err = helpers.rel_l2(got, ref)
+    say(f"  {which} S: attention rel L2 {err:.2e}")
+    assert err <= 2e-3
+
+
 def test_attention_rejects_bad_sequences_gracefully(env):
     ctx, S, cb = env
     say("attention with an unaligned / out-of-pool sequence")
