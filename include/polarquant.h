@@ -97,6 +97,18 @@ pq_status pq_init_preconditioner(pq_ctx **out, int d, uint64_t seed, const doubl
 pq_status pq_init_preconditioner_hadamard(pq_ctx **out, int d, uint64_t seed);
 
 /* Copies S (d*d doubles, row-major) to host memory S_out. */
+/* Replaces the codebooks of a context that has not launched anything yet (PQ_EINVAL
+ * afterwards: the tables are already on a device) -- the place where codebooks fitted
+ * to a prompt's own angles (Section 4.1, online variant) come in, and with S = I the
+ * un-preconditioned variant.  cb (host): 28 centroids in radians, level 1 first (16 in
+ * [0, 2 pi)), then 4 each for levels 2, 3, 4 (in [0, pi/2)), strictly increasing per
+ * level.  Cell boundaries are the midpoints of neighbouring centroids (procedure Quant:
+ * nearest centroid, linear distance, no wrap-around at level 1).  PQ_EUNSUPPORTED if two
+ * level-1 boundaries are closer than about 0.02 rad.  Encode, append, DeQuant and the
+ * attention kernels all follow the new codebooks; encoding is somewhat slower than with
+ * the analytic ones (level 1 no longer has equal cells). */
+pq_status pq_set_codebooks(pq_ctx *ctx, const double *cb);
+
 pq_status pq_get_preconditioner(const pq_ctx *ctx, double *S_out);
 
 /* level in 1..4.  centroids: K doubles (K = 16 for level 1, 4 otherwise);

@@ -43,6 +43,8 @@ def library():
     L.pq_init_preconditioner.argtypes = [ctypes.POINTER(vp), i32, u64, vp]
     L.pq_init_preconditioner_hadamard.restype = i32
     L.pq_init_preconditioner_hadamard.argtypes = [ctypes.POINTER(vp), i32, u64]
+    L.pq_set_codebooks.restype = i32
+    L.pq_set_codebooks.argtypes = [vp, vp]
     L.pq_get_preconditioner.restype = i32
     L.pq_get_preconditioner.argtypes = [vp, vp]
     L.pq_get_codebook.restype = i32
@@ -155,6 +157,13 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def set_codebooks(self, cb):
+        """cb: 28 centroids (16 of level 1, then 4 each of levels 2-4); only before the first launch."""
+        cb = np.ascontiguousarray(cb, dtype=np.float64).reshape(-1)
+        if cb.size != 28:
+            raise PolarQuantError("cb must hold 28 centroids")
+        _check(library().pq_set_codebooks(self._h, cb.ctypes.data_as(ctypes.c_void_p)))
 
     # ---- host-side getters -------------------------------------------------
     def preconditioner(self):

@@ -39,6 +39,14 @@ struct PqDeviceConsts {
        rebuilt with them for coordinate i of a block is sigma[i] times too large.
        The query is divided by sigma before the scores, the output after the sum. */
     float sigma[16];
+    /* Codebooks other than the analytic ones (set with pq_set_codebooks): general != 0.
+       Level 1 is then quantised through the pseudo-angle p(psi) in [0, 4) -- quadrant number
+       plus |y| / (|x| + |y|) or |x| / (|x| + |y|), monotone in psi -- and a table over 512
+       equal cells of p: cell c holds the number of level-1 boundaries in the cells before it
+       and the pseudo-angle of the one boundary inside it (+inf if none); code = count +
+       (p > that).  Levels 2-4 use tan_b with all three of its entries. */
+    int general;
+    struct Lut1Cell { float thr; uint32_t count; } lut1[512];
 };
 
 /* Per-device constant buffers of a context (created on first use). */
@@ -60,6 +68,7 @@ struct pq_ctx {
     /* every entry of S is +-1/sqrt(d) (a sign-flipped Hadamard matrix, say): sqrt(d) * S is then
        exact in bf16 and the encode kernel multiplies by one term instead of three */
     bool unit_entries;
+    bool general_codebooks; /* codebooks replaced by pq_set_codebooks */
     double centroids[4][16];
     double boundaries[4][17];
     PqDeviceConsts host_consts;

@@ -203,7 +203,9 @@ __device__ __forceinline__ void emit_value_full(uint32_t *img, int j, int b, con
 /* NTERMS = 3: S as three bf16 terms.  NTERMS = 1: every entry of S is +-1/sqrt(128), the
    operand is sqrt(128) * S (exactly +-1 in bf16), one product per k-step replaces three and
    the common factor is taken out of the block radius (the angles do not see it). */
-template <int XT, int KIND, int NTERMS>
+/* GENERAL: codebooks set by the caller; level 1 goes through the pseudo-angle cell table (staged
+   in LDS), the upper levels compare against three free boundaries. */
+template <int XT, int KIND, int NTERMS, bool GENERAL>
 __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(EncodeArgs a)
 {
     constexpr int kWaves = EncodeShape<XT>::waves, kThreads = kWaves * 64;
@@ -217,7 +219,13 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
     for (int c = threadIdx.x; c < kSChunks; c += kThreads) sS[c] = a.S_bf16x3[c];
     __syncthreads();
 
-    const Thresholds th = load_thresholds(*a.consts, NTERMS == 1 ? 0.08838834764831845f /* 1/sqrt(128) */ : 1.0f);
+    Thresholds th = load_thresholds(*a.consts, NTERMS == 1 ? 0.08838834764831845f /* 1/sqrt(128) */ : 1.0f);
+    __shared__ PqDeviceConsts::Lut1Cell sLut[GENERAL ? 512 : 1];
+    if (GENERAL) {
+        for (int c = threadIdx.x; c < 512; c += kThreads) sLut[c] = a.consts->lut1[c];
+        th.lut1 = sLut;
+        __syncthreads();
+    }
 
     uint32_t *img = sImg[wave];
     const int j = lane & 31, H = lane >> 5; /* vector within the 32-vector group, lane half */
@@ -348,9 +356,9 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
                 auto unit = [&](int ks, int u) {
                     const int v = NVT == 2 ? (u < 4 ? u >> 1 : u - 4) : 0;
                     const int part = NVT == 2 ? (u < 4 ? (u & 1) : 2) : u;
-                    if (part == 0) polar_level1_a(ps[v], cur[v], ks, th);
-                    if (part == 1) polar_level1_b(ps[v], cur[v], ks);
-                    if (part == 2) polar_upper(ps[v], ks, th);
+                    if (part == 0) polar_level1_a<GENERAL>(ps[v], cur[v], ks, th);
+                    if (part == 1) polar_level1_b<GENERAL>(ps[v], cur[v], ks);
+                    if (part == 2) polar_upper<GENERAL>(ps[v], ks, th);
                 };
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks) {
@@ -452,7 +460,7 @@ __global__ __launch_bounds__(512) void pq_append_pair_kernel(AppendArgs k, Appen
     else append_vector<XT>(v, PQ_VALUE, (int)blockIdx.x - n);
 }
 
-template <int XT, int KIND, int NTERMS>
+template <int XT, int KIND, int NTERMS, bool GENERAL>
 pq_status launch_encode(const EncodeArgs &a, hipStream_t stream)
 {
     static int cached_cus[PQ_MAX_DEVICES] = {0};
@@ -470,25 +478,30 @@ pq_status launch_encode(const EncodeArgs &a, hipStream_t stream)
     if (blocks > cus) blocks = cus;
     if (blocks < 1) blocks = 1;
     pq_prof_before(1, stream);
-    hipLaunchKernelGGL((pq_encode_kernel<XT, KIND, NTERMS>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((pq_encode_kernel<XT, KIND, NTERMS, GENERAL>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a);
     pq_prof_after(1, stream);
     PQ_HIP_TRY(hipGetLastError());
     return PQ_OK;
 }
 
-template <int NTERMS>
+template <int NTERMS, bool GENERAL>
 pq_status dispatch_encode_terms(const EncodeArgs &a, pq_dtype xt, pq_kind kind, hipStream_t stream)
 {
     if (xt == PQ_BF16)
-        return kind == PQ_KEY ? launch_encode<PQ_BF16, PQ_KEY, NTERMS>(a, stream)
-                              : launch_encode<PQ_BF16, PQ_VALUE, NTERMS>(a, stream);
-    return kind == PQ_KEY ? launch_encode<PQ_F32, PQ_KEY, NTERMS>(a, stream)
-                          : launch_encode<PQ_F32, PQ_VALUE, NTERMS>(a, stream);
+        return kind == PQ_KEY ? launch_encode<PQ_BF16, PQ_KEY, NTERMS, GENERAL>(a, stream)
+                              : launch_encode<PQ_BF16, PQ_VALUE, NTERMS, GENERAL>(a, stream);
+    return kind == PQ_KEY ? launch_encode<PQ_F32, PQ_KEY, NTERMS, GENERAL>(a, stream)
+                          : launch_encode<PQ_F32, PQ_VALUE, NTERMS, GENERAL>(a, stream);
 }
 
-pq_status dispatch_encode(const EncodeArgs &a, pq_dtype xt, pq_kind kind, bool unit_entries, hipStream_t stream)
+pq_status dispatch_encode(const EncodeArgs &a, pq_dtype xt, pq_kind kind, bool unit_entries, bool general,
+                          hipStream_t stream)
 {
-    return unit_entries ? dispatch_encode_terms<1>(a, xt, kind, stream) : dispatch_encode_terms<3>(a, xt, kind, stream);
+    if (general)
+        return unit_entries ? dispatch_encode_terms<1, true>(a, xt, kind, stream)
+                            : dispatch_encode_terms<3, true>(a, xt, kind, stream);
+    return unit_entries ? dispatch_encode_terms<1, false>(a, xt, kind, stream)
+                        : dispatch_encode_terms<3, false>(a, xt, kind, stream);
 }
 
 } // namespace
@@ -524,7 +537,7 @@ extern "C" pq_status pq_encode_kv(const pq_ctx *ctx, const void *x, pq_dtype xt,
     a.n_items = a.n_tiles * n_heads;
     a.S_bf16x3 = reinterpret_cast<const uint4 *>(ds->S_bf16x3);
     a.consts = ds->consts;
-    return dispatch_encode(a, xt, kind, ctx->unit_entries, static_cast<hipStream_t>(hip_stream));
+    return dispatch_encode(a, xt, kind, ctx->unit_entries, ctx->general_codebooks, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,

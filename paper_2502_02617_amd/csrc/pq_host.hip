@@ -214,6 +214,15 @@ double best_table_scale(const double *vals, int n)
     return best_s;
 }
 
+/* Monotone map of an angle in [0, 2 pi) to [0, 4): quadrant number plus the share of the
+   second coordinate (even quadrants) or of the first (odd quadrants) in |x| + |y|. */
+double pseudo_angle(double psi)
+{
+    const double x = cos(psi), y = sin(psi), a = fabs(x), b = fabs(y);
+    const int sa = x < 0, sb = y < 0, f = sa ^ sb, Q = 2 * sb + f;
+    return Q + (f ? a : b) / (a + b);
+}
+
 void build_tables(pq_ctx *ctx)
 {
     PqDeviceConsts &c = ctx->host_consts;
@@ -226,8 +235,20 @@ void build_tables(pq_ctx *ctx)
             c.tan_b[0][2] = (float)tan(3.0 * kPi / 8.0);
         } else {
             c.tan_b[l - 1][0] = (float)tan(bnd[1]);
-            c.tan_b[l - 1][1] = 1.0f; /* middle boundary is pi/4 by symmetry of the density */
+            /* analytic codebooks: the middle boundary is pi/4 by symmetry of the density */
+            c.tan_b[l - 1][1] = ctx->general_codebooks ? (float)tan(bnd[2]) : 1.0f;
             c.tan_b[l - 1][2] = (float)tan(bnd[3]);
+        }
+    }
+    c.general = ctx->general_codebooks ? 1 : 0;
+    if (ctx->general_codebooks) {
+        int cell_of[15];
+        for (int k = 1; k <= 15; ++k) cell_of[k - 1] = (int)floor(pseudo_angle(ctx->boundaries[0][k]) * 128.0);
+        for (int cell = 0, before = 0; cell < 512; ++cell) {
+            c.lut1[cell].thr = INFINITY;
+            c.lut1[cell].count = (uint32_t)before;
+            for (int k = 0; k < 15; ++k)
+                if (cell_of[k] == cell) { c.lut1[cell].thr = (float)pseudo_angle(ctx->boundaries[0][k + 1]); ++before; }
         }
     }
     for (int k = 0; k < 16; ++k) {
@@ -337,6 +358,7 @@ static pq_status init_context(pq_ctx **out, int d, uint64_t seed, const double *
     if (!ctx) return PQ_ENOMEM;
     ctx->d = d;
     ctx->seed = seed;
+    ctx->general_codebooks = false;
     if (S_in) {
         memcpy(ctx->S, S_in, sizeof(double) * d * d);
         for (int i = 0; i < d * d; ++i)
@@ -358,6 +380,40 @@ static pq_status init_context(pq_ctx **out, int d, uint64_t seed, const double *
     for (int l = 2; l <= 4; ++l) lloyd_max_level(l, ctx->centroids[l - 1], ctx->boundaries[l - 1]);
     build_tables(ctx);
     *out = ctx;
+    return PQ_OK;
+}
+
+extern "C" pq_status pq_set_codebooks(pq_ctx *ctx, const double *cb)
+{
+    if (!ctx || !cb) return PQ_EINVAL;
+    std::lock_guard<std::mutex> lock(ctx->mu);
+    for (int i = 0; i < PQ_MAX_DEVICES; ++i)
+        if (ctx->dev[i].ready) return PQ_EINVAL; /* tables already on a device: the context is in use */
+    const int off[4] = {0, 16, 20, 24}, K[4] = {16, 4, 4, 4};
+    const double hi[4] = {2.0 * kPi, kPi / 2.0, kPi / 2.0, kPi / 2.0};
+    for (int l = 0; l < 4; ++l)
+        for (int k = 0; k < K[l]; ++k) {
+            const double t = cb[off[l] + k];
+            if (!isfinite(t) || t < 0.0 || t >= hi[l]) return PQ_EINVAL;
+            if (k > 0 && !(t > cb[off[l] + k - 1])) return PQ_EINVAL; /* strictly increasing */
+        }
+    /* level 1: at most one boundary per pseudo-angle cell (cells are 0.008-0.011 rad wide) */
+    {
+        int last = -1;
+        for (int k = 1; k < 16; ++k) {
+            const int cell = (int)floor(pseudo_angle(0.5 * (cb[k - 1] + cb[k])) * 128.0);
+            if (cell <= last || cell > 511) return PQ_EUNSUPPORTED;
+            last = cell;
+        }
+    }
+    for (int l = 0; l < 4; ++l) {
+        for (int k = 0; k < K[l]; ++k) ctx->centroids[l][k] = cb[off[l] + k];
+        ctx->boundaries[l][0] = 0.0;
+        ctx->boundaries[l][K[l]] = hi[l];
+        for (int k = 1; k < K[l]; ++k) ctx->boundaries[l][k] = 0.5 * (ctx->centroids[l][k - 1] + ctx->centroids[l][k]);
+    }
+    ctx->general_codebooks = true;
+    build_tables(ctx);
     return PQ_OK;
 }
 

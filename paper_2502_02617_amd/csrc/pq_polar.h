@@ -25,19 +25,48 @@ __device__ __forceinline__ uint32_t quant3(float u, float v, float t1, float t3)
  * recursion carries squared radii (v > t u  <=>  v^2 > t^2 u^2 for u, v >= 0). */
 struct Thresholds {
     float t1a, t1c, t2a, t2c, t3a, t3c, t4a, t4c;
-    float radius_scale; /* the block radius is multiplied by this (1 unless the rotated coordinates
-                           come in scaled; the angles do not depend on a common scale) */
+    float t2b, t3b, t4b; /* middle boundaries (squared tangents), used with general codebooks only */
+    float radius_scale;  /* the block radius is multiplied by this (1 unless the rotated coordinates
+                            come in scaled; the angles do not depend on a common scale) */
+    const PqDeviceConsts::Lut1Cell *lut1; /* level-1 table of general codebooks (LDS or global) */
 };
 
 __device__ __forceinline__ Thresholds load_thresholds(const PqDeviceConsts &K, float radius_scale = 1.0f)
 {
     Thresholds t;
     t.radius_scale = radius_scale;
+    t.lut1 = K.lut1;
+    t.t2b = K.tan_b[1][1] * K.tan_b[1][1];
+    t.t3b = K.tan_b[2][1] * K.tan_b[2][1];
+    t.t4b = K.tan_b[3][1] * K.tan_b[3][1];
     t.t1a = K.tan_b[0][0]; t.t1c = K.tan_b[0][2];
     t.t2a = K.tan_b[1][0] * K.tan_b[1][0]; t.t2c = K.tan_b[1][2] * K.tan_b[1][2];
     t.t3a = K.tan_b[2][0] * K.tan_b[2][0]; t.t3c = K.tan_b[2][2] * K.tan_b[2][2];
     t.t4a = K.tan_b[3][0] * K.tan_b[3][0]; t.t4c = K.tan_b[3][2] * K.tan_b[3][2];
     return t;
+}
+
+/* the same with a general middle boundary */
+__device__ __forceinline__ uint32_t quant3g(float u, float v, float t1, float t2, float t3)
+{
+    const float d1 = __builtin_fmaf(t1, u, -v), d2 = __builtin_fmaf(t2, u, -v), d3 = __builtin_fmaf(t3, u, -v);
+    return (__float_as_uint(d1) >> 31) + (__float_as_uint(d2) >> 31) + (__float_as_uint(d3) >> 31);
+}
+
+/* Level-1 code for general codebooks: pseudo-angle p in [0, 4) of (ya, yb) -- quadrant number plus
+ * |yb| / (|ya| + |yb|) in even quadrants, |ya| / (|ya| + |yb|) in odd ones, monotone in the angle --
+ * then the cell table: boundaries in earlier cells plus one compare inside the cell. */
+__device__ __forceinline__ uint32_t level1_code_general(float ya, float yb, const PqDeviceConsts::Lut1Cell *lut)
+{
+    const uint32_t ba = __float_as_uint(ya), bb = __float_as_uint(yb);
+    const uint32_t sb = bb >> 31, f = (ba ^ bb) >> 31;
+    const float a = fabsf(ya), b = fabsf(yb), sum = a + b;
+    const float frac = sum > 0.0f ? (f ? a : b) * __builtin_amdgcn_rcpf(sum) : 0.0f;
+    const float p = (float)(2u * sb + f) + frac;
+    uint32_t cell = (uint32_t)(p * 128.0f);
+    cell = cell > 511u ? 511u : cell;
+    const PqDeviceConsts::Lut1Cell c = lut[cell];
+    return c.count + (p > c.thr ? 1u : 0u);
 }
 
 struct BlockCodes {
@@ -61,42 +90,52 @@ struct PolarState {
 };
 
 /* level-1 pair p, first part: position inside the quadrant */
-template <typename Y16>
+template <bool GENERAL = false, typename Y16>
 __device__ __forceinline__ void polar_level1_a(PolarState &s, const Y16 &y, int p, const Thresholds &th)
 {
-    s.mq = quant3(fabsf(y[2 * p]), fabsf(y[2 * p + 1]), th.t1a, th.t1c);
+    if (GENERAL) s.mq = level1_code_general(y[2 * p], y[2 * p + 1], th.lut1); /* the whole code */
+    else s.mq = quant3(fabsf(y[2 * p]), fabsf(y[2 * p + 1]), th.t1a, th.t1c);
 }
 
 /* level-1 pair p, second part: quadrant, code, squared radius */
-template <typename Y16>
+template <bool GENERAL = false, typename Y16>
 __device__ __forceinline__ void polar_level1_b(PolarState &s, const Y16 &y, int p)
 {
     const float ya = y[2 * p], yb = y[2 * p + 1];
-    /* cell of atan2(yb, ya) in [0, 2 pi), cells pi/8 wide: quadrant Q = 0..3 from the signs,
-       code = 4Q + mq in quadrants 0 and 2, 4Q + 3 - mq in 1 and 3 (angle measured from the
-       other axis), which is (mq xor 7f) + 8 sb with f = sa xor sb */
-    const uint32_t ba = __float_as_uint(ya), bb = __float_as_uint(yb);
-    const uint32_t f7 = (uint32_t)((int32_t)(ba ^ bb) >> 31) & 7u;
-    const uint32_t code = (s.mq ^ f7) + ((bb >> 28) & 8u);
+    uint32_t code;
+    if (GENERAL) {
+        code = s.mq;
+    } else {
+        /* cell of atan2(yb, ya) in [0, 2 pi), cells pi/8 wide: quadrant Q = 0..3 from the signs,
+           code = 4Q + mq in quadrants 0 and 2, 4Q + 3 - mq in 1 and 3 (angle measured from the
+           other axis), which is (mq xor 7f) + 8 sb with f = sa xor sb */
+        const uint32_t ba = __float_as_uint(ya), bb = __float_as_uint(yb);
+        const uint32_t f7 = (uint32_t)((int32_t)(ba ^ bb) >> 31) & 7u;
+        code = (s.mq ^ f7) + ((bb >> 28) & 8u);
+    }
     s.l1 = (p == 0) ? code : (s.l1 | (code << (4 * p)));
     s.q1[p] = __builtin_fmaf(ya, ya, yb * yb);
 }
 
 /* the upper-level nodes whose children are complete once level-1 pair p is done */
+template <bool GENERAL = false>
 __device__ __forceinline__ void polar_upper(PolarState &s, int p, const Thresholds &th)
 {
     if (p & 1) {
         const int n = p >> 1;
-        s.c2[n] = quant3(s.q1[2 * n], s.q1[2 * n + 1], th.t2a, th.t2c);
+        s.c2[n] = GENERAL ? quant3g(s.q1[2 * n], s.q1[2 * n + 1], th.t2a, th.t2b, th.t2c)
+                          : quant3(s.q1[2 * n], s.q1[2 * n + 1], th.t2a, th.t2c);
         s.q2[n] = s.q1[2 * n] + s.q1[2 * n + 1];
     }
     if ((p & 3) == 3) {
         const int h = p >> 2;
-        s.c3[h] = quant3(s.q2[2 * h], s.q2[2 * h + 1], th.t3a, th.t3c);
+        s.c3[h] = GENERAL ? quant3g(s.q2[2 * h], s.q2[2 * h + 1], th.t3a, th.t3b, th.t3c)
+                          : quant3(s.q2[2 * h], s.q2[2 * h + 1], th.t3a, th.t3c);
         s.q3[h] = s.q2[2 * h] + s.q2[2 * h + 1];
     }
     if (p == 7) {
-        s.out.c4 = quant3(s.q3[0], s.q3[1], th.t4a, th.t4c);
+        s.out.c4 = GENERAL ? quant3g(s.q3[0], s.q3[1], th.t4a, th.t4b, th.t4c)
+                           : quant3(s.q3[0], s.q3[1], th.t4a, th.t4c);
         const float r4 = __builtin_amdgcn_sqrtf(s.q3[0] + s.q3[1]) * th.radius_scale;
         const _Float16 rh = (_Float16)r4; /* round to nearest even */
         s.out.radius = __builtin_bit_cast(uint16_t, rh);
@@ -106,15 +145,15 @@ __device__ __forceinline__ void polar_upper(PolarState &s, int p, const Threshol
     }
 }
 
-template <typename Y16>
+template <bool GENERAL = false, typename Y16>
 __device__ __forceinline__ BlockCodes polar_quant_block(const Y16 &y, const Thresholds &th)
 {
     PolarState s;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-        polar_level1_a(s, y, p, th);
-        polar_level1_b(s, y, p);
-        polar_upper(s, p, th);
+        polar_level1_a<GENERAL>(s, y, p, th);
+        polar_level1_b<GENERAL>(s, y, p);
+        polar_upper<GENERAL>(s, p, th);
     }
     return s.out;
 }
@@ -176,7 +215,8 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
 #pragma unroll
         for (int r = 0; r < 16; ++r) y[r] = sy[16 * b + r];
         const Thresholds th = load_thresholds(*a.consts);
-        BlockCodes bc = polar_quant_block(y, th);
+        /* general codebooks: the level-1 table is read from the constants in global memory */
+        BlockCodes bc = a.consts->general ? polar_quant_block<true>(y, th) : polar_quant_block<false>(y, th);
         const int64_t tile = dst >> 6;
         const int tau = (int)(dst & 63);
         uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;

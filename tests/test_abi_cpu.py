@@ -139,3 +139,28 @@ def test_hadamard_preconditioner_structure():
         assert 30 <= int((D < 0).sum()) <= 98      # the signs look random
         seen.add(tuple(D))
     assert len(seen) == 3
+
+
+def test_set_codebooks_validation_and_readback():
+    cb = oracle.default_codebooks().copy()
+    rng = np.random.default_rng(5)
+    cb[:16] += rng.uniform(-0.05, 0.05, 16)
+    cb[16:] += rng.uniform(-0.03, 0.03, 12)
+    c = Context(seed=0)
+    c.set_codebooks(cb)
+    off, K = [0, 16, 20, 24], [16, 4, 4, 4]
+    for level in range(1, 5):
+        cent, bnd = c.codebook(level)
+        want = cb[off[level - 1]:off[level - 1] + K[level - 1]]
+        assert np.array_equal(cent, want)
+        assert np.allclose(bnd[1:-1], 0.5 * (want[:-1] + want[1:]), rtol=0, atol=1e-15)
+        assert bnd[0] == 0.0 and abs(bnd[-1] - (2 * math.pi if level == 1 else math.pi / 2)) < 1e-15
+    bad = cb.copy(); bad[3] = bad[2]                      # not strictly increasing
+    with pytest.raises(PolarQuantError):
+        Context(seed=0).set_codebooks(bad)
+    bad = cb.copy(); bad[17] = 2.0                        # level 2 centroid outside [0, pi/2)
+    with pytest.raises(PolarQuantError):
+        Context(seed=0).set_codebooks(bad)
+    bad = cb.copy(); bad[5] = bad[4] + 1e-3; bad[6] = bad[5] + 1e-3   # two boundaries in one table cell
+    with pytest.raises(PolarQuantError):
+        Context(seed=0).set_codebooks(bad)

@@ -537,6 +537,94 @@ def test_other_preconditioners_encode_and_attend(which):
     assert err <= 2e-3
 
 
+def lloyd_1d(samples, init, iters=8):
+    """Plain 1-D Lloyd iterations (nearest centroid by linear distance, centroid = mean of its cell)."""
+    c = np.array(init, dtype=np.float64)
+    for _ in range(iters):
+        edges = 0.5 * (c[:-1] + c[1:])
+        idx = np.searchsorted(edges, samples)
+        for k in range(c.size):
+            sel = samples[idx == k]
+            if sel.size:
+                c[k] = sel.mean()
+    return c
+
+
+@pytest.mark.parametrize("which", ["jittered", "fitted_no_rotation"])
+def test_general_codebooks_encode_and_attend(which):
+    """Codebooks set by the caller (pq_set_codebooks): the analytic ones moved at random, and codebooks fitted
+    by Lloyd iterations to the angles of un-rotated data with outlier channels (S = I, the paper's variant
+    without preconditioning).  Encode (bulk and append), DeQuant and attention against the oracle, which
+    takes the same centroids as data."""
+    cb = oracle.default_codebooks().copy()
+    if which == "jittered":
+        ctx = Context(seed=3)
+        rng = np.random.default_rng(11)
+        cb[:16] += rng.uniform(-0.08, 0.08, 16)
+        cb[16:] += rng.uniform(-0.04, 0.04, 12)
+        make = lambda n, H, seed: synth.kv_stream(n, H, seed).permute(1, 0, 2).contiguous()
+    else:
+        ctx = Context(S=np.eye(128))
+        # fp32 data with three strong channels: level-1 angles of the pairs that hold them crowd the axes
+        def make(n, H, seed):
+            x = synth.gaussian_vectors(n * H, seed=seed).reshape(n, H, 128).clone()
+            x[:, :, [5, 40, 99]] *= 6.0
+            return x
+        sample = make(4096, 1, 990).reshape(-1, 128).double().numpy()
+        _, psi, _ = oracle.encode(sample, np.eye(128), cb, want_psi=True, want_y=True)
+        psi = psi.reshape(-1, 120)
+        cb[:16] = lloyd_1d(psi[:, :64].ravel(), cb[:16])
+        cb[16:20] = lloyd_1d(psi[:, 64:96].ravel(), cb[16:20])
+        cb[20:24] = lloyd_1d(psi[:, 96:112].ravel(), cb[20:24])
+        cb[24:28] = lloyd_1d(psi[:, 112:120].ravel(), cb[24:28])
+    ctx.set_codebooks(cb)
+    S = ctx.preconditioner()
+    say(f"general codebooks ({which}): level-1 centroids {np.round(cb[:16], 3).tolist()}")
+    for kind in (PQ_KEY, PQ_VALUE):
+        x = make(700, 3, 991 + kind)
+        codes, radii, rec_gpu, rec_or = check_encode(ctx, S, cb, x, kind, f"{which} codebooks")
+        out = torch.empty((700, 3, 128), dtype=torch.float32, device=DEV)
+        ctx.decode_kv(kind, codes, radii, 0, 700, out, rotated=False)
+        torch.cuda.synchronize()
+        ref = oracle.decode(rec_gpu.reshape(-1, 62), S, cb).reshape(3, 700, 128)
+        assert helpers.rel_l2(out.cpu().numpy().transpose(1, 0, 2), ref) <= 1e-5
+        # append of one more token goes through the same codebooks
+        new = make(2, 3, 995 + kind)[:1].contiguous()            # [1, 3, 128]
+        ctx.append_kv(new.to(DEV), kind, codes, radii, torch.tensor([700], dtype=torch.int64, device=DEV))
+        torch.cuda.synchronize()
+        rec = canonical_both_ways(ctx, kind, codes, radii, 640, 64)[:, 700 - 640]
+        rec_o, psi_o, y_o = oracle_records(new, S, cb)
+        st, rg, ro = helpers.check_codes(rec.reshape(-1, 62), rec_o.reshape(-1, 62), psi_o.reshape(-1, 120))
+        helpers.check_radii(rg, ro, y_o.reshape(-1, 128))
+    # attention
+    lens, Hkv = [70, 900], 2
+    starts, pool = [], 0
+    for n in lens:
+        starts.append(pool)
+        pool += ((n + 63) // 64) * 64
+    kc, kr = Context.alloc_cache(Hkv, pool, DEV)
+    vc, vr = Context.alloc_cache(Hkv, pool, DEV)
+    for t in (kc, kr, vc, vr):
+        t.zero_()
+    k_rec = np.zeros((Hkv, pool, 62), dtype=np.uint8)
+    v_rec = np.zeros((Hkv, pool, 62), dtype=np.uint8)
+    for b, n in enumerate(lens):
+        k, v = make(n, Hkv, 996 + 2 * b), make(n, Hkv, 997 + 2 * b)
+        ctx.encode_kv(k.to(DEV), PQ_KEY, kc, kr, dst_token0=starts[b])
+        ctx.encode_kv(v.to(DEV), PQ_VALUE, vc, vr, dst_token0=starts[b])
+        k_rec[:, starts[b]:starts[b] + n] = oracle_records(k, S, cb)[0]
+        v_rec[:, starts[b]:starts[b] + n] = oracle_records(v, S, cb)[0]
+    torch.cuda.synchronize()
+    starts = np.array(starts, dtype=np.int64)
+    q = synth.queries(len(lens), 8, seed=998)
+    got = gpu_attention(ctx, q, (kc, kr, vc, vr), starts, lens)
+    ref = oracle.attention(q.to(torch.float64).numpy(), k_rec, v_rec, starts, np.array(lens, np.int32), S, cb,
+                           helpers.softmax_scale())
+    err = helpers.rel_l2(got, ref)
+    say(f"  {which} codebooks: attention rel L2 {err:.2e}")
+    assert err <= 2e-3
+
+
 def test_attention_rejects_bad_sequences_gracefully(env):
     ctx, S, cb = env
     say("attention with an unaligned / out-of-pool sequence")
