@@ -252,6 +252,18 @@ def attention_hybrid(q, k_rec, v_rec, seq_start, ctx_len, win_k, win_v, win_len,
     return out
 
 
+def fit_codebooks(x, S, cb_init, iterations):
+    """Online codebooks: `iterations` k-means (Lloyd) rounds on the angles of x[n,128] rotated by S,
+    from the 28 centroids cb_init -> 28 centroids."""
+    x = _f64(x).reshape(-1, D)
+    S = _f64(S)
+    cb_init = _f64(cb_init).reshape(-1)
+    assert cb_init.size == 28
+    out = np.empty(28, dtype=np.float64)
+    lib().orc_fit_codebooks(_p(x), ctypes.c_int64(x.shape[0]), _p(S), _p(cb_init), ctypes.c_int(int(iterations)), _p(out))
+    return out
+
+
 def attention_exact(q, K, V, scale):
     """Plain softmax attention on unquantised K,V[T,128] for q[G,128] (reporting only)."""
     q = _f64(q).reshape(-1, D)

@@ -646,6 +646,57 @@ void orc_attention_exact(const double *q, const double *K, const double *V,
     free(sc);
 }
 
+/* ------------------------------------------------------------------ */
+/* Online codebook (Section 4.1: 1-D k-means on the angles of the       */
+/* polar-transformed inputs; Eq. 3 with the samples in place of the     */
+/* density).  All angles of all n vectors of a level form one sample    */
+/* set; `iterations` rounds of the k-means (Lloyd) update from the      */
+/* centroids in cb_init: every angle goes to its nearest centroid       */
+/* (linear distance, lowest index on ties, as procedure Quant), every   */
+/* centroid moves to the mean of its angles; a centroid without angles  */
+/* stays.  Reading: the paper seeds with k-means++ (randomised); here   */
+/* the seed is cb_init (the analytic codebook, say), which makes the    */
+/* result a function of the data alone.                                 */
+/* ------------------------------------------------------------------ */
+void orc_fit_codebooks(const double *x, int64_t n, const double *S, const double *cb_init,
+                       int iterations, double *cb_out)
+{
+    double *psi = (double *)malloc(sizeof(double) * (size_t)n * ORC_NANG);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        double y[ORC_D], rblk[ORC_NBLK];
+        const double *xi = x + i * ORC_D;
+        for (int j = 0; j < ORC_D; ++j) {
+            double acc = 0.0;
+            for (int k = 0; k < ORC_D; ++k) acc += xi[k] * S[k * ORC_D + j];
+            y[j] = acc;
+        }
+        orc_polar(y, ORC_D, ORC_L, psi + i * ORC_NANG, rblk);
+    }
+    memcpy(cb_out, cb_init, sizeof(double) * 28);
+    int off = 0, cnt = ORC_D / 2;
+    for (int l = 1; l <= ORC_L; ++l) {
+        int K = orc_cb_K[l];
+        double *c = cb_out + orc_cb_off[l];
+        for (int it = 0; it < iterations; ++it) {
+            double sum[16];
+            int64_t num[16];
+            for (int k = 0; k < K; ++k) { sum[k] = 0.0; num[k] = 0; }
+            for (int64_t i = 0; i < n; ++i)
+                for (int j = 0; j < cnt; ++j) {
+                    double a = psi[i * ORC_NANG + off + j];
+                    int k = orc_quant(a, c, K);
+                    sum[k] += a;
+                    num[k] += 1;
+                }
+            for (int k = 0; k < K; ++k)
+                if (num[k] > 0) c[k] = sum[k] / (double)num[k];
+        }
+        off += cnt; cnt /= 2;
+    }
+    free(psi);
+}
+
 int orc_num_threads(void)
 {
 #ifdef _OPENMP

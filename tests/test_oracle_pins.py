@@ -507,6 +507,40 @@ def test_hybrid_attention_is_one_softmax_over_prefix_and_window(S, cb):
     assert np.all(none == 0.0)
 
 
+def test_online_codebook_fit_is_kmeans_on_the_angles(S, cb):
+    """Section 4.1's online codebook: k-means on the sampled angles.  Against scikit-learn's Lloyd from the
+    same start (its 1-D nearest-centroid rule is the same), the decrease of the sample distortion, the
+    convergence towards the analytic codebook on Gaussian data (where the samples follow Lemma 2's
+    densities), and zero iterations = the start."""
+    from sklearn.cluster import KMeans
+
+    x = synth.gaussian_vectors(3000, seed=81).numpy().astype(np.float64)
+    _, psi, _ = oracle.encode(x, S, cb, want_psi=True, want_y=True)
+    psi = psi.reshape(-1, 120)
+    start = cb.copy()
+    rng = np.random.default_rng(82)
+    start[:16] += rng.uniform(-0.1, 0.1, 16)
+    start[16:] += rng.uniform(-0.05, 0.05, 12)
+    assert np.array_equal(oracle.fit_codebooks(x, S, start, 0), start)
+    iters = 5
+    fit = oracle.fit_codebooks(x, S, start, iters)
+    cols = [(0, 64, 0, 16), (64, 96, 16, 20), (96, 112, 20, 24), (112, 120, 24, 28)]
+    for a0, a1, c0, c1 in cols:
+        samples = psi[:, a0:a1].reshape(-1, 1)
+        km = KMeans(n_clusters=c1 - c0, init=start[c0:c1].reshape(-1, 1), n_init=1, max_iter=iters, tol=0.0,
+                    algorithm="lloyd").fit(samples)
+        assert np.max(np.abs(np.sort(km.cluster_centers_.ravel()) - fit[c0:c1])) <= 1e-9
+
+        def distortion(c):
+            return np.mean(np.min((samples - c[None, :]) ** 2, axis=1))
+        assert distortion(fit[c0:c1]) <= distortion(start[c0:c1])
+    # many rounds on Gaussian data: close to the analytic optimum (sampling noise; on the flat level-1
+    # density Lloyd's iteration also converges slowly)
+    far = oracle.fit_codebooks(x, S, start, 40)
+    assert np.max(np.abs(far[:16] - cb[:16])) <= 0.04
+    assert np.max(np.abs(far[16:] - cb[16:])) <= 0.02
+
+
 def test_exact_attention_helper_is_plain_softmax():
     rng = np.random.default_rng(2)
     K, V = rng.standard_normal((2, 50, 128))
