@@ -109,6 +109,22 @@ pq_status pq_init_preconditioner_hadamard(pq_ctx **out, int d, uint64_t seed);
  * the analytic ones (level 1 no longer has equal cells). */
 pq_status pq_set_codebooks(pq_ctx *ctx, const double *cb);
 
+/* Online codebook construction (Section 4.1; line 3 of Algorithm 1 fitted to the input
+ * instead of the analytic densities): the vectors x (device, layout and strides as for
+ * pq_encode_kv, keys and values alike) are rotated with the context's S, their angles
+ * are counted on the GPU into fine per-level histograms (bin width 2 pi / 8192 at level
+ * 1, (pi/2) / 2048 above), and `iterations` k-means rounds -- nearest centroid, then
+ * centroid := mean of its cell -- run on the histograms from cb_init (host, 28
+ * centroids; NULL: the context's current codebooks).  The paper seeds k-means++ at
+ * random; a fixed seed codebook makes the result a function of the data.  cb_out
+ * (host): 28 centroids, ready for pq_set_codebooks on a fresh context.  workspace
+ * (device): pq_fit_workspace_bytes() bytes.  The call waits for the stream.
+ * PQ_EUNSUPPORTED beyond 2^26 vectors per call. */
+pq_status pq_fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
+                           int64_t ld_token, int64_t ld_head, const double *cb_init, int iterations,
+                           double *cb_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t pq_fit_workspace_bytes(void);
+
 pq_status pq_get_preconditioner(const pq_ctx *ctx, double *S_out);
 
 /* level in 1..4.  centroids: K doubles (K = 16 for level 1, 4 otherwise);
@@ -227,7 +243,7 @@ pq_status pq_decode_step_polar(const pq_ctx *ctx, const void *xk, const void *xv
 
 /* ---------------------------------------------------------------------------
  * Decode attention over a quantised prefix plus an unquantised recent window
- * (Section 5.2: the keys and values streamed in during generation are kept in
+ * (Section 5.3: the keys and values streamed in during generation are kept in
  * 16 bits, only the prompt's are quantised): one softmax over the DeQuant of
  * sequence b's ctx_len[b] cached tokens (Eq. 5) and its win_len[b] window
  * tokens, taken as given.  win_k, win_v (device): bf16 [B][Hkv][win_cap][128]

@@ -554,7 +554,7 @@ void orc_attention(const double *q, int B, int Hq, int Hkv,
 
 /* ------------------------------------------------------------------ */
 /* Attention over a quantised prefix plus an unquantised recent window  */
-/* (Section 5.2: the keys and values streamed in during generation are  */
+/* (Section 5.3: the keys and values streamed in during generation are  */
 /* kept in 16 bits, only the prompt's are quantised).  One softmax over */
 /* the concatenation: the first ctx_len[b] rows are the DeQuant of the  */
 /* cached records (Eq. 5), the next win_len[b] rows are the window's    */

@@ -45,6 +45,10 @@ def library():
     L.pq_init_preconditioner_hadamard.argtypes = [ctypes.POINTER(vp), i32, u64]
     L.pq_set_codebooks.restype = i32
     L.pq_set_codebooks.argtypes = [vp, vp]
+    L.pq_fit_codebooks.restype = i32
+    L.pq_fit_codebooks.argtypes = [vp, vp, i32, i64, i32, i64, i64, vp, i32, vp, vp, ctypes.c_size_t, vp]
+    L.pq_fit_workspace_bytes.restype = ctypes.c_size_t
+    L.pq_fit_workspace_bytes.argtypes = []
     L.pq_get_preconditioner.restype = i32
     L.pq_get_preconditioner.argtypes = [vp, vp]
     L.pq_get_codebook.restype = i32
@@ -164,6 +168,29 @@ class Context:
         if cb.size != 28:
             raise PolarQuantError("cb must hold 28 centroids")
         _check(library().pq_set_codebooks(self._h, cb.ctypes.data_as(ctypes.c_void_p)))
+
+    def fit_codebooks(self, x, iterations, cb_init=None, workspace=None):
+        """Online codebooks from x [n_tokens, n_heads, 128] (strides taken from the tensor, innermost contiguous):
+        `iterations` k-means rounds on its angles -> 28 centroids (numpy).  Waits for the stream."""
+        import torch
+
+        if x.stride(2) != 1:
+            raise PolarQuantError("innermost dimension must be contiguous")
+        nbytes = int(library().pq_fit_workspace_bytes())
+        if workspace is None:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=x.device)
+        init = None
+        if cb_init is not None:
+            init = np.ascontiguousarray(cb_init, dtype=np.float64).reshape(-1)
+            if init.size != 28:
+                raise PolarQuantError("cb_init must hold 28 centroids")
+        out = np.empty(28, dtype=np.float64)
+        _check(library().pq_fit_codebooks(
+            self._h, x.data_ptr(), _dtype_code(x), int(x.shape[0]), int(x.shape[1]), int(x.stride(0)), int(x.stride(1)),
+            init.ctypes.data_as(ctypes.c_void_p) if init is not None else None, int(iterations),
+            out.ctypes.data_as(ctypes.c_void_p), workspace.data_ptr(),
+            int(workspace.numel() * workspace.element_size()), _stream()))
+        return out
 
     # ---- host-side getters -------------------------------------------------
     def preconditioner(self):

@@ -706,7 +706,7 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
     }
 }
 
-/* ---- unquantised recent window (Section 5.2: generation-stage keys and values stay in
+/* ---- unquantised recent window (Section 5.3: generation-stage keys and values stay in
  * 16 bits): plain attention partials over bf16 rows, in the original domain.  One wavefront
  * per (sequence, kv head, chunk of 64 window tokens); lane t scores token t against the G
  * query heads of the group (q in LDS, read as broadcasts), the wavefront reduces maximum

@@ -625,6 +625,41 @@ def test_general_codebooks_encode_and_attend(which):
     assert err <= 2e-3
 
 
+@pytest.mark.parametrize("which", ["rotated", "no_rotation"])
+def test_online_codebook_fit(which):
+    """pq_fit_codebooks against the oracle's k-means on the exact angles: the GPU counts the angles into
+    fine histograms and clusters the bins, so the centroids agree to a fraction of a bin width; the fitted
+    codebooks then drive encode with bit-exact codes."""
+    base = oracle.default_codebooks()
+    if which == "rotated":
+        ctx = Context(seed=2)
+        x = synth.kv_stream(5000, 2, seed=60).permute(1, 0, 2).contiguous()          # bf16, outlier channels
+        x[4990:] *= 0.0                                                               # some all-zero vectors
+    else:
+        ctx = Context(S=np.eye(128))
+        x = synth.gaussian_vectors(2 * 3001, seed=61).reshape(3001, 2, 128).clone()   # fp32, ragged tile tail
+        x[:, :, [5, 40, 99]] *= 6.0
+    S = ctx.preconditioner()
+    iters = 6
+    say(f"online codebook fit ({which}): {x.shape[0]} tokens x {x.shape[1]} heads, {iters} rounds")
+    got = ctx.fit_codebooks(x.to(DEV), iters)
+    ref = oracle.fit_codebooks(x.reshape(-1, 128).double().numpy(), S, base, iters)
+    d1, du = np.max(np.abs(got[:16] - ref[:16])), np.max(np.abs(got[16:] - ref[16:]))
+    say(f"  max centroid difference: level 1 {d1:.2e} rad (bin 7.7e-4), levels 2-4 {du:.2e} rad (bin 7.7e-4)")
+    assert d1 <= 3e-4 and du <= 3e-4
+    if which == "no_rotation":
+        assert np.max(np.abs(got[:16] - base[:16])) > 0.005      # the data moved the level-1 codebook
+    # zero rounds give the start back; an explicit start is honoured
+    assert np.max(np.abs(ctx.fit_codebooks(x.to(DEV), 0) - base)) <= 1e-12   # the library's own analytic codebooks
+    start = base.copy(); start[16:20] += 0.01
+    assert np.array_equal(ctx.fit_codebooks(x.to(DEV), 0, cb_init=start), start)
+    # a context with the fitted codebooks encodes bit-exactly against the oracle using them
+    ctx2 = Context(S=S)
+    ctx2.set_codebooks(got)
+    xs = x[:700].contiguous()
+    check_encode(ctx2, S, got, xs, PQ_KEY, f"fitted ({which})")
+
+
 def test_attention_rejects_bad_sequences_gracefully(env):
     ctx, S, cb = env
     say("attention with an unaligned / out-of-pool sequence")

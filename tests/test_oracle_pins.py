@@ -463,7 +463,7 @@ def test_attention_degenerate_cases(S, cb):
 
 
 def test_hybrid_attention_is_one_softmax_over_prefix_and_window(S, cb):
-    """Quantised prefix + unquantised window (Section 5.2's protocol): the textbook softmax over the
+    """Quantised prefix + unquantised window (Section 5.3's protocol): the textbook softmax over the
     concatenation of the dequantised prefix rows and the window rows, from scipy; an empty window reduces
     it to Eq. 5, an empty prefix to plain attention on the window, and it equals the log-sum-exp merge of
     the two separate attentions."""
