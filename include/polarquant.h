@@ -211,7 +211,7 @@ pq_status pq_export_canonical(const pq_ctx *ctx, pq_kind kind, const uint8_t *co
  * == 0; the tile holding the last token must lie inside the pool).  The
  * query attends to all ctx_len[b] cached tokens (its own key/value are
  * appended before the call).  Query head h reads KV head h / (Hq/Hkv);
- * Hq/Hkv must be 1, 2 or 4.  ctx_len[b] == 0 gives a zero output row.
+ * Hq/Hkv must be 1, 2, 4 or 8.  ctx_len[b] == 0 gives a zero output row.
  * max_ctx (host) bounds every ctx_len[b]; it sizes the launch.
  * workspace (device): at least pq_attn_workspace_bytes(B, Hq, Hkv, max_ctx)
  * bytes, PQ_ENOMEM otherwise; contents need not be preserved between calls.
@@ -225,6 +225,24 @@ pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void *out, pq_d
                                void *hip_stream);
 
 size_t pq_attn_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ctx);
+
+/* The same for M query tokens per sequence at once (several draft tokens of a
+ * speculative step, or a chunk of a prompt): q, out (device): [B][M][Hq][128].  The
+ * M tokens are the M newest of the sequence and their keys and values are already in
+ * the cache (ctx_len counts them): query token m attends to the first
+ * ctx_len[b] - (M-1-m) cached tokens, i.e. up to and including its own (causal order,
+ * Eq. 4-5 with K_{:i}).  The keys and values are rebuilt once per kv head for all
+ * M * (Hq/Hkv) query rows, which is what makes this cheaper than M separate calls.
+ * M * (Hq/Hkv) <= 16, else PQ_EUNSUPPORTED.  workspace: pq_attn_mq_workspace_bytes. */
+pq_status pq_attn_decode_polar_mq(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
+                                  const uint8_t *k_codes, const uint16_t *k_radii,
+                                  const uint8_t *v_codes, const uint16_t *v_radii,
+                                  const int64_t *seq_start, const int32_t *ctx_len,
+                                  int B, int M, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
+                                  float softmax_scale, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+
+size_t pq_attn_mq_workspace_bytes(int B, int M, int Hq, int Hkv, int64_t max_ctx);
 
 /* One whole decode step (Algorithm 1 on the newest token of every sequence, then
  * Eq. 5 on the cache that now holds it): pq_append_kv_pair(xk, xv -> dst_token)

@@ -76,6 +76,11 @@ def library():
                                         ctypes.c_float, vp, ctypes.c_size_t, vp]
     L.pq_attn_hybrid_workspace_bytes.restype = ctypes.c_size_t
     L.pq_attn_hybrid_workspace_bytes.argtypes = [i32, i32, i32, i64, i64]
+    L.pq_attn_decode_polar_mq.restype = i32
+    L.pq_attn_decode_polar_mq.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64,
+                                          ctypes.c_float, vp, ctypes.c_size_t, vp]
+    L.pq_attn_mq_workspace_bytes.restype = ctypes.c_size_t
+    L.pq_attn_mq_workspace_bytes.argtypes = [i32, i32, i32, i32, i64]
     L.pq_attn_workspace_bytes.restype = ctypes.c_size_t
     L.pq_attn_workspace_bytes.argtypes = [i32, i32, i32, i64]
     L.pq_profile_begin.restype = i32
@@ -270,6 +275,24 @@ class Context:
     @staticmethod
     def attn_workspace_bytes(B, Hq, Hkv, max_ctx):
         return int(library().pq_attn_workspace_bytes(int(B), int(Hq), int(Hkv), int(max_ctx)))
+
+    def attn_decode_polar_mq(self, q, out, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len, max_ctx,
+                             softmax_scale, workspace):
+        """M query tokens per sequence: q, out [B, M, Hq, 128]; token m sees ctx_len - (M-1-m) cached tokens."""
+        B, M, Hq = q.shape[0], q.shape[1], q.shape[2]
+        Hkv = k_codes.shape[0]
+        if not (q.is_contiguous() and out.is_contiguous()):
+            raise PolarQuantError("q and out must be contiguous")
+        pool_tokens = k_codes.shape[1] * TILE_TOKENS
+        _check(library().pq_attn_decode_polar_mq(
+            self._h, q.data_ptr(), out.data_ptr(), _dtype_code(out), k_codes.data_ptr(), k_radii.data_ptr(),
+            v_codes.data_ptr(), v_radii.data_ptr(), seq_start.data_ptr(), ctx_len.data_ptr(), int(B), int(M), int(Hq),
+            int(Hkv), int(pool_tokens), int(max_ctx), float(softmax_scale), workspace.data_ptr(),
+            int(workspace.numel() * workspace.element_size()), _stream()))
+
+    @staticmethod
+    def attn_mq_workspace_bytes(B, M, Hq, Hkv, max_ctx):
+        return int(library().pq_attn_mq_workspace_bytes(int(B), int(M), int(Hq), int(Hkv), int(max_ctx)))
 
     def attn_decode_hybrid(self, q, out, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len, win_k, win_v, win_len,
                            max_ctx, softmax_scale, workspace):

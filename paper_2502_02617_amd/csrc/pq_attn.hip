@@ -63,17 +63,18 @@ constexpr int kT1 = 0, kT4 = 16, kTA = 32, kTB = 48, kT4B = 64, kT1F = 96;
 constexpr int kTAF = 128, kTBF = 160, kT4F = 192, kTabDwords = 208;
 
 struct AttnArgs {
-    const uint16_t *qrot; /* [B][Hq][2][128] binary16: rotated, pre-scaled q' as a leading part and its remainder */
+    const uint16_t *qrot; /* [B][M][Hq][2][128] binary16: rotated, pre-scaled q' as a leading part and its remainder */
     const uint8_t *k_codes, *v_codes;
     const uint16_t *k_radii, *v_radii;
     const int64_t *seq_start;
     const int32_t *ctx_len;
     int B, Hq, Hkv;
+    int M; /* query tokens per sequence: rows are ordered [B][M][Hq] */
     int64_t pool_tiles;
     int64_t max_ctx;
     int chunk_tiles, n_chunks;
-    float *ws_ml; /* [B][Hq][n_chunks][2] */
-    float *ws_o;  /* [B][Hq][n_chunks][128] */
+    float *ws_ml; /* [B][M][Hq][n_chunks][2] */
+    float *ws_o;  /* [B][M][Hq][n_chunks][128] */
     const PqDeviceConsts *consts;
 };
 
@@ -317,17 +318,16 @@ __device__ __forceinline__ uint32_t sel4(uint4 v, int c)
     return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w));
 }
 
-/* Scores of pass i of a 64-token tile: lane (g, n) gets s[e] = score of token
- * 16*i + 4*g + e against column n. */
+/* A operand of the scores of pass i of a 64-token tile: the rebuilt keys of tokens
+ * 16*i + m (m = lane & 15), this lane's quarter of the coordinates in four slices. */
 template <int i>
-__device__ __forceinline__ f4 score_pass(const uint32_t *tab, const KTileRaw &kcur, const H8 (&qb)[4])
+__device__ __forceinline__ void key_operand(const uint32_t *tab, const KTileRaw &kcur, H8 (&ka)[4])
 {
     const uint4 l1q = (i < 2) ? kcur.l1a : kcur.l1b;
     const uint32_t l1A = (i & 1) ? l1q.z : l1q.x, l1B = (i & 1) ? l1q.w : l1q.y;
     const GroupOffsets go = group_offsets(take24(kcur.g0, kcur.g1, kcur.g2, i));
     const uint32_t c4n = kcur.c4 >> (4 * i);
     const h2 rad = as_h2(sel4(kcur.rad, i));
-    H8 ka[4];
     const NibbleOffsets noA = nibble_offsets8(l1A), noB = nibble_offsets8(l1B);
     const uint32_t o4A = (c4n << 2) & 0xCu, o4B = c4n & 0xCu;
     const float t4Ac = lut_f(tab, kT4F, o4A), t4As = lut_f(tab, kT4F + 4, o4A);
@@ -351,19 +351,14 @@ __device__ __forceinline__ f4 score_pass(const uint32_t *tab, const KTileRaw &kc
         expand_key_half_block(radB * t4Bc, l0, ka[2].p);
         expand_key_half_block(radB * t4Bs, l1, ka[3].p);
     }
-    f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-        s4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[s].v, qb[s].v, s4, 0, 0, 0);
-    return s4;
 }
 
-/* Weighted value sum of pass i: acc_o += V(tokens 16*i + 4*g + e) * pb.  MASKED
- * zeroes the radii of slots beyond the context so that stale cache bytes there
- * cannot reach the sum. */
+/* A operands of the weighted value sum of pass i: the rebuilt values of tokens
+ * 16*i + 4*g + e, one operand per output column group c.  MASKED zeroes the radii of
+ * slots beyond the sequence's context so that stale cache bytes there cannot reach the sum. */
 template <int i, bool MASKED>
-__device__ __forceinline__ void pv_pass(const uint32_t *tab, const VTileRaw &vcur, const H8 &pb, f4 (&acc_o)[4],
-                                        int n_valid, int g, int t4b)
+__device__ __forceinline__ void value_operand(const uint32_t *tab, const VTileRaw &vcur, H8 (&va)[4],
+                                              int n_valid, int g, int t4b)
 {
     const uint4 l1q = (i < 2) ? vcur.l1a : vcur.l1b;
     const GroupOffsets go = group_offsets(take24(vcur.g0, vcur.g1, vcur.g2, i));
@@ -399,12 +394,9 @@ __device__ __forceinline__ void pv_pass(const uint32_t *tab, const VTileRaw &vcu
         expand_half_block(r1 * t4bb, l1, ve[2 * ep + 1]);
     }
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        H8 va;
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) va.p[e] = ve[e][c];
-        acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.v, pb.v, acc_o[c], 0, 0, 0);
-    }
+        for (int e = 0; e < 4; ++e) va[c].p[e] = ve[e][c];
 }
 
 /* Softmax state of a column: the exponent reference m_ref is shared by the four
@@ -412,49 +404,74 @@ __device__ __forceinline__ void pv_pass(const uint32_t *tab, const VTileRaw &vcu
  * kRefSlack, which after the first pass of a chunk is rare.  Probabilities are
  * exp2(s - m_ref + kProbShift): below 2^(kRefSlack + kProbShift), inside binary16,
  * and the partial result (m_ref, l, o) is consistent for any reference. */
-/* One pass: scores, reference check, probabilities, weighted values. */
-template <int i, bool MASKED>
+/* One pass: scores, reference check, probabilities, weighted values.  The operand
+ * columns come in NG groups of 16: a group carries four (query, head) pairs -- columns
+ * 0-7 their leading parts (pair n&3, parity (n>>2)&1), columns 8-15 the remainders -- and
+ * has its own softmax state and output accumulators; the rebuilt keys and values (the
+ * expensive part) are shared by all groups.  lim[k]: tokens of this tile that column
+ * group k's pair of this lane may see (MASKED only). */
+template <int i, bool MASKED, int NG>
 __device__ __forceinline__ void attend_pass(const uint32_t *tab, const KTileRaw &kcur, const VTileRaw &vcur,
-                                            const H8 (&qb)[4], f4 (&acc_o)[4], float &m_ref, float &l_run,
-                                            int n_valid, int g, uint32_t parity_shift, int t4b)
+                                            const H8 (&qb)[NG][4], f4 (&acc_o)[NG][4], float (&m_ref)[NG],
+                                            float (&l_run)[NG], const int (&lim)[NG], int n_valid, int g,
+                                            uint32_t parity_shift, int t4b)
 {
-    f4 s4 = score_pass<i>(tab, kcur, qb);
+    H8 pb[NG];
+    {
+        H8 ka[4];
+        key_operand<i>(tab, kcur, ka);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) /* leading part + remainder: columns n and n+8 (mod 16) of the same row of lanes */
-        s4[e] += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s4[e]), 0x128 /* row_ror:8 */, 0xF, 0xF, false));
-    if (MASKED) {
+        for (int k = 0; k < NG; ++k) {
+            f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (16 * i + 4 * g + e >= n_valid) s4[e] = -INFINITY;
+            for (int s = 0; s < 4; ++s)
+                s4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[s].v, qb[k][s].v, s4, 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) /* leading part + remainder: columns n and n+8 (mod 16) of the same row of lanes */
+                s4[e] += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s4[e]), 0x128 /* row_ror:8 */, 0xF, 0xF, false));
+            if (MASKED) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (16 * i + 4 * g + e >= lim[k]) s4[e] = -INFINITY;
+            }
+            const float pmax = fmaxf(fmaxf(fmaxf(s4[0], s4[1]), s4[2]), s4[3]);
+            if (__ballot(pmax > m_ref[k] + kRefSlack) != 0ull) { /* wave-uniform */
+                float cmax = fmaxf(pmax, __shfl_xor(pmax, 16));
+                cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
+                const float m_new = fmaxf(m_ref[k], cmax);
+                /* m_new is finite here for every column that has seen a valid token; a column
+                 * with none yet keeps -inf and contributes exact zeros below */
+                const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref[k] - m_new);
+                l_run[k] *= alpha;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc_o[k][c] *= alpha;
+                m_ref[k] = m_new;
+            }
+            const float m_sub = m_ref[k] - kProbShift;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float p = (MASKED && s4[e] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s4[e] - m_sub);
+                l_run[k] += p;
+                _Float16 ph = (_Float16)p;
+                uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, ph);
+                pb[k].w[e] = bits << parity_shift;
+            }
+        }
     }
-    const float pmax = fmaxf(fmaxf(fmaxf(s4[0], s4[1]), s4[2]), s4[3]);
-    if (__ballot(pmax > m_ref + kRefSlack) != 0ull) { /* wave-uniform */
-        float cmax = fmaxf(pmax, __shfl_xor(pmax, 16));
-        cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
-        const float m_new = fmaxf(m_ref, cmax);
-        /* m_new is finite here for every column that has seen a valid token; a column
-         * with none yet keeps -inf and contributes exact zeros below */
-        const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
-        l_run *= alpha;
+    H8 va[4];
+    value_operand<i, MASKED>(tab, vcur, va, n_valid, g, t4b);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc_o[c] *= alpha;
-        m_ref = m_new;
-    }
-    const float m_sub = m_ref - kProbShift;
-    H8 pb;
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        float p = (MASKED && s4[e] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s4[e] - m_sub);
-        l_run += p;
-        _Float16 ph = (_Float16)p;
-        uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, ph);
-        pb.w[e] = bits << parity_shift;
-    }
-    pv_pass<i, MASKED>(tab, vcur, pb, acc_o, n_valid, g, t4b);
+        for (int k = 0; k < NG; ++k)
+            acc_o[k][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[c].v, pb[k].v, acc_o[k][c], 0, 0, 0);
 }
 
-template <int G>
-__global__ __launch_bounds__(kWavesPerBlock * 64, 4) void pq_attn_partial_kernel(AttnArgs a)
+/* G query heads per kv head, M query tokens per sequence (a.M), NG column groups with
+ * M * G <= 4 * NG.  Query token m of a sequence is its (M-1-m)-th newest token and sees
+ * the cache up to and including its own key: ctx - (M-1-m) tokens. */
+template <int G, int NG>
+__global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2)) void pq_attn_partial_kernel(AttnArgs a)
 {
     __shared__ uint32_t tab[kTabDwords];
     {
@@ -499,70 +516,99 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 4) void pq_attn_partial_kernel
     const uint16_t *kr = a.k_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_RADII;
     const uint16_t *vr = a.v_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_RADII;
 
-    /* ---- q' operand: columns n < 8 = (head n&3, parity (n>>2)&1) hold the leading binary16
-     * part of q', columns n + 8 its binary16 remainder, so that q' enters the scores to
-     * ~22 bits at no extra matrix instruction; slice s = rotated coordinates 32*g + 8*s .. +8 ---- */
-    H8 qb[4];
-    {
-        const int head = n & 3;
-        const bool real = head < G;
-        const uint4 *qp = reinterpret_cast<const uint4 *>(
-            a.qrot + (((int64_t)b * a.Hq + hk * G + (real ? head : 0)) * 2 + (n >> 3)) * PQ_D + 32 * g);
+    /* ---- q' operands: in group k, columns n < 8 = (pair 4k + (n&3), parity (n>>2)&1) hold the
+     * leading binary16 part of q', columns n + 8 its binary16 remainder, so that q' enters the
+     * scores to ~22 bits at no extra matrix instruction; pair p = (query token p / G, head p % G);
+     * slice s = rotated coordinates 32*g + 8*s .. +8 ---- */
+    H8 qb[NG][4];
+    int lim_abs[NG]; /* tokens of the sequence that this lane's pair of group k may see */
 #pragma unroll
-        for (int s = 0; s < 4; ++s) qb[s].q = real ? qp[s] : make_uint4(0, 0, 0, 0);
+    for (int k = 0; k < NG; ++k) {
+        const int pair = 4 * k + (n & 3);
+        const bool real = pair < a.M * G;
+        const int m = real ? pair / G : 0, head = real ? pair % G : 0;
+        const uint4 *qp = reinterpret_cast<const uint4 *>(
+            a.qrot + ((((int64_t)b * a.M + m) * a.Hq + hk * G + head) * 2 + (n >> 3)) * PQ_D + 32 * g);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) qb[k][s].q = real ? qp[s] : make_uint4(0, 0, 0, 0);
+        lim_abs[k] = ctx - (a.M - 1 - m);
     }
     const uint32_t parity_shift = (n & 4) ? 16u : 0u;
     const int t4b = kT4B + ((n & 1) ? 4 : 0);
 
-    f4 acc_o[4];
+    f4 acc_o[NG][4];
+    float m_run[NG], l_run[NG];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) acc_o[c] = f4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
+    for (int k = 0; k < NG; ++k) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc_o[k][c] = f4{0.f, 0.f, 0.f, 0.f};
+        m_run[k] = -INFINITY;
+        l_run[k] = 0.f;
+    }
 
-    /* Tiles tile_lo .. tile_hi-1; all but possibly the last one of the sequence are full.
+    /* Tiles tile_lo .. tile_hi-1.  A tile is full when every query token sees all of its 64
+     * tokens; the tiles after that (the sequence's last one, or its last two when the M newest
+     * tokens straddle a tile boundary) are masked per pair.
      * The raw tile registers are single buffered: the next key tile is requested once the
      * last pass has scored, the next value tile once it has been consumed; the other
      * wavefronts resident on the SIMD cover the latency. */
-    const int n_full = min(tile_hi, ctx >> 6); /* tiles below this index are full */
+    const int n_full = min(tile_hi, max(ctx - (a.M - 1), 0) >> 6);
     KTileRaw kraw;
     VTileRaw vraw;
     load_k_tile(kraw, kc + (int64_t)tile_lo * PQL_CODE_BYTES, kr + (int64_t)tile_lo * PQL_RADII, lane);
     load_v_tile(vraw, vc + (int64_t)tile_lo * PQL_CODE_BYTES, vr + (int64_t)tile_lo * PQL_RADII, lane);
     int tile = tile_lo;
-    for (; tile < n_full; ++tile) {
-        attend_pass<0, false>(tab, kraw, vraw, qb, acc_o, m_run, l_run, 64, g, parity_shift, t4b);
-        attend_pass<1, false>(tab, kraw, vraw, qb, acc_o, m_run, l_run, 64, g, parity_shift, t4b);
-        attend_pass<2, false>(tab, kraw, vraw, qb, acc_o, m_run, l_run, 64, g, parity_shift, t4b);
-        attend_pass<3, false>(tab, kraw, vraw, qb, acc_o, m_run, l_run, 64, g, parity_shift, t4b);
+    {
+        int lim[NG];
+#pragma unroll
+        for (int k = 0; k < NG; ++k) lim[k] = 64;
+        for (; tile < n_full; ++tile) {
+            attend_pass<0, false, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b);
+            attend_pass<1, false, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b);
+            attend_pass<2, false, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b);
+            attend_pass<3, false, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b);
+            if (tile + 1 < tile_hi) {
+                load_k_tile(kraw, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * PQL_RADII, lane);
+                load_v_tile(vraw, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * PQL_RADII, lane);
+            }
+        }
+    }
+    for (; tile < tile_hi; ++tile) { /* the masked tiles at the end of the sequence */
+        const int nv = min(ctx - tile * 64, 64);
+        int lim[NG];
+#pragma unroll
+        for (int k = 0; k < NG; ++k) lim[k] = lim_abs[k] - tile * 64;
+        attend_pass<0, true, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b);
+        attend_pass<1, true, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b);
+        attend_pass<2, true, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b);
+        attend_pass<3, true, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b);
         if (tile + 1 < tile_hi) {
             load_k_tile(kraw, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * PQL_RADII, lane);
             load_v_tile(vraw, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * PQL_RADII, lane);
         }
     }
-    if (tile < tile_hi) { /* the partial last tile of the sequence */
-        const int nv = ctx - tile * 64;
-        attend_pass<0, true>(tab, kraw, vraw, qb, acc_o, m_run, l_run, nv, g, parity_shift, t4b);
-        attend_pass<1, true>(tab, kraw, vraw, qb, acc_o, m_run, l_run, nv, g, parity_shift, t4b);
-        attend_pass<2, true>(tab, kraw, vraw, qb, acc_o, m_run, l_run, nv, g, parity_shift, t4b);
-        attend_pass<3, true>(tab, kraw, vraw, qb, acc_o, m_run, l_run, nv, g, parity_shift, t4b);
-    }
 
     /* ---- partial results: l summed over the four token groups; o' scattered to coordinate order ---- */
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-    const int head = n & 3;
-    if (n < 8 && head < G) {
-        const int par = (n >> 2) & 1;
-        const int64_t slot = ((int64_t)b * a.Hq + hk * G + head) * a.n_chunks + chunk;
-        float *o = a.ws_o + slot * PQ_D;
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
+    for (int k = 0; k < NG; ++k) {
+        float l = l_run[k];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const int pair = 4 * k + (n & 3);
+        if (n < 8 && pair < a.M * G) {
+            const int m = pair / G, head = pair % G;
+            const int par = (n >> 2) & 1;
+            const int64_t slot = ((((int64_t)b * a.M + m) * a.Hq + hk * G + head)) * a.n_chunks + chunk;
+            float *o = a.ws_o + slot * PQ_D;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                o[2 * (16 * g + 4 * e + c) + par] = acc_o[c][e];
-        if (g == 0 && par == 0) {
-            a.ws_ml[slot * 2] = m_run;
-            a.ws_ml[slot * 2 + 1] = l_run;
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    o[2 * (16 * g + 4 * e + c) + par] = acc_o[k][c][e];
+            if (g == 0 && par == 0) {
+                a.ws_ml[slot * 2] = m_run[k];
+                a.ws_ml[slot * 2 + 1] = l;
+            }
         }
     }
 }
@@ -617,7 +663,7 @@ struct CombineArgs {
     const int64_t *seq_start;
     const int32_t *ctx_len;
     int64_t max_ctx, pool_tiles;
-    int Hq, n_chunks, chunk_tiles;
+    int Hq, M, n_chunks, chunk_tiles; /* rows are ordered [B][M][Hq] */
     const float *St; /* St[j*128 + i] = S[i][j] */
     void *out;       /* bf16 or f32 [B][Hq][128] */
     int out_f32;
@@ -642,8 +688,9 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
     const int row = blockIdx.x;
     MatrixSlice ms; /* requested first: its latency overlaps the reads of the partial results */
     matrix_slice_load(ms, a.St, tid);
-    const int b = row / a.Hq;
-    const int ctx = effective_ctx(a.seq_start, a.ctx_len, b, a.max_ctx, a.pool_tiles);
+    const int b = row / (a.M * a.Hq), mq = (row / a.Hq) % a.M;
+    /* query token mq sees the cache up to its own key: the sequence's context less the newer tokens */
+    const int ctx = max(effective_ctx(a.seq_start, a.ctx_len, b, a.max_ctx, a.pool_tiles) - (a.M - 1 - mq), 0);
     const int n_tiles = (ctx + 63) >> 6;
     const int used = min((n_tiles + a.chunk_tiles - 1) / a.chunk_tiles, a.n_chunks);
     const float *ml = a.ws_ml + (int64_t)row * a.n_chunks * 2;
@@ -843,7 +890,7 @@ struct Plan {
     size_t off_wml, off_wo;
 };
 
-Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap = 0)
+Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap = 0, int M = 1)
 {
     Plan p;
     int64_t max_tiles = (max_ctx + 63) / 64;
@@ -864,7 +911,7 @@ Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap = 0)
     if (ct > max_tiles) ct = max_tiles;
     p.chunk_tiles = (int)ct;
     p.n_chunks = (int)((max_tiles + ct - 1) / ct);
-    size_t rows = (size_t)B * Hq;
+    size_t rows = (size_t)B * M * Hq;
     p.off_ml = (rows * 2 * PQ_D * sizeof(uint16_t) + 255) & ~(size_t)255;
     p.off_o = (p.off_ml + rows * p.n_chunks * 2 * sizeof(float) + 255) & ~(size_t)255;
     p.total = p.off_o + rows * p.n_chunks * PQ_D * sizeof(float);
@@ -883,6 +930,12 @@ extern "C" size_t pq_attn_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ct
 {
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || max_ctx < 0) return 0;
     return make_plan(B, Hq, Hkv, max_ctx).total;
+}
+
+extern "C" size_t pq_attn_mq_workspace_bytes(int B, int M, int Hq, int Hkv, int64_t max_ctx)
+{
+    if (B <= 0 || M <= 0 || Hq <= 0 || Hkv <= 0 || max_ctx < 0) return 0;
+    return make_plan(B, Hq, Hkv, max_ctx, 0, M).total;
 }
 
 extern "C" size_t pq_attn_hybrid_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap)
@@ -908,8 +961,16 @@ struct StepWindow {
     int64_t win_cap;
 };
 
-pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const StepWindow *win, const void *q, void *out,
-                             pq_dtype out_dtype,
+template <int G>
+void launch_partial(int NG, dim3 grid, dim3 blk, hipStream_t s, const AttnArgs &aa)
+{
+    if (NG == 1) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 1>), grid, blk, 0, s, aa);
+    else if (NG == 2) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 2>), grid, blk, 0, s, aa);
+    else hipLaunchKernelGGL((pq_attn_partial_kernel<G, 4>), grid, blk, 0, s, aa);
+}
+
+pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const StepWindow *win, int M, const void *q,
+                             void *out, pq_dtype out_dtype,
                              uint8_t *k_codes, uint16_t *k_radii, uint8_t *v_codes, uint16_t *v_radii,
                              const int64_t *seq_start, const int32_t *ctx_len,
                              int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
@@ -922,7 +983,10 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     if (Hq % Hkv) return PQ_EINVAL;
     if (out_dtype != PQ_BF16 && out_dtype != PQ_F32) return PQ_EINVAL;
     const int G = Hq / Hkv;
-    if (G != 1 && G != 2 && G != 4) return PQ_EUNSUPPORTED;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return PQ_EUNSUPPORTED;
+    if (M < 1 || M * G > 16) return PQ_EUNSUPPORTED;   /* at most 16 (query token, head) pairs per kv head */
+    if ((app || win) && (M != 1 || G == 8)) return PQ_EUNSUPPORTED;
+    const int NG = M * G <= 4 ? 1 : (M * G <= 8 ? 2 : 4);
     if (!pq_aligned16(q) || !pq_aligned16(out) || !pq_aligned16(k_codes) || !pq_aligned16(k_radii) ||
         !pq_aligned16(v_codes) || !pq_aligned16(v_radii) || !pq_aligned16(workspace))
         return PQ_EALIGN;
@@ -937,7 +1001,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
         if (win->win_cap <= 0 || win->win_cap > 0x7FFFFFFF) return PQ_EINVAL;
         if (!pq_aligned16(win->win_k) || !pq_aligned16(win->win_v)) return PQ_EALIGN;
     }
-    const Plan p = make_plan(B, Hq, Hkv, max_ctx, win ? win->win_cap : 0);
+    const Plan p = make_plan(B, Hq, Hkv, max_ctx, win ? win->win_cap : 0, M);
     if ((int64_t)B * Hkv * p.n_wchunks > 0x7FFFFFFF) return PQ_EINVAL;
     if (workspace_bytes < p.total) return PQ_ENOMEM;
     const PqDeviceState *ds = nullptr;
@@ -948,7 +1012,8 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     uint16_t *qrot = reinterpret_cast<uint16_t *>(ws);
     float *ws_ml = reinterpret_cast<float *>(ws + p.off_ml);
     float *ws_o = reinterpret_cast<float *>(ws + p.off_o);
-    const int rows = B * Hq;
+    if ((int64_t)B * M * Hq > 0x7FFFFFFF) return PQ_EINVAL;
+    const int rows = B * M * Hq;
 
     if (win) {
         WindowArgs wa{static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(win->win_k),
@@ -977,7 +1042,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     aa.qrot = qrot;
     aa.k_codes = k_codes; aa.v_codes = v_codes; aa.k_radii = k_radii; aa.v_radii = v_radii;
     aa.seq_start = seq_start; aa.ctx_len = ctx_len;
-    aa.B = B; aa.Hq = Hq; aa.Hkv = Hkv;
+    aa.B = B; aa.Hq = Hq; aa.Hkv = Hkv; aa.M = M;
     aa.pool_tiles = pool_tokens / 64;
     aa.max_ctx = max_ctx;
     aa.chunk_tiles = p.chunk_tiles; aa.n_chunks = p.n_chunks;
@@ -987,12 +1052,13 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     const unsigned blocks = (unsigned)((items + kWavesPerBlock - 1) / kWavesPerBlock);
     pq_prof_before(0, s);
     const dim3 grid(blocks), blk(kWavesPerBlock * 64);
-    if (G == 4) hipLaunchKernelGGL(pq_attn_partial_kernel<4>, grid, blk, 0, s, aa);
-    else if (G == 2) hipLaunchKernelGGL(pq_attn_partial_kernel<2>, grid, blk, 0, s, aa);
-    else hipLaunchKernelGGL(pq_attn_partial_kernel<1>, grid, blk, 0, s, aa);
+    if (G == 8) launch_partial<8>(NG, grid, blk, s, aa);
+    else if (G == 4) launch_partial<4>(NG, grid, blk, s, aa);
+    else if (G == 2) launch_partial<2>(NG, grid, blk, s, aa);
+    else launch_partial<1>(NG, grid, blk, s, aa);
     pq_prof_after(0, s);
 
-    CombineArgs ca{ws_ml, ws_o, seq_start, ctx_len, max_ctx, pool_tokens / 64, Hq, p.n_chunks, p.chunk_tiles,
+    CombineArgs ca{ws_ml, ws_o, seq_start, ctx_len, max_ctx, pool_tokens / 64, Hq, M, p.n_chunks, p.chunk_tiles,
                    ds->St_f32, out, out_dtype == PQ_F32 ? 1 : 0, ds->consts,
                    reinterpret_cast<const float *>(ws + p.off_wml), reinterpret_cast<const float *>(ws + p.off_wo),
                    win ? win->win_len : nullptr, p.n_wchunks, win ? (int)win->win_cap : 0};
@@ -1013,7 +1079,7 @@ extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void
                                           void *hip_stream)
 {
     /* the caches are only read on this path */
-    return attention_launches(ctx, nullptr, nullptr, q, out, out_dtype, const_cast<uint8_t *>(k_codes),
+    return attention_launches(ctx, nullptr, nullptr, 1, q, out, out_dtype, const_cast<uint8_t *>(k_codes),
                               const_cast<uint16_t *>(k_radii), const_cast<uint8_t *>(v_codes),
                               const_cast<uint16_t *>(v_radii), seq_start, ctx_len, B, Hq, Hkv, pool_tokens, max_ctx,
                               softmax_scale, workspace, workspace_bytes, hip_stream);
@@ -1028,7 +1094,7 @@ extern "C" pq_status pq_decode_step_polar(const pq_ctx *ctx, const void *xk, con
                                           void *hip_stream)
 {
     const StepAppend app{xk, xv, xt, dst_token, Hkv};
-    return attention_launches(ctx, &app, nullptr, q, out, out_dtype, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len,
+    return attention_launches(ctx, &app, nullptr, 1, q, out, out_dtype, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len,
                               B, Hq, Hkv, pool_tokens, max_ctx, softmax_scale, workspace, workspace_bytes, hip_stream);
 }
 
@@ -1042,7 +1108,21 @@ extern "C" pq_status pq_attn_decode_hybrid(const pq_ctx *ctx, const void *q, voi
                                            size_t workspace_bytes, void *hip_stream)
 {
     const StepWindow win{win_k, win_v, win_len, win_cap};
-    return attention_launches(ctx, nullptr, &win, q, out, out_dtype, const_cast<uint8_t *>(k_codes),
+    return attention_launches(ctx, nullptr, &win, 1, q, out, out_dtype, const_cast<uint8_t *>(k_codes),
+                              const_cast<uint16_t *>(k_radii), const_cast<uint8_t *>(v_codes),
+                              const_cast<uint16_t *>(v_radii), seq_start, ctx_len, B, Hq, Hkv, pool_tokens, max_ctx,
+                              softmax_scale, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" pq_status pq_attn_decode_polar_mq(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
+                                             const uint8_t *k_codes, const uint16_t *k_radii,
+                                             const uint8_t *v_codes, const uint16_t *v_radii,
+                                             const int64_t *seq_start, const int32_t *ctx_len,
+                                             int B, int M, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
+                                             float softmax_scale, void *workspace, size_t workspace_bytes,
+                                             void *hip_stream)
+{
+    return attention_launches(ctx, nullptr, nullptr, M, q, out, out_dtype, const_cast<uint8_t *>(k_codes),
                               const_cast<uint16_t *>(k_radii), const_cast<uint8_t *>(v_codes),
                               const_cast<uint16_t *>(v_radii), seq_start, ctx_len, B, Hq, Hkv, pool_tokens, max_ctx,
                               softmax_scale, workspace, workspace_bytes, hip_stream);

@@ -76,7 +76,7 @@ def test_unsupported_dimension_and_null_arguments():
     assert L.pq_encode_kv(c._h, ctypes.c_void_p(0x1004), 1, 0, 1, 1, 128, 128, fake, fake, 64, 0, None) == -3
     assert L.pq_encode_kv(c._h, fake, 1, 0, 1, 1, 129, 128, fake, fake, 64, 0, None) == -3     # stride not 16-byte multiple
     assert L.pq_attn_decode_polar(c._h, fake, fake, 1, fake, fake, fake, fake, fake, fake, 1, 6, 4, 64, 64, 1.0, fake, 0, None) == -1  # Hq % Hkv
-    assert L.pq_attn_decode_polar(c._h, fake, fake, 1, fake, fake, fake, fake, fake, fake, 1, 8, 1, 64, 64, 1.0, fake, 0, None) == -2  # group of 8
+    assert L.pq_attn_decode_polar(c._h, fake, fake, 1, fake, fake, fake, fake, fake, fake, 1, 16, 1, 64, 64, 1.0, fake, 0, None) == -2  # group of 16
     assert L.pq_attn_decode_polar(c._h, fake, fake, 1, fake, fake, fake, fake, fake, fake, 1, 4, 1, 64, 64, 1.0, fake, 16, None) == -5  # workspace too small
     assert "PQ_EALIGN" in binding.pq_status_string(-3)
 

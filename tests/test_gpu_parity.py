@@ -262,8 +262,18 @@ def build_cache(ctx, S, cb, lens, Hkv, seed, want_oracle=True):
         ctx.encode_kv(k.to(DEV), PQ_KEY, kc, kr, dst_token0=starts[b])
         ctx.encode_kv(v.to(DEV), PQ_VALUE, vc, vr, dst_token0=starts[b])
         if want_oracle:
-            k_rec[:, starts[b] : starts[b] + n] = oracle_records(k, S, cb)[0]
-            v_rec[:, starts[b] : starts[b] + n] = oracle_records(v, S, cb)[0]
+            for kind, x, codes, radii, rec in ((PQ_KEY, k, kc, kr, k_rec), (PQ_VALUE, v, vc, vr, v_rec)):
+                rec_or, psi, y = oracle_records(x, S, cb)
+                # An angle within 1e-5 rad of a cell boundary may be coded either way: the attention
+                # results are compared on records that agree on those ties.  The encoder's own records
+                # are first held to the acceptance rule for codes and radii (every difference is such a
+                # tie, at the permitted rate); then the oracle's records take its choice of cell there.
+                # Radii stay the oracle's.
+                rec_gpu = canonical_both_ways(ctx, kind, codes, radii, starts[b], n)
+                _, rg, ro = helpers.check_codes(rec_gpu.reshape(-1, 62), rec_or.reshape(-1, 62), psi.reshape(-1, 120))
+                helpers.check_radii(rg, ro, y.reshape(-1, 128))
+                rec_or[:, :, :46] = rec_gpu[:, :, :46]
+                rec[:, starts[b] : starts[b] + n] = rec_or
     torch.cuda.synchronize()
     return (kc, kr, vc, vr), np.array(starts, dtype=np.int64), pool, k_rec, v_rec
 
@@ -658,6 +668,43 @@ def test_online_codebook_fit(which):
     ctx2.set_codebooks(got)
     xs = x[:700].contiguous()
     check_encode(ctx2, S, got, xs, PQ_KEY, f"fitted ({which})")
+
+
+@pytest.mark.parametrize("M,Hq,Hkv", [(2, 8, 2), (4, 4, 1), (3, 2, 2), (16, 1, 1), (1, 16, 2), (2, 16, 2)])
+def test_multi_query_attention(env, M, Hq, Hkv):
+    """M query tokens per sequence (and 8 query heads per kv head): row (b, m) equals single-query attention
+    over the first ctx_len - (M-1-m) cached tokens -- the oracle is called once per m with that length."""
+    ctx, S, cb = env
+    lens = [M, 64, 65 + M, 130, 1000, 64 * 5 + 1]      # tile boundaries inside the M newest tokens
+    say(f"multi-query attention M={M} Hq={Hq} Hkv={Hkv} lens={lens}")
+    B = len(lens)
+    caches, starts, pool, k_rec, v_rec = build_cache(ctx, S, cb, lens, Hkv, seed=1100 + M)
+    kc, kr, vc, vr = caches
+    q = synth.queries(B * M, Hq, seed=1101).reshape(B, M, Hq, 128).contiguous()
+    out = torch.full((B, M, Hq, 128), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(Context.attn_mq_workspace_bytes(B, M, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)
+    ctx.attn_decode_polar_mq(q.to(DEV), out, kc, kr, vc, vr, torch.from_numpy(starts).to(DEV),
+                             torch.tensor(lens, dtype=torch.int32, device=DEV), max(lens), helpers.softmax_scale(), ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    errs = []
+    for m in range(M):
+        lens_m = np.array([max(n - (M - 1 - m), 0) for n in lens], dtype=np.int32)
+        ref = oracle.attention(q[:, m].to(torch.float64).numpy(), k_rec, v_rec, starts, lens_m, S, cb,
+                               helpers.softmax_scale())
+        errs.append(helpers.rel_l2(got[:, m], ref))
+        for b in range(B):
+            if lens_m[b] == 0:
+                assert np.all(got[b, m] == 0.0)
+            else:
+                assert helpers.rel_l2(got[b, m], ref[b]) <= 2e-3, (b, m)
+    say(f"  rel L2 per query token {['%.1e' % e for e in errs]}")
+    assert max(errs) <= 2e-3
+    if M == 1:   # the multi-query entry point with one token is the plain one
+        plain = gpu_attention(ctx, q[:, 0], caches, starts, lens)
+        assert np.array_equal(plain, out[:, 0].cpu().numpy())
 
 
 def test_attention_rejects_bad_sequences_gracefully(env):
