@@ -199,6 +199,30 @@ def main():
     hybrid_ms = 1e3 * (time.perf_counter() - t0) / args.steps
     hybrid_bytes = step_bytes + 2 * 2 * D * B * HKV * WIN   # + bf16 keys and values of the window
 
+    # ---- multi-query line: M newest tokens of every sequence query the same cache in one pass
+    # (pq_attn_decode_polar_mq); the packed tile is expanded once for all M * (Hq/Hkv) columns
+    mq = {}
+    for M in (2, 4):
+        q_m = synth.queries(B * M, HQ, seed=13, device=dev).reshape(B, M, HQ, D).contiguous()
+        out_m = torch.empty((B, M, HQ, D), dtype=torch.bfloat16, device=dev)
+        ws_m = torch.empty(Context.attn_mq_workspace_bytes(B, M, HQ, HKV, CTX), dtype=torch.uint8, device=dev)
+
+        def mq_step(i):
+            kc_, kr_, vc_, vr_ = caches[i % N_CACHES]
+            ctx.attn_decode_polar_mq(q_m, out_m, kc_, kr_, vc_, vr_, seq_start, ctx_len, CTX, scale, ws_m)
+
+        for i in range(args.warmup):
+            mq_step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            mq_step(i)
+        torch.cuda.synchronize()
+        mq_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        mq[f"M={M}"] = {"ms_per_step": round(mq_ms, 4), "ms_per_query_token": round(mq_ms / M, 4),
+                        "gb_per_s": round(step_bytes / (mq_ms * 1e-3) / 1e9, 1)}
+        del q_m, out_m, ws_m
+
     result = {
         "metric": "decode attn HBM GB/s on polar-quantized KV @32k ctx",
         "value": round(value, 1),
@@ -259,6 +283,11 @@ def main():
             "ms_per_step": round(hybrid_ms, 4),
             "gb_per_s": round(hybrid_bytes / (hybrid_ms * 1e-3) / 1e9, 1),
             "algorithmic_bytes_per_step": hybrid_bytes,
+        },
+        "multi_query": {
+            "workload": "configs[2] cache, M query tokens per sequence under the causal mask, pq_attn_decode_polar_mq "
+                        "(attention only); gb_per_s counts the packed cache once per step",
+            **mq,
         },
         "setup_s": round(t_setup, 1),
     }
