@@ -272,3 +272,96 @@ def attention_exact(q, K, V, scale):
     out = np.empty_like(q)
     lib().orc_attention_exact(_p(q), _p(K), _p(V), ctypes.c_int64(K.shape[0]), ctypes.c_int(q.shape[0]), ctypes.c_double(scale), _p(out))
     return out
+
+
+# ---- full-depth recursion (L = 7): one radius per vector, 50-byte records ----
+REC_DEEP = 50
+NANG_DEEP = 127
+
+
+def _bits(bits):
+    b = np.ascontiguousarray(bits, dtype=np.int32).reshape(-1)
+    assert b.size == 3
+    return b
+
+
+def upper_codebooks(bits):
+    """Lloyd-Max codebooks of levels 5, 6, 7 with 2^bits[l-5] centroids: array [3, 8] (unused entries 0)."""
+    b = _bits(bits)
+    cbt = np.zeros((3, 8), dtype=np.float64)
+    rc = lib().orc_upper_codebooks(_p(b, ctypes.c_int32), _p(cbt))
+    assert rc == 0, "bits must be 1..3 each with 4 b5 + 2 b6 + b7 <= 16"
+    return cbt
+
+
+def unpack_deep(rec, bits):
+    rec = np.ascontiguousarray(rec, dtype=np.uint8).reshape(-1, REC_DEEP)
+    b = _bits(bits)
+    n = rec.shape[0]
+    J = np.empty((n, NANG_DEEP), dtype=np.int32)
+    rad = np.empty(n, dtype=np.uint16)
+    lib().orc_unpack_deep(_p(rec, ctypes.c_uint8), ctypes.c_int64(n), _p(b, ctypes.c_int32), _p(J, ctypes.c_int32),
+                          _p(rad, ctypes.c_uint16))
+    return J, rad
+
+
+def encode_deep(x, S, cb, bits, cbt, want_psi=False, want_y=False):
+    """x[n,128] -> deep records [n,50] (+ the 127 exact angles / rotated vectors)."""
+    x = _f64(x).reshape(-1, D)
+    S = _f64(S)
+    cb = _f64(cb)
+    b = _bits(bits)
+    cbt = _f64(cbt).reshape(3, 8)
+    n = x.shape[0]
+    rec = np.empty((n, REC_DEEP), dtype=np.uint8)
+    psi = np.empty((n, NANG_DEEP), dtype=np.float64) if want_psi else None
+    y = np.empty((n, D), dtype=np.float64) if want_y else None
+    lib().orc_encode_deep(
+        _p(x), ctypes.c_int64(n), _p(S), _p(cb), _p(b, ctypes.c_int32), _p(cbt), _p(rec, ctypes.c_uint8),
+        _p(psi) if want_psi else None, _p(y) if want_y else None,
+    )
+    out = [rec]
+    if want_psi:
+        out.append(psi)
+    if want_y:
+        out.append(y)
+    return out[0] if len(out) == 1 else tuple(out)
+
+
+def decode_deep(rec, S, cb, bits, cbt, rotated=False):
+    rec = np.ascontiguousarray(rec, dtype=np.uint8).reshape(-1, REC_DEEP)
+    S = _f64(S)
+    cb = _f64(cb)
+    b = _bits(bits)
+    cbt = _f64(cbt).reshape(3, 8)
+    n = rec.shape[0]
+    out = np.empty((n, D), dtype=np.float64)
+    lib().orc_decode_deep(_p(rec, ctypes.c_uint8), ctypes.c_int64(n), _p(S), _p(cb), _p(b, ctypes.c_int32), _p(cbt),
+                          ctypes.c_int(1 if rotated else 0), _p(out))
+    return out
+
+
+def attention_deep(q, k_rec, v_rec, seq_start, ctx_len, S, cb, bits, cbt, scale):
+    """q[B,Hq,128]; k_rec/v_rec [Hkv, plane_tokens, 50] -> out[B,Hq,128] (float64)."""
+    q = _f64(q)
+    B, Hq, _ = q.shape
+    k_rec = np.ascontiguousarray(k_rec, dtype=np.uint8)
+    v_rec = np.ascontiguousarray(v_rec, dtype=np.uint8)
+    Hkv, plane, rb = k_rec.shape
+    assert rb == REC_DEEP and v_rec.shape == k_rec.shape and Hq % Hkv == 0
+    seq_start = np.ascontiguousarray(seq_start, dtype=np.int64)
+    ctx_len = np.ascontiguousarray(ctx_len, dtype=np.int32)
+    assert seq_start.size == B and ctx_len.size == B
+    assert np.all(seq_start + ctx_len <= plane)
+    S = _f64(S)
+    cb = _f64(cb)
+    b = _bits(bits)
+    cbt = _f64(cbt).reshape(3, 8)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lib().orc_attention_deep(
+        _p(q), ctypes.c_int(B), ctypes.c_int(Hq), ctypes.c_int(Hkv),
+        _p(k_rec, ctypes.c_uint8), _p(v_rec, ctypes.c_uint8),
+        _p(seq_start, ctypes.c_int64), _p(ctx_len, ctypes.c_int32),
+        ctypes.c_int64(plane), _p(S), _p(cb), _p(b, ctypes.c_int32), _p(cbt), ctypes.c_double(scale), _p(out),
+    )
+    return out

@@ -658,6 +658,205 @@ void orc_attention_exact(const double *q, const double *K, const double *V,
 /* the seed is cb_init (the analytic codebook, say), which makes the    */
 /* result a function of the data alone.                                 */
 /* ------------------------------------------------------------------ */
+/* Full-depth recursion (Definition 1 and procedure Polar of Algorithm */
+/* 1 run to level log2 d = 7; Section 4's memory count: one radius per */
+/* vector plus the angle codes).  Levels 1..4 keep Section 4.1's bit   */
+/* widths and codebooks; levels 5, 6, 7 -- the 4 + 2 + 1 angles that   */
+/* join the 8 block radii -- take bits[0..2] bits each (the codebook   */
+/* size of a level is free: remark after Theorem 1) and the codebooks  */
+/* cbt[3][8]: row l-5 holds the 2^bits[l-5] centroids of level l.      */
+/*                                                                     */
+/* Canonical deep record (50 bytes): bytes 0..45 as in the 62-byte     */
+/* record (levels 1..4); bytes 46..47 a 16-bit little-endian word with */
+/* the level-5 codes j = 0..3 at bits [j b5, (j+1) b5), the level-6    */
+/* codes j = 0, 1 at bits [4 b5 + j b6, ...), the level-7 code at bit  */
+/* 4 b5 + 2 b6 (unused high bits zero; 4 b5 + 2 b6 + b7 <= 16);        */
+/* bytes 48..49 the binary16 radius r^(7) = |y|, little endian.        */
+/* Pinned by: levels 1..4 identical to the depth-4 record, DeQuant of  */
+/* the record lies on the sphere of the stored radius, DeQuant equals  */
+/* the inverse transform fed with the centroids of the unpacked codes, */
+/* angle statistics of levels 5..7 against Lemma 2, predicted error.   */
+/* ------------------------------------------------------------------ */
+#define ORC_REC_DEEP 50
+#define ORC_NANG_DEEP 127    /* 64 + 32 + 16 + 8 + 4 + 2 + 1 */
+#define ORC_L_DEEP 7
+
+int orc_upper_codebooks(const int *bits, double *cbt)
+{
+    double bnd[9];
+    for (int l = 5; l <= 7; ++l) {
+        int b = bits[l - 5];
+        if (b < 1 || b > 3) return -1;
+        for (int k = 0; k < 8; ++k) cbt[(l - 5) * 8 + k] = 0.0;
+        if (orc_codebook(l, 1 << b, cbt + (l - 5) * 8, bnd)) return -1;
+    }
+    return (4 * bits[0] + 2 * bits[1] + bits[2] <= 16) ? 0 : -1;
+}
+
+/* J: the 127 codes level-major; rad: binary16 bits of r^(7) */
+static void orc_pack_record_deep(const int *J, uint16_t rad, const int *bits, uint8_t *rec)
+{
+    uint8_t base[ORC_REC];
+    uint16_t none[ORC_NBLK] = {0};
+    orc_pack_record(J, none, base);
+    memcpy(rec, base, 46);
+    unsigned word = 0;
+    int pos = 0, at = ORC_NANG;
+    for (int l = 5; l <= 7; ++l)
+        for (int j = 0; j < (ORC_D >> l); ++j) {
+            word |= (unsigned)J[at++] << pos;
+            pos += bits[l - 5];
+        }
+    rec[46] = (uint8_t)(word & 0xFF); rec[47] = (uint8_t)(word >> 8);
+    rec[48] = (uint8_t)(rad & 0xFF);  rec[49] = (uint8_t)(rad >> 8);
+}
+
+static void orc_unpack_record_deep(const uint8_t *rec, const int *bits, int *J, uint16_t *rad)
+{
+    uint8_t base[ORC_REC];
+    uint16_t none[ORC_NBLK];
+    memset(base, 0, sizeof(base));
+    memcpy(base, rec, 46);
+    orc_unpack_record(base, J, none);
+    unsigned word = (unsigned)rec[46] | ((unsigned)rec[47] << 8);
+    int pos = 0, at = ORC_NANG;
+    for (int l = 5; l <= 7; ++l)
+        for (int j = 0; j < (ORC_D >> l); ++j) {
+            J[at++] = (int)((word >> pos) & ((1u << bits[l - 5]) - 1u));
+            pos += bits[l - 5];
+        }
+    *rad = (uint16_t)(rec[48] | (rec[49] << 8));
+}
+
+void orc_unpack_deep(const uint8_t *rec, int64_t n, const int *bits, int32_t *J, uint16_t *rad)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        int tmp[ORC_NANG_DEEP];
+        orc_unpack_record_deep(rec + i * ORC_REC_DEEP, bits, tmp, rad + i);
+        for (int a = 0; a < ORC_NANG_DEEP; ++a) J[i * ORC_NANG_DEEP + a] = tmp[a];
+    }
+}
+
+/* centroid list and size of level l = 1..7 */
+static const double *orc_level_centroids(int l, const double *cb, const int *bits, const double *cbt, int *K)
+{
+    if (l <= ORC_L) { *K = orc_cb_K[l]; return cb + orc_cb_off[l]; }
+    *K = 1 << bits[l - 5];
+    return cbt + (l - 5) * 8;
+}
+
+/* Encode at full depth: y = x S, procedure Polar with L = 7, procedure Quant per level, */
+/* the one radius r^(7) rounded to binary16.  Outputs (any may be NULL): rec[n][50],     */
+/* psi_out[n][127] (exact angles, level-major), y_out[n][128].                           */
+void orc_encode_deep(const double *x, int64_t n, const double *S, const double *cb,
+                     const int *bits, const double *cbt,
+                     uint8_t *rec, double *psi_out, double *y_out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        double y[ORC_D], psi[ORC_NANG_DEEP], r7[1];
+        int J[ORC_NANG_DEEP];
+        const double *xi = x + i * ORC_D;
+        for (int j = 0; j < ORC_D; ++j) {
+            double acc = 0.0;
+            for (int k = 0; k < ORC_D; ++k) acc += xi[k] * S[k * ORC_D + j];
+            y[j] = acc;
+        }
+        orc_polar(y, ORC_D, ORC_L_DEEP, psi, r7);
+        int off = 0, cnt = ORC_D / 2;
+        for (int l = 1; l <= ORC_L_DEEP; ++l) {
+            int K;
+            const double *theta = orc_level_centroids(l, cb, bits, cbt, &K);
+            for (int j = 0; j < cnt; ++j) J[off + j] = orc_quant(psi[off + j], theta, K);
+            off += cnt; cnt /= 2;
+        }
+        if (rec) orc_pack_record_deep(J, orc_f64_to_f16(r7[0]), bits, rec + i * ORC_REC_DEEP);
+        if (psi_out) memcpy(psi_out + i * ORC_NANG_DEEP, psi, sizeof(psi));
+        if (y_out) memcpy(y_out + i * ORC_D, y, sizeof(y));
+    }
+}
+
+/* DeQuant's loops for one deep record: r^(0) in the rotated domain. */
+static void orc_dequant_rotated_one_deep(const uint8_t *rec, const double *cb, const int *bits,
+                                         const double *cbt, double *y)
+{
+    int J[ORC_NANG_DEEP];
+    uint16_t rad;
+    double psi[ORC_NANG_DEEP], r[1];
+    orc_unpack_record_deep(rec, bits, J, &rad);
+    int off = 0, cnt = ORC_D / 2;
+    for (int l = 1; l <= ORC_L_DEEP; ++l) {
+        int K;
+        const double *theta = orc_level_centroids(l, cb, bits, cbt, &K);
+        for (int j = 0; j < cnt; ++j) psi[off + j] = theta[J[off + j]];
+        off += cnt; cnt /= 2;
+    }
+    r[0] = orc_f16_to_f64(rad);
+    orc_polar_inverse(psi, r, ORC_D, ORC_L_DEEP, y);
+}
+
+void orc_decode_deep(const uint8_t *rec, int64_t n, const double *S, const double *cb,
+                     const int *bits, const double *cbt, int rotated, double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        double y[ORC_D];
+        orc_dequant_rotated_one_deep(rec + t * ORC_REC_DEEP, cb, bits, cbt, y);
+        double *o = out + t * ORC_D;
+        if (rotated) { memcpy(o, y, sizeof(y)); continue; }
+        for (int i = 0; i < ORC_D; ++i) {
+            double acc = 0.0;
+            for (int j = 0; j < ORC_D; ++j) acc += y[j] * S[i * ORC_D + j];
+            o[i] = acc;
+        }
+    }
+}
+
+/* Eq. 5 on deep records: every cached row is dequantised (including S^T), then the      */
+/* textbook two-pass softmax; layout of the arguments as in orc_attention with 50-byte   */
+/* records.                                                                              */
+void orc_attention_deep(const double *q, int B, int Hq, int Hkv,
+                        const uint8_t *k_rec, const uint8_t *v_rec,
+                        const int64_t *seq_start, const int32_t *ctx_len,
+                        int64_t plane_tokens, const double *S, const double *cb,
+                        const int *bits, const double *cbt, double scale, double *out)
+{
+    int G = Hq / Hkv;
+    for (int64_t p = 0; p < (int64_t)B * Hkv; ++p) {
+        int b = (int)(p / Hkv), hk = (int)(p % Hkv);
+        int64_t T = ctx_len[b];
+        for (int g = 0; g < G; ++g)
+            memset(out + ((int64_t)b * Hq + hk * G + g) * ORC_D, 0, sizeof(double) * ORC_D);
+        if (T <= 0) continue;
+        const uint8_t *kr = k_rec + ((int64_t)hk * plane_tokens + seq_start[b]) * ORC_REC_DEEP;
+        const uint8_t *vr = v_rec + ((int64_t)hk * plane_tokens + seq_start[b]) * ORC_REC_DEEP;
+        double *Kh = (double *)malloc(sizeof(double) * T * ORC_D);
+        double *Vh = (double *)malloc(sizeof(double) * T * ORC_D);
+        double *sc = (double *)malloc(sizeof(double) * T);
+        orc_decode_deep(kr, T, S, cb, bits, cbt, 0, Kh);
+        orc_decode_deep(vr, T, S, cb, bits, cbt, 0, Vh);
+        for (int g = 0; g < G; ++g) {
+            const double *qh = q + ((int64_t)b * Hq + hk * G + g) * ORC_D;
+            double *oh = out + ((int64_t)b * Hq + hk * G + g) * ORC_D;
+            double mx = -INFINITY;
+            for (int64_t t = 0; t < T; ++t) {
+                double s = 0.0;
+                for (int j = 0; j < ORC_D; ++j) s += Kh[t * ORC_D + j] * qh[j];
+                sc[t] = s * scale;
+                if (sc[t] > mx) mx = sc[t];
+            }
+            double den = 0.0;
+            for (int64_t t = 0; t < T; ++t) { sc[t] = exp(sc[t] - mx); den += sc[t]; }
+            for (int64_t t = 0; t < T; ++t) {
+                double w = sc[t] / den;
+                for (int j = 0; j < ORC_D; ++j) oh[j] += w * Vh[t * ORC_D + j];
+            }
+        }
+        free(Kh); free(Vh); free(sc);
+    }
+}
+
+/* ------------------------------------------------------------------ */
 void orc_fit_codebooks(const double *x, int64_t n, const double *S, const double *cb_init,
                        int iterations, double *cb_out)
 {

@@ -548,3 +548,145 @@ def test_exact_attention_helper_is_plain_softmax():
     out = oracle.attention_exact(q, K, V, 0.1)
     ref = scipy.special.softmax(q @ K.T * 0.1, axis=1) @ V
     assert np.max(np.abs(out - ref)) <= 1e-12
+
+
+# ----------------------------------------------------------------------------
+# Full-depth recursion (Definition 1 / Algorithm 1 at L = log2 d = 7; Section 4's
+# memory count b_FPN + sum of code bits), per-level codebook sizes for levels 5..7
+# ----------------------------------------------------------------------------
+DEEP_BITS = [(2, 2, 2), (3, 1, 1), (1, 3, 2)]
+
+
+@pytest.mark.parametrize("level,K", [(5, 2), (5, 4), (6, 4), (6, 8), (7, 2), (7, 4), (7, 8)])
+def test_upper_level_codebooks_are_lloyd_max(level, K):
+    c, b = oracle.codebook(level, K)
+    assert b[0] == 0.0 and abs(b[K] - np.pi / 2) <= 1e-15
+    assert np.max(np.abs(c + c[::-1] - np.pi / 2)) <= 1e-11          # density symmetric about pi/4
+    assert np.max(np.abs(b[1:K] - 0.5 * (c[:-1] + c[1:]))) <= 1e-14   # midpoint condition
+    m = 2 ** (level - 1) - 1
+    logpdf = lambda t: m * math.log(max(math.sin(2 * t), 1e-300))
+    peak = 0.0                                                        # sin(2t) <= 1: no overflow
+    for k in range(K):                                                # centroid condition, independent quadrature
+        num, _ = scipy.integrate.quad(lambda t: t * math.exp(logpdf(t) - peak), b[k], b[k + 1], epsabs=0, epsrel=1e-13, limit=200)
+        den, _ = scipy.integrate.quad(lambda t: math.exp(logpdf(t) - peak), b[k], b[k + 1], epsabs=0, epsrel=1e-13, limit=200)
+        assert abs(num / den - c[k]) <= 1e-9, (k, num / den, c[k])
+    # bin probabilities from the closed-form CDF (sin^2 psi ~ Beta(2^(l-2), 2^(l-2))) sum to one
+    a = 2.0 ** (level - 2)
+    pr = np.diff(scipy.special.betainc(a, a, np.sin(b) ** 2))
+    assert abs(pr.sum() - 1.0) <= 1e-12 and np.max(np.abs(pr - pr[::-1])) <= 1e-10
+    # the angle concentrates around pi/4 as the level rises (Lemma 1: variance O(1/d))
+    assert oracle.codebook_distortion(level, c) < oracle.codebook_distortion(level - 1, oracle.codebook(level - 1, K)[0])
+
+
+def test_upper_level_angles_follow_lemma2(S):
+    Y = synth.gaussian_vectors(4096, seed=5).numpy().astype(np.float64) @ S
+    psi = np.stack([oracle.polar(y, 7)[0] for y in Y])
+    spans = {5: (120, 124), 6: (124, 126), 7: (126, 127)}
+    for l, (a0, a1) in spans.items():
+        a = 2.0 ** (l - 2)
+        d, p = scipy.stats.kstest(psi[:, a0:a1].ravel(), lambda t: scipy.special.betainc(a, a, np.sin(t) ** 2))
+        assert p > 1e-3, (l, d, p)
+    # the first 120 angles are those of the depth-4 transform; the level-5 angles are built on its block radii
+    p4, r4 = oracle.polar(Y[0], 4)
+    assert np.array_equal(psi[0, :120], p4)
+    assert np.max(np.abs(psi[0, 120:124] - np.arctan2(r4[1::2], r4[0::2]))) <= 1e-15
+
+
+@pytest.mark.parametrize("bits", DEEP_BITS)
+def test_deep_record_structure(S, cb, X0, bits):
+    cbt = oracle.upper_codebooks(bits)
+    rec, psi, Y = oracle.encode_deep(X0[:200], S, cb, bits, cbt, want_psi=True, want_y=True)
+    assert rec.shape == (200, 50)
+    # Section 4's count: one 16-bit number plus the code bits of all levels
+    code_bits = 64 * 4 + 32 * 2 + 16 * 2 + 8 * 2 + 4 * bits[0] + 2 * bits[1] + bits[2]
+    assert code_bits + 16 <= 50 * 8 and (50 * 8 - code_bits - 16) == 16 - (4 * bits[0] + 2 * bits[1] + bits[2])
+    # levels 1..4 are the depth-4 record's (the recursion is open loop: every angle comes from exact radii)
+    assert np.array_equal(rec[:, :46], oracle.encode(X0[:200], S, cb)[:, :46])
+    J, rad = oracle.unpack_deep(rec, bits)
+    assert np.array_equal(rad, np.linalg.norm(Y, axis=1).astype(np.float16).view(np.uint16))
+    for i in range(0, 200, 7):
+        p, r = oracle.polar(Y[i], 7)
+        assert np.array_equal(p, psi[i]) and abs(r[0] - np.linalg.norm(Y[i])) <= 1e-12
+        for l, (a0, a1) in {5: (120, 124), 6: (124, 126), 7: (126, 127)}.items():
+            theta = cbt[l - 5, : 2 ** bits[l - 5]]
+            assert np.array_equal(np.argmin(np.abs(theta[None, :] - p[a0:a1, None]), axis=1), J[i, a0:a1])
+    # hand-unpacked code word of one record: little-endian 16 bits, level 5 first, lowest bits first
+    word = int(rec[3, 46]) | (int(rec[3, 47]) << 8)
+    got, pos = [], 0
+    for l, n in ((5, 4), (6, 2), (7, 1)):
+        for _ in range(n):
+            got.append((word >> pos) & ((1 << bits[l - 5]) - 1))
+            pos += bits[l - 5]
+    assert got == list(J[3, 120:]) and word >> pos == 0
+    assert int(rec[3, 48]) | (int(rec[3, 49]) << 8) == int(rad[3])
+
+
+@pytest.mark.parametrize("bits", DEEP_BITS)
+def test_deep_dequant_is_inverse_transform_of_centroids(S, cb, X0, bits):
+    cbt = oracle.upper_codebooks(bits)
+    rec = oracle.encode_deep(X0[:64], S, cb, bits, cbt)
+    J, rad = oracle.unpack_deep(rec, bits)
+    yhat = oracle.decode_deep(rec, S, cb, bits, cbt, rotated=True)
+    r = rad.view(np.float16).astype(np.float64)
+    # the whole vector lies on the sphere of the one stored radius
+    assert np.max(np.abs(np.linalg.norm(yhat, axis=1) - r)) <= 1e-12
+    # closed product form of Definition 1 (0-based): coordinate i takes cos at level l if bit l-1 of i is 0
+    tables = [cb[0:16], cb[16:20], cb[20:24], cb[24:28], cbt[0], cbt[1], cbt[2]]
+    offs = [0, 64, 96, 112, 120, 124, 126]
+    for v in (0, 17, 63):
+        for i in range(128):
+            val = r[v]
+            for l in range(1, 8):
+                ang = tables[l - 1][J[v, offs[l - 1] + (i >> l)]]
+                val *= math.cos(ang) if ((i >> (l - 1)) & 1) == 0 else math.sin(ang)
+            assert abs(val - yhat[v, i]) <= 1e-12
+    xhat = oracle.decode_deep(rec, S, cb, bits, cbt)
+    assert np.max(np.abs(xhat - yhat @ S.T)) <= 1e-12
+    # a zero vector stays zero
+    z = oracle.encode_deep(np.zeros((1, 128)), S, cb, bits, cbt)
+    assert np.all(oracle.unpack_deep(z, bits)[0] == 0) and np.all(oracle.decode_deep(z, S, cb, bits, cbt) == 0.0)
+
+
+def test_deep_reconstruction_error_matches_per_level_prediction(S, cb, X0):
+    bits = (2, 2, 2)
+    cbt = oracle.upper_codebooks(bits)
+    prod = 1.0
+    for level in range(1, 8):
+        K = oracle.CB_K[level] if level <= 4 else 2 ** bits[level - 5]
+        c, b = oracle.codebook(level, K)
+        m = 0 if level == 1 else 2 ** (level - 1) - 1
+        pdf = lambda t: math.sin(2 * t) ** m if level > 1 else 1.0
+        norm, _ = scipy.integrate.quad(pdf, b[0], b[-1], limit=200)
+        prod *= sum(scipy.integrate.quad(lambda t, k=k: math.cos(t - c[k]) * pdf(t), b[k], b[k + 1], limit=200)[0]
+                    for k in range(K)) / norm
+    predicted = math.sqrt(2 * (1 - prod))
+    xhat = oracle.decode_deep(oracle.encode_deep(X0, S, cb, bits, cbt), S, cb, bits, cbt)
+    rel = np.linalg.norm(xhat - X0) / np.linalg.norm(X0)
+    assert abs(rel - predicted) <= 0.004, (rel, predicted)
+    # 3.11 bits per coordinate instead of 3.875 for a slightly larger error than depth 4
+    assert 0.18 < rel < 0.20
+    # more bits above level 4 can only help
+    b3 = (3, 3, 3)   # 4*3 + 2*3 + 3 = 21 > 16: rejected
+    with pytest.raises(AssertionError):
+        oracle.upper_codebooks(b3)
+
+
+def test_deep_attention_is_textbook_softmax(S, cb):
+    bits = (2, 2, 2)
+    cbt = oracle.upper_codebooks(bits)
+    T, Hkv, B = 29, 2, 2
+    k = synth.kv_stream(T * B, Hkv, 31).float().numpy().astype(np.float64)
+    v = synth.kv_stream(T * B, Hkv, 32).float().numpy().astype(np.float64)
+    k_rec = oracle.encode_deep(k.reshape(-1, 128), S, cb, bits, cbt).reshape(Hkv, T * B, 50)
+    v_rec = oracle.encode_deep(v.reshape(-1, 128), S, cb, bits, cbt).reshape(Hkv, T * B, 50)
+    q = synth.queries(B, 4 * Hkv, 33).float().numpy().astype(np.float64)
+    seq_start = np.array([0, T], dtype=np.int64)
+    ctx_len = np.array([T, 0], dtype=np.int32)
+    scale = 1 / math.sqrt(128)
+    out = oracle.attention_deep(q, k_rec, v_rec, seq_start, ctx_len, S, cb, bits, cbt, scale)
+    assert np.all(out[1] == 0.0)
+    for h in range(4 * Hkv):
+        Kh = oracle.decode_deep(k_rec[h // 4, :T], S, cb, bits, cbt)
+        Vh = oracle.decode_deep(v_rec[h // 4, :T], S, cb, bits, cbt)
+        p = scipy.special.softmax(Kh @ q[0, h] * scale)
+        assert np.max(np.abs(p @ Vh - out[0, h])) <= 1e-12
