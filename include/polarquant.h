@@ -125,6 +125,34 @@ pq_status pq_fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_
                            double *cb_out, void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t pq_fit_workspace_bytes(void);
 
+/* Full-depth recursion (Definition 1 and procedure Polar of Algorithm 1 run to level
+ * log2 d = 7; memory count of Section 4: one floating-point radius per vector plus the
+ * angle codes; remark after Theorem 1: the codebook size of a level is free).
+ * depth 4 (the default) is Section 4.1's truncation.  depth 7: the recursion continues
+ * over the 8 block radii of a vector with 4 + 2 + 1 more angles (levels 5, 6, 7), coded
+ * with upper_bits[0..2] (host) bits each, 1..3, 4 b5 + 2 b6 + b7 <= 16 (PQ_EUNSUPPORTED
+ * beyond); their codebooks are the optimal quantisers of Lemma 2's densities for those
+ * levels.  Levels 1..4 keep Section 4.1's widths (4, 2, 2, 2) and the context's codebooks.
+ * A vector then takes 46 code bytes + one 32-bit word (binary16 radius and the upper
+ * codes) = 50 bytes (3.125 bits per coordinate); other depths: PQ_EUNSUPPORTED.
+ * The cache layout changes with it: the radii buffer of a cache holds
+ * pq_radii_halves_per_tile(ctx) halves per tile (512 at depth 4; 128 at depth 7: word
+ * tau of a tile = radius << 16 | upper codes, level-5 codes lowest), canonical records
+ * have pq_record_bytes(ctx) bytes (62; 50 = bytes 0..45 as before, the 16-bit code word
+ * little endian, the radius little endian).  Like pq_set_codebooks this must precede the
+ * first launch with the context (PQ_EINVAL afterwards).  At depth 7 pq_encode_kv,
+ * pq_append_kv(_pair), pq_decode_kv, pq_export_canonical, pq_attn_decode_polar and
+ * pq_decode_step_polar follow the new format (Hq/Hkv <= 4); pq_attn_decode_hybrid,
+ * pq_attn_decode_polar_mq, and pq_encode_kv on a context whose codebooks were replaced
+ * with pq_set_codebooks, return PQ_EUNSUPPORTED. */
+pq_status pq_set_recursion_depth(pq_ctx *ctx, int depth, const int *upper_bits);
+int pq_recursion_depth(const pq_ctx *ctx);
+int pq_radii_halves_per_tile(const pq_ctx *ctx);
+int pq_record_bytes(const pq_ctx *ctx);
+/* level in 5..7 of a depth-7 context (PQ_EINVAL otherwise): its bit width, 2^bits
+ * centroids, 2^bits + 1 boundaries; any output may be NULL. */
+pq_status pq_get_upper_codebook(const pq_ctx *ctx, int level, int *bits, double *centroids, double *boundaries);
+
 pq_status pq_get_preconditioner(const pq_ctx *ctx, double *S_out);
 
 /* level in 1..4.  centroids: K doubles (K = 16 for level 1, 4 otherwise);

@@ -49,6 +49,16 @@ def library():
     L.pq_fit_codebooks.argtypes = [vp, vp, i32, i64, i32, i64, i64, vp, i32, vp, vp, ctypes.c_size_t, vp]
     L.pq_fit_workspace_bytes.restype = ctypes.c_size_t
     L.pq_fit_workspace_bytes.argtypes = []
+    L.pq_set_recursion_depth.restype = i32
+    L.pq_set_recursion_depth.argtypes = [vp, i32, vp]
+    L.pq_recursion_depth.restype = i32
+    L.pq_recursion_depth.argtypes = [vp]
+    L.pq_radii_halves_per_tile.restype = i32
+    L.pq_radii_halves_per_tile.argtypes = [vp]
+    L.pq_record_bytes.restype = i32
+    L.pq_record_bytes.argtypes = [vp]
+    L.pq_get_upper_codebook.restype = i32
+    L.pq_get_upper_codebook.argtypes = [vp, i32, vp, vp, vp]
     L.pq_get_preconditioner.restype = i32
     L.pq_get_preconditioner.argtypes = [vp, vp]
     L.pq_get_codebook.restype = i32
@@ -174,6 +184,38 @@ class Context:
             raise PolarQuantError("cb must hold 28 centroids")
         _check(library().pq_set_codebooks(self._h, cb.ctypes.data_as(ctypes.c_void_p)))
 
+    def set_recursion_depth(self, depth, upper_bits=None):
+        """depth 4 (default) or 7 (full recursion: upper_bits = bits of levels 5, 6, 7); only before the first launch."""
+        bits = None
+        if upper_bits is not None:
+            bits = np.ascontiguousarray(upper_bits, dtype=np.int32).reshape(-1)
+            if bits.size != 3:
+                raise PolarQuantError("upper_bits must hold 3 widths")
+        _check(library().pq_set_recursion_depth(self._h, int(depth), bits.ctypes.data_as(ctypes.c_void_p) if bits is not None else None))
+
+    def recursion_depth(self):
+        return int(library().pq_recursion_depth(self._h))
+
+    def radii_halves_per_tile(self):
+        return int(library().pq_radii_halves_per_tile(self._h))
+
+    def record_bytes(self):
+        return int(library().pq_record_bytes(self._h))
+
+    def upper_codebook(self, level):
+        """Level 5..7 of a depth-7 context: (bits, centroids, boundaries)."""
+        bits = ctypes.c_int(0)
+        c = np.zeros(8, dtype=np.float64)
+        b = np.zeros(9, dtype=np.float64)
+        _check(library().pq_get_upper_codebook(self._h, int(level), ctypes.byref(bits), c.ctypes.data_as(ctypes.c_void_p),
+                                               b.ctypes.data_as(ctypes.c_void_p)))
+        K = 1 << bits.value
+        return bits.value, c[:K].copy(), b[: K + 1].copy()
+
+    def alloc_cache_for(self, n_heads, pool_tokens, device="cuda"):
+        """Cache buffers in this context's format (the radius plane depends on the recursion depth)."""
+        return Context.alloc_cache(n_heads, pool_tokens, device, self.radii_halves_per_tile())
+
     def fit_codebooks(self, x, iterations, cb_init=None, workspace=None):
         """Online codebooks from x [n_tokens, n_heads, 128] (strides taken from the tensor, innermost contiguous):
         `iterations` k-means rounds on its angles -> 28 centroids (numpy).  Waits for the stream."""
@@ -213,14 +255,14 @@ class Context:
 
     # ---- cache allocation helper (torch owns the memory) --------------------
     @staticmethod
-    def alloc_cache(n_heads, pool_tokens, device="cuda"):
+    def alloc_cache(n_heads, pool_tokens, device="cuda", radii_halves=TILE_RADII):
         import torch
 
         if pool_tokens % TILE_TOKENS:
             raise PolarQuantError("pool_tokens must be a multiple of 64")
         tiles = pool_tokens // TILE_TOKENS
         codes = torch.empty((n_heads, tiles, TILE_CODE_BYTES), dtype=torch.uint8, device=device)
-        radii = torch.empty((n_heads, tiles, TILE_RADII), dtype=torch.int16, device=device)
+        radii = torch.empty((n_heads, tiles, radii_halves), dtype=torch.int16, device=device)
         return codes, radii
 
     # ---- kernels -------------------------------------------------------------
@@ -267,7 +309,7 @@ class Context:
                                       int(out.stride(0)), int(out.stride(1)), 1 if rotated else 0, _stream()))
 
     def export_canonical(self, kind, codes, radii, token0, n_tokens, rec):
-        """rec: uint8 [n_heads, n_tokens, 62] contiguous."""
+        """rec: uint8 [n_heads, n_tokens, record_bytes()] contiguous (62, or 50 at depth 7)."""
         pool_tokens = codes.shape[1] * TILE_TOKENS
         _check(library().pq_export_canonical(self._h, int(kind), codes.data_ptr(), radii.data_ptr(), int(pool_tokens),
                                              int(token0), int(n_tokens), int(codes.shape[0]), rec.data_ptr(), _stream()))

@@ -60,12 +60,15 @@ constexpr float kRefSlack = 6.0f;
  * TA [128,160), TB [160,192), T4 [192,200): the low halves of all entries, then the high
  * halves (two 16-entry dword tables, one entry per bank, read with one two-address load). */
 constexpr int kT1 = 0, kT4 = 16, kTA = 32, kTB = 48, kT4B = 64, kT1F = 96;
-constexpr int kTAF = 128, kTBF = 160, kT4F = 192, kTabDwords = 208;
+constexpr int kTAF = 128, kTBF = 160, kT4F = 192;
+/* full-depth recursion: (cos, sin) pairs of the centroids of levels 5, 6, 7, eight per level */
+constexpr int kTUp = 208, kTabDwords = 256;
 
 struct AttnArgs {
     const uint16_t *qrot; /* [B][M][Hq][2][128] binary16: rotated, pre-scaled q' as a leading part and its remainder */
     const uint8_t *k_codes, *v_codes;
     const uint16_t *k_radii, *v_radii;
+    int up_b5, up_b6, up_b7; /* bits of levels 5, 6, 7 (depth 7 only) */
     const int64_t *seq_start;
     const int32_t *ctx_len;
     int B, Hq, Hkv;
@@ -268,6 +271,7 @@ struct KTileRaw {
     uint32_t g0, g1, g2;
     uint32_t c4;    /* 16 bits used */
     uint4 rad;      /* chunk i: (radius A, radius B) */
+    uint32_t top;   /* depth 7 instead of rad: radius-plane word of token `lane` */
 };
 
 struct VTileRaw {
@@ -275,8 +279,10 @@ struct VTileRaw {
     uint32_t g0, g1, g2;
     uint32_t c4;    /* slot s at bits [2s, 2s+2) */
     uint4 rad0, rad1; /* slots 0..7 | 8..15 */
+    uint32_t top;     /* depth 7 instead of rad0, rad1: radius-plane word of token `lane` */
 };
 
+template <bool DEEP>
 __device__ __forceinline__ void load_k_tile(KTileRaw &t, const uint8_t *codes, const uint16_t *radii, int lane)
 {
     t.l1a = *reinterpret_cast<const uint4 *>(codes + PQL_OFF_L1A + lane * 16);
@@ -284,9 +290,11 @@ __device__ __forceinline__ void load_k_tile(KTileRaw &t, const uint8_t *codes, c
     const uint32_t *g = reinterpret_cast<const uint32_t *>(codes + PQL_OFF_G6 + lane * 12);
     t.g0 = g[0]; t.g1 = g[1]; t.g2 = g[2];
     t.c4 = *reinterpret_cast<const uint16_t *>(codes + PQL_OFF_C4 + lane * 2);
-    t.rad = *reinterpret_cast<const uint4 *>(radii + lane * 8);
+    if (DEEP) t.top = reinterpret_cast<const uint32_t *>(radii)[lane];
+    else t.rad = *reinterpret_cast<const uint4 *>(radii + lane * 8);
 }
 
+template <bool DEEP>
 __device__ __forceinline__ void load_v_tile(VTileRaw &t, const uint8_t *codes, const uint16_t *radii, int lane)
 {
     t.l1a = *reinterpret_cast<const uint4 *>(codes + PQL_OFF_L1A + lane * 16);
@@ -294,9 +302,52 @@ __device__ __forceinline__ void load_v_tile(VTileRaw &t, const uint8_t *codes, c
     const uint32_t *g = reinterpret_cast<const uint32_t *>(codes + PQL_OFF_G6 + lane * 12);
     t.g0 = g[0]; t.g1 = g[1]; t.g2 = g[2];
     t.c4 = *reinterpret_cast<const uint32_t *>(codes + PQL_OFF_C4 + (lane >> 1) * 4);
-    const uint4 *r = reinterpret_cast<const uint4 *>(radii + (lane >> 1) * 16);
-    t.rad0 = r[0];
-    t.rad1 = r[1];
+    if (DEEP) {
+        t.top = reinterpret_cast<const uint32_t *>(radii)[lane];
+    } else {
+        const uint4 *r = reinterpret_cast<const uint4 *>(radii + (lane >> 1) * 16);
+        t.rad0 = r[0];
+        t.rad1 = r[1];
+    }
+}
+
+/* Depth 7: the block radii of a tile are not stored but rebuilt from each token's radius and its
+ * codes of levels 7, 6, 5 (DeQuant's first three steps).  Lane tau does that for token tau, all
+ * eight blocks, and leaves the results in LDS in the order in which the passes consume the stored
+ * radii of a depth-4 tile: keys as fp32 (the key path forms every product in fp32),
+ * krad[(16 gk + m) * 8 + 2 i + beta] = radius of block 2 gk + beta of token 16 i + m; values as
+ * binary16, vrad[(8 g + b) * 16 + 4 i + e] = radius of block b of token 16 i + 4 g + e. */
+struct DeepRadii {
+    float *krad;       /* [512] */
+    uint16_t *vrad;    /* [512] */
+    int b5, b6, b7;
+};
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+__device__ __forceinline__ void expand_deep_radii(const uint32_t *tab, const DeepRadii &dr, uint32_t ktop, uint32_t vtop, int lane)
+{
+    const float2 *cs = reinterpret_cast<const float2 *>(tab + kTUp);
+    float r[8];
+    pq_deep_block_radii(ktop, dr.b5, dr.b6, dr.b7, cs, r);
+    {
+        const int i = lane >> 4, m = lane & 15;
+#pragma unroll
+        for (int gk = 0; gk < 4; ++gk)
+            *reinterpret_cast<float2 *>(dr.krad + (16 * gk + m) * 8 + 2 * i) = make_float2(r[2 * gk], r[2 * gk + 1]);
+    }
+    pq_deep_block_radii(vtop, dr.b5, dr.b6, dr.b7, cs, r);
+    {
+        const int i = lane >> 4, g = (lane >> 2) & 3, e = lane & 3;
+#pragma unroll
+        for (int b = 0; b < 8; ++b)
+            dr.vrad[(8 * g + b) * 16 + 4 * i + e] = __builtin_bit_cast(uint16_t, (_Float16)r[b]);
+    }
 }
 
 /* Context length the kernels act on: the caller's value clamped to [0, max_ctx];
@@ -320,19 +371,25 @@ __device__ __forceinline__ uint32_t sel4(uint4 v, int c)
 
 /* A operand of the scores of pass i of a 64-token tile: the rebuilt keys of tokens
  * 16*i + m (m = lane & 15), this lane's quarter of the coordinates in four slices. */
-template <int i>
-__device__ __forceinline__ void key_operand(const uint32_t *tab, const KTileRaw &kcur, H8 (&ka)[4])
+template <int i, bool DEEP>
+__device__ __forceinline__ void key_operand(const uint32_t *tab, const KTileRaw &kcur, H8 (&ka)[4], const DeepRadii &dr, int lane)
 {
     const uint4 l1q = (i < 2) ? kcur.l1a : kcur.l1b;
     const uint32_t l1A = (i & 1) ? l1q.z : l1q.x, l1B = (i & 1) ? l1q.w : l1q.y;
     const GroupOffsets go = group_offsets(take24(kcur.g0, kcur.g1, kcur.g2, i));
     const uint32_t c4n = kcur.c4 >> (4 * i);
-    const h2 rad = as_h2(sel4(kcur.rad, i));
+    float radA, radB; /* radii of blocks 2gk, 2gk+1 */
+    if (DEEP) {
+        const float2 rr = *reinterpret_cast<const float2 *>(dr.krad + lane * 8 + 2 * i);
+        radA = rr.x; radB = rr.y;
+    } else {
+        const h2 rad = as_h2(sel4(kcur.rad, i)); /* binary16 */
+        radA = (float)rad.x; radB = (float)rad.y;
+    }
     const NibbleOffsets noA = nibble_offsets8(l1A), noB = nibble_offsets8(l1B);
     const uint32_t o4A = (c4n << 2) & 0xCu, o4B = c4n & 0xCu;
     const float t4Ac = lut_f(tab, kT4F, o4A), t4As = lut_f(tab, kT4F + 4, o4A);
     const float t4Bc = lut_f(tab, kT4F, o4B), t4Bs = lut_f(tab, kT4F + 4, o4B);
-    const float radA = (float)rad.x, radB = (float)rad.y; /* binary16 radii of blocks 2gk, 2gk+1 */
     {   /* block A = 2*gk: slices 0, 1 */
         KeyHalfBlockLut l0, l1;
         gather_key_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(noA),
@@ -356,19 +413,27 @@ __device__ __forceinline__ void key_operand(const uint32_t *tab, const KTileRaw 
 /* A operands of the weighted value sum of pass i: the rebuilt values of tokens
  * 16*i + 4*g + e, one operand per output column group c.  MASKED zeroes the radii of
  * slots beyond the sequence's context so that stale cache bytes there cannot reach the sum. */
-template <int i, bool MASKED>
+template <int i, bool MASKED, bool DEEP>
 __device__ __forceinline__ void value_operand(const uint32_t *tab, const VTileRaw &vcur, H8 (&va)[4],
-                                              int n_valid, int g, int t4b)
+                                              int n_valid, int g, int t4b, const DeepRadii &dr, int lane)
 {
     const uint4 l1q = (i < 2) ? vcur.l1a : vcur.l1b;
     const GroupOffsets go = group_offsets(take24(vcur.g0, vcur.g1, vcur.g2, i));
-    const uint4 rq = (i < 2) ? vcur.rad0 : vcur.rad1;
+    uint32_t rpair[2]; /* radii of tokens (0, 1) and (2, 3) of the pass */
+    if (DEEP) {
+        const uint2 rr = *reinterpret_cast<const uint2 *>(dr.vrad + (lane >> 1) * 16 + 4 * i);
+        rpair[0] = rr.x; rpair[1] = rr.y;
+    } else {
+        const uint4 rq = (i < 2) ? vcur.rad0 : vcur.rad1;
+        rpair[0] = sel4(rq, 2 * (i & 1));
+        rpair[1] = sel4(rq, 2 * (i & 1) + 1);
+    }
     const uint32_t c4x = vcur.c4 >> (8 * i); /* slots 4i..4i+3: 2 bits each */
     h2 ve[4][4]; /* [token e][pair q] */
 #pragma unroll
     for (int ep = 0; ep < 2; ++ep) { /* tokens 2ep, 2ep+1 share one L1 dword and one radius dword */
         const NibbleOffsets no = nibble_offsets(sel4(l1q, 2 * (i & 1) + ep));
-        h2 rad = as_h2(sel4(rq, 2 * (i & 1) + ep));
+        h2 rad = as_h2(rpair[ep]);
         h2 r0 = bcast_lo(rad), r1 = bcast_hi(rad);
         if (MASKED) {
             const h2 zero = h2{(_Float16)0.f, (_Float16)0.f};
@@ -410,16 +475,16 @@ __device__ __forceinline__ void value_operand(const uint32_t *tab, const VTileRa
  * has its own softmax state and output accumulators; the rebuilt keys and values (the
  * expensive part) are shared by all groups.  lim[k]: tokens of this tile that column
  * group k's pair of this lane may see (MASKED only). */
-template <int i, bool MASKED, int NG>
+template <int i, bool MASKED, int NG, bool DEEP>
 __device__ __forceinline__ void attend_pass(const uint32_t *tab, const KTileRaw &kcur, const VTileRaw &vcur,
                                             const H8 (&qb)[NG][4], f4 (&acc_o)[NG][4], float (&m_ref)[NG],
                                             float (&l_run)[NG], const int (&lim)[NG], int n_valid, int g,
-                                            uint32_t parity_shift, int t4b)
+                                            uint32_t parity_shift, int t4b, const DeepRadii &dr, int lane)
 {
     H8 pb[NG];
     {
         H8 ka[4];
-        key_operand<i>(tab, kcur, ka);
+        key_operand<i, DEEP>(tab, kcur, ka, dr, lane);
 #pragma unroll
         for (int k = 0; k < NG; ++k) {
             f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
@@ -459,7 +524,7 @@ __device__ __forceinline__ void attend_pass(const uint32_t *tab, const KTileRaw 
         }
     }
     H8 va[4];
-    value_operand<i, MASKED>(tab, vcur, va, n_valid, g, t4b);
+    value_operand<i, MASKED, DEEP>(tab, vcur, va, n_valid, g, t4b, dr, lane);
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
@@ -470,10 +535,12 @@ __device__ __forceinline__ void attend_pass(const uint32_t *tab, const KTileRaw 
 /* G query heads per kv head, M query tokens per sequence (a.M), NG column groups with
  * M * G <= 4 * NG.  Query token m of a sequence is its (M-1-m)-th newest token and sees
  * the cache up to and including its own key: ctx - (M-1-m) tokens. */
-template <int G, int NG>
+template <int G, int NG, bool DEEP>
 __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2)) void pq_attn_partial_kernel(AttnArgs a)
 {
     __shared__ uint32_t tab[kTabDwords];
+    __shared__ float sKrad[DEEP ? kWavesPerBlock : 1][DEEP ? 512 : 1];
+    __shared__ uint16_t sVrad[DEEP ? kWavesPerBlock : 1][DEEP ? 512 : 2];
     {
         const PqDeviceConsts &K = *a.consts;
         int t = threadIdx.x;
@@ -491,6 +558,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
         if (t >= 160 && t < 192) tab[t] = __float_as_uint(K.tb_f32[(t - 160) >> 4][t & 15]);
         if (t >= 192 && t < 200) tab[t] = __float_as_uint(K.t4_f32[(t - 192) >> 2][t & 3]);
         if (t >= 200 && t < 208) tab[t] = 0u;
+        if (t >= kTUp && t < kTUp + 48) tab[t] = DEEP ? __float_as_uint(K.up_cs[(t - kTUp) >> 4][((t - kTUp) >> 1) & 7][t & 1]) : 0u;
     }
     __syncthreads();
 
@@ -513,8 +581,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
     const int64_t seq_tile0 = a.seq_start[b] >> 6;
     const uint8_t *kc = a.k_codes + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_CODE_BYTES;
     const uint8_t *vc = a.v_codes + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_CODE_BYTES;
-    const uint16_t *kr = a.k_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_RADII;
-    const uint16_t *vr = a.v_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_RADII;
+    constexpr int kRadiiHalves = DEEP ? PQ_DEEP_RADII_HALVES : PQL_RADII;
+    const uint16_t *kr = a.k_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * kRadiiHalves;
+    const uint16_t *vr = a.v_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * kRadiiHalves;
+    const DeepRadii dr{sKrad[DEEP ? wave : 0], sVrad[DEEP ? wave : 0], a.up_b5, a.up_b6, a.up_b7};
 
     /* ---- q' operands: in group k, columns n < 8 = (pair 4k + (n&3), parity (n>>2)&1) hold the
      * leading binary16 part of q', columns n + 8 its binary16 remainder, so that q' enters the
@@ -555,21 +625,26 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
     const int n_full = min(tile_hi, max(ctx - (a.M - 1), 0) >> 6);
     KTileRaw kraw;
     VTileRaw vraw;
-    load_k_tile(kraw, kc + (int64_t)tile_lo * PQL_CODE_BYTES, kr + (int64_t)tile_lo * PQL_RADII, lane);
-    load_v_tile(vraw, vc + (int64_t)tile_lo * PQL_CODE_BYTES, vr + (int64_t)tile_lo * PQL_RADII, lane);
+    load_k_tile<DEEP>(kraw, kc + (int64_t)tile_lo * PQL_CODE_BYTES, kr + (int64_t)tile_lo * kRadiiHalves, lane);
+    load_v_tile<DEEP>(vraw, vc + (int64_t)tile_lo * PQL_CODE_BYTES, vr + (int64_t)tile_lo * kRadiiHalves, lane);
     int tile = tile_lo;
     {
         int lim[NG];
 #pragma unroll
         for (int k = 0; k < NG; ++k) lim[k] = 64;
         for (; tile < n_full; ++tile) {
-            attend_pass<0, false, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b);
-            attend_pass<1, false, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b);
-            attend_pass<2, false, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b);
-            attend_pass<3, false, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b);
+            if (DEEP) { /* the reads of the previous tile's radii precede these writes in program order */
+                wave_lds_fence();
+                expand_deep_radii(tab, dr, kraw.top, vraw.top, lane);
+                wave_lds_fence();
+            }
+            attend_pass<0, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
+            attend_pass<1, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
+            attend_pass<2, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
+            attend_pass<3, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
             if (tile + 1 < tile_hi) {
-                load_k_tile(kraw, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * PQL_RADII, lane);
-                load_v_tile(vraw, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * PQL_RADII, lane);
+                load_k_tile<DEEP>(kraw, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * kRadiiHalves, lane);
+                load_v_tile<DEEP>(vraw, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * kRadiiHalves, lane);
             }
         }
     }
@@ -578,13 +653,18 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
         int lim[NG];
 #pragma unroll
         for (int k = 0; k < NG; ++k) lim[k] = lim_abs[k] - tile * 64;
-        attend_pass<0, true, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b);
-        attend_pass<1, true, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b);
-        attend_pass<2, true, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b);
-        attend_pass<3, true, NG>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b);
+        if (DEEP) {
+            wave_lds_fence();
+            expand_deep_radii(tab, dr, kraw.top, vraw.top, lane);
+            wave_lds_fence();
+        }
+        attend_pass<0, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
+        attend_pass<1, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
+        attend_pass<2, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
+        attend_pass<3, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
         if (tile + 1 < tile_hi) {
-            load_k_tile(kraw, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * PQL_RADII, lane);
-            load_v_tile(vraw, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * PQL_RADII, lane);
+            load_k_tile<DEEP>(kraw, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * kRadiiHalves, lane);
+            load_v_tile<DEEP>(vraw, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * kRadiiHalves, lane);
         }
     }
 
@@ -962,11 +1042,13 @@ struct StepWindow {
 };
 
 template <int G>
-void launch_partial(int NG, dim3 grid, dim3 blk, hipStream_t s, const AttnArgs &aa)
+void launch_partial(int NG, bool deep, dim3 grid, dim3 blk, hipStream_t s, const AttnArgs &aa)
 {
-    if (NG == 1) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 1>), grid, blk, 0, s, aa);
-    else if (NG == 2) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 2>), grid, blk, 0, s, aa);
-    else hipLaunchKernelGGL((pq_attn_partial_kernel<G, 4>), grid, blk, 0, s, aa);
+    if (deep) { /* NG == 1 checked by the caller, which excludes G == 8 */
+        if constexpr (G <= 4) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 1, true>), grid, blk, 0, s, aa);
+    } else if (NG == 1) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 1, false>), grid, blk, 0, s, aa);
+    else if (NG == 2) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 2, false>), grid, blk, 0, s, aa);
+    else hipLaunchKernelGGL((pq_attn_partial_kernel<G, 4, false>), grid, blk, 0, s, aa);
 }
 
 pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const StepWindow *win, int M, const void *q,
@@ -987,6 +1069,9 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     if (M < 1 || M * G > 16) return PQ_EUNSUPPORTED;   /* at most 16 (query token, head) pairs per kv head */
     if ((app || win) && (M != 1 || G == 8)) return PQ_EUNSUPPORTED;
     const int NG = M * G <= 4 ? 1 : (M * G <= 8 ? 2 : 4);
+    const bool deep = ctx->depth == 7;
+    /* full depth: one query token, at most 4 query heads per kv head, no unquantised window */
+    if (deep && (NG != 1 || win)) return PQ_EUNSUPPORTED;
     if (!pq_aligned16(q) || !pq_aligned16(out) || !pq_aligned16(k_codes) || !pq_aligned16(k_radii) ||
         !pq_aligned16(v_codes) || !pq_aligned16(v_radii) || !pq_aligned16(workspace))
         return PQ_EALIGN;
@@ -1048,14 +1133,15 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     aa.chunk_tiles = p.chunk_tiles; aa.n_chunks = p.n_chunks;
     aa.ws_ml = ws_ml; aa.ws_o = ws_o;
     aa.consts = ds->consts;
+    aa.up_b5 = ctx->upper_bits[0]; aa.up_b6 = ctx->upper_bits[1]; aa.up_b7 = ctx->upper_bits[2];
     const int64_t items = (int64_t)B * Hkv * p.n_chunks;
     const unsigned blocks = (unsigned)((items + kWavesPerBlock - 1) / kWavesPerBlock);
     pq_prof_before(0, s);
     const dim3 grid(blocks), blk(kWavesPerBlock * 64);
-    if (G == 8) launch_partial<8>(NG, grid, blk, s, aa);
-    else if (G == 4) launch_partial<4>(NG, grid, blk, s, aa);
-    else if (G == 2) launch_partial<2>(NG, grid, blk, s, aa);
-    else launch_partial<1>(NG, grid, blk, s, aa);
+    if (G == 8) launch_partial<8>(NG, false, grid, blk, s, aa); /* deep was rejected above: NG == 2 */
+    else if (G == 4) launch_partial<4>(NG, deep, grid, blk, s, aa);
+    else if (G == 2) launch_partial<2>(NG, deep, grid, blk, s, aa);
+    else launch_partial<1>(NG, deep, grid, blk, s, aa);
     pq_prof_after(0, s);
 
     CombineArgs ca{ws_ml, ws_o, seq_start, ctx_len, max_ctx, pool_tokens / 64, Hq, M, p.n_chunks, p.chunk_tiles,

@@ -47,7 +47,22 @@ struct PqDeviceConsts {
        (p > that).  Levels 2-4 use tan_b with all three of its entries. */
     int general;
     struct Lut1Cell { float thr; uint32_t count; } lut1[512];
+    /* Full-depth recursion (depth == 7, Definition 1): levels 5, 6, 7 join the 8 block radii of a
+       vector with 4 + 2 + 1 more angles of up_bits[l-5] bits each; the vector keeps one radius.
+       up_tan2[l-5][k]: squared tangent of inner boundary k of level l (the recursion carries
+       squared radii); up_cs[l-5][c]: (cos, sin) of centroid c.  depth == 4: unused. */
+    int depth;
+    int up_bits[3];
+    float up_tan2[3][7];
+    float up_cs[3][8][2];
 };
+
+/* Radius plane of a tile.  Depth 4: 512 binary16 block radii (pq_layout.h).  Depth 7: 64 words,
+   word tau = (binary16 radius of the vector << 16) | code word of levels 5..7 (level-5 codes
+   j = 0..3 at bits [j b5, (j+1) b5), level-6 codes j = 0, 1 at 4 b5 + j b6, level 7 at
+   4 b5 + 2 b6), the same for key and value tiles. */
+#define PQ_DEEP_RADII_HALVES 128
+#define PQ_DEEP_RECORD_BYTES 50
 
 /* Per-device constant buffers of a context (created on first use). */
 struct PqDeviceState {
@@ -71,6 +86,10 @@ struct pq_ctx {
     bool general_codebooks; /* codebooks replaced by pq_set_codebooks */
     double centroids[4][16];
     double boundaries[4][17];
+    int depth;              /* 4, or 7 after pq_set_recursion_depth */
+    int upper_bits[3];      /* bits of levels 5, 6, 7 (depth 7) */
+    double upper_centroids[3][8];
+    double upper_boundaries[3][9];
     PqDeviceConsts host_consts;
     std::mutex mu;
     PqDeviceState dev[PQ_MAX_DEVICES];
@@ -122,6 +141,60 @@ static __device__ __forceinline__ float vector_times_slice(const float (&sin)[PQ
     __syncthreads();
     return ((spart[0][j] + spart[1][j]) + spart[2][j]) + spart[3][j];
 }
+
+#if defined(__HIPCC__)
+/* ---- depth 7: block radii from a tile's radius-plane word (DeQuant's levels 7, 6, 5) ----
+ * cs: the (cos, sin) pairs of the centroids, [3][8] (levels 5, 6, 7), in LDS or global memory.
+ * Products in fp32, in the order radius * level 7 * level 6 * level 5. */
+static __device__ __forceinline__ float pq_half_bits_to_float(uint32_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+}
+
+static __device__ __forceinline__ void pq_deep_block_radii(uint32_t word, int b5, int b6, int b7, const float2 *cs,
+                                                           float (&r)[8])
+{
+    const float R = pq_half_bits_to_float(word >> 16);
+    const float2 t7 = cs[16 + __builtin_amdgcn_ubfe(word, 4 * b5 + 2 * b6, b7)];
+    const float r6[2] = {R * t7.x, R * t7.y};
+    float r5[4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const float2 t6 = cs[8 + __builtin_amdgcn_ubfe(word, 4 * b5 + j * b6, b6)];
+        r5[2 * j] = r6[j] * t6.x;
+        r5[2 * j + 1] = r6[j] * t6.y;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 t5 = cs[__builtin_amdgcn_ubfe(word, j * b5, b5)];
+        r[2 * j] = r5[j] * t5.x;
+        r[2 * j + 1] = r5[j] * t5.y;
+    }
+}
+
+/* the same for one block b (same products, same order) */
+static __device__ __forceinline__ float pq_deep_block_radius(uint32_t word, int b5, int b6, int b7, const float2 *cs, int b)
+{
+    const float R = pq_half_bits_to_float(word >> 16);
+    const float2 t7 = cs[16 + __builtin_amdgcn_ubfe(word, 4 * b5 + 2 * b6, b7)];
+    const float2 t6 = cs[8 + __builtin_amdgcn_ubfe(word, 4 * b5 + (b >> 2) * b6, b6)];
+    const float2 t5 = cs[__builtin_amdgcn_ubfe(word, (b >> 1) * b5, b5)];
+    const float r6 = R * ((b & 4) ? t7.y : t7.x);
+    const float r5 = r6 * ((b & 2) ? t6.y : t6.x);
+    return r5 * ((b & 1) ? t5.y : t5.x);
+}
+
+/* Procedure Quant above level 4: the number of inner boundaries below atan(sqrt(v2 / u2)), from
+ * squared radii; boundary k is passed when v2 > tan^2(t_k) u2 (one rounding in the fused form). */
+static __device__ __forceinline__ uint32_t pq_quant_upper(float u2, float v2, const float *tan2, int n_bounds)
+{
+    uint32_t c = 0;
+#pragma unroll
+    for (int k = 0; k < 7; ++k)
+        if (k < n_bounds) c += (__builtin_fmaf(tan2[k], u2, -v2) < 0.0f) ? 1u : 0u;
+    return c;
+}
+#endif
 
 /* Layout of S_bf16x3 (halves): [term 3][row-tile 4][k-step 8][lane 64][8].
  * Lane l = 32*kg + i of (term, rt, ks) holds S_term[64*kg + 8*ks + e][col(rt, i)]

@@ -1,6 +1,8 @@
 /*
  * pq_decode.hip -- pq_decode_kv (Algorithm 1, procedure DeQuant) and
- * pq_export_canonical (tile layout -> canonical 62-byte records).
+ * pq_export_canonical (tile layout -> canonical records: 62 bytes, or 50 at
+ * full recursion depth, where the block radii are themselves rebuilt from the
+ * vector's radius and the codes of levels 7, 6, 5).
  *
  * DeQuant rebuilds each block top-down from its stored radius: at level l the
  * radius of node j splits into (r cos theta, r sin theta) with theta the
@@ -27,6 +29,7 @@ struct DecodeArgs {
     int rotated;
     const PqDeviceConsts *consts;
     const float *St; /* St[j*128 + i] = S[i][j] */
+    int deep;        /* recursion depth 7: the radius plane holds one word per token */
 };
 
 template <int KIND, int OT>
@@ -45,9 +48,14 @@ __global__ __launch_bounds__(128) void pq_decode_kernel(DecodeArgs a)
             const int64_t tile = slot >> 6;
             const int tau = (int)(slot & 63);
             const uint8_t *tc = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
-            const uint16_t *tr = a.radii + ((int64_t)head * a.pool_tiles + tile) * PQL_RADII;
-            PqBlockFields f = pql_read_block(KIND, tc, tr, tau, b);
-            float r4 = (float)__builtin_bit_cast(_Float16, f.radius);
+            const uint16_t *tr = a.radii + ((int64_t)head * a.pool_tiles + tile) * (a.deep ? PQ_DEEP_RADII_HALVES : PQL_RADII);
+            PqBlockFields f = pql_read_block(KIND, tc, a.deep ? nullptr : tr, tau, b);
+            float r4;
+            if (a.deep)
+                r4 = pq_deep_block_radius(reinterpret_cast<const uint32_t *>(tr)[tau], K.up_bits[0], K.up_bits[1], K.up_bits[2],
+                                          reinterpret_cast<const float2 *>(&K.up_cs[0][0][0]), b);
+            else
+                r4 = (float)__builtin_bit_cast(_Float16, f.radius);
             float r3[2] = {r4 * K.cs234[2][f.c4][0], r4 * K.cs234[2][f.c4][1]};
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -101,6 +109,7 @@ struct ExportArgs {
     int64_t pool_tiles;
     int64_t token0, n_tokens;
     uint8_t *rec;
+    int deep;
 };
 
 /* one thread per (token, block): writes the block's share of the canonical record */
@@ -116,9 +125,9 @@ __global__ __launch_bounds__(256) void pq_export_kernel(ExportArgs a)
     const int64_t tile = slot >> 6;
     const int tau = (int)(slot & 63);
     const uint8_t *tc = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
-    const uint16_t *tr = a.radii + ((int64_t)head * a.pool_tiles + tile) * PQL_RADII;
-    PqBlockFields f = pql_read_block(KIND, tc, tr, tau, b);
-    uint8_t *rec = a.rec + ((int64_t)head * a.n_tokens + t) * PQ_RECORD_BYTES;
+    const uint16_t *tr = a.radii + ((int64_t)head * a.pool_tiles + tile) * (a.deep ? PQ_DEEP_RADII_HALVES : PQL_RADII);
+    PqBlockFields f = pql_read_block(KIND, tc, a.deep ? nullptr : tr, tau, b);
+    uint8_t *rec = a.rec + ((int64_t)head * a.n_tokens + t) * (a.deep ? PQ_DEEP_RECORD_BYTES : PQ_RECORD_BYTES);
     /* level 1: pairs 8b..8b+7 -> bytes 4b..4b+3, earlier code in the high nibble */
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -138,8 +147,18 @@ __global__ __launch_bounds__(256) void pq_export_kernel(ExportArgs a)
     acc4 |= __shfl_xor(acc4, 1);
     acc4 |= __shfl_xor(acc4, 2);
     if ((b & 3) == 0) rec[44 + (b >> 2)] = (uint8_t)acc4;
-    rec[46 + 2 * b] = (uint8_t)(f.radius & 0xFF);
-    rec[47 + 2 * b] = (uint8_t)(f.radius >> 8);
+    if (a.deep) {
+        if (b == 0) { /* code word of levels 5..7, then the vector's radius, both little endian */
+            const uint32_t word = reinterpret_cast<const uint32_t *>(tr)[tau];
+            rec[46] = (uint8_t)(word & 0xFF);
+            rec[47] = (uint8_t)((word >> 8) & 0xFF);
+            rec[48] = (uint8_t)((word >> 16) & 0xFF);
+            rec[49] = (uint8_t)(word >> 24);
+        }
+    } else {
+        rec[46 + 2 * b] = (uint8_t)(f.radius & 0xFF);
+        rec[47 + 2 * b] = (uint8_t)(f.radius >> 8);
+    }
 }
 
 } // namespace
@@ -160,7 +179,7 @@ extern "C" pq_status pq_decode_kv(const pq_ctx *ctx, pq_kind kind, const uint8_t
     pq_status st = pq_device_state(ctx, &ds);
     if (st != PQ_OK) return st;
     DecodeArgs a{codes, radii, pool_tokens / 64, token0, n_tokens, n_heads, out, ld_token, ld_head, rotated,
-                 ds->consts, ds->St_f32};
+                 ds->consts, ds->St_f32, ctx->depth == 7 ? 1 : 0};
     dim3 grid((unsigned)((n_tokens + kTok - 1) / kTok), (unsigned)n_heads), block(128);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (kind == PQ_KEY) {
@@ -184,7 +203,7 @@ extern "C" pq_status pq_export_canonical(const pq_ctx *ctx, pq_kind kind, const 
     if (token0 + n_tokens > pool_tokens) return PQ_EINVAL;
     if (!pq_aligned16(codes) || !pq_aligned16(radii)) return PQ_EALIGN;
     if (n_tokens == 0) return PQ_OK;
-    ExportArgs a{codes, radii, pool_tokens / 64, token0, n_tokens, rec};
+    ExportArgs a{codes, radii, pool_tokens / 64, token0, n_tokens, rec, ctx->depth == 7 ? 1 : 0};
     dim3 grid((unsigned)((n_tokens * 8 + 255) / 256), (unsigned)n_heads), block(256);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (kind == PQ_KEY) hipLaunchKernelGGL((pq_export_kernel<PQ_KEY>), grid, block, 0, s, a);

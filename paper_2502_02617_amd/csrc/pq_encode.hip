@@ -35,7 +35,12 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
    wavefronts working on one 32-vector half at a time in 128 registers measured slower: every
    A-operand fetch then feeds one matrix instruction instead of two. */
 template <int XT> struct EncodeShape { static constexpr int waves = 8; };
-constexpr int kImgDwords = (PQL_CODE_BYTES + PQL_RADII * 2) / 4; /* 992 */
+/* tile image in LDS: the code bytes, then the radius plane (512 binary16 block radii, or at
+   depth 7 the 64 words of radius and upper-level codes) */
+template <bool DEEP> struct TileImage {
+    static constexpr int radii_halves = DEEP ? PQ_DEEP_RADII_HALVES : PQL_RADII;
+    static constexpr int dwords = (PQL_CODE_BYTES + radii_halves * 2) / 4; /* 992 or 800 */
+};
 
 struct EncodeArgs {
     const void *x;
@@ -92,7 +97,7 @@ __device__ __forceinline__ void put_bits(uint32_t *img, uint32_t bit, int width,
 }
 
 /* Scatter the fields of block b of slot tau into the tile image (codes, then radii). */
-template <int KIND, bool CLEAR>
+template <int KIND, bool CLEAR, bool DEEP>
 __device__ __forceinline__ void emit_block(uint32_t *img, int tau, int b, const BlockCodes &bc)
 {
     const PqBlockPos pos = pql_pos(KIND, tau, b);
@@ -108,7 +113,7 @@ __device__ __forceinline__ void emit_block(uint32_t *img, int tau, int b, const 
         put_bits<CLEAR, true>(img, pos.g6_bit[1], 6, bc.g1);
     }
     put_bits<CLEAR, false>(img, pos.c4_bit, 2, bc.c4); /* even bit offset: never straddles */
-    img16[PQL_CODE_BYTES / 2 + pos.radius_half] = bc.radius;
+    if (!DEEP) img16[PQL_CODE_BYTES / 2 + pos.radius_half] = bc.radius;
 }
 
 /* ---- full tiles: whole dwords assembled in registers, no atomics ----
@@ -147,6 +152,7 @@ __device__ __forceinline__ void emit_key_l1(uint32_t *img, int j, int H, int st,
     img[((v ? PQL_OFF_L1B : PQL_OFF_L1A) + lam * 16 + (j >> 4) * 8 + (st & 1) * 4) >> 2] = l1;
 }
 
+template <bool DEEP>
 __device__ __forceinline__ void emit_key_pair(uint32_t *img, int j, int H, int st, const KeyHeld &even,
                                               const BlockCodes (&odd)[2])
 {
@@ -155,7 +161,7 @@ __device__ __forceinline__ void emit_key_pair(uint32_t *img, int j, int H, int s
 #pragma unroll
     for (int v = 0; v < 2; ++v) {
         const int i = 2 * v + (j >> 4);
-        img[PQL_CODE_BYTES / 4 + lam * 4 + i] = even.rad[v] | ((uint32_t)odd[v].radius << 16);
+        if (!DEEP) img[PQL_CODE_BYTES / 4 + lam * 4 + i] = even.rad[v] | ((uint32_t)odd[v].radius << 16);
         const uint32_t chunk = even.g12[v] | ((odd[v].g0 | (odd[v].g1 << 6)) << 12);
         P[v] = chunk | ((even.c4[v] | (odd[v].c4 << 2)) << 24);
         Q[v] = (uint32_t)__shfl_xor((int)P[v], 16);
@@ -169,6 +175,7 @@ __device__ __forceinline__ void emit_key_pair(uint32_t *img, int j, int H, int s
 
 /* Value tile, one row tile: the 16 slots of a (token group g, block b) pair sit in the
  * quads of lanes 4g..4g+3 and 16+4g..16+4g+3, both halves v. */
+template <bool DEEP>
 __device__ __forceinline__ void emit_value_full(uint32_t *img, int j, int b, const BlockCodes (&bc)[2])
 {
     const int g = (j >> 2) & 3, e = j & 3, jhi = j >> 4;
@@ -183,7 +190,7 @@ __device__ __forceinline__ void emit_value_full(uint32_t *img, int j, int b, con
         const int l1_base = ((v ? PQL_OFF_L1B : PQL_OFF_L1A) + (4 * jhi + (e & 2)) * 2) >> 2;
         if ((e & 1) == 0) {
             img[l1_base + lam0 * 4] = (bc[v].l1 & 0xFFFFu) | (nl1 << 16);
-            img[PQL_CODE_BYTES / 4 + ((gb * 16 + s) >> 1)] = (uint32_t)bc[v].radius | (nrad << 16);
+            if (!DEEP) img[PQL_CODE_BYTES / 4 + ((gb * 16 + s) >> 1)] = (uint32_t)bc[v].radius | (nrad << 16);
         } else {
             img[l1_base + (lam0 + 1) * 4] = (nl1 >> 16) | (bc[v].l1 & 0xFFFF0000u);
         }
@@ -205,9 +212,14 @@ __device__ __forceinline__ void emit_value_full(uint32_t *img, int j, int b, con
    the common factor is taken out of the block radius (the angles do not see it). */
 /* GENERAL: codebooks set by the caller; level 1 goes through the pseudo-angle cell table (staged
    in LDS), the upper levels compare against three free boundaries. */
-template <int XT, int KIND, int NTERMS, bool GENERAL>
+/* DEEP: recursion to level 7.  The squared radii of a vector's blocks are kept as the row tiles
+   complete (a lane half holds blocks 4H..4H+3 of its vectors); levels 5 and 6 then run inside the
+   lane, level 7 joins the two halves with one lane exchange, and the vector's radius and upper
+   codes go into its word of the radius plane. */
+template <int XT, int KIND, int NTERMS, bool GENERAL, bool DEEP>
 __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(EncodeArgs a)
 {
+    constexpr int kImgDwords = TileImage<DEEP>::dwords, kRadiiHalves = TileImage<DEEP>::radii_halves;
     constexpr int kWaves = EncodeShape<XT>::waves, kThreads = kWaves * 64;
     constexpr int kSChunks = NTERMS * 4 * 8 * 64;   /* 16-byte chunks of the copy of S that is used */
     __shared__ uint4 sS[kSChunks];                  /* 32 KB per term, in A-operand order */
@@ -271,7 +283,7 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
         const int64_t tile = geo.tile;
         const bool full = (tau_lo == 0 && tau_hi == 64);
         uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
-        uint16_t *gradii = a.radii + ((int64_t)head * a.pool_tiles + tile) * PQL_RADII;
+        uint16_t *gradii = a.radii + ((int64_t)head * a.pool_tiles + tile) * kRadiiHalves;
 
         /* ---- tile image: zeros, or the tile's present contents if only part of it is written ---- */
         constexpr bool kAssembled = (XT == PQ_BF16); /* full tiles written as whole dwords from registers */
@@ -282,7 +294,7 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
             const uint32_t *gc = reinterpret_cast<const uint32_t *>(gcodes);
             const uint32_t *gr = reinterpret_cast<const uint32_t *>(gradii);
             for (int c = lane; c < PQL_CODE_BYTES / 4; c += 64) img[c] = gc[c];
-            for (int c = lane; c < PQL_RADII / 2; c += 64) img[PQL_CODE_BYTES / 4 + c] = gr[c];
+            for (int c = lane; c < kRadiiHalves / 2; c += 64) img[PQL_CODE_BYTES / 4 + c] = gr[c];
         }
         wave_lds_sync();
 
@@ -340,6 +352,7 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
                quantises. */
             f32x16 acc_even[NVT], acc_odd[NVT];
             KeyHeld held = {};
+            float q4[NVT][4]; /* DEEP: squared radii of blocks 4H .. 4H+3 */
 #pragma unroll
             for (int st = -1; st < 4; ++st) {
                 f32x16 (&cur)[NVT] = (st & 1) ? acc_odd : acc_even;   /* row tile st: quantised now */
@@ -396,6 +409,10 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
                 if (quant) {
                     /* lane (H, j): cur[v][r] = rotated coordinate 16*(4H + st) + r of vector tau[v] */
                     const int b = 4 * H + st;
+                    if (DEEP) {
+#pragma unroll
+                        for (int v = 0; v < NVT; ++v) q4[v][st < 0 ? 0 : st] = ps[v].out.q4;
+                    }
                     /* a full tile has a slot for every lane: no per-lane branch there.  (Around a
                        single vector's fields it would let the optimiser move that vector's whole
                        recursion behind the branch and undo the interleaving above.) */
@@ -413,20 +430,32 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
                                         held.rad[v] = bc[v].radius;
                                     }
                                 } else {
-                                    emit_key_pair(img, j, H, st, held, bc);
+                                    emit_key_pair<DEEP>(img, j, H, st, held, bc);
                                 }
                             } else {
-                                emit_value_full(img, j, b, bc);
+                                emit_value_full<DEEP>(img, j, b, bc);
                             }
                         } else {
 #pragma unroll
-                            for (int v = 0; v < NVT; ++v) emit_block<KIND, false>(img, tau[v], b, ps[v].out);
+                            for (int v = 0; v < NVT; ++v) emit_block<KIND, false, DEEP>(img, tau[v], b, ps[v].out);
                         }
                     } else {
 #pragma unroll
                         for (int v = 0; v < NVT; ++v)
-                            if (valid[v]) emit_block<KIND, true>(img, tau[v], b, ps[v].out);
+                            if (valid[v]) emit_block<KIND, true, DEEP>(img, tau[v], b, ps[v].out);
                     }
+                }
+            }
+            if (DEEP) {
+#pragma unroll
+                for (int v = 0; v < NVT; ++v) {
+                    const UpperHalf mine = polar_upper_half(q4[v], H, *a.consts);
+                    UpperHalf other;
+                    other.codes = (uint32_t)__shfl_xor((int)mine.codes, 32);
+                    other.q6 = __shfl_xor(mine.q6, 32);
+                    const uint32_t word = H == 0 ? polar_upper_join(mine, other, th.radius_scale, *a.consts)
+                                                 : polar_upper_join(other, mine, th.radius_scale, *a.consts);
+                    if (H == 0 && valid[v]) img[PQL_CODE_BYTES / 4 + tau[v]] = word;
                 }
             }
         }
@@ -438,7 +467,7 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
             uint4 *dc = reinterpret_cast<uint4 *>(gcodes);
             uint4 *dr = reinterpret_cast<uint4 *>(gradii);
             for (int c = lane; c < PQL_CODE_BYTES / 16; c += 64) dc[c] = src[c];
-            for (int c = lane; c < PQL_RADII * 2 / 16; c += 64) dr[c] = src[PQL_CODE_BYTES / 16 + c];
+            for (int c = lane; c < kRadiiHalves * 2 / 16; c += 64) dr[c] = src[PQL_CODE_BYTES / 16 + c];
         }
         wave_lds_sync();
     }
@@ -460,7 +489,7 @@ __global__ __launch_bounds__(512) void pq_append_pair_kernel(AppendArgs k, Appen
     else append_vector<XT>(v, PQ_VALUE, (int)blockIdx.x - n);
 }
 
-template <int XT, int KIND, int NTERMS, bool GENERAL>
+template <int XT, int KIND, int NTERMS, bool GENERAL, bool DEEP>
 pq_status launch_encode(const EncodeArgs &a, hipStream_t stream)
 {
     static int cached_cus[PQ_MAX_DEVICES] = {0};
@@ -478,30 +507,35 @@ pq_status launch_encode(const EncodeArgs &a, hipStream_t stream)
     if (blocks > cus) blocks = cus;
     if (blocks < 1) blocks = 1;
     pq_prof_before(1, stream);
-    hipLaunchKernelGGL((pq_encode_kernel<XT, KIND, NTERMS, GENERAL>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((pq_encode_kernel<XT, KIND, NTERMS, GENERAL, DEEP>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a);
     pq_prof_after(1, stream);
     PQ_HIP_TRY(hipGetLastError());
     return PQ_OK;
 }
 
-template <int NTERMS, bool GENERAL>
+template <int NTERMS, bool GENERAL, bool DEEP>
 pq_status dispatch_encode_terms(const EncodeArgs &a, pq_dtype xt, pq_kind kind, hipStream_t stream)
 {
     if (xt == PQ_BF16)
-        return kind == PQ_KEY ? launch_encode<PQ_BF16, PQ_KEY, NTERMS, GENERAL>(a, stream)
-                              : launch_encode<PQ_BF16, PQ_VALUE, NTERMS, GENERAL>(a, stream);
-    return kind == PQ_KEY ? launch_encode<PQ_F32, PQ_KEY, NTERMS, GENERAL>(a, stream)
-                          : launch_encode<PQ_F32, PQ_VALUE, NTERMS, GENERAL>(a, stream);
+        return kind == PQ_KEY ? launch_encode<PQ_BF16, PQ_KEY, NTERMS, GENERAL, DEEP>(a, stream)
+                              : launch_encode<PQ_BF16, PQ_VALUE, NTERMS, GENERAL, DEEP>(a, stream);
+    return kind == PQ_KEY ? launch_encode<PQ_F32, PQ_KEY, NTERMS, GENERAL, DEEP>(a, stream)
+                          : launch_encode<PQ_F32, PQ_VALUE, NTERMS, GENERAL, DEEP>(a, stream);
 }
 
-pq_status dispatch_encode(const EncodeArgs &a, pq_dtype xt, pq_kind kind, bool unit_entries, bool general,
+pq_status dispatch_encode(const EncodeArgs &a, pq_dtype xt, pq_kind kind, bool unit_entries, bool general, bool deep,
                           hipStream_t stream)
 {
+    if (deep) { /* full depth comes with the analytic codebooks only */
+        if (general) return PQ_EUNSUPPORTED;
+        return unit_entries ? dispatch_encode_terms<1, false, true>(a, xt, kind, stream)
+                            : dispatch_encode_terms<3, false, true>(a, xt, kind, stream);
+    }
     if (general)
-        return unit_entries ? dispatch_encode_terms<1, true>(a, xt, kind, stream)
-                            : dispatch_encode_terms<3, true>(a, xt, kind, stream);
-    return unit_entries ? dispatch_encode_terms<1, false>(a, xt, kind, stream)
-                        : dispatch_encode_terms<3, false>(a, xt, kind, stream);
+        return unit_entries ? dispatch_encode_terms<1, true, false>(a, xt, kind, stream)
+                            : dispatch_encode_terms<3, true, false>(a, xt, kind, stream);
+    return unit_entries ? dispatch_encode_terms<1, false, false>(a, xt, kind, stream)
+                        : dispatch_encode_terms<3, false, false>(a, xt, kind, stream);
 }
 
 } // namespace
@@ -537,7 +571,8 @@ extern "C" pq_status pq_encode_kv(const pq_ctx *ctx, const void *x, pq_dtype xt,
     a.n_items = a.n_tiles * n_heads;
     a.S_bf16x3 = reinterpret_cast<const uint4 *>(ds->S_bf16x3);
     a.consts = ds->consts;
-    return dispatch_encode(a, xt, kind, ctx->unit_entries, ctx->general_codebooks, static_cast<hipStream_t>(hip_stream));
+    return dispatch_encode(a, xt, kind, ctx->unit_entries, ctx->general_codebooks, ctx->depth == 7,
+                           static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,

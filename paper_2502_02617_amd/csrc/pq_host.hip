@@ -88,7 +88,7 @@ double orthogonality_defect(const double *S, int d)
  * elementary antiderivatives. ---- */
 struct SinPower {
     int terms;
-    double coef[8], freq[8]; /* sin^m(2 psi) = sum coef[k] * sin(freq[k] * psi) */
+    double coef[32], freq[32]; /* sin^m(2 psi) = sum coef[k] * sin(freq[k] * psi); m <= 63 */
 };
 
 SinPower make_sin_power(int m)
@@ -122,9 +122,8 @@ double first_moment_antiderivative(const SinPower &sp, double x) /* int x sin^m(
     return acc;
 }
 
-void lloyd_max_level(int level, double *centroids /*4*/, double *boundaries /*5*/)
+void lloyd_max_level(int level, double *centroids /*K*/, double *boundaries /*K+1*/, int K = 4)
 {
-    const int K = 4;
     const SinPower sp = make_sin_power((1 << (level - 1)) - 1);
     const double lo = 0.0, hi = kPi / 2.0;
     for (int k = 0; k < K; ++k) centroids[k] = hi * (k + 0.5) / K;
@@ -240,6 +239,20 @@ void build_tables(pq_ctx *ctx)
             c.tan_b[l - 1][2] = (float)tan(bnd[3]);
         }
     }
+    c.depth = ctx->depth;
+    if (ctx->depth == 7)
+        for (int l = 0; l < 3; ++l) {
+            const int K = 1 << ctx->upper_bits[l];
+            c.up_bits[l] = ctx->upper_bits[l];
+            for (int k = 0; k < K - 1; ++k) {
+                const double t = tan(ctx->upper_boundaries[l][k + 1]);
+                c.up_tan2[l][k] = (float)(t * t);
+            }
+            for (int k = 0; k < K; ++k) {
+                c.up_cs[l][k][0] = (float)cos(ctx->upper_centroids[l][k]);
+                c.up_cs[l][k][1] = (float)sin(ctx->upper_centroids[l][k]);
+            }
+        }
     c.general = ctx->general_codebooks ? 1 : 0;
     if (ctx->general_codebooks) {
         int cell_of[15];
@@ -359,6 +372,7 @@ static pq_status init_context(pq_ctx **out, int d, uint64_t seed, const double *
     ctx->d = d;
     ctx->seed = seed;
     ctx->general_codebooks = false;
+    ctx->depth = 4;
     if (S_in) {
         memcpy(ctx->S, S_in, sizeof(double) * d * d);
         for (int i = 0; i < d * d; ++i)
@@ -414,6 +428,51 @@ extern "C" pq_status pq_set_codebooks(pq_ctx *ctx, const double *cb)
     }
     ctx->general_codebooks = true;
     build_tables(ctx);
+    return PQ_OK;
+}
+
+extern "C" pq_status pq_set_recursion_depth(pq_ctx *ctx, int depth, const int *upper_bits)
+{
+    if (!ctx) return PQ_EINVAL;
+    if (depth != 4 && depth != 7) return PQ_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(ctx->mu);
+    for (int i = 0; i < PQ_MAX_DEVICES; ++i)
+        if (ctx->dev[i].ready) return PQ_EINVAL; /* tables already on a device: the context is in use */
+    if (depth == 7) {
+        if (!upper_bits) return PQ_EINVAL;
+        for (int l = 0; l < 3; ++l)
+            if (upper_bits[l] < 1 || upper_bits[l] > 3) return PQ_EINVAL;
+        if (4 * upper_bits[0] + 2 * upper_bits[1] + upper_bits[2] > 16) return PQ_EUNSUPPORTED;
+        for (int l = 0; l < 3; ++l) {
+            ctx->upper_bits[l] = upper_bits[l];
+            lloyd_max_level(5 + l, ctx->upper_centroids[l], ctx->upper_boundaries[l], 1 << upper_bits[l]);
+        }
+    }
+    ctx->depth = depth;
+    build_tables(ctx);
+    return PQ_OK;
+}
+
+extern "C" int pq_recursion_depth(const pq_ctx *ctx) { return ctx ? ctx->depth : 0; }
+
+extern "C" int pq_radii_halves_per_tile(const pq_ctx *ctx)
+{
+    return !ctx ? 0 : (ctx->depth == 7 ? PQ_DEEP_RADII_HALVES : PQL_RADII);
+}
+
+extern "C" int pq_record_bytes(const pq_ctx *ctx)
+{
+    return !ctx ? 0 : (ctx->depth == 7 ? PQ_DEEP_RECORD_BYTES : PQ_RECORD_BYTES);
+}
+
+extern "C" pq_status pq_get_upper_codebook(const pq_ctx *ctx, int level, int *bits, double *centroids, double *boundaries)
+{
+    if (!ctx || level < 5 || level > 7) return PQ_EINVAL;
+    if (ctx->depth != 7) return PQ_EINVAL;
+    const int K = 1 << ctx->upper_bits[level - 5];
+    if (bits) *bits = ctx->upper_bits[level - 5];
+    if (centroids) memcpy(centroids, ctx->upper_centroids[level - 5], sizeof(double) * K);
+    if (boundaries) memcpy(boundaries, ctx->upper_boundaries[level - 5], sizeof(double) * (K + 1));
     return PQ_OK;
 }
 

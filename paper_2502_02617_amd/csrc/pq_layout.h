@@ -128,7 +128,8 @@ PQL_HD uint32_t pql_get_bits(const uint8_t *base, uint32_t bit, int width)
     return (v >> sh) & ((1u << width) - 1u);
 }
 
-/* Generic (slow) reader used by DeQuant and the canonical export. */
+/* Generic (slow) reader used by DeQuant and the canonical export.  radii == NULL: the
+ * radius field is left zero (caches whose radius plane is not made of block radii). */
 PQL_HD PqBlockFields pql_read_block(int kind, const uint8_t *codes, const uint16_t *radii, int tau, int b)
 {
     PqBlockPos p = pql_pos(kind, tau, b);
@@ -145,7 +146,7 @@ PQL_HD PqBlockFields pql_read_block(int kind, const uint8_t *codes, const uint16
         uint32_t byte = p.c4_bit >> 3, sh = p.c4_bit & 7;
         f.c4 = ((uint32_t)codes[byte] >> sh) & 3u;
     }
-    f.radius = radii[p.radius_half];
+    f.radius = radii ? radii[p.radius_half] : (uint16_t)0;
     return f;
 }
 

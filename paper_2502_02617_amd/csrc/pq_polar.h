@@ -74,7 +74,40 @@ struct BlockCodes {
     uint32_t g0, g1; /* [c2(2h) | c3(h) | c2(2h+1)] of half-block 0 / 1 */
     uint32_t c4;
     uint16_t radius; /* binary16 bits */
+    float q4;        /* squared radius of the block (before radius_scale): input of the levels above 4 */
 };
+
+/* Levels 5, 6, 7 of a vector from the squared radii of its blocks (full-depth recursion):
+ * lo = blocks 0..3, hi = blocks 4..7.  Returns the radius-plane word of the vector:
+ * binary16 radius << 16 | codes (level-5 codes j = 0..3 at bits [j b5, (j+1) b5), level 6
+ * above them, level 7 on top). */
+struct UpperHalf {
+    uint32_t codes; /* this half's level-5 and level-6 codes, already at their bit positions */
+    float q6;       /* squared radius of the half */
+};
+
+__device__ __forceinline__ UpperHalf polar_upper_half(const float (&q4)[4], int half, const PqDeviceConsts &K)
+{
+    const int b5 = K.up_bits[0], b6 = K.up_bits[1];
+    const uint32_t c5a = pq_quant_upper(q4[0], q4[1], K.up_tan2[0], (1 << b5) - 1);
+    const uint32_t c5b = pq_quant_upper(q4[2], q4[3], K.up_tan2[0], (1 << b5) - 1);
+    const float q5a = q4[0] + q4[1], q5b = q4[2] + q4[3];
+    const uint32_t c6 = pq_quant_upper(q5a, q5b, K.up_tan2[1], (1 << b6) - 1);
+    UpperHalf h;
+    h.codes = ((c5a | (c5b << b5)) << (2 * b5 * half)) | (c6 << (4 * b5 + b6 * half));
+    h.q6 = q5a + q5b;
+    return h;
+}
+
+__device__ __forceinline__ uint32_t polar_upper_join(const UpperHalf &lo, const UpperHalf &hi, float radius_scale,
+                                                     const PqDeviceConsts &K)
+{
+    const int b5 = K.up_bits[0], b6 = K.up_bits[1], b7 = K.up_bits[2];
+    const uint32_t c7 = pq_quant_upper(lo.q6, hi.q6, K.up_tan2[2], (1 << b7) - 1);
+    const float r7 = __builtin_amdgcn_sqrtf(lo.q6 + hi.q6) * radius_scale;
+    const _Float16 rh = (_Float16)r7; /* round to nearest even */
+    return lo.codes | hi.codes | (c7 << (4 * b5 + 2 * b6)) | ((uint32_t)__builtin_bit_cast(uint16_t, rh) << 16);
+}
 
 /* Procedure Polar on one block of 16 rotated coordinates with procedure Quant
  * folded in: four levels of (angle code, radius) pairs, all in registers.  Only
@@ -136,7 +169,8 @@ __device__ __forceinline__ void polar_upper(PolarState &s, int p, const Threshol
     if (p == 7) {
         s.out.c4 = GENERAL ? quant3g(s.q3[0], s.q3[1], th.t4a, th.t4b, th.t4c)
                            : quant3(s.q3[0], s.q3[1], th.t4a, th.t4c);
-        const float r4 = __builtin_amdgcn_sqrtf(s.q3[0] + s.q3[1]) * th.radius_scale;
+        s.out.q4 = s.q3[0] + s.q3[1];
+        const float r4 = __builtin_amdgcn_sqrtf(s.out.q4) * th.radius_scale;
         const _Float16 rh = (_Float16)r4; /* round to nearest even */
         s.out.radius = __builtin_bit_cast(uint16_t, rh);
         s.out.l1 = s.l1;
@@ -209,6 +243,10 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
     const float acc = vector_times_slice(sx, ms, spart, tid); /* y_j = sum_i x_i S[i][j] */
     if (tid < PQ_D) sy[j] = acc;
     __syncthreads();
+    __shared__ float sq4[8];
+    const bool deep = a.consts->depth == 7;
+    const int64_t tile = dst >> 6;
+    const int tau = (int)(dst & 63);
     if (tid < 8) {
         const int b = tid;
         float y[16];
@@ -217,17 +255,25 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
         const Thresholds th = load_thresholds(*a.consts);
         /* general codebooks: the level-1 table is read from the constants in global memory */
         BlockCodes bc = a.consts->general ? polar_quant_block<true>(y, th) : polar_quant_block<false>(y, th);
-        const int64_t tile = dst >> 6;
-        const int tau = (int)(dst & 63);
         uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
-        uint16_t *gradii = a.radii + ((int64_t)head * a.pool_tiles + tile) * PQL_RADII;
         PqBlockPos pos = pql_pos(kind, tau, b);
         *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[0]) = (uint16_t)(bc.l1 & 0xFFFFu);
         *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[1]) = (uint16_t)(bc.l1 >> 16);
         put_bits_global(gcodes, pos.g6_bit[0], 6, bc.g0);
         put_bits_global(gcodes, pos.g6_bit[1], 6, bc.g1);
         put_bits_global(gcodes, pos.c4_bit, 2, bc.c4);
-        gradii[pos.radius_half] = bc.radius;
+        if (deep) sq4[b] = bc.q4;
+        else a.radii[((int64_t)head * a.pool_tiles + tile) * PQL_RADII + pos.radius_half] = bc.radius;
+    }
+    if (deep) { /* levels 5..7 over the eight block radii: one thread, one whole word of the radius plane */
+        __syncthreads();
+        if (tid == 0) {
+            const float lo4[4] = {sq4[0], sq4[1], sq4[2], sq4[3]}, hi4[4] = {sq4[4], sq4[5], sq4[6], sq4[7]};
+            const UpperHalf lo = polar_upper_half(lo4, 0, *a.consts), hi = polar_upper_half(hi4, 1, *a.consts);
+            uint32_t *top = reinterpret_cast<uint32_t *>(a.radii) +
+                            ((int64_t)head * a.pool_tiles + tile) * (PQ_DEEP_RADII_HALVES / 2);
+            top[tau] = polar_upper_join(lo, hi, 1.0f, *a.consts);
+        }
     }
 }
 

@@ -60,6 +60,52 @@ def check_codes(rec_gpu, rec_oracle, psi):
     return stats, rg, ro
 
 
+def check_codes_deep(rec_gpu, rec_oracle, psi, bits):
+    """Deep (50-byte) records: psi [n,127] exact oracle angles.  Same rule as check_codes for all 127 codes.
+    Returns (stats, radii_gpu [n], radii_oracle [n])."""
+    Jg, rg = oracle.unpack_deep(rec_gpu, bits)
+    Jo, ro = oracle.unpack_deep(rec_oracle, bits)
+    bad = Jg != Jo
+    n_bad = int(bad.sum())
+    stats = {"angles": int(Jo.size), "code_mismatches": n_bad, "code_mismatch_rate": n_bad / Jo.size}
+    if n_bad:
+        dist = np.empty_like(psi)
+        dist[:, :120] = boundary_distance(psi[:, :120])
+        off = 120
+        for level, cnt in ((5, 4), (6, 2), (7, 1)):
+            _, bnd = oracle.codebook(level, 1 << bits[level - 5])
+            a = psi[:, off : off + cnt]
+            dist[:, off : off + cnt] = np.min(np.abs(a[..., None] - bnd[1:-1]), axis=-1)
+            off += cnt
+        worst = float(dist[bad].max())
+        stats["worst_mismatch_boundary_distance"] = worst
+        assert worst <= ANGLE_TOL, f"code mismatch {worst:.3e} rad away from any boundary"
+        diff = np.abs(Jg[bad].astype(np.int64) - Jo[bad])
+        lev = np.broadcast_to(np.concatenate([_LEVEL_OF, np.full(7, 5)]), Jo.shape)[bad]
+        assert np.all((diff == 1) | ((lev == 1) & (diff == 15))), "a mismatching code is not the neighbouring cell"
+    assert stats["code_mismatch_rate"] <= CODE_MISMATCH_RATE, stats
+    return stats, rg, ro
+
+
+def check_radii_deep(rg, ro, y_oracle):
+    """rg, ro uint16 [n]: the one radius of each vector; y_oracle [n,128] the oracle's rotated vectors."""
+    bad = rg != ro
+    n_bad = int(bad.sum())
+    stats = {"radii": int(ro.size), "radius_mismatches": n_bad, "radius_mismatch_rate": n_bad / ro.size}
+    if n_bad:
+        r_exact = np.linalg.norm(y_oracle, axis=1)
+        d = np.abs(rg[bad].astype(np.int64) - ro[bad].astype(np.int64))
+        assert np.all(d == 1), "radius off by more than one binary16 ulp"
+        lo = np.minimum(rg[bad], ro[bad]).astype(np.uint16)
+        hi = (lo + 1).astype(np.uint16)
+        mid = 0.5 * (lo.view(np.float16).astype(np.float64) + hi.view(np.float16).astype(np.float64))
+        rel = np.abs(r_exact[bad] - mid) / mid
+        stats["worst_radius_rel_distance"] = float(rel.max())
+        assert rel.max() <= RADIUS_REL_TOL, f"radius mismatch {rel.max():.3e} (relative) away from a rounding boundary"
+    assert stats["radius_mismatch_rate"] <= RADIUS_MISMATCH_RATE, stats
+    return stats
+
+
 def check_radii(rg, ro, y_oracle):
     """rg, ro uint16 [n,8]; y_oracle [n,128] the oracle's rotated vectors (exact radii)."""
     bad = rg != ro

@@ -70,3 +70,19 @@ def tiles_to_canonical(kind, codes, radii, n_tokens):
             rec[:, tau, 46 + 2 * b] = rad & 0xFF
             rec[:, tau, 47 + 2 * b] = rad >> 8
     return rec.reshape(T * 64, 62)[:n_tokens]
+
+
+def tiles_to_canonical_deep(kind, codes, top, n_tokens):
+    """Full-depth caches: codes uint8 [T, 2944] as above; the radius plane holds one 32-bit word per
+    token (top: [T, 128] 16-bit halves = [T, 64] little-endian words, word tau = radius << 16 | upper
+    codes) -> records uint8 [n_tokens, 50]: bytes 0..45 as in the 62-byte record, then the word."""
+    T = np.ascontiguousarray(codes).shape[0]
+    words = np.ascontiguousarray(top).view(np.uint16).reshape(T, 64, 2)   # [.., 0] low half: codes, [.., 1]: radius
+    base = tiles_to_canonical(kind, codes, np.zeros((T, RADII), np.uint16), T * 64).reshape(T, 64, 62)
+    rec = np.zeros((T, 64, 50), dtype=np.uint8)
+    rec[:, :, :46] = base[:, :, :46]
+    rec[:, :, 46] = words[:, :, 0] & 0xFF
+    rec[:, :, 47] = words[:, :, 0] >> 8
+    rec[:, :, 48] = words[:, :, 1] & 0xFF
+    rec[:, :, 49] = words[:, :, 1] >> 8
+    return rec.reshape(T * 64, 50)[:n_tokens]

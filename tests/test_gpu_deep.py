@@ -1,0 +1,227 @@
+"""GPU parity of the full-depth recursion (L = 7, one radius per vector) against the fp64 oracle.
+
+Every input is seeded and synthetic.  Each test prints what it is about to run before touching the GPU.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_02617_amd import Context, PQ_KEY, PQ_VALUE, PolarQuantError, synth
+from tests import helpers, layout_ref
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+BITS = [(2, 2, 2), (3, 1, 1), (1, 3, 2)]
+
+
+def say(msg):
+    print(f"[gpu-test] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def make(bits, **kw):
+    ctx = Context(seed=0, **kw)
+    ctx.set_recursion_depth(7, bits)
+    S = ctx.preconditioner() if kw else oracle.preconditioner(0)
+    return ctx, S, oracle.default_codebooks(), oracle.upper_codebooks(bits)
+
+
+def export_both_ways(ctx, kind, codes, top, token0, n_tokens):
+    """50-byte records via the library's export kernel and via the independent numpy reading of the layout."""
+    H = codes.shape[0]
+    rec = torch.empty((H, n_tokens, 50), dtype=torch.uint8, device=DEV)
+    ctx.export_canonical(kind, codes, top, token0, n_tokens, rec)
+    torch.cuda.synchronize()
+    rec_lib = rec.cpu().numpy()
+    c = codes.cpu().numpy()
+    t = top.cpu().numpy().view(np.uint16)
+    assert token0 % 64 == 0
+    t0 = token0 // 64
+    rec_np = np.stack([layout_ref.tiles_to_canonical_deep(kind, c[h, t0:], t[h, t0:], n_tokens) for h in range(H)])
+    assert np.array_equal(rec_lib, rec_np), "export kernel and layout specification disagree"
+    return rec_lib
+
+
+def oracle_records(x_cpu, S, cb, bits, cbt):
+    """x_cpu [T, H, 128] -> records [H, T, 50], psi [H, T, 127], y [H, T, 128]."""
+    T, H, _ = x_cpu.shape
+    xs = x_cpu.permute(1, 0, 2).contiguous().to(torch.float64).numpy().reshape(H * T, 128)
+    rec, psi, y = oracle.encode_deep(xs, S, cb, bits, cbt, want_psi=True, want_y=True)
+    return rec.reshape(H, T, 50), psi.reshape(H, T, 127), y.reshape(H, T, 128)
+
+
+def check_records(rec_gpu, rec_or, psi, y, bits):
+    st, rg, ro = helpers.check_codes_deep(rec_gpu.reshape(-1, 50), rec_or.reshape(-1, 50), psi.reshape(-1, 127), bits)
+    st.update(helpers.check_radii_deep(rg, ro, y.reshape(-1, 128)))
+    return st
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("kind", [PQ_KEY, PQ_VALUE])
+def test_deep_encode_and_dequant(bits, kind):
+    ctx, S, cb, cbt = make(bits)
+    assert ctx.recursion_depth() == 7 and ctx.radii_halves_per_tile() == 128 and ctx.record_bytes() == 50
+    for dtype, T, H in ((torch.bfloat16, 1000 + 37, 2), (torch.float32, 300, 1)):
+        say(f"deep encode bits={bits} kind={kind} dtype={dtype} T={T} H={H}")
+        if dtype == torch.bfloat16:
+            x = synth.kv_stream(T, H, seed=41 + kind).permute(1, 0, 2).contiguous()     # [T, H, 128] bf16, outlier channels
+        else:
+            x = synth.gaussian_vectors(T * H, seed=43).reshape(T, H, 128)
+        pool = ((T + 63) // 64) * 64
+        codes, top = ctx.alloc_cache_for(H, pool, DEV)
+        codes.fill_(0xA5)
+        top.fill_(0x5A5A)
+        ctx.encode_kv(x.to(DEV), kind, codes, top)
+        torch.cuda.synchronize()
+        rec_gpu = export_both_ways(ctx, kind, codes, top, 0, T)
+        rec_or, psi, y = oracle_records(x, S, cb, bits, cbt)
+        say(f"  {check_records(rec_gpu, rec_or, psi, y, bits)}")
+        # slots after the input keep their old bytes
+        if T % 64:
+            tail = export_both_ways(ctx, kind, codes, top, (T // 64) * 64, 64)[:, T % 64:]
+            assert np.all(tail[:, :, 46:] == 0x5A)
+        out = torch.empty((T, H, 128), dtype=torch.float32, device=DEV)
+        for rotated in (True, False):
+            ctx.decode_kv(kind, codes, top, 0, T, out, rotated=rotated)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            for h in range(H):
+                e_same = helpers.rel_l2(got[:, h], oracle.decode_deep(rec_gpu[h], S, cb, bits, cbt, rotated=rotated))
+                e_or = helpers.rel_l2(got[:, h], oracle.decode_deep(rec_or[h], S, cb, bits, cbt, rotated=rotated))
+                assert e_same <= 1e-5 and e_or <= 1e-3, (rotated, h, e_same, e_or)
+
+
+def test_deep_encode_hadamard_preconditioner():
+    bits = (2, 2, 2)
+    ctx, S, cb, cbt = make(bits, hadamard=True)
+    T, H = 200, 2
+    say(f"deep encode with a randomised Hadamard S: T={T} H={H}")
+    x = synth.kv_stream(T, H, seed=47).permute(1, 0, 2).contiguous()
+    codes, top = ctx.alloc_cache_for(H, 256, DEV)
+    codes.zero_()
+    top.zero_()
+    ctx.encode_kv(x.to(DEV), PQ_KEY, codes, top)
+    torch.cuda.synchronize()
+    rec_gpu = export_both_ways(ctx, PQ_KEY, codes, top, 0, T)
+    rec_or, psi, y = oracle_records(x, S, cb, bits, cbt)
+    say(f"  {check_records(rec_gpu, rec_or, psi, y, bits)}")
+
+
+def test_deep_offsets_and_append():
+    bits = (2, 2, 2)
+    ctx, S, cb, cbt = make(bits)
+    H, pool = 2, 256
+    say("deep: encode into the middle of a tile, then append single tokens")
+    x = synth.kv_stream(90, H, seed=51).permute(1, 0, 2).contiguous()        # [90, H, 128]
+    codes, top = ctx.alloc_cache_for(H, pool, DEV)
+    codes.zero_()
+    top.zero_()
+    for kind in (PQ_KEY, PQ_VALUE):
+        codes.zero_()
+        top.zero_()
+        ctx.encode_kv(x[:70].to(DEV), kind, codes, top, dst_token0=20)       # slots 20..89: two partial tiles
+        for t in range(70, 90):                                              # slots 90..109 one at a time
+            ctx.append_kv(x[t:t + 1].to(DEV), kind, codes, top, torch.tensor([20 + t], dtype=torch.int64, device=DEV))
+        torch.cuda.synchronize()
+        rec_gpu = export_both_ways(ctx, kind, codes, top, 0, 128)
+        rec_or, psi, y = oracle_records(x, S, cb, bits, cbt)
+        say(f"  kind {kind}: {check_records(rec_gpu[:, 20:110], rec_or, psi, y, bits)}")
+        assert np.all(rec_gpu[:, :20] == 0) and np.all(rec_gpu[:, 110:] == 0)
+
+
+def build_cache(ctx, S, cb, bits, cbt, lens, Hkv, seed):
+    starts, pool = [], 0
+    for n in lens:
+        starts.append(pool)
+        pool += ((max(n, 1) + 63) // 64) * 64
+    kc, kt = ctx.alloc_cache_for(Hkv, pool, DEV)
+    vc, vt = ctx.alloc_cache_for(Hkv, pool, DEV)
+    for t in (kc, vc):
+        t.fill_(0xFF)
+    for t in (kt, vt):
+        t.fill_(0x7E00)    # stale slots: binary16 NaN radius, arbitrary codes
+    k_rec = np.zeros((Hkv, pool, 50), dtype=np.uint8)
+    v_rec = np.zeros((Hkv, pool, 50), dtype=np.uint8)
+    for b, n in enumerate(lens):
+        if n == 0:
+            continue
+        k = synth.kv_stream(n, Hkv, seed + 2 * b).permute(1, 0, 2).contiguous()
+        v = synth.kv_stream(n, Hkv, seed + 2 * b + 1).permute(1, 0, 2).contiguous()
+        ctx.encode_kv(k.to(DEV), PQ_KEY, kc, kt, dst_token0=starts[b])
+        ctx.encode_kv(v.to(DEV), PQ_VALUE, vc, vt, dst_token0=starts[b])
+        for kind, x, codes, top, rec in ((PQ_KEY, k, kc, kt, k_rec), (PQ_VALUE, v, vc, vt, v_rec)):
+            # records that agree on validated boundary ties (see build_cache in test_gpu_parity.py)
+            rec_or, psi, y = oracle_records(x, S, cb, bits, cbt)
+            rec_gpu = export_both_ways(ctx, kind, codes, top, starts[b], n)
+            check_records(rec_gpu, rec_or, psi, y, bits)
+            rec_or[:, :, :48] = rec_gpu[:, :, :48]
+            rec[:, starts[b]:starts[b] + n] = rec_or
+    torch.cuda.synchronize()
+    return (kc, kt, vc, vt), np.array(starts, dtype=np.int64), pool, k_rec, v_rec
+
+
+@pytest.mark.parametrize("bits,Hq,Hkv", [((2, 2, 2), 8, 2), ((3, 1, 1), 2, 2), ((1, 3, 2), 3, 3)])
+def test_deep_attention(bits, Hq, Hkv):
+    ctx, S, cb, cbt = make(bits)
+    lens = [1, 64, 65, 0, 1000, 64 * 7 + 3]
+    say(f"deep attention bits={bits} Hq={Hq} Hkv={Hkv} lens={lens}")
+    B = len(lens)
+    caches, starts, pool, k_rec, v_rec = build_cache(ctx, S, cb, bits, cbt, lens, Hkv, seed=1300)
+    kc, kt, vc, vt = caches
+    q = synth.queries(B, Hq, seed=1301)
+    out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(Context.attn_workspace_bytes(B, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)
+    ctx.attn_decode_polar(q.to(DEV), out, kc, kt, vc, vt, torch.from_numpy(starts).to(DEV),
+                          torch.tensor(lens, dtype=torch.int32, device=DEV), max(lens), helpers.softmax_scale(), ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    ref = oracle.attention_deep(q.to(torch.float64).numpy(), k_rec, v_rec, starts, np.array(lens, np.int32), S, cb, bits,
+                                cbt, helpers.softmax_scale())
+    assert np.all(np.isfinite(got)) and np.all(got[3] == 0.0)
+    per_seq = [helpers.rel_l2(got[b], ref[b]) if lens[b] else 0.0 for b in range(B)]
+    say(f"  rel L2 {helpers.rel_l2(got, ref):.2e}; per sequence {['%.1e' % e for e in per_seq]}")
+    assert max(per_seq) <= 2e-3
+
+
+def test_deep_decode_step_and_unsupported_paths():
+    bits = (2, 2, 2)
+    ctx, S, cb, cbt = make(bits)
+    Hq, Hkv, lens = 8, 2, [130, 64, 700]
+    B = len(lens)
+    say(f"deep decode step (append newest token, then attention) lens={lens}")
+    caches, starts, pool, k_rec, v_rec = build_cache(ctx, S, cb, bits, cbt, [n - 1 for n in lens], Hkv, seed=1400)
+    kc, kt, vc, vt = caches
+    new_k = synth.kv_stream(B, Hkv, seed=1410).permute(1, 0, 2).contiguous()      # [B, Hkv, 128]
+    new_v = synth.kv_stream(B, Hkv, seed=1411).permute(1, 0, 2).contiguous()
+    q = synth.queries(B, Hq, seed=1412)
+    slots = torch.tensor([int(starts[b]) + lens[b] - 1 for b in range(B)], dtype=torch.int64, device=DEV)
+    out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(Context.attn_workspace_bytes(B, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
+    d_start = torch.from_numpy(starts).to(DEV)
+    d_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    ctx.decode_step_polar(new_k.to(DEV), new_v.to(DEV), slots, q.to(DEV), out, kc, kt, vc, vt, d_start, d_len, max(lens),
+                          helpers.softmax_scale(), ws)
+    torch.cuda.synchronize()
+    for b in range(B):      # the oracle's records of the appended tokens, ties validated as for the rest
+        for kind, x, codes, top, rec in ((PQ_KEY, new_k, kc, kt, k_rec), (PQ_VALUE, new_v, vc, vt, v_rec)):
+            rec_or, psi, y = oracle_records(x[b:b + 1], S, cb, bits, cbt)
+            tile0 = (int(slots[b]) // 64) * 64
+            rec_gpu = export_both_ways(ctx, kind, codes, top, tile0, 64)[:, int(slots[b]) - tile0][:, None]
+            check_records(rec_gpu, rec_or, psi, y, bits)
+            rec_or[:, :, :48] = rec_gpu[:, :, :48]
+            rec[:, int(slots[b])] = rec_or[:, 0]
+    ref = oracle.attention_deep(q.to(torch.float64).numpy(), k_rec, v_rec, starts, np.array(lens, np.int32), S, cb, bits,
+                                cbt, helpers.softmax_scale())
+    err = helpers.rel_l2(out.cpu().numpy(), ref)
+    say(f"  rel L2 {err:.2e}")
+    assert err <= 2e-3
+    # entry points that have no full-depth form say so
+    with pytest.raises(PolarQuantError):
+        qm = synth.queries(B * 2, Hq, seed=1).reshape(B, 2, Hq, 128).contiguous().to(DEV)
+        om = torch.empty((B, 2, Hq, 128), dtype=torch.float32, device=DEV)
+        wm = torch.empty(Context.attn_mq_workspace_bytes(B, 2, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
+        ctx.attn_decode_polar_mq(qm, om, kc, kt, vc, vt, d_start, d_len, max(lens), helpers.softmax_scale(), wm)
