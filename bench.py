@@ -223,6 +223,62 @@ def main():
                         "gb_per_s": round(step_bytes / (mq_ms * 1e-3) / 1e9, 1)}
         del q_m, out_m, ws_m
 
+    # ---- full-depth line: the same batch in the depth-7 format (one radius per vector, 2 bits for each
+    # angle of levels 5-7: 50 bytes per vector instead of 62), two rotating caches; encode and attention
+    ctx_d = Context(seed=0)
+    ctx_d.set_recursion_depth(7, [2, 2, 2])
+    deep_caches = []
+    for c in range(2):
+        dkc, dkr = ctx_d.alloc_cache_for(HKV, pool, dev)
+        dvc, dvr = ctx_d.alloc_cache_for(HKV, pool, dev)
+        for t in (dkc, dkr, dvc, dvr):
+            t.zero_()
+        for b in range(B):
+            k = synth.kv_stream(CTX, HKV, seed=1000 * c + 2 * b, device=dev)
+            v = synth.kv_stream(CTX, HKV, seed=1000 * c + 2 * b + 1, device=dev)
+            ctx_d.encode_kv(k, PQ_KEY, dkc, dkr, dst_token0=b * pool_per_seq, ld_token=k.stride(1), ld_head=k.stride(0),
+                            n_tokens=CTX, n_heads=HKV)
+            ctx_d.encode_kv(v, PQ_VALUE, dvc, dvr, dst_token0=b * pool_per_seq, ld_token=v.stride(1), ld_head=v.stride(0),
+                            n_tokens=CTX, n_heads=HKV)
+            del k, v
+        deep_caches.append((dkc, dkr, dvc, dvr))
+
+    def deep_step(i):
+        kc_, kr_, vc_, vr_ = deep_caches[i % 2]
+        ctx_d.decode_step_polar(new_k, new_v, newest_slot, q, out, kc_, kr_, vc_, vr_, seq_start, ctx_len, CTX, scale, ws)
+
+    for i in range(args.warmup):
+        deep_step(i)
+    torch.cuda.synchronize()
+    profile_begin(args.steps + 1)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        deep_step(i)
+    torch.cuda.synchronize()
+    deep_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    pr_d = profile_end()
+    deep_kern_ms = pr_d["attn_ms"] / max(pr_d["attn_launches"], 1)
+    deep_bytes = 2 * 50 * B * HKV * CTX
+
+    def encode_step_d(i):
+        k, v, slot0 = enc_inputs[i % len(enc_inputs)]
+        dkc, dkr, dvc, dvr = deep_caches[0]
+        ctx_d.encode_kv(k, PQ_KEY, dkc, dkr, dst_token0=slot0, ld_token=k.stride(1), ld_head=k.stride(0),
+                        n_tokens=CTX, n_heads=HKV)
+        ctx_d.encode_kv(v, PQ_VALUE, dvc, dvr, dst_token0=slot0, ld_token=v.stride(1), ld_head=v.stride(0),
+                        n_tokens=CTX, n_heads=HKV)
+
+    for i in range(args.warmup):
+        encode_step_d(i)
+    torch.cuda.synchronize()
+    profile_begin(2 * args.encode_steps + 2)
+    for i in range(args.encode_steps):
+        encode_step_d(i)
+    torch.cuda.synchronize()
+    pr_de = profile_end()
+    enc_d_mtok = CTX * args.encode_steps / (pr_de["encode_ms"] * 1e-3) / 1e6 if pr_de["encode_ms"] > 0 else 0.0
+    del deep_caches
+
     result = {
         "metric": "decode attn HBM GB/s on polar-quantized KV @32k ctx",
         "value": round(value, 1),
@@ -288,6 +344,15 @@ def main():
             "workload": "configs[2] cache, M query tokens per sequence under the causal mask, pq_attn_decode_polar_mq "
                         "(attention only); gb_per_s counts the packed cache once per step",
             **mq,
+        },
+        "full_depth": {
+            "workload": "configs[2] in the depth-7 format (pq_set_recursion_depth(7, {2,2,2}): 50 bytes per vector), "
+                        "pq_decode_step_polar; encode: configs[1] inputs",
+            "ms_per_step": round(deep_ms, 4),
+            "kernel_avg_ms": round(deep_kern_ms, 5),
+            "gb_per_s": round(deep_bytes / (deep_ms * 1e-3) / 1e9, 1),
+            "algorithmic_bytes_per_step": deep_bytes,
+            "encode_mtok_per_s": round(enc_d_mtok, 2),
         },
         "setup_s": round(t_setup, 1),
     }

@@ -239,6 +239,9 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
         __syncthreads();
     }
 
+    UpperTables ut = {};
+    if (DEEP) ut = load_upper_tables(*a.consts);
+
     uint32_t *img = sImg[wave];
     const int j = lane & 31, H = lane >> 5; /* vector within the 32-vector group, lane half */
 
@@ -449,12 +452,12 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
             if (DEEP) {
 #pragma unroll
                 for (int v = 0; v < NVT; ++v) {
-                    const UpperHalf mine = polar_upper_half(q4[v], H, *a.consts);
+                    const UpperHalf mine = polar_upper_half(q4[v], H, ut);
                     UpperHalf other;
                     other.codes = (uint32_t)__shfl_xor((int)mine.codes, 32);
                     other.q6 = __shfl_xor(mine.q6, 32);
-                    const uint32_t word = H == 0 ? polar_upper_join(mine, other, th.radius_scale, *a.consts)
-                                                 : polar_upper_join(other, mine, th.radius_scale, *a.consts);
+                    const uint32_t word = H == 0 ? polar_upper_join(mine, other, th.radius_scale, ut)
+                                                 : polar_upper_join(other, mine, th.radius_scale, ut);
                     if (H == 0 && valid[v]) img[PQL_CODE_BYTES / 4 + tau[v]] = word;
                 }
             }

@@ -86,27 +86,42 @@ struct UpperHalf {
     float q6;       /* squared radius of the half */
 };
 
-__device__ __forceinline__ UpperHalf polar_upper_half(const float (&q4)[4], int half, const PqDeviceConsts &K)
+/* boundaries and widths of levels 5..7, read once per kernel (the same in all lanes) */
+struct UpperTables {
+    float tan2[3][7];
+    int b5, b6, b7;
+};
+
+__device__ __forceinline__ UpperTables load_upper_tables(const PqDeviceConsts &K)
 {
-    const int b5 = K.up_bits[0], b6 = K.up_bits[1];
-    const uint32_t c5a = pq_quant_upper(q4[0], q4[1], K.up_tan2[0], (1 << b5) - 1);
-    const uint32_t c5b = pq_quant_upper(q4[2], q4[3], K.up_tan2[0], (1 << b5) - 1);
+    UpperTables u;
+#pragma unroll
+    for (int l = 0; l < 3; ++l)
+#pragma unroll
+        for (int k = 0; k < 7; ++k) u.tan2[l][k] = K.up_tan2[l][k];
+    u.b5 = K.up_bits[0]; u.b6 = K.up_bits[1]; u.b7 = K.up_bits[2];
+    return u;
+}
+
+__device__ __forceinline__ UpperHalf polar_upper_half(const float (&q4)[4], int half, const UpperTables &K)
+{
+    const uint32_t c5a = pq_quant_upper(q4[0], q4[1], K.tan2[0], (1 << K.b5) - 1);
+    const uint32_t c5b = pq_quant_upper(q4[2], q4[3], K.tan2[0], (1 << K.b5) - 1);
     const float q5a = q4[0] + q4[1], q5b = q4[2] + q4[3];
-    const uint32_t c6 = pq_quant_upper(q5a, q5b, K.up_tan2[1], (1 << b6) - 1);
+    const uint32_t c6 = pq_quant_upper(q5a, q5b, K.tan2[1], (1 << K.b6) - 1);
     UpperHalf h;
-    h.codes = ((c5a | (c5b << b5)) << (2 * b5 * half)) | (c6 << (4 * b5 + b6 * half));
+    h.codes = ((c5a | (c5b << K.b5)) << (2 * K.b5 * half)) | (c6 << (4 * K.b5 + K.b6 * half));
     h.q6 = q5a + q5b;
     return h;
 }
 
 __device__ __forceinline__ uint32_t polar_upper_join(const UpperHalf &lo, const UpperHalf &hi, float radius_scale,
-                                                     const PqDeviceConsts &K)
+                                                     const UpperTables &K)
 {
-    const int b5 = K.up_bits[0], b6 = K.up_bits[1], b7 = K.up_bits[2];
-    const uint32_t c7 = pq_quant_upper(lo.q6, hi.q6, K.up_tan2[2], (1 << b7) - 1);
+    const uint32_t c7 = pq_quant_upper(lo.q6, hi.q6, K.tan2[2], (1 << K.b7) - 1);
     const float r7 = __builtin_amdgcn_sqrtf(lo.q6 + hi.q6) * radius_scale;
     const _Float16 rh = (_Float16)r7; /* round to nearest even */
-    return lo.codes | hi.codes | (c7 << (4 * b5 + 2 * b6)) | ((uint32_t)__builtin_bit_cast(uint16_t, rh) << 16);
+    return lo.codes | hi.codes | (c7 << (4 * K.b5 + 2 * K.b6)) | ((uint32_t)__builtin_bit_cast(uint16_t, rh) << 16);
 }
 
 /* Procedure Polar on one block of 16 rotated coordinates with procedure Quant
@@ -269,10 +284,11 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
         __syncthreads();
         if (tid == 0) {
             const float lo4[4] = {sq4[0], sq4[1], sq4[2], sq4[3]}, hi4[4] = {sq4[4], sq4[5], sq4[6], sq4[7]};
-            const UpperHalf lo = polar_upper_half(lo4, 0, *a.consts), hi = polar_upper_half(hi4, 1, *a.consts);
+            const UpperTables ut = load_upper_tables(*a.consts);
+            const UpperHalf lo = polar_upper_half(lo4, 0, ut), hi = polar_upper_half(hi4, 1, ut);
             uint32_t *top = reinterpret_cast<uint32_t *>(a.radii) +
                             ((int64_t)head * a.pool_tiles + tile) * (PQ_DEEP_RADII_HALVES / 2);
-            top[tau] = polar_upper_join(lo, hi, 1.0f, *a.consts);
+            top[tau] = polar_upper_join(lo, hi, 1.0f, ut);
         }
     }
 }

@@ -164,3 +164,31 @@ def test_set_codebooks_validation_and_readback():
     bad = cb.copy(); bad[5] = bad[4] + 1e-3; bad[6] = bad[5] + 1e-3   # two boundaries in one table cell
     with pytest.raises(PolarQuantError):
         Context(seed=0).set_codebooks(bad)
+
+
+def test_recursion_depth_validation_and_upper_codebooks():
+    """pq_set_recursion_depth on the host: accepted widths, format sizes, codebooks of levels 5-7 equal to the
+    oracle's Lloyd-Max quantisers (different integrators)."""
+    ctx = Context(seed=0)
+    assert ctx.recursion_depth() == 4 and ctx.radii_halves_per_tile() == 512 and ctx.record_bytes() == 62
+    with pytest.raises(PolarQuantError):
+        ctx.upper_codebook(5)                      # no upper levels at depth 4
+    for bad in ([0, 2, 2], [4, 1, 1], [3, 3, 3]):  # widths outside 1..3, or more than 16 bits in all
+        with pytest.raises(PolarQuantError):
+            ctx.set_recursion_depth(7, bad)
+    with pytest.raises(PolarQuantError):
+        ctx.set_recursion_depth(6, [2, 2, 2])      # only the truncation of Section 4.1 and the full depth
+    with pytest.raises(PolarQuantError):
+        ctx.set_recursion_depth(7, None)
+    for bits in ([2, 2, 2], [3, 1, 1], [1, 3, 2]):
+        ctx.set_recursion_depth(7, bits)
+        assert ctx.recursion_depth() == 7 and ctx.radii_halves_per_tile() == 128 and ctx.record_bytes() == 50
+        cbt = oracle.upper_codebooks(bits)
+        for level in (5, 6, 7):
+            b, cen, bnd = ctx.upper_codebook(level)
+            assert b == bits[level - 5] and cen.size == 2 ** b and bnd.size == 2 ** b + 1
+            assert np.max(np.abs(cen - cbt[level - 5, : 2 ** b])) <= 1e-12
+            assert bnd[0] == 0.0 and abs(bnd[-1] - np.pi / 2) <= 1e-15
+            assert np.max(np.abs(bnd[1:-1] - 0.5 * (cen[:-1] + cen[1:]))) <= 1e-15
+    ctx.set_recursion_depth(4)
+    assert ctx.record_bytes() == 62
