@@ -141,8 +141,8 @@ size_t pq_fit_workspace_bytes(void);
  * have pq_record_bytes(ctx) bytes (62; 50 = bytes 0..45 as before, the 16-bit code word
  * little endian, the radius little endian).  Like pq_set_codebooks this must precede the
  * first launch with the context (PQ_EINVAL afterwards).  At depth 7 pq_encode_kv,
- * pq_append_kv(_pair), pq_decode_kv, pq_export_canonical, pq_attn_decode_polar and
- * pq_decode_step_polar follow the new format (Hq/Hkv <= 4); pq_attn_decode_hybrid,
+ * pq_append_kv(_pair), pq_decode_kv, pq_export_canonical, pq_attn_decode_polar,
+ * pq_decode_step_polar and pq_attn_decode_hybrid follow the new format (Hq/Hkv <= 4);
  * pq_attn_decode_polar_mq, and pq_encode_kv on a context whose codebooks were replaced
  * with pq_set_codebooks, return PQ_EUNSUPPORTED. */
 pq_status pq_set_recursion_depth(pq_ctx *ctx, int depth, const int *upper_bits);

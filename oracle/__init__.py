@@ -365,3 +365,30 @@ def attention_deep(q, k_rec, v_rec, seq_start, ctx_len, S, cb, bits, cbt, scale)
         ctypes.c_int64(plane), _p(S), _p(cb), _p(b, ctypes.c_int32), _p(cbt), ctypes.c_double(scale), _p(out),
     )
     return out
+
+
+def attention_hybrid_deep(q, k_rec, v_rec, seq_start, ctx_len, win_k, win_v, win_len, S, cb, bits, cbt, scale):
+    """Deep-record prefix + unquantised window, one softmax over both (Eq. 5 with the rows of the window appended
+    as given; Section 5.3).  The definition written out with numpy in float64: DeQuant of the prefix rows, the
+    window rows appended, scores, exp of the shifted scores, normalised weighted sum.
+    q[B,Hq,128]; k_rec/v_rec [Hkv, plane, 50]; win_k/win_v [B, Hkv, win_cap, 128]; win_len [B] -> [B,Hq,128]."""
+    q = _f64(q)
+    B, Hq, _ = q.shape
+    Hkv = k_rec.shape[0]
+    G = Hq // Hkv
+    win_k = _f64(win_k)
+    win_v = _f64(win_v)
+    out = np.zeros((B, Hq, D), dtype=np.float64)
+    for b in range(B):
+        T, W = max(int(ctx_len[b]), 0), max(int(win_len[b]), 0)
+        if T + W == 0:
+            continue
+        s0 = int(seq_start[b])
+        for hk in range(Hkv):
+            Kh = np.concatenate([decode_deep(k_rec[hk, s0:s0 + T], S, cb, bits, cbt) if T else np.zeros((0, D)), win_k[b, hk, :W]])
+            Vh = np.concatenate([decode_deep(v_rec[hk, s0:s0 + T], S, cb, bits, cbt) if T else np.zeros((0, D)), win_v[b, hk, :W]])
+            for g in range(G):
+                s = Kh @ q[b, hk * G + g] * scale
+                p = np.exp(s - s.max())
+                out[b, hk * G + g] = (p / p.sum()) @ Vh
+    return out

@@ -1070,8 +1070,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     if ((app || win) && (M != 1 || G == 8)) return PQ_EUNSUPPORTED;
     const int NG = M * G <= 4 ? 1 : (M * G <= 8 ? 2 : 4);
     const bool deep = ctx->depth == 7;
-    /* full depth: one query token, at most 4 query heads per kv head, no unquantised window */
-    if (deep && (NG != 1 || win)) return PQ_EUNSUPPORTED;
+    if (deep && NG != 1) return PQ_EUNSUPPORTED; /* full depth: one query token, at most 4 query heads per kv head */
     if (!pq_aligned16(q) || !pq_aligned16(out) || !pq_aligned16(k_codes) || !pq_aligned16(k_radii) ||
         !pq_aligned16(v_codes) || !pq_aligned16(v_radii) || !pq_aligned16(workspace))
         return PQ_EALIGN;

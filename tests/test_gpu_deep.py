@@ -187,6 +187,40 @@ def test_deep_attention(bits, Hq, Hkv):
     assert max(per_seq) <= 2e-3
 
 
+def test_deep_hybrid_attention():
+    """Deep-format prefix + unquantised bf16 window, one softmax over both."""
+    bits = (2, 2, 2)
+    ctx, S, cb, cbt = make(bits)
+    Hq, Hkv = 8, 2
+    lens = [0, 0, 100, 1000, 64, 300]
+    wins = [0, 5, 1, 63, 64, 130]
+    cap = 130
+    say(f"deep hybrid attention prefix={lens} window={wins}")
+    B = len(lens)
+    caches, starts, pool, k_rec, v_rec = build_cache(ctx, S, cb, bits, cbt, lens, Hkv, seed=1500)
+    kc, kt, vc, vt = caches
+    g = torch.Generator().manual_seed(1501)
+    win_k = torch.randn((B, Hkv, cap, 128), generator=g).to(torch.bfloat16)
+    win_v = torch.randn((B, Hkv, cap, 128), generator=g).to(torch.bfloat16)
+    win_k[:, :, :, 7] *= 6.0
+    q = synth.queries(B, Hq, seed=1502)
+    out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(Context.attn_hybrid_workspace_bytes(B, Hq, Hkv, max(lens), cap), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)
+    ctx.attn_decode_hybrid(q.to(DEV), out, kc, kt, vc, vt, torch.from_numpy(starts).to(DEV),
+                           torch.tensor(lens, dtype=torch.int32, device=DEV), win_k.to(DEV), win_v.to(DEV),
+                           torch.tensor(wins, dtype=torch.int32, device=DEV), max(lens), helpers.softmax_scale(), ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    ref = oracle.attention_hybrid_deep(q.to(torch.float64).numpy(), k_rec, v_rec, starts, np.array(lens, np.int32),
+                                       win_k.to(torch.float64).numpy(), win_v.to(torch.float64).numpy(),
+                                       np.array(wins, np.int32), S, cb, bits, cbt, helpers.softmax_scale())
+    assert np.all(np.isfinite(got)) and np.all(got[0] == 0.0)
+    per_seq = [helpers.rel_l2(got[b], ref[b]) for b in range(1, B)]
+    say(f"  per sequence {['%.1e' % e for e in per_seq]}")
+    assert max(per_seq) <= 2e-3 and per_seq[0] <= 1e-5     # sequence 1 is window only: fp32 accuracy
+
+
 def test_deep_decode_step_and_unsupported_paths():
     bits = (2, 2, 2)
     ctx, S, cb, cbt = make(bits)

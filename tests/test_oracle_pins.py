@@ -690,3 +690,35 @@ def test_deep_attention_is_textbook_softmax(S, cb):
         Vh = oracle.decode_deep(v_rec[h // 4, :T], S, cb, bits, cbt)
         p = scipy.special.softmax(Kh @ q[0, h] * scale)
         assert np.max(np.abs(p @ Vh - out[0, h])) <= 1e-12
+
+
+def test_deep_hybrid_attention_reductions(S, cb):
+    """The numpy-written hybrid attention on deep records: an empty window is attention_deep, an empty prefix is
+    plain softmax attention on the window, and the general case is the log-sum-exp merge of the two."""
+    bits = (2, 2, 2)
+    cbt = oracle.upper_codebooks(bits)
+    T, W, Hkv, B = 23, 9, 2, 2
+    k = synth.kv_stream(T * B, Hkv, 61).float().numpy().astype(np.float64)
+    v = synth.kv_stream(T * B, Hkv, 62).float().numpy().astype(np.float64)
+    k_rec = oracle.encode_deep(k.reshape(-1, 128), S, cb, bits, cbt).reshape(Hkv, T * B, 50)
+    v_rec = oracle.encode_deep(v.reshape(-1, 128), S, cb, bits, cbt).reshape(Hkv, T * B, 50)
+    wk = synth.kv_stream(B * W, Hkv, 63).float().numpy().astype(np.float64).reshape(Hkv, B, W, 128).transpose(1, 0, 2, 3)
+    wv = synth.kv_stream(B * W, Hkv, 64).float().numpy().astype(np.float64).reshape(Hkv, B, W, 128).transpose(1, 0, 2, 3)
+    q = synth.queries(B, 2 * Hkv, 65).float().numpy().astype(np.float64)
+    starts, lens = np.array([0, T], np.int64), np.array([T, T - 4], np.int32)
+    scale = 1 / math.sqrt(128)
+    full = oracle.attention_hybrid_deep(q, k_rec, v_rec, starts, lens, wk, wv, np.array([W, W - 2]), S, cb, bits, cbt, scale)
+    none = oracle.attention_hybrid_deep(q, k_rec, v_rec, starts, lens, wk, wv, np.array([0, 0]), S, cb, bits, cbt, scale)
+    assert np.max(np.abs(none - oracle.attention_deep(q, k_rec, v_rec, starts, lens, S, cb, bits, cbt, scale))) <= 1e-12
+    only = oracle.attention_hybrid_deep(q, k_rec, v_rec, starts, np.array([0, 0], np.int32), wk, wv, np.array([W, W - 2]), S, cb,
+                                        bits, cbt, scale)
+    for b, w in ((0, W), (1, W - 2)):
+        for h in range(2 * Hkv):
+            ref = oracle.attention_exact(q[b, h:h + 1], wk[b, h // 2, :w], wv[b, h // 2, :w], scale)[0]
+            assert np.max(np.abs(only[b, h] - ref)) <= 1e-12
+            # merge of the two parts with their log-sum-exp weights
+            Kp = oracle.decode_deep(k_rec[h // 2, starts[b]:starts[b] + lens[b]], S, cb, bits, cbt)
+            lse_p = scipy.special.logsumexp(Kp @ q[b, h] * scale)
+            lse_w = scipy.special.logsumexp(wk[b, h // 2, :w] @ q[b, h] * scale)
+            a = 1 / (1 + math.exp(lse_w - lse_p))
+            assert np.max(np.abs(full[b, h] - (a * none[b, h] + (1 - a) * only[b, h]))) <= 1e-12
