@@ -228,27 +228,16 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
     const int lane = threadIdx.x & 63;
     /* same value in all lanes: keeps the item geometry and the tile pointers in scalar registers */
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    for (int c = threadIdx.x; c < kSChunks; c += kThreads) sS[c] = a.S_bf16x3[c];
-    __syncthreads();
-
-    Thresholds th = load_thresholds(*a.consts, NTERMS == 1 ? 0.08838834764831845f /* 1/sqrt(128) */ : 1.0f);
-    __shared__ PqDeviceConsts::Lut1Cell sLut[GENERAL ? 512 : 1];
-    if (GENERAL) {
-        for (int c = threadIdx.x; c < 512; c += kThreads) sLut[c] = a.consts->lut1[c];
-        th.lut1 = sLut;
-        __syncthreads();
-    }
-
-    UpperTables ut = {};
-    if (DEEP) ut = load_upper_tables(*a.consts);
-
-    uint32_t *img = sImg[wave];
     const int j = lane & 31, H = lane >> 5; /* vector within the 32-vector group, lane half */
 
     /* bf16 input: both 32-vector halves of the tile share every A-operand fetch (halves the
        LDS traffic); fp32 input carries three bf16 terms per value and goes one half at a time */
     constexpr int NXT = (XT == PQ_BF16) ? 1 : 3; /* bf16 terms of x */
     constexpr int NVT = (XT == PQ_BF16) ? 2 : 1; /* 32-vector halves per pass */
+    /* bf16 input: the operand registers of a tile are dead once its last row tile has been multiplied,
+       so the next tile's rows are requested then, under the last quantisation stage, and the first
+       tile's before S is staged */
+    constexpr bool kPipelined = (XT == PQ_BF16);
     BOperand xb[NVT][NXT][8];
 
     /* which tile and which source rows an item covers */
@@ -277,8 +266,47 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
         const int64_t t_src = g.src_t0 + (ok ? tau_ - g.tau_lo : 0);
         return t_src * a.ld_token + (int64_t)g.head * a.ld_head;
     };
-    const int64_t item_stride = (int64_t)gridDim.x * kWaves;
-    const int64_t item0 = (int64_t)blockIdx.x * kWaves + wave;
+    /* B operands of a bf16 tile: this lane's 8-coordinate slices of its two vectors, every k-step
+       (coordinates 64 H + 8 ks .. + 7: one contiguous half row per lane) */
+    auto load_bf16_rows = [&](const Geometry &g) {
+        if constexpr (XT == PQ_BF16) {
+#pragma unroll
+            for (int v = 0; v < NVT; ++v) {
+                const int64_t row = source_row(g, 32 * v + j);
+                const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.x) + row);
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) xb[v][0][ks].q = xr[8 * H + ks];
+            }
+        }
+    };
+    const int64_t item_stride = (int64_t)gridDim.x * (EncodeShape<XT>::waves);
+    const int64_t item0 = (int64_t)blockIdx.x * (EncodeShape<XT>::waves) + wave;
+    if (kPipelined && item0 < a.n_items) load_bf16_rows(geometry(item0));
+
+    {   /* all of a thread's chunks are requested before the first one is stored: one round trip to L2
+           instead of one per chunk */
+        constexpr int kPerThread = kSChunks / kThreads;
+        static_assert(kSChunks % kThreads == 0, "S chunks must divide evenly over the workgroup");
+        uint4 stage[kPerThread];
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) stage[i] = a.S_bf16x3[threadIdx.x + i * kThreads];
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) sS[threadIdx.x + i * kThreads] = stage[i];
+    }
+    __syncthreads();
+
+    Thresholds th = load_thresholds(*a.consts, NTERMS == 1 ? 0.08838834764831845f /* 1/sqrt(128) */ : 1.0f);
+    __shared__ PqDeviceConsts::Lut1Cell sLut[GENERAL ? 512 : 1];
+    if (GENERAL) {
+        for (int c = threadIdx.x; c < 512; c += kThreads) sLut[c] = a.consts->lut1[c];
+        th.lut1 = sLut;
+        __syncthreads();
+    }
+
+    UpperTables ut = {};
+    if (DEEP) ut = load_upper_tables(*a.consts);
+
+    uint32_t *img = sImg[wave];
 
     for (int64_t item = item0; item < a.n_items; item += item_stride) {
         const Geometry geo = geometry(item);
@@ -313,12 +341,8 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
                 valid[v] = tau[v] >= tau_lo && tau[v] < tau_hi;
                 /* ---- B operands: this lane's 8-coordinate slices of its vector, every k-step
                    (coordinates 64 H + 8 ks .. + 7: one contiguous half row per lane) ---- */
-                const int64_t row = source_row(geo, tau[v]);
-                if constexpr (XT == PQ_BF16) {
-                    const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.x) + row);
-#pragma unroll
-                    for (int ks = 0; ks < 8; ++ks) xb[v][0][ks].q = xr[8 * H + ks];
-                } else {
+                if constexpr (XT != PQ_BF16) { /* bf16 rows were requested ahead (load_bf16_rows) */
+                    const int64_t row = source_row(geo, tau[v]);
                     const float4 *xr = reinterpret_cast<const float4 *>(static_cast<const float *>(a.x) + row);
 #pragma unroll
                     for (int ks = 0; ks < 8; ++ks) {
@@ -361,6 +385,7 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
                 f32x16 (&cur)[NVT] = (st & 1) ? acc_odd : acc_even;   /* row tile st: quantised now */
                 f32x16 (&nxt)[NVT] = (st & 1) ? acc_even : acc_odd;   /* row tile st+1: accumulated now */
                 const bool mul = st < 3, quant = st >= 0;
+                if (kPipelined && st == 3 && item + item_stride < a.n_items) load_bf16_rows(geometry(item + item_stride));
                 PolarState ps[NVT];
                 BOperand sa_next;
                 if (mul) sa_next.q = sS[(((NTERMS - 1) * 4 + (st + 1)) * 8 + 0) * 64 + lane];

@@ -48,7 +48,18 @@ __global__ __launch_bounds__(kFitThreads) void pq_angle_histogram_kernel(FitArgs
     __shared__ float sy[kTileVecs][PQ_D + 4]; /* +4: the 16-float rows of different vectors start in different banks */
     __shared__ uint32_t sh[kHistSize];
     const int tid = threadIdx.x;
-    for (int c = tid; c < PQ_D * PQ_D; c += kFitThreads) sS[c] = a.S[c];
+    {   /* S: 16 float4 per thread, requested in two batches of 8 before they are stored */
+        const float4 *src = reinterpret_cast<const float4 *>(a.S);
+        float4 *dst = reinterpret_cast<float4 *>(sS);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            float4 stage[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) stage[i] = src[tid + (8 * half + i) * kFitThreads];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dst[tid + (8 * half + i) * kFitThreads] = stage[i];
+        }
+    }
     for (int c = tid; c < kHistSize; c += kFitThreads) sh[c] = 0u;
     __syncthreads();
 
