@@ -133,6 +133,21 @@ __device__ __forceinline__ uint32_t from_odd_even_neighbour(uint32_t x)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false);
 }
 
+/* For lanes of rows 0 and 2 (16-lane rows): the value held by the lane 16 further on; the lanes of
+ * rows 1 and 3 get their own value back.  One row-swap instruction of the vector ALU instead of a
+ * trip through the LDS crossbar. */
+__device__ __forceinline__ uint32_t from_next_row(uint32_t x)
+{
+    return __builtin_amdgcn_permlane16_swap(x, x, false, false)[1];
+}
+
+/* lanes 0..31: the value of lane + 32; lanes 32..63: the value of lane - 32 */
+__device__ __forceinline__ uint32_t from_other_half(uint32_t x, int upper_half)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return upper_half ? r[0] : r[1];
+}
+
 /* four 24-bit chunks -> the three dwords of a lane's 96-bit G6 string */
 __device__ __forceinline__ void store_chunks96(uint32_t *dst, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3)
 {
@@ -164,7 +179,7 @@ __device__ __forceinline__ void emit_key_pair(uint32_t *img, int j, int H, int s
         if (!DEEP) img[PQL_CODE_BYTES / 4 + lam * 4 + i] = even.rad[v] | ((uint32_t)odd[v].radius << 16);
         const uint32_t chunk = even.g12[v] | ((odd[v].g0 | (odd[v].g1 << 6)) << 12);
         P[v] = chunk | ((even.c4[v] | (odd[v].c4 << 2)) << 24);
-        Q[v] = (uint32_t)__shfl_xor((int)P[v], 16);
+        Q[v] = from_next_row(P[v]); /* used by the lanes of rows 0 and 2 only */
     }
     if ((j >> 4) == 0) { /* chunks 0 and 2 are this lane's, 1 and 3 the partner's */
         store_chunks96(img + (PQL_OFF_G6 >> 2) + 3 * lam, P[0], Q[0], P[1], Q[1]);
@@ -196,8 +211,8 @@ __device__ __forceinline__ void emit_value_full(uint32_t *img, int j, int b, con
         }
         P0[v] = quad_or((bc[v].g0 << (6 * e)) | (bc[v].c4 << (24 + 2 * e)));
         P1[v] = quad_or(bc[v].g1 << (6 * e));
-        Q0[v] = (uint32_t)__shfl_xor((int)P0[v], 16);
-        Q1[v] = (uint32_t)__shfl_xor((int)P1[v], 16);
+        Q0[v] = from_next_row(P0[v]); /* used by the lanes of rows 0 and 2 only */
+        Q1[v] = from_next_row(P1[v]);
     }
     if (jhi == 0) { /* this quad holds chunks 0 and 2, the other one chunks 1 and 3 */
         if (e == 0) store_chunks96(img + (PQL_OFF_G6 >> 2) + 3 * lam0, P0[0], Q0[0], P0[1], Q0[1]);
@@ -479,8 +494,8 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
                 for (int v = 0; v < NVT; ++v) {
                     const UpperHalf mine = polar_upper_half(q4[v], H, ut);
                     UpperHalf other;
-                    other.codes = (uint32_t)__shfl_xor((int)mine.codes, 32);
-                    other.q6 = __shfl_xor(mine.q6, 32);
+                    other.codes = from_other_half(mine.codes, H);
+                    other.q6 = __uint_as_float(from_other_half(__float_as_uint(mine.q6), H));
                     const uint32_t word = H == 0 ? polar_upper_join(mine, other, th.radius_scale, ut)
                                                  : polar_upper_join(other, mine, th.radius_scale, ut);
                     if (H == 0 && valid[v]) img[PQL_CODE_BYTES / 4 + tau[v]] = word;
