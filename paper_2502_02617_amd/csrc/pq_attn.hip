@@ -282,32 +282,60 @@ struct VTileRaw {
     uint32_t top;     /* depth 7 instead of rad0, rad1: radius-plane word of token `lane` */
 };
 
-template <bool DEEP>
-__device__ __forceinline__ void load_k_tile(KTileRaw &t, const uint8_t *codes, const uint16_t *radii, int lane)
+/* The tiles of one (sequence, kv head) stream are read through buffer descriptors: the address of a
+ * field is (descriptor base, scalar tile offset, 32-bit lane offset), so no 64-bit per-lane address
+ * registers are carried through the tile loop, and a read beyond the stream's tiles returns zero
+ * instead of touching memory. */
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t stream_descriptor(const void *base, uint32_t bytes)
 {
-    t.l1a = *reinterpret_cast<const uint4 *>(codes + PQL_OFF_L1A + lane * 16);
-    t.l1b = *reinterpret_cast<const uint4 *>(codes + PQL_OFF_L1B + lane * 16);
-    const uint32_t *g = reinterpret_cast<const uint32_t *>(codes + PQL_OFF_G6 + lane * 12);
-    t.g0 = g[0]; t.g1 = g[1]; t.g2 = g[2];
-    t.c4 = *reinterpret_cast<const uint16_t *>(codes + PQL_OFF_C4 + lane * 2);
-    if (DEEP) t.top = reinterpret_cast<const uint32_t *>(radii)[lane];
-    else t.rad = *reinterpret_cast<const uint4 *>(radii + lane * 8);
+    /* raw buffer (stride 0), 32-bit data format word as for every untyped dword access on this family */
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ uint4 load16(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t tile_off)
+{
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, tile_off, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+/* The lane offsets are recomputed for every tile from the lane number (a handful of shifts), which the
+ * empty asm statement hides from loop-invariant code motion: hoisted, they would cost more registers
+ * than the kernel has and come back as spills inside the tile loop.  Plane offsets ride on the scalar
+ * tile offset. */
+template <bool DEEP>
+__device__ __forceinline__ void load_k_tile(KTileRaw &t, __amdgpu_buffer_rsrc_t codes, __amdgpu_buffer_rsrc_t radii,
+                                            uint32_t tile, uint32_t lane)
+{
+    asm volatile("" : "+v"(lane));
+    const uint32_t co = tile * PQL_CODE_BYTES;
+    t.l1a = load16(codes, lane * 16u, co + PQL_OFF_L1A);
+    t.l1b = load16(codes, lane * 16u, co + PQL_OFF_L1B);
+    const u32x3 g = __builtin_amdgcn_raw_buffer_load_b96(codes, lane * 12u, co + PQL_OFF_G6, 0);
+    t.g0 = g.x; t.g1 = g.y; t.g2 = g.z;
+    t.c4 = __builtin_amdgcn_raw_buffer_load_b16(codes, lane * 2u, co + PQL_OFF_C4, 0);
+    if (DEEP) t.top = __builtin_amdgcn_raw_buffer_load_b32(radii, lane * 4u, tile * (PQ_DEEP_RADII_HALVES * 2u), 0);
+    else t.rad = load16(radii, lane * 16u, tile * (PQL_RADII * 2u));
 }
 
 template <bool DEEP>
-__device__ __forceinline__ void load_v_tile(VTileRaw &t, const uint8_t *codes, const uint16_t *radii, int lane)
+__device__ __forceinline__ void load_v_tile(VTileRaw &t, __amdgpu_buffer_rsrc_t codes, __amdgpu_buffer_rsrc_t radii,
+                                            uint32_t tile, uint32_t lane)
 {
-    t.l1a = *reinterpret_cast<const uint4 *>(codes + PQL_OFF_L1A + lane * 16);
-    t.l1b = *reinterpret_cast<const uint4 *>(codes + PQL_OFF_L1B + lane * 16);
-    const uint32_t *g = reinterpret_cast<const uint32_t *>(codes + PQL_OFF_G6 + lane * 12);
-    t.g0 = g[0]; t.g1 = g[1]; t.g2 = g[2];
-    t.c4 = *reinterpret_cast<const uint32_t *>(codes + PQL_OFF_C4 + (lane >> 1) * 4);
+    asm volatile("" : "+v"(lane));
+    const uint32_t co = tile * PQL_CODE_BYTES;
+    t.l1a = load16(codes, lane * 16u, co + PQL_OFF_L1A);
+    t.l1b = load16(codes, lane * 16u, co + PQL_OFF_L1B);
+    const u32x3 g = __builtin_amdgcn_raw_buffer_load_b96(codes, lane * 12u, co + PQL_OFF_G6, 0);
+    t.g0 = g.x; t.g1 = g.y; t.g2 = g.z;
+    t.c4 = __builtin_amdgcn_raw_buffer_load_b32(codes, (lane >> 1) * 4u, co + PQL_OFF_C4, 0);
     if (DEEP) {
-        t.top = reinterpret_cast<const uint32_t *>(radii)[lane];
+        t.top = __builtin_amdgcn_raw_buffer_load_b32(radii, lane * 4u, tile * (PQ_DEEP_RADII_HALVES * 2u), 0);
     } else {
-        const uint4 *r = reinterpret_cast<const uint4 *>(radii + (lane >> 1) * 16);
-        t.rad0 = r[0];
-        t.rad1 = r[1];
+        t.rad0 = load16(radii, (lane >> 1) * 32u, tile * (PQL_RADII * 2u));
+        t.rad1 = load16(radii, (lane >> 1) * 32u, tile * (PQL_RADII * 2u) + 16u);
     }
 }
 
@@ -579,11 +607,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, DEEP ? 3 : (NG == 1 ? 4 : (NG 
 
     const int g = lane >> 4, n = lane & 15;
     const int64_t seq_tile0 = a.seq_start[b] >> 6;
-    const uint8_t *kc = a.k_codes + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_CODE_BYTES;
-    const uint8_t *vc = a.v_codes + ((int64_t)hk * a.pool_tiles + seq_tile0) * PQL_CODE_BYTES;
     constexpr int kRadiiHalves = DEEP ? PQ_DEEP_RADII_HALVES : PQL_RADII;
-    const uint16_t *kr = a.k_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * kRadiiHalves;
-    const uint16_t *vr = a.v_radii + ((int64_t)hk * a.pool_tiles + seq_tile0) * kRadiiHalves;
+    const int64_t stream_tile0 = (int64_t)hk * a.pool_tiles + seq_tile0;
+    /* descriptors of this sequence's tiles in the four planes (the context is at most 2^31 tokens: 32-bit sizes) */
+    const uint32_t code_bytes = (uint32_t)n_tiles * PQL_CODE_BYTES, radii_bytes = (uint32_t)n_tiles * (kRadiiHalves * 2u);
+    const __amdgpu_buffer_rsrc_t kc = stream_descriptor(a.k_codes + stream_tile0 * PQL_CODE_BYTES, code_bytes);
+    const __amdgpu_buffer_rsrc_t vc = stream_descriptor(a.v_codes + stream_tile0 * PQL_CODE_BYTES, code_bytes);
+    const __amdgpu_buffer_rsrc_t kr = stream_descriptor(a.k_radii + stream_tile0 * kRadiiHalves, radii_bytes);
+    const __amdgpu_buffer_rsrc_t vr = stream_descriptor(a.v_radii + stream_tile0 * kRadiiHalves, radii_bytes);
     const DeepRadii dr{sKrad[DEEP ? wave : 0], sVrad[DEEP ? wave : 0], a.up_b5, a.up_b6, a.up_b7};
 
     /* ---- q' operands: in group k, columns n < 8 = (pair 4k + (n&3), parity (n>>2)&1) hold the
@@ -591,7 +622,6 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, DEEP ? 3 : (NG == 1 ? 4 : (NG 
      * scores to ~22 bits at no extra matrix instruction; pair p = (query token p / G, head p % G);
      * slice s = rotated coordinates 32*g + 8*s .. +8 ---- */
     H8 qb[NG][4];
-    int lim_abs[NG]; /* tokens of the sequence that this lane's pair of group k may see */
 #pragma unroll
     for (int k = 0; k < NG; ++k) {
         const int pair = 4 * k + (n & 3);
@@ -601,7 +631,6 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, DEEP ? 3 : (NG == 1 ? 4 : (NG 
             a.qrot + ((((int64_t)b * a.M + m) * a.Hq + hk * G + head) * 2 + (n >> 3)) * PQ_D + 32 * g);
 #pragma unroll
         for (int s = 0; s < 4; ++s) qb[k][s].q = real ? qp[s] : make_uint4(0, 0, 0, 0);
-        lim_abs[k] = ctx - (a.M - 1 - m);
     }
     const uint32_t parity_shift = (n & 4) ? 16u : 0u;
     const int t4b = kT4B + ((n & 1) ? 4 : 0);
@@ -625,8 +654,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, DEEP ? 3 : (NG == 1 ? 4 : (NG 
     const int n_full = min(tile_hi, max(ctx - (a.M - 1), 0) >> 6);
     KTileRaw kraw;
     VTileRaw vraw;
-    load_k_tile<DEEP>(kraw, kc + (int64_t)tile_lo * PQL_CODE_BYTES, kr + (int64_t)tile_lo * kRadiiHalves, lane);
-    load_v_tile<DEEP>(vraw, vc + (int64_t)tile_lo * PQL_CODE_BYTES, vr + (int64_t)tile_lo * kRadiiHalves, lane);
+    load_k_tile<DEEP>(kraw, kc, kr, tile_lo, lane);
+    load_v_tile<DEEP>(vraw, vc, vr, tile_lo, lane);
     int tile = tile_lo;
     {
         int lim[NG];
@@ -643,16 +672,20 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, DEEP ? 3 : (NG == 1 ? 4 : (NG 
             attend_pass<2, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
             attend_pass<3, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
             if (tile + 1 < tile_hi) {
-                load_k_tile<DEEP>(kraw, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * kRadiiHalves, lane);
-                load_v_tile<DEEP>(vraw, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * kRadiiHalves, lane);
+                load_k_tile<DEEP>(kraw, kc, kr, tile + 1, lane);
+                load_v_tile<DEEP>(vraw, vc, vr, tile + 1, lane);
             }
         }
     }
     for (; tile < tile_hi; ++tile) { /* the masked tiles at the end of the sequence */
         const int nv = min(ctx - tile * 64, 64);
-        int lim[NG];
+        int lim[NG]; /* tokens of this tile that this lane's pair of group k may see */
 #pragma unroll
-        for (int k = 0; k < NG; ++k) lim[k] = lim_abs[k] - tile * 64;
+        for (int k = 0; k < NG; ++k) {
+            const int pair = 4 * k + (n & 3);
+            const int m = pair < a.M * G ? pair / G : 0;
+            lim[k] = ctx - (a.M - 1 - m) - tile * 64;
+        }
         if (DEEP) {
             wave_lds_fence();
             expand_deep_radii(tab, dr, kraw.top, vraw.top, lane);
@@ -663,8 +696,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, DEEP ? 3 : (NG == 1 ? 4 : (NG 
         attend_pass<2, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
         attend_pass<3, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
         if (tile + 1 < tile_hi) {
-            load_k_tile<DEEP>(kraw, kc + (int64_t)(tile + 1) * PQL_CODE_BYTES, kr + (int64_t)(tile + 1) * kRadiiHalves, lane);
-            load_v_tile<DEEP>(vraw, vc + (int64_t)(tile + 1) * PQL_CODE_BYTES, vr + (int64_t)(tile + 1) * kRadiiHalves, lane);
+            load_k_tile<DEEP>(kraw, kc, kr, tile + 1, lane);
+            load_v_tile<DEEP>(vraw, vc, vr, tile + 1, lane);
         }
     }
 
