@@ -564,7 +564,7 @@ __device__ __forceinline__ void attend_pass(const uint32_t *tab, const KTileRaw 
  * M * G <= 4 * NG.  Query token m of a sequence is its (M-1-m)-th newest token and sees
  * the cache up to and including its own key: ctx - (M-1-m) tokens. */
 template <int G, int NG, bool DEEP>
-__global__ __launch_bounds__(kWavesPerBlock * 64, DEEP ? 3 : (NG == 1 ? 4 : (NG == 2 ? 3 : 2))) void pq_attn_partial_kernel(AttnArgs a)
+__global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2)) void pq_attn_partial_kernel(AttnArgs a)
 {
     __shared__ uint32_t tab[kTabDwords];
     __shared__ float sKrad[DEEP ? kWavesPerBlock : 1][DEEP ? 512 : 1];
