@@ -240,7 +240,8 @@ pq_status pq_export_canonical(const pq_ctx *ctx, pq_kind kind, const uint8_t *co
  * query attends to all ctx_len[b] cached tokens (its own key/value are
  * appended before the call).  Query head h reads KV head h / (Hq/Hkv);
  * Hq/Hkv must be 1, 2, 4 or 8.  ctx_len[b] == 0 gives a zero output row.
- * max_ctx (host) bounds every ctx_len[b]; it sizes the launch.
+ * max_ctx (host) bounds every ctx_len[b]; it sizes the launch; at most 2^26
+ * tokens (PQ_EUNSUPPORTED beyond).
  * workspace (device): at least pq_attn_workspace_bytes(B, Hq, Hkv, max_ctx)
  * bytes, PQ_ENOMEM otherwise; contents need not be preserved between calls.
  * ------------------------------------------------------------------------- */

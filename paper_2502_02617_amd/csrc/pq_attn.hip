@@ -1096,6 +1096,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || pool_tokens <= 0 || (pool_tokens & 63) || max_ctx < 0 || max_ctx > pool_tokens)
         return PQ_EINVAL;
     if (Hq % Hkv) return PQ_EINVAL;
+    if (max_ctx > ((int64_t)1 << 26)) return PQ_EUNSUPPORTED; /* a sequence's tiles are addressed with 32-bit byte offsets */
     if (out_dtype != PQ_BF16 && out_dtype != PQ_F32) return PQ_EINVAL;
     const int G = Hq / Hkv;
     if (G != 1 && G != 2 && G != 4 && G != 8) return PQ_EUNSUPPORTED;
