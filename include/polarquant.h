@@ -141,10 +141,9 @@ size_t pq_fit_workspace_bytes(void);
  * have pq_record_bytes(ctx) bytes (62; 50 = bytes 0..45 as before, the 16-bit code word
  * little endian, the radius little endian).  Like pq_set_codebooks this must precede the
  * first launch with the context (PQ_EINVAL afterwards).  At depth 7 pq_encode_kv,
- * pq_append_kv(_pair), pq_decode_kv, pq_export_canonical, pq_attn_decode_polar,
- * pq_decode_step_polar and pq_attn_decode_hybrid follow the new format (Hq/Hkv <= 4);
- * pq_attn_decode_polar_mq returns PQ_EUNSUPPORTED.  Full depth and pq_set_codebooks
- * exclude each other: whichever is called second returns PQ_EUNSUPPORTED. */
+ * pq_append_kv(_pair), pq_decode_kv, pq_export_canonical and every attention entry
+ * point follow the new format.  Full depth and pq_set_codebooks exclude each other:
+ * whichever is called second returns PQ_EUNSUPPORTED. */
 pq_status pq_set_recursion_depth(pq_ctx *ctx, int depth, const int *upper_bits);
 int pq_recursion_depth(const pq_ctx *ctx);
 int pq_radii_halves_per_tile(const pq_ctx *ctx);

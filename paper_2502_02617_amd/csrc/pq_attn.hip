@@ -1074,14 +1074,19 @@ struct StepWindow {
     int64_t win_cap;
 };
 
+template <int G, bool DEEP>
+void launch_partial_depth(int NG, dim3 grid, dim3 blk, hipStream_t s, const AttnArgs &aa)
+{
+    if (NG == 1) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 1, DEEP>), grid, blk, 0, s, aa);
+    else if (NG == 2) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 2, DEEP>), grid, blk, 0, s, aa);
+    else hipLaunchKernelGGL((pq_attn_partial_kernel<G, 4, DEEP>), grid, blk, 0, s, aa);
+}
+
 template <int G>
 void launch_partial(int NG, bool deep, dim3 grid, dim3 blk, hipStream_t s, const AttnArgs &aa)
 {
-    if (deep) { /* NG == 1 checked by the caller, which excludes G == 8 */
-        if constexpr (G <= 4) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 1, true>), grid, blk, 0, s, aa);
-    } else if (NG == 1) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 1, false>), grid, blk, 0, s, aa);
-    else if (NG == 2) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 2, false>), grid, blk, 0, s, aa);
-    else hipLaunchKernelGGL((pq_attn_partial_kernel<G, 4, false>), grid, blk, 0, s, aa);
+    if (deep) launch_partial_depth<G, true>(NG, grid, blk, s, aa);
+    else launch_partial_depth<G, false>(NG, grid, blk, s, aa);
 }
 
 pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const StepWindow *win, int M, const void *q,
@@ -1104,7 +1109,6 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     if ((app || win) && (M != 1 || G == 8)) return PQ_EUNSUPPORTED;
     const int NG = M * G <= 4 ? 1 : (M * G <= 8 ? 2 : 4);
     const bool deep = ctx->depth == 7;
-    if (deep && NG != 1) return PQ_EUNSUPPORTED; /* full depth: one query token, at most 4 query heads per kv head */
     if (!pq_aligned16(q) || !pq_aligned16(out) || !pq_aligned16(k_codes) || !pq_aligned16(k_radii) ||
         !pq_aligned16(v_codes) || !pq_aligned16(v_radii) || !pq_aligned16(workspace))
         return PQ_EALIGN;
@@ -1171,7 +1175,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     const unsigned blocks = (unsigned)((items + kWavesPerBlock - 1) / kWavesPerBlock);
     pq_prof_before(0, s);
     const dim3 grid(blocks), blk(kWavesPerBlock * 64);
-    if (G == 8) launch_partial<8>(NG, false, grid, blk, s, aa); /* deep was rejected above: NG == 2 */
+    if (G == 8) launch_partial<8>(NG, deep, grid, blk, s, aa);
     else if (G == 4) launch_partial<4>(NG, deep, grid, blk, s, aa);
     else if (G == 2) launch_partial<2>(NG, deep, grid, blk, s, aa);
     else launch_partial<1>(NG, deep, grid, blk, s, aa);

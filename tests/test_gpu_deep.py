@@ -221,7 +221,7 @@ def test_deep_hybrid_attention():
     assert max(per_seq) <= 2e-3 and per_seq[0] <= 1e-5     # sequence 1 is window only: fp32 accuracy
 
 
-def test_deep_decode_step_and_unsupported_paths():
+def test_deep_decode_step():
     bits = (2, 2, 2)
     ctx, S, cb, cbt = make(bits)
     Hq, Hkv, lens = 8, 2, [130, 64, 700]
@@ -253,9 +253,37 @@ def test_deep_decode_step_and_unsupported_paths():
     err = helpers.rel_l2(out.cpu().numpy(), ref)
     say(f"  rel L2 {err:.2e}")
     assert err <= 2e-3
-    # entry points that have no full-depth form say so
-    with pytest.raises(PolarQuantError):
-        qm = synth.queries(B * 2, Hq, seed=1).reshape(B, 2, Hq, 128).contiguous().to(DEV)
-        om = torch.empty((B, 2, Hq, 128), dtype=torch.float32, device=DEV)
-        wm = torch.empty(Context.attn_mq_workspace_bytes(B, 2, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
-        ctx.attn_decode_polar_mq(qm, om, kc, kt, vc, vt, d_start, d_len, max(lens), helpers.softmax_scale(), wm)
+
+
+@pytest.mark.parametrize("M,Hq,Hkv", [(2, 8, 2), (4, 4, 1), (1, 16, 2), (3, 2, 2)])
+def test_deep_multi_query_attention(M, Hq, Hkv):
+    """Several query tokens per sequence (and groups of 8 query heads) on depth-7 caches: row (b, m) is
+    single-query attention over the first ctx_len - (M-1-m) cached tokens."""
+    bits = (2, 2, 2)
+    ctx, S, cb, cbt = make(bits)
+    lens = [M, 64, 65 + M, 1000, 64 * 5 + 1]
+    say(f"deep multi-query attention M={M} Hq={Hq} Hkv={Hkv} lens={lens}")
+    B = len(lens)
+    caches, starts, pool, k_rec, v_rec = build_cache(ctx, S, cb, bits, cbt, lens, Hkv, seed=1600 + M)
+    kc, kt, vc, vt = caches
+    q = synth.queries(B * M, Hq, seed=1601).reshape(B, M, Hq, 128).contiguous()
+    out = torch.full((B, M, Hq, 128), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(Context.attn_mq_workspace_bytes(B, M, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)
+    ctx.attn_decode_polar_mq(q.to(DEV), out, kc, kt, vc, vt, torch.from_numpy(starts).to(DEV),
+                             torch.tensor(lens, dtype=torch.int32, device=DEV), max(lens), helpers.softmax_scale(), ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    errs = []
+    for m in range(M):
+        lens_m = np.array([max(n - (M - 1 - m), 0) for n in lens], dtype=np.int32)
+        ref = oracle.attention_deep(q[:, m].to(torch.float64).numpy(), k_rec, v_rec, starts, lens_m, S, cb, bits, cbt,
+                                    helpers.softmax_scale())
+        errs.append(helpers.rel_l2(got[:, m], ref))
+        for b in range(B):
+            if lens_m[b] == 0:
+                assert np.all(got[b, m] == 0.0)
+            else:
+                assert helpers.rel_l2(got[b, m], ref[b]) <= 2e-3, (b, m)
+    say(f"  rel L2 per query token {['%.1e' % e for e in errs]}")
