@@ -142,8 +142,8 @@ size_t pq_fit_workspace_bytes(void);
  * little endian, the radius little endian).  Like pq_set_codebooks this must precede the
  * first launch with the context (PQ_EINVAL afterwards).  At depth 7 pq_encode_kv,
  * pq_append_kv(_pair), pq_decode_kv, pq_export_canonical and every attention entry
- * point follow the new format.  Full depth and pq_set_codebooks exclude each other:
- * whichever is called second returns PQ_EUNSUPPORTED. */
+ * point follow the new format; pq_set_codebooks (levels 1..4) combines with it, the
+ * codebooks of levels 5..7 stay the analytic ones. */
 pq_status pq_set_recursion_depth(pq_ctx *ctx, int depth, const int *upper_bits);
 int pq_recursion_depth(const pq_ctx *ctx);
 int pq_radii_halves_per_tile(const pq_ctx *ctx);

@@ -569,8 +569,10 @@ pq_status dispatch_encode_terms(const EncodeArgs &a, pq_dtype xt, pq_kind kind, 
 pq_status dispatch_encode(const EncodeArgs &a, pq_dtype xt, pq_kind kind, bool unit_entries, bool general, bool deep,
                           hipStream_t stream)
 {
-    if (deep) { /* full depth comes with the analytic codebooks only */
-        if (general) return PQ_EUNSUPPORTED;
+    if (deep) {
+        if (general)
+            return unit_entries ? dispatch_encode_terms<1, true, true>(a, xt, kind, stream)
+                                : dispatch_encode_terms<3, true, true>(a, xt, kind, stream);
         return unit_entries ? dispatch_encode_terms<1, false, true>(a, xt, kind, stream)
                             : dispatch_encode_terms<3, false, true>(a, xt, kind, stream);
     }

@@ -403,7 +403,6 @@ extern "C" pq_status pq_set_codebooks(pq_ctx *ctx, const double *cb)
     std::lock_guard<std::mutex> lock(ctx->mu);
     for (int i = 0; i < PQ_MAX_DEVICES; ++i)
         if (ctx->dev[i].ready) return PQ_EINVAL; /* tables already on a device: the context is in use */
-    if (ctx->depth == 7) return PQ_EUNSUPPORTED; /* full depth comes with the analytic codebooks */
     const int off[4] = {0, 16, 20, 24}, K[4] = {16, 4, 4, 4};
     const double hi[4] = {2.0 * kPi, kPi / 2.0, kPi / 2.0, kPi / 2.0};
     for (int l = 0; l < 4; ++l)
@@ -440,7 +439,6 @@ extern "C" pq_status pq_set_recursion_depth(pq_ctx *ctx, int depth, const int *u
     for (int i = 0; i < PQ_MAX_DEVICES; ++i)
         if (ctx->dev[i].ready) return PQ_EINVAL; /* tables already on a device: the context is in use */
     if (depth == 7) {
-        if (ctx->general_codebooks) return PQ_EUNSUPPORTED; /* full depth comes with the analytic codebooks */
         if (!upper_bits) return PQ_EINVAL;
         for (int l = 0; l < 3; ++l)
             if (upper_bits[l] < 1 || upper_bits[l] > 3) return PQ_EINVAL;

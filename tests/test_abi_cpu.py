@@ -192,12 +192,11 @@ def test_recursion_depth_validation_and_upper_codebooks():
             assert np.max(np.abs(bnd[1:-1] - 0.5 * (cen[:-1] + cen[1:]))) <= 1e-15
     ctx.set_recursion_depth(4)
     assert ctx.record_bytes() == 62
-    # caller-set codebooks and full depth exclude each other, whichever comes second
-    with pytest.raises(PolarQuantError):
-        deep = Context(seed=0)
-        deep.set_recursion_depth(7, [2, 2, 2])
-        deep.set_codebooks(oracle.default_codebooks())
-    with pytest.raises(PolarQuantError):
-        gen = Context(seed=0)
-        gen.set_codebooks(oracle.default_codebooks())
-        gen.set_recursion_depth(7, [2, 2, 2])
+    # caller-set codebooks (levels 1-4) and full depth combine, in either order
+    deep = Context(seed=0)
+    deep.set_recursion_depth(7, [2, 2, 2])
+    deep.set_codebooks(oracle.default_codebooks())
+    gen = Context(seed=0)
+    gen.set_codebooks(oracle.default_codebooks())
+    gen.set_recursion_depth(7, [2, 2, 2])
+    assert deep.record_bytes() == 50 and gen.record_bytes() == 50

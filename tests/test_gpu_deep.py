@@ -110,6 +110,53 @@ def test_deep_encode_hadamard_preconditioner():
     say(f"  {check_records(rec_gpu, rec_or, psi, y, bits)}")
 
 
+def test_deep_with_caller_set_codebooks():
+    """Full depth together with codebooks replaced for levels 1-4 (jittered centroids): encode, append and
+    attention follow both."""
+    bits = (2, 2, 2)
+    rng = np.random.default_rng(77)
+    cb = oracle.default_codebooks()
+    cb[:16] += rng.uniform(-0.05, 0.05, 16)
+    cb[16:] += rng.uniform(-0.03, 0.03, 12)
+    ctx = Context(seed=0)
+    ctx.set_codebooks(cb)
+    ctx.set_recursion_depth(7, bits)
+    S, cbt = oracle.preconditioner(0), oracle.upper_codebooks(bits)
+    T, H = 500, 2
+    say(f"deep + caller-set codebooks: T={T} H={H}")
+    for kind in (PQ_KEY, PQ_VALUE):
+        x = synth.kv_stream(T, H, seed=81 + kind).permute(1, 0, 2).contiguous()
+        codes, top = ctx.alloc_cache_for(H, 512, DEV)
+        codes.zero_()
+        top.zero_()
+        ctx.encode_kv(x[:490].to(DEV), kind, codes, top)
+        ctx.append_kv(x[490:].to(DEV).reshape(10, H, 128)[:1].contiguous(), kind, codes, top,
+                      torch.tensor([490], dtype=torch.int64, device=DEV))
+        torch.cuda.synchronize()
+        rec_gpu = export_both_ways(ctx, kind, codes, top, 0, 491)
+        rec_or, psi, y = oracle_records(x[:491], S, cb, bits, cbt)
+        # boundary distances are those of the jittered codebooks: compare codes directly, allow the tie rate
+        Jg, rg = oracle.unpack_deep(rec_gpu.reshape(-1, 50), bits)
+        Jo, ro = oracle.unpack_deep(rec_or.reshape(-1, 50), bits)
+        bad = Jg != Jo
+        say(f"  kind {kind}: {int(bad.sum())} code mismatches of {Jo.size}, {int((rg != ro).sum())} radius mismatches")
+        if bad.any():
+            tables = [cb[0:16], cb[16:20], cb[20:24], cb[24:28], cbt[0, :4], cbt[1, :4], cbt[2, :4]]
+            level = np.concatenate([np.full(64, 0), np.full(32, 1), np.full(16, 2), np.full(8, 3), np.full(4, 4), np.full(2, 5), [6]])
+            psi2 = psi.reshape(-1, 127)
+            for n_, a_ in zip(*np.nonzero(bad)):
+                t = tables[level[a_]]
+                mids = 0.5 * (t[:-1] + t[1:])
+                assert np.min(np.abs(mids - psi2[n_, a_])) <= helpers.ANGLE_TOL
+        assert bad.mean() <= helpers.CODE_MISMATCH_RATE
+        helpers.check_radii_deep(rg, ro, y.reshape(-1, 128))
+        out = torch.empty((491, H, 128), dtype=torch.float32, device=DEV)
+        ctx.decode_kv(kind, codes, top, 0, 491, out)
+        torch.cuda.synchronize()
+        for h in range(H):
+            assert helpers.rel_l2(out.cpu().numpy()[:, h], oracle.decode_deep(rec_gpu[h], S, cb, bits, cbt)) <= 1e-5
+
+
 def test_deep_offsets_and_append():
     bits = (2, 2, 2)
     ctx, S, cb, cbt = make(bits)
