@@ -200,3 +200,16 @@ def test_recursion_depth_validation_and_upper_codebooks():
     gen.set_codebooks(oracle.default_codebooks())
     gen.set_recursion_depth(7, [2, 2, 2])
     assert deep.record_bytes() == 50 and gen.record_bytes() == 50
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only: --gpus 2 exits with a message before anything touches a device."""
+    import os
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr and res.stdout.strip() == ""
