@@ -284,8 +284,8 @@ struct VTileRaw {
 
 /* The tiles of one (sequence, kv head) stream are read through buffer descriptors: the address of a
  * field is (descriptor base, scalar tile offset, 32-bit lane offset), so no 64-bit per-lane address
- * registers are carried through the tile loop, and a read beyond the stream's tiles returns zero
- * instead of touching memory. */
+ * registers are carried through the tile loop.  The kernel only forms offsets of tiles below the
+ * sequence's tile count, which is also the size the descriptor is given. */
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
 
