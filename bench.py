@@ -129,20 +129,18 @@ def main():
 
     # ---- encode line (configs[1]: 8 KV heads x 32768 tokens, keys + values = 16 vectors per token):
     # the same three sequences are encoded again into their own slots of cache 0 (same bytes as
-    # before), one K and one V launch per step, each kernel timed by HIP events on its stream
+    # before), keys and values in one launch per step (pq_encode_kv_pair), timed by HIP events on its stream
     kc, kr, vc, vr = caches[0]
 
     def encode_step(i):
         k, v, slot0 = enc_inputs[i % len(enc_inputs)]
-        ctx.encode_kv(k, PQ_KEY, kc, kr, dst_token0=slot0, ld_token=k.stride(1), ld_head=k.stride(0),
-                      n_tokens=CTX, n_heads=HKV)
-        ctx.encode_kv(v, PQ_VALUE, vc, vr, dst_token0=slot0, ld_token=v.stride(1), ld_head=v.stride(0),
-                      n_tokens=CTX, n_heads=HKV)
+        ctx.encode_kv_pair(k, v, kc, kr, vc, vr, dst_token0=slot0, ld_token=k.stride(1), ld_head=k.stride(0),
+                           n_tokens=CTX, n_heads=HKV)
 
     for i in range(args.warmup):
         encode_step(i)
     torch.cuda.synchronize()
-    profile_begin(2 * args.encode_steps + 2)
+    profile_begin(args.encode_steps + 2)
     for i in range(args.encode_steps):
         encode_step(i)
     torch.cuda.synchronize()
@@ -161,10 +159,8 @@ def main():
     def encode_step_h(i):
         k, v, _ = enc_inputs[i % len(enc_inputs)]
         slot0 = (i % len(enc_inputs)) * pool_per_seq
-        ctx_h.encode_kv(k, PQ_KEY, hk_c, hk_r, dst_token0=slot0, ld_token=k.stride(1), ld_head=k.stride(0),
-                        n_tokens=CTX, n_heads=HKV)
-        ctx_h.encode_kv(v, PQ_VALUE, hv_c, hv_r, dst_token0=slot0, ld_token=v.stride(1), ld_head=v.stride(0),
-                        n_tokens=CTX, n_heads=HKV)
+        ctx_h.encode_kv_pair(k, v, hk_c, hk_r, hv_c, hv_r, dst_token0=slot0, ld_token=k.stride(1), ld_head=k.stride(0),
+                             n_tokens=CTX, n_heads=HKV)
 
     for i in range(args.warmup):
         encode_step_h(i)
@@ -263,10 +259,8 @@ def main():
     def encode_step_d(i):
         k, v, slot0 = enc_inputs[i % len(enc_inputs)]
         dkc, dkr, dvc, dvr = deep_caches[0]
-        ctx_d.encode_kv(k, PQ_KEY, dkc, dkr, dst_token0=slot0, ld_token=k.stride(1), ld_head=k.stride(0),
-                        n_tokens=CTX, n_heads=HKV)
-        ctx_d.encode_kv(v, PQ_VALUE, dvc, dvr, dst_token0=slot0, ld_token=v.stride(1), ld_head=v.stride(0),
-                        n_tokens=CTX, n_heads=HKV)
+        ctx_d.encode_kv_pair(k, v, dkc, dkr, dvc, dvr, dst_token0=slot0, ld_token=k.stride(1), ld_head=k.stride(0),
+                             n_tokens=CTX, n_heads=HKV)
 
     for i in range(args.warmup):
         encode_step_d(i)

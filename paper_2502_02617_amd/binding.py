@@ -67,6 +67,8 @@ def library():
     L.pq_destroy.argtypes = [vp]
     L.pq_encode_kv.restype = i32
     L.pq_encode_kv.argtypes = [vp, vp, i32, i32, i64, i32, i64, i64, vp, vp, i64, i64, vp]
+    L.pq_encode_kv_pair.restype = i32
+    L.pq_encode_kv_pair.argtypes = [vp, vp, vp, i32, i64, i32, i64, i64, vp, vp, vp, vp, i64, i64, vp]
     L.pq_append_kv.restype = i32
     L.pq_append_kv.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i64, vp, vp]
     L.pq_append_kv_pair.restype = i32
@@ -277,6 +279,26 @@ class Context:
         _check(library().pq_encode_kv(self._h, x.data_ptr(), _dtype_code(x), int(kind), int(n_tokens), int(n_heads),
                                       int(ld_token), int(ld_head), codes.data_ptr(), radii.data_ptr(),
                                       int(pool_tokens), int(dst_token0), _stream()))
+
+    def encode_kv_pair(self, xk, xv, k_codes, k_radii, v_codes, v_radii, dst_token0=0, ld_token=None, ld_head=None,
+                       n_tokens=None, n_heads=None):
+        """Keys and values of the same tokens in one launch; xk, xv as x of encode_kv, same shape, strides, dtype."""
+        if ld_token is None:
+            n_tokens, n_heads = xk.shape[0], xk.shape[1]
+            ld_token, ld_head = xk.stride(0), xk.stride(1)
+            if xk.stride(2) != 1 or xv.stride(2) != 1:
+                raise PolarQuantError("innermost dimension must be contiguous")
+            if xv.shape != xk.shape or xv.stride() != xk.stride():
+                raise PolarQuantError("xk and xv must have the same shape and strides")
+        if xk.dtype != xv.dtype:
+            raise PolarQuantError("xk and xv must have the same dtype")
+        if k_codes.shape != v_codes.shape:
+            raise PolarQuantError("key and value caches must have the same pool size")
+        pool_tokens = k_codes.shape[1] * TILE_TOKENS
+        _check(library().pq_encode_kv_pair(self._h, xk.data_ptr(), xv.data_ptr(), _dtype_code(xk), int(n_tokens),
+                                           int(n_heads), int(ld_token), int(ld_head), k_codes.data_ptr(),
+                                           k_radii.data_ptr(), v_codes.data_ptr(), v_radii.data_ptr(),
+                                           int(pool_tokens), int(dst_token0), _stream()))
 
     def append_kv(self, x, kind, codes, radii, dst_token):
         """x: [n_seq, n_heads, 128] contiguous; dst_token: int64 device tensor [n_seq]."""

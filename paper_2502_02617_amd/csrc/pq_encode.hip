@@ -231,14 +231,22 @@ __device__ __forceinline__ void emit_value_full(uint32_t *img, int j, int b, con
    complete (a lane half holds blocks 4H..4H+3 of its vectors); levels 5 and 6 then run inside the
    lane, level 7 joins the two halves with one lane exchange, and the vector's radius and upper
    codes go into its word of the radius plane. */
+/* LDS of the encode kernels, shared by all their variants (a workgroup runs alone on its CU):
+   S in A-operand order, 32 KB per bf16 term; one tile image per wavefront; the level-1 cell table of
+   caller-set codebooks. */
+__shared__ uint4 sS[3 * 4 * 8 * 64];
+__shared__ uint32_t sImg[8][TileImage<false>::dwords];
+__shared__ PqDeviceConsts::Lut1Cell sLut[512];
+
+/* The tiles of one launch share: workgroup `block` of `n_blocks` takes every n_blocks-th group of
+   eight items (an item = one destination tile of one head plane). */
 template <int XT, int KIND, int NTERMS, bool GENERAL, bool DEEP>
-__global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(EncodeArgs a)
+__device__ __forceinline__ void encode_tiles(const EncodeArgs &a, int block, int n_blocks)
 {
     constexpr int kImgDwords = TileImage<DEEP>::dwords, kRadiiHalves = TileImage<DEEP>::radii_halves;
     constexpr int kWaves = EncodeShape<XT>::waves, kThreads = kWaves * 64;
+    static_assert(kWaves == 8, "sImg holds eight tile images");
     constexpr int kSChunks = NTERMS * 4 * 8 * 64;   /* 16-byte chunks of the copy of S that is used */
-    __shared__ uint4 sS[kSChunks];                  /* 32 KB per term, in A-operand order */
-    __shared__ uint32_t sImg[kWaves][kImgDwords];   /* one tile image per wavefront */
 
     const int lane = threadIdx.x & 63;
     /* same value in all lanes: keeps the item geometry and the tile pointers in scalar registers */
@@ -294,8 +302,8 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
             }
         }
     };
-    const int64_t item_stride = (int64_t)gridDim.x * (EncodeShape<XT>::waves);
-    const int64_t item0 = (int64_t)blockIdx.x * (EncodeShape<XT>::waves) + wave;
+    const int64_t item_stride = (int64_t)n_blocks * (EncodeShape<XT>::waves);
+    const int64_t item0 = (int64_t)block * (EncodeShape<XT>::waves) + wave;
     if (kPipelined && item0 < a.n_items) load_bf16_rows(geometry(item0));
 
     {   /* all of a thread's chunks are requested before the first one is stored: one round trip to L2
@@ -311,7 +319,6 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
     __syncthreads();
 
     Thresholds th = load_thresholds(*a.consts, NTERMS == 1 ? 0.08838834764831845f /* 1/sqrt(128) */ : 1.0f);
-    __shared__ PqDeviceConsts::Lut1Cell sLut[GENERAL ? 512 : 1];
     if (GENERAL) {
         for (int c = threadIdx.x; c < 512; c += kThreads) sLut[c] = a.consts->lut1[c];
         th.lut1 = sLut;
@@ -516,6 +523,21 @@ __global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(
     }
 }
 
+template <int XT, int KIND, int NTERMS, bool GENERAL, bool DEEP>
+__global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_kernel(EncodeArgs a)
+{
+    encode_tiles<XT, KIND, NTERMS, GENERAL, DEEP>(a, (int)blockIdx.x, (int)gridDim.x);
+}
+
+/* Keys and values of the same tokens in one launch: workgroups [0, k_blocks) encode the key tiles, the
+   rest the value tiles.  One launch instead of two, S staged once per CU, twice as many tiles per
+   wavefront to spread the start-up over. */
+template <int XT, int NTERMS, bool GENERAL, bool DEEP>
+__global__ __launch_bounds__(EncodeShape<XT>::waves * 64) void pq_encode_pair_kernel(EncodeArgs k, EncodeArgs v, int k_blocks)
+{
+    if ((int)blockIdx.x < k_blocks) encode_tiles<XT, PQ_KEY, NTERMS, GENERAL, DEEP>(k, (int)blockIdx.x, k_blocks);
+    else encode_tiles<XT, PQ_VALUE, NTERMS, GENERAL, DEEP>(v, (int)blockIdx.x - k_blocks, (int)gridDim.x - k_blocks);
+}
 
 template <int XT, int KIND>
 __global__ __launch_bounds__(512) void pq_append_kernel(AppendArgs a)
@@ -556,6 +578,45 @@ pq_status launch_encode(const EncodeArgs &a, hipStream_t stream)
     return PQ_OK;
 }
 
+template <int XT, int NTERMS, bool GENERAL, bool DEEP>
+pq_status launch_encode_pair(const EncodeArgs &k, const EncodeArgs &v, hipStream_t stream)
+{
+    int dev = 0, cus = 0;
+    PQ_HIP_TRY(hipGetDevice(&dev));
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    constexpr int kWaves = EncodeShape<XT>::waves, kThreads = kWaves * 64;
+    /* both streams have the same number of items: half of the CUs each, at least one workgroup */
+    int64_t per_kind = (k.n_items + kWaves - 1) / kWaves;
+    if (per_kind > cus / 2) per_kind = cus / 2;
+    if (per_kind < 1) per_kind = 1;
+    pq_prof_before(1, stream);
+    hipLaunchKernelGGL((pq_encode_pair_kernel<XT, NTERMS, GENERAL, DEEP>), dim3((unsigned)(2 * per_kind)), dim3(kThreads), 0,
+                       stream, k, v, (int)per_kind);
+    pq_prof_after(1, stream);
+    PQ_HIP_TRY(hipGetLastError());
+    return PQ_OK;
+}
+
+template <int NTERMS, bool GENERAL, bool DEEP>
+pq_status dispatch_pair_terms(const EncodeArgs &k, const EncodeArgs &v, pq_dtype xt, hipStream_t stream)
+{
+    return xt == PQ_BF16 ? launch_encode_pair<PQ_BF16, NTERMS, GENERAL, DEEP>(k, v, stream)
+                         : launch_encode_pair<PQ_F32, NTERMS, GENERAL, DEEP>(k, v, stream);
+}
+
+pq_status dispatch_encode_pair(const EncodeArgs &k, const EncodeArgs &v, pq_dtype xt, bool unit_entries, bool general,
+                               bool deep, hipStream_t stream)
+{
+    if (deep) {
+        if (general)
+            return unit_entries ? dispatch_pair_terms<1, true, true>(k, v, xt, stream) : dispatch_pair_terms<3, true, true>(k, v, xt, stream);
+        return unit_entries ? dispatch_pair_terms<1, false, true>(k, v, xt, stream) : dispatch_pair_terms<3, false, true>(k, v, xt, stream);
+    }
+    if (general)
+        return unit_entries ? dispatch_pair_terms<1, true, false>(k, v, xt, stream) : dispatch_pair_terms<3, true, false>(k, v, xt, stream);
+    return unit_entries ? dispatch_pair_terms<1, false, false>(k, v, xt, stream) : dispatch_pair_terms<3, false, false>(k, v, xt, stream);
+}
+
 template <int NTERMS, bool GENERAL, bool DEEP>
 pq_status dispatch_encode_terms(const EncodeArgs &a, pq_dtype xt, pq_kind kind, hipStream_t stream)
 {
@@ -587,26 +648,20 @@ pq_status dispatch_encode(const EncodeArgs &a, pq_dtype xt, pq_kind kind, bool u
 
 extern "C" const char *pq_kernel_name_encode(void) { return "pq_encode_kernel"; }
 
-extern "C" pq_status pq_encode_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,
-                                  int64_t n_tokens, int n_heads, int64_t ld_token, int64_t ld_head,
-                                  uint8_t *codes, uint16_t *radii, int64_t pool_tokens,
-                                  int64_t dst_token0, void *hip_stream)
+namespace {
+
+/* argument checks and launch geometry shared by pq_encode_kv and pq_encode_kv_pair */
+pq_status make_encode_args(const void *x, pq_dtype xt, int64_t n_tokens, int n_heads, int64_t ld_token, int64_t ld_head,
+                           uint8_t *codes, uint16_t *radii, int64_t pool_tokens, int64_t dst_token0, EncodeArgs &a)
 {
-    if (!ctx) return PQ_EINVAL;
-    if (n_tokens == 0) return PQ_OK;
     if (!x || !codes || !radii) return PQ_EINVAL;
-    if (xt != PQ_F32 && xt != PQ_BF16) return PQ_EINVAL;
-    if (kind != PQ_KEY && kind != PQ_VALUE) return PQ_EINVAL;
     if (n_tokens < 0 || n_heads <= 0 || pool_tokens <= 0 || (pool_tokens & 63) || dst_token0 < 0) return PQ_EINVAL;
     if (dst_token0 + n_tokens > pool_tokens) return PQ_EINVAL;
     if (ld_token < 0 || ld_head < 0) return PQ_EINVAL;
     const int64_t elems16 = xt == PQ_BF16 ? 8 : 4;
     if (!pq_aligned16(x) || !pq_aligned16(codes) || !pq_aligned16(radii)) return PQ_EALIGN;
     if ((ld_token % elems16) || (ld_head % elems16)) return PQ_EALIGN;
-    const PqDeviceState *ds = nullptr;
-    pq_status st = pq_device_state(ctx, &ds);
-    if (st != PQ_OK) return st;
-    EncodeArgs a{};
+    a = EncodeArgs{};
     a.x = x; a.ld_token = ld_token; a.ld_head = ld_head;
     a.codes = codes; a.radii = radii; a.pool_tiles = pool_tokens / 64; a.pool_tokens = pool_tokens;
     a.dst0 = dst_token0; a.n_tokens = n_tokens;
@@ -614,10 +669,57 @@ extern "C" pq_status pq_encode_kv(const pq_ctx *ctx, const void *x, pq_dtype xt,
     a.n_tiles = (dst_token0 + n_tokens + 63) / 64 - a.first_tile;
     a.n_heads = n_heads;
     a.n_items = a.n_tiles * n_heads;
+    return PQ_OK;
+}
+
+void set_device_tables(EncodeArgs &a, const PqDeviceState *ds)
+{
     a.S_bf16x3 = reinterpret_cast<const uint4 *>(ds->S_bf16x3);
     a.consts = ds->consts;
+}
+
+} // namespace
+
+extern "C" pq_status pq_encode_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,
+                                  int64_t n_tokens, int n_heads, int64_t ld_token, int64_t ld_head,
+                                  uint8_t *codes, uint16_t *radii, int64_t pool_tokens,
+                                  int64_t dst_token0, void *hip_stream)
+{
+    if (!ctx) return PQ_EINVAL;
+    if (n_tokens == 0) return PQ_OK;
+    if (xt != PQ_F32 && xt != PQ_BF16) return PQ_EINVAL;
+    if (kind != PQ_KEY && kind != PQ_VALUE) return PQ_EINVAL;
+    EncodeArgs a;
+    pq_status st = make_encode_args(x, xt, n_tokens, n_heads, ld_token, ld_head, codes, radii, pool_tokens, dst_token0, a);
+    if (st != PQ_OK) return st;
+    const PqDeviceState *ds = nullptr;
+    st = pq_device_state(ctx, &ds);
+    if (st != PQ_OK) return st;
+    set_device_tables(a, ds);
     return dispatch_encode(a, xt, kind, ctx->unit_entries, ctx->general_codebooks, ctx->depth == 7,
                            static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" pq_status pq_encode_kv_pair(const pq_ctx *ctx, const void *xk, const void *xv, pq_dtype xt,
+                                       int64_t n_tokens, int n_heads, int64_t ld_token, int64_t ld_head,
+                                       uint8_t *k_codes, uint16_t *k_radii, uint8_t *v_codes, uint16_t *v_radii,
+                                       int64_t pool_tokens, int64_t dst_token0, void *hip_stream)
+{
+    if (!ctx) return PQ_EINVAL;
+    if (n_tokens == 0) return PQ_OK;
+    if (xt != PQ_F32 && xt != PQ_BF16) return PQ_EINVAL;
+    EncodeArgs ak, av;
+    pq_status st = make_encode_args(xk, xt, n_tokens, n_heads, ld_token, ld_head, k_codes, k_radii, pool_tokens, dst_token0, ak);
+    if (st != PQ_OK) return st;
+    st = make_encode_args(xv, xt, n_tokens, n_heads, ld_token, ld_head, v_codes, v_radii, pool_tokens, dst_token0, av);
+    if (st != PQ_OK) return st;
+    const PqDeviceState *ds = nullptr;
+    st = pq_device_state(ctx, &ds);
+    if (st != PQ_OK) return st;
+    set_device_tables(ak, ds);
+    set_device_tables(av, ds);
+    return dispatch_encode_pair(ak, av, xt, ctx->unit_entries, ctx->general_codebooks, ctx->depth == 7,
+                                static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt, pq_kind kind,
