@@ -1106,7 +1106,8 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     const int G = Hq / Hkv;
     if (G != 1 && G != 2 && G != 4 && G != 8) return PQ_EUNSUPPORTED;
     if (M < 1 || M * G > 16) return PQ_EUNSUPPORTED;   /* at most 16 (query token, head) pairs per kv head */
-    if ((app || win) && (M != 1 || G == 8)) return PQ_EUNSUPPORTED;
+    if ((app || win) && M != 1) return PQ_EUNSUPPORTED;
+    if (win && G == 8) return PQ_EUNSUPPORTED; /* the window kernel handles groups of 1, 2 or 4 query heads */
     const int NG = M * G <= 4 ? 1 : (M * G <= 8 ? 2 : 4);
     const bool deep = ctx->depth == 7;
     if (!pq_aligned16(q) || !pq_aligned16(out) || !pq_aligned16(k_codes) || !pq_aligned16(k_radii) ||

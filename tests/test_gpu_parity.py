@@ -439,13 +439,14 @@ def test_attention_moving_maximum(env, shape):
     assert err <= 2e-3
 
 
-def test_decode_step_equals_append_then_attention(env):
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (16, 2)])
+def test_decode_step_equals_append_then_attention(env, Hq, Hkv):
     """pq_decode_step_polar gives, bit for bit, the caches and the output of pq_append_kv_pair followed by
-    pq_attn_decode_polar."""
+    pq_attn_decode_polar (groups of 4 and of 8 query heads)."""
     ctx, S, cb = env
     lens = [1, 64, 65, 300, 1000]      # context lengths including the token appended in the step
-    say(f"decode step vs append + attention, lens={lens}")
-    B, Hq, Hkv = len(lens), 8, 2
+    say(f"decode step vs append + attention, Hq={Hq} Hkv={Hkv} lens={lens}")
+    B = len(lens)
     results = []
     for fused in (False, True):
         starts, pool = [], 0
