@@ -484,6 +484,57 @@ def test_decode_step_equals_append_then_attention(env, Hq, Hkv):
     assert torch.isfinite(results[1][4]).all()
 
 
+def test_decode_step_under_graph_replay(env):
+    """The decode step (three launches, no memset nodes, no allocation once the context's tables are on the
+    device) captured into a HIP graph: every replay, with eager work and synchronisations in between, gives
+    the eager result bit for bit, including after the inputs have changed in place."""
+    ctx, S, cb = env
+    lens = [70, 300, 1000]
+    say(f"decode step under graph replay, lens={lens}")
+    B, Hq, Hkv = len(lens), 8, 2
+    caches, starts, pool, _, _ = build_cache(ctx, S, cb, [n - 1 for n in lens], Hkv, seed=1700, want_oracle=False)
+    kc, kr, vc, vr = caches
+    seq_start = torch.from_numpy(starts).to(DEV)
+    ctx_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    dst = seq_start + ctx_len.to(torch.int64) - 1
+    nk = synth.kv_stream(B, Hkv, 1710).permute(1, 0, 2).contiguous().to(DEV)
+    nv = synth.kv_stream(B, Hkv, 1711).permute(1, 0, 2).contiguous().to(DEV)
+    q = synth.queries(B, Hq, seed=1712).to(DEV)
+    out = torch.empty((B, Hq, 128), dtype=torch.float32, device=DEV)
+    ws = torch.empty(Context.attn_workspace_bytes(B, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
+
+    def step():
+        ctx.decode_step_polar(nk, nv, dst, q, out, kc, kr, vc, vr, seq_start, ctx_len, max(lens), helpers.softmax_scale(), ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):       # warm-up on a side stream, as graph capture wants it
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        if rep == 2:                    # new query and new token vectors, written in place
+            q.copy_(synth.queries(B, Hq, seed=1720).to(DEV))
+            nk.copy_(synth.kv_stream(B, Hkv, 1721).permute(1, 0, 2).contiguous().to(DEV))
+        out.fill_(float("nan"))
+        step()
+        torch.cuda.synchronize()
+        eager = out.clone()
+        eager_cache = (kc.clone(), kr.clone())
+        out.fill_(float("nan"))
+        ws.fill_(0xFF)                  # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
+        assert torch.equal(kc, eager_cache[0]) and torch.equal(kr, eager_cache[1])
+    assert torch.isfinite(out).all()
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(8, 2), (2, 2)])
 def test_hybrid_attention_prefix_plus_window(env, Hq, Hkv):
     """Quantised prefix + bf16 window against the oracle: every mix of empty / one-tile / ragged prefix and
