@@ -1,7 +1,8 @@
 /*
- * pq_attn.hip -- pq_attn_decode_polar: attention of one query token per
- * sequence computed directly on the packed PolarQuant cache (Eq. 5 with the
- * DeQuant of Algorithm 1 fused in), for gfx950.
+ * pq_attn.hip -- pq_attn_decode_polar and its relatives (the whole decode step,
+ * several query tokens per sequence, a quantised prefix plus an unquantised
+ * window): attention computed directly on the packed PolarQuant cache (Eq. 5
+ * with the DeQuant of Algorithm 1 fused in), for gfx950.
  *
  * Because S is a rotation, <q, khat> = <q S, khat S>: keys and values stay in
  * the rotated domain r^(0) (DeQuant without its trailing S^T), the query is
@@ -21,10 +22,13 @@
  *       16*i + m from its own registers: radius -> level 4 -> (level 3 x level 2
  *       product table) -> level 1, every factor a (cos, sin) pair fetched from a
  *       16-entry LDS table (all entries in distinct banks, so the gathers are
- *       conflict free), the products formed in fp32 by mixed-precision
- *       multiplies and rounded to binary16 once.  The 4 x 8 values are
+ *       conflict free), the products formed in fp32 on fp32 copies of the
+ *       tables and rounded to binary16 once.  The 4 x 8 values are
  *       the A operand (token rows) of v_mfma_f32_16x16x32_f16 against q'
- *       (columns = query heads), accumulated over the four 32-coordinate slices.
+ *       (columns = (query token, head) pairs in groups of four, each with its
+ *       binary16 remainder in a second column), accumulated over the four
+ *       32-coordinate slices.  At recursion depth 7 the block radii are first
+ *       rebuilt per tile from the vector's radius and its upper-level codes.
  *   softmax: the score tile comes out with lane (g, col) holding tokens
  *       16*i + 4*g + {0..3}; running max and sum per column.
  *   V:  lane (g, n) rebuilds half-block n (8 coordinates = 4 (cos, sin) pairs) of

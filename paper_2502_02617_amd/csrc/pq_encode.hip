@@ -1,9 +1,10 @@
 /*
- * pq_encode.hip -- pq_encode_kv / pq_append_kv: Algorithm 1 lines 2 and 4
- * (precondition with S, procedure Polar, procedure Quant) plus bit-packing
- * into the tile layout, for gfx950.
+ * pq_encode.hip -- pq_encode_kv / pq_encode_kv_pair / pq_append_kv: Algorithm 1
+ * lines 2 and 4 (precondition with S, procedure Polar, procedure Quant) plus
+ * bit-packing into the tile layout, for gfx950.
  *
- * Bulk kernel (pq_encode_kv; the append kernel is described further down):
+ * Bulk kernel (pq_encode_kv, and for keys and values in one launch
+ * pq_encode_kv_pair; the append kernel lives in pq_polar.h):
  * one wavefront owns one destination tile (64 token slots of one head plane).
  *   1. y = x * S on the matrix cores.  S is held as three bf16 terms
  *      S1 + S2 + S3 (24 significant bits) so that bf16 MFMAs with fp32
@@ -20,8 +21,11 @@
  *      squared radii above level 1), which is the nearest-centroid rule of
  *      procedure Quant without evaluating an arctangent or, but for the
  *      block radius, a square root.
- *   3. The fields are scattered into an image of the tile in LDS and the
- *      image is written out with full-width stores.
+ *   3. The fields are assembled into whole dwords in registers (full tiles) or
+ *      scattered with LDS atomics (partially written tiles) into an image of
+ *      the tile in LDS, and the image is written out with full-width stores.
+ *   At recursion depth 7 the recursion goes on over the block radii of a vector
+ *   (levels 5, 6, 7) and one word per token replaces the block radii.
  */
 #include "pq_common.h"
 #include "pq_polar.h"
