@@ -903,6 +903,8 @@ __device__ __forceinline__ float wave_sum_fixed(float x)
     return x;
 }
 
+/* G = query heads handled by one wavefront: the group of a kv head (Hq/Hkv), or half of it when the group
+   has four heads -- the kernel has little work per launch and runs faster spread over more wavefronts */
 template <int G>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_window_kernel(WindowArgs a)
 {
@@ -911,9 +913,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_window_kernel(Win
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int n_hg = a.Hq / G; /* head groups of G heads; head0 = first query head of this wavefront */
     const int wc = (int)(item % a.n_wchunks);
-    const int hk = (int)((item / a.n_wchunks) % a.Hkv);
-    const int b = (int)(item / ((int64_t)a.n_wchunks * a.Hkv));
+    const int head0 = (int)((item / a.n_wchunks) % n_hg) * G;
+    const int hk = head0 / (a.Hq / a.Hkv);
+    const int b = (int)(item / ((int64_t)a.n_wchunks * n_hg));
     if (b >= a.B) return;
     int W = a.win_len[b];
     W = W < 0 ? 0 : (W > a.win_cap ? a.win_cap : W);
@@ -924,7 +928,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_window_kernel(Win
     /* q of the group's heads, scaled, as fp32 in LDS */
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        const uint32_t two = reinterpret_cast<const uint32_t *>(a.q + ((int64_t)b * a.Hq + hk * G + h) * PQ_D)[lane];
+        const uint32_t two = reinterpret_cast<const uint32_t *>(a.q + ((int64_t)b * a.Hq + head0 + h) * PQ_D)[lane];
         sq[wave][h][2 * lane] = __uint_as_float(two << 16) * a.scale;
         sq[wave][h][2 * lane + 1] = __uint_as_float(two & 0xFFFF0000u) * a.scale;
     }
@@ -939,9 +943,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_window_kernel(Win
     float s[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) s[h] = 0.f;
-#pragma unroll 4
+    uint4 krow_v[16]; /* the whole 256-byte row is requested at once: one memory round trip */
+#pragma unroll
+    for (int c = 0; c < 16; ++c) krow_v[c] = krow[c];
+#pragma unroll
     for (int c = 0; c < 16; ++c) { /* 8 coordinates per step */
-        const uint4 kv = krow[c];
+        const uint4 kv = krow_v[c];
         const uint32_t w[4] = {kv.x, kv.y, kv.z, kv.w};
 #pragma unroll
         for (int h = 0; h < G; ++h) {
@@ -978,19 +985,24 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_window_kernel(Win
     float o0[G], o1[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) { o0[h] = 0.f; o1[h] = 0.f; }
-    for (int t = 0; t < n_valid; ++t) {
-        const uint32_t two = vbase[(int64_t)t * (PQ_D / 2)];
-        const float v0 = __uint_as_float(two << 16), v1 = __uint_as_float(two & 0xFFFF0000u);
+    for (int tb = 0; tb < n_valid; tb += 8) { /* eight value rows in flight; rows beyond the window re-read the last one with weight 0 */
+        uint32_t two[8];
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-            const float p = sp[wave][h][t];
-            o0[h] = fmaf(p, v0, o0[h]);
-            o1[h] = fmaf(p, v1, o1[h]);
+        for (int k = 0; k < 8; ++k) two[k] = vbase[(int64_t)min(tb + k, n_valid - 1) * (PQ_D / 2)];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float v0 = __uint_as_float(two[k] << 16), v1 = __uint_as_float(two[k] & 0xFFFF0000u);
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const float p = tb + k < n_valid ? sp[wave][h][tb + k] : 0.f;
+                o0[h] = fmaf(p, v0, o0[h]);
+                o1[h] = fmaf(p, v1, o1[h]);
+            }
         }
     }
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        const int64_t slot = ((int64_t)b * a.Hq + hk * G + h) * a.n_wchunks + wc;
+        const int64_t slot = ((int64_t)b * a.Hq + head0 + h) * a.n_wchunks + wc;
         reinterpret_cast<float2 *>(a.win_o + slot * PQ_D)[lane] = make_float2(o0[h], o1[h]);
         if (lane == 0) {
             a.win_ml[slot * 2] = m[h];
@@ -1147,10 +1159,11 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
                       static_cast<const uint16_t *>(win->win_v), win->win_len, B, Hq, Hkv, (int)win->win_cap,
                       p.n_wchunks, softmax_scale * kLog2e, reinterpret_cast<float *>(ws + p.off_wml),
                       reinterpret_cast<float *>(ws + p.off_wo)};
-        const int64_t witems = (int64_t)B * Hkv * p.n_wchunks;
+        const int per_wave = G == 4 ? 2 : 1; /* query heads per wavefront */
+        const int64_t witems = (int64_t)B * (Hq / per_wave) * p.n_wchunks;
+        if (witems > 0x7FFFFFFF) return PQ_EINVAL;
         const dim3 wgrid((unsigned)((witems + kWavesPerBlock - 1) / kWavesPerBlock)), wblk(kWavesPerBlock * 64);
-        if (G == 4) hipLaunchKernelGGL(pq_attn_window_kernel<4>, wgrid, wblk, 0, s, wa);
-        else if (G == 2) hipLaunchKernelGGL(pq_attn_window_kernel<2>, wgrid, wblk, 0, s, wa);
+        if (per_wave == 2) hipLaunchKernelGGL(pq_attn_window_kernel<2>, wgrid, wblk, 0, s, wa);
         else hipLaunchKernelGGL(pq_attn_window_kernel<1>, wgrid, wblk, 0, s, wa);
     }
 
