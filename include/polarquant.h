@@ -332,6 +332,9 @@ size_t pq_attn_hybrid_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ctx, i
  * output may be NULL) and turns recording off.  Process-wide, not per ctx.
  * ------------------------------------------------------------------------- */
 pq_status pq_profile_begin(int max_launches);
+/* The same, timing only every `every`-th launch of each kernel (the two event records around a launch
+ * cost a few microseconds of stream time: sampling keeps a timed loop close to its untimed speed). */
+pq_status pq_profile_begin_sampled(int max_launches, int every);
 pq_status pq_profile_end(double *attn_ms, int *attn_launches, double *encode_ms, int *encode_launches);
 
 /* Name of the dominant kernel of the last pq_attn_decode_polar / pq_encode_kv

@@ -97,6 +97,8 @@ def library():
     L.pq_attn_workspace_bytes.argtypes = [i32, i32, i32, i64]
     L.pq_profile_begin.restype = i32
     L.pq_profile_begin.argtypes = [i32]
+    L.pq_profile_begin_sampled.restype = i32
+    L.pq_profile_begin_sampled.argtypes = [i32, i32]
     L.pq_profile_end.restype = i32
     L.pq_profile_end.argtypes = [vp, vp, vp, vp]
     L.pq_kernel_name_attn.restype = ctypes.c_char_p
@@ -109,8 +111,9 @@ def pq_status_string(code):
     return library().pq_status_string(int(code)).decode()
 
 
-def profile_begin(max_launches):
-    _check(library().pq_profile_begin(int(max_launches)))
+def profile_begin(max_launches, every=1):
+    """Time at most max_launches launches of each of the two dominant kernels, every `every`-th one."""
+    _check(library().pq_profile_begin_sampled(int(max_launches), int(every)))
 
 
 def profile_end():

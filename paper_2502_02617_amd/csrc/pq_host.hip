@@ -575,6 +575,9 @@ struct Profiler {
     int cap = 0;
     std::vector<hipEvent_t> start[2], stop[2];
     int used[2] = {0, 0};
+    int every = 1;            /* every `every`-th launch of a kernel is timed */
+    int seen[2] = {0, 0};     /* launches since pq_profile_begin */
+    bool timing_now[2] = {false, false};
 } g_prof;
 } // namespace
 
@@ -582,22 +585,28 @@ void pq_prof_before(int kind, hipStream_t s)
 {
     if (!g_prof.on) return;
     std::lock_guard<std::mutex> lock(g_prof.mu);
-    if (g_prof.on && g_prof.used[kind] < g_prof.cap) (void)hipEventRecord(g_prof.start[kind][g_prof.used[kind]], s);
+    if (!g_prof.on) return;
+    g_prof.timing_now[kind] = g_prof.used[kind] < g_prof.cap && (g_prof.seen[kind] % g_prof.every) == 0;
+    g_prof.seen[kind] += 1;
+    if (g_prof.timing_now[kind]) (void)hipEventRecord(g_prof.start[kind][g_prof.used[kind]], s);
 }
 
 void pq_prof_after(int kind, hipStream_t s)
 {
     if (!g_prof.on) return;
     std::lock_guard<std::mutex> lock(g_prof.mu);
-    if (g_prof.on && g_prof.used[kind] < g_prof.cap) {
+    if (g_prof.on && g_prof.timing_now[kind]) {
         (void)hipEventRecord(g_prof.stop[kind][g_prof.used[kind]], s);
         g_prof.used[kind] += 1;
+        g_prof.timing_now[kind] = false;
     }
 }
 
-extern "C" pq_status pq_profile_begin(int max_launches)
+extern "C" pq_status pq_profile_begin(int max_launches) { return pq_profile_begin_sampled(max_launches, 1); }
+
+extern "C" pq_status pq_profile_begin_sampled(int max_launches, int every)
 {
-    if (max_launches <= 0 || max_launches > 65536) return PQ_EINVAL;
+    if (max_launches <= 0 || max_launches > 65536 || every <= 0) return PQ_EINVAL;
     std::lock_guard<std::mutex> lock(g_prof.mu);
     if (g_prof.on) return PQ_EINVAL;
     for (int k = 0; k < 2; ++k) {
@@ -609,7 +618,10 @@ extern "C" pq_status pq_profile_begin(int max_launches)
             g_prof.stop[k].push_back(b);
         }
         g_prof.used[k] = 0;
+        g_prof.seen[k] = 0;
+        g_prof.timing_now[k] = false;
     }
+    g_prof.every = every;
     g_prof.cap = max_launches;
     g_prof.on = true;
     return PQ_OK;
