@@ -275,6 +275,119 @@ def main():
     enc_d_mtok = CTX * args.encode_steps / (pr_de["encode_ms"] * 1e-3) / 1e6 if pr_de["encode_ms"] > 0 else 0.0
     del deep_caches
 
+    cache0 = caches[0]  # kept for the CPU baseline's cross-check
+    del caches, enc_inputs, win_k, win_v, ws_h
+    torch.cuda.empty_cache()
+
+    # ---- long-context line (configs[3]): batch 4, 131072-token context; decode step on two rotating caches
+    # and the bulk encoder over the full context (4 sequences x 8 heads x 131072 tokens, keys and values)
+    B3, CTX3 = 4, 131072
+    pool3_per_seq = CTX3 + 64
+    seq_start3 = torch.arange(B3, dtype=torch.int64, device=dev) * pool3_per_seq
+    ctx_len3 = torch.full((B3,), CTX3, dtype=torch.int32, device=dev)
+    newest3 = seq_start3 + (CTX3 - 1)
+    caches3, enc3_inputs = [], []
+    for c in range(2):
+        kc, kr = Context.alloc_cache(HKV, B3 * pool3_per_seq, dev)
+        vc, vr = Context.alloc_cache(HKV, B3 * pool3_per_seq, dev)
+        for t in (kc, kr, vc, vr):
+            t.zero_()
+        for b in range(B3):
+            k = synth.kv_stream(CTX3, HKV, seed=3000 + 100 * c + 2 * b, device=dev)
+            v = synth.kv_stream(CTX3, HKV, seed=3000 + 100 * c + 2 * b + 1, device=dev)
+            ctx.encode_kv_pair(k, v, kc, kr, vc, vr, dst_token0=b * pool3_per_seq, ld_token=k.stride(1),
+                               ld_head=k.stride(0), n_tokens=CTX3, n_heads=HKV)
+            if c == 0:
+                enc3_inputs.append((k, v, b * pool3_per_seq))
+            del k, v
+        caches3.append((kc, kr, vc, vr))
+    ws3 = torch.empty(Context.attn_workspace_bytes(B3, HQ, HKV, CTX3), dtype=torch.uint8, device=dev)
+    q3, out3 = q[:B3].contiguous(), torch.empty((B3, HQ, D), dtype=torch.bfloat16, device=dev)
+    new_k3, new_v3 = new_k[:B3].contiguous(), new_v[:B3].contiguous()
+
+    def long_step(i):
+        kc_, kr_, vc_, vr_ = caches3[i % 2]
+        ctx.decode_step_polar(new_k3, new_v3, newest3, q3, out3, kc_, kr_, vc_, vr_, seq_start3, ctx_len3, CTX3, scale, ws3)
+
+    for i in range(args.warmup):
+        long_step(i)
+    torch.cuda.synchronize()
+    profile_begin(args.steps + 1, every=4)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        long_step(i)
+    torch.cuda.synchronize()
+    long_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    pr_l = profile_end()
+    long_kern_ms = pr_l["attn_ms"] / max(pr_l["attn_launches"], 1)
+    long_bytes = BYTES_PER_TOKEN_HEAD * B3 * HKV * CTX3
+
+    def encode_step3(i):
+        k, v, slot0 = enc3_inputs[i % B3]
+        kc_, kr_, vc_, vr_ = caches3[0]
+        ctx.encode_kv_pair(k, v, kc_, kr_, vc_, vr_, dst_token0=slot0, ld_token=k.stride(1), ld_head=k.stride(0),
+                           n_tokens=CTX3, n_heads=HKV)
+
+    for i in range(B3):
+        encode_step3(i)
+    torch.cuda.synchronize()
+    enc3_launches = 3 * B3  # the full context of the batch, three times over
+    profile_begin(2 * enc3_launches + 2)
+    for i in range(enc3_launches):
+        encode_step3(i)
+    torch.cuda.synchronize()
+    pr_e3 = profile_end()
+    enc3_mtok = CTX3 * enc3_launches / (pr_e3["encode_ms"] * 1e-3) / 1e6 if pr_e3["encode_ms"] > 0 else 0.0
+    del caches3, enc3_inputs, ws3
+    torch.cuda.empty_cache()
+
+    # ---- ragged serving line (configs[4]): 64 sequences with context lengths uniform in [1024, 65536]; one
+    # step = 32 layers, each with its own cache buffers: append one new token per sequence, then attend
+    B4, LAYERS = 64, 32
+    lens4 = [int(n) for n in synth.ragged_lengths(B4, 1024, 65536, seed=4)]
+    starts4, pos = [], 0
+    for n in lens4:
+        starts4.append(pos)
+        pos += ((n + 63) // 64) * 64 + 64
+    pool4 = pos
+    seq_start4 = torch.tensor(starts4, dtype=torch.int64, device=dev)
+    ctx_len4 = torch.tensor(lens4, dtype=torch.int32, device=dev)
+    newest4 = seq_start4 + ctx_len4.to(torch.int64) - 1
+    kc, kr = Context.alloc_cache(HKV, pool4, dev)
+    vc, vr = Context.alloc_cache(HKV, pool4, dev)
+    for t in (kc, kr, vc, vr):
+        t.zero_()
+    for b, n in enumerate(lens4):
+        k = synth.kv_stream(n, HKV, seed=4000 + 2 * b, device=dev)
+        v = synth.kv_stream(n, HKV, seed=4000 + 2 * b + 1, device=dev)
+        ctx.encode_kv_pair(k, v, kc, kr, vc, vr, dst_token0=starts4[b], ld_token=k.stride(1), ld_head=k.stride(0),
+                           n_tokens=n, n_heads=HKV)
+        del k, v
+    layers4 = [(kc, kr, vc, vr)] + [tuple(t.clone() for t in (kc, kr, vc, vr)) for _ in range(LAYERS - 1)]
+    max_ctx4 = max(lens4)
+    ws4 = torch.empty(Context.attn_workspace_bytes(B4, HQ, HKV, max_ctx4), dtype=torch.uint8, device=dev)
+    q4 = synth.queries(B4, HQ, seed=14, device=dev)
+    out4 = torch.empty((B4, HQ, D), dtype=torch.bfloat16, device=dev)
+    new_k4 = synth.kv_stream(B4, HKV, seed=15, device=dev).permute(1, 0, 2).contiguous()
+    new_v4 = synth.kv_stream(B4, HKV, seed=16, device=dev).permute(1, 0, 2).contiguous()
+
+    def ragged_step():
+        for kc_, kr_, vc_, vr_ in layers4:
+            ctx.decode_step_polar(new_k4, new_v4, newest4, q4, out4, kc_, kr_, vc_, vr_, seq_start4, ctx_len4,
+                                  max_ctx4, scale, ws4)
+
+    ragged_steps = max(args.steps // 10, 2)
+    ragged_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(ragged_steps):
+        ragged_step()
+    torch.cuda.synchronize()
+    ragged_ms = 1e3 * (time.perf_counter() - t0) / ragged_steps
+    ragged_bytes = BYTES_PER_TOKEN_HEAD * HKV * sum(lens4) * LAYERS
+    del layers4, kc, kr, vc, vr, ws4
+    torch.cuda.empty_cache()
+
     result = {
         "metric": "decode attn HBM GB/s on polar-quantized KV @32k ctx",
         "value": round(value, 1),
@@ -350,11 +463,32 @@ def main():
             "algorithmic_bytes_per_step": deep_bytes,
             "encode_mtok_per_s": round(enc_d_mtok, 2),
         },
+        "long_context": {
+            "workload": "configs[3]: batch 4, 32 q heads / 8 kv heads, 131072-token context, decode step on two rotating "
+                        "caches; encode = pq_encode_kv_pair over the full context (8.39 M vectors)",
+            "ms_per_step": round(long_ms, 4),
+            "kernel_avg_ms": round(long_kern_ms, 5),
+            "gb_per_s": round(long_bytes / (long_ms * 1e-3) / 1e9, 1),
+            "pct_of_hbm_peak": round(100.0 * long_bytes / (long_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+            "algorithmic_bytes_per_step": long_bytes,
+            "encode_mtok_per_s": round(enc3_mtok, 2),
+        },
+        "ragged_serving": {
+            "workload": "configs[4]: 64 sequences, context lengths uniform in [1024, 65536] (seed 4), one step = 32 layers "
+                        "with distinct cache buffers, each pq_decode_step_polar (append one token per sequence, attend)",
+            "ms_per_step": round(ragged_ms, 3),
+            "ms_per_layer": round(ragged_ms / LAYERS, 4),
+            "gb_per_s": round(ragged_bytes / (ragged_ms * 1e-3) / 1e9, 1),
+            "pct_of_hbm_peak": round(100.0 * ragged_bytes / (ragged_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+            "algorithmic_bytes_per_step": ragged_bytes,
+            "tokens_in_context": sum(lens4),
+            "steps_timed": ragged_steps,
+        },
         "setup_s": round(t_setup, 1),
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(args, kept, q, scale, caches[0], seq_start, ctx_len, ctx, pool_per_seq)
+        result["cpu_baseline"] = cpu_baseline(args, kept, q, scale, cache0, seq_start, ctx_len, ctx, pool_per_seq)
 
     print(json.dumps(result))
 

@@ -250,8 +250,12 @@ pq_status pq_export_canonical(const pq_ctx *ctx, pq_kind kind, const uint8_t *co
  * query attends to all ctx_len[b] cached tokens (its own key/value are
  * appended before the call).  Query head h reads KV head h / (Hq/Hkv);
  * Hq/Hkv must be 1, 2, 4 or 8.  ctx_len[b] == 0 gives a zero output row.
- * max_ctx (host) bounds every ctx_len[b]; it sizes the launch; at most 2^26
- * tokens (PQ_EUNSUPPORTED beyond).
+ * max_ctx (host) bounds every ctx_len[b]; it sizes the workspace; at most
+ * 2^26 tokens, and B * Hkv * ceil(max_ctx / 64) must stay below 2^31 - 4096
+ * (PQ_EUNSUPPORTED beyond).  The context lengths themselves are only read on
+ * the device: the work is split there into equal shares of 64-token tiles
+ * per wavefront, whatever the mix of lengths, so a ragged batch costs what
+ * its total number of cached tokens costs.
  * workspace (device): at least pq_attn_workspace_bytes(B, Hq, Hkv, max_ctx)
  * bytes, PQ_ENOMEM otherwise; contents need not be preserved between calls.
  * ------------------------------------------------------------------------- */

@@ -9,13 +9,15 @@
  * rotated once and the weighted value sum is multiplied by S^T once.
  *
  * Three kernels per call:
- *   pq_rotate_q_kernel      q' = (q S) * softmax_scale * log2(e), binary16
- *   pq_attn_partial_kernel  one wavefront per (sequence, kv head, chunk of
- *                           tiles): streams K and V tiles, rebuilds them in
- *                           registers, scores and weighted sums on the matrix
- *                           cores, online softmax; writes (m, l, o') partials
- *   pq_attn_combine_kernel  merges the partials of a (sequence, query head) in
- *                           chunk order, divides by l, multiplies by S^T, bf16
+ *   pq_rotate_q_kernel      q' = (q S) * softmax_scale * log2(e), binary16; one more
+ *                           workgroup builds the work plan from ctx_len: an equal
+ *                           share of all tiles for every wavefront of the next launch
+ *   pq_attn_partial_kernel  one wavefront per share: streams the K and V tiles of
+ *                           its piece(s) of (sequence, kv head) streams, rebuilds
+ *                           them in registers, scores and weighted sums on the matrix
+ *                           cores, online softmax; writes (m, l, o') per piece
+ *   pq_attn_combine_kernel  merges the pieces of a (sequence, query head) in tile
+ *                           order, divides by l, multiplies by S^T, bf16
  *
  * Partial kernel, per 16-token pass (four passes per 64-token tile):
  *   K:  lane (gk, m) rebuilds the 32 rotated coordinates of quarter gk of token
@@ -79,11 +81,28 @@ struct AttnArgs {
     int M; /* query tokens per sequence: rows are ordered [B][M][Hq] */
     int64_t pool_tiles;
     int64_t max_ctx;
-    int chunk_tiles, n_chunks;
-    float *ws_ml; /* [B][M][Hq][n_chunks][2] */
-    float *ws_o;  /* [B][M][Hq][n_chunks][128] */
+    const int32_t *plan; /* device work plan, see below */
+    float *ws_ml; /* [piece][M * G pairs][2] */
+    float *ws_o;  /* [piece][M * G pairs][128] */
     const PqDeviceConsts *consts;
 };
+
+/* Work plan of one attention call, built on the device from ctx_len by the launch that
+ * precedes the partial kernel (the host never reads the context lengths).  The tiles of all
+ * (sequence, kv head) streams form one global sequence, stream (b, hk) before (b, hk + 1)
+ * before (b + 1, 0); wavefront w of the partial kernel takes global tiles
+ * [w * share, (w + 1) * share): every wavefront gets the same number of tiles whatever
+ * the mix of context lengths, and a wavefront whose range crosses a stream boundary works
+ * through one piece per stream.  Piece ids are w + (b * Hkv + hk): along the global
+ * sequence either w or the stream index grows from one piece to the next, so the id is unique
+ * and the pieces of one stream are consecutive ids.
+ * All counts fit 31 bits (the launch code refuses batches whose tile count could not).
+ *   plan[0] = total tiles (all streams), plan[1] = share (tiles per wavefront),
+ *   plan[2 + b] = tiles of sequences 0 .. b-1 of ONE kv head (b = 0 .. B), then for every
+ *   stream s = b * Hkv + hk, from plan[2 + B + 1 + 2 s]: the wavefront of its first piece and
+ *   the number of its pieces (what the combine kernel needs). */
+constexpr int kPlanHeader = 2;
+constexpr int kMinShareTiles = 4;
 
 union H8 {
     h8 v;
@@ -385,15 +404,18 @@ __device__ __forceinline__ void expand_deep_radii(const uint32_t *tab, const Dee
 /* Context length the kernels act on: the caller's value clamped to [0, max_ctx];
  * a sequence whose slots would leave the pool or that does not start on a tile
  * boundary is treated as empty (zero output) instead of being read. */
+__device__ __forceinline__ int effective_ctx_of(int64_t c, int64_t s0, int64_t max_ctx, int64_t pool_tiles)
+{
+    if (c > max_ctx) c = max_ctx;
+    if (c <= 0) return 0;
+    if (s0 < 0 || (s0 & 63) || (s0 >> 6) + ((c + 63) >> 6) > pool_tiles) return 0;
+    return (int)c;
+}
+
 __device__ __forceinline__ int effective_ctx(const int64_t *seq_start, const int32_t *ctx_len, int b,
                                              int64_t max_ctx, int64_t pool_tiles)
 {
-    int64_t c = ctx_len[b];
-    if (c > max_ctx) c = max_ctx;
-    if (c <= 0) return 0;
-    int64_t s0 = seq_start[b];
-    if (s0 < 0 || (s0 & 63) || (s0 >> 6) + ((c + 63) >> 6) > pool_tiles) return 0;
-    return (int)c;
+    return effective_ctx_of(ctx_len[b], seq_start[b], max_ctx, pool_tiles); /* two independent loads */
 }
 
 __device__ __forceinline__ uint32_t sel4(uint4 v, int c)
@@ -573,6 +595,23 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
     __shared__ uint32_t tab[kTabDwords];
     __shared__ float sKrad[DEEP ? kWavesPerBlock : 1][DEEP ? 512 : 1];
     __shared__ uint16_t sVrad[DEEP ? kWavesPerBlock : 1][DEEP ? 512 : 2];
+    /* per-sequence data of batches of up to 64 sequences is staged in LDS with the tables, so that
+       nothing between the barrier and the first tile request waits for global memory; its loads
+       are requested first (last wavefront of the workgroup, which has the least table work) */
+    __shared__ int sPre[65];
+    __shared__ int sCtx[64];
+    __shared__ int64_t sTile0[64];
+    const bool staged = a.B <= 64;
+    const int total = a.plan[0], share = a.plan[1];
+    int st_pre = 0, st_last = 0, st_len = 0;
+    int64_t st_start = 0;
+    if (staged && threadIdx.x >= 192) {
+        const int bb = (int)threadIdx.x - 192;
+        st_pre = a.plan[kPlanHeader + min(bb, a.B)];
+        st_last = a.plan[kPlanHeader + a.B];
+        st_len = a.ctx_len[min(bb, a.B - 1)];
+        st_start = a.seq_start[min(bb, a.B - 1)];
+    }
     {
         const PqDeviceConsts &K = *a.consts;
         int t = threadIdx.x;
@@ -592,140 +631,209 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
         if (t >= 200 && t < 208) tab[t] = 0u;
         if (t >= kTUp && t < kTUp + 48) tab[t] = DEEP ? __float_as_uint(K.up_cs[(t - kTUp) >> 4][((t - kTUp) >> 1) & 7][t & 1]) : 0u;
     }
+    if (staged && threadIdx.x >= 192) {
+        const int bb = (int)threadIdx.x - 192;
+        sPre[bb] = st_pre;
+        if (bb == 63) sPre[64] = st_last;
+        sCtx[bb] = bb < a.B ? effective_ctx_of(st_len, st_start, a.max_ctx, a.pool_tiles) : 0;
+        sTile0[bb] = st_start >> 6;
+    }
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
     /* the wavefront index is the same in all lanes: telling the compiler so keeps everything
-       derived from it (work item, pointers, loop bounds) in scalar registers */
+       derived from it (work range, pointers, loop bounds) in scalar registers */
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
-    const int chunk = (int)(item % a.n_chunks);
-    const int hk = (int)((item / a.n_chunks) % a.Hkv);
-    const int b = (int)(item / ((int64_t)a.n_chunks * a.Hkv));
-    if (b >= a.B) return;
-    const int ctx = effective_ctx(a.seq_start, a.ctx_len, b, a.max_ctx, a.pool_tiles);
-    const int n_tiles = (ctx + 63) >> 6;
-    const int tile_lo = chunk * a.chunk_tiles;
-    if (tile_lo >= n_tiles) return;
-    const int tile_hi = min(tile_lo + a.chunk_tiles, n_tiles);
-
-    const int g = lane >> 4, n = lane & 15;
-    const int64_t seq_tile0 = a.seq_start[b] >> 6;
-    constexpr int kRadiiHalves = DEEP ? PQ_DEEP_RADII_HALVES : PQL_RADII;
-    const int64_t stream_tile0 = (int64_t)hk * a.pool_tiles + seq_tile0;
-    /* descriptors of this sequence's tiles in the four planes (the context is at most 2^31 tokens: 32-bit sizes) */
-    const uint32_t code_bytes = (uint32_t)n_tiles * PQL_CODE_BYTES, radii_bytes = (uint32_t)n_tiles * (kRadiiHalves * 2u);
-    const __amdgpu_buffer_rsrc_t kc = stream_descriptor(a.k_codes + stream_tile0 * PQL_CODE_BYTES, code_bytes);
-    const __amdgpu_buffer_rsrc_t vc = stream_descriptor(a.v_codes + stream_tile0 * PQL_CODE_BYTES, code_bytes);
-    const __amdgpu_buffer_rsrc_t kr = stream_descriptor(a.k_radii + stream_tile0 * kRadiiHalves, radii_bytes);
-    const __amdgpu_buffer_rsrc_t vr = stream_descriptor(a.v_radii + stream_tile0 * kRadiiHalves, radii_bytes);
-    const DeepRadii dr{sKrad[DEEP ? wave : 0], sVrad[DEEP ? wave : 0], a.up_b5, a.up_b6, a.up_b7};
-
-    /* ---- q' operands: in group k, columns n < 8 = (pair 4k + (n&3), parity (n>>2)&1) hold the
-     * leading binary16 part of q', columns n + 8 its binary16 remainder, so that q' enters the
-     * scores to ~22 bits at no extra matrix instruction; pair p = (query token p / G, head p % G);
-     * slice s = rotated coordinates 32*g + 8*s .. +8 ---- */
-    H8 qb[NG][4];
-#pragma unroll
-    for (int k = 0; k < NG; ++k) {
-        const int pair = 4 * k + (n & 3);
-        const bool real = pair < a.M * G;
-        const int m = real ? pair / G : 0, head = real ? pair % G : 0;
-        const uint4 *qp = reinterpret_cast<const uint4 *>(
-            a.qrot + ((((int64_t)b * a.M + m) * a.Hq + hk * G + head) * 2 + (n >> 3)) * PQ_D + 32 * g);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) qb[k][s].q = real ? qp[s] : make_uint4(0, 0, 0, 0);
+    const int w = (int)blockIdx.x * kWavesPerBlock + wave;
+    if (share <= 0 || (int64_t)w * share >= total) return;
+    int gpos = w * share;
+    const int gend = min(gpos + share, total);
+    /* wave-uniform reads of the per-sequence data (LDS values come back in vector registers:
+       readfirstlane returns them to scalar ones) */
+    auto prefix_at = [&](int i) -> int {
+        return staged ? __builtin_amdgcn_readfirstlane(sPre[i]) : a.plan[kPlanHeader + i];
+    };
+    auto ctx_of = [&](int bb) -> int {
+        return staged ? __builtin_amdgcn_readfirstlane(sCtx[bb])
+                      : effective_ctx(a.seq_start, a.ctx_len, bb, a.max_ctx, a.pool_tiles);
+    };
+    auto tile0_of = [&](int bb) -> int64_t {
+        if (!staged) return a.seq_start[bb] >> 6;
+        const int64_t v = sTile0[bb];
+        return (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(v >> 32)) << 32) |
+                         (uint32_t)__builtin_amdgcn_readfirstlane((int)v));
+    };
+    /* sequence of the first tile: the last b whose streams start at or before gpos (a ballot
+       over the prefix table, 64 entries per round; empty sequences share their successor's entry) */
+    int b;
+    {
+        int cnt = 0;
+        if (staged) {
+            cnt = __popcll(__ballot(lane <= a.B && (int64_t)sPre[lane] * a.Hkv <= gpos));
+        } else {
+            for (int base = 0; base <= a.B; base += 64) {
+                const int i = base + lane;
+                const bool at_or_before = i <= a.B && (int64_t)a.plan[kPlanHeader + min(i, a.B)] * a.Hkv <= gpos;
+                cnt += __popcll(__ballot(at_or_before));
+            }
+        }
+        b = min(max(cnt - 1, 0), a.B - 1);
     }
+    int before = prefix_at(b);
+    int seq_tiles = prefix_at(b + 1) - before;
+    if (seq_tiles <= 0) return;
+    int hk, tile_lo;
+    {
+        const int r = gpos - before * a.Hkv; /* below Hkv * seq_tiles */
+        hk = min(r / seq_tiles, a.Hkv - 1);
+        tile_lo = r - hk * seq_tiles;
+    }
+    const int g = lane >> 4, n = lane & 15;
+    constexpr int kRadiiHalves = DEEP ? PQ_DEEP_RADII_HALVES : PQL_RADII;
+    const DeepRadii dr{sKrad[DEEP ? wave : 0], sVrad[DEEP ? wave : 0], a.up_b5, a.up_b6, a.up_b7};
     const uint32_t parity_shift = (n & 4) ? 16u : 0u;
     const int t4b = kT4B + ((n & 1) ? 4 : 0);
 
-    f4 acc_o[NG][4];
-    float m_run[NG], l_run[NG];
-#pragma unroll
-    for (int k = 0; k < NG; ++k) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) acc_o[k][c] = f4{0.f, 0.f, 0.f, 0.f};
-        m_run[k] = -INFINITY;
-        l_run[k] = 0.f;
-    }
+    for (;;) { /* one piece per round: tiles [tile_lo, tile_hi) of stream (b, hk) */
+        const int ctx = ctx_of(b);
+        const int n_tiles = (ctx + 63) >> 6; /* == seq_tiles */
+        const int tile_hi = min(min(seq_tiles, n_tiles), tile_lo + (gend - gpos));
+        const int piece_tiles = tile_hi - tile_lo;
+        if (piece_tiles <= 0) return; /* cannot happen with a consistent plan */
+        const int64_t piece = (int64_t)w + (int64_t)b * a.Hkv + hk;
 
-    /* Tiles tile_lo .. tile_hi-1.  A tile is full when every query token sees all of its 64
-     * tokens; the tiles after that (the sequence's last one, or its last two when the M newest
-     * tokens straddle a tile boundary) are masked per pair.
-     * The raw tile registers are single buffered: the next key tile is requested once the
-     * last pass has scored, the next value tile once it has been consumed; the other
-     * wavefronts resident on the SIMD cover the latency. */
-    const int n_full = min(tile_hi, max(ctx - (a.M - 1), 0) >> 6);
-    KTileRaw kraw;
-    VTileRaw vraw;
-    load_k_tile<DEEP>(kraw, kc, kr, tile_lo, lane);
-    load_v_tile<DEEP>(vraw, vc, vr, tile_lo, lane);
-    int tile = tile_lo;
-    {
-        int lim[NG];
+        const int64_t seq_tile0 = tile0_of(b);
+        const int64_t stream_tile0 = (int64_t)hk * a.pool_tiles + seq_tile0;
+        /* descriptors of this sequence's tiles in the four planes (the context is at most 2^31 tokens: 32-bit sizes) */
+        const uint32_t code_bytes = (uint32_t)n_tiles * PQL_CODE_BYTES, radii_bytes = (uint32_t)n_tiles * (kRadiiHalves * 2u);
+        const __amdgpu_buffer_rsrc_t kc = stream_descriptor(a.k_codes + stream_tile0 * PQL_CODE_BYTES, code_bytes);
+        const __amdgpu_buffer_rsrc_t vc = stream_descriptor(a.v_codes + stream_tile0 * PQL_CODE_BYTES, code_bytes);
+        const __amdgpu_buffer_rsrc_t kr = stream_descriptor(a.k_radii + stream_tile0 * kRadiiHalves, radii_bytes);
+        const __amdgpu_buffer_rsrc_t vr = stream_descriptor(a.v_radii + stream_tile0 * kRadiiHalves, radii_bytes);
+
+        /* ---- q' operands: in group k, columns n < 8 = (pair 4k + (n&3), parity (n>>2)&1) hold the
+         * leading binary16 part of q', columns n + 8 its binary16 remainder, so that q' enters the
+         * scores to ~22 bits at no extra matrix instruction; pair p = (query token p / G, head p % G);
+         * slice s = rotated coordinates 32*g + 8*s .. +8 ---- */
+        H8 qb[NG][4];
+        /* lane-dependent addresses of the piece's prologue and epilogue are formed from a copy of the lane
+           number that the compiler cannot trace: hoisted out of the piece loop they would be spilled */
+        int lane_q = lane;
+        asm volatile("" : "+v"(lane_q));
 #pragma unroll
-        for (int k = 0; k < NG; ++k) lim[k] = 64;
-        for (; tile < n_full; ++tile) {
-            if (DEEP) { /* the reads of the previous tile's radii precede these writes in program order */
+        for (int k = 0; k < NG; ++k) {
+            const int nq = lane_q & 15, gq = lane_q >> 4;
+            const int pair = 4 * k + (nq & 3);
+            const bool real = pair < a.M * G;
+            const int m = real ? pair / G : 0, head = real ? pair % G : 0;
+            const uint4 *qp = reinterpret_cast<const uint4 *>(
+                a.qrot + ((((int64_t)b * a.M + m) * a.Hq + hk * G + head) * 2 + (nq >> 3)) * PQ_D + 32 * gq);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) qb[k][s].q = real ? qp[s] : make_uint4(0, 0, 0, 0);
+        }
+        f4 acc_o[NG][4];
+        float m_run[NG], l_run[NG];
+#pragma unroll
+        for (int k = 0; k < NG; ++k) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc_o[k][c] = f4{0.f, 0.f, 0.f, 0.f};
+            m_run[k] = -INFINITY;
+            l_run[k] = 0.f;
+        }
+
+        /* Tiles tile_lo .. tile_hi-1.  A tile is full when every query token sees all of its 64
+         * tokens; the tiles after that (the sequence's last one, or its last two when the M newest
+         * tokens straddle a tile boundary) are masked per pair.
+         * The raw tile registers are single buffered: the next key tile is requested once the
+         * last pass has scored, the next value tile once it has been consumed; the other
+         * wavefronts resident on the SIMD cover the latency. */
+        const int n_full = min(tile_hi, max(ctx - (a.M - 1), 0) >> 6);
+        KTileRaw kraw;
+        VTileRaw vraw;
+        load_k_tile<DEEP>(kraw, kc, kr, tile_lo, lane);
+        load_v_tile<DEEP>(vraw, vc, vr, tile_lo, lane);
+        int tile = tile_lo;
+        {
+            int lim[NG];
+#pragma unroll
+            for (int k = 0; k < NG; ++k) lim[k] = 64;
+            for (; tile < n_full; ++tile) {
+                if (DEEP) { /* the reads of the previous tile's radii precede these writes in program order */
+                    wave_lds_fence();
+                    expand_deep_radii(tab, dr, kraw.top, vraw.top, lane);
+                    wave_lds_fence();
+                }
+                attend_pass<0, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
+                attend_pass<1, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
+                attend_pass<2, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
+                attend_pass<3, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
+                if (tile + 1 < tile_hi) {
+                    load_k_tile<DEEP>(kraw, kc, kr, tile + 1, lane);
+                    load_v_tile<DEEP>(vraw, vc, vr, tile + 1, lane);
+                }
+            }
+        }
+        for (; tile < tile_hi; ++tile) { /* the masked tiles at the end of the sequence */
+            const int nv = min(ctx - tile * 64, 64);
+            int lim[NG]; /* tokens of this tile that this lane's pair of group k may see */
+#pragma unroll
+            for (int k = 0; k < NG; ++k) {
+                const int pair = 4 * k + (n & 3);
+                const int m = pair < a.M * G ? pair / G : 0;
+                lim[k] = ctx - (a.M - 1 - m) - tile * 64;
+            }
+            if (DEEP) {
                 wave_lds_fence();
                 expand_deep_radii(tab, dr, kraw.top, vraw.top, lane);
                 wave_lds_fence();
             }
-            attend_pass<0, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
-            attend_pass<1, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
-            attend_pass<2, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
-            attend_pass<3, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
+            attend_pass<0, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
+            attend_pass<1, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
+            attend_pass<2, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
+            attend_pass<3, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
             if (tile + 1 < tile_hi) {
                 load_k_tile<DEEP>(kraw, kc, kr, tile + 1, lane);
                 load_v_tile<DEEP>(vraw, vc, vr, tile + 1, lane);
             }
         }
-    }
-    for (; tile < tile_hi; ++tile) { /* the masked tiles at the end of the sequence */
-        const int nv = min(ctx - tile * 64, 64);
-        int lim[NG]; /* tokens of this tile that this lane's pair of group k may see */
+
+        /* ---- partial results: l summed over the four token groups; o' scattered to coordinate order ---- */
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
 #pragma unroll
         for (int k = 0; k < NG; ++k) {
-            const int pair = 4 * k + (n & 3);
-            const int m = pair < a.M * G ? pair / G : 0;
-            lim[k] = ctx - (a.M - 1 - m) - tile * 64;
-        }
-        if (DEEP) {
-            wave_lds_fence();
-            expand_deep_radii(tab, dr, kraw.top, vraw.top, lane);
-            wave_lds_fence();
-        }
-        attend_pass<0, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
-        attend_pass<1, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
-        attend_pass<2, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
-        attend_pass<3, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
-        if (tile + 1 < tile_hi) {
-            load_k_tile<DEEP>(kraw, kc, kr, tile + 1, lane);
-            load_v_tile<DEEP>(vraw, vc, vr, tile + 1, lane);
-        }
-    }
-
-    /* ---- partial results: l summed over the four token groups; o' scattered to coordinate order ---- */
+            float l = l_run[k];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            const int ne = lane_e & 15, ge = lane_e >> 4;
+            const int pair = 4 * k + (ne & 3);
+            if (ne < 8 && pair < a.M * G) {
+                const int par = (ne >> 2) & 1;
+                const int64_t slot = piece * (a.M * G) + pair;
+                float *o = a.ws_o + slot * PQ_D;
 #pragma unroll
-    for (int k = 0; k < NG; ++k) {
-        float l = l_run[k];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        const int pair = 4 * k + (n & 3);
-        if (n < 8 && pair < a.M * G) {
-            const int m = pair / G, head = pair % G;
-            const int par = (n >> 2) & 1;
-            const int64_t slot = ((((int64_t)b * a.M + m) * a.Hq + hk * G + head)) * a.n_chunks + chunk;
-            float *o = a.ws_o + slot * PQ_D;
+                for (int c = 0; c < 4; ++c)
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    o[2 * (16 * g + 4 * e + c) + par] = acc_o[k][c][e];
-            if (g == 0 && par == 0) {
-                a.ws_ml[slot * 2] = m_run[k];
-                a.ws_ml[slot * 2 + 1] = l;
+                    for (int e = 0; e < 4; ++e)
+                        o[2 * (16 * ge + 4 * e + c) + par] = acc_o[k][c][e];
+                if (ge == 0 && par == 0) {
+                    a.ws_ml[slot * 2] = m_run[k];
+                    a.ws_ml[slot * 2 + 1] = l;
+                }
             }
+        }
+
+        /* next piece: the first tiles of the next non-empty stream, as far as this wavefront's range goes */
+        gpos += piece_tiles;
+        if (gpos >= gend) return;
+        tile_lo = 0;
+        if (++hk == a.Hkv) {
+            hk = 0;
+            do {
+                if (++b >= a.B) return; /* cannot happen: gpos < total */
+                before = prefix_at(b);
+                seq_tiles = prefix_at(b + 1) - before;
+            } while (seq_tiles <= 0);
         }
     }
 }
@@ -758,29 +866,102 @@ __device__ __forceinline__ void rotate_query_row(const RotateArgs &a, int row)
     }
 }
 
-__global__ __launch_bounds__(512) void pq_rotate_q_kernel(RotateArgs a)
+struct PlanArgs {
+    const int64_t *seq_start;
+    const int32_t *ctx_len;
+    int B, Hkv;
+    int64_t max_ctx, pool_tiles;
+    int slots;     /* wavefronts of the partial kernel's launch */
+    int32_t *plan; /* [kPlanHeader + (B + 1) + 2 * B * Hkv] */
+};
+
+/* Builds the work plan (one workgroup of 512 threads): running sum of the sequences' tile
+ * counts, 512 sequences per round (a shuffle scan inside each wavefront, then the
+ * wavefronts' totals), the total and the share of a wavefront, and from those the first
+ * wavefront and the piece count of every stream. */
+__device__ __forceinline__ void build_plan(const PlanArgs &a)
 {
-    rotate_query_row(a, (int)blockIdx.x);
+    __shared__ int wave_sum[8];
+    __shared__ int s_share;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    int carry = 0;
+    for (int base = 0; base < a.B; base += 512) {
+        const int b = base + tid;
+        int v = b < a.B ? (effective_ctx(a.seq_start, a.ctx_len, b, a.max_ctx, a.pool_tiles) + 63) >> 6 : 0;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(v, d);
+            if (lane >= d) v += up;
+        }
+        if (lane == 63) wave_sum[wv] = v;
+        __syncthreads();
+        int offset = carry, round_total = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int ws = wave_sum[k];
+            if (k < wv) offset += ws;
+            round_total += ws;
+        }
+        if (b < a.B) a.plan[kPlanHeader + b + 1] = offset + v;
+        carry += round_total;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const uint32_t total = (uint32_t)carry * (uint32_t)a.Hkv;
+        uint32_t share = (total + (uint32_t)a.slots - 1u) / (uint32_t)a.slots;
+        if (share < (uint32_t)kMinShareTiles) share = kMinShareTiles;
+        a.plan[0] = (int)total;
+        a.plan[1] = (int)share;
+        a.plan[kPlanHeader] = 0;
+        s_share = (int)share;
+    }
+    __syncthreads(); /* also orders this workgroup's plan[] stores before the loads below */
+    const uint32_t share = (uint32_t)s_share;
+    int32_t *streams = a.plan + kPlanHeader + a.B + 1;
+    for (int s = tid; s < a.B * a.Hkv; s += 512) {
+        const int b = s / a.Hkv, hk = s - b * a.Hkv;
+        const uint32_t before = (uint32_t)a.plan[kPlanHeader + b];
+        const uint32_t seq_tiles = (uint32_t)a.plan[kPlanHeader + b + 1] - before;
+        const uint32_t first_tile = before * (uint32_t)a.Hkv + (uint32_t)hk * seq_tiles; /* in the global tile sequence */
+        const uint32_t w_first = first_tile / share;
+        streams[2 * s] = (int)w_first;
+        streams[2 * s + 1] = seq_tiles > 0 ? (int)((first_tile + seq_tiles - 1) / share - w_first) + 1 : 0;
+    }
+}
+
+/* workgroups [0, rows) rotate one query row each, workgroup `rows` builds the work plan */
+__global__ __launch_bounds__(512) void pq_rotate_q_kernel(RotateArgs a, PlanArgs p, int rows)
+{
+    if ((int)blockIdx.x < rows) rotate_query_row(a, (int)blockIdx.x);
+    else build_plan(p);
 }
 
 /* First launch of a whole decode step: workgroups [0, n) append the new key vectors,
-   [n, 2n) the new value vectors, the rest rotate one query row each; the three jobs are
-   independent of each other and all of them precede the attention proper. */
+   [n, 2n) the new value vectors, the next `rows` rotate one query row each and the last one
+   builds the work plan; the jobs are independent of each other and all of them precede
+   the attention proper. */
 template <int XT>
-__global__ __launch_bounds__(512) void pq_step_prologue_kernel(RotateArgs r, AppendArgs k, AppendArgs v, int n)
+__global__ __launch_bounds__(512) void pq_step_prologue_kernel(RotateArgs r, AppendArgs k, AppendArgs v, int n,
+                                                               PlanArgs p, int rows)
 {
     const int blk = (int)blockIdx.x;
     if (blk < n) append_vector<XT>(k, PQ_KEY, blk);
     else if (blk < 2 * n) append_vector<XT>(v, PQ_VALUE, blk - n);
-    else rotate_query_row(r, blk - 2 * n);
+    else if (blk < 2 * n + rows) rotate_query_row(r, blk - 2 * n);
+    else build_plan(p);
+}
+
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) x = fmaxf(x, __shfl_xor(x, d));
+    return x;
 }
 
 struct CombineArgs {
-    const float *ws_ml, *ws_o;
-    const int64_t *seq_start;
-    const int32_t *ctx_len;
-    int64_t max_ctx, pool_tiles;
-    int Hq, M, n_chunks, chunk_tiles; /* rows are ordered [B][M][Hq] */
+    const float *ws_ml, *ws_o; /* [piece][M * G pairs][2], [piece][M * G pairs][128] */
+    int B, Hq, Hkv, M; /* rows are ordered [B][M][Hq] */
+    const int32_t *plan;
     const float *St; /* St[j*128 + i] = S[i][j] */
     void *out;       /* bf16 or f32 [B][Hq][128] */
     int out_f32;
@@ -805,13 +986,18 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
     const int row = blockIdx.x;
     MatrixSlice ms; /* requested first: its latency overlaps the reads of the partial results */
     matrix_slice_load(ms, a.St, tid);
-    const int b = row / (a.M * a.Hq), mq = (row / a.Hq) % a.M;
-    /* query token mq sees the cache up to its own key: the sequence's context less the newer tokens */
-    const int ctx = max(effective_ctx(a.seq_start, a.ctx_len, b, a.max_ctx, a.pool_tiles) - (a.M - 1 - mq), 0);
-    const int n_tiles = (ctx + 63) >> 6;
-    const int used = min((n_tiles + a.chunk_tiles - 1) / a.chunk_tiles, a.n_chunks);
-    const float *ml = a.ws_ml + (int64_t)row * a.n_chunks * 2;
-    const float *op = a.ws_o + (int64_t)row * a.n_chunks * PQ_D + j;
+    const int b = row / (a.M * a.Hq), mq = (row / a.Hq) % a.M, head = row % a.Hq;
+    /* the pieces of this row's stream (sequence b, kv head hk): the wavefronts whose tile ranges
+       meet the stream's, in order; their ids are consecutive.  A piece beyond what query token
+       mq may see carries (m, l) = (-inf, 0) and drops out below. */
+    const int G = a.Hq / a.Hkv, hk = head / G, pairs = a.M * G, pair = mq * G + head % G;
+    const int s_index = b * a.Hkv + hk;
+    const int32_t *stream = a.plan + kPlanHeader + a.B + 1 + 2 * s_index;
+    const int w_first = stream[0], used = stream[1];
+    const int64_t slot0 = ((int64_t)w_first + s_index) * pairs + pair;
+    const int64_t ml_stride = 2 * (int64_t)pairs, o_stride = (int64_t)pairs * PQ_D;
+    const float *ml = a.ws_ml + slot0 * 2;
+    const float *op = a.ws_o + slot0 * PQ_D + j;
     int used_w = 0;
     const float *wml = nullptr, *wop = nullptr;
     if (HYBRID) {
@@ -821,18 +1007,25 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
         wml = a.win_ml + (int64_t)row * a.n_wchunks * 2;
         wop = a.win_o + (int64_t)row * a.n_wchunks * PQ_D + j;
     }
-    /* overall maximum first, then the weighted sums; thread group cq takes chunks cq, cq+4, ...
+    /* overall maximum first (every wavefront on its own: lane i reads the maximum of piece i, 64 + i, ...,
+       so the reads are in flight together), then the weighted sums; thread group cq takes chunks cq, cq+4, ...
        and the four group sums are added in a fixed order: the result does not depend on scheduling */
     float m = -INFINITY;
-    for (int c = 0; c < used; ++c) m = fmaxf(m, ml[2 * c]);
-    if (HYBRID)
-        for (int c = 0; c < used_w; ++c) m = fmaxf(m, wml[2 * c]);
+    {
+        const int lane = tid & 63;
+        for (int c = lane; c < used; c += 64) m = fmaxf(m, ml[c * ml_stride]);
+        if (HYBRID)
+            for (int c = lane; c < used_w; c += 64) m = fmaxf(m, wml[2 * c]);
+        m = wave_max(m);
+    }
     float l = 0.f, o = 0.f, ow = 0.f;
+    if (m != -INFINITY) {
 #pragma unroll 4
-    for (int c = cq; c < used; c += 4) {
-        const float w = exp2f(ml[2 * c] - m);
-        l = fmaf(ml[2 * c + 1], w, l);
-        o = fmaf(op[(int64_t)c * PQ_D], w, o);
+        for (int c = cq; c < used; c += 4) {
+            const float w = exp2f(ml[c * ml_stride] - m);
+            l = fmaf(ml[c * ml_stride + 1], w, l);
+            o = fmaf(op[c * o_stride], w, o);
+        }
     }
     if (HYBRID) {
         for (int c = cq; c < used_w; c += 4) {
@@ -852,15 +1045,15 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
         /* rebuilt values carry the table scale sigma of their coordinate */
         if (HYBRID) {
             owt = ((sw[0][j] + sw[1][j]) + sw[2][j]) + sw[3][j];
-            so[j] = used > 0 ? ot / a.consts->sigma[j & 15] : 0.f;
+            so[j] = ot / a.consts->sigma[j & 15];
         } else {
-            so[j] = used > 0 ? ot / (lt * a.consts->sigma[j & 15]) : 0.f;
+            so[j] = lt > 0.f ? ot / (lt * a.consts->sigma[j & 15]) : 0.f; /* lt == 0: no visible token */
         }
     }
     __syncthreads();
     float acc = vector_times_slice(so, ms, spart, tid); /* out_j = sum_k o'_k S[j][k] */
     if (tid < PQ_D) {
-        if (HYBRID) acc = (used > 0 || used_w > 0) ? (acc + owt) / lt : 0.f;
+        if (HYBRID) acc = lt > 0.f ? (acc + owt) / lt : 0.f;
         if (a.out_f32) {
             static_cast<float *>(a.out)[(int64_t)row * PQ_D + j] = acc;
         } else {
@@ -887,13 +1080,6 @@ struct WindowArgs {
     float *win_ml;          /* [B][Hq][n_wchunks][2] */
     float *win_o;           /* [B][Hq][n_wchunks][128] */
 };
-
-__device__ __forceinline__ float wave_max(float x)
-{
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) x = fmaxf(x, __shfl_xor(x, d));
-    return x;
-}
 
 __device__ __forceinline__ float wave_sum_fixed(float x)
 {
@@ -1012,38 +1198,40 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_window_kernel(Win
 }
 
 struct Plan {
-    int chunk_tiles, n_chunks;
-    size_t off_ml, off_o, total;
+    int slots;       /* wavefronts of the partial kernel's launch */
+    unsigned blocks; /* its workgroups */
+    size_t off_plan, off_ml, off_o, total;
     /* window partials (hybrid attention; n_wchunks == 0 otherwise) */
     int n_wchunks;
     size_t off_wml, off_wo;
 };
 
+/* Workspace: rotated queries | work plan | (m, l) of every piece | o' of every piece | window partials. */
 Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap = 0, int M = 1)
 {
     Plan p;
     int64_t max_tiles = (max_ctx + 63) / 64;
     if (max_tiles < 1) max_tiles = 1;
-    /* 256 CUs x 16 resident wavefronts (4 per SIMD): one work item per resident wavefront
-       measured fastest on the 32k-context batch (143 us against 149-156 us for 3/4 or 3/2
-       of that) and writes few partial results */
-    const int64_t target_items = 256 * 16;
-    int64_t streams = (int64_t)B * Hkv;
-    int64_t per_stream = (target_items + streams - 1) / streams;
-    if (per_stream < 1) per_stream = 1;
-    int64_t ct = (max_tiles + per_stream - 1) / per_stream;
-    if (ct < 4) ct = 4;
-    /* ragged batches: sequences shorter than max_ctx leave their upper chunks empty, so with long
-       chunks a few long sequences would set the pace; at most 32 tiles per chunk keeps the work items
-       small enough to balance (64 sequences of 1k..64k tokens: 6 % faster than uncapped) */
-    if (ct > 32) ct = 32;
-    if (ct > max_tiles) ct = max_tiles;
-    p.chunk_tiles = (int)ct;
-    p.n_chunks = (int)((max_tiles + ct - 1) / ct);
+    const int G = Hq / Hkv > 0 ? Hq / Hkv : 1;
+    const int pairs = M * G;
+    /* One wavefront per resident slot: 256 CUs x 4 SIMDs x the wavefronts per SIMD the kernel variant's
+       register budget allows.  Every wavefront gets an equal share of the tiles (see DevicePlan above), so one
+       round of resident wavefronts does the whole job and all of them finish together; more, smaller
+       work items measured slower on the 32k-context batch (143 us against 149-156 us for 3/2 or 2 times
+       as many) and write more partial results.  Small problems: no more wavefronts than shares of
+       kMinShareTiles tiles. */
+    const int per_simd = pairs <= 4 ? 4 : (pairs <= 8 ? 3 : 2);
+    int64_t slots = 256 * 4 * per_simd;
+    const int64_t most = ((int64_t)B * Hkv * max_tiles + kMinShareTiles - 1) / kMinShareTiles;
+    if (slots > most) slots = most;
+    p.blocks = (unsigned)((slots + kWavesPerBlock - 1) / kWavesPerBlock);
+    p.slots = (int)(p.blocks * kWavesPerBlock);
+    const size_t pieces = (size_t)p.slots + (size_t)B * Hkv; /* ids run below slots + streams */
     size_t rows = (size_t)B * M * Hq;
-    p.off_ml = (rows * 2 * PQ_D * sizeof(uint16_t) + 255) & ~(size_t)255;
-    p.off_o = (p.off_ml + rows * p.n_chunks * 2 * sizeof(float) + 255) & ~(size_t)255;
-    p.total = p.off_o + rows * p.n_chunks * PQ_D * sizeof(float);
+    p.off_plan = (rows * 2 * PQ_D * sizeof(uint16_t) + 255) & ~(size_t)255;
+    p.off_ml = (p.off_plan + (kPlanHeader + (size_t)B + 1 + 2 * (size_t)B * Hkv) * sizeof(int32_t) + 255) & ~(size_t)255;
+    p.off_o = (p.off_ml + pieces * pairs * 2 * sizeof(float) + 255) & ~(size_t)255;
+    p.total = p.off_o + pieces * pairs * PQ_D * sizeof(float);
     p.n_wchunks = (int)((win_cap + 63) / 64);
     p.off_wml = (p.total + 255) & ~(size_t)255;
     p.off_wo = (p.off_wml + rows * p.n_wchunks * 2 * sizeof(float) + 255) & ~(size_t)255;
@@ -1118,6 +1306,8 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
         return PQ_EINVAL;
     if (Hq % Hkv) return PQ_EINVAL;
     if (max_ctx > ((int64_t)1 << 26)) return PQ_EUNSUPPORTED; /* a sequence's tiles are addressed with 32-bit byte offsets */
+    /* the work plan counts the tiles of all (sequence, kv head) streams in 31 bits (288 GB of cache hold 2^25) */
+    if ((int64_t)B * Hkv * ((max_ctx + 63) / 64) >= ((int64_t)1 << 31) - 4096) return PQ_EUNSUPPORTED;
     if (out_dtype != PQ_BF16 && out_dtype != PQ_F32) return PQ_EINVAL;
     const int G = Hq / Hkv;
     if (G != 1 && G != 2 && G != 4 && G != 8) return PQ_EUNSUPPORTED;
@@ -1133,7 +1323,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
         if (!app->xk || !app->xv || !app->dst_token) return PQ_EINVAL;
         if (app->xt != PQ_F32 && app->xt != PQ_BF16) return PQ_EINVAL;
         if (!pq_aligned16(app->xk) || !pq_aligned16(app->xv)) return PQ_EALIGN;
-        if (2 * (int64_t)B * Hkv + (int64_t)B * Hq > 0x7FFFFFFF) return PQ_EINVAL;
+        if (2 * (int64_t)B * Hkv + (int64_t)B * Hq + 1 > 0x7FFFFFFF) return PQ_EINVAL;
     }
     if (win) {
         if (!win->win_k || !win->win_v || !win->win_len) return PQ_EINVAL;
@@ -1151,7 +1341,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     uint16_t *qrot = reinterpret_cast<uint16_t *>(ws);
     float *ws_ml = reinterpret_cast<float *>(ws + p.off_ml);
     float *ws_o = reinterpret_cast<float *>(ws + p.off_o);
-    if ((int64_t)B * M * Hq > 0x7FFFFFFF) return PQ_EINVAL;
+    if ((int64_t)B * M * Hq >= 0x7FFFFFFF) return PQ_EINVAL; /* one more workgroup builds the plan */
     const int rows = B * M * Hq;
 
     if (win) {
@@ -1167,16 +1357,18 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
         else hipLaunchKernelGGL(pq_attn_window_kernel<1>, wgrid, wblk, 0, s, wa);
     }
 
+    int32_t *plan = reinterpret_cast<int32_t *>(ws + p.off_plan);
+    const PlanArgs pa{seq_start, ctx_len, B, Hkv, max_ctx, pool_tokens / 64, p.slots, plan};
     RotateArgs ra{static_cast<const uint16_t *>(q), qrot, ds->S_f32, softmax_scale * kLog2e, ds->consts};
     if (app) {
         AppendArgs ak{app->xk, k_codes, k_radii, pool_tokens / 64, pool_tokens, app->dst_token, Hkv, ds->S_f32, ds->consts};
         AppendArgs av{app->xv, v_codes, v_radii, pool_tokens / 64, pool_tokens, app->dst_token, Hkv, ds->S_f32, ds->consts};
         const int n = B * Hkv;
-        const dim3 grid((unsigned)(2 * n + rows)), blk(512);
-        if (app->xt == PQ_BF16) hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_BF16>), grid, blk, 0, s, ra, ak, av, n);
-        else hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_F32>), grid, blk, 0, s, ra, ak, av, n);
+        const dim3 grid((unsigned)(2 * n + rows + 1)), blk(512);
+        if (app->xt == PQ_BF16) hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_BF16>), grid, blk, 0, s, ra, ak, av, n, pa, rows);
+        else hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_F32>), grid, blk, 0, s, ra, ak, av, n, pa, rows);
     } else {
-        hipLaunchKernelGGL(pq_rotate_q_kernel, dim3(rows), dim3(512), 0, s, ra);
+        hipLaunchKernelGGL(pq_rotate_q_kernel, dim3((unsigned)rows + 1u), dim3(512), 0, s, ra, pa, rows);
     }
     AttnArgs aa{};
     aa.qrot = qrot;
@@ -1185,21 +1377,19 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     aa.B = B; aa.Hq = Hq; aa.Hkv = Hkv; aa.M = M;
     aa.pool_tiles = pool_tokens / 64;
     aa.max_ctx = max_ctx;
-    aa.chunk_tiles = p.chunk_tiles; aa.n_chunks = p.n_chunks;
+    aa.plan = plan;
     aa.ws_ml = ws_ml; aa.ws_o = ws_o;
     aa.consts = ds->consts;
     aa.up_b5 = ctx->upper_bits[0]; aa.up_b6 = ctx->upper_bits[1]; aa.up_b7 = ctx->upper_bits[2];
-    const int64_t items = (int64_t)B * Hkv * p.n_chunks;
-    const unsigned blocks = (unsigned)((items + kWavesPerBlock - 1) / kWavesPerBlock);
     pq_prof_before(0, s);
-    const dim3 grid(blocks), blk(kWavesPerBlock * 64);
+    const dim3 grid(p.blocks), blk(kWavesPerBlock * 64);
     if (G == 8) launch_partial<8>(NG, deep, grid, blk, s, aa);
     else if (G == 4) launch_partial<4>(NG, deep, grid, blk, s, aa);
     else if (G == 2) launch_partial<2>(NG, deep, grid, blk, s, aa);
     else launch_partial<1>(NG, deep, grid, blk, s, aa);
     pq_prof_after(0, s);
 
-    CombineArgs ca{ws_ml, ws_o, seq_start, ctx_len, max_ctx, pool_tokens / 64, Hq, M, p.n_chunks, p.chunk_tiles,
+    CombineArgs ca{ws_ml, ws_o, B, Hq, Hkv, M, plan,
                    ds->St_f32, out, out_dtype == PQ_F32 ? 1 : 0, ds->consts,
                    reinterpret_cast<const float *>(ws + p.off_wml), reinterpret_cast<const float *>(ws + p.off_wo),
                    win ? win->win_len : nullptr, p.n_wchunks, win ? (int)win->win_cap : 0};

@@ -40,8 +40,10 @@ def boundary_distance(psi):
     return dist
 
 
-def check_codes(rec_gpu, rec_oracle, psi):
-    """Returns a dict of statistics; raises AssertionError when the acceptance rule fails."""
+def check_codes(rec_gpu, rec_oracle, psi, enforce_rate=True):
+    """Returns a dict of statistics; raises AssertionError when the acceptance rule fails.
+    enforce_rate=False leaves the rate limit to the caller, who pools the counts of several small calls
+    (on a few hundred angles one legitimate tie already exceeds the rate)."""
     Jg, rg = oracle.unpack(rec_gpu)
     Jo, ro = oracle.unpack(rec_oracle)
     bad = Jg != Jo
@@ -56,7 +58,8 @@ def check_codes(rec_gpu, rec_oracle, psi):
         lev = np.broadcast_to(_LEVEL_OF, Jo.shape)[bad]
         ok = (diff == 1) | ((lev == 1) & (diff == 15))
         assert np.all(ok), "a mismatching code is not the neighbouring cell"
-    assert stats["code_mismatch_rate"] <= CODE_MISMATCH_RATE, stats
+    if enforce_rate:
+        assert stats["code_mismatch_rate"] <= CODE_MISMATCH_RATE, stats
     return stats, rg, ro
 
 
@@ -106,7 +109,7 @@ def check_radii_deep(rg, ro, y_oracle):
     return stats
 
 
-def check_radii(rg, ro, y_oracle):
+def check_radii(rg, ro, y_oracle, enforce_rate=True):
     """rg, ro uint16 [n,8]; y_oracle [n,128] the oracle's rotated vectors (exact radii)."""
     bad = rg != ro
     n_bad = int(bad.sum())
@@ -122,7 +125,8 @@ def check_radii(rg, ro, y_oracle):
         rel = np.abs(r_exact[bad] - mid) / mid
         stats["worst_radius_rel_distance"] = float(rel.max())
         assert rel.max() <= RADIUS_REL_TOL, f"radius mismatch {rel.max():.3e} (relative) away from a rounding boundary"
-    assert stats["radius_mismatch_rate"] <= RADIUS_MISMATCH_RATE, stats
+    if enforce_rate:
+        assert stats["radius_mismatch_rate"] <= RADIUS_MISMATCH_RATE, stats
     return stats
 
 
