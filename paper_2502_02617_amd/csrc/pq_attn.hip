@@ -846,23 +846,43 @@ struct RotateArgs {
     const PqDeviceConsts *consts;
 };
 
-__device__ __forceinline__ void rotate_query_row(const RotateArgs &a, int row)
+/* Four query rows per workgroup: the workgroup's slice of S (64 KB, what bounds this launch) is
+ * fetched once for the four.  Thread (kq, j) accumulates the quarter kq of the sum over i for
+ * column j of each row; thread (r, j) then adds the four quarters of row r in a fixed order
+ * (the same order as vector_times_slice). */
+constexpr int kRotateRows = 4;
+
+__device__ __forceinline__ void rotate_query_rows(const RotateArgs &a, int row0, int n_rows)
 {
-    __shared__ float sq[PQ_D];
-    __shared__ float spart[4][PQ_D];
-    const int tid = threadIdx.x, j = tid & 127;
+    __shared__ float sq[kRotateRows][PQ_D];
+    __shared__ float spart[kRotateRows][4][PQ_D];
+    const int tid = threadIdx.x, r = tid >> 7, j = tid & 127;
     MatrixSlice ms;
     matrix_slice_load(ms, a.S, tid);
-    if (tid < PQ_D) sq[j] = __uint_as_float((uint32_t)a.q[(int64_t)row * PQ_D + j] << 16);
+    const int row = row0 + r;
+    sq[r][j] = row < n_rows ? __uint_as_float((uint32_t)a.q[(int64_t)row * PQ_D + j] << 16) : 0.f;
     __syncthreads();
-    const float acc = vector_times_slice(sq, ms, spart, tid); /* q'_j = sum_i q_i S[i][j] */
-    if (tid < PQ_D) {
+    {
+        const int kq = r; /* the same thread index split serves as (quarter, column) here */
+        float acc[kRotateRows];
+#pragma unroll
+        for (int rr = 0; rr < kRotateRows; ++rr) acc[rr] = 0.f;
+#pragma unroll
+        for (int k = 0; k < 32; ++k)
+#pragma unroll
+            for (int rr = 0; rr < kRotateRows; ++rr) acc[rr] = fmaf(sq[rr][32 * kq + k], ms.m[k], acc[rr]); /* q'_j = sum_i q_i S[i][j] */
+#pragma unroll
+        for (int rr = 0; rr < kRotateRows; ++rr) spart[rr][kq][j] = acc[rr];
+    }
+    __syncthreads();
+    if (row < n_rows) {
+        const float acc = ((spart[r][0][j] + spart[r][1][j]) + spart[r][2][j]) + spart[r][3][j];
         /* rebuilt keys carry the table scale sigma of their coordinate: take it out here */
         const float v = acc * a.scale / a.consts->sigma[j & 15];
         const _Float16 h = (_Float16)v;
-        const _Float16 r = (_Float16)(v - (float)h);
+        const _Float16 rem = (_Float16)(v - (float)h);
         a.qrot[(int64_t)row * 2 * PQ_D + j] = __builtin_bit_cast(uint16_t, h);
-        a.qrot[(int64_t)row * 2 * PQ_D + PQ_D + j] = __builtin_bit_cast(uint16_t, r);
+        a.qrot[(int64_t)row * 2 * PQ_D + PQ_D + j] = __builtin_bit_cast(uint16_t, rem);
     }
 }
 
@@ -929,25 +949,25 @@ __device__ __forceinline__ void build_plan(const PlanArgs &a)
     }
 }
 
-/* workgroups [0, rows) rotate one query row each, workgroup `rows` builds the work plan */
-__global__ __launch_bounds__(512) void pq_rotate_q_kernel(RotateArgs a, PlanArgs p, int rows)
+/* workgroups [0, row_blocks) rotate kRotateRows query rows each, the last workgroup builds the work plan */
+__global__ __launch_bounds__(512) void pq_rotate_q_kernel(RotateArgs a, PlanArgs p, int rows, int row_blocks)
 {
-    if ((int)blockIdx.x < rows) rotate_query_row(a, (int)blockIdx.x);
+    if ((int)blockIdx.x < row_blocks) rotate_query_rows(a, kRotateRows * (int)blockIdx.x, rows);
     else build_plan(p);
 }
 
 /* First launch of a whole decode step: workgroups [0, n) append the new key vectors,
-   [n, 2n) the new value vectors, the next `rows` rotate one query row each and the last one
-   builds the work plan; the jobs are independent of each other and all of them precede
+   [n, 2n) the new value vectors, the next row_blocks rotate kRotateRows query rows each and the
+   last one builds the work plan; the jobs are independent of each other and all of them precede
    the attention proper. */
 template <int XT>
 __global__ __launch_bounds__(512) void pq_step_prologue_kernel(RotateArgs r, AppendArgs k, AppendArgs v, int n,
-                                                               PlanArgs p, int rows)
+                                                               PlanArgs p, int rows, int row_blocks)
 {
     const int blk = (int)blockIdx.x;
     if (blk < n) append_vector<XT>(k, PQ_KEY, blk);
     else if (blk < 2 * n) append_vector<XT>(v, PQ_VALUE, blk - n);
-    else if (blk < 2 * n + rows) rotate_query_row(r, blk - 2 * n);
+    else if (blk < 2 * n + row_blocks) rotate_query_rows(r, kRotateRows * (blk - 2 * n), rows);
     else build_plan(p);
 }
 
@@ -1342,7 +1362,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     float *ws_ml = reinterpret_cast<float *>(ws + p.off_ml);
     float *ws_o = reinterpret_cast<float *>(ws + p.off_o);
     if ((int64_t)B * M * Hq >= 0x7FFFFFFF) return PQ_EINVAL; /* one more workgroup builds the plan */
-    const int rows = B * M * Hq;
+    const int rows = B * M * Hq, row_blocks = (rows + kRotateRows - 1) / kRotateRows;
 
     if (win) {
         WindowArgs wa{static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(win->win_k),
@@ -1364,11 +1384,11 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
         AppendArgs ak{app->xk, k_codes, k_radii, pool_tokens / 64, pool_tokens, app->dst_token, Hkv, ds->S_f32, ds->consts};
         AppendArgs av{app->xv, v_codes, v_radii, pool_tokens / 64, pool_tokens, app->dst_token, Hkv, ds->S_f32, ds->consts};
         const int n = B * Hkv;
-        const dim3 grid((unsigned)(2 * n + rows + 1)), blk(512);
-        if (app->xt == PQ_BF16) hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_BF16>), grid, blk, 0, s, ra, ak, av, n, pa, rows);
-        else hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_F32>), grid, blk, 0, s, ra, ak, av, n, pa, rows);
+        const dim3 grid((unsigned)(2 * n + row_blocks + 1)), blk(512);
+        if (app->xt == PQ_BF16) hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_BF16>), grid, blk, 0, s, ra, ak, av, n, pa, rows, row_blocks);
+        else hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_F32>), grid, blk, 0, s, ra, ak, av, n, pa, rows, row_blocks);
     } else {
-        hipLaunchKernelGGL(pq_rotate_q_kernel, dim3((unsigned)rows + 1u), dim3(512), 0, s, ra, pa, rows);
+        hipLaunchKernelGGL(pq_rotate_q_kernel, dim3((unsigned)row_blocks + 1u), dim3(512), 0, s, ra, pa, rows, row_blocks);
     }
     AttnArgs aa{};
     aa.qrot = qrot;
