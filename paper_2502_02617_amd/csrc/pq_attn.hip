@@ -82,6 +82,7 @@ struct AttnArgs {
     int64_t pool_tiles;
     int64_t max_ctx;
     const int32_t *plan; /* device work plan, see below */
+    int n_pieces;        /* piece ids run below this (sizes ws_ml, ws_o) */
     float *ws_ml; /* [piece][M * G pairs][2] */
     float *ws_o;  /* [piece][M * G pairs][128] */
     const PqDeviceConsts *consts;
@@ -693,11 +694,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
     const DeepRadii dr{sKrad[DEEP ? wave : 0], sVrad[DEEP ? wave : 0], a.up_b5, a.up_b6, a.up_b7};
     const uint32_t parity_shift = (n & 4) ? 16u : 0u;
     const int t4b = kT4B + ((n & 1) ? 4 : 0);
+    /* rotated queries and partial results: the launch code keeps all three below 4 GB */
+    const __amdgpu_buffer_rsrc_t q_rsrc = stream_descriptor(a.qrot, (uint32_t)a.B * a.M * a.Hq * (2 * PQ_D * 2u));
+    const __amdgpu_buffer_rsrc_t o_rsrc = stream_descriptor(a.ws_o, (uint32_t)a.n_pieces * (a.M * G) * (PQ_D * 4u));
+    const __amdgpu_buffer_rsrc_t ml_rsrc = stream_descriptor(a.ws_ml, (uint32_t)a.n_pieces * (a.M * G) * 8u);
 
     for (;;) { /* one piece per round: tiles [tile_lo, tile_hi) of stream (b, hk) */
         const int ctx = ctx_of(b);
         const int n_tiles = (ctx + 63) >> 6; /* == seq_tiles */
-        const int tile_hi = min(min(seq_tiles, n_tiles), tile_lo + (gend - gpos));
+        const int tile_hi = min(n_tiles, tile_lo + (gend - gpos)); /* n_tiles bounds every read inside the pool */
         const int piece_tiles = tile_hi - tile_lo;
         if (piece_tiles <= 0) return; /* cannot happen with a consistent plan */
         const int64_t piece = (int64_t)w + (int64_t)b * a.Hkv + hk;
@@ -726,10 +731,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
             const int pair = 4 * k + (nq & 3);
             const bool real = pair < a.M * G;
             const int m = real ? pair / G : 0, head = real ? pair % G : 0;
-            const uint4 *qp = reinterpret_cast<const uint4 *>(
-                a.qrot + ((((int64_t)b * a.M + m) * a.Hq + hk * G + head) * 2 + (nq >> 3)) * PQ_D + 32 * gq);
+            /* 32-bit offsets into the rotated queries: lane part in bytes, (sequence, kv head) part scalar */
+            const uint32_t lane_off = (uint32_t)(((m * a.Hq + head) * 2 + (nq >> 3)) * PQ_D + 32 * gq) * 2u;
+            const uint32_t row_off = (uint32_t)((b * a.M * a.Hq + hk * G) * 2 * PQ_D) * 2u;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) qb[k][s].q = real ? qp[s] : make_uint4(0, 0, 0, 0);
+            for (int s = 0; s < 4; ++s)
+                qb[k][s].q = real ? load16(q_rsrc, lane_off + 16u * s, row_off) : make_uint4(0, 0, 0, 0);
         }
         f4 acc_o[NG][4];
         float m_run[NG], l_run[NG];
@@ -809,16 +816,19 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
             const int pair = 4 * k + (ne & 3);
             if (ne < 8 && pair < a.M * G) {
                 const int par = (ne >> 2) & 1;
-                const int64_t slot = piece * (a.M * G) + pair;
-                float *o = a.ws_o + slot * PQ_D;
+                /* stores through descriptors as well: scalar piece offset, 32-bit lane offset */
+                const uint32_t piece_o = (uint32_t)piece * (uint32_t)(a.M * G) * (PQ_D * 4u);
+                const uint32_t lane_o = (uint32_t)(pair * PQ_D + 2 * 16 * ge + par) * 4u;
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        o[2 * (16 * ge + 4 * e + c) + par] = acc_o[k][c][e];
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc_o[k][c][e]), o_rsrc,
+                                                              lane_o + 8u * (4 * e + c), piece_o, 0);
                 if (ge == 0 && par == 0) {
-                    a.ws_ml[slot * 2] = m_run[k];
-                    a.ws_ml[slot * 2 + 1] = l;
+                    const uint32_t piece_ml = (uint32_t)piece * (uint32_t)(a.M * G) * 8u;
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(m_run[k]), ml_rsrc, pair * 8u, piece_ml, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(l), ml_rsrc, pair * 8u + 4u, piece_ml, 0);
                 }
             }
         }
@@ -1221,6 +1231,7 @@ struct Plan {
     int slots;       /* wavefronts of the partial kernel's launch */
     unsigned blocks; /* its workgroups */
     size_t off_plan, off_ml, off_o, total;
+    size_t pieces, o_bytes; /* piece ids run below `pieces`; bytes of their o' */
     /* window partials (hybrid attention; n_wchunks == 0 otherwise) */
     int n_wchunks;
     size_t off_wml, off_wo;
@@ -1247,6 +1258,8 @@ Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap = 0, int
     p.blocks = (unsigned)((slots + kWavesPerBlock - 1) / kWavesPerBlock);
     p.slots = (int)(p.blocks * kWavesPerBlock);
     const size_t pieces = (size_t)p.slots + (size_t)B * Hkv; /* ids run below slots + streams */
+    p.pieces = pieces;
+    p.o_bytes = pieces * pairs * PQ_D * sizeof(float);
     size_t rows = (size_t)B * M * Hq;
     p.off_plan = (rows * 2 * PQ_D * sizeof(uint16_t) + 255) & ~(size_t)255;
     p.off_ml = (p.off_plan + (kPlanHeader + (size_t)B + 1 + 2 * (size_t)B * Hkv) * sizeof(int32_t) + 255) & ~(size_t)255;
@@ -1352,6 +1365,8 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     }
     const Plan p = make_plan(B, Hq, Hkv, max_ctx, win ? win->win_cap : 0, M);
     if ((int64_t)B * Hkv * p.n_wchunks > 0x7FFFFFFF) return PQ_EINVAL;
+    /* the partial kernel addresses the rotated queries and its partial results with 32-bit byte offsets */
+    if ((uint64_t)B * M * Hq * (2 * PQ_D * 2) > 0xFFFFFFFFull || p.o_bytes > 0xFFFFFFFFull) return PQ_EUNSUPPORTED;
     if (workspace_bytes < p.total) return PQ_ENOMEM;
     const PqDeviceState *ds = nullptr;
     pq_status st = pq_device_state(ctx, &ds);
@@ -1398,6 +1413,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     aa.pool_tiles = pool_tokens / 64;
     aa.max_ctx = max_ctx;
     aa.plan = plan;
+    aa.n_pieces = (int)p.pieces;
     aa.ws_ml = ws_ml; aa.ws_o = ws_o;
     aa.consts = ds->consts;
     aa.up_b5 = ctx->upper_bits[0]; aa.up_b6 = ctx->upper_bits[1]; aa.up_b7 = ctx->upper_bits[2];
