@@ -16,8 +16,15 @@ consecutive steps cannot be served from the 256 MB last-level cache.
 
 Also reported: the roofline line of the dominant kernel (HIP events recorded
 around it on the launch stream during the timed steps), bulk-encode throughput
-on benchmark configs[1] (8 KV heads x 32768 tokens, keys and values), and
-the fp64 CPU oracle timed on a bounded sample of the same workload.
+on benchmark configs[1] (8 KV heads x 32768 tokens, keys and values), the
+decode step on configs[3] (batch 4 x 131072 tokens) and configs[4] (64 ragged
+sequences, 32 layers per step), the widened entry points (hybrid, several
+query tokens, full recursion depth), and the fp64 CPU oracle timed on a
+bounded sample of the same workload.
+
+The default warm-up is 100 steps (16 ms of GPU work): after the idle time of
+the set-up the chip needs some milliseconds of load to reach its steady
+clock, and the first steps run about 4 % slower than the rest.
 """
 import argparse
 import json
@@ -48,9 +55,9 @@ VALU_PEAK_GINSTR = 256 * 4 * 2.4 / 4.0
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
-    ap.add_argument("--warmup", type=int, default=6)
-    ap.add_argument("--encode-steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--encode-steps", type=int, default=60)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-seqs", type=int, default=16)
     args = ap.parse_args()
@@ -376,7 +383,7 @@ def main():
             ctx.decode_step_polar(new_k4, new_v4, newest4, q4, out4, kc_, kr_, vc_, vr_, seq_start4, ctx_len4,
                                   max_ctx4, scale, ws4)
 
-    ragged_steps = max(args.steps // 10, 2)
+    ragged_steps = max(args.steps // 20, 2)
     ragged_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()

@@ -210,8 +210,8 @@ __device__ __forceinline__ BlockCodes polar_quant_block(const Y16 &y, const Thre
 /* ---- decode-time append: one vector per (sequence, head) ----
  * Too little work for the matrix cores: one workgroup per vector computes
  * y_j = sum_i x_i S[i][j] in fp32 (S read from L2, four partial sums per
- * coordinate added in a fixed order), eight threads then run the polar recursion of one block each and patch the fields
- * into the tile in place.  Fields narrower than a byte share dwords with other
+ * coordinate added in a fixed order), the first wavefront then runs the polar recursion
+ * (one lane per level-1 pair) and patches the fields into the tile in place.  Fields narrower than a byte share dwords with other
  * slots of the tile, so they are updated with dword atomics. */
 struct AppendArgs {
     const void *x;
@@ -262,23 +262,59 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
     const bool deep = a.consts->depth == 7;
     const int64_t tile = dst >> 6;
     const int tau = (int)(dst & 63);
-    if (tid < 8) {
-        const int b = tid;
-        float y[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) y[r] = sy[16 * b + r];
+    if (tid < 64) {
+        /* The first wavefront runs the recursion with one lane per level-1 pair: lane p holds pair p & 7
+           of block p >> 3; the nodes of the upper levels sit in the lanes of their first leaf and fetch
+           the sibling's squared radius with a shuffle (the other lanes compute along and are ignored).
+           Operations and operand order per node are those of polar_quant_block. */
+        const int p = tid, i = p & 7, b = p >> 3;
         const Thresholds th = load_thresholds(*a.consts);
-        /* general codebooks: the level-1 table is read from the constants in global memory */
-        BlockCodes bc = a.consts->general ? polar_quant_block<true>(y, th) : polar_quant_block<false>(y, th);
-        uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
-        PqBlockPos pos = pql_pos(kind, tau, b);
-        *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[0]) = (uint16_t)(bc.l1 & 0xFFFFu);
-        *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[1]) = (uint16_t)(bc.l1 >> 16);
-        put_bits_global(gcodes, pos.g6_bit[0], 6, bc.g0);
-        put_bits_global(gcodes, pos.g6_bit[1], 6, bc.g1);
-        put_bits_global(gcodes, pos.c4_bit, 2, bc.c4);
-        if (deep) sq4[b] = bc.q4;
-        else a.radii[((int64_t)head * a.pool_tiles + tile) * PQL_RADII + pos.radius_half] = bc.radius;
+        const float ya = sy[2 * p], yb = sy[2 * p + 1];
+        uint32_t code1;
+        if (a.consts->general) { /* the level-1 table is read from the constants in global memory */
+            code1 = level1_code_general(ya, yb, th.lut1);
+        } else {
+            const uint32_t mq = quant3(fabsf(ya), fabsf(yb), th.t1a, th.t1c);
+            const uint32_t ba = __float_as_uint(ya), bb = __float_as_uint(yb);
+            const uint32_t f7 = (uint32_t)((int32_t)(ba ^ bb) >> 31) & 7u;
+            code1 = (mq ^ f7) + ((bb >> 28) & 8u);
+        }
+        const float q1 = __builtin_fmaf(ya, ya, yb * yb);
+        const float q1s = __shfl_xor(q1, 1);
+        const uint32_t c2 = a.consts->general ? quant3g(q1, q1s, th.t2a, th.t2b, th.t2c) : quant3(q1, q1s, th.t2a, th.t2c);
+        const float q2 = q1 + q1s;
+        const float q2s = __shfl_xor(q2, 2);
+        const uint32_t c3 = a.consts->general ? quant3g(q2, q2s, th.t3a, th.t3b, th.t3c) : quant3(q2, q2s, th.t3a, th.t3c);
+        const float q3 = q2 + q2s;
+        const float q3s = __shfl_xor(q3, 4);
+        BlockCodes bc;
+        bc.c4 = a.consts->general ? quant3g(q3, q3s, th.t4a, th.t4b, th.t4c) : quant3(q3, q3s, th.t4a, th.t4c);
+        bc.q4 = q3 + q3s;
+        const _Float16 rh = (_Float16)(__builtin_amdgcn_sqrtf(bc.q4) * th.radius_scale); /* round to nearest even */
+        bc.radius = __builtin_bit_cast(uint16_t, rh);
+        /* the block's fields gathered into its first lane: level-1 codes at their nibbles; the 6-bit
+           groups [c2(2h) | c3(h) | c2(2h+1)] of half-block h at bits [8h, 8h+6) of a second word */
+        uint32_t l1 = code1 << (4 * i);
+        uint32_t gw = (i & 1) ? 0u : ((i & 2) ? c2 : ((c2 << 4) | (c3 << 2))) << (2 * (i & 4));
+#pragma unroll
+        for (int d = 1; d < 8; d <<= 1) {
+            l1 |= __shfl_xor(l1, d);
+            gw |= __shfl_xor(gw, d);
+        }
+        bc.l1 = l1;
+        bc.g0 = gw & 63u;
+        bc.g1 = (gw >> 8) & 63u;
+        if (i == 0) {
+            uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
+            PqBlockPos pos = pql_pos(kind, tau, b);
+            *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[0]) = (uint16_t)(bc.l1 & 0xFFFFu);
+            *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[1]) = (uint16_t)(bc.l1 >> 16);
+            put_bits_global(gcodes, pos.g6_bit[0], 6, bc.g0);
+            put_bits_global(gcodes, pos.g6_bit[1], 6, bc.g1);
+            put_bits_global(gcodes, pos.c4_bit, 2, bc.c4);
+            if (deep) sq4[b] = bc.q4;
+            else a.radii[((int64_t)head * a.pool_tiles + tile) * PQL_RADII + pos.radius_half] = bc.radius;
+        }
     }
     if (deep) { /* levels 5..7 over the eight block radii: one thread, one whole word of the radius plane */
         __syncthreads();
