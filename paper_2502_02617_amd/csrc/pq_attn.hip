@@ -60,15 +60,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kProbShift = 9.0f;
 constexpr float kRefSlack = 6.0f;
 
-/* LDS table block (dwords).  Binary16 pairs for the value path: T1 [0,16)  T4 [16,20)
- * TA [32,48)  TB [48,64); T4 broadcast per half: [64,68) cos, [68,72) sin as (f, f) pairs.
- * fp32 for the key path: T1 [96,128) as 16 (cos, sin) pairs, one pair per two banks;
- * TA [128,160), TB [160,192), T4 [192,200): the low halves of all entries, then the high
- * halves (two 16-entry dword tables, one entry per bank, read with one two-address load). */
-constexpr int kT1 = 0, kT4 = 16, kTA = 32, kTB = 48, kT4B = 64, kT1F = 96;
-constexpr int kTAF = 128, kTBF = 160, kT4F = 192;
-/* full-depth recursion: (cos, sin) pairs of the centroids of levels 5, 6, 7, eight per level */
-constexpr int kTUp = 208, kTabDwords = 256;
+/* LDS table block: layout in pq_common.h (PQ_TAB_*), image built on the host */
+constexpr int kT1 = PQ_TAB_T1, kT4 = PQ_TAB_T4, kTA = PQ_TAB_TA, kTB = PQ_TAB_TB, kT4B = PQ_TAB_T4B, kT1F = PQ_TAB_T1F;
+constexpr int kTAF = PQ_TAB_TAF, kTBF = PQ_TAB_TBF, kT4F = PQ_TAB_T4F;
+constexpr int kTUp = PQ_TAB_UP, kTabDwords = PQ_TAB_DWORDS;
+static_assert(kTabDwords == kWavesPerBlock * 64, "one table dword per thread of a workgroup");
 
 struct AttnArgs {
     const uint16_t *qrot; /* [B][M][Hq][2][128] binary16: rotated, pre-scaled q' as a leading part and its remainder */
@@ -613,25 +609,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
         st_len = a.ctx_len[min(bb, a.B - 1)];
         st_start = a.seq_start[min(bb, a.B - 1)];
     }
-    {
-        const PqDeviceConsts &K = *a.consts;
-        int t = threadIdx.x;
-        if (t < 16) { tab[kT1 + t] = K.t1_h2[t]; tab[kTA + t] = K.ta_h2[t]; tab[kTB + t] = K.tb_h2[t]; }
-        if (t < 4) {
-            uint32_t cs = K.t4_h2[t];
-            tab[kT4 + t] = cs;
-            tab[kT4B + t] = (cs & 0xFFFFu) * 0x10001u;
-            tab[kT4B + 4 + t] = (cs >> 16) * 0x10001u;
-        }
-        if (t >= 20 && t < 32) tab[t] = 0u;
-        if (t >= 72 && t < 96) tab[t] = 0u;
-        if (t >= 96 && t < 128) tab[t] = __float_as_uint(K.t1_f32[(t - 96) >> 1][t & 1]);
-        if (t >= 128 && t < 160) tab[t] = __float_as_uint(K.ta_f32[(t - 128) >> 4][t & 15]);
-        if (t >= 160 && t < 192) tab[t] = __float_as_uint(K.tb_f32[(t - 160) >> 4][t & 15]);
-        if (t >= 192 && t < 200) tab[t] = __float_as_uint(K.t4_f32[(t - 192) >> 2][t & 3]);
-        if (t >= 200 && t < 208) tab[t] = 0u;
-        if (t >= kTUp && t < kTUp + 48) tab[t] = DEEP ? __float_as_uint(K.up_cs[(t - kTUp) >> 4][((t - kTUp) >> 1) & 7][t & 1]) : 0u;
-    }
+    tab[threadIdx.x] = a.consts->attn_tab[threadIdx.x];
     if (staged && threadIdx.x >= 192) {
         const int bb = (int)threadIdx.x - 192;
         sPre[bb] = st_pre;

@@ -55,6 +55,20 @@ struct PqDeviceConsts {
     int up_bits[3];
     float up_tan2[3][7];
     float up_cs[3][8][2];
+    /* The attention kernels' LDS table block, entry for entry (layout: PQ_TAB_* below), so that a
+       workgroup fills its LDS with one coalesced load per thread. */
+    uint32_t attn_tab[256];
+};
+
+/* LDS table block of the attention kernels (dwords).  Binary16 pairs for the value path: T1 [0,16)
+ * T4 [16,20)  TA [32,48)  TB [48,64); T4 broadcast per half: [64,68) cos, [68,72) sin as (f, f) pairs.
+ * fp32 for the key path: T1 [96,128) as 16 (cos, sin) pairs, one pair per two banks;
+ * TA [128,160), TB [160,192), T4 [192,200): the low halves of all entries, then the high
+ * halves (two 16-entry dword tables, one entry per bank, read with one two-address load).
+ * Full-depth recursion: (cos, sin) pairs of the centroids of levels 5, 6, 7, eight per level, from 208. */
+enum {
+    PQ_TAB_T1 = 0, PQ_TAB_T4 = 16, PQ_TAB_TA = 32, PQ_TAB_TB = 48, PQ_TAB_T4B = 64, PQ_TAB_T1F = 96,
+    PQ_TAB_TAF = 128, PQ_TAB_TBF = 160, PQ_TAB_T4F = 192, PQ_TAB_UP = 208, PQ_TAB_DWORDS = 256
 };
 
 /* Radius plane of a tile.  Depth 4: 512 binary16 block radii (pq_layout.h).  Depth 7: 64 words,

@@ -315,6 +315,31 @@ void build_tables(pq_ctx *ctx)
         int h = i >> 3, q = (i >> 1) & 3, par = i & 1;
         c.sigma[i] = (float)(s4[h] * (q < 2 ? sa[q & 1] : sb[q & 1]) * s1[par]);
     }
+    /* the attention kernels' LDS image of the tables above */
+    auto f2u = [](float f) { uint32_t u; memcpy(&u, &f, 4); return u; };
+    for (int t = 0; t < PQ_TAB_DWORDS; ++t) c.attn_tab[t] = 0u;
+    for (int k = 0; k < 16; ++k) {
+        c.attn_tab[PQ_TAB_T1 + k] = c.t1_h2[k];
+        c.attn_tab[PQ_TAB_TA + k] = c.ta_h2[k];
+        c.attn_tab[PQ_TAB_TB + k] = c.tb_h2[k];
+        c.attn_tab[PQ_TAB_T1F + 2 * k] = f2u(c.t1_f32[k][0]);
+        c.attn_tab[PQ_TAB_T1F + 2 * k + 1] = f2u(c.t1_f32[k][1]);
+        for (int col = 0; col < 2; ++col) {
+            c.attn_tab[PQ_TAB_TAF + 16 * col + k] = f2u(c.ta_f32[col][k]);
+            c.attn_tab[PQ_TAB_TBF + 16 * col + k] = f2u(c.tb_f32[col][k]);
+        }
+    }
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t cs = c.t4_h2[k];
+        c.attn_tab[PQ_TAB_T4 + k] = cs;
+        c.attn_tab[PQ_TAB_T4B + k] = (cs & 0xFFFFu) * 0x10001u;
+        c.attn_tab[PQ_TAB_T4B + 4 + k] = (cs >> 16) * 0x10001u;
+        for (int col = 0; col < 2; ++col) c.attn_tab[PQ_TAB_T4F + 4 * col + k] = f2u(c.t4_f32[col][k]);
+    }
+    if (ctx->depth == 7)
+        for (int l = 0; l < 3; ++l)
+            for (int k = 0; k < 8; ++k)
+                for (int h = 0; h < 2; ++h) c.attn_tab[PQ_TAB_UP + 16 * l + 2 * k + h] = f2u(c.up_cs[l][k][h]);
 }
 
 } // namespace
