@@ -142,9 +142,16 @@ size_t pq_fit_workspace_bytes(void);
  * little endian, the radius little endian).  Like pq_set_codebooks this must precede the
  * first launch with the context (PQ_EINVAL afterwards).  At depth 7 pq_encode_kv,
  * pq_append_kv(_pair), pq_decode_kv, pq_export_canonical and every attention entry
- * point follow the new format; pq_set_codebooks (levels 1..4) combines with it, the
- * codebooks of levels 5..7 stay the analytic ones. */
+ * point follow the new format; pq_set_codebooks (levels 1..4) combines with it, and
+ * pq_set_upper_codebooks replaces the codebooks of levels 5..7. */
 pq_status pq_set_recursion_depth(pq_ctx *ctx, int depth, const int *upper_bits);
+/* Replaces the codebooks of levels 5, 6, 7 of a depth-7 context (Algorithm 1 takes a
+ * codebook per level as input; Section 4.1's online variant fits them to the data): cbt
+ * (host) [3][8] doubles, row l-5 holds the 2^bits(l) centroids of level l in (0, pi/2),
+ * strictly increasing, the rest of the row ignored.  Cell boundaries are the midpoints
+ * of neighbouring centroids.  After pq_set_recursion_depth(ctx, 7, ...) and before the
+ * first launch with the context (PQ_EINVAL otherwise). */
+pq_status pq_set_upper_codebooks(pq_ctx *ctx, const double *cbt);
 int pq_recursion_depth(const pq_ctx *ctx);
 int pq_radii_halves_per_tile(const pq_ctx *ctx);
 int pq_record_bytes(const pq_ctx *ctx);

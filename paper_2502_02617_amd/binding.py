@@ -51,6 +51,8 @@ def library():
     L.pq_fit_workspace_bytes.argtypes = []
     L.pq_set_recursion_depth.restype = i32
     L.pq_set_recursion_depth.argtypes = [vp, i32, vp]
+    L.pq_set_upper_codebooks.restype = i32
+    L.pq_set_upper_codebooks.argtypes = [vp, vp]
     L.pq_recursion_depth.restype = i32
     L.pq_recursion_depth.argtypes = [vp]
     L.pq_radii_halves_per_tile.restype = i32
@@ -197,6 +199,13 @@ class Context:
             if bits.size != 3:
                 raise PolarQuantError("upper_bits must hold 3 widths")
         _check(library().pq_set_recursion_depth(self._h, int(depth), bits.ctypes.data_as(ctypes.c_void_p) if bits is not None else None))
+
+    def set_upper_codebooks(self, cbt):
+        """Centroids of levels 5, 6, 7 of a depth-7 context, array [3, 8] (2^bits used per row); before the first launch."""
+        c = np.ascontiguousarray(cbt, dtype=np.float64)
+        if c.shape != (3, 8):
+            raise PolarQuantError("cbt must have shape [3, 8]")
+        _check(library().pq_set_upper_codebooks(self._h, c.ctypes.data_as(ctypes.c_void_p)))
 
     def recursion_depth(self):
         return int(library().pq_recursion_depth(self._h))

@@ -478,6 +478,33 @@ extern "C" pq_status pq_set_recursion_depth(pq_ctx *ctx, int depth, const int *u
     return PQ_OK;
 }
 
+extern "C" pq_status pq_set_upper_codebooks(pq_ctx *ctx, const double *cbt)
+{
+    if (!ctx || !cbt) return PQ_EINVAL;
+    std::lock_guard<std::mutex> lock(ctx->mu);
+    if (ctx->depth != 7) return PQ_EINVAL;
+    for (int i = 0; i < PQ_MAX_DEVICES; ++i)
+        if (ctx->dev[i].ready) return PQ_EINVAL; /* tables already on a device: the context is in use */
+    for (int l = 0; l < 3; ++l) {
+        const int K = 1 << ctx->upper_bits[l];
+        for (int k = 0; k < K; ++k) {
+            const double t = cbt[8 * l + k];
+            if (!isfinite(t) || t <= 0.0 || t >= kPi / 2.0) return PQ_EINVAL;
+            if (k > 0 && !(t > cbt[8 * l + k - 1])) return PQ_EINVAL; /* strictly increasing */
+        }
+    }
+    for (int l = 0; l < 3; ++l) {
+        const int K = 1 << ctx->upper_bits[l];
+        for (int k = 0; k < K; ++k) ctx->upper_centroids[l][k] = cbt[8 * l + k];
+        ctx->upper_boundaries[l][0] = 0.0;
+        ctx->upper_boundaries[l][K] = kPi / 2.0;
+        for (int k = 1; k < K; ++k)
+            ctx->upper_boundaries[l][k] = 0.5 * (ctx->upper_centroids[l][k - 1] + ctx->upper_centroids[l][k]);
+    }
+    build_tables(ctx);
+    return PQ_OK;
+}
+
 extern "C" int pq_recursion_depth(const pq_ctx *ctx) { return ctx ? ctx->depth : 0; }
 
 extern "C" int pq_radii_halves_per_tile(const pq_ctx *ctx)

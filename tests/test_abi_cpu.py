@@ -200,6 +200,23 @@ def test_recursion_depth_validation_and_upper_codebooks():
     gen.set_codebooks(oracle.default_codebooks())
     gen.set_recursion_depth(7, [2, 2, 2])
     assert deep.record_bytes() == 50 and gen.record_bytes() == 50
+    # codebooks of levels 5-7 set by the caller: only at depth 7, increasing inside (0, pi/2), midpoint boundaries
+    with pytest.raises(PolarQuantError):
+        Context(seed=0).set_upper_codebooks(oracle.upper_codebooks([2, 2, 2]))
+    cbt = oracle.upper_codebooks([2, 2, 2])
+    for bad_row, bad_val in ((0, [0.9, 0.8, 1.0, 1.1]), (1, [0.0, 0.5, 0.7, 0.9]), (2, [0.5, 0.7, 0.9, 1.6])):
+        bad = cbt.copy()
+        bad[bad_row, :4] = bad_val
+        with pytest.raises(PolarQuantError):
+            deep.set_upper_codebooks(bad)
+    mine = cbt.copy()
+    mine[:, :4] += np.array([[-0.01, 0.004, -0.003, 0.008]])
+    deep.set_upper_codebooks(mine)
+    for level in (5, 6, 7):
+        b, cen, bnd = deep.upper_codebook(level)
+        assert b == 2 and np.array_equal(cen, mine[level - 5, :4])
+        assert bnd[0] == 0.0 and abs(bnd[-1] - np.pi / 2) <= 1e-15
+        assert np.max(np.abs(bnd[1:-1] - 0.5 * (cen[:-1] + cen[1:]))) <= 1e-15
 
 
 def test_bench_refuses_more_than_one_gpu():

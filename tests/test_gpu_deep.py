@@ -110,10 +110,10 @@ def test_deep_encode_hadamard_preconditioner():
     say(f"  {check_records(rec_gpu, rec_or, psi, y, bits)}")
 
 
-def test_deep_with_caller_set_codebooks():
-    """Full depth together with codebooks replaced for levels 1-4 (jittered centroids): encode, append and
-    attention follow both."""
-    bits = (2, 2, 2)
+@pytest.mark.parametrize("bits,upper", [((2, 2, 2), False), ((2, 2, 2), True), ((3, 1, 2), True)])
+def test_deep_with_caller_set_codebooks(bits, upper):
+    """Full depth together with codebooks replaced for levels 1-4 (jittered centroids) and, with
+    upper, for levels 5-7 as well: encode, append and DeQuant follow them."""
     rng = np.random.default_rng(77)
     cb = oracle.default_codebooks()
     cb[:16] += rng.uniform(-0.05, 0.05, 16)
@@ -122,8 +122,19 @@ def test_deep_with_caller_set_codebooks():
     ctx.set_codebooks(cb)
     ctx.set_recursion_depth(7, bits)
     S, cbt = oracle.preconditioner(0), oracle.upper_codebooks(bits)
+    if upper:
+        for l in range(3):
+            K = 1 << bits[l]
+            cbt[l, :K] += rng.uniform(-0.01, 0.01, K)
+        ctx.set_upper_codebooks(cbt)
+        for l in range(3):
+            got_bits, cen, bnd = ctx.upper_codebook(5 + l)
+            K = 1 << bits[l]
+            assert got_bits == bits[l] and np.array_equal(cen[:K], cbt[l, :K])
+            assert np.allclose(bnd[1:K], 0.5 * (cbt[l, :K - 1] + cbt[l, 1:K]), rtol=0, atol=1e-15)
     T, H = 500, 2
     say(f"deep + caller-set codebooks: T={T} H={H}")
+    caches, records = {}, {}
     for kind in (PQ_KEY, PQ_VALUE):
         x = synth.kv_stream(T, H, seed=81 + kind).permute(1, 0, 2).contiguous()
         codes, top = ctx.alloc_cache_for(H, 512, DEV)
@@ -141,7 +152,8 @@ def test_deep_with_caller_set_codebooks():
         bad = Jg != Jo
         say(f"  kind {kind}: {int(bad.sum())} code mismatches of {Jo.size}, {int((rg != ro).sum())} radius mismatches")
         if bad.any():
-            tables = [cb[0:16], cb[16:20], cb[20:24], cb[24:28], cbt[0, :4], cbt[1, :4], cbt[2, :4]]
+            tables = [cb[0:16], cb[16:20], cb[20:24], cb[24:28], cbt[0, :1 << bits[0]], cbt[1, :1 << bits[1]],
+                      cbt[2, :1 << bits[2]]]
             level = np.concatenate([np.full(64, 0), np.full(32, 1), np.full(16, 2), np.full(8, 3), np.full(4, 4), np.full(2, 5), [6]])
             psi2 = psi.reshape(-1, 127)
             for n_, a_ in zip(*np.nonzero(bad)):
@@ -155,6 +167,21 @@ def test_deep_with_caller_set_codebooks():
         torch.cuda.synchronize()
         for h in range(H):
             assert helpers.rel_l2(out.cpu().numpy()[:, h], oracle.decode_deep(rec_gpu[h], S, cb, bits, cbt)) <= 1e-5
+        caches[kind], records[kind] = (codes, top), rec_gpu
+    # attention on the two caches against the oracle on the same (exported) records
+    n, Hq = 491, 4 * H
+    q = synth.queries(1, Hq, seed=83)
+    out = torch.empty((1, Hq, 128), dtype=torch.float32, device=DEV)
+    ws = torch.empty(Context.attn_workspace_bytes(1, Hq, H, n), dtype=torch.uint8, device=DEV)
+    ctx.attn_decode_polar(q.to(DEV), out, caches[PQ_KEY][0], caches[PQ_KEY][1], caches[PQ_VALUE][0], caches[PQ_VALUE][1],
+                          torch.zeros(1, dtype=torch.int64, device=DEV), torch.tensor([n], dtype=torch.int32, device=DEV),
+                          n, helpers.softmax_scale(), ws)
+    torch.cuda.synchronize()
+    ref = oracle.attention_deep(q.to(torch.float64).numpy(), records[PQ_KEY], records[PQ_VALUE], np.zeros(1, np.int64),
+                                np.array([n], np.int32), S, cb, bits, cbt, helpers.softmax_scale())
+    err = helpers.rel_l2(out.cpu().numpy(), ref)
+    say(f"  attention rel L2 {err:.2e}")
+    assert err <= 2e-3
 
 
 def test_deep_offsets_and_append():
