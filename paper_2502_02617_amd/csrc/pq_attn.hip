@@ -1099,14 +1099,12 @@ __device__ __forceinline__ float wave_sum_fixed(float x)
 
 /* G = query heads handled by one wavefront: the group of a kv head (Hq/Hkv), or half of it when the group
    has four heads -- the kernel has little work per launch and runs faster spread over more wavefronts */
+constexpr int kWindowWaves = 4; /* work items per workgroup: one per SIMD, as many workgroups as possible */
+
 template <int G>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_window_kernel(WindowArgs a)
+__device__ __forceinline__ void window_item(const WindowArgs &a, int64_t item, int wave, int lane,
+                                            float (&sq)[kWindowWaves][G][PQ_D], float (&sp)[kWindowWaves][G][64])
 {
-    __shared__ float sq[kWavesPerBlock][G][PQ_D];
-    __shared__ float sp[kWavesPerBlock][G][64];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
     const int n_hg = a.Hq / G; /* head groups of G heads; head0 = first query head of this wavefront */
     const int wc = (int)(item % a.n_wchunks);
     const int head0 = (int)((item / a.n_wchunks) % n_hg) * G;
@@ -1202,6 +1200,28 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void pq_attn_window_kernel(Win
             a.win_ml[slot * 2] = m[h];
             a.win_ml[slot * 2 + 1] = l[h];
         }
+    }
+}
+
+/* First launch of hybrid attention: workgroups [0, wblocks) take four window items each (the first four
+   wavefronts; these are the longest jobs of the launch, so they start first), the next row_blocks rotate
+   the queries, the last one builds the work plan.  The window partials need the original queries only,
+   so they share this launch instead of taking one of their own before it. */
+template <int G>
+__global__ __launch_bounds__(512) void pq_rotate_window_kernel(RotateArgs r, PlanArgs p, int rows, int row_blocks, WindowArgs w,
+                                                               int wblocks)
+{
+    const int blk = (int)blockIdx.x;
+    if (blk < wblocks) {
+        __shared__ float sq[kWindowWaves][G][PQ_D];
+        __shared__ float sp[kWindowWaves][G][64];
+        const int lane = threadIdx.x & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        if (wave < kWindowWaves) window_item<G>(w, (int64_t)blk * kWindowWaves + wave, wave, lane, sq, sp);
+    } else if (blk < wblocks + row_blocks) {
+        rotate_query_rows(r, kRotateRows * (blk - wblocks), rows);
+    } else {
+        build_plan(p);
     }
 }
 
@@ -1357,19 +1377,6 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     if ((int64_t)B * M * Hq >= 0x7FFFFFFF) return PQ_EINVAL; /* one more workgroup builds the plan */
     const int rows = B * M * Hq, row_blocks = (rows + kRotateRows - 1) / kRotateRows;
 
-    if (win) {
-        WindowArgs wa{static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(win->win_k),
-                      static_cast<const uint16_t *>(win->win_v), win->win_len, B, Hq, Hkv, (int)win->win_cap,
-                      p.n_wchunks, softmax_scale * kLog2e, reinterpret_cast<float *>(ws + p.off_wml),
-                      reinterpret_cast<float *>(ws + p.off_wo)};
-        const int per_wave = G == 4 ? 2 : 1; /* query heads per wavefront */
-        const int64_t witems = (int64_t)B * (Hq / per_wave) * p.n_wchunks;
-        if (witems > 0x7FFFFFFF) return PQ_EINVAL;
-        const dim3 wgrid((unsigned)((witems + kWavesPerBlock - 1) / kWavesPerBlock)), wblk(kWavesPerBlock * 64);
-        if (per_wave == 2) hipLaunchKernelGGL(pq_attn_window_kernel<2>, wgrid, wblk, 0, s, wa);
-        else hipLaunchKernelGGL(pq_attn_window_kernel<1>, wgrid, wblk, 0, s, wa);
-    }
-
     int32_t *plan = reinterpret_cast<int32_t *>(ws + p.off_plan);
     const PlanArgs pa{seq_start, ctx_len, B, Hkv, max_ctx, pool_tokens / 64, p.slots, plan};
     RotateArgs ra{static_cast<const uint16_t *>(q), qrot, ds->S_f32, softmax_scale * kLog2e, ds->consts};
@@ -1380,6 +1387,18 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
         const dim3 grid((unsigned)(2 * n + row_blocks + 1)), blk(512);
         if (app->xt == PQ_BF16) hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_BF16>), grid, blk, 0, s, ra, ak, av, n, pa, rows, row_blocks);
         else hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_F32>), grid, blk, 0, s, ra, ak, av, n, pa, rows, row_blocks);
+    } else if (win) {
+        WindowArgs wa{static_cast<const uint16_t *>(q), static_cast<const uint16_t *>(win->win_k),
+                      static_cast<const uint16_t *>(win->win_v), win->win_len, B, Hq, Hkv, (int)win->win_cap,
+                      p.n_wchunks, softmax_scale * kLog2e, reinterpret_cast<float *>(ws + p.off_wml),
+                      reinterpret_cast<float *>(ws + p.off_wo)};
+        const int per_wave = G == 4 ? 2 : 1; /* query heads per wavefront */
+        const int64_t witems = (int64_t)B * (Hq / per_wave) * p.n_wchunks;
+        const int64_t wblocks = (witems + kWindowWaves - 1) / kWindowWaves;
+        if (wblocks + row_blocks + 1 > 0x7FFFFFFF) return PQ_EINVAL;
+        const dim3 grid((unsigned)(row_blocks + 1 + wblocks)), blk(512);
+        if (per_wave == 2) hipLaunchKernelGGL(pq_rotate_window_kernel<2>, grid, blk, 0, s, ra, pa, rows, row_blocks, wa, (int)wblocks);
+        else hipLaunchKernelGGL(pq_rotate_window_kernel<1>, grid, blk, 0, s, ra, pa, rows, row_blocks, wa, (int)wblocks);
     } else {
         hipLaunchKernelGGL(pq_rotate_q_kernel, dim3((unsigned)row_blocks + 1u), dim3(512), 0, s, ra, pa, rows, row_blocks);
     }
