@@ -320,7 +320,7 @@ pq_status pq_decode_step_polar(const pq_ctx *ctx, const void *xk, const void *xv
  * pq_attn_decode_polar (ctx_len counts the quantised tokens only); workspace:
  * at least pq_attn_hybrid_workspace_bytes(B, Hq, Hkv, max_ctx, win_cap) bytes.
  * A sequence with neither prefix nor window gives a zero output row.
- * Hq/Hkv must be 1, 2 or 4 here (PQ_EUNSUPPORTED for 8).
+ * Hq/Hkv must be 1, 2, 4 or 8.
  * ------------------------------------------------------------------------- */
 pq_status pq_attn_decode_hybrid(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
                                 const uint8_t *k_codes, const uint16_t *k_radii,

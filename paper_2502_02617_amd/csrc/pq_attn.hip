@@ -1344,7 +1344,6 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     if (G != 1 && G != 2 && G != 4 && G != 8) return PQ_EUNSUPPORTED;
     if (M < 1 || M * G > 16) return PQ_EUNSUPPORTED;   /* at most 16 (query token, head) pairs per kv head */
     if ((app || win) && M != 1) return PQ_EUNSUPPORTED;
-    if (win && G == 8) return PQ_EUNSUPPORTED; /* the window kernel handles groups of 1, 2 or 4 query heads */
     const int NG = M * G <= 4 ? 1 : (M * G <= 8 ? 2 : 4);
     const bool deep = ctx->depth == 7;
     if (!pq_aligned16(q) || !pq_aligned16(out) || !pq_aligned16(k_codes) || !pq_aligned16(k_radii) ||
@@ -1392,7 +1391,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
                       static_cast<const uint16_t *>(win->win_v), win->win_len, B, Hq, Hkv, (int)win->win_cap,
                       p.n_wchunks, softmax_scale * kLog2e, reinterpret_cast<float *>(ws + p.off_wml),
                       reinterpret_cast<float *>(ws + p.off_wo)};
-        const int per_wave = G == 4 ? 2 : 1; /* query heads per wavefront */
+        const int per_wave = G >= 4 ? 2 : 1; /* query heads per wavefront */
         const int64_t witems = (int64_t)B * (Hq / per_wave) * p.n_wchunks;
         const int64_t wblocks = (witems + kWindowWaves - 1) / kWindowWaves;
         if (wblocks + row_blocks + 1 > 0x7FFFFFFF) return PQ_EINVAL;

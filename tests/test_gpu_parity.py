@@ -575,7 +575,7 @@ def test_decode_step_under_graph_replay(env):
     assert torch.isfinite(out).all()
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (2, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (2, 2), (16, 2)])
 def test_hybrid_attention_prefix_plus_window(env, Hq, Hkv):
     """Quantised prefix + bf16 window against the oracle: every mix of empty / one-tile / ragged prefix and
     empty / partial / several-chunk window."""
