@@ -294,6 +294,32 @@ def upper_codebooks(bits):
     return cbt
 
 
+def fit_upper_codebooks(x, S, bits, cbt_init, iterations):
+    """Online codebooks of levels 5, 6, 7 (Section 4.1's k-means on the data's own angles, at the levels
+    that Definition 1 adds above level 4): `iterations` Lloyd rounds per level on the exact angles of
+    x[n,128] rotated by S, from the centroids cbt_init[3,8] (2^bits[l-5] used per row) -> [3,8].
+    Nearest centroid by linear distance, the lower cell on a tie; a centroid with an empty cell stays."""
+    b = _bits(bits)
+    cbt = _f64(cbt_init).reshape(3, 8).copy()
+    x = _f64(x).reshape(-1, D)
+    _, psi, _ = encode_deep(x, S, default_codebooks(), b, upper_codebooks(b), want_psi=True, want_y=True)
+    psi = psi.reshape(-1, NANG_DEEP)
+    cols = ((120, 124), (124, 126), (126, 127))
+    for l in range(3):
+        K = 1 << int(b[l])
+        samples = np.sort(psi[:, cols[l][0]:cols[l][1]].reshape(-1))
+        c = cbt[l, :K].copy()
+        for _ in range(int(iterations)):
+            edges = 0.5 * (c[:-1] + c[1:])
+            cell = np.searchsorted(edges, samples, side="left")
+            for k in range(K):
+                mine = samples[cell == k]
+                if mine.size:
+                    c[k] = mine.mean()
+        cbt[l, :K] = c
+    return cbt
+
+
 def unpack_deep(rec, bits):
     rec = np.ascontiguousarray(rec, dtype=np.uint8).reshape(-1, REC_DEEP)
     b = _bits(bits)

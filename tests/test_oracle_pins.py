@@ -541,6 +541,41 @@ def test_online_codebook_fit_is_kmeans_on_the_angles(S, cb):
     assert np.max(np.abs(far[16:] - cb[16:])) <= 0.02
 
 
+@pytest.mark.parametrize("bits", [(2, 2, 2), (3, 1, 2)])
+def test_online_fit_of_upper_level_codebooks(S, bits):
+    """The same k-means for the angles of levels 5-7 (one vector gives 4, 2 and 1 of them): against
+    scikit-learn's Lloyd from the same start, the decrease of the sample distortion, the approach to
+    the Lloyd-Max quantisers of Lemma 2's densities on Gaussian data, and zero iterations = the start."""
+    from sklearn.cluster import KMeans
+
+    x = synth.gaussian_vectors(6000, seed=91).numpy().astype(np.float64)
+    cbt = oracle.upper_codebooks(bits)
+    _, psi, _ = oracle.encode_deep(x, S, oracle.default_codebooks(), bits, cbt, want_psi=True, want_y=True)
+    psi = psi.reshape(-1, 127)
+    start = cbt.copy()
+    rng = np.random.default_rng(92)
+    for l in range(3):
+        start[l, : 1 << bits[l]] += rng.uniform(-0.02, 0.02, 1 << bits[l])
+    assert np.array_equal(oracle.fit_upper_codebooks(x, S, bits, start, 0), start)
+    iters = 5
+    fit = oracle.fit_upper_codebooks(x, S, bits, start, iters)
+    for l, (a0, a1) in enumerate(((120, 124), (124, 126), (126, 127))):
+        K = 1 << bits[l]
+        samples = psi[:, a0:a1].reshape(-1, 1)
+        km = KMeans(n_clusters=K, init=start[l, :K].reshape(-1, 1), n_init=1, max_iter=iters, tol=0.0,
+                    algorithm="lloyd").fit(samples)
+        assert np.max(np.abs(np.sort(km.cluster_centers_.ravel()) - fit[l, :K])) <= 1e-9
+
+        def distortion(c):
+            return np.mean(np.min((samples - c[None, :]) ** 2, axis=1))
+        assert distortion(fit[l, :K]) <= distortion(start[l, :K])
+        assert np.all(fit[l, K:] == start[l, K:])        # unused entries pass through
+    far = oracle.fit_upper_codebooks(x, S, bits, start, 60)
+    for l in range(3):
+        K = 1 << bits[l]
+        assert np.max(np.abs(far[l, :K] - cbt[l, :K])) <= 0.01   # sampling noise of 24000 / 12000 / 6000 angles
+
+
 def test_exact_attention_helper_is_plain_softmax():
     rng = np.random.default_rng(2)
     K, V = rng.standard_normal((2, 50, 128))
