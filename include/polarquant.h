@@ -125,6 +125,16 @@ pq_status pq_fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_
                            double *cb_out, void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t pq_fit_workspace_bytes(void);
 
+/* The same for a depth-7 context (PQ_EINVAL otherwise): the angles of levels 5, 6, 7 -- 4 + 2 + 1
+ * per vector, formed from the 8 block radii -- are counted as well ((pi/2) / 2048 bins) and
+ * clustered from cbt_init (host, [3][8] as for pq_set_upper_codebooks; NULL: the context's
+ * current ones) with the bit widths of the context.  cbt_out (host): [3][8], ready for
+ * pq_set_upper_codebooks on a fresh context; cb_out as above.  Same workspace. */
+pq_status pq_fit_codebooks_deep(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
+                                int64_t ld_token, int64_t ld_head, const double *cb_init, const double *cbt_init,
+                                int iterations, double *cb_out, double *cbt_out, void *workspace,
+                                size_t workspace_bytes, void *hip_stream);
+
 /* Full-depth recursion (Definition 1 and procedure Polar of Algorithm 1 run to level
  * log2 d = 7; memory count of Section 4: one floating-point radius per vector plus the
  * angle codes; remark after Theorem 1: the codebook size of a level is free).

@@ -47,6 +47,8 @@ def library():
     L.pq_set_codebooks.argtypes = [vp, vp]
     L.pq_fit_codebooks.restype = i32
     L.pq_fit_codebooks.argtypes = [vp, vp, i32, i64, i32, i64, i64, vp, i32, vp, vp, ctypes.c_size_t, vp]
+    L.pq_fit_codebooks_deep.restype = i32
+    L.pq_fit_codebooks_deep.argtypes = [vp, vp, i32, i64, i32, i64, i64, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
     L.pq_fit_workspace_bytes.restype = ctypes.c_size_t
     L.pq_fit_workspace_bytes.argtypes = []
     L.pq_set_recursion_depth.restype = i32
@@ -252,6 +254,34 @@ class Context:
             out.ctypes.data_as(ctypes.c_void_p), workspace.data_ptr(),
             int(workspace.numel() * workspace.element_size()), _stream()))
         return out
+
+    def fit_codebooks_deep(self, x, iterations, cb_init=None, cbt_init=None, workspace=None):
+        """fit_codebooks for a depth-7 context: also the codebooks of levels 5-7 -> (28 centroids, [3, 8] centroids)."""
+        import torch
+
+        if x.stride(2) != 1:
+            raise PolarQuantError("innermost dimension must be contiguous")
+        nbytes = int(library().pq_fit_workspace_bytes())
+        if workspace is None:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=x.device)
+        init = init_t = None
+        if cb_init is not None:
+            init = np.ascontiguousarray(cb_init, dtype=np.float64).reshape(-1)
+            if init.size != 28:
+                raise PolarQuantError("cb_init must hold 28 centroids")
+        if cbt_init is not None:
+            init_t = np.ascontiguousarray(cbt_init, dtype=np.float64)
+            if init_t.shape != (3, 8):
+                raise PolarQuantError("cbt_init must have shape [3, 8]")
+        out = np.empty(28, dtype=np.float64)
+        out_t = np.empty((3, 8), dtype=np.float64)
+        _check(library().pq_fit_codebooks_deep(
+            self._h, x.data_ptr(), _dtype_code(x), int(x.shape[0]), int(x.shape[1]), int(x.stride(0)), int(x.stride(1)),
+            init.ctypes.data_as(ctypes.c_void_p) if init is not None else None,
+            init_t.ctypes.data_as(ctypes.c_void_p) if init_t is not None else None, int(iterations),
+            out.ctypes.data_as(ctypes.c_void_p), out_t.ctypes.data_as(ctypes.c_void_p), workspace.data_ptr(),
+            int(workspace.numel() * workspace.element_size()), _stream()))
+        return out, out_t
 
     # ---- host-side getters -------------------------------------------------
     def preconditioner(self):

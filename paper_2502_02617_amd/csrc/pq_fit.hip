@@ -6,7 +6,8 @@
  * The heavy part runs on the GPU: every input vector is rotated (y = x S, fp32),
  * its 120 angles are formed (procedure Polar) and counted into fine histograms,
  * one per level (8192 bins over [0, 2 pi) for level 1, 2048 over [0, pi/2] for
- * levels 2-4).  The k-means rounds then run on the 14336 bin counts on the host
+ * levels 2-4; for a full-depth context 2048 more for each of levels 5-7, see
+ * pq_fit_codebooks_deep).  The k-means rounds then run on the bin counts on the host
  * in fp64 -- each bin stands for its centre -- which costs microseconds and is
  * where the result is wanted (pq_set_codebooks takes host centroids).
  *
@@ -27,6 +28,7 @@ namespace {
 
 constexpr int kBins1 = 8192, kBinsU = 2048;
 constexpr int kHistSize = kBins1 + 3 * kBinsU; /* 14336 counters */
+constexpr int kHistUpper = 3 * kBinsU;         /* levels 5..7 (full-depth recursion): 6144 more, in global memory */
 constexpr int kFitThreads = 256;
 constexpr int kTileVecs = 32;
 constexpr float kTwoPi = 6.28318530717958647692f, kHalfPi = 1.57079632679489661923f;
@@ -38,6 +40,7 @@ struct FitArgs {
     int64_t tiles_per_head, n_items;
     const float *S;     /* S[i*128 + j] */
     uint32_t *hist;     /* [kHistSize], zeroed by the caller of the kernel */
+    uint32_t *hist_up;  /* [kHistUpper] or NULL: angles of levels 5..7 */
 };
 
 template <int XT>
@@ -102,6 +105,7 @@ __global__ __launch_bounds__(kFitThreads) void pq_angle_histogram_kernel(FitArgs
         /* procedure Polar on block (tid & 7) of vector (tid >> 3); every angle goes into its bin */
         {
             const int v = tid >> 3, b = tid & 7;
+            float rb = 0.f; /* radius of the block */
             if (v < n_valid) {
                 float r[16];
 #pragma unroll
@@ -130,6 +134,25 @@ __global__ __launch_bounds__(kFitThreads) void pq_angle_histogram_kernel(FitArgs
                     }
                     n >>= 1;
                     base += kBinsU;
+                }
+                rb = r[0];
+            }
+            if (a.hist_up) {
+                /* levels 5..7 join the eight block radii of a vector, which sit in eight neighbouring lanes:
+                   the node of a level lives in the lane of its first block and fetches its sibling's radius
+                   with a shuffle.  A vector gives 7 angles here: they are counted in global memory (the
+                   LDS is full). */
+                float r = rb;
+#pragma unroll
+                for (int l = 0; l < 3; ++l) {
+                    const float sib = __shfl_xor(r, 1 << l);
+                    if (v < n_valid && (b & ((2 << l) - 1)) == 0) {
+                        const float ang = atan2f(sib, r); /* both >= 0: in [0, pi/2] */
+                        int bin = (int)(ang * ((float)kBinsU / kHalfPi));
+                        bin = bin < 0 ? 0 : (bin > kBinsU - 1 ? kBinsU - 1 : bin);
+                        atomicAdd(&a.hist_up[l * kBinsU + bin], 1u);
+                    }
+                    r = sqrtf(r * r + sib * sib);
                 }
             }
         }
@@ -175,15 +198,19 @@ void lloyd_on_histogram(const uint32_t *hist, int bins, double width, int K, int
 
 } // namespace
 
-extern "C" size_t pq_fit_workspace_bytes(void) { return (size_t)kHistSize * sizeof(uint32_t); }
+extern "C" size_t pq_fit_workspace_bytes(void) { return (size_t)(kHistSize + kHistUpper) * sizeof(uint32_t); }
 
-extern "C" pq_status pq_fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
-                                      int64_t ld_token, int64_t ld_head, const double *cb_init, int iterations,
-                                      double *cb_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+namespace {
+
+pq_status fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
+                        int64_t ld_token, int64_t ld_head, const double *cb_init, const double *cbt_init, bool upper,
+                        int iterations, double *cb_out, double *cbt_out, void *workspace, size_t workspace_bytes,
+                        void *hip_stream)
 {
-    if (!ctx || !x || !cb_out || !workspace) return PQ_EINVAL;
+    if (!ctx || !x || !cb_out || !workspace || (upper && !cbt_out)) return PQ_EINVAL;
     if (xt != PQ_F32 && xt != PQ_BF16) return PQ_EINVAL;
     if (n_tokens <= 0 || n_heads <= 0 || ld_token < 0 || ld_head < 0 || iterations < 0) return PQ_EINVAL;
+    if (upper && ctx->depth != 7) return PQ_EINVAL;
     if (workspace_bytes < pq_fit_workspace_bytes()) return PQ_ENOMEM;
     if (!pq_aligned16(workspace)) return PQ_EALIGN;
     /* every bin counter must hold the angles of a level: 64 per vector at level 1 */
@@ -202,6 +229,17 @@ extern "C" pq_status pq_fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype
             if (!std::isfinite(c[off[l] + k])) return PQ_EINVAL;
             if (k > 0 && !(c[off[l] + k] > c[off[l] + k - 1])) return PQ_EINVAL;
         }
+    double ct[3][8] = {};
+    if (upper) {
+        for (int l = 0; l < 3; ++l) {
+            const int Kl = 1 << ctx->upper_bits[l];
+            for (int k = 0; k < 8; ++k) ct[l][k] = cbt_init ? cbt_init[8 * l + k] : (k < Kl ? ctx->upper_centroids[l][k] : 0.0);
+            for (int k = 0; k < Kl; ++k) {
+                if (!std::isfinite(ct[l][k])) return PQ_EINVAL;
+                if (k > 0 && !(ct[l][k] > ct[l][k - 1])) return PQ_EINVAL;
+            }
+        }
+    }
     const PqDeviceState *ds = nullptr;
     pq_status st = pq_device_state(ctx, &ds);
     if (st != PQ_OK) return st;
@@ -214,11 +252,12 @@ extern "C" pq_status pq_fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype
     a.n_items = a.tiles_per_head * n_heads;
     a.S = ds->S_f32;
     a.hist = hist;
+    a.hist_up = upper ? hist + kHistSize : nullptr;
     int64_t blocks = a.n_items < 256 ? a.n_items : 256;
     if (xt == PQ_BF16) hipLaunchKernelGGL(pq_angle_histogram_kernel<PQ_BF16>, dim3((unsigned)blocks), dim3(kFitThreads), 0, s, a);
     else hipLaunchKernelGGL(pq_angle_histogram_kernel<PQ_F32>, dim3((unsigned)blocks), dim3(kFitThreads), 0, s, a);
     PQ_HIP_TRY(hipGetLastError());
-    std::vector<uint32_t> h(kHistSize);
+    std::vector<uint32_t> h(kHistSize + kHistUpper);
     PQ_HIP_TRY(hipMemcpyAsync(h.data(), hist, pq_fit_workspace_bytes(), hipMemcpyDeviceToHost, s));
     PQ_HIP_TRY(hipStreamSynchronize(s));
     const double pi = 3.14159265358979323846264338327950288;
@@ -226,5 +265,30 @@ extern "C" pq_status pq_fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype
     for (int l = 1; l < 4; ++l)
         lloyd_on_histogram(h.data() + kBins1 + (l - 1) * kBinsU, kBinsU, 0.5 * pi / kBinsU, 4, iterations, c + off[l]);
     memcpy(cb_out, c, sizeof(c));
+    if (upper) {
+        for (int l = 0; l < 3; ++l)
+            lloyd_on_histogram(h.data() + kHistSize + l * kBinsU, kBinsU, 0.5 * pi / kBinsU, 1 << ctx->upper_bits[l],
+                               iterations, ct[l]);
+        memcpy(cbt_out, ct, sizeof(ct));
+    }
     return PQ_OK;
+}
+
+} // namespace
+
+extern "C" pq_status pq_fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
+                                      int64_t ld_token, int64_t ld_head, const double *cb_init, int iterations,
+                                      double *cb_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return fit_codebooks(ctx, x, xt, n_tokens, n_heads, ld_token, ld_head, cb_init, nullptr, false, iterations, cb_out,
+                         nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" pq_status pq_fit_codebooks_deep(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
+                                           int64_t ld_token, int64_t ld_head, const double *cb_init,
+                                           const double *cbt_init, int iterations, double *cb_out, double *cbt_out,
+                                           void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return fit_codebooks(ctx, x, xt, n_tokens, n_heads, ld_token, ld_head, cb_init, cbt_init, true, iterations, cb_out,
+                         cbt_out, workspace, workspace_bytes, hip_stream);
 }

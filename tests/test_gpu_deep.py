@@ -184,6 +184,57 @@ def test_deep_with_caller_set_codebooks(bits, upper):
     assert err <= 2e-3
 
 
+@pytest.mark.parametrize("bits", [(2, 2, 2), (3, 1, 2)])
+def test_deep_online_codebook_fit(bits):
+    """pq_fit_codebooks_deep against the oracle's k-means on the exact angles, all seven levels; the fitted
+    codebooks then drive a fresh context whose codes match the oracle's with the same codebooks."""
+    ctx = Context(seed=3)
+    ctx.set_recursion_depth(7, bits)
+    S = ctx.preconditioner()
+    x = synth.kv_stream(6000, 2, seed=70).permute(1, 0, 2).contiguous()          # bf16, outlier channels
+    x[5990:] *= 0.0                                                               # some all-zero vectors
+    iters = 6
+    say(f"deep online codebook fit bits={bits}: {x.shape[0]} tokens x {x.shape[1]} heads, {iters} rounds")
+    base, base_t = oracle.default_codebooks(), oracle.upper_codebooks(bits)
+    got, got_t = ctx.fit_codebooks_deep(x.to(DEV), iters)
+    xs = x.reshape(-1, 128).double().numpy()
+    ref = oracle.fit_codebooks(xs, S, base, iters)
+    ref_t = oracle.fit_upper_codebooks(xs, S, bits, base_t, iters)
+    d_low = np.max(np.abs(got - ref))
+    d_up = max(np.max(np.abs(got_t[l, :1 << bits[l]] - ref_t[l, :1 << bits[l]])) for l in range(3))
+    say(f"  max centroid difference: levels 1-4 {d_low:.2e} rad, levels 5-7 {d_up:.2e} rad (bin 7.7e-4)")
+    assert d_low <= 3e-4 and d_up <= 3e-4
+    # zero rounds give the start back; an explicit start is honoured
+    z, z_t = ctx.fit_codebooks_deep(x.to(DEV), 0)
+    assert np.max(np.abs(z - base)) <= 1e-12
+    assert all(np.max(np.abs(z_t[l, :1 << bits[l]] - base_t[l, :1 << bits[l]])) <= 1e-12 for l in range(3))
+    start_t = base_t.copy()
+    start_t[0, :1 << bits[0]] += 0.004
+    assert np.array_equal(ctx.fit_codebooks_deep(x.to(DEV), 0, cbt_init=start_t)[1], start_t)
+    with pytest.raises(PolarQuantError):
+        Context(seed=3).fit_codebooks_deep(x.to(DEV), 1)     # not a depth-7 context
+    # a fresh context with the fitted codebooks encodes like the oracle with them
+    ctx2 = Context(S=S)
+    ctx2.set_codebooks(got)
+    ctx2.set_recursion_depth(7, bits)
+    ctx2.set_upper_codebooks(got_t)
+    T, H = 700, 2
+    xe = x[:T].contiguous()
+    codes, top = ctx2.alloc_cache_for(H, 704, DEV)
+    codes.zero_()
+    top.zero_()
+    ctx2.encode_kv(xe.to(DEV), PQ_KEY, codes, top)
+    torch.cuda.synchronize()
+    rec_gpu = export_both_ways(ctx2, PQ_KEY, codes, top, 0, T)
+    rec_or, psi, y = oracle_records(xe, S, got, bits, got_t)
+    Jg, rg = oracle.unpack_deep(rec_gpu.reshape(-1, 50), bits)
+    Jo, ro = oracle.unpack_deep(rec_or.reshape(-1, 50), bits)
+    bad = Jg != Jo
+    say(f"  encode with the fitted codebooks: {int(bad.sum())} code mismatches of {Jo.size}")
+    assert bad.mean() <= helpers.CODE_MISMATCH_RATE
+    helpers.check_radii_deep(rg, ro, y.reshape(-1, 128))
+
+
 def test_deep_offsets_and_append():
     bits = (2, 2, 2)
     ctx, S, cb, cbt = make(bits)
