@@ -61,7 +61,7 @@ constexpr float kProbShift = 9.0f;
 constexpr float kRefSlack = 6.0f;
 
 /* LDS table block: layout in pq_common.h (PQ_TAB_*), image built on the host */
-constexpr int kT1 = PQ_TAB_T1, kT4 = PQ_TAB_T4, kTA = PQ_TAB_TA, kTB = PQ_TAB_TB, kT4B = PQ_TAB_T4B, kT1F = PQ_TAB_T1F;
+constexpr int kT1 = PQ_TAB_T1, kTA = PQ_TAB_TA, kTB = PQ_TAB_TB, kT4B = PQ_TAB_T4B, kT1F = PQ_TAB_T1F;
 constexpr int kTAF = PQ_TAB_TAF, kTBF = PQ_TAB_TBF, kT4F = PQ_TAB_T4F;
 constexpr int kTUp = PQ_TAB_UP, kTabDwords = PQ_TAB_DWORDS;
 static_assert(kTabDwords == kWavesPerBlock * 64, "one table dword per thread of a workgroup");
@@ -415,6 +415,15 @@ __device__ __forceinline__ int effective_ctx(const int64_t *seq_start, const int
     return effective_ctx_of(ctx_len[b], seq_start[b], max_ctx, pool_tiles); /* two independent loads */
 }
 
+/* Issue priority of the wavefront among those of its SIMD (0..3, scalar argument). */
+__device__ __forceinline__ void set_wave_priority(int prio)
+{
+    if (prio <= 0) __builtin_amdgcn_s_setprio(0);
+    else if (prio == 1) __builtin_amdgcn_s_setprio(1);
+    else if (prio == 2) __builtin_amdgcn_s_setprio(2);
+    else __builtin_amdgcn_s_setprio(3);
+}
+
 __device__ __forceinline__ uint32_t sel4(uint4 v, int c)
 {
     return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w));
@@ -677,6 +686,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
     const __amdgpu_buffer_rsrc_t o_rsrc = stream_descriptor(a.ws_o, (uint32_t)a.n_pieces * (a.M * G) * (PQ_D * 4u));
     const __amdgpu_buffer_rsrc_t ml_rsrc = stream_descriptor(a.ws_ml, (uint32_t)a.n_pieces * (a.M * G) * 8u);
 
+    const int quarter_tiles = max((gend - gpos + 3) >> 2, 1);
+    int prio = 4, next_drop = gpos; /* drops to 3 at the first tile */
     for (;;) { /* one piece per round: tiles [tile_lo, tile_hi) of stream (b, hk) */
         const int ctx = ctx_of(b);
         const int n_tiles = (ctx + 63) >> 6; /* == seq_tiles */
@@ -743,6 +754,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
 #pragma unroll
             for (int k = 0; k < NG; ++k) lim[k] = 64;
             for (; tile < n_full; ++tile) {
+                /* progress through the share, in quarters: the further along, the lower the priority */
+                if (gpos + (tile - tile_lo) >= next_drop) {
+                    next_drop += quarter_tiles;
+                    set_wave_priority(--prio);
+                }
                 if (DEEP) { /* the reads of the previous tile's radii precede these writes in program order */
                     wave_lds_fence();
                     expand_deep_radii(tab, dr, kraw.top, vraw.top, lane);
