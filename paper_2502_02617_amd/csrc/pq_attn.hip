@@ -63,8 +63,7 @@ constexpr float kRefSlack = 6.0f;
 /* LDS table block: layout in pq_common.h (PQ_TAB_*), image built on the host */
 constexpr int kT1 = PQ_TAB_T1, kTA = PQ_TAB_TA, kTB = PQ_TAB_TB, kT4B = PQ_TAB_T4B, kT1F = PQ_TAB_T1F;
 constexpr int kTAF = PQ_TAB_TAF, kTBF = PQ_TAB_TBF, kT4F = PQ_TAB_T4F;
-constexpr int kTUp = PQ_TAB_UP, kTabDwords = PQ_TAB_DWORDS;
-static_assert(kTabDwords == kWavesPerBlock * 64, "one table dword per thread of a workgroup");
+constexpr int kTUp = PQ_TAB_UP, kTG = PQ_TAB_TG, kTGF = PQ_TAB_TGF, kTabDwords = PQ_TAB_DWORDS;
 
 struct AttnArgs {
     const uint16_t *qrot; /* [B][M][Hq][2][128] binary16: rotated, pre-scaled q' as a leading part and its remainder */
@@ -171,29 +170,32 @@ __device__ __forceinline__ uint32_t nibble_offset(const NibbleOffsets &n)
     return __builtin_amdgcn_ubfe(src, 8 * k, 8);
 }
 
-/* The same idea for the four 6-bit groups [c2a | c3 | c2b] of a 24-bit string:
- * offA holds 4*(c2a<<2|c3) and offB holds 4*(c3<<2|c2b) of group k at bits [6k, 6k+6). */
+/* The same idea for the four 6-bit groups g = [c2a | c3 | c2b] of a 24-bit string: two masked copies of
+ * the string shifted left by SHIFT hold the even and the odd groups, so that (g << SHIFT) -- the byte
+ * offset of entry g of a table with 2^SHIFT-byte entries -- is one extraction per group. */
 struct GroupOffsets {
-    uint32_t offA, offB;
+    uint32_t even, odd; /* even: groups 0, 2 at bits [SHIFT, SHIFT+6), [SHIFT+12, SHIFT+18); odd: 1, 3 six bits higher */
 };
 
+template <int SHIFT>
 __device__ __forceinline__ GroupOffsets group_offsets(uint32_t g24)
 {
     GroupOffsets r;
-    const uint32_t m = scalar_const(0xF3CF3Cu);
-    r.offA = g24 & m;
-    r.offB = (g24 << 2) & m;
-    asm("" : "+v"(r.offA));
-    asm("" : "+v"(r.offB));
+    const uint32_t p = g24 << SHIFT;
+    r.even = p & scalar_const((0x3Fu << SHIFT) | (0x3Fu << (SHIFT + 12)));
+    r.odd = p & scalar_const((0x3Fu << (SHIFT + 6)) | (0x3Fu << (SHIFT + 18)));
+    asm("" : "+v"(r.even));
+    asm("" : "+v"(r.odd));
     return r;
 }
 
-template <int K>
-__device__ __forceinline__ uint32_t group_offset(uint32_t packed)
+template <int K, int SHIFT>
+__device__ __forceinline__ uint32_t group_offset(const GroupOffsets &g)
 {
-    if (K == 0) return packed & 0x3Fu;
-    if (K == 3) return packed >> 18;
-    return __builtin_amdgcn_ubfe(packed, 6 * K, 6);
+    if (K == 0) return g.even & ((1u << (SHIFT + 6)) - 1u);
+    if (K == 2) return g.even >> 12;
+    if (K == 1) return __builtin_amdgcn_ubfe(g.odd, 6, SHIFT + 6);
+    return g.odd >> 18;
 }
 
 /* Table entries of one half-block, fetched before any arithmetic so that the LDS
@@ -202,11 +204,12 @@ struct HalfBlockLut {
     h2 ta, tb, t1[4];
 };
 
-__device__ __forceinline__ void gather_half_block(const uint32_t *tab, uint32_t offA, uint32_t offB,
+__device__ __forceinline__ void gather_half_block(const uint32_t *tab, uint32_t offG,
                                                   uint32_t o0, uint32_t o1, uint32_t o2, uint32_t o3, HalfBlockLut &l)
 {
-    l.ta = lut(tab, kTA, offA);
-    l.tb = lut(tab, kTB, offB);
+    const uint2 g = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(tab + kTG) + offG); /* offG = 8 * group */
+    l.ta = as_h2(g.x);
+    l.tb = as_h2(g.y);
     l.t1[0] = lut(tab, kT1, o0);
     l.t1[1] = lut(tab, kT1, o1);
     l.t1[2] = lut(tab, kT1, o2);
@@ -243,14 +246,15 @@ __device__ __forceinline__ float lut_f(const uint32_t *tab, int table, uint32_t 
     return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(tab + table) + byte_off);
 }
 
-__device__ __forceinline__ void gather_key_half_block(const uint32_t *tab, uint32_t offA, uint32_t offB,
+__device__ __forceinline__ void gather_key_half_block(const uint32_t *tab, uint32_t offG,
                                                       uint32_t o0, uint32_t o1, uint32_t o2, uint32_t o3,
                                                       KeyHalfBlockLut &l)
 {
-    l.ta0 = lut_f(tab, kTAF, offA);
-    l.ta1 = lut_f(tab, kTAF + 16, offA);
-    l.tb0 = lut_f(tab, kTBF, offB);
-    l.tb1 = lut_f(tab, kTBF + 16, offB);
+    const float4 g = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(tab + kTGF) + offG); /* offG = 16 * group */
+    l.ta0 = g.x;
+    l.ta1 = g.y;
+    l.tb0 = g.z;
+    l.tb1 = g.w;
     l.t1[0] = lut_f2(tab, o0);
     l.t1[1] = lut_f2(tab, o1);
     l.t1[2] = lut_f2(tab, o2);
@@ -275,13 +279,14 @@ __device__ __forceinline__ void expand_key_half_block(float r3, const KeyHalfBlo
     out[3] = round_pair(r13 * l.t1[3].x, r13 * l.t1[3].y);
 }
 
-/* 24 bits starting at bit 24*i of the 96-bit little-endian string (d0, d1, d2) */
+/* 24 bits starting at bit 24*i of the 96-bit little-endian string (d0, d1, d2), in the low 24 bits of
+ * the result; the bits above them are not cleared (group_offsets masks what it uses) */
 __device__ __forceinline__ uint32_t take24(uint32_t d0, uint32_t d1, uint32_t d2, int i)
 {
     switch (i) {
-    case 0: return d0 & 0xFFFFFFu;
-    case 1: return ((d0 >> 24) | (d1 << 8)) & 0xFFFFFFu;
-    case 2: return ((d1 >> 16) | (d2 << 16)) & 0xFFFFFFu;
+    case 0: return d0;
+    case 1: return __builtin_amdgcn_alignbit(d1, d0, 24);
+    case 2: return __builtin_amdgcn_alignbit(d2, d1, 16);
     default: return d2 >> 8;
     }
 }
@@ -436,7 +441,7 @@ __device__ __forceinline__ void key_operand(const uint32_t *tab, const KTileRaw 
 {
     const uint4 l1q = (i < 2) ? kcur.l1a : kcur.l1b;
     const uint32_t l1A = (i & 1) ? l1q.z : l1q.x, l1B = (i & 1) ? l1q.w : l1q.y;
-    const GroupOffsets go = group_offsets(take24(kcur.g0, kcur.g1, kcur.g2, i));
+    const GroupOffsets go = group_offsets<4>(take24(kcur.g0, kcur.g1, kcur.g2, i));
     const uint32_t c4n = kcur.c4 >> (4 * i);
     float radA, radB; /* radii of blocks 2gk, 2gk+1 */
     if (DEEP) {
@@ -452,18 +457,18 @@ __device__ __forceinline__ void key_operand(const uint32_t *tab, const KTileRaw 
     const float t4Bc = lut_f(tab, kT4F, o4B), t4Bs = lut_f(tab, kT4F + 4, o4B);
     {   /* block A = 2*gk: slices 0, 1 */
         KeyHalfBlockLut l0, l1;
-        gather_key_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(noA),
+        gather_key_half_block(tab, group_offset<0, 4>(go), nibble_offset<0>(noA),
                               nibble_offset<1>(noA), nibble_offset<2>(noA), nibble_offset<3>(noA), l0);
-        gather_key_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(noA),
+        gather_key_half_block(tab, group_offset<1, 4>(go), nibble_offset<4>(noA),
                               nibble_offset<5>(noA), nibble_offset<6>(noA), nibble_offset<7>(noA), l1);
         expand_key_half_block(radA * t4Ac, l0, ka[0].p);
         expand_key_half_block(radA * t4As, l1, ka[1].p);
     }
     {   /* block B = 2*gk + 1: slices 2, 3 */
         KeyHalfBlockLut l0, l1;
-        gather_key_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(noB),
+        gather_key_half_block(tab, group_offset<2, 4>(go), nibble_offset<0>(noB),
                               nibble_offset<1>(noB), nibble_offset<2>(noB), nibble_offset<3>(noB), l0);
-        gather_key_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(noB),
+        gather_key_half_block(tab, group_offset<3, 4>(go), nibble_offset<4>(noB),
                               nibble_offset<5>(noB), nibble_offset<6>(noB), nibble_offset<7>(noB), l1);
         expand_key_half_block(radB * t4Bc, l0, ka[2].p);
         expand_key_half_block(radB * t4Bs, l1, ka[3].p);
@@ -478,7 +483,7 @@ __device__ __forceinline__ void value_operand(const uint32_t *tab, const VTileRa
                                               int n_valid, int g, int t4b, const DeepRadii &dr, int lane)
 {
     const uint4 l1q = (i < 2) ? vcur.l1a : vcur.l1b;
-    const GroupOffsets go = group_offsets(take24(vcur.g0, vcur.g1, vcur.g2, i));
+    const GroupOffsets go = group_offsets<3>(take24(vcur.g0, vcur.g1, vcur.g2, i));
     uint32_t rpair[2]; /* radii of tokens (0, 1) and (2, 3) of the pass */
     if (DEEP) {
         const uint2 rr = *reinterpret_cast<const uint2 *>(dr.vrad + (lane >> 1) * 16 + 4 * i);
@@ -505,14 +510,14 @@ __device__ __forceinline__ void value_operand(const uint32_t *tab, const VTileRa
         const h2 t4a = lut(tab, t4b, c4a), t4bb = lut(tab, t4b, c4b);
         HalfBlockLut l0, l1;
         if (ep == 0) {
-            gather_half_block(tab, group_offset<0>(go.offA), group_offset<0>(go.offB), nibble_offset<0>(no),
+            gather_half_block(tab, group_offset<0, 3>(go), nibble_offset<0>(no),
                               nibble_offset<1>(no), nibble_offset<2>(no), nibble_offset<3>(no), l0);
-            gather_half_block(tab, group_offset<1>(go.offA), group_offset<1>(go.offB), nibble_offset<4>(no),
+            gather_half_block(tab, group_offset<1, 3>(go), nibble_offset<4>(no),
                               nibble_offset<5>(no), nibble_offset<6>(no), nibble_offset<7>(no), l1);
         } else {
-            gather_half_block(tab, group_offset<2>(go.offA), group_offset<2>(go.offB), nibble_offset<0>(no),
+            gather_half_block(tab, group_offset<2, 3>(go), nibble_offset<0>(no),
                               nibble_offset<1>(no), nibble_offset<2>(no), nibble_offset<3>(no), l0);
-            gather_half_block(tab, group_offset<3>(go.offA), group_offset<3>(go.offB), nibble_offset<4>(no),
+            gather_half_block(tab, group_offset<3, 3>(go), nibble_offset<4>(no),
                               nibble_offset<5>(no), nibble_offset<6>(no), nibble_offset<7>(no), l1);
         }
         expand_half_block(r0 * t4a, l0, ve[2 * ep]);
@@ -618,7 +623,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
         st_len = a.ctx_len[min(bb, a.B - 1)];
         st_start = a.seq_start[min(bb, a.B - 1)];
     }
-    tab[threadIdx.x] = a.consts->attn_tab[threadIdx.x];
+#pragma unroll
+    for (int t = threadIdx.x; t < kTabDwords; t += kWavesPerBlock * 64) tab[t] = a.consts->attn_tab[t];
     if (staged && threadIdx.x >= 192) {
         const int bb = (int)threadIdx.x - 192;
         sPre[bb] = st_pre;

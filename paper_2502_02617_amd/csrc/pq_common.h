@@ -57,7 +57,7 @@ struct PqDeviceConsts {
     float up_cs[3][8][2];
     /* The attention kernels' LDS table block, entry for entry (layout: PQ_TAB_* below), so that a
        workgroup fills its LDS with one coalesced load per thread. */
-    uint32_t attn_tab[256];
+    uint32_t attn_tab[640];
 };
 
 /* LDS table block of the attention kernels (dwords).  Binary16 pairs for the value path: T1 [0,16)
@@ -68,7 +68,11 @@ struct PqDeviceConsts {
  * Full-depth recursion: (cos, sin) pairs of the centroids of levels 5, 6, 7, eight per level, from 208. */
 enum {
     PQ_TAB_T1 = 0, PQ_TAB_T4 = 16, PQ_TAB_TA = 32, PQ_TAB_TB = 48, PQ_TAB_T4B = 64, PQ_TAB_T1F = 96,
-    PQ_TAB_TAF = 128, PQ_TAB_TBF = 160, PQ_TAB_T4F = 192, PQ_TAB_UP = 208, PQ_TAB_DWORDS = 256
+    PQ_TAB_TAF = 128, PQ_TAB_TBF = 160, PQ_TAB_T4F = 192, PQ_TAB_UP = 208,
+    /* level-3 x level-2 products by the 6-bit group g = [c2a | c3 | c2b] of a half-block: for the values 64 entries
+       (TA[g >> 2], TB[g & 15]) as two binary16 pairs, for the keys 64 entries of four fp32 (TA low, TA high, TB low,
+       TB high): one gather per half-block instead of two */
+    PQ_TAB_TG = 256, PQ_TAB_TGF = 384, PQ_TAB_DWORDS = 640
 };
 
 /* Radius plane of a tile.  Depth 4: 512 binary16 block radii (pq_layout.h).  Depth 7: 64 words,

@@ -340,6 +340,15 @@ void build_tables(pq_ctx *ctx)
         for (int l = 0; l < 3; ++l)
             for (int k = 0; k < 8; ++k)
                 for (int h = 0; h < 2; ++h) c.attn_tab[PQ_TAB_UP + 16 * l + 2 * k + h] = f2u(c.up_cs[l][k][h]);
+    for (int g = 0; g < 64; ++g) {
+        const int ia = g >> 2, ib = g & 15;
+        c.attn_tab[PQ_TAB_TG + 2 * g] = c.ta_h2[ia];
+        c.attn_tab[PQ_TAB_TG + 2 * g + 1] = c.tb_h2[ib];
+        c.attn_tab[PQ_TAB_TGF + 4 * g] = f2u(c.ta_f32[0][ia]);
+        c.attn_tab[PQ_TAB_TGF + 4 * g + 1] = f2u(c.ta_f32[1][ia]);
+        c.attn_tab[PQ_TAB_TGF + 4 * g + 2] = f2u(c.tb_f32[0][ib]);
+        c.attn_tab[PQ_TAB_TGF + 4 * g + 3] = f2u(c.tb_f32[1][ib]);
+    }
 }
 
 } // namespace
