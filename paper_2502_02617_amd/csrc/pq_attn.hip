@@ -63,7 +63,7 @@ constexpr float kRefSlack = 6.0f;
 /* LDS table block: layout in pq_common.h (PQ_TAB_*), image built on the host */
 constexpr int kT1 = PQ_TAB_T1, kTA = PQ_TAB_TA, kTB = PQ_TAB_TB, kT4B = PQ_TAB_T4B, kT1F = PQ_TAB_T1F;
 constexpr int kTAF = PQ_TAB_TAF, kTBF = PQ_TAB_TBF, kT4F = PQ_TAB_T4F;
-constexpr int kTUp = PQ_TAB_UP, kTG = PQ_TAB_TG, kTGF = PQ_TAB_TGF, kTabDwords = PQ_TAB_DWORDS;
+constexpr int kTUp = PQ_TAB_UP, kTG = PQ_TAB_TG, kTGF = PQ_TAB_TGF, kT1B = PQ_TAB_T1B, kTabDwords = PQ_TAB_DWORDS;
 
 struct AttnArgs {
     const uint16_t *qrot; /* [B][M][Hq][2][128] binary16: rotated, pre-scaled q' as a leading part and its remainder */
@@ -170,6 +170,29 @@ __device__ __forceinline__ uint32_t nibble_offset(const NibbleOffsets &n)
     return __builtin_amdgcn_ubfe(src, 8 * k, 8);
 }
 
+/* Byte offsets (8 * byte) of the four bytes of a dword, each byte a pair of 4-bit codes: table entries of 8 bytes */
+struct ByteOffsets {
+    uint32_t even, odd; /* even: bytes 0, 2 at bits [3, 11), [19, 27); odd: bytes 1, 3 likewise */
+};
+
+__device__ __forceinline__ ByteOffsets byte_offsets8(uint32_t w)
+{
+    ByteOffsets r;
+    const uint32_t m = scalar_const(0x07F807F8u);
+    r.even = (w << 3) & m;
+    r.odd = (w >> 5) & m;
+    asm("" : "+v"(r.even));
+    asm("" : "+v"(r.odd));
+    return r;
+}
+
+template <int BYTE>
+__device__ __forceinline__ uint32_t byte_offset(const ByteOffsets &b)
+{
+    const uint32_t src = (BYTE & 1) ? b.odd : b.even;
+    return (BYTE & 2) ? src >> 16 : src & 0xFFFFu;
+}
+
 /* The same idea for the four 6-bit groups g = [c2a | c3 | c2b] of a 24-bit string: two masked copies of
  * the string shifted left by SHIFT hold the even and the odd groups, so that (g << SHIFT) -- the byte
  * offset of entry g of a table with 2^SHIFT-byte entries -- is one extraction per group. */
@@ -204,16 +227,17 @@ struct HalfBlockLut {
     h2 ta, tb, t1[4];
 };
 
-__device__ __forceinline__ void gather_half_block(const uint32_t *tab, uint32_t offG,
-                                                  uint32_t o0, uint32_t o1, uint32_t o2, uint32_t o3, HalfBlockLut &l)
+__device__ __forceinline__ void gather_half_block(const uint32_t *tab, uint32_t offG, uint32_t b0, uint32_t b1, HalfBlockLut &l)
 {
     const uint2 g = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(tab + kTG) + offG); /* offG = 8 * group */
     l.ta = as_h2(g.x);
     l.tb = as_h2(g.y);
-    l.t1[0] = lut(tab, kT1, o0);
-    l.t1[1] = lut(tab, kT1, o1);
-    l.t1[2] = lut(tab, kT1, o2);
-    l.t1[3] = lut(tab, kT1, o3);
+    const uint2 p0 = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(tab + kT1B) + b0); /* 8 * code pair */
+    const uint2 p1 = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(tab + kT1B) + b1);
+    l.t1[0] = as_h2(p0.x);
+    l.t1[1] = as_h2(p0.y);
+    l.t1[2] = as_h2(p1.x);
+    l.t1[3] = as_h2(p1.y);
 }
 
 /* The four level-1 radii of a half-block times their (cos, sin) pairs:
@@ -497,7 +521,7 @@ __device__ __forceinline__ void value_operand(const uint32_t *tab, const VTileRa
     h2 ve[4][4]; /* [token e][pair q] */
 #pragma unroll
     for (int ep = 0; ep < 2; ++ep) { /* tokens 2ep, 2ep+1 share one L1 dword and one radius dword */
-        const NibbleOffsets no = nibble_offsets(sel4(l1q, 2 * (i & 1) + ep));
+        const ByteOffsets no = byte_offsets8(sel4(l1q, 2 * (i & 1) + ep));
         h2 rad = as_h2(rpair[ep]);
         h2 r0 = bcast_lo(rad), r1 = bcast_hi(rad);
         if (MASKED) {
@@ -510,15 +534,11 @@ __device__ __forceinline__ void value_operand(const uint32_t *tab, const VTileRa
         const h2 t4a = lut(tab, t4b, c4a), t4bb = lut(tab, t4b, c4b);
         HalfBlockLut l0, l1;
         if (ep == 0) {
-            gather_half_block(tab, group_offset<0, 3>(go), nibble_offset<0>(no),
-                              nibble_offset<1>(no), nibble_offset<2>(no), nibble_offset<3>(no), l0);
-            gather_half_block(tab, group_offset<1, 3>(go), nibble_offset<4>(no),
-                              nibble_offset<5>(no), nibble_offset<6>(no), nibble_offset<7>(no), l1);
+            gather_half_block(tab, group_offset<0, 3>(go), byte_offset<0>(no), byte_offset<1>(no), l0);
+            gather_half_block(tab, group_offset<1, 3>(go), byte_offset<2>(no), byte_offset<3>(no), l1);
         } else {
-            gather_half_block(tab, group_offset<2, 3>(go), nibble_offset<0>(no),
-                              nibble_offset<1>(no), nibble_offset<2>(no), nibble_offset<3>(no), l0);
-            gather_half_block(tab, group_offset<3, 3>(go), nibble_offset<4>(no),
-                              nibble_offset<5>(no), nibble_offset<6>(no), nibble_offset<7>(no), l1);
+            gather_half_block(tab, group_offset<2, 3>(go), byte_offset<0>(no), byte_offset<1>(no), l0);
+            gather_half_block(tab, group_offset<3, 3>(go), byte_offset<2>(no), byte_offset<3>(no), l1);
         }
         expand_half_block(r0 * t4a, l0, ve[2 * ep]);
         expand_half_block(r1 * t4bb, l1, ve[2 * ep + 1]);

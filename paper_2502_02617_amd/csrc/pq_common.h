@@ -57,7 +57,7 @@ struct PqDeviceConsts {
     float up_cs[3][8][2];
     /* The attention kernels' LDS table block, entry for entry (layout: PQ_TAB_* below), so that a
        workgroup fills its LDS with one coalesced load per thread. */
-    uint32_t attn_tab[640];
+    uint32_t attn_tab[1152];
 };
 
 /* LDS table block of the attention kernels (dwords).  Binary16 pairs for the value path: T1 [0,16)
@@ -72,7 +72,10 @@ enum {
     /* level-3 x level-2 products by the 6-bit group g = [c2a | c3 | c2b] of a half-block: for the values 64 entries
        (TA[g >> 2], TB[g & 15]) as two binary16 pairs, for the keys 64 entries of four fp32 (TA low, TA high, TB low,
        TB high): one gather per half-block instead of two */
-    PQ_TAB_TG = 256, PQ_TAB_TGF = 384, PQ_TAB_DWORDS = 640
+    PQ_TAB_TG = 256, PQ_TAB_TGF = 384,
+    /* level 1 of the values by code pair: entry (code 2j+1 << 4 | code 2j), the byte as stored, holds the binary16
+       (cos, sin) pairs of both codes: one gather and one index extraction per two pairs */
+    PQ_TAB_T1B = 640, PQ_TAB_DWORDS = 1152
 };
 
 /* Radius plane of a tile.  Depth 4: 512 binary16 block radii (pq_layout.h).  Depth 7: 64 words,

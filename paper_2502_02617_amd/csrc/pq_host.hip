@@ -340,6 +340,10 @@ void build_tables(pq_ctx *ctx)
         for (int l = 0; l < 3; ++l)
             for (int k = 0; k < 8; ++k)
                 for (int h = 0; h < 2; ++h) c.attn_tab[PQ_TAB_UP + 16 * l + 2 * k + h] = f2u(c.up_cs[l][k][h]);
+    for (int b = 0; b < 256; ++b) {
+        c.attn_tab[PQ_TAB_T1B + 2 * b] = c.t1_h2[b & 15];
+        c.attn_tab[PQ_TAB_T1B + 2 * b + 1] = c.t1_h2[b >> 4];
+    }
     for (int g = 0; g < 64; ++g) {
         const int ia = g >> 2, ib = g & 15;
         c.attn_tab[PQ_TAB_TG + 2 * g] = c.ta_h2[ia];
