@@ -45,10 +45,10 @@ BYTES_PER_TOKEN_HEAD = 124  # 62-byte key record + 62-byte value record
 # HBM bytes per launch of pq_attn_partial_kernel on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled
 # by a plain copy of known size (profiles/attn_partial_cfg2_counters.txt): 522.5 MB read + 8.5 MB written.
 MEASURED_TRAFFIC_BYTES = 522.5e6 + 8.5e6
-# Secondary bound of the same kernel: vector-ALU issue.  Its tile loop holds 1012 vector instructions per 64-token
+# Secondary bound of the same kernel: vector-ALU issue.  Its tile loop holds 947 vector instructions per 64-token
 # tile of one kv head (compiled code, counted in the assembly listing); one SIMD issues one 64-lane vector
 # instruction per 4 cycles: 256 CUs x 4 SIMDs x 2.4 GHz / 4 = 614.4 G wavefront instructions/s at most.
-VALU_INSTR_PER_TILE = 1015
+VALU_INSTR_PER_TILE = 947
 VALU_PEAK_GINSTR = 256 * 4 * 2.4 / 4.0
 
 
