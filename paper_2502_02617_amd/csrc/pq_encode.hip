@@ -334,7 +334,20 @@ __device__ __forceinline__ void encode_tiles(const EncodeArgs &a, int block, int
 
     uint32_t *img = sImg[wave];
 
+    /* The hardware prefers the older of the two wavefronts of a SIMD, which then finishes well before the other
+       and leaves it to run alone; each wavefront lowers its issue priority as it works through its items, so
+       that the one behind catches up. */
+    const int my_items = item0 < a.n_items ? (int)((a.n_items - item0 + item_stride - 1) / item_stride) : 0;
+    int items_done = 0;
     for (int64_t item = item0; item < a.n_items; item += item_stride) {
+        {
+            const int prio = 3 - (4 * items_done) / my_items;
+            if (prio >= 3) __builtin_amdgcn_s_setprio(3);
+            else if (prio == 2) __builtin_amdgcn_s_setprio(2);
+            else if (prio == 1) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+            ++items_done;
+        }
         const Geometry geo = geometry(item);
         const int head = geo.head, tau_lo = geo.tau_lo, tau_hi = geo.tau_hi;
         const int64_t tile = geo.tile;
