@@ -889,6 +889,7 @@ __device__ __forceinline__ void rotate_query_rows(const RotateArgs &a, int row0,
     const int tid = threadIdx.x, r = tid >> 7, j = tid & 127;
     MatrixSlice ms;
     matrix_slice_load(ms, a.S, tid);
+    const float sigma = a.consts->sigma[j & 15]; /* requested with the slice, used after the last barrier */
     const int row = row0 + r;
     sq[r][j] = row < n_rows ? __uint_as_float((uint32_t)a.q[(int64_t)row * PQ_D + j] << 16) : 0.f;
     __syncthreads();
@@ -908,7 +909,7 @@ __device__ __forceinline__ void rotate_query_rows(const RotateArgs &a, int row0,
     if (row < n_rows) {
         const float acc = ((spart[r][0][j] + spart[r][1][j]) + spart[r][2][j]) + spart[r][3][j];
         /* rebuilt keys carry the table scale sigma of their coordinate: take it out here */
-        const float v = acc * a.scale / a.consts->sigma[j & 15];
+        const float v = acc * a.scale / sigma;
         const _Float16 h = (_Float16)v;
         const _Float16 rem = (_Float16)(v - (float)h);
         a.qrot[(int64_t)row * 2 * PQ_D + j] = __builtin_bit_cast(uint16_t, h);
@@ -1036,6 +1037,7 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
     const int row = blockIdx.x;
     MatrixSlice ms; /* requested first: its latency overlaps the reads of the partial results */
     matrix_slice_load(ms, a.St, tid);
+    const float sigma = a.consts->sigma[j & 15];
     const int b = row / (a.M * a.Hq), mq = (row / a.Hq) % a.M, head = row % a.Hq;
     /* the pieces of this row's stream (sequence b, kv head hk): the wavefronts whose tile ranges
        meet the stream's, in order; their ids are consecutive.  A piece beyond what query token
@@ -1095,9 +1097,9 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
         /* rebuilt values carry the table scale sigma of their coordinate */
         if (HYBRID) {
             owt = ((sw[0][j] + sw[1][j]) + sw[2][j]) + sw[3][j];
-            so[j] = ot / a.consts->sigma[j & 15];
+            so[j] = ot / sigma;
         } else {
-            so[j] = lt > 0.f ? ot / (lt * a.consts->sigma[j & 15]) : 0.f; /* lt == 0: no visible token */
+            so[j] = lt > 0.f ? ot / (lt * sigma) : 0.f; /* lt == 0: no visible token */
         }
     }
     __syncthreads();
