@@ -551,7 +551,7 @@ __device__ __forceinline__ void value_operand(const uint32_t *tab, const VTileRa
 
 /* Softmax state of a column: the exponent reference m_ref is shared by the four
  * token groups of the column and only moves when a score exceeds it by more than
- * kRefSlack, which after the first pass of a chunk is rare.  Probabilities are
+ * kRefSlack, which after the first pass of a piece is rare.  Probabilities are
  * exp2(s - m_ref + kProbShift): below 2^(kRefSlack + kProbShift), inside binary16,
  * and the partial result (m_ref, l, o) is consistent for any reference. */
 /* One pass: scores, reference check, probabilities, weighted values.  The operand
