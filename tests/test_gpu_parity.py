@@ -527,12 +527,14 @@ def test_decode_step_equals_append_then_attention(env, Hq, Hkv):
 def test_decode_step_under_graph_replay(env):
     """The decode step (three launches, no memset nodes, no allocation once the context's tables are on the
     device) captured into a HIP graph: every replay, with eager work and synchronisations in between, gives
-    the eager result bit for bit, including after the inputs have changed in place."""
+    the eager result bit for bit, including after the inputs have changed in place and after the contexts have
+    grown (the launch shapes depend on max_ctx only; the work is split on the device from ctx_len)."""
     ctx, S, cb = env
     lens = [70, 300, 1000]
     say(f"decode step under graph replay, lens={lens}")
     B, Hq, Hkv = len(lens), 8, 2
-    caches, starts, pool, _, _ = build_cache(ctx, S, cb, [n - 1 for n in lens], Hkv, seed=1700, want_oracle=False)
+    grow = 70                            # tokens the contexts grow by during the test (crosses a tile boundary)
+    caches, starts, pool, _, _ = build_cache(ctx, S, cb, [n + grow for n in lens], Hkv, seed=1700, want_oracle=False)
     kc, kr, vc, vr = caches
     seq_start = torch.from_numpy(starts).to(DEV)
     ctx_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
@@ -541,10 +543,11 @@ def test_decode_step_under_graph_replay(env):
     nv = synth.kv_stream(B, Hkv, 1711).permute(1, 0, 2).contiguous().to(DEV)
     q = synth.queries(B, Hq, seed=1712).to(DEV)
     out = torch.empty((B, Hq, 128), dtype=torch.float32, device=DEV)
-    ws = torch.empty(Context.attn_workspace_bytes(B, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
+    max_ctx = max(lens) + grow
+    ws = torch.empty(Context.attn_workspace_bytes(B, Hq, Hkv, max_ctx), dtype=torch.uint8, device=DEV)
 
     def step():
-        ctx.decode_step_polar(nk, nv, dst, q, out, kc, kr, vc, vr, seq_start, ctx_len, max(lens), helpers.softmax_scale(), ws)
+        ctx.decode_step_polar(nk, nv, dst, q, out, kc, kr, vc, vr, seq_start, ctx_len, max_ctx, helpers.softmax_scale(), ws)
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -556,10 +559,14 @@ def test_decode_step_under_graph_replay(env):
     with torch.cuda.graph(graph):
         step()
     torch.cuda.synchronize()
-    for rep in range(4):
+    for rep in range(6):
         if rep == 2:                    # new query and new token vectors, written in place
             q.copy_(synth.queries(B, Hq, seed=1720).to(DEV))
             nk.copy_(synth.kv_stream(B, Hkv, 1721).permute(1, 0, 2).contiguous().to(DEV))
+        if rep >= 3:                    # the contexts grow (by 1, 1 and then to the limit), in place
+            step_by = 1 if rep < 5 else grow - 2
+            ctx_len.add_(step_by)
+            dst.add_(step_by)
         out.fill_(float("nan"))
         step()
         torch.cuda.synchronize()
