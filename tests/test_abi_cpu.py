@@ -78,6 +78,10 @@ def test_unsupported_dimension_and_null_arguments():
     assert L.pq_attn_decode_polar(c._h, fake, fake, 1, fake, fake, fake, fake, fake, fake, 1, 6, 4, 64, 64, 1.0, fake, 0, None) == -1  # Hq % Hkv
     assert L.pq_attn_decode_polar(c._h, fake, fake, 1, fake, fake, fake, fake, fake, fake, 1, 16, 1, 64, 64, 1.0, fake, 0, None) == -2  # group of 16
     assert L.pq_attn_decode_polar(c._h, fake, fake, 1, fake, fake, fake, fake, fake, fake, 1, 4, 1, 64, 64, 1.0, fake, 16, None) == -5  # workspace too small
+    # the device work plan counts the tiles of all (sequence, kv head) streams in 31 bits
+    big = 1 << 26
+    assert L.pq_attn_decode_polar(c._h, fake, fake, 1, fake, fake, fake, fake, fake, fake, 4096, 8, 8, big, big, 1.0, fake, 0,
+                                  None) == -2
     assert "PQ_EALIGN" in binding.pq_status_string(-3)
 
 
