@@ -426,6 +426,35 @@ def test_attention_many_sequences(env, B, Hq, Hkv, lo, hi):
     assert helpers.rel_l2(got2, ref) <= 2e-3
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6])
+def test_attention_random_batch_shapes(env, seed):
+    """Batch size, head counts and context lengths drawn at random (seeded): the device-side split of the
+    work has to cover every tile of every stream exactly once whatever the mix."""
+    ctx, S, cb = env
+    rng = np.random.default_rng(9000 + seed)
+    B = int(rng.integers(1, 100))
+    Hkv = int(rng.choice([1, 2, 3, 8]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hq = Hkv * G
+    hi = int(rng.choice([3, 70, 300, 900]))
+    lens = [int(n) for n in rng.integers(0, hi + 1, size=B)]
+    if sum(lens) == 0:
+        lens[0] = 1
+    say(f"attention, random shapes seed {seed}: B={B} Hq={Hq} Hkv={Hkv} lengths 0..{hi}, {sum(lens)} tokens")
+    caches, starts, pool, k_rec, v_rec = build_cache(ctx, S, cb, lens, Hkv, seed=9100 + 10 * seed)
+    q = synth.queries(B, Hq, seed=9200 + seed)
+    got = gpu_attention(ctx, q, caches, starts, lens)
+    ref = oracle.attention(q.to(torch.float64).numpy(), k_rec, v_rec, starts, np.array(lens, np.int32), S, cb,
+                           helpers.softmax_scale())
+    assert np.all(np.isfinite(got))
+    for b in range(B):
+        if lens[b] == 0:
+            assert np.all(got[b] == 0.0)
+    err = helpers.rel_l2(got, ref)
+    say(f"  rel L2 all rows {err:.2e}")
+    assert err <= 2e-3
+
+
 @pytest.mark.parametrize("shape", ["rising", "falling", "spike"])
 def test_attention_moving_maximum(env, shape):
     """Scores that climb (or fall) steadily along the context, or jump by a large amount at one token:
