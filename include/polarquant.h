@@ -56,7 +56,9 @@ typedef enum {
     PQ_EUNSUPPORTED = -2, /* d != 128, Hq/Hkv not in {1,2,4,8}, ... */
     PQ_EALIGN = -3,       /* device pointer or stride not 16-byte aligned */
     PQ_EHIP = -4,         /* a HIP runtime call failed (no device, launch error) */
-    PQ_ENOMEM = -5        /* host or device allocation failed, workspace too small */
+    PQ_ENOMEM = -5,       /* host or device allocation failed, workspace too small */
+    PQ_ESCRATCH = -6,     /* pq_attn_decode_polar_static: the problem needs more than PQ_STATIC_SCRATCH_BYTES */
+    PQ_ENOTREADY = -7     /* pq_attn_decode_polar_static: pq_prepare_device has not run for this context and device */
 } pq_status;
 
 #define PQ_D 128               /* head dimension */
@@ -285,6 +287,35 @@ pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void *out, pq_d
                                void *hip_stream);
 
 size_t pq_attn_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ctx);
+
+/* ---------------------------------------------------------------------------
+ * pq_attn_decode_polar for callers that cannot allocate device memory or hand
+ * over a workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same kernels and bit-identical results,
+ * but the workspace is a device array inside the library of
+ * PQ_STATIC_SCRATCH_BYTES bytes (held by every GPU the library runs on until the
+ * process ends).  The call itself allocates nothing and frees nothing:
+ *   - a problem whose workspace (pq_attn_workspace_bytes) exceeds the array is
+ *     refused with PQ_ESCRATCH before anything is launched;
+ *   - the context's constants must already be on the current device, which
+ *     pq_prepare_device(ctx) does once (it allocates; so does the first
+ *     pq_encode_kv or attention call with the context on that device):
+ *     PQ_ENOTREADY otherwise.
+ * Every call on a GPU uses that GPU's one array, and the array keeps the last
+ * call's contents (nothing in it has to start at zero: the work plan and every
+ * partial result are written before they are read).  Calls that overlap in time
+ * on one GPU -- two streams, two threads -- race on it; calls ordered on one
+ * stream do not.
+ * ------------------------------------------------------------------------- */
+#define PQ_STATIC_SCRATCH_BYTES (16u << 20)
+size_t pq_static_scratch_bytes(void);
+pq_status pq_prepare_device(const pq_ctx *ctx);
+pq_status pq_attn_decode_polar_static(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
+                                      const uint8_t *k_codes, const uint16_t *k_radii,
+                                      const uint8_t *v_codes, const uint16_t *v_radii,
+                                      const int64_t *seq_start, const int32_t *ctx_len,
+                                      int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
+                                      float softmax_scale, void *hip_stream);
 
 /* The same for M query tokens per sequence at once (several draft tokens of a
  * speculative step, or a chunk of a prompt): q, out (device): [B][M][Hq][128].  The

@@ -99,6 +99,13 @@ def library():
     L.pq_attn_mq_workspace_bytes.argtypes = [i32, i32, i32, i32, i64]
     L.pq_attn_workspace_bytes.restype = ctypes.c_size_t
     L.pq_attn_workspace_bytes.argtypes = [i32, i32, i32, i64]
+    L.pq_static_scratch_bytes.restype = ctypes.c_size_t
+    L.pq_static_scratch_bytes.argtypes = []
+    L.pq_prepare_device.restype = i32
+    L.pq_prepare_device.argtypes = [vp]
+    L.pq_attn_decode_polar_static.restype = i32
+    L.pq_attn_decode_polar_static.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, i64,
+                                              ctypes.c_float, vp]
     L.pq_profile_begin.restype = i32
     L.pq_profile_begin.argtypes = [i32]
     L.pq_profile_begin_sampled.restype = i32
@@ -438,6 +445,25 @@ class Context:
             _dtype_code(out), k_codes.data_ptr(), k_radii.data_ptr(), v_codes.data_ptr(), v_radii.data_ptr(),
             seq_start.data_ptr(), ctx_len.data_ptr(), int(B), int(Hq), int(Hkv), int(pool_tokens), int(max_ctx),
             float(softmax_scale), workspace.data_ptr(), int(workspace.numel() * workspace.element_size()), _stream()))
+
+    @staticmethod
+    def static_scratch_bytes():
+        return int(library().pq_static_scratch_bytes())
+
+    def prepare_device(self):
+        """Uploads the context's constants to the current device (the one call of the static path that allocates)."""
+        _check(library().pq_prepare_device(self._h))
+
+    def attn_decode_polar_static(self, q, out, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len, max_ctx,
+                                 softmax_scale):
+        """attn_decode_polar with the workspace in the library's static device array; allocates nothing."""
+        B, Hq = q.shape[0], q.shape[1]
+        Hkv = k_codes.shape[0]
+        pool_tokens = k_codes.shape[1] * TILE_TOKENS
+        _check(library().pq_attn_decode_polar_static(
+            self._h, q.data_ptr(), out.data_ptr(), _dtype_code(out), k_codes.data_ptr(), k_radii.data_ptr(), v_codes.data_ptr(),
+            v_radii.data_ptr(), seq_start.data_ptr(), ctx_len.data_ptr(), int(B), int(Hq), int(Hkv), int(pool_tokens),
+            int(max_ctx), float(softmax_scale), _stream()))
 
     def attn_decode_polar(self, q, out, k_codes, k_radii, v_codes, v_radii, seq_start, ctx_len, max_ctx,
                           softmax_scale, workspace):

@@ -1492,6 +1492,69 @@ extern "C" pq_status pq_attn_decode_polar(const pq_ctx *ctx, const void *q, void
                               softmax_scale, workspace, workspace_bytes, hip_stream);
 }
 
+/* ---- the entry point that allocates nothing ----
+ * pq_attn_decode_polar with the workspace (rotated queries, work plan, partial results) in a
+ * file-scope device array instead of a caller buffer.  `scratch` is the host-side stand-in of
+ * the array: host code never passes it to a kernel or a copy, only the device address that
+ * hipGetSymbolAddress returns for the current device (every device holds its own copy of the
+ * array at its own address), resolved once per device and kept. */
+static __device__ __align__(256) unsigned char scratch[PQ_STATIC_SCRATCH_BYTES];
+
+namespace {
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[PQ_MAX_DEVICES] = {nullptr};
+
+pq_status scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    PQ_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= PQ_MAX_DEVICES) return PQ_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PQ_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return PQ_OK;
+}
+} // namespace
+
+extern "C" size_t pq_static_scratch_bytes(void) { return PQ_STATIC_SCRATCH_BYTES; }
+
+extern "C" pq_status pq_prepare_device(const pq_ctx *ctx)
+{
+    if (!ctx) return PQ_EINVAL;
+    const PqDeviceState *ds = nullptr;
+    const pq_status st = pq_device_state(ctx, &ds); /* uploads the context's constants on first use (allocates) */
+    if (st != PQ_OK) return st;
+    void *p = nullptr;
+    return scratch_of_current_device(&p);
+}
+
+extern "C" pq_status pq_attn_decode_polar_static(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
+                                                 const uint8_t *k_codes, const uint16_t *k_radii,
+                                                 const uint8_t *v_codes, const uint16_t *v_radii,
+                                                 const int64_t *seq_start, const int32_t *ctx_len,
+                                                 int B, int Hq, int Hkv, int64_t pool_tokens, int64_t max_ctx,
+                                                 float softmax_scale, void *hip_stream)
+{
+    if (!ctx) return PQ_EINVAL;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || max_ctx < 0 || Hq % Hkv) return PQ_EINVAL;
+    /* sizes first: a problem beyond the array is refused before anything else is looked at */
+    if (max_ctx > ((int64_t)1 << 26) || (int64_t)B * Hkv * ((max_ctx + 63) / 64) >= ((int64_t)1 << 31) - 4096)
+        return PQ_EUNSUPPORTED;
+    if (make_plan(B, Hq, Hkv, max_ctx).total > (size_t)PQ_STATIC_SCRATCH_BYTES) return PQ_ESCRATCH;
+    if (!pq_device_state_ready(ctx)) return PQ_ENOTREADY; /* the upload of the constants would allocate */
+    void *ws = nullptr;
+    const pq_status st = scratch_of_current_device(&ws);
+    if (st != PQ_OK) return st;
+    return attention_launches(ctx, nullptr, nullptr, 1, q, out, out_dtype, const_cast<uint8_t *>(k_codes),
+                              const_cast<uint16_t *>(k_radii), const_cast<uint8_t *>(v_codes),
+                              const_cast<uint16_t *>(v_radii), seq_start, ctx_len, B, Hq, Hkv, pool_tokens, max_ctx,
+                              softmax_scale, ws, PQ_STATIC_SCRATCH_BYTES, hip_stream);
+}
+
 extern "C" pq_status pq_decode_step_polar(const pq_ctx *ctx, const void *xk, const void *xv, pq_dtype xt,
                                           const int64_t *dst_token, const void *q, void *out, pq_dtype out_dtype,
                                           uint8_t *k_codes, uint16_t *k_radii, uint8_t *v_codes, uint16_t *v_radii,

@@ -119,6 +119,8 @@ struct pq_ctx {
 /* Returns the constant buffers of the current device, uploading them on the
  * first call per device.  PQ_EHIP if there is no usable device. */
 pq_status pq_device_state(const pq_ctx *ctx, const PqDeviceState **out);
+/* true once pq_device_state has uploaded the constants of ctx to the current device */
+bool pq_device_state_ready(const pq_ctx *ctx);
 
 #define PQ_HIP_TRY(expr)                         \
     do {                                         \

@@ -366,6 +366,8 @@ extern "C" const char *pq_status_string(pq_status s)
     case PQ_EALIGN: return "PQ_EALIGN: device pointer or stride not 16-byte aligned";
     case PQ_EHIP: return "PQ_EHIP: HIP runtime error or no device";
     case PQ_ENOMEM: return "PQ_ENOMEM: allocation failed or workspace too small";
+    case PQ_ESCRATCH: return "PQ_ESCRATCH: the problem needs more than the static scratch buffer (pq_static_scratch_bytes)";
+    case PQ_ENOTREADY: return "PQ_ENOTREADY: the context's constants are not on this device yet (call pq_prepare_device first)";
     }
     return "unknown pq_status";
 }
@@ -630,6 +632,15 @@ pq_status pq_device_state(const pq_ctx *cctx, const PqDeviceState **out)
     }
     *out = &s;
     return PQ_OK;
+}
+
+bool pq_device_state_ready(const pq_ctx *cctx)
+{
+    pq_ctx *ctx = const_cast<pq_ctx *>(cctx);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= PQ_MAX_DEVICES) return false;
+    std::lock_guard<std::mutex> lock(ctx->mu);
+    return ctx->dev[dev].ready;
 }
 
 /* ---- optional kernel timing with HIP events on the launch stream ---- */
