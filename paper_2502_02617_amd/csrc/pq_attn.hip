@@ -42,6 +42,8 @@
  *       slots of the other parity.  The result accumulates o' for the even
  *       coordinates in the parity-0 columns and for the odd ones in parity 1.
  */
+#include <type_traits>
+
 #include "pq_common.h"
 #include "pq_polar.h"
 
@@ -51,7 +53,11 @@ typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWavesPerBlock = 4;
+/* One workgroup per CU: the lookup tables are laid out in LDS with a private bank column per lane (see
+ * stage_tables), which takes 48 KB, so all wavefronts resident on a CU share one copy: 4 SIMDs x the
+ * wavefronts per SIMD that the variant's register budget allows. */
+constexpr int waves_per_simd(int NG) { return NG == 1 ? 4 : (NG == 2 ? 3 : 2); }
+constexpr int waves_per_block(int NG) { return 4 * waves_per_simd(NG); }
 constexpr float kLog2e = 1.4426950408889634f;
 /* Probabilities are handed to the matrix cores as binary16.  They are computed
  * as 2^(s - m + kProbShift) against an exponent reference m that may lag the true
@@ -61,9 +67,30 @@ constexpr float kProbShift = 9.0f;
 constexpr float kRefSlack = 6.0f;
 
 /* LDS table block: layout in pq_common.h (PQ_TAB_*), image built on the host */
-constexpr int kT1 = PQ_TAB_T1, kTA = PQ_TAB_TA, kTB = PQ_TAB_TB, kT4B = PQ_TAB_T4B, kT1F = PQ_TAB_T1F;
-constexpr int kTAF = PQ_TAB_TAF, kTBF = PQ_TAB_TBF, kT4F = PQ_TAB_T4F;
-constexpr int kTUp = PQ_TAB_UP, kTG = PQ_TAB_TG, kTGF = PQ_TAB_TGF, kT1B = PQ_TAB_T1B, kTabDwords = PQ_TAB_DWORDS;
+constexpr int kTabDwords = PQ_TAB_DWORDS;
+/* The tables as the kernel lays them out in LDS (dwords).  Random gathers from a table collide in the LDS banks
+ * unless every lane that is served in the same cycle reads its own bank: a 4-byte gather is served 32 lanes at a
+ * time, a 16-byte gather 16 lanes at a time, so the small tables are replicated into one column per lane (mod 32,
+ * mod 16) -- entry e of lane l at row e, column l -- and their gathers never collide (2.4 instead of 4.1 cycles
+ * per 4-byte gather from 64 entries, 4.6 instead of 10.4 per 16-byte gather).
+ *   kTQ   [1024][2]       quarter table, by Q (8 KB, gathered as it is: 32 columns of it would be 256 KB)
+ *   kTQA  [64][32]        first pair of a quarter, by Q & 63 = c2 << 4 | c1
+ *   kTQB  [64][32]        second pair, by Q >> 4 = c1' << 2 | c2
+ *   kTBF  [64][16][4]     block table of the keys (fp32), by B
+ *   kTBH  [64][32]        block table of the values: column l holds the binary16 pair of half-block l & 1
+ *   kTUp  [3][8][2]       levels 5..7 (full depth) */
+constexpr int kTQ = 0, kTQA = 2048, kTQB = 4096, kTBF = 6144, kTBH = 10240, kTUp = 12288, kLdsTabDwords = 12336;
+/* how a quarter's table entry is fetched: as one 8-byte gather from kTQ (bank conflicts, but one index), or as
+   two conflict-free 4-byte gathers from the pair tables (two indices) */
+#ifndef PQ_KEY_PAIRS
+#define PQ_KEY_PAIRS 1
+#endif
+#ifndef PQ_VALUE_PAIRS
+#define PQ_VALUE_PAIRS 0
+#endif
+#ifndef PQ_Q_REMAINDER
+#define PQ_Q_REMAINDER 1
+#endif
 
 struct AttnArgs {
     const uint16_t *qrot; /* [B][M][Hq][2][128] binary16: rotated, pre-scaled q' as a leading part and its remainder */
@@ -100,6 +127,8 @@ struct AttnArgs {
 constexpr int kPlanHeader = 2;
 constexpr int kMinShareTiles = 4;
 
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+
 union H8 {
     h8 v;
     uint4 q;
@@ -107,26 +136,18 @@ union H8 {
     h2 p[4];
 };
 
+union H4 {
+    h4 v;
+    uint2 d;
+    uint32_t w[2];
+    h2 p[2];
+};
+
 __device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
 __device__ __forceinline__ uint32_t as_u32(h2 v) { return __builtin_bit_cast(uint32_t, v); }
 
-/* fetch a packed (lo, hi) binary16 pair from an LDS table; byte_off is 4 * index */
-__device__ __forceinline__ h2 lut(const uint32_t *tab, int table, uint32_t byte_off)
-{
-    return as_h2(*reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(tab + table) + byte_off));
-}
-
 __device__ __forceinline__ h2 bcast_lo(h2 v) { return h2{v.x, v.x}; }
 __device__ __forceinline__ h2 bcast_hi(h2 v) { return h2{v.y, v.y}; }
-
-/* Byte offsets (4 * code) of eight 4-bit codes packed in one dword, with 12
- * operations instead of 16: two masked copies hold the even and the odd codes
- * already multiplied by four, one per byte, and each offset is then a single
- * byte extraction.  The empty asm statements keep the compiler from folding
- * the masks back into per-code shift-and-mask pairs. */
-struct NibbleOffsets {
-    uint32_t even, odd; /* byte k of even: 4 * code 2k; of odd: 4 * code 2k+1 */
-};
 
 /* A 32-bit literal doubles the size of a vector instruction; masks used hundreds of times
  * per tile are kept in scalar registers instead (the empty asm hides their value from
@@ -137,198 +158,58 @@ __device__ __forceinline__ uint32_t scalar_const(uint32_t v)
     return v;
 }
 
-__device__ __forceinline__ NibbleOffsets nibble_offsets(uint32_t w)
+/* Byte offset of a table entry from the index stored at bit BIT of the little-endian bit string
+ * w[0], w[1], ...: (index << SHIFT), entries of 2^SHIFT bytes.  The position is a compile-time
+ * constant, so this is one shift (a funnel shift where the field straddles two dwords) and one
+ * mask-and-or; a field that already sits at bit SHIFT of its dword needs the latter only. */
+template <int BIT, int WIDTH, int SHIFT>
+__device__ __forceinline__ uint32_t table_offset(const uint32_t *w, uint32_t column = 0u)
 {
-    NibbleOffsets r;
-    const uint32_t m = scalar_const(0x3C3C3C3Cu);
-    r.even = (w << 2) & m;
-    r.odd = (w >> 2) & m;
-    asm("" : "+v"(r.even));
-    asm("" : "+v"(r.odd));
-    return r;
+    constexpr int d = BIT >> 5, s = BIT & 31;
+    const uint32_t mask = scalar_const(((1u << WIDTH) - 1u) << SHIFT);
+    uint32_t v;
+    if constexpr (s + WIDTH <= 32) {
+        if constexpr (s == SHIFT) v = w[d];
+        else if constexpr (s > SHIFT) v = w[d] >> (s - SHIFT);
+        else v = w[d] << (SHIFT - s);
+    } else {
+        static_assert(s + WIDTH <= 32 || s >= SHIFT, "a straddling field starts above bit SHIFT");
+        v = __builtin_amdgcn_alignbit(w[d + 1], w[d], s - SHIFT);
+    }
+    return (v & mask) | column; /* column: the lane's byte offset inside a row of a table with a column per lane */
 }
 
-/* the same with 8 * code (8-byte table entries) */
-__device__ __forceinline__ NibbleOffsets nibble_offsets8(uint32_t w)
+/* The four binary16 values of a quarter from the 10-bit index stored at bit BIT of the string w: either entry Q of
+ * the quarter table, or entries Q & 63 and Q >> 4 of the two pair tables (col4 = 4 * (lane & 31)). */
+template <int BIT, bool PAIRS>
+__device__ __forceinline__ uint2 quarter_entry(const uint32_t *tab, const uint32_t *w, uint32_t col4)
 {
-    NibbleOffsets r;
-    const uint32_t m = scalar_const(0x78787878u);
-    r.even = (w << 3) & m;
-    r.odd = (w >> 1) & m;
-    asm("" : "+v"(r.even));
-    asm("" : "+v"(r.odd));
-    return r;
-}
-
-template <int CODE>
-__device__ __forceinline__ uint32_t nibble_offset(const NibbleOffsets &n)
-{
-    const uint32_t src = (CODE & 1) ? n.odd : n.even;
-    constexpr int k = CODE >> 1;
-    if (k == 0) return src & 0xFFu;
-    if (k == 3) return src >> 24;
-    return __builtin_amdgcn_ubfe(src, 8 * k, 8);
-}
-
-/* Byte offsets (8 * byte) of the four bytes of a dword, each byte a pair of 4-bit codes: table entries of 8 bytes */
-struct ByteOffsets {
-    uint32_t even, odd; /* even: bytes 0, 2 at bits [3, 11), [19, 27); odd: bytes 1, 3 likewise */
-};
-
-__device__ __forceinline__ ByteOffsets byte_offsets8(uint32_t w)
-{
-    ByteOffsets r;
-    const uint32_t m = scalar_const(0x07F807F8u);
-    r.even = (w << 3) & m;
-    r.odd = (w >> 5) & m;
-    asm("" : "+v"(r.even));
-    asm("" : "+v"(r.odd));
-    return r;
-}
-
-template <int BYTE>
-__device__ __forceinline__ uint32_t byte_offset(const ByteOffsets &b)
-{
-    const uint32_t src = (BYTE & 1) ? b.odd : b.even;
-    return (BYTE & 2) ? src >> 16 : src & 0xFFFFu;
-}
-
-/* The same idea for the four 6-bit groups g = [c2a | c3 | c2b] of a 24-bit string: two masked copies of
- * the string shifted left by SHIFT hold the even and the odd groups, so that (g << SHIFT) -- the byte
- * offset of entry g of a table with 2^SHIFT-byte entries -- is one extraction per group. */
-struct GroupOffsets {
-    uint32_t even, odd; /* even: groups 0, 2 at bits [SHIFT, SHIFT+6), [SHIFT+12, SHIFT+18); odd: 1, 3 six bits higher */
-};
-
-template <int SHIFT>
-__device__ __forceinline__ GroupOffsets group_offsets(uint32_t g24)
-{
-    GroupOffsets r;
-    const uint32_t p = g24 << SHIFT;
-    r.even = p & scalar_const((0x3Fu << SHIFT) | (0x3Fu << (SHIFT + 12)));
-    r.odd = p & scalar_const((0x3Fu << (SHIFT + 6)) | (0x3Fu << (SHIFT + 18)));
-    asm("" : "+v"(r.even));
-    asm("" : "+v"(r.odd));
-    return r;
-}
-
-template <int K, int SHIFT>
-__device__ __forceinline__ uint32_t group_offset(const GroupOffsets &g)
-{
-    if (K == 0) return g.even & ((1u << (SHIFT + 6)) - 1u);
-    if (K == 2) return g.even >> 12;
-    if (K == 1) return __builtin_amdgcn_ubfe(g.odd, 6, SHIFT + 6);
-    return g.odd >> 18;
-}
-
-/* Table entries of one half-block, fetched before any arithmetic so that the LDS
- * gathers of a whole block are in flight together. */
-struct HalfBlockLut {
-    h2 ta, tb, t1[4];
-};
-
-__device__ __forceinline__ void gather_half_block(const uint32_t *tab, uint32_t offG, uint32_t b0, uint32_t b1, HalfBlockLut &l)
-{
-    const uint2 g = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(tab + kTG) + offG); /* offG = 8 * group */
-    l.ta = as_h2(g.x);
-    l.tb = as_h2(g.y);
-    const uint2 p0 = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(tab + kT1B) + b0); /* 8 * code pair */
-    const uint2 p1 = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(tab + kT1B) + b1);
-    l.t1[0] = as_h2(p0.x);
-    l.t1[1] = as_h2(p0.y);
-    l.t1[2] = as_h2(p1.x);
-    l.t1[3] = as_h2(p1.y);
-}
-
-/* The four level-1 radii of a half-block times their (cos, sin) pairs:
- * r3 = (r, r) radius of the level-3 node. */
-__device__ __forceinline__ void expand_half_block(h2 r3, const HalfBlockLut &l, h2 out[4])
-{
-    h2 ra = r3 * l.ta; /* (r1_0, r1_1) */
-    h2 rb = r3 * l.tb; /* (r1_2, r1_3) */
-    out[0] = bcast_lo(ra) * l.t1[0];
-    out[1] = bcast_hi(ra) * l.t1[1];
-    out[2] = bcast_lo(rb) * l.t1[2];
-    out[3] = bcast_hi(rb) * l.t1[3];
-}
-
-/* Key-side tables of one half-block, all fp32: level-3 x level-2 products (low and high
- * half of the packed entry the value path uses), level-1 (cos, sin) pairs. */
-struct KeyHalfBlockLut {
-    float ta0, ta1, tb0, tb1;
-    float2 t1[4];
-};
-
-__device__ __forceinline__ float2 lut_f2(const uint32_t *tab, uint32_t byte_off) /* byte_off = 8 * index */
-{
-    return *reinterpret_cast<const float2 *>(reinterpret_cast<const char *>(tab + kT1F) + byte_off);
-}
-
-/* fp32 entry `index` of a dword table; byte_off is 4 * index */
-__device__ __forceinline__ float lut_f(const uint32_t *tab, int table, uint32_t byte_off)
-{
-    return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(tab + table) + byte_off);
-}
-
-__device__ __forceinline__ void gather_key_half_block(const uint32_t *tab, uint32_t offG,
-                                                      uint32_t o0, uint32_t o1, uint32_t o2, uint32_t o3,
-                                                      KeyHalfBlockLut &l)
-{
-    const float4 g = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(tab + kTGF) + offG); /* offG = 16 * group */
-    l.ta0 = g.x;
-    l.ta1 = g.y;
-    l.tb0 = g.z;
-    l.tb1 = g.w;
-    l.t1[0] = lut_f2(tab, o0);
-    l.t1[1] = lut_f2(tab, o1);
-    l.t1[2] = lut_f2(tab, o2);
-    l.t1[3] = lut_f2(tab, o3);
-}
-
-/* Key-side half-block expansion with every product formed in fp32 from fp32 tables and
- * each of the 8 results rounded to binary16 exactly once.  r3 is the radius times the
- * level-4 entry.  The scores are the precision-critical contraction (an error of a key
- * element moves a softmax weight, and those errors do not average out over the context),
- * so the keys pay for the extra instructions; the values use the packed binary16 chain.
- * Plain fp32 multiplies plus one packed conversion per pair issue faster than mixed-
- * precision multiplies on binary16 table entries. */
-__device__ __forceinline__ h2 round_pair(float a, float b) { return h2{(_Float16)a, (_Float16)b}; }
-
-__device__ __forceinline__ void expand_key_half_block(float r3, const KeyHalfBlockLut &l, h2 out[4])
-{
-    const float r10 = r3 * l.ta0, r11 = r3 * l.ta1, r12 = r3 * l.tb0, r13 = r3 * l.tb1;
-    out[0] = round_pair(r10 * l.t1[0].x, r10 * l.t1[0].y);
-    out[1] = round_pair(r11 * l.t1[1].x, r11 * l.t1[1].y);
-    out[2] = round_pair(r12 * l.t1[2].x, r12 * l.t1[2].y);
-    out[3] = round_pair(r13 * l.t1[3].x, r13 * l.t1[3].y);
-}
-
-/* 24 bits starting at bit 24*i of the 96-bit little-endian string (d0, d1, d2), in the low 24 bits of
- * the result; the bits above them are not cleared (group_offsets masks what it uses) */
-__device__ __forceinline__ uint32_t take24(uint32_t d0, uint32_t d1, uint32_t d2, int i)
-{
-    switch (i) {
-    case 0: return d0;
-    case 1: return __builtin_amdgcn_alignbit(d1, d0, 24);
-    case 2: return __builtin_amdgcn_alignbit(d2, d1, 16);
-    default: return d2 >> 8;
+    if constexpr (PAIRS) {
+        const uint32_t oa = table_offset<BIT, 6, 7>(w, col4), ob = table_offset<BIT + 4, 6, 7>(w, col4);
+        return make_uint2(*reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(tab + kTQA) + oa),
+                          *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(tab + kTQB) + ob));
+    } else {
+        const uint32_t o = table_offset<BIT, 10, 3>(w);
+        return *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(tab + kTQ) + o);
     }
 }
 
+/* Raw registers of a key tile: lane tau holds token tau -- its 46 code bytes (12 dwords, the last one
+ * half used) and its 8 block radii, or at depth 7 its word of the radius plane. */
 struct KTileRaw {
-    uint4 l1a, l1b; /* chunks 0,1 | 2,3: {L1 block A, L1 block B} each */
-    uint32_t g0, g1, g2;
-    uint32_t c4;    /* 16 bits used */
-    uint4 rad;      /* chunk i: (radius A, radius B) */
-    uint32_t top;   /* depth 7 instead of rad: radius-plane word of token `lane` */
+    uint32_t w[12];
+    uint4 rad;
+    uint32_t top;
 };
 
+/* Raw registers of a value tile: lane (g, n) holds the 40-byte index string of half-block n for its 16
+ * token slots, the 12-byte block-index string and the 16 radii of its block (both shared with the lane
+ * of the block's other half), or at depth 7 the radius-plane word of token `lane`. */
 struct VTileRaw {
-    uint4 l1a, l1b; /* slots 0..7 | 8..15, 16 bits each */
-    uint32_t g0, g1, g2;
-    uint32_t c4;    /* slot s at bits [2s, 2s+2) */
+    uint32_t q[10];
+    uint32_t b[3];
     uint4 rad0, rad1; /* slots 0..7 | 8..15 */
-    uint32_t top;     /* depth 7 instead of rad0, rad1: radius-plane word of token `lane` */
+    uint32_t top;
 };
 
 /* The tiles of one (sequence, kv head) stream are read through buffer descriptors: the address of a
@@ -337,6 +218,7 @@ struct VTileRaw {
  * sequence's tile count, which is also the size the descriptor is given. */
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t stream_descriptor(const void *base, uint32_t bytes)
 {
@@ -360,11 +242,13 @@ __device__ __forceinline__ void load_k_tile(KTileRaw &t, __amdgpu_buffer_rsrc_t 
 {
     asm volatile("" : "+v"(lane));
     const uint32_t co = tile * PQL_CODE_BYTES;
-    t.l1a = load16(codes, lane * 16u, co + PQL_OFF_L1A);
-    t.l1b = load16(codes, lane * 16u, co + PQL_OFF_L1B);
-    const u32x3 g = __builtin_amdgcn_raw_buffer_load_b96(codes, lane * 12u, co + PQL_OFF_G6, 0);
-    t.g0 = g.x; t.g1 = g.y; t.g2 = g.z;
-    t.c4 = __builtin_amdgcn_raw_buffer_load_b16(codes, lane * 2u, co + PQL_OFF_C4, 0);
+    const uint4 a = load16(codes, lane * 16u, co + PQL_OFF_P0);
+    const uint4 b = load16(codes, lane * 16u, co + PQL_OFF_P1);
+    const u32x3 c = __builtin_amdgcn_raw_buffer_load_b96(codes, lane * 12u, co + PQL_OFF_P2, 0);
+    t.w[0] = a.x; t.w[1] = a.y; t.w[2] = a.z; t.w[3] = a.w;
+    t.w[4] = b.x; t.w[5] = b.y; t.w[6] = b.z; t.w[7] = b.w;
+    t.w[8] = c.x; t.w[9] = c.y; t.w[10] = c.z;
+    t.w[11] = __builtin_amdgcn_raw_buffer_load_b16(codes, lane * 2u, co + PQL_OFF_KP3, 0);
     if (DEEP) t.top = __builtin_amdgcn_raw_buffer_load_b32(radii, lane * 4u, tile * (PQ_DEEP_RADII_HALVES * 2u), 0);
     else t.rad = load16(radii, lane * 16u, tile * (PQL_RADII * 2u));
 }
@@ -375,11 +259,14 @@ __device__ __forceinline__ void load_v_tile(VTileRaw &t, __amdgpu_buffer_rsrc_t 
 {
     asm volatile("" : "+v"(lane));
     const uint32_t co = tile * PQL_CODE_BYTES;
-    t.l1a = load16(codes, lane * 16u, co + PQL_OFF_L1A);
-    t.l1b = load16(codes, lane * 16u, co + PQL_OFF_L1B);
-    const u32x3 g = __builtin_amdgcn_raw_buffer_load_b96(codes, lane * 12u, co + PQL_OFF_G6, 0);
-    t.g0 = g.x; t.g1 = g.y; t.g2 = g.z;
-    t.c4 = __builtin_amdgcn_raw_buffer_load_b32(codes, (lane >> 1) * 4u, co + PQL_OFF_C4, 0);
+    const uint4 a = load16(codes, lane * 16u, co + PQL_OFF_P0);
+    const uint4 b = load16(codes, lane * 16u, co + PQL_OFF_P1);
+    const u32x2 c = __builtin_amdgcn_raw_buffer_load_b64(codes, lane * 8u, co + PQL_OFF_P2, 0);
+    const u32x3 x = __builtin_amdgcn_raw_buffer_load_b96(codes, (lane >> 1) * 12u, co + PQL_OFF_VB, 0);
+    t.q[0] = a.x; t.q[1] = a.y; t.q[2] = a.z; t.q[3] = a.w;
+    t.q[4] = b.x; t.q[5] = b.y; t.q[6] = b.z; t.q[7] = b.w;
+    t.q[8] = c.x; t.q[9] = c.y;
+    t.b[0] = x.x; t.b[1] = x.y; t.b[2] = x.z;
     if (DEEP) {
         t.top = __builtin_amdgcn_raw_buffer_load_b32(radii, lane * 4u, tile * (PQ_DEEP_RADII_HALVES * 2u), 0);
     } else {
@@ -388,18 +275,6 @@ __device__ __forceinline__ void load_v_tile(VTileRaw &t, __amdgpu_buffer_rsrc_t 
     }
 }
 
-/* Depth 7: the block radii of a tile are not stored but rebuilt from each token's radius and its
- * codes of levels 7, 6, 5 (DeQuant's first three steps).  Lane tau does that for token tau, all
- * eight blocks, and leaves the results in LDS in the order in which the passes consume the stored
- * radii of a depth-4 tile: keys as fp32 (the key path forms every product in fp32),
- * krad[(16 gk + m) * 8 + 2 i + beta] = radius of block 2 gk + beta of token 16 i + m; values as
- * binary16, vrad[(8 g + b) * 16 + 4 i + e] = radius of block b of token 16 i + 4 g + e. */
-struct DeepRadii {
-    float *krad;       /* [512] */
-    uint16_t *vrad;    /* [512] */
-    int b5, b6, b7;
-};
-
 __device__ __forceinline__ void wave_lds_fence()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -407,24 +282,25 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
-__device__ __forceinline__ void expand_deep_radii(const uint32_t *tab, const DeepRadii &dr, uint32_t ktop, uint32_t vtop, int lane)
+/* Depth 7: the block radii of a tile are not stored but rebuilt from each token's radius and its
+ * codes of levels 7, 6, 5 (DeQuant's first three steps).  On the key side lane tau does that for its
+ * own token, in registers.  On the value side lane tau does it for token tau and leaves the eight radii
+ * in LDS as binary16 in the order in which the passes read the stored radii of a depth-4 tile:
+ * vrad[(8 g + b) * 16 + 4 i + e] = radius of block b of token 16 i + 4 g + e. */
+struct DeepRadii {
+    uint16_t *vrad;    /* [512] */
+    int b5, b6, b7;
+};
+
+__device__ __forceinline__ void stage_deep_value_radii(const uint32_t *tab, const DeepRadii &dr, uint32_t vtop, int lane)
 {
     const float2 *cs = reinterpret_cast<const float2 *>(tab + kTUp);
     float r[8];
-    pq_deep_block_radii(ktop, dr.b5, dr.b6, dr.b7, cs, r);
-    {
-        const int i = lane >> 4, m = lane & 15;
-#pragma unroll
-        for (int gk = 0; gk < 4; ++gk)
-            *reinterpret_cast<float2 *>(dr.krad + (16 * gk + m) * 8 + 2 * i) = make_float2(r[2 * gk], r[2 * gk + 1]);
-    }
     pq_deep_block_radii(vtop, dr.b5, dr.b6, dr.b7, cs, r);
-    {
-        const int i = lane >> 4, g = (lane >> 2) & 3, e = lane & 3;
+    const int i = lane >> 4, g = (lane >> 2) & 3, e = lane & 3;
 #pragma unroll
-        for (int b = 0; b < 8; ++b)
-            dr.vrad[(8 * g + b) * 16 + 4 * i + e] = __builtin_bit_cast(uint16_t, (_Float16)r[b]);
-    }
+    for (int b = 0; b < 8; ++b)
+        dr.vrad[(8 * g + b) * 16 + 4 * i + e] = __builtin_bit_cast(uint16_t, (_Float16)r[b]);
 }
 
 /* Context length the kernels act on: the caller's value clamped to [0, max_ctx];
@@ -458,177 +334,162 @@ __device__ __forceinline__ uint32_t sel4(uint4 v, int c)
     return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w));
 }
 
-/* A operand of the scores of pass i of a 64-token tile: the rebuilt keys of tokens
- * 16*i + m (m = lane & 15), this lane's quarter of the coordinates in four slices. */
-template <int i, bool DEEP>
-__device__ __forceinline__ void key_operand(const uint32_t *tab, const KTileRaw &kcur, H8 (&ka)[4], const DeepRadii &dr, int lane)
+__device__ __forceinline__ float half_lo_to_float(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xFFFFu)); }
+__device__ __forceinline__ float half_hi_to_float(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); }
+
+/* Query operand of the scores: for column group k, A[k][set][part] holds in lane (i = lane >> 2, slot = lane & 3)
+ * the four rotated query coordinates 4 x .. 4 x + 3 of quarter x = 16 set + i for pair 4 k + slot, as the leading
+ * binary16 part (part 0) or its binary16 remainder (part 1).  v_mfma_f32_4x4x4_16b_f16 multiplies 16 independent
+ * 4x4 blocks; with the A block of one lane group broadcast to all sixteen (cbsz = 4, abid = i) one register pair
+ * serves sixteen quarters. */
+template <int NG> struct QueryOperand { H4 a[NG][2][2]; };
+
+/* Scores of one 64-token tile, one token per lane (Eq. 5 with DeQuant unrolled into table products):
+ *   s_pair(tau) = sum_b r_b(tau) sum_j T43[B_b][j] * < q'[16 b + 4 j .. + 3], T21[Q_{b,j}] >
+ * T21[Q] (binary16, from LDS) = the four products (cos|sin) theta2 * (cos|sin) theta1 of a quarter -- it is the B
+ * operand of the matrix instruction as fetched; T43[B] (fp32) = the four products (cos|sin) theta4 * (cos|sin)
+ * theta3 of a block.  The matrix cores form the 4-coordinate inner products of a quarter for four (query token,
+ * head) pairs per group (leading part and remainder of q' accumulate into the same result); each is scaled in fp32
+ * by r_b T43[B_b][j] and summed.  A key element is therefore never rounded beyond its table entry.
+ * s comes in holding the negated exponent reference (the first product of a tile adds to it). */
+template <int NG, bool DEEP>
+__device__ __forceinline__ void key_scores(const uint32_t *tab, const KTileRaw &k, const QueryOperand<NG> &qo,
+                                           float (&s)[NG][4], const DeepRadii &dr, int lane)
 {
-    const uint4 l1q = (i < 2) ? kcur.l1a : kcur.l1b;
-    const uint32_t l1A = (i & 1) ? l1q.z : l1q.x, l1B = (i & 1) ? l1q.w : l1q.y;
-    const GroupOffsets go = group_offsets<4>(take24(kcur.g0, kcur.g1, kcur.g2, i));
-    const uint32_t c4n = kcur.c4 >> (4 * i);
-    float radA, radB; /* radii of blocks 2gk, 2gk+1 */
+    const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
+    float rb[8];
     if (DEEP) {
-        const float2 rr = *reinterpret_cast<const float2 *>(dr.krad + lane * 8 + 2 * i);
-        radA = rr.x; radB = rr.y;
+        pq_deep_block_radii(k.top, dr.b5, dr.b6, dr.b7, reinterpret_cast<const float2 *>(tab + kTUp), rb);
     } else {
-        const h2 rad = as_h2(sel4(kcur.rad, i)); /* binary16 */
-        radA = (float)rad.x; radB = (float)rad.y;
+        rb[0] = half_lo_to_float(k.rad.x); rb[1] = half_hi_to_float(k.rad.x);
+        rb[2] = half_lo_to_float(k.rad.y); rb[3] = half_hi_to_float(k.rad.y);
+        rb[4] = half_lo_to_float(k.rad.z); rb[5] = half_hi_to_float(k.rad.z);
+        rb[6] = half_lo_to_float(k.rad.w); rb[7] = half_hi_to_float(k.rad.w);
     }
-    const NibbleOffsets noA = nibble_offsets8(l1A), noB = nibble_offsets8(l1B);
-    const uint32_t o4A = (c4n << 2) & 0xCu, o4B = c4n & 0xCu;
-    const float t4Ac = lut_f(tab, kT4F, o4A), t4As = lut_f(tab, kT4F + 4, o4A);
-    const float t4Bc = lut_f(tab, kT4F, o4B), t4Bs = lut_f(tab, kT4F + 4, o4B);
-    {   /* block A = 2*gk: slices 0, 1 */
-        KeyHalfBlockLut l0, l1;
-        gather_key_half_block(tab, group_offset<0, 4>(go), nibble_offset<0>(noA),
-                              nibble_offset<1>(noA), nibble_offset<2>(noA), nibble_offset<3>(noA), l0);
-        gather_key_half_block(tab, group_offset<1, 4>(go), nibble_offset<4>(noA),
-                              nibble_offset<5>(noA), nibble_offset<6>(noA), nibble_offset<7>(noA), l1);
-        expand_key_half_block(radA * t4Ac, l0, ka[0].p);
-        expand_key_half_block(radA * t4As, l1, ka[1].p);
-    }
-    {   /* block B = 2*gk + 1: slices 2, 3 */
-        KeyHalfBlockLut l0, l1;
-        gather_key_half_block(tab, group_offset<2, 4>(go), nibble_offset<0>(noB),
-                              nibble_offset<1>(noB), nibble_offset<2>(noB), nibble_offset<3>(noB), l0);
-        gather_key_half_block(tab, group_offset<3, 4>(go), nibble_offset<4>(noB),
-                              nibble_offset<5>(noB), nibble_offset<6>(noB), nibble_offset<7>(noB), l1);
-        expand_key_half_block(radB * t4Bc, l0, ka[2].p);
-        expand_key_half_block(radB * t4Bs, l1, ka[3].p);
-    }
+    const uint32_t col4 = (uint32_t)(lane & 31) * 4u, col16 = (uint32_t)(lane & 15) * 16u;
+    auto block = [&](auto bc) {
+        constexpr int b = decltype(bc)::value;
+        const uint32_t boff = table_offset<PQL_BLOCK_BITS * b + 40, 6, 8>(k.w, col16);
+        const float4 t43 = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(tab + kTBF) + boff);
+        const float rq[4] = {rb[b] * t43.x, rb[b] * t43.y, rb[b] * t43.z, rb[b] * t43.w};
+        H4 kq[4];
+        kq[0].d = quarter_entry<PQL_BLOCK_BITS * b + 0, PQ_KEY_PAIRS != 0>(tab, k.w, col4);
+        kq[1].d = quarter_entry<PQL_BLOCK_BITS * b + 10, PQ_KEY_PAIRS != 0>(tab, k.w, col4);
+        kq[2].d = quarter_entry<PQL_BLOCK_BITS * b + 20, PQ_KEY_PAIRS != 0>(tab, k.w, col4);
+        kq[3].d = quarter_entry<PQL_BLOCK_BITS * b + 30, PQ_KEY_PAIRS != 0>(tab, k.w, col4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            constexpr int set = b >> 2;         /* quarters 0..15 | 16..31 */
+            const int abid = (4 * b + j) & 15;  /* compile-time after unrolling */
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                f4 d;
+                switch (abid) { /* the broadcast selector is an immediate of the instruction */
+#define PQ_SCORE_CASE(N)                                                                                     \
+    case N:                                                                                                  \
+        d = __builtin_amdgcn_mfma_f32_4x4x4f16(qo.a[g][set][0].v, kq[j].v, zero, 4, N, 0);                      \
+        if (PQ_Q_REMAINDER) d = __builtin_amdgcn_mfma_f32_4x4x4f16(qo.a[g][set][1].v, kq[j].v, d, 4, N, 0);    \
+        break;
+                    PQ_SCORE_CASE(0) PQ_SCORE_CASE(1) PQ_SCORE_CASE(2) PQ_SCORE_CASE(3)
+                    PQ_SCORE_CASE(4) PQ_SCORE_CASE(5) PQ_SCORE_CASE(6) PQ_SCORE_CASE(7)
+                    PQ_SCORE_CASE(8) PQ_SCORE_CASE(9) PQ_SCORE_CASE(10) PQ_SCORE_CASE(11)
+                    PQ_SCORE_CASE(12) PQ_SCORE_CASE(13) PQ_SCORE_CASE(14)
+                    default: PQ_SCORE_CASE(15)
+#undef PQ_SCORE_CASE
+                }
+#pragma unroll
+                for (int h = 0; h < 4; ++h) s[g][h] = __builtin_fmaf(d[h], rq[j], s[g][h]);
+            }
+        }
+    };
+    block(std::integral_constant<int, 0>{}); block(std::integral_constant<int, 1>{});
+    block(std::integral_constant<int, 2>{}); block(std::integral_constant<int, 3>{});
+    block(std::integral_constant<int, 4>{}); block(std::integral_constant<int, 5>{});
+    block(std::integral_constant<int, 6>{}); block(std::integral_constant<int, 7>{});
 }
 
-/* A operands of the weighted value sum of pass i: the rebuilt values of tokens
- * 16*i + 4*g + e, one operand per output column group c.  MASKED zeroes the radii of
- * slots beyond the sequence's context so that stale cache bytes there cannot reach the sum. */
+/* A operands of the weighted value sum of pass i: the rebuilt values of tokens 16 i + 4 g + e, e = 0..3, for
+ * this lane's half-block, one operand per pair of coordinates c.  Per token: the radius times the block-table
+ * entry of this half (one packed product: the two quarter radii), times the two quarter entries T21[Q]
+ * (four packed products).  MASKED zeroes the radii of slots beyond the sequence's context so that stale
+ * cache bytes there cannot reach the sum. */
 template <int i, bool MASKED, bool DEEP>
-__device__ __forceinline__ void value_operand(const uint32_t *tab, const VTileRaw &vcur, H8 (&va)[4],
-                                              int n_valid, int g, int t4b, const DeepRadii &dr, int lane)
+__device__ __forceinline__ void value_operand(const uint32_t *tab, const char *tbh /* block table of the values */,
+                                              const VTileRaw &v, H8 (&va)[4], int n_valid, int g, const DeepRadii &dr,
+                                              int lane)
 {
-    const uint4 l1q = (i < 2) ? vcur.l1a : vcur.l1b;
-    const GroupOffsets go = group_offsets<3>(take24(vcur.g0, vcur.g1, vcur.g2, i));
     uint32_t rpair[2]; /* radii of tokens (0, 1) and (2, 3) of the pass */
     if (DEEP) {
         const uint2 rr = *reinterpret_cast<const uint2 *>(dr.vrad + (lane >> 1) * 16 + 4 * i);
         rpair[0] = rr.x; rpair[1] = rr.y;
     } else {
-        const uint4 rq = (i < 2) ? vcur.rad0 : vcur.rad1;
+        const uint4 rq = (i < 2) ? v.rad0 : v.rad1;
         rpair[0] = sel4(rq, 2 * (i & 1));
         rpair[1] = sel4(rq, 2 * (i & 1) + 1);
     }
-    const uint32_t c4x = vcur.c4 >> (8 * i); /* slots 4i..4i+3: 2 bits each */
-    h2 ve[4][4]; /* [token e][pair q] */
-#pragma unroll
-    for (int ep = 0; ep < 2; ++ep) { /* tokens 2ep, 2ep+1 share one L1 dword and one radius dword */
-        const ByteOffsets no = byte_offsets8(sel4(l1q, 2 * (i & 1) + ep));
-        h2 rad = as_h2(rpair[ep]);
-        h2 r0 = bcast_lo(rad), r1 = bcast_hi(rad);
+    h2 ve[4][4]; /* [token e][pair c] */
+    const uint32_t col4 = (uint32_t)(lane & 31) * 4u;
+    auto token = [&](auto ec) {
+        constexpr int e = decltype(ec)::value, s = 4 * i + e;
+        const h2 rad = as_h2(rpair[e >> 1]);
+        h2 r = (e & 1) ? bcast_hi(rad) : bcast_lo(rad);
         if (MASKED) {
-            const h2 zero = h2{(_Float16)0.f, (_Float16)0.f};
-            if (16 * i + 4 * g + 2 * ep >= n_valid) r0 = zero;
-            if (16 * i + 4 * g + 2 * ep + 1 >= n_valid) r1 = zero;
+            if (16 * i + 4 * g + e >= n_valid) r = h2{(_Float16)0.f, (_Float16)0.f};
         }
-        const uint32_t c4a = ep == 0 ? ((c4x << 2) & 0xCu) : ((c4x >> 2) & 0xCu);
-        const uint32_t c4b = ep == 0 ? (c4x & 0xCu) : ((c4x >> 4) & 0xCu);
-        const h2 t4a = lut(tab, t4b, c4a), t4bb = lut(tab, t4b, c4b);
-        HalfBlockLut l0, l1;
-        if (ep == 0) {
-            gather_half_block(tab, group_offset<0, 3>(go), byte_offset<0>(no), byte_offset<1>(no), l0);
-            gather_half_block(tab, group_offset<1, 3>(go), byte_offset<2>(no), byte_offset<3>(no), l1);
-        } else {
-            gather_half_block(tab, group_offset<2, 3>(go), byte_offset<0>(no), byte_offset<1>(no), l0);
-            gather_half_block(tab, group_offset<3, 3>(go), byte_offset<2>(no), byte_offset<3>(no), l1);
-        }
-        expand_half_block(r0 * t4a, l0, ve[2 * ep]);
-        expand_half_block(r1 * t4bb, l1, ve[2 * ep + 1]);
-    }
+        const uint32_t boff = table_offset<6 * s, 6, 7>(v.b, col4);
+        const h2 t43 = as_h2(*reinterpret_cast<const uint32_t *>(tbh + boff));
+        const uint2 ta = quarter_entry<PQL_SLOT_BITS * s, PQ_VALUE_PAIRS != 0>(tab, v.q, col4);
+        const uint2 tb = quarter_entry<PQL_SLOT_BITS * s + 10, PQ_VALUE_PAIRS != 0>(tab, v.q, col4);
+        const h2 rq = r * t43; /* radii of the half-block's two quarters */
+        const h2 ra = bcast_lo(rq), rbq = bcast_hi(rq);
+        ve[e][0] = ra * as_h2(ta.x);
+        ve[e][1] = ra * as_h2(ta.y);
+        ve[e][2] = rbq * as_h2(tb.x);
+        ve[e][3] = rbq * as_h2(tb.y);
+    };
+    token(std::integral_constant<int, 0>{}); token(std::integral_constant<int, 1>{});
+    token(std::integral_constant<int, 2>{}); token(std::integral_constant<int, 3>{});
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int e = 0; e < 4; ++e) va[c].p[e] = ve[e][c];
 }
 
-/* Softmax state of a column: the exponent reference m_ref is shared by the four
- * token groups of the column and only moves when a score exceeds it by more than
- * kRefSlack, which after the first pass of a piece is rare.  Probabilities are
- * exp2(s - m_ref + kProbShift): below 2^(kRefSlack + kProbShift), inside binary16,
- * and the partial result (m_ref, l, o) is consistent for any reference. */
-/* One pass: scores, reference check, probabilities, weighted values.  The operand
- * columns come in NG groups of 16: a group carries four (query, head) pairs -- columns
- * 0-7 their leading parts (pair n&3, parity (n>>2)&1), columns 8-15 the remainders -- and
- * has its own softmax state and output accumulators; the rebuilt keys and values (the
- * expensive part) are shared by all groups.  lim[k]: tokens of this tile that column
- * group k's pair of this lane may see (MASKED only). */
-template <int i, bool MASKED, int NG, bool DEEP>
-__device__ __forceinline__ void attend_pass(const uint32_t *tab, const KTileRaw &kcur, const VTileRaw &vcur,
-                                            const H8 (&qb)[NG][4], f4 (&acc_o)[NG][4], float (&m_ref)[NG],
-                                            float (&l_run)[NG], const int (&lim)[NG], int n_valid, int g,
-                                            uint32_t parity_shift, int t4b, const DeepRadii &dr, int lane)
+__device__ __forceinline__ float wave_max_f(float x)
 {
-    H8 pb[NG];
-    {
-        H8 ka[4];
-        key_operand<i, DEEP>(tab, kcur, ka, dr, lane);
 #pragma unroll
-        for (int k = 0; k < NG; ++k) {
-            f4 s4 = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-                s4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[s].v, qb[k][s].v, s4, 0, 0, 0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) /* leading part + remainder: columns n and n+8 (mod 16) of the same row of lanes */
-                s4[e] += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s4[e]), 0x128 /* row_ror:8 */, 0xF, 0xF, false));
-            if (MASKED) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (16 * i + 4 * g + e >= lim[k]) s4[e] = -INFINITY;
-            }
-            const float pmax = fmaxf(fmaxf(fmaxf(s4[0], s4[1]), s4[2]), s4[3]);
-            if (__ballot(pmax > m_ref[k] + kRefSlack) != 0ull) { /* wave-uniform */
-                float cmax = fmaxf(pmax, __shfl_xor(pmax, 16));
-                cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
-                const float m_new = fmaxf(m_ref[k], cmax);
-                /* m_new is finite here for every column that has seen a valid token; a column
-                 * with none yet keeps -inf and contributes exact zeros below */
-                const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref[k] - m_new);
-                l_run[k] *= alpha;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) acc_o[k][c] *= alpha;
-                m_ref[k] = m_new;
-            }
-            const float m_sub = m_ref[k] - kProbShift;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float p = (MASKED && s4[e] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s4[e] - m_sub);
-                l_run[k] += p;
-                _Float16 ph = (_Float16)p;
-                uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, ph);
-                pb[k].w[e] = bits << parity_shift;
-            }
-        }
-    }
-    H8 va[4];
-    value_operand<i, MASKED, DEEP>(tab, vcur, va, n_valid, g, t4b, dr, lane);
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-        for (int k = 0; k < NG; ++k)
-            acc_o[k][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[c].v, pb[k].v, acc_o[k][c], 0, 0, 0);
+    for (int d = 32; d >= 1; d >>= 1) x = fmaxf(x, __shfl_xor(x, d));
+    return x;
 }
 
 /* G query heads per kv head, M query tokens per sequence (a.M), NG column groups with
  * M * G <= 4 * NG.  Query token m of a sequence is its (M-1-m)-th newest token and sees
- * the cache up to and including its own key: ctx - (M-1-m) tokens. */
+ * the cache up to and including its own key: ctx - (M-1-m) tokens.
+ *
+ * Per 64-token tile: scores with one token per lane (key_scores), probabilities
+ * p = 2^(s - m + kProbShift) against an exponent reference m per pair that only moves when a score
+ * exceeds it by more than kRefSlack (wave-uniform test, rare after the first tile of a piece), the
+ * probabilities handed through LDS to the layout of the value contraction (lane (g, column) needs
+ * four consecutive tokens of one pair), then four passes of 16 tokens of weighted values on
+ * v_mfma_f32_16x16x32_f16.  The (cos, sin)-like pairs of a table entry are two coordinates of one
+ * token, while a matrix-core operand wants several tokens of one coordinate per lane; instead of
+ * transposing, the contraction index is widened to (token, parity): operand rows are coordinate
+ * pairs, and the probability operand has one column per (pair, parity) with zeros in the slots of
+ * the other parity.  The result accumulates o' for the even coordinates in the parity-0 columns and
+ * for the odd ones in parity 1. */
 template <int G, int NG, bool DEEP>
-__global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2)) void pq_attn_partial_kernel(AttnArgs a)
+__global__ __launch_bounds__(waves_per_block(NG) * 64, 1) void pq_attn_partial_kernel(AttnArgs a)
 {
-    __shared__ uint32_t tab[kTabDwords];
-    __shared__ float sKrad[DEEP ? kWavesPerBlock : 1][DEEP ? 512 : 1];
-    __shared__ uint16_t sVrad[DEEP ? kWavesPerBlock : 1][DEEP ? 512 : 2];
+    constexpr int kWavesPerBlock = waves_per_block(NG), kThreads = kWavesPerBlock * 64;
+    __shared__ __attribute__((aligned(16))) uint32_t tab[kLdsTabDwords];
+    /* probabilities of a tile: sP[wave][group][column = pair slot + 4 parity][token] as dwords; a parity-0 column
+       keeps its binary16 value in the low half, a parity-1 column in the high half, and the other halves stay
+       zero from the start of the kernel (nothing ever writes them) */
+    __shared__ __attribute__((aligned(16))) uint32_t sP[kWavesPerBlock][NG][8][64];
+    __shared__ __attribute__((aligned(16))) uint16_t sVrad[DEEP ? kWavesPerBlock : 1][DEEP ? 512 : 8];
     /* per-sequence data of batches of up to 64 sequences is staged in LDS with the tables, so that
        nothing between the barrier and the first tile request waits for global memory; its loads
-       are requested first (last wavefront of the workgroup, which has the least table work) */
+       are requested first (last wavefront of the workgroup) */
     __shared__ int sPre[65];
     __shared__ int sCtx[64];
     __shared__ int64_t sTile0[64];
@@ -636,17 +497,30 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
     const int total = a.plan[0], share = a.plan[1];
     int st_pre = 0, st_last = 0, st_len = 0;
     int64_t st_start = 0;
-    if (staged && threadIdx.x >= 192) {
-        const int bb = (int)threadIdx.x - 192;
+    constexpr int kStager = kThreads - 64; /* first thread of the last wavefront */
+    if (staged && threadIdx.x >= kStager) {
+        const int bb = (int)threadIdx.x - kStager;
         st_pre = a.plan[kPlanHeader + min(bb, a.B)];
         st_last = a.plan[kPlanHeader + a.B];
         st_len = a.ctx_len[min(bb, a.B - 1)];
         st_start = a.seq_start[min(bb, a.B - 1)];
     }
-#pragma unroll
-    for (int t = threadIdx.x; t < kTabDwords; t += kWavesPerBlock * 64) tab[t] = a.consts->attn_tab[t];
-    if (staged && threadIdx.x >= 192) {
-        const int bb = (int)threadIdx.x - 192;
+    {   /* tables: the image in global memory is compact (PQ_TAB_*); the small ones are spread over a column per lane */
+        const uint32_t *src = a.consts->attn_tab;
+        for (int t = threadIdx.x; t < 2048; t += kThreads) tab[kTQ + t] = src[PQ_TAB_TQ + t];
+        for (int t = threadIdx.x; t < 2048; t += kThreads) { /* entry t >> 5, column t & 31 */
+            tab[kTQA + t] = src[PQ_TAB_TQA + (t >> 5)];
+            tab[kTQB + t] = src[PQ_TAB_TQB + (t >> 5)];
+            tab[kTBH + t] = src[PQ_TAB_TBH + 2 * (t >> 5) + (t & 1)];
+        }
+        for (int t = threadIdx.x; t < 4096; t += kThreads) /* entry t >> 6, column (t >> 2) & 15, float t & 3 */
+            tab[kTBF + t] = src[PQ_TAB_TBF + 4 * (t >> 6) + (t & 3)];
+        if (threadIdx.x < 48) tab[kTUp + threadIdx.x] = src[PQ_TAB_UP + threadIdx.x];
+        uint4 *pz = reinterpret_cast<uint4 *>(&sP[0][0][0][0]);
+        for (int t = threadIdx.x; t < kWavesPerBlock * NG * 8 * 64 / 4; t += kThreads) pz[t] = make_uint4(0, 0, 0, 0);
+    }
+    if (staged && threadIdx.x >= kStager) {
+        const int bb = (int)threadIdx.x - kStager;
         sPre[bb] = st_pre;
         if (bb == 63) sPre[64] = st_last;
         sCtx[bb] = bb < a.B ? effective_ctx_of(st_len, st_start, a.max_ctx, a.pool_tiles) : 0;
@@ -704,9 +578,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
     }
     const int g = lane >> 4, n = lane & 15;
     constexpr int kRadiiHalves = DEEP ? PQ_DEEP_RADII_HALVES : PQL_RADII;
-    const DeepRadii dr{sKrad[DEEP ? wave : 0], sVrad[DEEP ? wave : 0], a.up_b5, a.up_b6, a.up_b7};
-    const uint32_t parity_shift = (n & 4) ? 16u : 0u;
-    const int t4b = kT4B + ((n & 1) ? 4 : 0);
+    const DeepRadii dr{sVrad[DEEP ? wave : 0], a.up_b5, a.up_b6, a.up_b7};
+    const char *tbh = reinterpret_cast<const char *>(tab + kTBH);
+    /* where this lane (token) leaves its probabilities and where it (column) picks its operand up */
+    uint32_t *p_mine = &sP[wave][0][0][lane];
+    const uint32_t *p_col = &sP[wave][0][n & 7][4 * g];
     /* rotated queries and partial results: the launch code keeps all three below 4 GB */
     const __amdgpu_buffer_rsrc_t q_rsrc = stream_descriptor(a.qrot, (uint32_t)a.B * a.M * a.Hq * (2 * PQ_D * 2u));
     const __amdgpu_buffer_rsrc_t o_rsrc = stream_descriptor(a.ws_o, (uint32_t)a.n_pieces * (a.M * G) * (PQ_D * 4u));
@@ -731,44 +607,127 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
         const __amdgpu_buffer_rsrc_t kr = stream_descriptor(a.k_radii + stream_tile0 * kRadiiHalves, radii_bytes);
         const __amdgpu_buffer_rsrc_t vr = stream_descriptor(a.v_radii + stream_tile0 * kRadiiHalves, radii_bytes);
 
-        /* ---- q' operands: in group k, columns n < 8 = (pair 4k + (n&3), parity (n>>2)&1) hold the
-         * leading binary16 part of q', columns n + 8 its binary16 remainder, so that q' enters the
-         * scores to ~22 bits at no extra matrix instruction; pair p = (query token p / G, head p % G);
-         * slice s = rotated coordinates 32*g + 8*s .. +8 ---- */
-        H8 qb[NG][4];
+        /* ---- q' operands (see QueryOperand); pair p = (query token p / G, head p % G) ---- */
+        QueryOperand<NG> qo;
         /* lane-dependent addresses of the piece's prologue and epilogue are formed from a copy of the lane
            number that the compiler cannot trace: hoisted out of the piece loop they would be spilled */
         int lane_q = lane;
         asm volatile("" : "+v"(lane_q));
 #pragma unroll
         for (int k = 0; k < NG; ++k) {
-            const int nq = lane_q & 15, gq = lane_q >> 4;
-            const int pair = 4 * k + (nq & 3);
+            const int slot = lane_q & 3, qi = lane_q >> 2;
+            const int pair = 4 * k + slot;
             const bool real = pair < a.M * G;
             const int m = real ? pair / G : 0, head = real ? pair % G : 0;
             /* 32-bit offsets into the rotated queries: lane part in bytes, (sequence, kv head) part scalar */
-            const uint32_t lane_off = (uint32_t)(((m * a.Hq + head) * 2 + (nq >> 3)) * PQ_D + 32 * gq) * 2u;
+            const uint32_t lane_off = (uint32_t)((m * a.Hq + head) * 2 * PQ_D + 4 * qi) * 2u;
             const uint32_t row_off = (uint32_t)((b * a.M * a.Hq + hk * G) * 2 * PQ_D) * 2u;
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-                qb[k][s].q = real ? load16(q_rsrc, lane_off + 16u * s, row_off) : make_uint4(0, 0, 0, 0);
+            for (int set = 0; set < 2; ++set)
+#pragma unroll
+                for (int part = 0; part < 2; ++part) {
+                    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(q_rsrc, lane_off + (uint32_t)(part * PQ_D + 64 * set) * 2u, row_off, 0);
+                    qo.a[k][set][part].w[0] = real ? v.x : 0u;
+                    qo.a[k][set][part].w[1] = real ? v.y : 0u;
+                }
         }
         f4 acc_o[NG][4];
-        float m_run[NG], l_run[NG];
+        /* exponent reference of a pair: the same in all lanes; l: this lane's share of the sum of its token's weights */
+        float m_ref[NG][4], l_run[NG][4];
 #pragma unroll
         for (int k = 0; k < NG; ++k) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) acc_o[k][c] = f4{0.f, 0.f, 0.f, 0.f};
-            m_run[k] = -INFINITY;
-            l_run[k] = 0.f;
+#pragma unroll
+            for (int h = 0; h < 4; ++h) { m_ref[k][h] = 0.f; l_run[k][h] = 0.f; }
         }
+        bool have_ref = false; /* m_ref is a place holder until the first tile of the piece has set it */
+
+        /* One tile.  MASKED: the tile holds tokens beyond the context, or beyond what one of the query
+         * tokens may see (lim[k][h]: tokens of this tile that pair 4 k + h sees; nv: tokens inside the context). */
+        auto do_tile = [&](auto masked_c, const KTileRaw &kraw, const VTileRaw &vraw, const int (&lim)[NG][4], int nv) {
+            constexpr bool MASKED = decltype(masked_c)::value;
+            float s[NG][4];
+#pragma unroll
+            for (int k = 0; k < NG; ++k)
+#pragma unroll
+                for (int h = 0; h < 4; ++h) s[k][h] = kProbShift - m_ref[k][h];
+            key_scores<NG, DEEP>(tab, kraw, qo, s, dr, lane); /* s = score - m_ref + kProbShift */
+            if (MASKED) {
+#pragma unroll
+                for (int k = 0; k < NG; ++k)
+#pragma unroll
+                    for (int h = 0; h < 4; ++h)
+                        if (lane >= lim[k][h]) s[k][h] = -INFINITY;
+            }
+            float top = s[0][0];
+#pragma unroll
+            for (int k = 0; k < NG; ++k)
+#pragma unroll
+                for (int h = 0; h < 4; ++h) top = fmaxf(top, s[k][h]);
+            if (!have_ref || __ballot(top > kProbShift + kRefSlack) != 0ull) { /* wave-uniform */
+#pragma unroll
+                for (int k = 0; k < NG; ++k) {
+                    float alpha_lane = 1.f; /* factor of this lane's output column (pair n & 3 of the group) */
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        const float smax = __builtin_amdgcn_readfirstlane(wave_max_f(s[k][h]));
+                        /* move the reference so that the largest weight of the tile is 2^kProbShift; a pair that has
+                           seen no token yet (smax == -inf) keeps its place holder */
+                        float delta = smax == -INFINITY ? 0.f : smax - kProbShift;
+                        if (have_ref) delta = fmaxf(delta, 0.f);
+                        const float alpha = have_ref ? __builtin_amdgcn_exp2f(-delta) : 1.f; /* nothing accumulated yet */
+                        m_ref[k][h] += delta;
+                        s[k][h] -= delta;
+                        l_run[k][h] *= alpha;
+                        if ((n & 3) == h) alpha_lane = alpha;
+                    }
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc_o[k][c] *= alpha_lane;
+                }
+                have_ref = true;
+            }
+            wave_lds_fence(); /* the passes of the previous tile have read their operands */
+#pragma unroll
+            for (int k = 0; k < NG; ++k) {
+                _Float16 ph[4];
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    const float p = __builtin_amdgcn_exp2f(s[k][h]); /* exp2(-inf) = 0 for masked tokens */
+                    l_run[k][h] += p;
+                    ph[h] = (_Float16)p;
+                }
+                _Float16 *dst = reinterpret_cast<_Float16 *>(p_mine + k * (8 * 64));
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    dst[2 * (h * 64)] = ph[h];                /* column (h, parity 0): low half */
+                    dst[2 * ((4 + h) * 64) + 1] = ph[h];      /* column (h, parity 1): high half */
+                }
+            }
+            if (DEEP) stage_deep_value_radii(tab, dr, vraw.top, lane);
+            wave_lds_fence();
+            auto pass = [&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                H8 va[4];
+                value_operand<i, MASKED, DEEP>(tab, tbh, vraw, va, nv, g, dr, lane);
+#pragma unroll
+                for (int k = 0; k < NG; ++k) {
+                    H8 pb;
+                    pb.q = *reinterpret_cast<const uint4 *>(p_col + k * (8 * 64) + 16 * i);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        acc_o[k][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[c].v, pb.v, acc_o[k][c], 0, 0, 0);
+                }
+            };
+            pass(std::integral_constant<int, 0>{}); pass(std::integral_constant<int, 1>{});
+            pass(std::integral_constant<int, 2>{}); pass(std::integral_constant<int, 3>{});
+        };
 
         /* Tiles tile_lo .. tile_hi-1.  A tile is full when every query token sees all of its 64
          * tokens; the tiles after that (the sequence's last one, or its last two when the M newest
          * tokens straddle a tile boundary) are masked per pair.
-         * The raw tile registers are single buffered: the next key tile is requested once the
-         * last pass has scored, the next value tile once it has been consumed; the other
-         * wavefronts resident on the SIMD cover the latency. */
+         * The raw tile registers are single buffered: the next tiles are requested once the
+         * last pass has consumed the current ones; the other wavefronts resident on the SIMD cover the latency. */
         const int n_full = min(tile_hi, max(ctx - (a.M - 1), 0) >> 6);
         KTileRaw kraw;
         VTileRaw vraw;
@@ -776,24 +735,18 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
         load_v_tile<DEEP>(vraw, vc, vr, tile_lo, lane);
         int tile = tile_lo;
         {
-            int lim[NG];
+            int lim[NG][4];
 #pragma unroll
-            for (int k = 0; k < NG; ++k) lim[k] = 64;
+            for (int k = 0; k < NG; ++k)
+#pragma unroll
+                for (int h = 0; h < 4; ++h) lim[k][h] = 64;
             for (; tile < n_full; ++tile) {
                 /* progress through the share, in quarters: the further along, the lower the priority */
                 if (gpos + (tile - tile_lo) >= next_drop) {
                     next_drop += quarter_tiles;
                     set_wave_priority(--prio);
                 }
-                if (DEEP) { /* the reads of the previous tile's radii precede these writes in program order */
-                    wave_lds_fence();
-                    expand_deep_radii(tab, dr, kraw.top, vraw.top, lane);
-                    wave_lds_fence();
-                }
-                attend_pass<0, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
-                attend_pass<1, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
-                attend_pass<2, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
-                attend_pass<3, false, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, 64, g, parity_shift, t4b, dr, lane);
+                do_tile(std::false_type{}, kraw, vraw, lim, 64);
                 if (tile + 1 < tile_hi) {
                     load_k_tile<DEEP>(kraw, kc, kr, tile + 1, lane);
                     load_v_tile<DEEP>(vraw, vc, vr, tile + 1, lane);
@@ -802,36 +755,35 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
         }
         for (; tile < tile_hi; ++tile) { /* the masked tiles at the end of the sequence */
             const int nv = min(ctx - tile * 64, 64);
-            int lim[NG]; /* tokens of this tile that this lane's pair of group k may see */
+            int lim[NG][4]; /* tokens of this tile that pair 4 k + h may see */
 #pragma unroll
-            for (int k = 0; k < NG; ++k) {
-                const int pair = 4 * k + (n & 3);
-                const int m = pair < a.M * G ? pair / G : 0;
-                lim[k] = ctx - (a.M - 1 - m) - tile * 64;
-            }
-            if (DEEP) {
-                wave_lds_fence();
-                expand_deep_radii(tab, dr, kraw.top, vraw.top, lane);
-                wave_lds_fence();
-            }
-            attend_pass<0, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
-            attend_pass<1, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
-            attend_pass<2, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
-            attend_pass<3, true, NG, DEEP>(tab, kraw, vraw, qb, acc_o, m_run, l_run, lim, nv, g, parity_shift, t4b, dr, lane);
+            for (int k = 0; k < NG; ++k)
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    const int pair = 4 * k + h;
+                    const int m = pair < a.M * G ? pair / G : 0;
+                    lim[k][h] = ctx - (a.M - 1 - m) - tile * 64;
+                }
+            do_tile(std::true_type{}, kraw, vraw, lim, nv);
             if (tile + 1 < tile_hi) {
                 load_k_tile<DEEP>(kraw, kc, kr, tile + 1, lane);
                 load_v_tile<DEEP>(vraw, vc, vr, tile + 1, lane);
             }
         }
 
-        /* ---- partial results: l summed over the four token groups; o' scattered to coordinate order ---- */
+        /* ---- partial results: l summed over the tokens (lanes); o' scattered to coordinate order ---- */
         int lane_e = lane;
         asm volatile("" : "+v"(lane_e));
 #pragma unroll
         for (int k = 0; k < NG; ++k) {
-            float l = l_run[k];
-            l += __shfl_xor(l, 16);
-            l += __shfl_xor(l, 32);
+            float l_pair[4];
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                float l = l_run[k][h];
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) l += __shfl_xor(l, d); /* the same order in every lane */
+                l_pair[h] = l;
+            }
             const int ne = lane_e & 15, ge = lane_e >> 4;
             const int pair = 4 * k + (ne & 3);
             if (ne < 8 && pair < a.M * G) {
@@ -846,9 +798,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, NG == 1 ? 4 : (NG == 2 ? 3 : 2
                         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc_o[k][c][e]), o_rsrc,
                                                               lane_o + 8u * (4 * e + c), piece_o, 0);
                 if (ge == 0 && par == 0) {
+                    const int h = ne & 3;
+                    const float mm = h == 0 ? m_ref[k][0] : (h == 1 ? m_ref[k][1] : (h == 2 ? m_ref[k][2] : m_ref[k][3]));
+                    const float ll = h == 0 ? l_pair[0] : (h == 1 ? l_pair[1] : (h == 2 ? l_pair[2] : l_pair[3]));
                     const uint32_t piece_ml = (uint32_t)piece * (uint32_t)(a.M * G) * 8u;
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(m_run[k]), ml_rsrc, pair * 8u, piece_ml, 0);
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(l), ml_rsrc, pair * 8u + 4u, piece_ml, 0);
+                    /* a pair that saw no token reports (-inf, 0), which the combine step drops */
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(ll > 0.f ? mm : -INFINITY), ml_rsrc, pair * 8u, piece_ml, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(ll), ml_rsrc, pair * 8u + 4u, piece_ml, 0);
                 }
             }
         }
@@ -889,7 +845,6 @@ __device__ __forceinline__ void rotate_query_rows(const RotateArgs &a, int row0,
     const int tid = threadIdx.x, r = tid >> 7, j = tid & 127;
     MatrixSlice ms;
     matrix_slice_load(ms, a.S, tid);
-    const float sigma = a.consts->sigma[j & 15]; /* requested with the slice, used after the last barrier */
     const int row = row0 + r;
     sq[r][j] = row < n_rows ? __uint_as_float((uint32_t)a.q[(int64_t)row * PQ_D + j] << 16) : 0.f;
     __syncthreads();
@@ -908,8 +863,7 @@ __device__ __forceinline__ void rotate_query_rows(const RotateArgs &a, int row0,
     __syncthreads();
     if (row < n_rows) {
         const float acc = ((spart[r][0][j] + spart[r][1][j]) + spart[r][2][j]) + spart[r][3][j];
-        /* rebuilt keys carry the table scale sigma of their coordinate: take it out here */
-        const float v = acc * a.scale / sigma;
+        const float v = acc * a.scale;
         const _Float16 h = (_Float16)v;
         const _Float16 rem = (_Float16)(v - (float)h);
         a.qrot[(int64_t)row * 2 * PQ_D + j] = __builtin_bit_cast(uint16_t, h);
@@ -1025,7 +979,7 @@ struct CombineArgs {
 
 /* HYBRID adds the partial results of the unquantised window.  They live in the original
  * domain, so they join after the un-rotation of the prefix sum:
- * out = (S^T-product of (sum_c w_c o'_c / sigma) + sum_w w_w o_w) / (sum of all w l). */
+ * out = (S^T-product of (sum_c w_c o'_c) + sum_w w_w o_w) / (sum of all w l). */
 template <bool HYBRID>
 __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
 {
@@ -1037,7 +991,6 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
     const int row = blockIdx.x;
     MatrixSlice ms; /* requested first: its latency overlaps the reads of the partial results */
     matrix_slice_load(ms, a.St, tid);
-    const float sigma = a.consts->sigma[j & 15];
     const int b = row / (a.M * a.Hq), mq = (row / a.Hq) % a.M, head = row % a.Hq;
     /* the pieces of this row's stream (sequence b, kv head hk): the wavefronts whose tile ranges
        meet the stream's, in order; their ids are consecutive.  A piece beyond what query token
@@ -1094,12 +1047,11 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
     if (tid < PQ_D) {
         const float ot = ((spart[0][j] + spart[1][j]) + spart[2][j]) + spart[3][j];
         lt = ((sl[0][j] + sl[1][j]) + sl[2][j]) + sl[3][j];
-        /* rebuilt values carry the table scale sigma of their coordinate */
         if (HYBRID) {
             owt = ((sw[0][j] + sw[1][j]) + sw[2][j]) + sw[3][j];
-            so[j] = ot / sigma;
+            so[j] = ot;
         } else {
-            so[j] = lt > 0.f ? ot / (lt * sigma) : 0.f; /* lt == 0: no visible token */
+            so[j] = lt > 0.f ? ot / lt : 0.f; /* lt == 0: no visible token */
         }
     }
     __syncthreads();
@@ -1297,8 +1249,9 @@ Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap = 0, int
     int64_t slots = 256 * 4 * per_simd;
     const int64_t most = ((int64_t)B * Hkv * max_tiles + kMinShareTiles - 1) / kMinShareTiles;
     if (slots > most) slots = most;
-    p.blocks = (unsigned)((slots + kWavesPerBlock - 1) / kWavesPerBlock);
-    p.slots = (int)(p.blocks * kWavesPerBlock);
+    const int block_waves = 4 * per_simd; /* = waves_per_block of the variant: one workgroup fills a CU */
+    p.blocks = (unsigned)((slots + block_waves - 1) / block_waves);
+    p.slots = (int)(p.blocks * block_waves);
     const size_t pieces = (size_t)p.slots + (size_t)B * Hkv; /* ids run below slots + streams */
     p.pieces = pieces;
     p.o_bytes = pieces * pairs * PQ_D * sizeof(float);
@@ -1458,7 +1411,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     aa.consts = ds->consts;
     aa.up_b5 = ctx->upper_bits[0]; aa.up_b6 = ctx->upper_bits[1]; aa.up_b7 = ctx->upper_bits[2];
     pq_prof_before(0, s);
-    const dim3 grid(p.blocks), blk(kWavesPerBlock * 64);
+    const dim3 grid(p.blocks), blk((unsigned)(waves_per_block(NG) * 64));
     if (G == 8) launch_partial<8>(NG, deep, grid, blk, s, aa);
     else if (G == 4) launch_partial<4>(NG, deep, grid, blk, s, aa);
     else if (G == 2) launch_partial<2>(NG, deep, grid, blk, s, aa);

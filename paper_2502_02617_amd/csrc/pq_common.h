@@ -13,6 +13,23 @@
 #include "../../include/polarquant.h"
 #include "pq_layout.h"
 
+/* Lookup tables of the attention kernels as the host builds them (dwords); the kernel spreads the small ones
+ * over a column per lane when it copies them into LDS.
+ *   TQ  [1024][2]: quarter table, by the stored quarter index Q = c1' << 6 | c2 << 4 | c1: the four binary16 products
+ *                  (cos t2 cos t1, cos t2 sin t1, sin t2 cos t1', sin t2 sin t1') -- the level-2 x level-1 part of
+ *                  the four coordinates of a quarter.  Values multiply an entry by the quarter's radius.
+ *   TQA [64]:      its first pair alone, by Q & 63 = c2 << 4 | c1; TQB [64]: its second pair, by Q >> 4 = c1' << 2 | c2.
+ *                  Keys fetch the two and use them as a matrix-core operand as they are.
+ *   TBF [64][4]:   block table for the keys, by the stored block index B = c4 << 4 | c3 << 2 | c3': the four fp32
+ *                  products (cos t4 cos t3, cos t4 sin t3, sin t4 cos t3', sin t4 sin t3') -- what the block radius
+ *                  is multiplied by to give the radii of its four quarters.
+ *   TBH [64][2]:   the same as binary16 pairs for the values: dword 0 the first half-block's two, dword 1 the second's.
+ *   UP  [3][8][2]: full-depth recursion: fp32 (cos, sin) of the centroids of levels 5, 6, 7. */
+enum {
+    PQ_TAB_TQ = 0, PQ_TAB_TQA = 2048, PQ_TAB_TQB = 2112, PQ_TAB_TBF = 2176, PQ_TAB_TBH = 2432, PQ_TAB_UP = 2560,
+    PQ_TAB_DWORDS = 2608
+};
+
 /* Constants every kernel reads; one copy per device in global memory. */
 struct PqDeviceConsts {
     /* Quantisation by comparison in the tangent domain (Algorithm 1, Quant):
@@ -23,22 +40,6 @@ struct PqDeviceConsts {
     /* cos / sin of the centroids, fp32 (DeQuant). */
     float cs1[16][2];
     float cs234[3][4][2];
-    /* Packed binary16 pairs (low half, high half) for the attention kernel. */
-    uint32_t t1_h2[16]; /* (cos, sin) of level-1 centroid c                        */
-    float t1_f32[16][2]; /* the same (scaled) pairs in fp32, for the key path        */
-    uint32_t t4_h2[4];  /* (cos, sin) of level-4 centroid c                        */
-    uint32_t ta_h2[16]; /* index (c2<<2 | c3): cos(th3[c3]) * (cos, sin)(th2[c2])  */
-    uint32_t tb_h2[16]; /* index (c3<<2 | c2): sin(th3[c3]) * (cos, sin)(th2[c2])  */
-    /* The level-2..4 tables once more in fp32 (same scaling), one array per half, for the
-       key path, whose radius chain runs in fp32: [0] the low halves, [1] the high halves. */
-    float ta_f32[2][16];
-    float tb_f32[2][16];
-    float t4_f32[2][4];
-    /* Every column of the binary16 tables is stored times a constant in [1, 2)
-       chosen so that its entries round to binary16 with the least error; a value
-       rebuilt with them for coordinate i of a block is sigma[i] times too large.
-       The query is divided by sigma before the scores, the output after the sum. */
-    float sigma[16];
     /* Codebooks other than the analytic ones (set with pq_set_codebooks): general != 0.
        Level 1 is then quantised through the pseudo-angle p(psi) in [0, 4) -- quadrant number
        plus |y| / (|x| + |y|) or |x| / (|x| + |y|), monotone in psi -- and a table over 512
@@ -55,27 +56,9 @@ struct PqDeviceConsts {
     int up_bits[3];
     float up_tan2[3][7];
     float up_cs[3][8][2];
-    /* The attention kernels' LDS table block, entry for entry (layout: PQ_TAB_* below), so that a
-       workgroup fills its LDS with one coalesced load per thread. */
-    uint32_t attn_tab[1152];
-};
-
-/* LDS table block of the attention kernels (dwords).  Binary16 pairs for the value path: T1 [0,16)
- * T4 [16,20)  TA [32,48)  TB [48,64); T4 broadcast per half: [64,68) cos, [68,72) sin as (f, f) pairs.
- * fp32 for the key path: T1 [96,128) as 16 (cos, sin) pairs, one pair per two banks;
- * TA [128,160), TB [160,192), T4 [192,200): the low halves of all entries, then the high
- * halves (two 16-entry dword tables, one entry per bank, read with one two-address load).
- * Full-depth recursion: (cos, sin) pairs of the centroids of levels 5, 6, 7, eight per level, from 208. */
-enum {
-    PQ_TAB_T1 = 0, PQ_TAB_T4 = 16, PQ_TAB_TA = 32, PQ_TAB_TB = 48, PQ_TAB_T4B = 64, PQ_TAB_T1F = 96,
-    PQ_TAB_TAF = 128, PQ_TAB_TBF = 160, PQ_TAB_T4F = 192, PQ_TAB_UP = 208,
-    /* level-3 x level-2 products by the 6-bit group g = [c2a | c3 | c2b] of a half-block: for the values 64 entries
-       (TA[g >> 2], TB[g & 15]) as two binary16 pairs, for the keys 64 entries of four fp32 (TA low, TA high, TB low,
-       TB high): one gather per half-block instead of two */
-    PQ_TAB_TG = 256, PQ_TAB_TGF = 384,
-    /* level 1 of the values by code pair: entry (code 2j+1 << 4 | code 2j), the byte as stored, holds the binary16
-       (cos, sin) pairs of both codes: one gather and one index extraction per two pairs */
-    PQ_TAB_T1B = 640, PQ_TAB_DWORDS = 1152
+    /* The attention kernels' LDS table block, entry for entry (layout: PQ_TAB_* above), copied by a
+       workgroup in 16-byte pieces. */
+    alignas(16) uint32_t attn_tab[PQ_TAB_DWORDS];
 };
 
 /* Radius plane of a tile.  Depth 4: 512 binary16 block radii (pq_layout.h).  Depth 7: 64 words,

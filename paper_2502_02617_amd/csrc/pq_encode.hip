@@ -81,68 +81,13 @@ union BOperand {
     uint32_t w[4];
 };
 
-/* Set `width` bits at bit offset `bit` (from the start of the image) to v.  The image is
- * shared by the lanes of one wavefront: LDS atomics keep concurrent updates of neighbouring
- * fields in one dword intact.  The second dword is always touched (with zeros when the field
- * does not straddle): no divergent branch, and every field that can straddle lies in the
- * G6 plane, whose following dword is still inside the image. */
-template <bool CLEAR, bool MAY_STRADDLE>
-__device__ __forceinline__ void put_bits(uint32_t *img, uint32_t bit, int width, uint32_t v)
-{
-    const uint32_t dw = bit >> 5, sh = bit & 31;
-    const uint64_t vv = (uint64_t)v << sh;
-    if (CLEAR) {
-        const uint64_t mm = (uint64_t)((1u << width) - 1u) << sh;
-        atomicAnd(&img[dw], ~(uint32_t)mm);
-        if (MAY_STRADDLE) atomicAnd(&img[dw + 1], ~(uint32_t)(mm >> 32));
-    }
-    atomicOr(&img[dw], (uint32_t)vv);
-    if (MAY_STRADDLE) atomicOr(&img[dw + 1], (uint32_t)(vv >> 32));
-}
-
-/* Scatter the fields of block b of slot tau into the tile image (codes, then radii). */
+/* Scatter the fields of block b of slot tau into the tile image (codes, then radii).  The image is shared by
+ * the lanes of one wavefront and the fields of different slots share dwords: LDS atomics. */
 template <int KIND, bool CLEAR, bool DEEP>
 __device__ __forceinline__ void emit_block(uint32_t *img, int tau, int b, const BlockCodes &bc)
 {
-    const PqBlockPos pos = pql_pos(KIND, tau, b);
-    uint16_t *img16 = reinterpret_cast<uint16_t *>(img);
-    if (KIND == PQ_KEY) {
-        /* the two L1 halves are one aligned dword, the two G6 groups 12 consecutive bits */
-        img[pos.l1_byte[0] >> 2] = bc.l1;
-        put_bits<CLEAR, true>(img, pos.g6_bit[0], 12, bc.g0 | (bc.g1 << 6));
-    } else {
-        img16[pos.l1_byte[0] >> 1] = (uint16_t)(bc.l1 & 0xFFFFu);
-        img16[pos.l1_byte[1] >> 1] = (uint16_t)(bc.l1 >> 16);
-        put_bits<CLEAR, true>(img, pos.g6_bit[0], 6, bc.g0);
-        put_bits<CLEAR, true>(img, pos.g6_bit[1], 6, bc.g1);
-    }
-    put_bits<CLEAR, false>(img, pos.c4_bit, 2, bc.c4); /* even bit offset: never straddles */
-    if (!DEEP) img16[PQL_CODE_BYTES / 2 + pos.radius_half] = bc.radius;
-}
-
-/* ---- full tiles: whole dwords assembled in registers, no atomics ----
- * In the bulk kernel lane (H, j) holds, at row tile st, block b = 4H + st of tokens
- * tau = j (v = 0) and 32 + j (v = 1).  The fields narrower than a dword that share
- * dwords with other tokens (G6, C4) are collected across lanes with DPP and one
- * lane-exchange, so that each dword of the image is written once by one lane. */
-__device__ __forceinline__ uint32_t quad_or(uint32_t x)
-{
-    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false);
-    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, false);
-    return x;
-}
-
-__device__ __forceinline__ uint32_t from_odd_even_neighbour(uint32_t x)
-{
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false);
-}
-
-/* For lanes of rows 0 and 2 (16-lane rows): the value held by the lane 16 further on; the lanes of
- * rows 1 and 3 get their own value back.  One row-swap instruction of the vector ALU instead of a
- * trip through the LDS crossbar. */
-__device__ __forceinline__ uint32_t from_next_row(uint32_t x)
-{
-    return __builtin_amdgcn_permlane16_swap(x, x, false, false)[1];
+    pql_put_block<CLEAR>(img, KIND, tau, b, bc);
+    if (!DEEP) reinterpret_cast<uint16_t *>(img)[PQL_CODE_BYTES / 2 + pql_pos(KIND, tau, b).radius_half] = bc.radius;
 }
 
 /* lanes 0..31: the value of lane + 32; lanes 32..63: the value of lane - 32 */
@@ -150,80 +95,6 @@ __device__ __forceinline__ uint32_t from_other_half(uint32_t x, int upper_half)
 {
     const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
     return upper_half ? r[0] : r[1];
-}
-
-/* four 24-bit chunks -> the three dwords of a lane's 96-bit G6 string */
-__device__ __forceinline__ void store_chunks96(uint32_t *dst, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3)
-{
-    dst[0] = (c0 & 0xFFFFFFu) | (c1 << 24);
-    dst[1] = ((c1 >> 8) & 0xFFFFu) | (c2 << 16);
-    dst[2] = ((c2 >> 16) & 0xFFu) | (c3 << 8);
-}
-
-/* Key tile, fields of two consecutive row tiles (blocks 2gk and 2gk+1 of the same
- * tokens): lane lambda = 16 gk + m of the tile owns chunk i of token 16 i + m;
- * here lane j holds chunks i = j>>4 (v = 0) and 2 + (j>>4) (v = 1). */
-struct KeyHeld { uint32_t g12[2], c4[2], rad[2]; };
-
-__device__ __forceinline__ void emit_key_l1(uint32_t *img, int j, int H, int st, int v, uint32_t l1)
-{
-    const int lam = 16 * (2 * H + (st >> 1)) + (j & 15);
-    img[((v ? PQL_OFF_L1B : PQL_OFF_L1A) + lam * 16 + (j >> 4) * 8 + (st & 1) * 4) >> 2] = l1;
-}
-
-template <bool DEEP>
-__device__ __forceinline__ void emit_key_pair(uint32_t *img, int j, int H, int st, const KeyHeld &even,
-                                              const BlockCodes (&odd)[2])
-{
-    const int lam = 16 * (2 * H + (st >> 1)) + (j & 15);
-    uint32_t P[2], Q[2];
-#pragma unroll
-    for (int v = 0; v < 2; ++v) {
-        const int i = 2 * v + (j >> 4);
-        if (!DEEP) img[PQL_CODE_BYTES / 4 + lam * 4 + i] = even.rad[v] | ((uint32_t)odd[v].radius << 16);
-        const uint32_t chunk = even.g12[v] | ((odd[v].g0 | (odd[v].g1 << 6)) << 12);
-        P[v] = chunk | ((even.c4[v] | (odd[v].c4 << 2)) << 24);
-        Q[v] = from_next_row(P[v]); /* used by the lanes of rows 0 and 2 only */
-    }
-    if ((j >> 4) == 0) { /* chunks 0 and 2 are this lane's, 1 and 3 the partner's */
-        store_chunks96(img + (PQL_OFF_G6 >> 2) + 3 * lam, P[0], Q[0], P[1], Q[1]);
-        reinterpret_cast<uint16_t *>(img)[(PQL_OFF_C4 >> 1) + lam] =
-            (uint16_t)((P[0] >> 24) | ((Q[0] >> 24) << 4) | ((P[1] >> 24) << 8) | ((Q[1] >> 24) << 12));
-    }
-}
-
-/* Value tile, one row tile: the 16 slots of a (token group g, block b) pair sit in the
- * quads of lanes 4g..4g+3 and 16+4g..16+4g+3, both halves v. */
-template <bool DEEP>
-__device__ __forceinline__ void emit_value_full(uint32_t *img, int j, int b, const BlockCodes (&bc)[2])
-{
-    const int g = (j >> 2) & 3, e = j & 3, jhi = j >> 4;
-    const int lam0 = 16 * g + 2 * b, gb = g * 8 + b;
-    uint32_t P0[2], P1[2], Q0[2], Q1[2];
-#pragma unroll
-    for (int v = 0; v < 2; ++v) {
-        const int s = 8 * v + 4 * jhi + e;
-        /* level-1 halves and radii: lanes e, e+1 (e even) fill one dword together */
-        const uint32_t nl1 = from_odd_even_neighbour(bc[v].l1);
-        const uint32_t nrad = from_odd_even_neighbour(bc[v].radius);
-        const int l1_base = ((v ? PQL_OFF_L1B : PQL_OFF_L1A) + (4 * jhi + (e & 2)) * 2) >> 2;
-        if ((e & 1) == 0) {
-            img[l1_base + lam0 * 4] = (bc[v].l1 & 0xFFFFu) | (nl1 << 16);
-            if (!DEEP) img[PQL_CODE_BYTES / 4 + ((gb * 16 + s) >> 1)] = (uint32_t)bc[v].radius | (nrad << 16);
-        } else {
-            img[l1_base + (lam0 + 1) * 4] = (nl1 >> 16) | (bc[v].l1 & 0xFFFF0000u);
-        }
-        P0[v] = quad_or((bc[v].g0 << (6 * e)) | (bc[v].c4 << (24 + 2 * e)));
-        P1[v] = quad_or(bc[v].g1 << (6 * e));
-        Q0[v] = from_next_row(P0[v]); /* used by the lanes of rows 0 and 2 only */
-        Q1[v] = from_next_row(P1[v]);
-    }
-    if (jhi == 0) { /* this quad holds chunks 0 and 2, the other one chunks 1 and 3 */
-        if (e == 0) store_chunks96(img + (PQL_OFF_G6 >> 2) + 3 * lam0, P0[0], Q0[0], P0[1], Q0[1]);
-        if (e == 1) store_chunks96(img + (PQL_OFF_G6 >> 2) + 3 * (lam0 + 1), P1[0], Q1[0], P1[1], Q1[1]);
-        if (e == 2)
-            img[(PQL_OFF_C4 >> 2) + gb] = (P0[0] >> 24) | ((Q0[0] >> 24) << 8) | ((P0[1] >> 24) << 16) | ((Q0[1] >> 24) << 24);
-    }
 }
 
 /* NTERMS = 3: S as three bf16 terms.  NTERMS = 1: every entry of S is +-1/sqrt(128), the
@@ -356,10 +227,8 @@ __device__ __forceinline__ void encode_tiles(const EncodeArgs &a, int block, int
         uint16_t *gradii = a.radii + ((int64_t)head * a.pool_tiles + tile) * kRadiiHalves;
 
         /* ---- tile image: zeros, or the tile's present contents if only part of it is written ---- */
-        constexpr bool kAssembled = (XT == PQ_BF16); /* full tiles written as whole dwords from registers */
         if (full) {
-            if (!kAssembled)
-                for (int c = lane; c < kImgDwords; c += 64) img[c] = 0u;
+            for (int c = lane; c < kImgDwords; c += 64) img[c] = 0u;
         } else {
             const uint32_t *gc = reinterpret_cast<const uint32_t *>(gcodes);
             const uint32_t *gr = reinterpret_cast<const uint32_t *>(gradii);
@@ -417,7 +286,6 @@ __device__ __forceinline__ void encode_tiles(const EncodeArgs &a, int block, int
                cores run while the vector ALU quantises.  Stage -1 only multiplies, stage 3 only
                quantises. */
             f32x16 acc_even[NVT], acc_odd[NVT];
-            KeyHeld held = {};
             float q4[NVT][4]; /* DEEP: squared radii of blocks 4H .. 4H+3 */
 #pragma unroll
             for (int st = -1; st < 4; ++st) {
@@ -484,28 +352,8 @@ __device__ __forceinline__ void encode_tiles(const EncodeArgs &a, int block, int
                        single vector's fields it would let the optimiser move that vector's whole
                        recursion behind the branch and undo the interleaving above.) */
                     if (full) {
-                        if constexpr (kAssembled && NVT == 2) {
-                            BlockCodes bc[2] = {ps[0].out, ps[1].out};
-                            if (KIND == PQ_KEY) {
 #pragma unroll
-                                for (int v = 0; v < 2; ++v) emit_key_l1(img, j, H, st, v, bc[v].l1);
-                                if ((st & 1) == 0) {
-#pragma unroll
-                                    for (int v = 0; v < 2; ++v) {
-                                        held.g12[v] = bc[v].g0 | (bc[v].g1 << 6);
-                                        held.c4[v] = bc[v].c4;
-                                        held.rad[v] = bc[v].radius;
-                                    }
-                                } else {
-                                    emit_key_pair<DEEP>(img, j, H, st, held, bc);
-                                }
-                            } else {
-                                emit_value_full<DEEP>(img, j, b, bc);
-                            }
-                        } else {
-#pragma unroll
-                            for (int v = 0; v < NVT; ++v) emit_block<KIND, false, DEEP>(img, tau[v], b, ps[v].out);
-                        }
+                        for (int v = 0; v < NVT; ++v) emit_block<KIND, false, DEEP>(img, tau[v], b, ps[v].out);
                     } else {
 #pragma unroll
                         for (int v = 0; v < NVT; ++v)

@@ -193,26 +193,6 @@ double from_binary16(uint16_t h)
     return (h & 0x8000) ? -v : v;
 }
 
-/* Scale in [1, 2) for which vals[0..n) * scale round to binary16 with the least
- * root-mean-square relative error.  The rounding errors of a lookup table are
- * the same for every token and do not average out in the attention sums; with
- * only 4..16 distinct magnitudes per column a good common scale removes most
- * of them at no run-time cost. */
-double best_table_scale(const double *vals, int n)
-{
-    double best_s = 1.0, best_e = 1e300;
-    for (int k = 0; k < 65536; ++k) {
-        double sc = 1.0 + k / 65536.0, e = 0.0;
-        for (int i = 0; i < n; ++i) {
-            double x = fabs(vals[i]) * sc;
-            double d = (from_binary16(to_binary16(x)) - x) / x;
-            e += d * d;
-        }
-        if (e < best_e) { best_e = e; best_s = sc; }
-    }
-    return best_s;
-}
-
 /* Monotone map of an angle in [0, 2 pi) to [0, 4): quadrant number plus the share of the
    second coordinate (even quadrants) or of the first (odd quadrants) in |x| + |y|. */
 double pseudo_angle(double psi)
@@ -275,84 +255,36 @@ void build_tables(pq_ctx *ctx)
             c.cs234[l - 2][k][0] = (float)cos(t);
             c.cs234[l - 2][k][1] = (float)sin(t);
         }
-    /* exact table columns: [0] low half, [1] high half of each packed pair */
-    double t1[2][16], t4[2][4], ta[2][16], tb[2][16];
-    for (int k = 0; k < 16; ++k) { t1[0][k] = cos(ctx->centroids[0][k]); t1[1][k] = sin(ctx->centroids[0][k]); }
-    for (int k = 0; k < 4; ++k) { t4[0][k] = cos(ctx->centroids[3][k]); t4[1][k] = sin(ctx->centroids[3][k]); }
-    for (int c2 = 0; c2 < 4; ++c2)
-        for (int c3 = 0; c3 < 4; ++c3) {
-            double th2 = ctx->centroids[1][c2], th3 = ctx->centroids[2][c3];
-            ta[0][(c2 << 2) | c3] = cos(th3) * cos(th2);
-            ta[1][(c2 << 2) | c3] = cos(th3) * sin(th2);
-            tb[0][(c3 << 2) | c2] = sin(th3) * cos(th2);
-            tb[1][(c3 << 2) | c2] = sin(th3) * sin(th2);
-        }
-    double s1[2], s4[2], sa[2], sb[2];
-    for (int col = 0; col < 2; ++col) {
-        s1[col] = best_table_scale(t1[col], 16);
-        s4[col] = best_table_scale(t4[col], 4);
-        sa[col] = best_table_scale(ta[col], 16);
-        sb[col] = best_table_scale(tb[col], 16);
-    }
-    for (int k = 0; k < 16; ++k) {
-        c.t1_h2[k] = pack_h2(t1[0][k] * s1[0], t1[1][k] * s1[1]);
-        c.t1_f32[k][0] = (float)(t1[0][k] * s1[0]);
-        c.t1_f32[k][1] = (float)(t1[1][k] * s1[1]);
-        c.ta_h2[k] = pack_h2(ta[0][k] * sa[0], ta[1][k] * sa[1]);
-        c.tb_h2[k] = pack_h2(tb[0][k] * sb[0], tb[1][k] * sb[1]);
-    }
-    for (int k = 0; k < 4; ++k) c.t4_h2[k] = pack_h2(t4[0][k] * s4[0], t4[1][k] * s4[1]);
-    for (int col = 0; col < 2; ++col) {
-        for (int k = 0; k < 16; ++k) {
-            c.ta_f32[col][k] = (float)(ta[col][k] * sa[col]);
-            c.tb_f32[col][k] = (float)(tb[col][k] * sb[col]);
-        }
-        for (int k = 0; k < 4; ++k) c.t4_f32[col][k] = (float)(t4[col][k] * s4[col]);
-    }
-    /* coordinate i of a block: half-block h = i>>3 (level-4 side), pair q = (i>>1)&3
-       (q < 2: table A, else table B; q&1: its low / high half), parity i&1 (level-1 cos / sin) */
-    for (int i = 0; i < 16; ++i) {
-        int h = i >> 3, q = (i >> 1) & 3, par = i & 1;
-        c.sigma[i] = (float)(s4[h] * (q < 2 ? sa[q & 1] : sb[q & 1]) * s1[par]);
-    }
-    /* the attention kernels' LDS image of the tables above */
+    /* The attention kernels' LDS image (layout: PQ_TAB_* in pq_common.h).  Entries are products of exact cosines and
+       sines formed in double precision and rounded once. */
     auto f2u = [](float f) { uint32_t u; memcpy(&u, &f, 4); return u; };
     for (int t = 0; t < PQ_TAB_DWORDS; ++t) c.attn_tab[t] = 0u;
-    for (int k = 0; k < 16; ++k) {
-        c.attn_tab[PQ_TAB_T1 + k] = c.t1_h2[k];
-        c.attn_tab[PQ_TAB_TA + k] = c.ta_h2[k];
-        c.attn_tab[PQ_TAB_TB + k] = c.tb_h2[k];
-        c.attn_tab[PQ_TAB_T1F + 2 * k] = f2u(c.t1_f32[k][0]);
-        c.attn_tab[PQ_TAB_T1F + 2 * k + 1] = f2u(c.t1_f32[k][1]);
-        for (int col = 0; col < 2; ++col) {
-            c.attn_tab[PQ_TAB_TAF + 16 * col + k] = f2u(c.ta_f32[col][k]);
-            c.attn_tab[PQ_TAB_TBF + 16 * col + k] = f2u(c.tb_f32[col][k]);
+    for (int q = 0; q < 1024; ++q) { /* Q = c1' << 6 | c2 << 4 | c1 */
+        const double t2 = ctx->centroids[1][(q >> 4) & 3], t1a = ctx->centroids[0][q & 15], t1b = ctx->centroids[0][q >> 6];
+        c.attn_tab[PQ_TAB_TQ + 2 * q] = pack_h2(cos(t2) * cos(t1a), cos(t2) * sin(t1a));
+        c.attn_tab[PQ_TAB_TQ + 2 * q + 1] = pack_h2(sin(t2) * cos(t1b), sin(t2) * sin(t1b));
+    }
+    for (int e = 0; e < 64; ++e) {
+        {   /* e = c2 << 4 | c1 */
+            const double t2 = ctx->centroids[1][e >> 4], t1 = ctx->centroids[0][e & 15];
+            c.attn_tab[PQ_TAB_TQA + e] = pack_h2(cos(t2) * cos(t1), cos(t2) * sin(t1));
+        }
+        {   /* e = c1' << 2 | c2 */
+            const double t2 = ctx->centroids[1][e & 3], t1 = ctx->centroids[0][e >> 2];
+            c.attn_tab[PQ_TAB_TQB + e] = pack_h2(sin(t2) * cos(t1), sin(t2) * sin(t1));
         }
     }
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t cs = c.t4_h2[k];
-        c.attn_tab[PQ_TAB_T4 + k] = cs;
-        c.attn_tab[PQ_TAB_T4B + k] = (cs & 0xFFFFu) * 0x10001u;
-        c.attn_tab[PQ_TAB_T4B + 4 + k] = (cs >> 16) * 0x10001u;
-        for (int col = 0; col < 2; ++col) c.attn_tab[PQ_TAB_T4F + 4 * col + k] = f2u(c.t4_f32[col][k]);
+    for (int b = 0; b < 64; ++b) {
+        const double t4 = ctx->centroids[3][b >> 4], t3a = ctx->centroids[2][(b >> 2) & 3], t3b = ctx->centroids[2][b & 3];
+        const double v[4] = {cos(t4) * cos(t3a), cos(t4) * sin(t3a), sin(t4) * cos(t3b), sin(t4) * sin(t3b)};
+        for (int j = 0; j < 4; ++j) c.attn_tab[PQ_TAB_TBF + 4 * b + j] = f2u((float)v[j]);
+        c.attn_tab[PQ_TAB_TBH + 2 * b] = pack_h2(v[0], v[1]);
+        c.attn_tab[PQ_TAB_TBH + 2 * b + 1] = pack_h2(v[2], v[3]);
     }
     if (ctx->depth == 7)
         for (int l = 0; l < 3; ++l)
             for (int k = 0; k < 8; ++k)
                 for (int h = 0; h < 2; ++h) c.attn_tab[PQ_TAB_UP + 16 * l + 2 * k + h] = f2u(c.up_cs[l][k][h]);
-    for (int b = 0; b < 256; ++b) {
-        c.attn_tab[PQ_TAB_T1B + 2 * b] = c.t1_h2[b & 15];
-        c.attn_tab[PQ_TAB_T1B + 2 * b + 1] = c.t1_h2[b >> 4];
-    }
-    for (int g = 0; g < 64; ++g) {
-        const int ia = g >> 2, ib = g & 15;
-        c.attn_tab[PQ_TAB_TG + 2 * g] = c.ta_h2[ia];
-        c.attn_tab[PQ_TAB_TG + 2 * g + 1] = c.tb_h2[ib];
-        c.attn_tab[PQ_TAB_TGF + 4 * g] = f2u(c.ta_f32[0][ia]);
-        c.attn_tab[PQ_TAB_TGF + 4 * g + 1] = f2u(c.ta_f32[1][ia]);
-        c.attn_tab[PQ_TAB_TGF + 4 * g + 2] = f2u(c.tb_f32[0][ib]);
-        c.attn_tab[PQ_TAB_TGF + 4 * g + 3] = f2u(c.tb_f32[1][ib]);
-    }
 }
 
 } // namespace

@@ -211,7 +211,7 @@ __device__ __forceinline__ BlockCodes polar_quant_block(const Y16 &y, const Thre
  * Too little work for the matrix cores: one workgroup per vector computes
  * y_j = sum_i x_i S[i][j] in fp32 (S read from L2, four partial sums per
  * coordinate added in a fixed order), the first wavefront then runs the polar recursion
- * (one lane per level-1 pair) and patches the fields into the tile in place.  Fields narrower than a byte share dwords with other
+ * (one lane per level-1 pair) and patches the fields into the tile in place.  Fields share dwords with other
  * slots of the tile, so they are updated with dword atomics. */
 struct AppendArgs {
     const void *x;
@@ -224,16 +224,49 @@ struct AppendArgs {
     const PqDeviceConsts *consts;
 };
 
-__device__ __forceinline__ void put_bits_global(uint8_t *codes, uint32_t bit, int width, uint32_t v)
+/* Sets `width` (<= 32) bits at bit offset `bit` of a layout string inside a tile's code bytes (global memory
+ * or an LDS image of the tile) to v.  Inside a plane the bytes of a string are contiguous, so a run of bits goes
+ * in with one update of the dword pair that holds it; a run ends where the string moves on to its next plane.
+ * Other lanes update neighbouring fields of the same dwords at the same time: dword atomics.
+ * CLEAR = false: the bits are known to be zero. */
+template <bool CLEAR>
+__device__ __forceinline__ void pql_put_bits(uint32_t *tile_dwords, PqString s, int bit, int width, uint32_t v)
 {
-    uint32_t *w = reinterpret_cast<uint32_t *>(codes) + (bit >> 5);
-    const uint32_t sh = bit & 31, mask = (1u << width) - 1u;
-    atomicAnd(w, ~(mask << sh));
-    atomicOr(w, v << sh);
-    if (sh + width > 32) {
-        const uint32_t done = 32 - sh;
-        atomicAnd(w + 1, ~(mask >> done));
-        atomicOr(w + 1, v >> done);
+    while (width > 0) {
+        const int k = bit >> 3;
+        const int run = min(width, 8 * pql_string_run_end(s, k) - bit); /* bits that are contiguous in the tile */
+        const uint32_t at_bit = 8u * pql_string_byte(s, k) + (uint32_t)(bit & 7);
+        const uint32_t dw = at_bit >> 5, sh = at_bit & 31u;
+        const uint64_t mask = (run >= 32 ? 0xFFFFFFFFull : ((1ull << run) - 1ull)) << sh;
+        const uint64_t val = ((uint64_t)v << sh) & mask;
+        if (CLEAR) atomicAnd(&tile_dwords[dw], ~(uint32_t)mask);
+        atomicOr(&tile_dwords[dw], (uint32_t)val);
+        if (mask >> 32) {
+            if (CLEAR) atomicAnd(&tile_dwords[dw + 1], ~(uint32_t)(mask >> 32));
+            atomicOr(&tile_dwords[dw + 1], (uint32_t)(val >> 32));
+        }
+        v = run >= 32 ? 0u : v >> run;
+        bit += run;
+        width -= run;
+    }
+}
+
+/* all code fields of block b of slot tau (not the radius) */
+template <bool CLEAR>
+__device__ __forceinline__ void pql_put_block(uint32_t *tile_dwords, int kind, int tau, int b, const BlockCodes &bc)
+{
+    const PqBlockPos pos = pql_pos(kind, tau, b);
+    PqBlockFields f;
+    f.l1 = bc.l1; f.g6[0] = bc.g0; f.g6[1] = bc.g1; f.c4 = bc.c4; f.radius = bc.radius;
+    const uint32_t q0 = pql_quarter_index(f, 0), q1 = pql_quarter_index(f, 1), q2 = pql_quarter_index(f, 2),
+                   q3 = pql_quarter_index(f, 3), bi = pql_block_index(f);
+    if (kind == 0) { /* one run of 46 bits: Q_0 | Q_1 << 10 | Q_2 << 20 | Q_3 << 30 | B << 40 */
+        pql_put_bits<CLEAR>(tile_dwords, pos.b_str, pos.q_bit[0], 32, q0 | (q1 << 10) | (q2 << 20) | (q3 << 30));
+        pql_put_bits<CLEAR>(tile_dwords, pos.b_str, pos.q_bit[0] + 32, 14, (q3 >> 2) | (bi << 8));
+    } else {  /* two slots of 20 bits and the block index */
+        pql_put_bits<CLEAR>(tile_dwords, pos.q_str[0], pos.q_bit[0], 20, q0 | (q1 << 10));
+        pql_put_bits<CLEAR>(tile_dwords, pos.q_str[1], pos.q_bit[2], 20, q2 | (q3 << 10));
+        pql_put_bits<CLEAR>(tile_dwords, pos.b_str, pos.b_bit, 6, bi);
     }
 }
 
@@ -306,14 +339,9 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
         bc.g1 = (gw >> 8) & 63u;
         if (i == 0) {
             uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
-            PqBlockPos pos = pql_pos(kind, tau, b);
-            *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[0]) = (uint16_t)(bc.l1 & 0xFFFFu);
-            *reinterpret_cast<uint16_t *>(gcodes + pos.l1_byte[1]) = (uint16_t)(bc.l1 >> 16);
-            put_bits_global(gcodes, pos.g6_bit[0], 6, bc.g0);
-            put_bits_global(gcodes, pos.g6_bit[1], 6, bc.g1);
-            put_bits_global(gcodes, pos.c4_bit, 2, bc.c4);
+            pql_put_block<true>(reinterpret_cast<uint32_t *>(gcodes), kind, tau, b, bc);
             if (deep) sq4[b] = bc.q4;
-            else a.radii[((int64_t)head * a.pool_tiles + tile) * PQL_RADII + pos.radius_half] = bc.radius;
+            else a.radii[((int64_t)head * a.pool_tiles + tile) * PQL_RADII + pql_pos(kind, tau, b).radius_half] = bc.radius;
         }
     }
     if (deep) { /* levels 5..7 over the eight block radii: one thread, one whole word of the radius plane */

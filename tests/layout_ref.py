@@ -1,75 +1,144 @@
-"""Numpy reading of the tile layout, written from its specification (not from the kernels).
+"""Numpy reading and writing of the tile layout, written from its specification (the comment at
+the top of paper_2502_02617_amd/csrc/pq_layout.h), not from the kernels.
 
-``tiles_to_canonical`` turns the codes / radii tiles of one head plane into
-canonical 62-byte records, so that what the encode kernel stores can be
-compared byte for byte with the oracle's records without going through the
-library's own export kernel.
+``tiles_to_canonical`` turns the codes / radii tiles of one head plane into canonical 62-byte
+records, so that what the encode kernel stores can be compared byte for byte with the oracle's
+records without going through the library's own export kernel.  ``canonical_to_tiles`` is its
+inverse: it lays canonical records (the oracle's) out as tiles, so that the attention kernels can
+be run on a cache that no library kernel has written.
+
+Specification, restated.  A block of 16 coordinates has four 10-bit quarter indices
+Q_j = c1_{2j+1} << 6 | c2_j << 4 | c1_{2j}, one 6-bit block index B = c4 << 4 | c3_0 << 2 | c3_1 and a
+binary16 radius.  Bit strings are little endian.
+  key tile:   token tau owns a 368-bit string, block b at bit 46 b: Q_0 | Q_1 << 10 | Q_2 << 20 | Q_3 << 30 |
+              B << 40; string bytes 0..15 at tile byte 16 tau, 16..31 at 1024 + 16 tau, 32..43 at
+              2048 + 12 tau, 44..45 at 2816 + 2 tau; radius of block b at half 8 tau + b.
+  value tile: token tau = 16 i + 4 g + e is slot s = 4 i + e of the lanes 16 g + 2 b + h (h = 0, 1: the halves
+              of block b); lane lam owns a 320-bit string, slot s at bit 20 s: Q_{2h} | Q_{2h+1} << 10; string
+              bytes 0..15 at tile byte 16 lam, 16..31 at 1024 + 16 lam, 32..39 at 2048 + 8 lam; the block
+              indices of (g, b) are a 96-bit string at tile byte 2560 + 12 (8 g + b), slot s at bit 6 s; radius
+              of slot s of (g, b) at half 16 (8 g + b) + s.
 """
 import numpy as np
 
-OFF_L1A, OFF_L1B, OFF_G6, OFF_C4 = 0, 1024, 2048, 2816
 CODE_BYTES, RADII = 2944, 512
+KEY, VALUE_Q, VALUE_B = 0, 1, 2
 
 
-def _bits(buf, bit, width):
-    """buf: uint8 [..., nbytes]; little-endian bit string; returns the field as int."""
-    byte, sh = bit // 8, bit % 8
-    v = buf[..., byte].astype(np.uint32) | (buf[..., byte + 1].astype(np.uint32) << 8)
-    return (v >> sh) & ((1 << width) - 1)
+def string_byte(stype, owner, k):
+    """tile byte holding byte k of a string"""
+    if stype == VALUE_B:
+        return 2560 + 12 * owner + k
+    if k < 16:
+        return 16 * owner + k
+    if k < 32:
+        return 1024 + 16 * owner + (k - 16)
+    if stype == KEY:
+        return 2048 + 12 * owner + (k - 32) if k < 44 else 2816 + 2 * owner + (k - 44)
+    return 2048 + 8 * owner + (k - 32)
 
 
-def block_fields(kind, codes, radii, tau, b):
-    """codes: uint8 [T, 2944], radii: uint16 [T, 512] -> (l1 32-bit, g6[2], c4, radius) arrays over tiles."""
-    i = tau >> 4
-    if kind == 0:  # key tile: lane = 16*quarter + (tau mod 16), chunk i
-        m, gk, beta = tau & 15, b >> 1, b & 1
-        lam = 16 * gk + m
-        l1_at = (OFF_L1A if i < 2 else OFF_L1B) + lam * 16 + (i & 1) * 8 + beta * 4
-        l1 = codes[:, l1_at : l1_at + 4].copy().view(np.uint32)[:, 0]
-        gbit = (OFF_G6 + lam * 12) * 8 + 24 * i + 12 * beta
-        g6 = [_bits(codes, gbit, 6), _bits(codes, gbit + 6, 6)]
-        c4 = _bits(codes, (OFF_C4 + lam * 2) * 8 + 4 * i + 2 * beta, 2)
-        rad = radii[:, lam * 8 + 2 * i + beta]
-    else:  # value tile: lane = 16*g + half-block, slot s
-        g, e = (tau >> 2) & 3, tau & 3
-        s = 4 * i + e
-        halves, g6 = [], []
-        for h in range(2):
-            lam = 16 * g + 2 * b + h
-            at = (OFF_L1A if s < 8 else OFF_L1B) + lam * 16 + (s & 7) * 2
-            halves.append(codes[:, at].astype(np.uint32) | (codes[:, at + 1].astype(np.uint32) << 8))
-            g6.append(_bits(codes, (OFF_G6 + lam * 12) * 8 + 6 * s, 6))
-        l1 = halves[0] | (halves[1] << 16)
-        c4 = _bits(codes, (OFF_C4 + (g * 8 + b) * 4) * 8 + 2 * s, 2)
-        rad = radii[:, (g * 8 + b) * 16 + s]
-    return l1, g6, c4, rad
+def get_bits(codes, stype, owner, bit, width):
+    """codes uint8 [T, 2944] -> the field (width <= 16) as uint32 [T]; the bytes of a string are looked up one by one"""
+    first, sh = divmod(bit, 8)
+    v = np.zeros(codes.shape[0], dtype=np.uint32)
+    for n in range((sh + width + 7) // 8):
+        v |= codes[:, string_byte(stype, owner, first + n)].astype(np.uint32) << np.uint32(8 * n)
+    return (v >> np.uint32(sh)) & np.uint32((1 << width) - 1)
+
+
+def put_bits(codes, stype, owner, bit, width, value):
+    """writes value (uint32 [T], width <= 16) into codes uint8 [T, 2944], byte piece by byte piece"""
+    first, sh = divmod(bit, 8)
+    v = (value.astype(np.uint32) & np.uint32((1 << width) - 1)) << np.uint32(sh)
+    m = ((1 << width) - 1) << sh
+    for n in range((sh + width + 7) // 8):
+        at = string_byte(stype, owner, first + n)
+        keep = 0xFF ^ ((m >> (8 * n)) & 0xFF)
+        codes[:, at] = (codes[:, at] & np.uint8(keep)) | ((v >> np.uint32(8 * n)) & np.uint32(0xFF)).astype(np.uint8)
+
+
+def block_places(kind, tau, b):
+    """-> ([(stype, owner, bit) of Q_0..Q_3], (stype, owner, bit) of B, radius half)"""
+    if kind == 0:
+        return [(KEY, tau, 46 * b + 10 * j) for j in range(4)], (KEY, tau, 46 * b + 40), 8 * tau + b
+    i, g, e = tau >> 4, (tau >> 2) & 3, tau & 3
+    s = 4 * i + e
+    q = [(VALUE_Q, 16 * g + 2 * b + (j >> 1), 20 * s + 10 * (j & 1)) for j in range(4)]
+    return q, (VALUE_B, 8 * g + b, 6 * s), 16 * (8 * g + b) + s
+
+
+def _codes_of_tile_fields(Q, B):
+    """Q [T, 4], B [T] -> (c1 [T, 8], c2 [T, 4], c3 [T, 2], c4 [T])"""
+    c1 = np.stack([(Q[:, p >> 1] >> (6 * (p & 1))) & 15 for p in range(8)], axis=1)
+    c2 = (Q >> 4) & 3
+    c3 = np.stack([(B >> 2) & 3, B & 3], axis=1)
+    return c1, c2, c3, B >> 4
 
 
 def tiles_to_canonical(kind, codes, radii, n_tokens):
     """codes uint8 [T, 2944], radii uint16 [T, 512] of one head plane -> records uint8 [n_tokens, 62]."""
     codes = np.ascontiguousarray(codes)
-    # one spare byte so that 2-byte windows at the very end stay in range
-    codes = np.concatenate([codes, np.zeros((codes.shape[0], 2), np.uint8)], axis=1)
     radii = np.ascontiguousarray(radii).view(np.uint16)
     T = codes.shape[0]
     rec = np.zeros((T, 64, 62), dtype=np.uint8)
     for tau in range(64):
         for b in range(8):
-            l1, g6, c4, rad = block_fields(kind, codes, radii, tau, b)
+            qp, bp, rh = block_places(kind, tau, b)
+            Q = np.stack([get_bits(codes, *p, 10) for p in qp], axis=1)
+            B = get_bits(codes, *bp, 6)
+            c1, c2, c3, c4 = _codes_of_tile_fields(Q, B)
             for k in range(4):
-                even = (l1 >> (8 * k)) & 15
-                odd = (l1 >> (8 * k + 4)) & 15
-                rec[:, tau, 4 * b + k] = (even << 4) | odd
-            c2 = [g6[0] >> 4, g6[0] & 3, g6[1] >> 4, g6[1] & 3]
-            rec[:, tau, 32 + b] = (c2[0] << 6) | (c2[1] << 4) | (c2[2] << 2) | c2[3]
-            c3 = [(g6[0] >> 2) & 3, (g6[1] >> 2) & 3]
+                rec[:, tau, 4 * b + k] = (c1[:, 2 * k] << 4) | c1[:, 2 * k + 1]
+            rec[:, tau, 32 + b] = (c2[:, 0] << 6) | (c2[:, 1] << 4) | (c2[:, 2] << 2) | c2[:, 3]
             for h in range(2):
                 j = 2 * b + h
-                rec[:, tau, 40 + j // 4] |= (c3[h] << (6 - 2 * (j & 3))).astype(np.uint8)
+                rec[:, tau, 40 + j // 4] |= (c3[:, h] << (6 - 2 * (j & 3))).astype(np.uint8)
             rec[:, tau, 44 + b // 4] |= (c4 << (6 - 2 * (b & 3))).astype(np.uint8)
+            rad = radii[:, rh]
             rec[:, tau, 46 + 2 * b] = rad & 0xFF
             rec[:, tau, 47 + 2 * b] = rad >> 8
     return rec.reshape(T * 64, 62)[:n_tokens]
+
+
+def _record_codes(rec):
+    """rec uint8 [n, >=46] -> (c1 [n, 64], c2 [n, 32], c3 [n, 16], c4 [n, 8]) in coordinate order"""
+    r = rec.astype(np.uint32)
+    c1 = np.stack([r[:, :32] >> 4, r[:, :32] & 15], axis=2).reshape(-1, 64)
+    four = lambda x: np.stack([(x >> 6) & 3, (x >> 4) & 3, (x >> 2) & 3, x & 3], axis=2).reshape(x.shape[0], -1)
+    return c1, four(r[:, 32:40]), four(r[:, 40:44]), four(r[:, 44:46])
+
+
+def canonical_to_tiles(kind, rec, n_tiles=None, fill=0):
+    """rec uint8 [n, 62] (slots 0..n-1 of one head plane) -> (codes uint8 [T, 2944], radii uint16 [T, 512]).
+    Slots beyond n keep `fill` in every code byte and radius."""
+    n = rec.shape[0]
+    T = (n + 63) // 64 if n_tiles is None else n_tiles
+    assert T * 64 >= n
+    full = np.zeros((T * 64, 62), dtype=np.uint8)
+    full[:n] = rec
+    c1, c2, c3, c4 = _record_codes(full)
+    rad = full[:, 46:62].astype(np.uint16)
+    rad = (rad[:, 0::2] | (rad[:, 1::2] << 8)).reshape(T, 64, 8)
+    c1, c2, c3, c4 = c1.reshape(T, 64, 64), c2.reshape(T, 64, 32), c3.reshape(T, 64, 16), c4.reshape(T, 64, 8)
+    codes = np.full((T, CODE_BYTES), fill & 0xFF, dtype=np.uint8)
+    radii = np.full((T, RADII), (fill & 0xFF) * 0x0101, dtype=np.uint16)
+    for tau in range(64):
+        # which tiles actually hold slot tau
+        live = (np.arange(T) * 64 + tau) < n
+        if not live.any():
+            continue
+        sub = codes[live]
+        for b in range(8):
+            qp, bp, rh = block_places(kind, tau, b)
+            for j in range(4):
+                Q = (c1[live, tau, 8 * b + 2 * j + 1] << 6) | (c2[live, tau, 4 * b + j] << 4) | c1[live, tau, 8 * b + 2 * j]
+                put_bits(sub, *qp[j], 10, Q)
+            B = (c4[live, tau, b] << 4) | (c3[live, tau, 2 * b] << 2) | c3[live, tau, 2 * b + 1]
+            put_bits(sub, *bp, 6, B)
+            radii[live, rh] = rad[live, tau, b]
+        codes[live] = sub
+    return codes, radii
 
 
 def tiles_to_canonical_deep(kind, codes, top, n_tokens):
@@ -86,3 +155,17 @@ def tiles_to_canonical_deep(kind, codes, top, n_tokens):
     rec[:, :, 48] = words[:, :, 1] & 0xFF
     rec[:, :, 49] = words[:, :, 1] >> 8
     return rec.reshape(T * 64, 50)[:n_tokens]
+
+
+def canonical_to_tiles_deep(kind, rec, n_tiles=None, fill=0):
+    """rec uint8 [n, 50] -> (codes uint8 [T, 2944], top uint16 [T, 128]): the inverse of tiles_to_canonical_deep."""
+    n = rec.shape[0]
+    T = (n + 63) // 64 if n_tiles is None else n_tiles
+    wide = np.zeros((n, 62), dtype=np.uint8)
+    wide[:, :46] = rec[:, :46]
+    codes, _ = canonical_to_tiles(kind, wide, T, fill)
+    top = np.full((T * 64, 2), (fill & 0xFF) * 0x0101, dtype=np.uint16)
+    r = rec.astype(np.uint16)
+    top[:n, 0] = r[:, 46] | (r[:, 47] << 8)
+    top[:n, 1] = r[:, 48] | (r[:, 49] << 8)
+    return codes, top.reshape(T, 128)
