@@ -16,8 +16,17 @@
  *     memory.  The library allocates device memory only for the constants of
  *     a pq_ctx (< 1 MB per device, on the first call that uses that device).
  *   - Kernels are enqueued on the caller's hipStream_t (passed as void*; NULL
- *     is the default stream).  The library never synchronises the stream.
- *   - A pq_ctx is immutable after creation and may be shared by threads.
+ *     is the default stream).  The library does not synchronise the stream and
+ *     records no memset or copy nodes, so its calls can be captured into a HIP
+ *     graph -- with one exception, stated where it is declared:
+ *     pq_fit_codebooks(_deep) copy their histograms to the host and wait.
+ *   - A pq_ctx is configured (pq_set_codebooks, pq_set_recursion_depth,
+ *     pq_set_upper_codebooks) before its first launch; from then on it is
+ *     immutable and may be shared by threads.
+ *   - Block norms: the stored radius is a binary16 number; a block whose norm
+ *     exceeds the format's range is stored with the largest finite radius,
+ *     65504 (its direction is kept).  Everything computed from a cache of finite
+ *     inputs is finite.
  *
  * Cache layout ("tiles")
  *   A cache holds keys or values of n_heads head planes.  Each plane is an
@@ -82,8 +91,10 @@ const char *pq_status_string(pq_status s);
  * verbatim after checking ||S^T S - I||_max <= 1e-10 (PQ_EINVAL otherwise);
  * if NULL, S is generated on the host in double precision from `seed`:
  * a Gaussian matrix from a counter-based generator (splitmix64 finaliser +
- * Box-Muller), Householder QR, columns sign-fixed so that R has a positive
- * diagonal.  Codebooks are computed on the host in double precision.
+ * Box-Muller), whose columns are orthonormalised in order (modified
+ * Gram-Schmidt, every projection pass done twice): the Q factor of its QR
+ * factorisation with a positive diagonal of R.  Codebooks are computed on the
+ * host in double precision.
  * No device is touched; *out receives the context (caller frees it with
  * pq_destroy).
  * ------------------------------------------------------------------------- */
@@ -98,7 +109,6 @@ pq_status pq_init_preconditioner(pq_ctx **out, int d, uint64_t seed, const doubl
  * whose entries all have that magnitude takes the same path. */
 pq_status pq_init_preconditioner_hadamard(pq_ctx **out, int d, uint64_t seed);
 
-/* Copies S (d*d doubles, row-major) to host memory S_out. */
 /* Replaces the codebooks of a context that has not launched anything yet (PQ_EINVAL
  * afterwards: the tables are already on a device) -- the place where codebooks fitted
  * to a prompt's own angles (Section 4.1, online variant) come in, and with S = I the
@@ -120,12 +130,29 @@ pq_status pq_set_codebooks(pq_ctx *ctx, const double *cb);
  * centroids; NULL: the context's current codebooks).  The paper seeds k-means++ at
  * random; a fixed seed codebook makes the result a function of the data.  cb_out
  * (host): 28 centroids, ready for pq_set_codebooks on a fresh context.  workspace
- * (device): pq_fit_workspace_bytes() bytes.  The call waits for the stream.
- * PQ_EUNSUPPORTED beyond 2^26 vectors per call. */
+ * (device): pq_fit_workspace_bytes() bytes.  This call copies the histograms
+ * to the host and WAITS for the stream (it cannot be captured into a graph);
+ * pq_fit_count_angles and pq_fit_cluster below are its two halves for callers
+ * that place the wait themselves.  x, ld_token, ld_head aligned as for
+ * pq_encode_kv (PQ_EALIGN).  PQ_EUNSUPPORTED beyond 2^26 vectors per call. */
 pq_status pq_fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
                            int64_t ld_token, int64_t ld_head, const double *cb_init, int iterations,
                            double *cb_out, void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t pq_fit_workspace_bytes(void);
+
+/* The two halves of pq_fit_codebooks(_deep).
+ * pq_fit_count_angles: clears the histograms in workspace (device) with a kernel of
+ * its own and counts the angles of x into them (for a depth-7 context also those of
+ * levels 5..7); enqueued on the stream, returns at once, no memset or copy nodes.
+ * pq_fit_cluster: host only; hist (host) is a copy of those pq_fit_workspace_bytes()
+ * bytes, taken after the stream has reached that point; the k-means rounds of Section
+ * 4.1 on the bins from cb_init / cbt_init (NULL: the context's codebooks) ->
+ * cb_out (28), cbt_out ([3][8]; required for a depth-7 context, ignored otherwise). */
+pq_status pq_fit_count_angles(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
+                              int64_t ld_token, int64_t ld_head, void *workspace, size_t workspace_bytes,
+                              void *hip_stream);
+pq_status pq_fit_cluster(const pq_ctx *ctx, const uint32_t *hist, const double *cb_init, const double *cbt_init,
+                         int iterations, double *cb_out, double *cbt_out);
 
 /* The same for a depth-7 context (PQ_EINVAL otherwise): the angles of levels 5, 6, 7 -- 4 + 2 + 1
  * per vector, formed from the 8 block radii -- are counted as well ((pi/2) / 2048 bins) and
@@ -171,6 +198,7 @@ int pq_record_bytes(const pq_ctx *ctx);
  * centroids, 2^bits + 1 boundaries; any output may be NULL. */
 pq_status pq_get_upper_codebook(const pq_ctx *ctx, int level, int *bits, double *centroids, double *boundaries);
 
+/* Copies S (d*d doubles, row-major, S[i][j] at i*d+j) to host memory S_out. */
 pq_status pq_get_preconditioner(const pq_ctx *ctx, double *S_out);
 
 /* level in 1..4.  centroids: K doubles (K = 16 for level 1, 4 otherwise);

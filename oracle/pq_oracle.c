@@ -33,6 +33,7 @@
 #define ORC_D 128            /* head dimension of Section 4.1's example   */
 #define ORC_L 4              /* recursion depth L = 4 (Section 4.1)       */
 #define ORC_BLOCK 16         /* 2^L coordinates share one stored radius   */
+#define ORC_F16_MAX 65504.0  /* largest finite binary16: stored radii saturate there */
 #define ORC_NBLK (ORC_D / ORC_BLOCK)
 #define ORC_REC 62           /* 46 code bytes + 8 half radii per vector   */
 #define ORC_NANG 120         /* 64 + 32 + 16 + 8 angles per vector        */
@@ -419,7 +420,10 @@ void orc_encode(const double *x, int64_t n, const double *S, const double *cb,
                 J[off + j] = orc_quant(psi[off + j], cb + orc_cb_off[l], orc_cb_K[l]);
             off += cnt; cnt /= 2;
         }
-        for (int b = 0; b < ORC_NBLK; ++b) rad[b] = orc_f64_to_f16(rblk[b]);
+        /* b_FPN = 16 (Section 4.1): binary16.  The paper is silent on radii beyond the format's range; reading:
+           the stored radius saturates at the largest finite binary16 value, so that a block of extreme norm
+           keeps its direction and stays finite instead of turning into infinity. */
+        for (int b = 0; b < ORC_NBLK; ++b) rad[b] = orc_f64_to_f16(fmin(rblk[b], ORC_F16_MAX));
         if (rec) orc_pack_record(J, rad, rec + i * ORC_REC);
         if (psi_out) memcpy(psi_out + i * ORC_NANG, psi, sizeof(psi));
         if (y_out) memcpy(y_out + i * ORC_D, y, sizeof(y));
@@ -647,17 +651,6 @@ void orc_attention_exact(const double *q, const double *K, const double *V,
 }
 
 /* ------------------------------------------------------------------ */
-/* Online codebook (Section 4.1: 1-D k-means on the angles of the       */
-/* polar-transformed inputs; Eq. 3 with the samples in place of the     */
-/* density).  All angles of all n vectors of a level form one sample    */
-/* set; `iterations` rounds of the k-means (Lloyd) update from the      */
-/* centroids in cb_init: every angle goes to its nearest centroid       */
-/* (linear distance, lowest index on ties, as procedure Quant), every   */
-/* centroid moves to the mean of its angles; a centroid without angles  */
-/* stays.  Reading: the paper seeds with k-means++ (randomised); here   */
-/* the seed is cb_init (the analytic codebook, say), which makes the    */
-/* result a function of the data alone.                                 */
-/* ------------------------------------------------------------------ */
 /* Full-depth recursion (Definition 1 and procedure Polar of Algorithm */
 /* 1 run to level log2 d = 7; Section 4's memory count: one radius per */
 /* vector plus the angle codes).  Levels 1..4 keep Section 4.1's bit   */
@@ -770,7 +763,7 @@ void orc_encode_deep(const double *x, int64_t n, const double *S, const double *
             for (int j = 0; j < cnt; ++j) J[off + j] = orc_quant(psi[off + j], theta, K);
             off += cnt; cnt /= 2;
         }
-        if (rec) orc_pack_record_deep(J, orc_f64_to_f16(r7[0]), bits, rec + i * ORC_REC_DEEP);
+        if (rec) orc_pack_record_deep(J, orc_f64_to_f16(fmin(r7[0], ORC_F16_MAX)), bits, rec + i * ORC_REC_DEEP); /* saturates like the block radii */
         if (psi_out) memcpy(psi_out + i * ORC_NANG_DEEP, psi, sizeof(psi));
         if (y_out) memcpy(y_out + i * ORC_D, y, sizeof(y));
     }
@@ -856,6 +849,17 @@ void orc_attention_deep(const double *q, int B, int Hq, int Hkv,
     }
 }
 
+/* ------------------------------------------------------------------ */
+/* Online codebook (Section 4.1: 1-D k-means on the angles of the       */
+/* polar-transformed inputs; Eq. 3 with the samples in place of the     */
+/* density).  All angles of all n vectors of a level form one sample    */
+/* set; `iterations` rounds of the k-means (Lloyd) update from the      */
+/* centroids in cb_init: every angle goes to its nearest centroid       */
+/* (linear distance, lowest index on ties, as procedure Quant), every   */
+/* centroid moves to the mean of its angles; a centroid without angles  */
+/* stays.  Reading: the paper seeds with k-means++ (randomised); here   */
+/* the seed is cb_init (the analytic codebook, say), which makes the    */
+/* result a function of the data alone.                                 */
 /* ------------------------------------------------------------------ */
 void orc_fit_codebooks(const double *x, int64_t n, const double *S, const double *cb_init,
                        int iterations, double *cb_out)

@@ -51,6 +51,10 @@ def library():
     L.pq_fit_codebooks_deep.argtypes = [vp, vp, i32, i64, i32, i64, i64, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
     L.pq_fit_workspace_bytes.restype = ctypes.c_size_t
     L.pq_fit_workspace_bytes.argtypes = []
+    L.pq_fit_count_angles.restype = i32
+    L.pq_fit_count_angles.argtypes = [vp, vp, i32, i64, i32, i64, i64, vp, ctypes.c_size_t, vp]
+    L.pq_fit_cluster.restype = i32
+    L.pq_fit_cluster.argtypes = [vp, vp, vp, vp, i32, vp, vp]
     L.pq_set_recursion_depth.restype = i32
     L.pq_set_recursion_depth.argtypes = [vp, i32, vp]
     L.pq_set_upper_codebooks.restype = i32
@@ -261,6 +265,35 @@ class Context:
             out.ctypes.data_as(ctypes.c_void_p), workspace.data_ptr(),
             int(workspace.numel() * workspace.element_size()), _stream()))
         return out
+
+    def fit_count_angles(self, x, workspace):
+        """First half of fit_codebooks: counts the angles of x into the histograms in workspace (uint8 device tensor of
+        fit_workspace_bytes()); enqueued on the current stream, does not wait."""
+        if x.stride(2) != 1:
+            raise PolarQuantError("innermost dimension must be contiguous")
+        _check(library().pq_fit_count_angles(
+            self._h, x.data_ptr(), _dtype_code(x), int(x.shape[0]), int(x.shape[1]), int(x.stride(0)), int(x.stride(1)),
+            workspace.data_ptr(), int(workspace.numel() * workspace.element_size()), _stream()))
+
+    def fit_cluster(self, hist, iterations, cb_init=None, cbt_init=None):
+        """Second half: hist = host copy (numpy uint32) of the workspace -> 28 centroids, and [3, 8] upper centroids for a
+        depth-7 context (None otherwise)."""
+        hist = np.ascontiguousarray(hist, dtype=np.uint32)
+        if hist.size * 4 != self.fit_workspace_bytes():
+            raise PolarQuantError("hist must be a copy of the whole fit workspace")
+        init = None if cb_init is None else np.ascontiguousarray(cb_init, dtype=np.float64).reshape(-1)
+        init_t = None if cbt_init is None else np.ascontiguousarray(cbt_init, dtype=np.float64)
+        out, out_t = np.empty(28, dtype=np.float64), np.empty((3, 8), dtype=np.float64)
+        _check(library().pq_fit_cluster(
+            self._h, hist.ctypes.data_as(ctypes.c_void_p),
+            init.ctypes.data_as(ctypes.c_void_p) if init is not None else None,
+            init_t.ctypes.data_as(ctypes.c_void_p) if init_t is not None else None, int(iterations),
+            out.ctypes.data_as(ctypes.c_void_p), out_t.ctypes.data_as(ctypes.c_void_p)))
+        return out, (out_t if self.recursion_depth() == 7 else None)
+
+    @staticmethod
+    def fit_workspace_bytes():
+        return int(library().pq_fit_workspace_bytes())
 
     def fit_codebooks_deep(self, x, iterations, cb_init=None, cbt_init=None, workspace=None):
         """fit_codebooks for a depth-7 context: also the codebooks of levels 5-7 -> (28 centroids, [3, 8] centroids)."""

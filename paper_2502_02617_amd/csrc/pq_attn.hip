@@ -19,28 +19,25 @@
  *   pq_attn_combine_kernel  merges the pieces of a (sequence, query head) in tile
  *                           order, divides by l, multiplies by S^T, bf16
  *
- * Partial kernel, per 16-token pass (four passes per 64-token tile):
- *   K:  lane (gk, m) rebuilds the 32 rotated coordinates of quarter gk of token
- *       16*i + m from its own registers: radius -> level 4 -> (level 3 x level 2
- *       product table) -> level 1, every factor a (cos, sin) pair fetched from a
- *       16-entry LDS table (all entries in distinct banks, so the gathers are
- *       conflict free), the products formed in fp32 on fp32 copies of the
- *       tables and rounded to binary16 once.  The 4 x 8 values are
- *       the A operand (token rows) of v_mfma_f32_16x16x32_f16 against q'
- *       (columns = (query token, head) pairs in groups of four, each with its
- *       binary16 remainder in a second column), accumulated over the four
- *       32-coordinate slices.  At recursion depth 7 the block radii are first
- *       rebuilt per tile from the vector's radius and its upper-level codes.
- *   softmax: the score tile comes out with lane (g, col) holding tokens
- *       16*i + 4*g + {0..3}; running max and sum per column.
- *   V:  lane (g, n) rebuilds half-block n (8 coordinates = 4 (cos, sin) pairs) of
- *       those same four tokens with packed binary16 multiplies.  A (cos, sin) register holds two coordinates of
- *       one token, while a matrix-core operand wants several tokens of one
- *       coordinate per lane; instead of transposing, the contraction index is
- *       widened to (token, parity): operand rows are coordinate pairs, and the
- *       probability operand has one column per (head, parity) with zeros in the
- *       slots of the other parity.  The result accumulates o' for the even
- *       coordinates in the parity-0 columns and for the odd ones in parity 1.
+ * Partial kernel, per 64-token tile (the cache stores, per block of 16 coordinates, four 10-bit quarter
+ * indices Q, one 6-bit block index B and the binary16 block radius: pq_layout.h):
+ *   K:  one token per lane.  For each of the token's 32 quarters the lane fetches the quarter's table
+ *       entry -- the four binary16 products (cos|sin) theta2 * (cos|sin) theta1 -- and hands it to
+ *       v_mfma_f32_4x4x4_16b_f16 as it is: the matrix cores form the 4-coordinate inner products with
+ *       q' for four (query token, head) pairs.  Each result is multiplied in fp32 by the quarter's
+ *       radius (block radius x block-table entry (cos|sin) theta4 * (cos|sin) theta3) and added to the
+ *       token's scores.  At recursion depth 7 the lane first rebuilds its token's block radii from the
+ *       vector's radius and its upper-level codes.
+ *   softmax: probabilities 2^(s - m + 9) against a lagging exponent reference m per pair; a lane holds
+ *       the four pairs of its token, and hands them through LDS to the lanes that need them as operands.
+ *   V:  four passes of 16 tokens.  Lane (g, n) rebuilds half-block n (8 coordinates) of tokens
+ *       16 i + 4 g + {0..3} with packed binary16 multiplies: radius x block-table entry -> the radii of
+ *       the half's two quarters, times the two quarter entries.  A register of a quarter entry holds two
+ *       coordinates of one token, while a matrix-core operand wants several tokens of one coordinate per
+ *       lane; instead of transposing, the contraction index of v_mfma_f32_16x16x32_f16 is widened to
+ *       (token, parity): operand rows are coordinate pairs, and the probability operand has one column per
+ *       (pair, parity) with zeros in the slots of the other parity.  The result accumulates o' for the
+ *       even coordinates in the parity-0 columns and for the odd ones in parity 1.
  */
 #include <type_traits>
 
@@ -88,12 +85,9 @@ constexpr int kTQ = 0, kTQA = 2048, kTQB = 4096, kTBF = 6144, kTBH = 10240, kTUp
 #ifndef PQ_VALUE_PAIRS
 #define PQ_VALUE_PAIRS 0
 #endif
-#ifndef PQ_Q_REMAINDER
-#define PQ_Q_REMAINDER 1
-#endif
 
 struct AttnArgs {
-    const uint16_t *qrot; /* [B][M][Hq][2][128] binary16: rotated, pre-scaled q' as a leading part and its remainder */
+    const uint16_t *qrot; /* [B][M][Hq][128] binary16: rotated, pre-scaled q' */
     const uint8_t *k_codes, *v_codes;
     const uint16_t *k_radii, *v_radii;
     int up_b5, up_b6, up_b7; /* bits of levels 5, 6, 7 (depth 7 only) */
@@ -337,19 +331,18 @@ __device__ __forceinline__ uint32_t sel4(uint4 v, int c)
 __device__ __forceinline__ float half_lo_to_float(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xFFFFu)); }
 __device__ __forceinline__ float half_hi_to_float(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); }
 
-/* Query operand of the scores: for column group k, A[k][set][part] holds in lane (i = lane >> 2, slot = lane & 3)
- * the four rotated query coordinates 4 x .. 4 x + 3 of quarter x = 16 set + i for pair 4 k + slot, as the leading
- * binary16 part (part 0) or its binary16 remainder (part 1).  v_mfma_f32_4x4x4_16b_f16 multiplies 16 independent
- * 4x4 blocks; with the A block of one lane group broadcast to all sixteen (cbsz = 4, abid = i) one register pair
- * serves sixteen quarters. */
-template <int NG> struct QueryOperand { H4 a[NG][2][2]; };
+/* Query operand of the scores: for column group k, a[k][set] holds in lane (i = lane >> 2, slot = lane & 3) the four
+ * rotated query coordinates 4 x .. 4 x + 3 of quarter x = 16 set + i for pair 4 k + slot, in binary16.
+ * v_mfma_f32_4x4x4_16b_f16 multiplies 16 independent 4x4 blocks; with the A block of one lane group broadcast to
+ * all sixteen (cbsz = 4, abid = i) one register pair serves sixteen quarters. */
+template <int NG> struct QueryOperand { H4 a[NG][2]; };
 
 /* Scores of one 64-token tile, one token per lane (Eq. 5 with DeQuant unrolled into table products):
  *   s_pair(tau) = sum_b r_b(tau) sum_j T43[B_b][j] * < q'[16 b + 4 j .. + 3], T21[Q_{b,j}] >
  * T21[Q] (binary16, from LDS) = the four products (cos|sin) theta2 * (cos|sin) theta1 of a quarter -- it is the B
  * operand of the matrix instruction as fetched; T43[B] (fp32) = the four products (cos|sin) theta4 * (cos|sin)
  * theta3 of a block.  The matrix cores form the 4-coordinate inner products of a quarter for four (query token,
- * head) pairs per group (leading part and remainder of q' accumulate into the same result); each is scaled in fp32
+ * head) pairs per group; each is scaled in fp32
  * by r_b T43[B_b][j] and summed.  A key element is therefore never rounded beyond its table entry.
  * s comes in holding the negated exponent reference (the first product of a tile adds to it). */
 template <int NG, bool DEEP>
@@ -387,8 +380,7 @@ __device__ __forceinline__ void key_scores(const uint32_t *tab, const KTileRaw &
                 switch (abid) { /* the broadcast selector is an immediate of the instruction */
 #define PQ_SCORE_CASE(N)                                                                                     \
     case N:                                                                                                  \
-        d = __builtin_amdgcn_mfma_f32_4x4x4f16(qo.a[g][set][0].v, kq[j].v, zero, 4, N, 0);                      \
-        if (PQ_Q_REMAINDER) d = __builtin_amdgcn_mfma_f32_4x4x4f16(qo.a[g][set][1].v, kq[j].v, d, 4, N, 0);    \
+        d = __builtin_amdgcn_mfma_f32_4x4x4f16(qo.a[g][set].v, kq[j].v, zero, 4, N, 0);                         \
         break;
                     PQ_SCORE_CASE(0) PQ_SCORE_CASE(1) PQ_SCORE_CASE(2) PQ_SCORE_CASE(3)
                     PQ_SCORE_CASE(4) PQ_SCORE_CASE(5) PQ_SCORE_CASE(6) PQ_SCORE_CASE(7)
@@ -584,7 +576,7 @@ __global__ __launch_bounds__(waves_per_block(NG) * 64, 1) void pq_attn_partial_k
     uint32_t *p_mine = &sP[wave][0][0][lane];
     const uint32_t *p_col = &sP[wave][0][n & 7][4 * g];
     /* rotated queries and partial results: the launch code keeps all three below 4 GB */
-    const __amdgpu_buffer_rsrc_t q_rsrc = stream_descriptor(a.qrot, (uint32_t)a.B * a.M * a.Hq * (2 * PQ_D * 2u));
+    const __amdgpu_buffer_rsrc_t q_rsrc = stream_descriptor(a.qrot, (uint32_t)a.B * a.M * a.Hq * (PQ_D * 2u));
     const __amdgpu_buffer_rsrc_t o_rsrc = stream_descriptor(a.ws_o, (uint32_t)a.n_pieces * (a.M * G) * (PQ_D * 4u));
     const __amdgpu_buffer_rsrc_t ml_rsrc = stream_descriptor(a.ws_ml, (uint32_t)a.n_pieces * (a.M * G) * 8u);
 
@@ -620,16 +612,14 @@ __global__ __launch_bounds__(waves_per_block(NG) * 64, 1) void pq_attn_partial_k
             const bool real = pair < a.M * G;
             const int m = real ? pair / G : 0, head = real ? pair % G : 0;
             /* 32-bit offsets into the rotated queries: lane part in bytes, (sequence, kv head) part scalar */
-            const uint32_t lane_off = (uint32_t)((m * a.Hq + head) * 2 * PQ_D + 4 * qi) * 2u;
-            const uint32_t row_off = (uint32_t)((b * a.M * a.Hq + hk * G) * 2 * PQ_D) * 2u;
+            const uint32_t lane_off = (uint32_t)((m * a.Hq + head) * PQ_D + 4 * qi) * 2u;
+            const uint32_t row_off = (uint32_t)((b * a.M * a.Hq + hk * G) * PQ_D) * 2u;
 #pragma unroll
-            for (int set = 0; set < 2; ++set)
-#pragma unroll
-                for (int part = 0; part < 2; ++part) {
-                    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(q_rsrc, lane_off + (uint32_t)(part * PQ_D + 64 * set) * 2u, row_off, 0);
-                    qo.a[k][set][part].w[0] = real ? v.x : 0u;
-                    qo.a[k][set][part].w[1] = real ? v.y : 0u;
-                }
+            for (int set = 0; set < 2; ++set) {
+                const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(q_rsrc, lane_off + (uint32_t)(64 * set) * 2u, row_off, 0);
+                qo.a[k][set].w[0] = real ? v.x : 0u;
+                qo.a[k][set].w[1] = real ? v.y : 0u;
+            }
         }
         f4 acc_o[NG][4];
         /* exponent reference of a pair: the same in all lanes; l: this lane's share of the sum of its token's weights */
@@ -826,7 +816,7 @@ __global__ __launch_bounds__(waves_per_block(NG) * 64, 1) void pq_attn_partial_k
 
 struct RotateArgs {
     const uint16_t *q; /* bf16 [rows][128] */
-    uint16_t *qrot;    /* binary16 [rows][2][128]: leading part, remainder */
+    uint16_t *qrot;    /* binary16 [rows][128] */
     const float *S;    /* S[i*128 + j] */
     float scale;       /* softmax_scale * log2(e) */
     const PqDeviceConsts *consts;
@@ -864,10 +854,7 @@ __device__ __forceinline__ void rotate_query_rows(const RotateArgs &a, int row0,
     if (row < n_rows) {
         const float acc = ((spart[r][0][j] + spart[r][1][j]) + spart[r][2][j]) + spart[r][3][j];
         const float v = acc * a.scale;
-        const _Float16 h = (_Float16)v;
-        const _Float16 rem = (_Float16)(v - (float)h);
-        a.qrot[(int64_t)row * 2 * PQ_D + j] = __builtin_bit_cast(uint16_t, h);
-        a.qrot[(int64_t)row * 2 * PQ_D + PQ_D + j] = __builtin_bit_cast(uint16_t, rem);
+        a.qrot[(int64_t)row * PQ_D + j] = __builtin_bit_cast(uint16_t, (_Float16)v);
     }
 }
 
@@ -1256,7 +1243,7 @@ Plan make_plan(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap = 0, int
     p.pieces = pieces;
     p.o_bytes = pieces * pairs * PQ_D * sizeof(float);
     size_t rows = (size_t)B * M * Hq;
-    p.off_plan = (rows * 2 * PQ_D * sizeof(uint16_t) + 255) & ~(size_t)255;
+    p.off_plan = (rows * PQ_D * sizeof(uint16_t) + 255) & ~(size_t)255;
     p.off_ml = (p.off_plan + (kPlanHeader + (size_t)B + 1 + 2 * (size_t)B * Hkv) * sizeof(int32_t) + 255) & ~(size_t)255;
     p.off_o = (p.off_ml + pieces * pairs * 2 * sizeof(float) + 255) & ~(size_t)255;
     p.total = p.off_o + pieces * pairs * PQ_D * sizeof(float);
@@ -1360,7 +1347,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     const Plan p = make_plan(B, Hq, Hkv, max_ctx, win ? win->win_cap : 0, M);
     if ((int64_t)B * Hkv * p.n_wchunks > 0x7FFFFFFF) return PQ_EINVAL;
     /* the partial kernel addresses the rotated queries and its partial results with 32-bit byte offsets */
-    if ((uint64_t)B * M * Hq * (2 * PQ_D * 2) > 0xFFFFFFFFull || p.o_bytes > 0xFFFFFFFFull) return PQ_EUNSUPPORTED;
+    if ((uint64_t)B * M * Hq * (PQ_D * 2) > 0xFFFFFFFFull || p.o_bytes > 0xFFFFFFFFull) return PQ_EUNSUPPORTED;
     if (workspace_bytes < p.total) return PQ_ENOMEM;
     const PqDeviceState *ds = nullptr;
     pq_status st = pq_device_state(ctx, &ds);

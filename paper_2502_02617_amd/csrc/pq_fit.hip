@@ -202,20 +202,15 @@ extern "C" size_t pq_fit_workspace_bytes(void) { return (size_t)(kHistSize + kHi
 
 namespace {
 
-pq_status fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
-                        int64_t ld_token, int64_t ld_head, const double *cb_init, const double *cbt_init, bool upper,
-                        int iterations, double *cb_out, double *cbt_out, void *workspace, size_t workspace_bytes,
-                        void *hip_stream)
+/* clears the histograms with a kernel of the library's own: a memset node would not survive graph capture */
+__global__ __launch_bounds__(256) void pq_fit_clear_kernel(uint32_t *hist, int n)
 {
-    if (!ctx || !x || !cb_out || !workspace || (upper && !cbt_out)) return PQ_EINVAL;
-    if (xt != PQ_F32 && xt != PQ_BF16) return PQ_EINVAL;
-    if (n_tokens <= 0 || n_heads <= 0 || ld_token < 0 || ld_head < 0 || iterations < 0) return PQ_EINVAL;
-    if (upper && ctx->depth != 7) return PQ_EINVAL;
-    if (workspace_bytes < pq_fit_workspace_bytes()) return PQ_ENOMEM;
-    if (!pq_aligned16(workspace)) return PQ_EALIGN;
-    /* every bin counter must hold the angles of a level: 64 per vector at level 1 */
-    if ((double)n_tokens * n_heads * 64.0 >= 4294967295.0) return PQ_EUNSUPPORTED;
-    double c[28];
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) hist[i] = 0u;
+}
+
+pq_status check_start(const pq_ctx *ctx, const double *cb_init, const double *cbt_init, bool upper, double (&c)[28],
+                      double (&ct)[3][8])
+{
     if (cb_init) {
         memcpy(c, cb_init, sizeof(c));
     } else {
@@ -229,7 +224,6 @@ pq_status fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n
             if (!std::isfinite(c[off[l] + k])) return PQ_EINVAL;
             if (k > 0 && !(c[off[l] + k] > c[off[l] + k - 1])) return PQ_EINVAL;
         }
-    double ct[3][8] = {};
     if (upper) {
         for (int l = 0; l < 3; ++l) {
             const int Kl = 1 << ctx->upper_bits[l];
@@ -240,12 +234,30 @@ pq_status fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n
             }
         }
     }
+    return PQ_OK;
+}
+
+} // namespace
+
+extern "C" pq_status pq_fit_count_angles(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
+                                         int64_t ld_token, int64_t ld_head, void *workspace, size_t workspace_bytes,
+                                         void *hip_stream)
+{
+    if (!ctx || !x || !workspace) return PQ_EINVAL;
+    if (xt != PQ_F32 && xt != PQ_BF16) return PQ_EINVAL;
+    if (n_tokens <= 0 || n_heads <= 0 || ld_token < 0 || ld_head < 0) return PQ_EINVAL;
+    if (workspace_bytes < pq_fit_workspace_bytes()) return PQ_ENOMEM;
+    const int64_t elems16 = xt == PQ_BF16 ? 8 : 4;
+    if (!pq_aligned16(workspace) || !pq_aligned16(x) || (ld_token % elems16) || (ld_head % elems16)) return PQ_EALIGN;
+    /* every bin counter must hold the angles of a level: 64 per vector at level 1 */
+    if ((double)n_tokens * n_heads * 64.0 >= 4294967295.0) return PQ_EUNSUPPORTED;
+    const bool upper = ctx->depth == 7;
     const PqDeviceState *ds = nullptr;
     pq_status st = pq_device_state(ctx, &ds);
     if (st != PQ_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     uint32_t *hist = static_cast<uint32_t *>(workspace);
-    PQ_HIP_TRY(hipMemsetAsync(hist, 0, pq_fit_workspace_bytes(), s));
+    hipLaunchKernelGGL(pq_fit_clear_kernel, dim3(16), dim3(256), 0, s, hist, kHistSize + kHistUpper);
     FitArgs a{};
     a.x = x; a.ld_token = ld_token; a.ld_head = ld_head; a.n_tokens = n_tokens; a.n_heads = n_heads;
     a.tiles_per_head = (n_tokens + kTileVecs - 1) / kTileVecs;
@@ -257,21 +269,55 @@ pq_status fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n
     if (xt == PQ_BF16) hipLaunchKernelGGL(pq_angle_histogram_kernel<PQ_BF16>, dim3((unsigned)blocks), dim3(kFitThreads), 0, s, a);
     else hipLaunchKernelGGL(pq_angle_histogram_kernel<PQ_F32>, dim3((unsigned)blocks), dim3(kFitThreads), 0, s, a);
     PQ_HIP_TRY(hipGetLastError());
-    std::vector<uint32_t> h(kHistSize + kHistUpper);
-    PQ_HIP_TRY(hipMemcpyAsync(h.data(), hist, pq_fit_workspace_bytes(), hipMemcpyDeviceToHost, s));
-    PQ_HIP_TRY(hipStreamSynchronize(s));
+    return PQ_OK;
+}
+
+extern "C" pq_status pq_fit_cluster(const pq_ctx *ctx, const uint32_t *hist, const double *cb_init, const double *cbt_init,
+                                    int iterations, double *cb_out, double *cbt_out)
+{
+    if (!ctx || !hist || !cb_out || iterations < 0) return PQ_EINVAL;
+    const bool upper = ctx->depth == 7;
+    if (upper && !cbt_out) return PQ_EINVAL;
+    double c[28], ct[3][8] = {};
+    const pq_status st = check_start(ctx, cb_init, cbt_init, upper, c, ct);
+    if (st != PQ_OK) return st;
+    const int off[4] = {0, 16, 20, 24};
     const double pi = 3.14159265358979323846264338327950288;
-    lloyd_on_histogram(h.data(), kBins1, 2.0 * pi / kBins1, 16, iterations, c);
+    lloyd_on_histogram(hist, kBins1, 2.0 * pi / kBins1, 16, iterations, c);
     for (int l = 1; l < 4; ++l)
-        lloyd_on_histogram(h.data() + kBins1 + (l - 1) * kBinsU, kBinsU, 0.5 * pi / kBinsU, 4, iterations, c + off[l]);
+        lloyd_on_histogram(hist + kBins1 + (l - 1) * kBinsU, kBinsU, 0.5 * pi / kBinsU, 4, iterations, c + off[l]);
     memcpy(cb_out, c, sizeof(c));
     if (upper) {
         for (int l = 0; l < 3; ++l)
-            lloyd_on_histogram(h.data() + kHistSize + l * kBinsU, kBinsU, 0.5 * pi / kBinsU, 1 << ctx->upper_bits[l],
+            lloyd_on_histogram(hist + kHistSize + l * kBinsU, kBinsU, 0.5 * pi / kBinsU, 1 << ctx->upper_bits[l],
                                iterations, ct[l]);
         memcpy(cbt_out, ct, sizeof(ct));
     }
     return PQ_OK;
+}
+
+namespace {
+
+/* the two steps with a copy of the histograms and a wait for the stream in between */
+pq_status fit_codebooks(const pq_ctx *ctx, const void *x, pq_dtype xt, int64_t n_tokens, int n_heads,
+                        int64_t ld_token, int64_t ld_head, const double *cb_init, const double *cbt_init, bool upper,
+                        int iterations, double *cb_out, double *cbt_out, void *workspace, size_t workspace_bytes,
+                        void *hip_stream)
+{
+    if (!ctx || !cb_out || (upper && !cbt_out) || iterations < 0) return PQ_EINVAL;
+    if (upper && ctx->depth != 7) return PQ_EINVAL;
+    double unused_upper[3][8];
+    if (!upper && ctx->depth == 7) cbt_out = &unused_upper[0][0]; /* levels 1..4 only were asked for */
+    double c[28], ct[3][8] = {};
+    pq_status st = check_start(ctx, cb_init, cbt_init, upper, c, ct); /* before anything is launched */
+    if (st != PQ_OK) return st;
+    st = pq_fit_count_angles(ctx, x, xt, n_tokens, n_heads, ld_token, ld_head, workspace, workspace_bytes, hip_stream);
+    if (st != PQ_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    std::vector<uint32_t> h(kHistSize + kHistUpper);
+    PQ_HIP_TRY(hipMemcpyAsync(h.data(), workspace, pq_fit_workspace_bytes(), hipMemcpyDeviceToHost, s));
+    PQ_HIP_TRY(hipStreamSynchronize(s));
+    return pq_fit_cluster(ctx, h.data(), cb_init, cbt_init, iterations, cb_out, cbt_out);
 }
 
 } // namespace

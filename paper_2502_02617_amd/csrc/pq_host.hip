@@ -11,6 +11,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <new>
 #include <vector>
 
@@ -551,14 +552,23 @@ pq_status pq_device_state(const pq_ctx *cctx, const PqDeviceState **out)
                         sb[2 * (size_t)PQ_SB_TERM_STRIDE + at] = t3;
                     }
         PqDeviceState t;
-        if (hipMalloc((void **)&t.consts, sizeof(PqDeviceConsts)) != hipSuccess) return PQ_ENOMEM;
-        if (hipMalloc((void **)&t.S_f32, Sf.size() * 4) != hipSuccess) return PQ_ENOMEM;
-        if (hipMalloc((void **)&t.St_f32, Stf.size() * 4) != hipSuccess) return PQ_ENOMEM;
-        if (hipMalloc((void **)&t.S_bf16x3, sb.size() * 2) != hipSuccess) return PQ_ENOMEM;
-        PQ_HIP_TRY(hipMemcpy(t.consts, &ctx->host_consts, sizeof(PqDeviceConsts), hipMemcpyHostToDevice));
-        PQ_HIP_TRY(hipMemcpy(t.S_f32, Sf.data(), Sf.size() * 4, hipMemcpyHostToDevice));
-        PQ_HIP_TRY(hipMemcpy(t.St_f32, Stf.data(), Stf.size() * 4, hipMemcpyHostToDevice));
-        PQ_HIP_TRY(hipMemcpy(t.S_bf16x3, sb.data(), sb.size() * 2, hipMemcpyHostToDevice));
+        auto release = [&t]() { /* a failed set-up leaves nothing behind: the next call starts over */
+            (void)hipFree(t.consts); (void)hipFree(t.S_f32); (void)hipFree(t.St_f32); (void)hipFree(t.S_bf16x3);
+        };
+        if (hipMalloc((void **)&t.consts, sizeof(PqDeviceConsts)) != hipSuccess ||
+            hipMalloc((void **)&t.S_f32, Sf.size() * 4) != hipSuccess ||
+            hipMalloc((void **)&t.St_f32, Stf.size() * 4) != hipSuccess ||
+            hipMalloc((void **)&t.S_bf16x3, sb.size() * 2) != hipSuccess) {
+            release();
+            return PQ_ENOMEM;
+        }
+        if (hipMemcpy(t.consts, &ctx->host_consts, sizeof(PqDeviceConsts), hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(t.S_f32, Sf.data(), Sf.size() * 4, hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(t.St_f32, Stf.data(), Stf.size() * 4, hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(t.S_bf16x3, sb.data(), sb.size() * 2, hipMemcpyHostToDevice) != hipSuccess) {
+            release();
+            return PQ_EHIP;
+        }
         t.ready = true;
         s = t;
     }
@@ -579,7 +589,7 @@ bool pq_device_state_ready(const pq_ctx *cctx)
 namespace {
 struct Profiler {
     std::mutex mu;
-    bool on = false;
+    std::atomic<bool> on{false}; /* read without the lock on every launch */
     int cap = 0;
     std::vector<hipEvent_t> start[2], stop[2];
     int used[2] = {0, 0};
@@ -591,9 +601,9 @@ struct Profiler {
 
 void pq_prof_before(int kind, hipStream_t s)
 {
-    if (!g_prof.on) return;
+    if (!g_prof.on.load(std::memory_order_acquire)) return;
     std::lock_guard<std::mutex> lock(g_prof.mu);
-    if (!g_prof.on) return;
+    if (!g_prof.on.load()) return;
     g_prof.timing_now[kind] = g_prof.used[kind] < g_prof.cap && (g_prof.seen[kind] % g_prof.every) == 0;
     g_prof.seen[kind] += 1;
     if (g_prof.timing_now[kind]) (void)hipEventRecord(g_prof.start[kind][g_prof.used[kind]], s);
@@ -601,9 +611,9 @@ void pq_prof_before(int kind, hipStream_t s)
 
 void pq_prof_after(int kind, hipStream_t s)
 {
-    if (!g_prof.on) return;
+    if (!g_prof.on.load(std::memory_order_acquire)) return;
     std::lock_guard<std::mutex> lock(g_prof.mu);
-    if (g_prof.on && g_prof.timing_now[kind]) {
+    if (g_prof.on.load() && g_prof.timing_now[kind]) {
         (void)hipEventRecord(g_prof.stop[kind][g_prof.used[kind]], s);
         g_prof.used[kind] += 1;
         g_prof.timing_now[kind] = false;

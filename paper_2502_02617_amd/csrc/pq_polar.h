@@ -10,6 +10,11 @@
 
 #if defined(__HIPCC__)
 
+/* The stored radius is a binary16 number (b_FPN = 16, Section 4.1).  The paper does not say what becomes of a radius
+ * beyond that format's range; here it saturates at the largest finite binary16 value, 65504: the block keeps its
+ * direction, and everything computed from the cache stays finite. */
+__device__ __forceinline__ float pq_saturate_radius(float r) { return fminf(r, 65504.0f); }
+
 /* Quantise one quadrant angle: number of inner boundaries below atan(v/u), for
  * u, v >= 0.  Boundary k is passed when v > t_k * u, that is when the fused
  * t_k * u - v (one rounding, so its sign is the exact one) is negative; the sign
@@ -119,7 +124,7 @@ __device__ __forceinline__ uint32_t polar_upper_join(const UpperHalf &lo, const 
                                                      const UpperTables &K)
 {
     const uint32_t c7 = pq_quant_upper(lo.q6, hi.q6, K.tan2[2], (1 << K.b7) - 1);
-    const float r7 = __builtin_amdgcn_sqrtf(lo.q6 + hi.q6) * radius_scale;
+    const float r7 = pq_saturate_radius(__builtin_amdgcn_sqrtf(lo.q6 + hi.q6) * radius_scale);
     const _Float16 rh = (_Float16)r7; /* round to nearest even */
     return lo.codes | hi.codes | (c7 << (4 * K.b5 + 2 * K.b6)) | ((uint32_t)__builtin_bit_cast(uint16_t, rh) << 16);
 }
@@ -185,7 +190,7 @@ __device__ __forceinline__ void polar_upper(PolarState &s, int p, const Threshol
         s.out.c4 = GENERAL ? quant3g(s.q3[0], s.q3[1], th.t4a, th.t4b, th.t4c)
                            : quant3(s.q3[0], s.q3[1], th.t4a, th.t4c);
         s.out.q4 = s.q3[0] + s.q3[1];
-        const float r4 = __builtin_amdgcn_sqrtf(s.out.q4) * th.radius_scale;
+        const float r4 = pq_saturate_radius(__builtin_amdgcn_sqrtf(s.out.q4) * th.radius_scale);
         const _Float16 rh = (_Float16)r4; /* round to nearest even */
         s.out.radius = __builtin_bit_cast(uint16_t, rh);
         s.out.l1 = s.l1;
@@ -323,7 +328,7 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
         BlockCodes bc;
         bc.c4 = a.consts->general ? quant3g(q3, q3s, th.t4a, th.t4b, th.t4c) : quant3(q3, q3s, th.t4a, th.t4c);
         bc.q4 = q3 + q3s;
-        const _Float16 rh = (_Float16)(__builtin_amdgcn_sqrtf(bc.q4) * th.radius_scale); /* round to nearest even */
+        const _Float16 rh = (_Float16)pq_saturate_radius(__builtin_amdgcn_sqrtf(bc.q4) * th.radius_scale); /* round to nearest even */
         bc.radius = __builtin_bit_cast(uint16_t, rh);
         /* the block's fields gathered into its first lane: level-1 codes at their nibbles; the 6-bit
            groups [c2(2h) | c3(h) | c2(2h+1)] of half-block h at bits [8h, 8h+6) of a second word */

@@ -15,6 +15,7 @@ import math
 import numpy as np
 
 import oracle
+from tests import layout_ref
 
 ANGLE_TOL = 1e-5
 CODE_MISMATCH_RATE = 1e-4
@@ -44,7 +45,7 @@ def check_codes(rec_gpu, rec_oracle, psi, enforce_rate=True):
     """Returns a dict of statistics; raises AssertionError when the acceptance rule fails.
     enforce_rate=False leaves the rate limit to the caller, who pools the counts of several small calls
     (on a few hundred angles one legitimate tie already exceeds the rate)."""
-    Jg, rg = oracle.unpack(rec_gpu)
+    Jg, rg = layout_ref.unpack_canonical(rec_gpu)   # the library's records never pass through the oracle package
     Jo, ro = oracle.unpack(rec_oracle)
     bad = Jg != Jo
     n_bad = int(bad.sum())
@@ -66,7 +67,7 @@ def check_codes(rec_gpu, rec_oracle, psi, enforce_rate=True):
 def check_codes_deep(rec_gpu, rec_oracle, psi, bits):
     """Deep (50-byte) records: psi [n,127] exact oracle angles.  Same rule as check_codes for all 127 codes.
     Returns (stats, radii_gpu [n], radii_oracle [n])."""
-    Jg, rg = oracle.unpack_deep(rec_gpu, bits)
+    Jg, rg = layout_ref.unpack_canonical_deep(rec_gpu, bits)
     Jo, ro = oracle.unpack_deep(rec_oracle, bits)
     bad = Jg != Jo
     n_bad = int(bad.sum())
@@ -138,3 +139,31 @@ def rel_l2(a, b):
 
 def softmax_scale():
     return 1.0 / math.sqrt(128.0)
+
+
+def upload_records(kind, rec, codes, radii, start, fill=0xFF):
+    """Lays canonical records out as tiles (numpy, from the layout specification) and copies them into a device
+    cache: rec uint8 [H, n, 62] -> slots [start, start + n) of every head plane; start on a tile boundary.  The rest
+    of the last tile gets `fill` in every byte (0xFF: a NaN radius and arbitrary codes)."""
+    import torch
+
+    H, n, _ = rec.shape
+    assert start % 64 == 0
+    T, t0 = (n + 63) // 64, start // 64
+    for h in range(H):
+        c, r = layout_ref.canonical_to_tiles(kind, rec[h], T, fill)
+        codes[h, t0:t0 + T] = torch.from_numpy(c).to(codes.device)
+        radii[h, t0:t0 + T] = torch.from_numpy(r.view(np.int16)).to(radii.device)
+
+
+def upload_records_deep(kind, rec, codes, top, start, fill=0xFF):
+    """The same for full-depth caches: rec uint8 [H, n, 50]; top: the radius plane, int16 [H, tiles, 128]."""
+    import torch
+
+    H, n, _ = rec.shape
+    assert start % 64 == 0
+    T, t0 = (n + 63) // 64, start // 64
+    for h in range(H):
+        c, t = layout_ref.canonical_to_tiles_deep(kind, rec[h], T, fill)
+        codes[h, t0:t0 + T] = torch.from_numpy(c).to(codes.device)
+        top[h, t0:t0 + T] = torch.from_numpy(t.view(np.int16)).to(top.device)

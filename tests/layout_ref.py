@@ -169,3 +169,30 @@ def canonical_to_tiles_deep(kind, rec, n_tiles=None, fill=0):
     top[:n, 0] = r[:, 46] | (r[:, 47] << 8)
     top[:n, 1] = r[:, 48] | (r[:, 49] << 8)
     return codes, top.reshape(T, 128)
+
+
+def unpack_canonical(rec):
+    """Canonical 62-byte records -> (codes int32 [n, 120]: the 64 level-1, 32 level-2, 16 level-3 and 8 level-4
+    codes in coordinate order; radii uint16 [n, 8]).  Written from the record specification (bytes 0..31 level 1,
+    two codes per byte, earlier code in the high nibble; 32..39 / 40..43 / 44..45 levels 2 / 3 / 4, four per byte,
+    earlier code in the higher bits; 46..61 the radii, little endian)."""
+    rec = np.ascontiguousarray(rec).reshape(-1, 62)
+    c1, c2, c3, c4 = _record_codes(rec)
+    r = rec[:, 46:62].astype(np.uint16)
+    return np.concatenate([c1, c2, c3, c4], axis=1).astype(np.int32), (r[:, 0::2] | (r[:, 1::2] << 8)).astype(np.uint16)
+
+
+def unpack_canonical_deep(rec, bits):
+    """Full-depth 50-byte records -> (codes int32 [n, 127]: as above, then the 4 + 2 + 1 codes of levels 5, 6, 7 from
+    the 16-bit word at bytes 46..47 (level-5 codes lowest, bits[l-5] bits each); radius uint16 [n] from bytes 48..49)."""
+    rec = np.ascontiguousarray(rec).reshape(-1, 50)
+    c1, c2, c3, c4 = _record_codes(rec)
+    r = rec.astype(np.uint32)
+    word = r[:, 46] | (r[:, 47] << 8)
+    up, at = [], 0
+    for count, b in ((4, bits[0]), (2, bits[1]), (1, bits[2])):
+        for _ in range(count):
+            up.append((word >> at) & ((1 << b) - 1))
+            at += b
+    radius = (r[:, 48] | (r[:, 49] << 8)).astype(np.uint16)
+    return np.concatenate([c1, c2, c3, c4, np.stack(up, axis=1)], axis=1).astype(np.int32), radius

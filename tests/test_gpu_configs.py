@@ -1,9 +1,10 @@
-"""GPU parity at the full sizes of the benchmark configurations, on sampled outputs.
+"""GPU parity at the full sizes of the benchmark configurations.
 
 The launch configurations are the ones bench.py times.  Inputs are drawn on the GPU
 with the seeded recipes of synth.py (same recipe as the CPU draws, other random
-stream) and the sampled parts are copied to the host for the fp64 oracle, which
-encodes and attends on its own.
+stream) and copied to the host for the fp64 oracle, which encodes and attends on its own:
+config 2 and config 3 on every output row, config 4 (one layer) on every sequence with one of
+its kv heads, so that every sequence and every kv head is covered.
 """
 import math
 import sys
@@ -74,9 +75,23 @@ def test_config1_encode_all_vectors(env, kind):
     assert err <= 1e-3
 
 
-def run_attention_case(ctx, S, cb, lens, sample_pairs, seed, append=False):
-    """Builds the cache of a whole batch on the GPU, runs pq_attn_decode_polar for all rows and
-    checks the sampled (sequence, kv head) pairs against the oracle."""
+def row_errors(got, ref):
+    """Error of every output row relative to its own norm or to the root-mean-square row norm of the reference,
+    whichever is larger (a row whose output nearly cancels has a small norm of its own but the same absolute
+    error as its neighbours)."""
+    rms = math.sqrt(float(np.mean(np.sum(ref * ref, axis=-1))))
+    return np.sqrt(np.sum((got - ref) ** 2, axis=-1)) / np.maximum(np.sqrt(np.sum(ref * ref, axis=-1)), rms)
+
+
+def run_attention_case(ctx, S, cb, lens, heads_of, seed, step=False):
+    """Builds the cache of a whole batch on the GPU with the library's encoder, runs attention for all rows in the
+    launch configuration bench.py times, and checks the (sequence, kv head) pairs named by heads_of(b) against the
+    oracle, which encodes the same inputs and attends on its own records.
+    step=False: pq_attn_decode_polar, fp32 output.
+    step=True:  the newest token of every sequence goes in through pq_decode_step_polar (append + attention in one
+                call, bf16 output: what bench.py times), then pq_attn_decode_polar with fp32 output runs on the
+                same cache; both are checked.
+    Returns {label: (rel L2 over the compared rows, worst row error, rel L2 of the oracle's result rounded to the output format)}."""
     B = len(lens)
     starts, pool = [], 0
     for n in lens:
@@ -86,74 +101,92 @@ def run_attention_case(ctx, S, cb, lens, sample_pairs, seed, append=False):
     vc, vr = Context.alloc_cache(HKV, pool, DEV)
     for t in (kc, kr, vc, vr):
         t.zero_()
-    wanted = {}
-    for b, hk in sample_pairs:
-        wanted.setdefault(b, []).append(hk)
-    kept = {}
+    q = synth.queries(B, HQ, seed=seed + 999, device=DEV)
+    q_host = q.cpu().to(torch.float64).numpy()
+    new_k, new_v, ref, where = [], [], [], []
     for b, n in enumerate(lens):
         k = synth.kv_stream(n, HKV, seed=seed + 2 * b, device=DEV)
         v = synth.kv_stream(n, HKV, seed=seed + 2 * b + 1, device=DEV)
-        n_bulk = n - 1 if append else n
+        n_bulk = n - 1 if step else n
         encode_stream(ctx, k[:, :n_bulk], PQ_KEY, kc, kr, starts[b])
         encode_stream(ctx, v[:, :n_bulk], PQ_VALUE, vc, vr, starts[b])
-        if append:
-            kept.setdefault("new_k", []).append(k[:, n - 1])
-            kept.setdefault("new_v", []).append(v[:, n - 1])
-        for hk in wanted.get(b, []):
-            kept[(b, hk)] = (k[hk:hk + 1].clone(), v[hk:hk + 1].clone())
+        if step:
+            new_k.append(k[:, n - 1])
+            new_v.append(v[:, n - 1])
+        heads = list(heads_of(b))
+        if heads:   # the oracle's side of this sequence: its own records of the same inputs, then Eq. 5
+            k_rec = oracle_encode_heads(k[heads], S, cb)[0]
+            v_rec = oracle_encode_heads(v[heads], S, cb)[0]
+            qs = np.concatenate([q_host[b:b + 1, 4 * hk:4 * hk + 4] for hk in heads], axis=1)
+            r = oracle.attention(qs, k_rec, v_rec, np.array([0], np.int64), np.array([n], np.int32), S, cb, SCALE)
+            for i, hk in enumerate(heads):
+                ref.append(r[0, 4 * i:4 * i + 4])
+                where.append((b, hk))
         del k, v
+    ref = np.stack(ref)
     seq_start = torch.tensor(starts, dtype=torch.int64, device=DEV)
     ctx_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
-    if append:  # decode-time order: append the newest token of every sequence, then attend
-        newest = seq_start + ctx_len.to(torch.int64) - 1
-        ctx.append_kv(torch.stack(kept["new_k"]).contiguous(), PQ_KEY, kc, kr, newest)
-        ctx.append_kv(torch.stack(kept["new_v"]).contiguous(), PQ_VALUE, vc, vr, newest)
-    q = synth.queries(B, HQ, seed=seed + 999, device=DEV)
-    out = torch.empty((B, HQ, 128), dtype=torch.float32, device=DEV)
     max_ctx = max(lens)
     ws = torch.empty(Context.attn_workspace_bytes(B, HQ, HKV, max_ctx), dtype=torch.uint8, device=DEV)
+    outs = {}
+    if step:  # decode-time order: the newest token of every sequence is appended, then attended to
+        newest = seq_start + ctx_len.to(torch.int64) - 1
+        out_b = torch.empty((B, HQ, 128), dtype=torch.bfloat16, device=DEV)
+        ctx.decode_step_polar(torch.stack(new_k).contiguous(), torch.stack(new_v).contiguous(), newest, q, out_b,
+                              kc, kr, vc, vr, seq_start, ctx_len, max_ctx, SCALE, ws)
+        outs["pq_decode_step_polar bf16"] = out_b
+    out = torch.empty((B, HQ, 128), dtype=torch.float32, device=DEV)
     ctx.attn_decode_polar(q, out, kc, kr, vc, vr, seq_start, ctx_len, max_ctx, SCALE, ws)
+    outs["pq_attn_decode_polar fp32"] = out
     torch.cuda.synchronize()
-    got_all = out.cpu().numpy().astype(np.float64)
-    assert np.all(np.isfinite(got_all))
-    got, ref = [], []
-    for b, hk in sample_pairs:
-        k, v = kept[(b, hk)]
-        k_rec = oracle_encode_heads(k, S, cb)[0]
-        v_rec = oracle_encode_heads(v, S, cb)[0]
-        qs = q[b:b + 1, 4 * hk:4 * hk + 4].cpu().to(torch.float64).numpy()
-        r = oracle.attention(qs, k_rec, v_rec, np.array([0], np.int64), np.array([lens[b]], np.int32), S, cb, SCALE)
-        ref.append(r[0])
-        got.append(got_all[b, 4 * hk:4 * hk + 4])
-    got, ref = np.stack(got), np.stack(ref)
-    err = helpers.rel_l2(got, ref)
-    per_pair = [helpers.rel_l2(g, r) for g, r in zip(got, ref)]
-    say(f"  sampled pairs {sample_pairs}: rel L2 {err:.2e}; per pair {['%.1e' % e for e in per_pair]}")
-    return err
+    result = {}
+    for label, o in outs.items():
+        got_all = o.float().cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got_all))
+        got = np.stack([got_all[b, 4 * hk:4 * hk + 4] for b, hk in where])
+        err = helpers.rel_l2(got, ref)
+        rows = row_errors(got.reshape(-1, 128), ref.reshape(-1, 128))
+        say(f"  {label}: {len(where)} (sequence, kv head) pairs = {rows.size} rows: rel L2 {err:.2e}; "
+            f"worst row {rows.max():.2e}")
+        # what rounding the oracle's own result to the output format costs (zero for fp32 output)
+        fmt = helpers.rel_l2(torch.from_numpy(ref).to(o.dtype).double().numpy(), ref)
+        result[label] = (err, float(rows.max()), fmt)
+    return result
+
+
+# Bounds.  Attention: 2e-3 relative L2 over the compared rows (bf16 inputs, fp32 output).  A bf16 output is the same
+# numbers rounded to 8 significant bits, which by itself costs 1.7e-3 .. 2.0e-3 relative L2 (measured on the oracle's
+# own result), so for bf16 output the format's rounding is added in quadrature; config 2, the configuration the
+# benchmark times, is additionally held to the flat 2e-3 with bf16 output.
+# Single rows are heavy-tailed -- a row dominated by one or two tokens carries those tokens' quantisation and rounding
+# errors undiluted, and the encoder may code an angle on a cell boundary either way -- so the per-row limit is a
+# detector of gross errors (a piece of a stream attended twice or not at all moves a row by far more): ten times the
+# aggregate tolerance.  Measured worst rows: 2.8e-3 (fp32 output), 3.9e-3 (bf16 output) of the 512 of config 2.
+ATTN_TOL, ROW_TOL = 2e-3, 2e-2
+
+
+def check_case(result, flat_bf16=False):
+    for label, (err, worst, fmt) in result.items():
+        bound = ATTN_TOL if flat_bf16 else math.sqrt(ATTN_TOL ** 2 + fmt ** 2)
+        assert err <= bound, (label, err, bound)
+        assert worst <= ROW_TOL, (label, worst)
 
 
 def test_config2_decode_32k(env):
     ctx, S, cb = env
-    say("config 2: batch 16, 32768-token context, sampled (sequence, kv head) pairs")
-    pairs = [(0, 0), (3, 5), (7, 2), (9, 7), (12, 4), (15, 1), (5, 3), (10, 6)]
-    err = run_attention_case(ctx, S, cb, [32768] * 16, pairs, seed=2000)
-    assert err <= 2e-3
+    say("config 2: batch 16, 32768-token context, all 512 output rows, decode step (bf16) and attention (fp32)")
+    check_case(run_attention_case(ctx, S, cb, [32768] * 16, lambda b: range(HKV), seed=2000, step=True), flat_bf16=True)
 
 
 def test_config3_long_context_128k(env):
     ctx, S, cb = env
-    say("config 3: batch 4, 131072-token context")
-    pairs = [(0, 0), (1, 3), (2, 6), (3, 7)]
-    err = run_attention_case(ctx, S, cb, [131072] * 4, pairs, seed=3000)
-    assert err <= 2e-3
+    say("config 3: batch 4, 131072-token context, all 128 output rows")
+    check_case(run_attention_case(ctx, S, cb, [131072] * 4, lambda b: range(HKV), seed=3000))
 
 
 def test_config4_ragged_serving_step(env):
     ctx, S, cb = env
     lens = [int(n) for n in synth.ragged_lengths(64, 1024, 65536, seed=4)]
-    say(f"config 4: 64 ragged sequences, lengths {min(lens)}..{max(lens)}, append then attend")
-    order = np.argsort(lens)
-    picks = [int(order[0]), int(order[-1]), int(order[len(order) // 2]), int(order[5]), int(order[-5]), 17]
-    pairs = [(b, (3 * i) % HKV) for i, b in enumerate(picks)]
-    err = run_attention_case(ctx, S, cb, lens, pairs, seed=4000, append=True)
-    assert err <= 2e-3
+    say(f"config 4: 64 ragged sequences, lengths {min(lens)}..{max(lens)}, decode step (append, then attend); "
+        "every sequence with one kv head, every kv head eight times")
+    check_case(run_attention_case(ctx, S, cb, lens, lambda b: [(b + b // HKV) % HKV], seed=4000, step=True))

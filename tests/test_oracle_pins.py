@@ -757,3 +757,28 @@ def test_deep_hybrid_attention_reductions(S, cb):
             lse_w = scipy.special.logsumexp(wk[b, h // 2, :w] @ q[b, h] * scale)
             a = 1 / (1 + math.exp(lse_w - lse_p))
             assert np.max(np.abs(full[b, h] - (a * none[b, h] + (1 - a) * only[b, h]))) <= 1e-12
+
+
+def test_stored_radius_saturates_at_the_largest_finite_binary16():
+    """Section 4.1 stores radii in 16 bits and is silent on what lies beyond the format's range.  Reading: the stored
+    radius saturates at 65504; the codes (the direction) are those of the exact vector, and DeQuant stays finite."""
+    S, cb = oracle.preconditioner(0), oracle.default_codebooks()
+    g = np.random.default_rng(5).standard_normal((4, 128))
+    x = np.stack([g[0], 3e4 * g[1], 1e6 * g[2], g[3]])
+    rec = oracle.encode(x, S, cb)
+    J, r = oracle.unpack(rec)
+    radii = r.view(np.float16).astype(np.float64)
+    assert np.all(np.isfinite(radii))
+    exact = np.linalg.norm((x @ S).reshape(4, 8, 16), axis=2)
+    assert np.all(radii[1][exact[1] > 65520] == 65504.0) and np.all(radii[2] == 65504.0)
+    small = exact < 65504
+    assert np.allclose(radii[small], exact[small], rtol=2.0 ** -11)
+    # the direction is unaffected by the scale: the codes of 1e6 * g equal those of g
+    assert np.array_equal(J[2], oracle.unpack(oracle.encode(g[2:3], S, cb))[0][0])
+    assert np.all(np.isfinite(oracle.decode(rec, S, cb)))
+    for bits in ((2, 2, 2),):
+        cbt = oracle.upper_codebooks(bits)
+        rec7 = oracle.encode_deep(x, S, cb, bits, cbt)
+        _, r7 = oracle.unpack_deep(rec7, bits)
+        r7 = r7.view(np.float16).astype(np.float64)
+        assert r7[2] == 65504.0 and np.isclose(r7[0], np.linalg.norm(g[0]), rtol=2.0 ** -11)
