@@ -81,13 +81,72 @@ union BOperand {
     uint32_t w[4];
 };
 
-/* Scatter the fields of block b of slot tau into the tile image (codes, then radii).  The image is shared by
- * the lanes of one wavefront and the fields of different slots share dwords: LDS atomics. */
+/* Scatter the fields of block b of slot tau into the tile image (codes, then radii), without branches: every
+ * field is shifted to its place inside a pair of dwords and OR-ed in.  The image is shared by the lanes of one
+ * wavefront and the fields of different slots share dwords: LDS atomics.  CLEAR = false: the image started as
+ * zeros (a tile written whole); CLEAR = true: it holds the tile's present contents and the field's bits are
+ * cleared first.  The positions are those of pq_layout.h, written out per plane. */
+template <bool CLEAR>
+__device__ __forceinline__ void put_pair(uint32_t *img, uint32_t at0, uint32_t at1, uint32_t field, uint32_t width, uint32_t sh)
+{
+    if (CLEAR) {
+        const uint64_t m = (uint64_t)((1u << width) - 1u) << sh;
+        atomicAnd(&img[at0], ~(uint32_t)m);
+        atomicAnd(&img[at1], ~(uint32_t)(m >> 32));
+    }
+    const uint64_t w = (uint64_t)field << sh;
+    atomicOr(&img[at0], (uint32_t)w);
+    atomicOr(&img[at1], (uint32_t)(w >> 32));
+}
+
 template <int KIND, bool CLEAR, bool DEEP>
 __device__ __forceinline__ void emit_block(uint32_t *img, int tau, int b, const BlockCodes &bc)
 {
-    pql_put_block<CLEAR>(img, KIND, tau, b, bc);
-    if (!DEEP) reinterpret_cast<uint16_t *>(img)[PQL_CODE_BYTES / 2 + pql_pos(KIND, tau, b).radius_half] = bc.radius;
+    PqBlockFields f;
+    f.l1 = bc.l1; f.g6[0] = bc.g0; f.g6[1] = bc.g1; f.c4 = bc.c4; f.radius = bc.radius;
+    const uint32_t q0 = pql_quarter_index(f, 0), q1 = pql_quarter_index(f, 1), q2 = pql_quarter_index(f, 2),
+                   q3 = pql_quarter_index(f, 3), bi = pql_block_index(f);
+    uint32_t radius_half;
+    if (KIND == PQ_KEY) {
+        /* dword d of the token's string: planes of 4, 4, 3 dwords per token, then one half per token */
+        auto at = [&](uint32_t d) {
+            return d < 4u ? 4u * tau + d : d < 8u ? (PQL_OFF_P1 / 4 - 4) + 4u * tau + d
+                 : d < 11u ? (PQL_OFF_P2 / 4 - 8) + 3u * tau + d : PQL_OFF_KP3 / 4 + ((uint32_t)tau >> 1);
+        };
+        const uint32_t bit = PQL_BLOCK_BITS * (uint32_t)b, d = bit >> 5, sh = bit & 31u;
+        /* the string's last half sits in a dword shared by two tokens */
+        const uint32_t sh1 = (d + 1u == 11u) ? 16u * ((uint32_t)tau & 1u) : 0u;
+        /* 46 bits reach into a third dword when they start above bit 18 (never in the string's last dwords) */
+        const bool third = sh > 18u;
+        const uint32_t a0 = at(d), a1 = at(d + 1u), a2 = at(third ? d + 2u : d);
+        if (CLEAR) {
+            const uint64_t m = ((1ull << PQL_BLOCK_BITS) - 1ull) << sh;
+            atomicAnd(&img[a0], ~(uint32_t)m);
+            atomicAnd(&img[a1], ~((uint32_t)(m >> 32) << sh1));
+            if (third) atomicAnd(&img[a2], ~(0x3FFFu >> (32u - sh)));
+        }
+        const uint32_t lo = q0 | (q1 << 10) | (q2 << 20) | (q3 << 30), hi = (q3 >> 2) | (bi << 8); /* 32 + 14 bits */
+        const uint64_t w = (((uint64_t)hi << 32) | lo) << sh;
+        atomicOr(&img[a0], (uint32_t)w);
+        atomicOr(&img[a1], (uint32_t)(w >> 32) << sh1);
+        if (third) atomicOr(&img[a2], hi >> (32u - sh));
+        radius_half = 8u * tau + b;
+    } else {
+        const uint32_t i = (uint32_t)tau >> 4, g = ((uint32_t)tau >> 2) & 3u, e = (uint32_t)tau & 3u, s = 4u * i + e;
+        /* dword d of lane lam's string: planes of 4, 4, 2 dwords per lane */
+        auto at = [&](uint32_t lam, uint32_t d) {
+            return d < 4u ? 4u * lam + d : d < 8u ? (PQL_OFF_P1 / 4 - 4) + 4u * lam + d : (PQL_OFF_P2 / 4 - 8) + 2u * lam + d;
+        };
+        const uint32_t bit = PQL_SLOT_BITS * s, d = bit >> 5, sh = bit & 31u;
+        /* the dword after a string's last one belongs to the next lane (or the next plane): it gets zeros */
+        const uint32_t lam0 = 16u * g + 2u * b;
+        put_pair<CLEAR>(img, at(lam0, d), at(lam0, d + 1u), q0 | (q1 << 10), PQL_SLOT_BITS, sh);
+        put_pair<CLEAR>(img, at(lam0 + 1u, d), at(lam0 + 1u, d + 1u), q2 | (q3 << 10), PQL_SLOT_BITS, sh);
+        const uint32_t bbit = 6u * s, base = PQL_OFF_VB / 4 + 3u * (8u * g + b) + (bbit >> 5);
+        put_pair<CLEAR>(img, base, base + 1u, bi, 6u, bbit & 31u);
+        radius_half = 16u * (8u * g + b) + s;
+    }
+    if (!DEEP) reinterpret_cast<uint16_t *>(img)[PQL_CODE_BYTES / 2 + radius_half] = bc.radius;
 }
 
 /* lanes 0..31: the value of lane + 32; lanes 32..63: the value of lane - 32 */
@@ -110,7 +169,7 @@ __device__ __forceinline__ uint32_t from_other_half(uint32_t x, int upper_half)
    S in A-operand order, 32 KB per bf16 term; one tile image per wavefront; the level-1 cell table of
    caller-set codebooks. */
 __shared__ uint4 sS[3 * 4 * 8 * 64];
-__shared__ uint32_t sImg[8][TileImage<false>::dwords];
+__shared__ __align__(16) uint32_t sImg[8][TileImage<false>::dwords];
 __shared__ PqDeviceConsts::Lut1Cell sLut[512];
 
 /* The tiles of one launch share: workgroup `block` of `n_blocks` takes every n_blocks-th group of
@@ -228,7 +287,7 @@ __device__ __forceinline__ void encode_tiles(const EncodeArgs &a, int block, int
 
         /* ---- tile image: zeros, or the tile's present contents if only part of it is written ---- */
         if (full) {
-            for (int c = lane; c < kImgDwords; c += 64) img[c] = 0u;
+            for (int c = lane; c < kImgDwords / 4; c += 64) reinterpret_cast<uint4 *>(img)[c] = make_uint4(0u, 0u, 0u, 0u);
         } else {
             const uint32_t *gc = reinterpret_cast<const uint32_t *>(gcodes);
             const uint32_t *gr = reinterpret_cast<const uint32_t *>(gradii);
