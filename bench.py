@@ -42,14 +42,27 @@ HBM_PEAK_GBS = 8000.0
 B, HQ, HKV, CTX, D = 16, 32, 8, 32768, 128
 N_CACHES = 3
 BYTES_PER_TOKEN_HEAD = 124  # 62-byte key record + 62-byte value record
-# HBM bytes per launch of pq_attn_partial_kernel on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled
-# by a plain copy of known size (profiles/attn_partial_cfg2_counters.txt): 522.5 MB read + 8.5 MB written.
-MEASURED_TRAFFIC_BYTES = 522.5e6 + 8.5e6
-# Secondary bound of the same kernel: vector-ALU issue.  Its tile loop holds 947 vector instructions per 64-token
-# tile of one kv head (compiled code, counted in the assembly listing); one SIMD issues one 64-lane vector
-# instruction per 4 cycles: 256 CUs x 4 SIMDs x 2.4 GHz / 4 = 614.4 G wavefront instructions/s at most.
-VALU_INSTR_PER_TILE = 947
+PROFILE_FILE = os.path.join(ROOT, "profiles", "attn_partial_cfg2_counters.txt")
+# Secondary bound of the dominant kernel: vector-ALU issue.  One SIMD issues at most one 64-lane vector instruction
+# per 4 cycles: 256 CUs x 4 SIMDs x 2.4 GHz / 4 = 614.4 G wavefront instructions/s.
 VALU_PEAK_GINSTR = 256 * 4 * 2.4 / 4.0
+
+
+def profile_figures():
+    """Counter figures of the dominant kernel on this workload, from the tracked rocprofv3 summary (lines
+    `name = value` under its "figures read by bench.py" heading; the file names the commit they were taken on).
+    They come from separate profiling runs of this same script: HBM bytes per launch (FETCH_SIZE / WRITE_SIZE scaled
+    by a plain copy of known size) and executed vector instructions per launch (SQ_INSTS_VALU).  {} if absent."""
+    out = {}
+    try:
+        with open(PROFILE_FILE) as f:
+            for line in f:
+                parts = line.split("=")
+                if len(parts) == 2 and parts[0].strip().replace("_", "").isalnum() and " " not in parts[0].strip():
+                    out[parts[0].strip()] = parts[1].strip()
+    except OSError:
+        pass
+    return out
 
 
 def main():
@@ -181,6 +194,27 @@ def main():
     pr_h = profile_end()
     enc_h_mtok = CTX * args.encode_steps / (pr_h["encode_ms"] * 1e-3) / 1e6 if pr_h["encode_ms"] > 0 else 0.0
     del hk_c, hk_r, hv_c, hv_r
+
+    # ---- online codebook fit (Section 4.1): the GPU half of pq_fit_codebooks -- rotate, polar transform, count
+    # every angle -- over the keys of one configs[1] sequence (8 kv heads x 32768 tokens = 262144 vectors)
+    fit_ws = torch.empty(Context.fit_workspace_bytes(), dtype=torch.uint8, device=dev)
+    fit_x = enc_inputs[0][0].permute(1, 0, 2)  # [tokens, heads, 128] view of the [heads, tokens, 128] stream
+    for i in range(3):
+        ctx.fit_count_angles(fit_x, fit_ws)
+    torch.cuda.synchronize()
+    fit_reps = max(args.encode_steps // 4, 2)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for i in range(fit_reps):
+        ctx.fit_count_angles(fit_x, fit_ws)
+    ev1.record()
+    torch.cuda.synchronize()
+    fit_ms = ev0.elapsed_time(ev1) / fit_reps
+    fit_vectors = fit_x.shape[0] * fit_x.shape[1]
+    t0 = time.perf_counter()
+    ctx.fit_cluster(fit_ws.cpu().numpy().view(np.uint32), 10)
+    fit_host_ms = 1e3 * (time.perf_counter() - t0)
+    del fit_ws
 
     # ---- hybrid line: the same quantised 32k-token prefix plus a bf16 window of 256 recent tokens per
     # sequence (the keys and values of the generation stage kept in 16 bits), pq_attn_decode_hybrid
@@ -395,6 +429,27 @@ def main():
     del layers4, kc, kr, vc, vr, ws4
     torch.cuda.empty_cache()
 
+    # ---- counter figures of the dominant kernel (separate profiling runs of this script, kept in profiles/) ----
+    figures = profile_figures()
+    traffic = None
+    if "fetch_bytes_per_launch" in figures and "write_bytes_per_launch" in figures:
+        traffic = float(figures["fetch_bytes_per_launch"]) + float(figures["write_bytes_per_launch"])
+    roofline_alu = None
+    if "sq_insts_valu_per_launch" in figures and kern_ms > 0:
+        valu = float(figures["sq_insts_valu_per_launch"])  # executed wavefront vector instructions, matrix ones included
+        ginstr = valu / (kern_ms * 1e-3) / 1e9
+        roofline_alu = {
+            "bound": "alu",
+            "kernel": "pq_attn_partial_kernel",
+            "achieved": round(ginstr, 1),
+            "peak": VALU_PEAK_GINSTR,
+            "unit": "G wavefront vector instructions/s",
+            "frac": round(ginstr / VALU_PEAK_GINSTR, 4),
+            "instructions_per_launch": valu,
+            "source": "SQ_INSTS_VALU of a separate rocprofv3 run (" + os.path.relpath(PROFILE_FILE, ROOT) + ", commit "
+                      + figures.get("commit", "?") + ") over the launch duration measured here",
+        }
+
     result = {
         "metric": "decode attn HBM GB/s on polar-quantized KV @32k ctx",
         "value": round(value, 1),
@@ -422,19 +477,13 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES,
-            "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated; separate profiling run)",
+            "traffic": traffic,
+            "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated; separate profiling runs, "
+                            "figures from " + os.path.relpath(PROFILE_FILE, ROOT) + ", taken on commit " + figures.get("commit", "?") + ")",
             "kernel_avg_ms": round(kern_ms, 5),
             "launches_timed": prof["attn_launches"],
         },
-        "roofline_alu": {
-            "bound": "alu",
-            "kernel": "pq_attn_partial_kernel",
-            "achieved": round(VALU_INSTR_PER_TILE * B * HKV * (CTX // 64) / (kern_ms * 1e-3) / 1e9, 1) if kern_ms > 0 else 0.0,
-            "peak": VALU_PEAK_GINSTR,
-            "unit": "G wavefront vector instructions/s",
-            "frac": round(VALU_INSTR_PER_TILE * B * HKV * (CTX // 64) / (kern_ms * 1e-3) / 1e9 / VALU_PEAK_GINSTR, 4) if kern_ms > 0 else 0.0,
-        },
+        "roofline_alu": roofline_alu,
         "encode": {
             "workload": "configs[1]: 8 kv heads x 32768 tokens, bf16 keys and values with outlier channels",
             "mtok_per_s": round(enc_mtok, 2),
@@ -448,6 +497,15 @@ def main():
             "mtok_per_s": round(enc_h_mtok, 2),
             "gb_per_s": round(enc_h_mtok * 1e6 * enc_bytes_per_token / 1e9, 1),
             "frac_of_hbm_roofline": round(enc_h_mtok * 1e6 * enc_bytes_per_token / 1e9 / HBM_PEAK_GBS, 4),
+        },
+        "fit": {
+            "workload": "online codebooks (Section 4.1) from the keys of one configs[1] sequence: pq_fit_count_angles "
+                        "(clear, rotate, polar transform, 120 angles per vector into histograms) on the launch stream, "
+                        "then pq_fit_cluster (10 k-means rounds on the counts, host)",
+            "vectors": fit_vectors,
+            "count_ms": round(fit_ms, 4),
+            "g_vectors_per_s": round(fit_vectors / (fit_ms * 1e-3) / 1e9, 3),
+            "cluster_host_ms": round(fit_host_ms, 3),
         },
         "hybrid": {
             "workload": "configs[2] prefix + 256 unquantised (bf16) recent tokens per sequence, pq_attn_decode_hybrid "
