@@ -278,6 +278,51 @@ def test_encode_degenerate_inputs(env):
         ctx.encode_kv(torch.zeros((65, 1, 128), dtype=torch.bfloat16, device=DEV), PQ_KEY, codes, radii)
 
 
+def test_extreme_block_norms(env):
+    """Block norms beyond the binary16 range: the stored radius saturates at 65504 (0x7BFF) in the library exactly as
+    in the oracle (Section 4.1 fixes 16-bit radii and is silent beyond their range), codes are unaffected, and
+    attention on such records stays finite and within the usual bound."""
+    ctx, S, cb = env
+    say("extreme block norms: radii saturate at the largest finite binary16")
+    g = torch.Generator().manual_seed(77)
+    n, H = 130, 2
+    x = torch.randn((n, H, 128), generator=g, dtype=torch.float32)
+    x[0::3] *= 3.0e4                      # every block of these vectors has a norm far beyond 65504
+    x[1::3, :, 32:48] *= 1.0e5            # one block beyond the range, the others ordinary
+    for kind in (PQ_KEY, PQ_VALUE):
+        codes, radii = gpu_encode(ctx, x, kind, 192)
+        rec = canonical_both_ways(ctx, kind, codes, radii, 0, n)
+        rec_or, psi, y = oracle_records(x, S, cb)
+        st, rg, ro = helpers.check_codes(rec.reshape(-1, 62), rec_or.reshape(-1, 62), psi.reshape(-1, 120))
+        helpers.check_radii(rg, ro, y.reshape(-1, 128))
+        sat = ro == 0x7BFF
+        assert sat.sum() >= (n // 3) * H * 8 and np.array_equal(rg[sat], ro[sat])
+        assert not np.any((rg & 0x7C00) == 0x7C00)  # no infinity, no NaN
+    # attention on the oracle's records of such vectors: huge values under ordinary keys, and huge keys
+    lens = [n, n]
+    rec_x = oracle_records(x, S, cb)[0]
+    rec_n = oracle_records(torch.randn((n, H, 128), generator=g, dtype=torch.float32), S, cb)[0]
+    pool = 2 * 192
+    kc, kr = Context.alloc_cache(H, pool, DEV)
+    vc, vr = Context.alloc_cache(H, pool, DEV)
+    k_rec = np.zeros((H, pool, 62), dtype=np.uint8)
+    v_rec = np.zeros((H, pool, 62), dtype=np.uint8)
+    for b, (rk, rv) in enumerate(((rec_n, rec_x), (rec_x, rec_n))):
+        k_rec[:, 192 * b : 192 * b + n] = rk
+        v_rec[:, 192 * b : 192 * b + n] = rv
+        helpers.upload_records(PQ_KEY, rk, kc, kr, 192 * b)
+        helpers.upload_records(PQ_VALUE, rv, vc, vr, 192 * b)
+    starts = np.array([0, 192], dtype=np.int64)
+    q = synth.queries(2, 4, seed=78)
+    got = gpu_attention(ctx, q, (kc, kr, vc, vr), starts, lens)
+    ref = oracle.attention(q.to(torch.float64).numpy(), k_rec, v_rec, starts, np.array(lens, np.int32), S, cb,
+                           helpers.softmax_scale())
+    assert np.all(np.isfinite(got))
+    errs = [helpers.rel_l2(got[b], ref[b]) for b in range(2)]
+    say(f"  attention rel L2: huge values {errs[0]:.2e}, huge keys {errs[1]:.2e}")
+    assert max(errs) <= 2e-3
+
+
 # ---------------------------------------------------------------------------
 # attention
 # ---------------------------------------------------------------------------
