@@ -124,8 +124,9 @@ pq_status pq_set_codebooks(pq_ctx *ctx, const double *cb);
 /* Online codebook construction (Section 4.1; line 3 of Algorithm 1 fitted to the input
  * instead of the analytic densities): the vectors x (device, layout and strides as for
  * pq_encode_kv, keys and values alike) are rotated with the context's S, their angles
- * are counted on the GPU into fine per-level histograms (bin width 2 pi / 8192 at level
- * 1, (pi/2) / 2048 above), and `iterations` k-means rounds -- nearest centroid, then
+ * are counted on the GPU into fine per-level histograms (8192 bins over [0, 2 pi) at
+ * level 1, 2048 over [0, pi/2] above; bins uniform in v / (u + v) of a node's two inputs,
+ * 4.9e-4 to 9.8e-4 rad wide), and `iterations` k-means rounds -- nearest centroid, then
  * centroid := mean of its cell -- run on the histograms from cb_init (host, 28
  * centroids; NULL: the context's current codebooks).  The paper seeds k-means++ at
  * random; a fixed seed codebook makes the result a function of the data.  cb_out

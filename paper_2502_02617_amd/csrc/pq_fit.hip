@@ -3,19 +3,28 @@
  * line 3 of Algorithm 1 in its online variant: 1-D k-means on the angles of the
  * polar-transformed inputs), for gfx950.
  *
- * The heavy part runs on the GPU: every input vector is rotated (y = x S, fp32),
- * its 120 angles are formed (procedure Polar) and counted into fine histograms,
+ * The heavy part runs on the GPU: every input vector is rotated (y = x S), its
+ * 120 angles are formed (procedure Polar) and counted into fine histograms,
  * one per level (8192 bins over [0, 2 pi) for level 1, 2048 over [0, pi/2] for
  * levels 2-4; for a full-depth context 2048 more for each of levels 5-7, see
  * pq_fit_codebooks_deep).  The k-means rounds then run on the bin counts on the host
- * in fp64 -- each bin stands for its centre -- which costs microseconds and is
- * where the result is wanted (pq_set_codebooks takes host centroids).
+ * in fp64, which costs well under a millisecond and is where the result is
+ * wanted (pq_set_codebooks takes host centroids).
  *
- * Kernel: a workgroup keeps S (64 KB, fp32) and its four histograms (56 KB) in
- * LDS and walks over tiles of 32 vectors: the tile is staged as fp32, thread
- * (half, j) accumulates coordinate j of 16 vectors (S[i][j] from LDS once per
- * 16 products, x as LDS broadcasts), then thread (vector, block) runs the polar
- * recursion of one 16-coordinate block and bumps the bins with LDS atomics.
+ * Kernel: one wavefront per tile of 64 vectors, sixteen wavefronts per
+ * workgroup, S and the histograms in LDS.
+ *   Rotation on the matrix cores as in the encode kernel (same operand image of
+ *   S, same register layout of the result: a lane ends up with complete blocks
+ *   of 16 rotated coordinates of one vector), with the two leading bf16 terms
+ *   of S (16 significant bits; bf16 inputs are exact operands, fp32 inputs are
+ *   split into two terms and the three products above 2^-16 are used): the
+ *   angle error of 1e-5 rad is a hundredth of a bin.
+ *   Bins are uniform in the pseudo-angle t = v / (u + v) of a node's two inputs
+ *   (level 1: quadrant + t, with |y| or |x| on top so that it grows with the
+ *   angle), which is monotone in the angle and costs a reciprocal instead of
+ *   an arctangent: bin edge k / 2048 is the angle atan2(k, 2048 - k).  The
+ *   host part knows the edges and treats the angles of a bin as spread evenly
+ *   between them.
  * Counts are integers: the result does not depend on scheduling.
  */
 #include "pq_common.h"
@@ -28,146 +37,192 @@ namespace {
 
 constexpr int kBins1 = 8192, kBinsU = 2048;
 constexpr int kHistSize = kBins1 + 3 * kBinsU; /* 14336 counters */
-constexpr int kHistUpper = 3 * kBinsU;         /* levels 5..7 (full-depth recursion): 6144 more, in global memory */
-constexpr int kFitThreads = 256;
-constexpr int kTileVecs = 32;
-constexpr float kTwoPi = 6.28318530717958647692f, kHalfPi = 1.57079632679489661923f;
+constexpr int kHistUpper = 3 * kBinsU;         /* levels 5..7 (full-depth recursion): 6144 more */
+constexpr int kFitWaves = 16, kFitThreads = kFitWaves * 64;
+constexpr int kTileVecs = 64;
+constexpr int kFitTerms = 2;                   /* bf16 terms of S that take part */
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 struct FitArgs {
     const void *x;
     int64_t ld_token, ld_head, n_tokens;
     int n_heads;
     int64_t tiles_per_head, n_items;
-    const float *S;     /* S[i*128 + j] */
-    uint32_t *hist;     /* [kHistSize], zeroed by the caller of the kernel */
-    uint32_t *hist_up;  /* [kHistUpper] or NULL: angles of levels 5..7 */
+    const uint4 *S_bf16x3; /* the encode kernel's operand image of S, term-major */
+    uint32_t *hist;        /* [kHistSize], zeroed before the launch */
+    uint32_t *hist_up;     /* [kHistUpper] or NULL: angles of levels 5..7 */
 };
 
-template <int XT>
-__global__ __launch_bounds__(kFitThreads) void pq_angle_histogram_kernel(FitArgs a)
+union FitOperand {
+    bf16x8 v;
+    uint4 q;
+    uint32_t w[4];
+};
+
+__device__ __forceinline__ uint32_t fit_bf16_rne(float f)
 {
-    __shared__ float sS[PQ_D * PQ_D];
-    __shared__ float sx[kTileVecs][PQ_D];
-    __shared__ float sy[kTileVecs][PQ_D + 4]; /* +4: the 16-float rows of different vectors start in different banks */
-    __shared__ uint32_t sh[kHistSize];
-    const int tid = threadIdx.x;
-    {   /* S: 16 float4 per thread, requested in two batches of 8 before they are stored */
-        const float4 *src = reinterpret_cast<const float4 *>(a.S);
-        float4 *dst = reinterpret_cast<float4 *>(sS);
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+/* bin of the angle of (u, v), both >= 0, among kBinsU bins uniform in t = v / (u + v); atan2(0, 0) counts as 0 */
+__device__ __forceinline__ int upper_bin(float u, float v)
+{
+    const float t = v * __builtin_amdgcn_rcpf(fmaxf(u + v, 1e-37f));
+    return min((int)(t * (float)kBinsU), kBinsU - 1);
+}
+
+/* Angles of one block of 16 rotated coordinates into the LDS histograms; returns the block's radius. */
+__device__ __forceinline__ float count_block_angles(const f32x16 &y, uint32_t *sh)
+{
+    float r[8];
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            float4 stage[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) stage[i] = src[tid + (8 * half + i) * kFitThreads];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) dst[tid + (8 * half + i) * kFitThreads] = stage[i];
-        }
+    for (int p = 0; p < 8; ++p) {
+        const float a = y[2 * p], b = y[2 * p + 1];
+        const float fa = fabsf(a), fb = fabsf(b);
+        const uint32_t sa = __float_as_uint(a) >> 31, sb = __float_as_uint(b) >> 31;
+        const uint32_t odd = sa ^ sb, quadrant = 2u * sb + odd; /* [0, 2 pi): (+,+), (-,+), (-,-), (+,-) */
+        const float t = (odd ? fa : fb) * __builtin_amdgcn_rcpf(fmaxf(fa + fb, 1e-37f));
+        const int bin = (int)quadrant * (kBins1 / 4) + min((int)(t * (float)(kBins1 / 4)), kBins1 / 4 - 1);
+        atomicAdd(&sh[bin], 1u);
+        r[p] = sqrtf(a * a + b * b);
     }
-    for (int c = tid; c < kHistSize; c += kFitThreads) sh[c] = 0u;
+    int base = kBins1;
+#pragma unroll
+    for (int n = 4; n >= 1; n >>= 1) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (p < n) {
+                const float u = r[2 * p], v = r[2 * p + 1];
+                atomicAdd(&sh[base + upper_bin(u, v)], 1u);
+                r[p] = sqrtf(u * u + v * v);
+            }
+        }
+        base += kBinsU;
+    }
+    return r[0];
+}
+
+template <int XT>
+__global__ __launch_bounds__(kFitThreads, 1) void pq_angle_histogram_kernel(FitArgs a)
+{
+    __shared__ uint4 sS[kFitTerms * 4 * 8 * 64];    /* 64 KB */
+    __shared__ uint32_t sh[kHistSize + kHistUpper]; /* 80 KB */
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    {
+        uint4 stage[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) stage[i] = a.S_bf16x3[tid + i * kFitThreads];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sS[tid + i * kFitThreads] = stage[i];
+    }
+    for (int c = tid; c < kHistSize + kHistUpper; c += kFitThreads) sh[c] = 0u;
     __syncthreads();
 
-    const int j = tid & 127, vhalf = tid >> 7;
-    for (int64_t item = blockIdx.x; item < a.n_items; item += gridDim.x) {
+    const int j = lane & 31, H = lane >> 5; /* vector within a 32-vector half, lane half */
+    constexpr int NXT = (XT == PQ_BF16) ? 1 : 2; /* bf16 terms of x */
+    for (int64_t item = (int64_t)blockIdx.x * kFitWaves + wave; item < a.n_items; item += (int64_t)gridDim.x * kFitWaves) {
         const int head = (int)(item / a.tiles_per_head);
         const int64_t t0 = (item % a.tiles_per_head) * kTileVecs;
-        const int n_valid = (int)min((int64_t)kTileVecs, a.n_tokens - t0);
-        /* stage the tile as fp32 (rows beyond the input are zero and are not counted below) */
-        for (int c = tid; c < kTileVecs * PQ_D; c += kFitThreads) {
-            const int v = c >> 7, k = c & 127;
-            float val = 0.f;
-            if (v < n_valid) {
-                const int64_t at = (t0 + v) * a.ld_token + (int64_t)head * a.ld_head + k;
-                if (XT == PQ_BF16) val = __uint_as_float((uint32_t)static_cast<const uint16_t *>(a.x)[at] << 16);
-                else val = static_cast<const float *>(a.x)[at];
-            }
-            sx[v][k] = val;
-        }
-        __syncthreads();
-        /* y[v][j] = sum_i x[v][i] S[i][j] for the 16 vectors of this thread's half */
-        float acc[16];
+        float rb[2][4]; /* radii of blocks 4H .. 4H+3 of this lane's two vectors */
+        bool valid[2];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-        for (int i = 0; i < PQ_D; i += 4) {
-            const float s0 = sS[(i + 0) * PQ_D + j], s1 = sS[(i + 1) * PQ_D + j];
-            const float s2 = sS[(i + 2) * PQ_D + j], s3 = sS[(i + 3) * PQ_D + j];
+        for (int v = 0; v < 2; ++v) {
+            const int64_t tok = t0 + 32 * v + j;
+            valid[v] = tok < a.n_tokens;
+            /* a lane without a vector reads the tile's first one again and counts nothing */
+            const int64_t at = (valid[v] ? tok : t0) * a.ld_token + (int64_t)head * a.ld_head;
+            /* B operands: this lane's 8-coordinate slices (coordinates 64 H + 8 ks .. + 7) of its vector */
+            FitOperand xb[NXT][8];
+            if constexpr (XT == PQ_BF16) {
+                const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.x) + at);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float4 xv = *reinterpret_cast<const float4 *>(&sx[16 * vhalf + v][i]);
-                acc[v] = fmaf(xv.x, s0, acc[v]);
-                acc[v] = fmaf(xv.y, s1, acc[v]);
-                acc[v] = fmaf(xv.z, s2, acc[v]);
-                acc[v] = fmaf(xv.w, s3, acc[v]);
-            }
-        }
+                for (int ks = 0; ks < 8; ++ks) xb[0][ks].q = xr[8 * H + ks];
+            } else {
+                const float4 *xr = reinterpret_cast<const float4 *>(static_cast<const float *>(a.x) + at);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sy[16 * vhalf + v][j] = acc[v];
-        __syncthreads();
-        /* procedure Polar on block (tid & 7) of vector (tid >> 3); every angle goes into its bin */
-        {
-            const int v = tid >> 3, b = tid & 7;
-            float rb = 0.f; /* radius of the block */
-            if (v < n_valid) {
-                float r[16];
+                for (int ks = 0; ks < 8; ++ks) {
+                    const float4 p0 = xr[16 * H + 2 * ks], p1 = xr[16 * H + 2 * ks + 1];
+                    const float f[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
 #pragma unroll
-                for (int k = 0; k < 16; ++k) r[k] = sy[v][16 * b + k];
+                    for (int e = 0; e < 8; e += 2) {
+                        uint32_t hi[2], lo[2];
 #pragma unroll
-                for (int p = 0; p < 8; ++p) {
-                    float ang = atan2f(r[2 * p + 1], r[2 * p]);
-                    if (ang < 0.f) ang += kTwoPi;
-                    int bin = (int)(ang * ((float)kBins1 / kTwoPi));
-                    bin = bin < 0 ? 0 : (bin > kBins1 - 1 ? kBins1 - 1 : bin);
-                    atomicAdd(&sh[bin], 1u);
-                    r[p] = sqrtf(r[2 * p] * r[2 * p] + r[2 * p + 1] * r[2 * p + 1]);
-                }
-                int n = 4, base = kBins1;
-#pragma unroll
-                for (int l = 2; l <= 4; ++l) {
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) {
-                        if (p < n) {
-                            const float ang = atan2f(r[2 * p + 1], r[2 * p]); /* both >= 0: in [0, pi/2] */
-                            int bin = (int)(ang * ((float)kBinsU / kHalfPi));
-                            bin = bin < 0 ? 0 : (bin > kBinsU - 1 ? kBinsU - 1 : bin);
-                            atomicAdd(&sh[base + bin], 1u);
-                            r[p] = sqrtf(r[2 * p] * r[2 * p] + r[2 * p + 1] * r[2 * p + 1]);
+                        for (int z = 0; z < 2; ++z) {
+                            hi[z] = fit_bf16_rne(f[e + z]);
+                            lo[z] = fit_bf16_rne(f[e + z] - __uint_as_float(hi[z] << 16));
                         }
+                        xb[0][ks].w[e / 2] = hi[0] | (hi[1] << 16);
+                        xb[NXT - 1][ks].w[e / 2] = lo[0] | (lo[1] << 16);
                     }
-                    n >>= 1;
-                    base += kBinsU;
                 }
-                rb = r[0];
             }
-            if (a.hist_up) {
-                /* levels 5..7 join the eight block radii of a vector, which sit in eight neighbouring lanes:
-                   the node of a level lives in the lane of its first block and fetches its sibling's radius
-                   with a shuffle.  A vector gives 7 angles here: they are counted in global memory (the
-                   LDS is full). */
-                float r = rb;
 #pragma unroll
-                for (int l = 0; l < 3; ++l) {
-                    const float sib = __shfl_xor(r, 1 << l);
-                    if (v < n_valid && (b & ((2 << l) - 1)) == 0) {
-                        const float ang = atan2f(sib, r); /* both >= 0: in [0, pi/2] */
-                        int bin = (int)(ang * ((float)kBinsU / kHalfPi));
-                        bin = bin < 0 ? 0 : (bin > kBinsU - 1 ? kBinsU - 1 : bin);
-                        atomicAdd(&a.hist_up[l * kBinsU + bin], 1u);
-                    }
-                    r = sqrtf(r * r + sib * sib);
+            for (int rt = 0; rt < 4; ++rt) {
+                /* D[i][j] = sum_k S[k][col(rt, i)] x[j][k]: lane (H, j) receives rotated coordinates
+                   16 (4 H + rt) .. + 15 of vector j */
+                f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                    for (int term = kFitTerms - 1; term >= 0; --term)
+#pragma unroll
+                        for (int xt = 0; xt < NXT; ++xt) {
+                            if (term + xt > 1) continue; /* below 2^-16 of the leading product */
+                            FitOperand sa;
+                            sa.q = sS[((term * 4 + rt) * 8 + ks) * 64 + lane];
+                            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa.v, xb[xt][ks].v, acc, 0, 0, 0);
+                        }
+                const float r = valid[v] ? count_block_angles(acc, sh) : 0.f;
+                rb[v][rt] = r;
+            }
+        }
+        if (a.hist_up) {
+            /* levels 5 and 6 inside the lane (blocks 4H .. 4H+3), level 7 joins the two lane halves */
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                const float r50 = sqrtf(rb[v][0] * rb[v][0] + rb[v][1] * rb[v][1]);
+                const float r51 = sqrtf(rb[v][2] * rb[v][2] + rb[v][3] * rb[v][3]);
+                const float r6 = sqrtf(r50 * r50 + r51 * r51);
+                const float other = __shfl_xor(r6, 32);
+                if (valid[v]) {
+                    uint32_t *up = sh + kHistSize;
+                    atomicAdd(&up[upper_bin(rb[v][0], rb[v][1])], 1u);
+                    atomicAdd(&up[upper_bin(rb[v][2], rb[v][3])], 1u);
+                    atomicAdd(&up[kBinsU + upper_bin(r50, r51)], 1u);
+                    if (H == 0) atomicAdd(&up[2 * kBinsU + upper_bin(r6, other)], 1u);
                 }
             }
         }
-        __syncthreads();
     }
+    __syncthreads();
     for (int c = tid; c < kHistSize; c += kFitThreads)
         if (sh[c]) atomicAdd(&a.hist[c], sh[c]);
+    if (a.hist_up)
+        for (int c = tid; c < kHistUpper; c += kFitThreads)
+            if (sh[kHistSize + c]) atomicAdd(&a.hist_up[c], sh[kHistSize + c]);
+}
+
+/* angle of the lower edge of bin b of a level's histogram (b = bins gives the upper end of the range) */
+double bin_edge(int b, int bins, bool level1)
+{
+    const double half_pi = 1.57079632679489661923132169163975144;
+    const int per = level1 ? bins / 4 : bins; /* bins per quarter turn */
+    const int q = b / per, k = b % per;
+    return q * half_pi + atan2((double)k, (double)(per - k));
 }
 
 /* k-means rounds on one level's histogram.  The angles of a bin are taken as spread evenly over
    it: a bin that a cell boundary (midpoint of two centroids) cuts gives each side its share of
    the count, centred on its part of the bin; an uncut bin stands for its centre.  Nearest
    centroid by linear distance (procedure Quant); a centroid whose cell is empty stays. */
-void lloyd_on_histogram(const uint32_t *hist, int bins, double width, int K, int iterations, double *c)
+void lloyd_on_histogram(const uint32_t *hist, int bins, bool level1, int K, int iterations, double *c)
 {
+    std::vector<double> edges((size_t)bins + 1);
+    for (int b = 0; b <= bins; ++b) edges[b] = bin_edge(b, bins, level1);
     for (int it = 0; it < iterations; ++it) {
         double sum[16] = {0};
         double num[16] = {0};
@@ -178,7 +233,7 @@ void lloyd_on_histogram(const uint32_t *hist, int bins, double width, int K, int
         int k = 0;
         for (int b = 0; b < bins; ++b) {
             if (!hist[b]) continue;
-            const double lo = b * width, hi = lo + width, per_rad = (double)hist[b] / width;
+            const double lo = edges[b], hi = edges[b + 1], per_rad = (double)hist[b] / (hi - lo);
             while (k + 1 < K && edge[k + 1] <= lo) ++k;
             double from = lo;
             int q = k;
@@ -262,10 +317,11 @@ extern "C" pq_status pq_fit_count_angles(const pq_ctx *ctx, const void *x, pq_dt
     a.x = x; a.ld_token = ld_token; a.ld_head = ld_head; a.n_tokens = n_tokens; a.n_heads = n_heads;
     a.tiles_per_head = (n_tokens + kTileVecs - 1) / kTileVecs;
     a.n_items = a.tiles_per_head * n_heads;
-    a.S = ds->S_f32;
+    a.S_bf16x3 = reinterpret_cast<const uint4 *>(ds->S_bf16x3);
     a.hist = hist;
     a.hist_up = upper ? hist + kHistSize : nullptr;
-    int64_t blocks = a.n_items < 256 ? a.n_items : 256;
+    int64_t blocks = (a.n_items + kFitWaves - 1) / kFitWaves;
+    if (blocks > 256) blocks = 256;
     if (xt == PQ_BF16) hipLaunchKernelGGL(pq_angle_histogram_kernel<PQ_BF16>, dim3((unsigned)blocks), dim3(kFitThreads), 0, s, a);
     else hipLaunchKernelGGL(pq_angle_histogram_kernel<PQ_F32>, dim3((unsigned)blocks), dim3(kFitThreads), 0, s, a);
     PQ_HIP_TRY(hipGetLastError());
@@ -282,15 +338,13 @@ extern "C" pq_status pq_fit_cluster(const pq_ctx *ctx, const uint32_t *hist, con
     const pq_status st = check_start(ctx, cb_init, cbt_init, upper, c, ct);
     if (st != PQ_OK) return st;
     const int off[4] = {0, 16, 20, 24};
-    const double pi = 3.14159265358979323846264338327950288;
-    lloyd_on_histogram(hist, kBins1, 2.0 * pi / kBins1, 16, iterations, c);
+    lloyd_on_histogram(hist, kBins1, true, 16, iterations, c);
     for (int l = 1; l < 4; ++l)
-        lloyd_on_histogram(hist + kBins1 + (l - 1) * kBinsU, kBinsU, 0.5 * pi / kBinsU, 4, iterations, c + off[l]);
+        lloyd_on_histogram(hist + kBins1 + (l - 1) * kBinsU, kBinsU, false, 4, iterations, c + off[l]);
     memcpy(cb_out, c, sizeof(c));
     if (upper) {
         for (int l = 0; l < 3; ++l)
-            lloyd_on_histogram(hist + kHistSize + l * kBinsU, kBinsU, 0.5 * pi / kBinsU, 1 << ctx->upper_bits[l],
-                               iterations, ct[l]);
+            lloyd_on_histogram(hist + kHistSize + l * kBinsU, kBinsU, false, 1 << ctx->upper_bits[l], iterations, ct[l]);
         memcpy(cbt_out, ct, sizeof(ct));
     }
     return PQ_OK;

@@ -210,7 +210,7 @@ def test_deep_online_codebook_fit(bits):
     ref_t = oracle.fit_upper_codebooks(xs, S, bits, base_t, iters)
     d_low = np.max(np.abs(got - ref))
     d_up = max(np.max(np.abs(got_t[l, :1 << bits[l]] - ref_t[l, :1 << bits[l]])) for l in range(3))
-    say(f"  max centroid difference: levels 1-4 {d_low:.2e} rad, levels 5-7 {d_up:.2e} rad (bin 7.7e-4)")
+    say(f"  max centroid difference: levels 1-4 {d_low:.2e} rad, levels 5-7 {d_up:.2e} rad (bins 4.9e-4 .. 9.8e-4 rad)")
     assert d_low <= 3e-4 and d_up <= 3e-4
     # zero rounds give the start back; an explicit start is honoured
     z, z_t = ctx.fit_codebooks_deep(x.to(DEV), 0)
