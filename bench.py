@@ -505,6 +505,8 @@ def main():
             "vectors": fit_vectors,
             "count_ms": round(fit_ms, 4),
             "g_vectors_per_s": round(fit_vectors / (fit_ms * 1e-3) / 1e9, 3),
+            "frac_of_hbm_roofline": round(fit_vectors * 256 / (fit_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),  # 256 B read per vector
+            "cluster_rounds": 10,
             "cluster_host_ms": round(fit_host_ms, 3),
         },
         "hybrid": {
