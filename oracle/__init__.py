@@ -418,3 +418,77 @@ def attention_hybrid_deep(q, k_rec, v_rec, seq_start, ctx_len, win_k, win_v, win
                 p = np.exp(s - s.max())
                 out[b, hk * G + g] = (p / p.sum()) @ Vh
     return out
+
+
+# ---- general format: any depth 1..7, any bits per level (remark after Theorem 1; Definition 1) ----
+def _gbits(bits):
+    b = np.ascontiguousarray(bits, dtype=np.int32)
+    return b, b.ctypes.data_as(ctypes.POINTER(ctypes.c_int))
+
+
+def general_nang(L):
+    return sum(D >> l for l in range(1, L + 1))
+
+
+def general_record_bytes(L, bits):
+    b, bp = _gbits(bits)
+    n = lib().orc_general_record_bytes(ctypes.c_int(L), bp)
+    if n < 0:
+        raise ValueError("bad depth or bits")
+    return int(n)
+
+
+def general_codebooks(L, bits):
+    """Lloyd-Max centroids of levels 1..L, concatenated (level l: 2^bits[l-1] entries)."""
+    b, bp = _gbits(bits)
+    out = np.zeros(sum(1 << int(w) for w in b[:L]), dtype=np.float64)
+    if lib().orc_general_codebooks(ctypes.c_int(L), bp, _p(out)):
+        raise RuntimeError("codebook iteration failed")
+    return out
+
+
+def encode_general(x, S, L, bits, cbg, want_psi=False, want_codes=False):
+    x = _f64(x).reshape(-1, D)
+    S, cbg = _f64(S), _f64(cbg)
+    b, bp = _gbits(bits)
+    n, rb, nang = x.shape[0], general_record_bytes(L, bits), general_nang(L)
+    rec = np.zeros((n, rb), dtype=np.uint8)
+    psi = np.zeros((n, nang), dtype=np.float64) if want_psi else None
+    J = np.zeros((n, nang), dtype=np.int32) if want_codes else None
+    lib().orc_encode_general(_p(x), ctypes.c_int64(n), _p(S), ctypes.c_int(L), bp, _p(cbg), _p(rec, ctypes.c_uint8),
+                             _p(psi) if want_psi else None, _p(J, ctypes.c_int32) if want_codes else None)
+    res = [rec]
+    if want_psi:
+        res.append(psi)
+    if want_codes:
+        res.append(J)
+    return res[0] if len(res) == 1 else tuple(res)
+
+
+def decode_general(rec, S, L, bits, cbg, rotated=False):
+    rb = general_record_bytes(L, bits)
+    rec = np.ascontiguousarray(rec, dtype=np.uint8).reshape(-1, rb)
+    S, cbg = _f64(S), _f64(cbg)
+    b, bp = _gbits(bits)
+    out = np.zeros((rec.shape[0], D), dtype=np.float64)
+    lib().orc_decode_general(_p(rec, ctypes.c_uint8), ctypes.c_int64(rec.shape[0]), _p(S), ctypes.c_int(L), bp, _p(cbg),
+                             ctypes.c_int(1 if rotated else 0), _p(out))
+    return out
+
+
+def attention_general(q, k_rec, v_rec, seq_start, ctx_len, S, L, bits, cbg, scale):
+    """q [B, Hq, 128]; k_rec, v_rec [Hkv, plane_tokens, record bytes]."""
+    q = _f64(q)
+    B, Hq, _ = q.shape
+    k_rec = np.ascontiguousarray(k_rec, dtype=np.uint8)
+    v_rec = np.ascontiguousarray(v_rec, dtype=np.uint8)
+    Hkv, plane = k_rec.shape[0], k_rec.shape[1]
+    S, cbg = _f64(S), _f64(cbg)
+    b, bp = _gbits(bits)
+    ss = np.ascontiguousarray(seq_start, dtype=np.int64)
+    cl = np.ascontiguousarray(ctx_len, dtype=np.int32)
+    out = np.zeros((B, Hq, D), dtype=np.float64)
+    lib().orc_attention_general(_p(q), ctypes.c_int(B), ctypes.c_int(Hq), ctypes.c_int(Hkv), _p(k_rec, ctypes.c_uint8),
+                                _p(v_rec, ctypes.c_uint8), _p(ss, ctypes.c_int64), _p(cl, ctypes.c_int32),
+                                ctypes.c_int64(plane), _p(S), ctypes.c_int(L), bp, _p(cbg), ctypes.c_double(scale), _p(out))
+    return out

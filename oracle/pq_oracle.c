@@ -191,7 +191,9 @@ int orc_codebook(int level, int K, double *centroids, double *boundaries)
             if (dlt > delta) delta = dlt;
             centroids[k] = c;
         }
-        if (delta < 1e-15) break;
+        /* the fixed point is reached when the centroids stop moving; with more cells rounding in the
+           quadrature keeps successive iterates a few 1e-16 apart, which is as converged as it gets */
+        if (delta < 1e-15 || (it > 500 && delta < 1e-13)) break;
     }
     boundaries[0] = lo; boundaries[K] = hi;
     for (int k = 1; k < K; ++k) boundaries[k] = 0.5 * (centroids[k - 1] + centroids[k]);
@@ -898,6 +900,181 @@ void orc_fit_codebooks(const double *x, int64_t n, const double *S, const double
         off += cnt; cnt /= 2;
     }
     free(psi);
+}
+
+/* ================================================================== */
+/* General format: any recursion depth L in 1..7 and any number of     */
+/* bits per level (Definition 1 recurses to log2 d; the remark after    */
+/* Theorem 1 leaves the codebook size of each level free; Section 4.1   */
+/* is the instance L = 4, bits 4/2/2/2).  d = 128.                      */
+/*   bits[l-1]   bits of level l, 1..4 (level 1 up to 6)               */
+/*   cbg         centroids of levels 1..L one after another, level l   */
+/*               holding 2^bits[l-1] entries                           */
+/*   record      the codes of level 1 (64 of them, in coordinate       */
+/*               order), then level 2 (32), ..., each bits[l-1] wide,  */
+/*               written into one little-endian bit stream (bit p of   */
+/*               the stream is bit p & 7 of byte p >> 3), padded to a  */
+/*               whole byte; then the 128 >> L radii r^(L) as          */
+/*               little-endian binary16 (saturating like the others).  */
+/* Pinned by: L = 4 with bits 4/2/2/2 gives the codes, radii and       */
+/* decoded vectors of the Section 4.1 functions above; exact inverse   */
+/* with exact angles at every depth (orc_polar pins); Lloyd-Max        */
+/* conditions of the larger codebooks by independent quadrature; the   */
+/* predicted reconstruction error; textbook softmax.                   */
+/* ================================================================== */
+static int orc_general_nang(int L)
+{
+    int n = 0;
+    for (int l = 1; l <= L; ++l) n += ORC_D >> l;
+    return n;
+}
+
+int orc_general_record_bytes(int L, const int *bits)
+{
+    if (L < 1 || L > 7) return -1;
+    int nbits = 0;
+    for (int l = 1; l <= L; ++l) {
+        if (bits[l - 1] < 1 || bits[l - 1] > 6) return -1;
+        nbits += (ORC_D >> l) * bits[l - 1];
+    }
+    return (nbits + 7) / 8 + 2 * (ORC_D >> L);
+}
+
+/* Lloyd-Max codebooks of Lemma 2's densities for the given sizes (level 1: equal cells). */
+int orc_general_codebooks(int L, const int *bits, double *cbg)
+{
+    double bnd[65];
+    int off = 0;
+    for (int l = 1; l <= L; ++l) {
+        int K = 1 << bits[l - 1];
+        if (orc_codebook(l, K, cbg + off, bnd)) return -1;
+        off += K;
+    }
+    return 0;
+}
+
+static void orc_put_bits(uint8_t *stream, int pos, int width, int v)
+{
+    for (int i = 0; i < width; ++i)
+        if ((v >> i) & 1) stream[(pos + i) >> 3] |= (uint8_t)(1u << ((pos + i) & 7));
+}
+
+static int orc_get_bits(const uint8_t *stream, int pos, int width)
+{
+    int v = 0;
+    for (int i = 0; i < width; ++i) v |= ((stream[(pos + i) >> 3] >> ((pos + i) & 7)) & 1) << i;
+    return v;
+}
+
+/* x[n][128] -> rec[n][record bytes]; psi_out[n][nang] (exact angles, level-major) and J_out[n][nang] optional */
+void orc_encode_general(const double *x, int64_t n, const double *S, int L, const int *bits, const double *cbg,
+                        uint8_t *rec, double *psi_out, int32_t *J_out)
+{
+    const int nang = orc_general_nang(L), nrad = ORC_D >> L, rb = orc_general_record_bytes(L, bits);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        double y[ORC_D], psi[ORC_NANG_DEEP], r[ORC_D];
+        const double *xi = x + i * ORC_D;
+        for (int j = 0; j < ORC_D; ++j) {
+            double acc = 0.0;
+            for (int k = 0; k < ORC_D; ++k) acc += xi[k] * S[k * ORC_D + j];
+            y[j] = acc;
+        }
+        orc_polar(y, ORC_D, L, psi, r);
+        uint8_t *ri = rec + i * rb;
+        memset(ri, 0, (size_t)rb);
+        int off = 0, cnt = ORC_D / 2, cboff = 0, pos = 0;
+        for (int l = 1; l <= L; ++l) {
+            int K = 1 << bits[l - 1];
+            for (int j = 0; j < cnt; ++j) {
+                int code = orc_quant(psi[off + j], cbg + cboff, K);
+                orc_put_bits(ri, pos, bits[l - 1], code);
+                pos += bits[l - 1];
+                if (J_out) J_out[i * nang + off + j] = code;
+            }
+            off += cnt; cnt /= 2; cboff += K;
+        }
+        uint8_t *rr = ri + (pos + 7) / 8;
+        for (int b = 0; b < nrad; ++b) {
+            uint16_t h = orc_f64_to_f16(fmin(r[b], ORC_F16_MAX));
+            rr[2 * b] = (uint8_t)(h & 0xFF);
+            rr[2 * b + 1] = (uint8_t)(h >> 8);
+        }
+        if (psi_out) memcpy(psi_out + i * nang, psi, sizeof(double) * nang);
+    }
+}
+
+/* DeQuant's loops for one general record: r^(0) in the rotated domain */
+static void orc_dequant_rotated_general(const uint8_t *rec, int L, const int *bits, const double *cbg, double *y)
+{
+    double psi[ORC_NANG_DEEP], r[ORC_D];
+    const int nrad = ORC_D >> L;
+    int off = 0, cnt = ORC_D / 2, cboff = 0, pos = 0;
+    for (int l = 1; l <= L; ++l) {
+        for (int j = 0; j < cnt; ++j) {
+            psi[off + j] = cbg[cboff + orc_get_bits(rec, pos, bits[l - 1])];
+            pos += bits[l - 1];
+        }
+        off += cnt; cnt /= 2; cboff += 1 << bits[l - 1];
+    }
+    const uint8_t *rr = rec + (pos + 7) / 8;
+    for (int b = 0; b < nrad; ++b) r[b] = orc_f16_to_f64((uint16_t)(rr[2 * b] | (rr[2 * b + 1] << 8)));
+    orc_polar_inverse(psi, r, ORC_D, L, y);
+}
+
+/* records -> vectors; rotated != 0 stops before the trailing S^T */
+void orc_decode_general(const uint8_t *rec, int64_t n, const double *S, int L, const int *bits, const double *cbg,
+                        int rotated, double *out)
+{
+    const int rb = orc_general_record_bytes(L, bits);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        double y[ORC_D];
+        orc_dequant_rotated_general(rec + t * rb, L, bits, cbg, y);
+        double *o = out + t * ORC_D;
+        if (rotated) { memcpy(o, y, sizeof(y)); continue; }
+        for (int i = 0; i < ORC_D; ++i) {
+            double acc = 0.0;
+            for (int j = 0; j < ORC_D; ++j) acc += y[j] * S[i * ORC_D + j];
+            o[i] = acc;
+        }
+    }
+}
+
+/* Eq. 5 on general records: the definition (rows fully dequantised, textbook two-pass softmax).
+   Shapes as orc_attention; records are [Hkv][plane_tokens][record bytes]. */
+void orc_attention_general(const double *q, int B, int Hq, int Hkv, const uint8_t *k_rec, const uint8_t *v_rec,
+                           const int64_t *seq_start, const int32_t *ctx_len, int64_t plane_tokens, const double *S,
+                           int L, const int *bits, const double *cbg, double scale, double *out)
+{
+    const int G = Hq / Hkv, rb = orc_general_record_bytes(L, bits);
+    for (int64_t p = 0; p < (int64_t)B * Hkv; ++p) {
+        int b = (int)(p / Hkv), hk = (int)(p % Hkv);
+        int64_t T = ctx_len[b];
+        for (int g = 0; g < G; ++g)
+            memset(out + ((int64_t)b * Hq + hk * G + g) * ORC_D, 0, sizeof(double) * ORC_D);
+        if (T <= 0) continue;
+        double *Kh = (double *)malloc(sizeof(double) * T * ORC_D);
+        double *Vh = (double *)malloc(sizeof(double) * T * ORC_D);
+        double *w = (double *)malloc(sizeof(double) * T);
+        orc_decode_general(k_rec + ((int64_t)hk * plane_tokens + seq_start[b]) * rb, T, S, L, bits, cbg, 0, Kh);
+        orc_decode_general(v_rec + ((int64_t)hk * plane_tokens + seq_start[b]) * rb, T, S, L, bits, cbg, 0, Vh);
+        for (int g = 0; g < G; ++g) {
+            const double *qh = q + ((int64_t)b * Hq + hk * G + g) * ORC_D;
+            double *o = out + ((int64_t)b * Hq + hk * G + g) * ORC_D;
+            double mx = -INFINITY, sum = 0.0;
+            for (int64_t t = 0; t < T; ++t) {
+                double acc = 0.0;
+                for (int i = 0; i < ORC_D; ++i) acc += qh[i] * Kh[t * ORC_D + i];
+                w[t] = acc * scale;
+                if (w[t] > mx) mx = w[t];
+            }
+            for (int64_t t = 0; t < T; ++t) { w[t] = exp(w[t] - mx); sum += w[t]; }
+            for (int64_t t = 0; t < T; ++t)
+                for (int i = 0; i < ORC_D; ++i) o[i] += (w[t] / sum) * Vh[t * ORC_D + i];
+        }
+        free(Kh); free(Vh); free(w);
+    }
 }
 
 int orc_num_threads(void)
