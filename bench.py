@@ -216,6 +216,35 @@ def main():
     fit_host_ms = 1e3 * (time.perf_counter() - t0)
     del fit_ws
 
+    # ---- general format (other bit widths / recursion depths; the plain, untuned path): encode of 65536 key
+    # vectors and attention of 4 sequences x 2048 tokens at depth 5, bits 4/2/2/2/2 (55 bytes per vector)
+    from paper_2502_02617_amd import GeneralFormat, general_attn_decode, general_encode
+    gfmt = GeneralFormat(5, [4, 2, 2, 2, 2])
+    gcb = gfmt.codebooks()
+    g_n, g_B, g_ctx, g_hq, g_hkv = 65536, 4, 2048, 8, 2
+    gx = enc_inputs[0][0].reshape(-1, D)[:g_n]
+    grec = torch.empty((g_n, gfmt.record_bytes()), dtype=torch.uint8, device=dev)
+    general_encode(ctx, gfmt, gcb, gx, grec)
+    torch.cuda.synchronize()
+    ev0.record()
+    general_encode(ctx, gfmt, gcb, gx, grec)
+    ev1.record()
+    torch.cuda.synchronize()
+    g_enc_ms = ev0.elapsed_time(ev1)
+    gk = grec[:g_hkv * g_B * g_ctx].reshape(g_hkv, g_B * g_ctx, -1)
+    gv = grec[g_hkv * g_B * g_ctx:2 * g_hkv * g_B * g_ctx].reshape(g_hkv, g_B * g_ctx, -1)
+    g_start = torch.arange(g_B, dtype=torch.int64, device=dev) * g_ctx
+    g_len = torch.full((g_B,), g_ctx, dtype=torch.int32, device=dev)
+    g_out = torch.empty((g_B, g_hq, D), dtype=torch.float32, device=dev)
+    general_attn_decode(ctx, gfmt, gcb, q[:g_B, :g_hq].contiguous(), g_out, gk, gv, g_start, g_len, scale)
+    torch.cuda.synchronize()
+    ev0.record()
+    general_attn_decode(ctx, gfmt, gcb, q[:g_B, :g_hq].contiguous(), g_out, gk, gv, g_start, g_len, scale)
+    ev1.record()
+    torch.cuda.synchronize()
+    g_attn_ms = ev0.elapsed_time(ev1)
+    del grec
+
     # ---- hybrid line: the same quantised 32k-token prefix plus a bf16 window of 256 recent tokens per
     # sequence (the keys and values of the generation stage kept in 16 bits), pq_attn_decode_hybrid
     WIN = 256
@@ -508,6 +537,15 @@ def main():
             "frac_of_hbm_roofline": round(fit_vectors * 256 / (fit_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),  # 256 B read per vector
             "cluster_rounds": 10,
             "cluster_host_ms": round(fit_host_ms, 3),
+        },
+        "general_format": {
+            "workload": "the plain path for other bit widths and recursion depths (pq_general_*), depth 5, bits 4/2/2/2/2 "
+                        "(55 bytes per vector): encode of 65536 bf16 vectors; attention of 4 sequences x 2048 tokens, "
+                        "8 q / 2 kv heads; generic bit reader, fp32, one wavefront per vector or (sequence, head): not tuned",
+            "encode_ms": round(g_enc_ms, 4),
+            "encode_m_vectors_per_s": round(g_n / (g_enc_ms * 1e-3) / 1e6, 1),
+            "attention_ms": round(g_attn_ms, 4),
+            "attention_m_tokens_per_s": round(g_B * g_hq * g_ctx / (g_attn_ms * 1e-3) / 1e6, 2),
         },
         "hybrid": {
             "workload": "configs[2] prefix + 256 unquantised (bf16) recent tokens per sequence, pq_attn_decode_hybrid "

@@ -404,6 +404,52 @@ pq_status pq_attn_decode_hybrid(const pq_ctx *ctx, const void *q, void *out, pq_
 size_t pq_attn_hybrid_workspace_bytes(int B, int Hq, int Hkv, int64_t max_ctx, int64_t win_cap);
 
 /* ---------------------------------------------------------------------------
+ * The general format: recursion depths 4 to 7 with other bit widths than
+ * Section 4.1's (Definition 1 recurses to log2 d; the remark after Theorem 1
+ * leaves the codebook size of each level free).  A plain path next to the tuned
+ * one: records in the canonical general layout, one after another, read through
+ * a generic bit reader by simple fp32 kernels (one wavefront per vector, or per
+ * (sequence, query head) in attention); not tuned.
+ *   format: depth in 4..7; bits[l-1] bits for the angles of level l:
+ *           level 1: 3 or 4; levels 2-4: 2 or 3; levels 5-7 (up to depth): 1, 2 or 3.
+ *   record: the codes of level 1 (64, in coordinate order), then level 2 (32), ...,
+ *           each bits[l-1] wide, in one little-endian bit stream (bit p of the
+ *           stream is bit p & 7 of byte p >> 3) padded to a whole byte, then the
+ *           128 >> depth radii r^(depth) as little-endian binary16 (saturating at
+ *           65504).  pq_general_record_bytes gives its size (0: format refused).
+ *   cbg (host): the centroids of levels 1..depth one after another, level l holding
+ *           2^bits[l-1] ascending entries (level 1 in [0, 2 pi], others in [0, pi/2]);
+ *           cell boundaries are midpoints (procedure Quant).  pq_general_codebooks
+ *           writes the Lloyd-Max codebooks of Lemma 2's densities (level 1: equal
+ *           cells) into cbg[pq_general_codebook_entries(f)].
+ * All of them use the context's S only.  x: device, n_vectors rows of 128 values
+ * (PQ_BF16 or PQ_F32), row r at element r * ld_vector.  records: device,
+ * [n_vectors][record bytes].  pq_general_decode: out device fp32 [n_vectors][128];
+ * rotated != 0 stops before the trailing S^T of procedure DeQuant.
+ * pq_general_attn_decode: Eq. 5 for one bf16 query per sequence (q device
+ * [B][Hq][128]) on records [Hkv][pool_tokens][record bytes], sequence b owning
+ * tokens [seq_start[b], seq_start[b] + ctx_len[b]) of every head plane (device
+ * arrays; a range outside the pool or an empty one gives a zero row), out device
+ * fp32 [B][Hq][128].  No workspace, nothing allocated, launches only.
+ * ------------------------------------------------------------------------- */
+typedef struct pq_general_format {
+    int depth;
+    int bits[7];
+} pq_general_format;
+
+size_t pq_general_record_bytes(const pq_general_format *f);
+int pq_general_codebook_entries(const pq_general_format *f);
+pq_status pq_general_codebooks(const pq_general_format *f, double *cbg);
+pq_status pq_general_encode(const pq_ctx *ctx, const pq_general_format *f, const double *cbg, const void *x,
+                            pq_dtype xt, int64_t n_vectors, int64_t ld_vector, uint8_t *records, void *hip_stream);
+pq_status pq_general_decode(const pq_ctx *ctx, const pq_general_format *f, const double *cbg, const uint8_t *records,
+                            int64_t n_vectors, int rotated, float *out, void *hip_stream);
+pq_status pq_general_attn_decode(const pq_ctx *ctx, const pq_general_format *f, const double *cbg, const void *q,
+                                 float *out, const uint8_t *k_records, const uint8_t *v_records,
+                                 const int64_t *seq_start, const int32_t *ctx_len, int B, int Hq, int Hkv,
+                                 int64_t pool_tokens, float softmax_scale, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
  * Optional timing of the two dominant kernels (the attention partial kernel
  * and the encode kernel) with HIP events recorded on the launch stream,
  * for benchmarks: pq_profile_begin(max_launches) creates the events and turns

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libpolarquant.so")
-SOURCES = ["pq_host.hip", "pq_encode.hip", "pq_decode.hip", "pq_attn.hip", "pq_fit.hip"]
+SOURCES = ["pq_host.hip", "pq_encode.hip", "pq_decode.hip", "pq_attn.hip", "pq_fit.hip", "pq_general.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -110,6 +110,18 @@ def library():
     L.pq_attn_decode_polar_static.restype = i32
     L.pq_attn_decode_polar_static.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, i64,
                                               ctypes.c_float, vp]
+    L.pq_general_record_bytes.restype = ctypes.c_size_t
+    L.pq_general_record_bytes.argtypes = [vp]
+    L.pq_general_codebook_entries.restype = i32
+    L.pq_general_codebook_entries.argtypes = [vp]
+    L.pq_general_codebooks.restype = i32
+    L.pq_general_codebooks.argtypes = [vp, vp]
+    L.pq_general_encode.restype = i32
+    L.pq_general_encode.argtypes = [vp, vp, vp, vp, i32, i64, i64, vp, vp]
+    L.pq_general_decode.restype = i32
+    L.pq_general_decode.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp]
+    L.pq_general_attn_decode.restype = i32
+    L.pq_general_attn_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, ctypes.c_float, vp]
     L.pq_profile_begin.restype = i32
     L.pq_profile_begin.argtypes = [i32]
     L.pq_profile_begin_sampled.restype = i32
@@ -509,3 +521,56 @@ class Context:
             v_radii.data_ptr(), seq_start.data_ptr(), ctx_len.data_ptr(), int(B), int(Hq), int(Hkv), int(pool_tokens),
             int(max_ctx), float(softmax_scale), workspace.data_ptr(), int(workspace.numel() * workspace.element_size()),
             _stream()))
+
+
+class GeneralFormat(ctypes.Structure):
+    """pq_general_format: recursion depth 4..7 and bits per level (level 1: 3 or 4; 2-4: 2 or 3; 5-7: 1..3)."""
+    _fields_ = [("depth", ctypes.c_int), ("bits", ctypes.c_int * 7)]
+
+    def __init__(self, depth, bits):
+        super().__init__()
+        self.depth = int(depth)
+        for l in range(7):
+            self.bits[l] = int(bits[l]) if l < len(bits) else 0
+
+    def record_bytes(self):
+        n = int(library().pq_general_record_bytes(ctypes.byref(self)))
+        if n == 0:
+            raise PolarQuantError("general format refused (depth 4..7; bits: level 1 in {3,4}, 2-4 in {2,3}, 5-7 in {1,2,3})")
+        return n
+
+    def codebooks(self):
+        """Lloyd-Max centroids of levels 1..depth, concatenated (numpy float64)."""
+        n = int(library().pq_general_codebook_entries(ctypes.byref(self)))
+        if n == 0:
+            raise PolarQuantError("general format refused")
+        out = np.empty(n, dtype=np.float64)
+        _check(library().pq_general_codebooks(ctypes.byref(self), out.ctypes.data_as(ctypes.c_void_p)))
+        return out
+
+
+def _cbg(cbg):
+    return np.ascontiguousarray(cbg, dtype=np.float64)
+
+
+def general_encode(ctx, fmt, cbg, x, records):
+    """x [n, 128] (bf16 or fp32 device tensor, rows contiguous) -> records (uint8 device tensor [n, record bytes])."""
+    cb = _cbg(cbg)
+    _check(library().pq_general_encode(ctx._h, ctypes.byref(fmt), cb.ctypes.data_as(ctypes.c_void_p), x.data_ptr(),
+                                       _dtype_code(x), int(x.shape[0]), int(x.stride(0)), records.data_ptr(), _stream()))
+
+
+def general_decode(ctx, fmt, cbg, records, n, out, rotated=False):
+    cb = _cbg(cbg)
+    _check(library().pq_general_decode(ctx._h, ctypes.byref(fmt), cb.ctypes.data_as(ctypes.c_void_p), records.data_ptr(),
+                                       int(n), 1 if rotated else 0, out.data_ptr(), _stream()))
+
+
+def general_attn_decode(ctx, fmt, cbg, q, out, k_records, v_records, seq_start, ctx_len, scale):
+    """q bf16 [B, Hq, 128]; records uint8 [Hkv, pool_tokens, record bytes]; out fp32 [B, Hq, 128]."""
+    cb = _cbg(cbg)
+    B, Hq, _ = q.shape
+    _check(library().pq_general_attn_decode(ctx._h, ctypes.byref(fmt), cb.ctypes.data_as(ctypes.c_void_p), q.data_ptr(),
+                                            out.data_ptr(), k_records.data_ptr(), v_records.data_ptr(),
+                                            seq_start.data_ptr(), ctx_len.data_ptr(), int(B), int(Hq),
+                                            int(k_records.shape[0]), int(k_records.shape[1]), float(scale), _stream()))

@@ -117,6 +117,9 @@ bool pq_device_state_ready(const pq_ctx *ctx);
 void pq_prof_before(int kind, hipStream_t s);
 void pq_prof_after(int kind, hipStream_t s);
 
+/* Lloyd-Max quantiser of Lemma 2's density of level `level` (>= 2) with K cells: centroids[K], boundaries[K + 1] */
+void pq_lloyd_max(int level, int K, double *centroids, double *boundaries);
+
 static inline bool pq_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 /* ---- small dense products with S: one vector per 512-thread workgroup ----

@@ -125,8 +125,10 @@ double first_moment_antiderivative(const SinPower &sp, double x) /* int x sin^m(
 
 void lloyd_max_level(int level, double *centroids /*K*/, double *boundaries /*K+1*/, int K = 4)
 {
-    const SinPower sp = make_sin_power((1 << (level - 1)) - 1);
+    const int m_pow = (1 << (level - 1)) - 1;
+    const SinPower sp = make_sin_power(m_pow);
     const double lo = 0.0, hi = kPi / 2.0;
+    const double total = mass_antiderivative(sp, hi) - mass_antiderivative(sp, lo);
     for (int k = 0; k < K; ++k) centroids[k] = hi * (k + 0.5) / K;
     for (int it = 0; it < 200000; ++it) {
         boundaries[0] = lo; boundaries[K] = hi;
@@ -135,7 +137,22 @@ void lloyd_max_level(int level, double *centroids /*K*/, double *boundaries /*K+
         for (int k = 0; k < K; ++k) {
             double mass = mass_antiderivative(sp, boundaries[k + 1]) - mass_antiderivative(sp, boundaries[k]);
             double mom = first_moment_antiderivative(sp, boundaries[k + 1]) - first_moment_antiderivative(sp, boundaries[k]);
-            double c = mom / mass;
+            if (!(mass > 1e-7 * total)) {
+                /* a cell far out in the tail of a high power (the outer cells of eight at level 7 hold 1e-20 of the
+                   mass): the alternating sum cancels there, so the cell is integrated numerically instead
+                   (composite Simpson on sin^m(2 psi) itself, all terms positive) */
+                const int N = 2048;
+                const double a = boundaries[k], h = (boundaries[k + 1] - a) / N;
+                mass = 0.0; mom = 0.0;
+                for (int i = 0; i <= N; ++i) {
+                    const double x = a + h * i, w = (i == 0 || i == N) ? 1.0 : ((i & 1) ? 4.0 : 2.0);
+                    const double g = pow(sin(2.0 * x), (double)m_pow);
+                    mass += w * g;
+                    mom += w * g * x;
+                }
+                mass *= h / 3.0; mom *= h / 3.0;
+            }
+            double c = mass > 0.0 ? mom / mass : 0.5 * (boundaries[k] + boundaries[k + 1]);
             moved = fmax(moved, fabs(c - centroids[k]));
             centroids[k] = c;
         }
@@ -144,6 +161,13 @@ void lloyd_max_level(int level, double *centroids /*K*/, double *boundaries /*K+
     boundaries[0] = lo; boundaries[K] = hi;
     for (int k = 1; k < K; ++k) boundaries[k] = 0.5 * (centroids[k - 1] + centroids[k]);
 }
+
+} // namespace
+
+/* the same quantiser for the other files of the library (the general format builds codebooks of other sizes) */
+void pq_lloyd_max(int level, int K, double *centroids, double *boundaries) { lloyd_max_level(level, centroids, boundaries, K); }
+
+namespace {
 
 /* ---- binary16 / bfloat16 from double, round to nearest even ---- */
 uint16_t to_binary16(double v)
