@@ -36,11 +36,14 @@
  *   buffer, i.e. exactly 62 bytes per token.
  *     codes: uint8_t [n_heads][pool_tokens/64][2944]
  *     radii: uint16_t[n_heads][pool_tokens/64][512]
- *   Inside a tile the fields are stored planar and lane-major so that a
- *   64-lane wavefront reads them with full-width coalesced loads; keys
- *   (PQ_KEY) and values (PQ_VALUE) use different in-tile orders because the
- *   score and the weighted-sum contractions consume them differently.  The
- *   exact bit positions are specified at the top of csrc/pq_layout.h;
+ *   Inside a tile the 46 code bits of a block are stored as the table
+ *   indices the attention kernel gathers with (four 10-bit quarter indices
+ *   and one 6-bit block index), in per-lane bit strings spread over planes
+ *   that a 64-lane wavefront reads with full-width coalesced loads; keys
+ *   (PQ_KEY: one token per lane) and values (PQ_VALUE: one half-block of 16
+ *   tokens per lane) use different in-tile orders because the score and the
+ *   weighted-sum contractions consume them differently.  The exact bit
+ *   positions are specified at the top of csrc/pq_layout.h;
  *   pq_export_canonical converts tiles to the order-independent canonical
  *   62-byte records.
  *   A sequence must start on a tile boundary (seq_start % 64 == 0).
