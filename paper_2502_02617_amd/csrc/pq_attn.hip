@@ -482,6 +482,9 @@ __global__ __launch_bounds__(waves_per_block(NG) * 64, 1) void pq_attn_partial_k
     /* per-sequence data of batches of up to 64 sequences is staged in LDS with the tables, so that
        nothing between the barrier and the first tile request waits for global memory; its loads
        are requested first (last wavefront of the workgroup) */
+    /* tiles done so far by every wavefront, [wavefront & 3][wavefront >> 2]: the wavefronts of a workgroup go to the
+       four SIMDs in turn, so a row holds the wavefronts that share a SIMD (see the issue priority in the tile loop) */
+    __shared__ __attribute__((aligned(16))) int sDone[4][4];
     __shared__ int sPre[65];
     __shared__ int sCtx[64];
     __shared__ int64_t sTile0[64];
@@ -497,19 +500,45 @@ __global__ __launch_bounds__(waves_per_block(NG) * 64, 1) void pq_attn_partial_k
         st_len = a.ctx_len[min(bb, a.B - 1)];
         st_start = a.seq_start[min(bb, a.B - 1)];
     }
-    {   /* tables: the image in global memory is compact (PQ_TAB_*); the small ones are spread over a column per lane */
+    {   /* tables: the image in global memory is compact (PQ_TAB_*); the small ones are spread over a column per lane.
+           All of a thread's entries are requested before the first one is stored: one trip to memory, not one per
+           entry. */
         const uint32_t *src = a.consts->attn_tab;
-        for (int t = threadIdx.x; t < 2048; t += kThreads) tab[kTQ + t] = src[PQ_TAB_TQ + t];
-        for (int t = threadIdx.x; t < 2048; t += kThreads) { /* entry t >> 5, column t & 31 */
-            tab[kTQA + t] = src[PQ_TAB_TQA + (t >> 5)];
-            tab[kTQB + t] = src[PQ_TAB_TQB + (t >> 5)];
-            tab[kTBH + t] = src[PQ_TAB_TBH + 2 * (t >> 5) + (t & 1)];
+        constexpr int kR2 = (2048 + kThreads - 1) / kThreads, kR4 = (4096 + kThreads - 1) / kThreads;
+        uint32_t tq[kR2], tqa[kR2], tqb[kR2], tbh[kR2], tbf[kR4], tup = 0;
+#pragma unroll
+        for (int i = 0; i < kR2; ++i) {
+            const int t = min((int)threadIdx.x + i * kThreads, 2047); /* entry t >> 5, column t & 31 */
+            tq[i] = src[PQ_TAB_TQ + t];
+            tqa[i] = src[PQ_TAB_TQA + (t >> 5)];
+            tqb[i] = src[PQ_TAB_TQB + (t >> 5)];
+            tbh[i] = src[PQ_TAB_TBH + 2 * (t >> 5) + (t & 1)];
         }
-        for (int t = threadIdx.x; t < 4096; t += kThreads) /* entry t >> 6, column (t >> 2) & 15, float t & 3 */
-            tab[kTBF + t] = src[PQ_TAB_TBF + 4 * (t >> 6) + (t & 3)];
-        if (threadIdx.x < 48) tab[kTUp + threadIdx.x] = src[PQ_TAB_UP + threadIdx.x];
+#pragma unroll
+        for (int i = 0; i < kR4; ++i) {
+            const int t = min((int)threadIdx.x + i * kThreads, 4095); /* entry t >> 6, column (t >> 2) & 15, float t & 3 */
+            tbf[i] = src[PQ_TAB_TBF + 4 * (t >> 6) + (t & 3)];
+        }
+        if (threadIdx.x < 48) tup = src[PQ_TAB_UP + threadIdx.x];
         uint4 *pz = reinterpret_cast<uint4 *>(&sP[0][0][0][0]);
         for (int t = threadIdx.x; t < kWavesPerBlock * NG * 8 * 64 / 4; t += kThreads) pz[t] = make_uint4(0, 0, 0, 0);
+        if (threadIdx.x < 16) sDone[threadIdx.x >> 2][threadIdx.x & 3] = threadIdx.x < kWavesPerBlock ? 0 : 0x7FFFFFFF;
+#pragma unroll
+        for (int i = 0; i < kR2; ++i) {
+            const int t = (int)threadIdx.x + i * kThreads;
+            if (t < 2048) {
+                tab[kTQ + t] = tq[i];
+                tab[kTQA + t] = tqa[i];
+                tab[kTQB + t] = tqb[i];
+                tab[kTBH + t] = tbh[i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kR4; ++i) {
+            const int t = (int)threadIdx.x + i * kThreads;
+            if (t < 4096) tab[kTBF + t] = tbf[i];
+        }
+        if (threadIdx.x < 48) tab[kTUp + threadIdx.x] = tup;
     }
     if (staged && threadIdx.x >= kStager) {
         const int bb = (int)threadIdx.x - kStager;
@@ -580,8 +609,9 @@ __global__ __launch_bounds__(waves_per_block(NG) * 64, 1) void pq_attn_partial_k
     const __amdgpu_buffer_rsrc_t o_rsrc = stream_descriptor(a.ws_o, (uint32_t)a.n_pieces * (a.M * G) * (PQ_D * 4u));
     const __amdgpu_buffer_rsrc_t ml_rsrc = stream_descriptor(a.ws_ml, (uint32_t)a.n_pieces * (a.M * G) * 8u);
 
-    const int quarter_tiles = max((gend - gpos + 3) >> 2, 1);
-    int prio = 4, next_drop = gpos; /* drops to 3 at the first tile */
+    const int gpos0 = gpos;
+    int *my_done = &sDone[wave & 3][wave >> 2];
+    const int4 *simd_done = reinterpret_cast<const int4 *>(&sDone[wave & 3][0]);
     for (;;) { /* one piece per round: tiles [tile_lo, tile_hi) of stream (b, hk) */
         const int ctx = ctx_of(b);
         const int n_tiles = (ctx + 63) >> 6; /* == seq_tiles */
@@ -731,10 +761,16 @@ __global__ __launch_bounds__(waves_per_block(NG) * 64, 1) void pq_attn_partial_k
 #pragma unroll
                 for (int h = 0; h < 4; ++h) lim[k][h] = 64;
             for (; tile < n_full; ++tile) {
-                /* progress through the share, in quarters: the further along, the lower the priority */
-                if (gpos + (tile - tile_lo) >= next_drop) {
-                    next_drop += quarter_tiles;
-                    set_wave_priority(--prio);
+                /* Issue priority by rank among the wavefronts of the SIMD: the hardware prefers the oldest, which
+                   would run ahead and leave the youngest to finish alone at a fraction of the SIMD's issue rate.
+                   Every wavefront publishes the tiles it has done; the more of its neighbours are ahead of it, the
+                   higher its priority (a slot without a wavefront counts as infinitely far ahead). */
+                {
+                    const int done = gpos - gpos0 + (tile - tile_lo);
+                    if (lane == 0) *my_done = done;
+                    const int4 d4 = *simd_done;
+                    const int ahead = (d4.x > done) + (d4.y > done) + (d4.z > done) + (d4.w > done);
+                    set_wave_priority(min(__builtin_amdgcn_readfirstlane(ahead), 3));
                 }
                 do_tile(std::false_type{}, kraw, vraw, lim, 64);
                 if (tile + 1 < tile_hi) {
