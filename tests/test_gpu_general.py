@@ -8,7 +8,7 @@ import torch
 import oracle
 from paper_2502_02617_amd import (Context, GeneralFormat, PolarQuantError, general_attn_decode, general_decode,
                                   general_encode, synth)
-from tests import helpers
+from tests import helpers, layout_ref
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -161,7 +161,7 @@ def test_general_format_with_section_4_1_settings_matches_the_tuned_path():
     ctx.export_canonical(0, codes, radii, 0, n, rec_t)
     torch.cuda.synchronize()
     J_g, r_g = unpack_general(rec_g.cpu().numpy(), 4, [4, 2, 2, 2])
-    J_t, r_t = oracle.unpack(rec_t.cpu().numpy().reshape(n, 62))
+    J_t, r_t = layout_ref.unpack_canonical(rec_t.cpu().numpy().reshape(n, 62))   # numpy reader of the canonical record
     assert (J_g != J_t).mean() <= 1e-4 and np.all(np.abs(r_g.astype(np.int32) - r_t.astype(np.int32)) <= 1)
 
 
