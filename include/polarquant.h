@@ -65,7 +65,7 @@ typedef enum { PQ_KEY = 0, PQ_VALUE = 1 } pq_kind;
 typedef enum {
     PQ_OK = 0,
     PQ_EINVAL = -1,       /* null pointer, bad size, bad enum */
-    PQ_EUNSUPPORTED = -2, /* d != 128, Hq/Hkv not in {1,2,4,8}, ... */
+    PQ_EUNSUPPORTED = -2, /* d != 128, more than 16 query heads per kv head, ... */
     PQ_EALIGN = -3,       /* device pointer or stride not 16-byte aligned */
     PQ_EHIP = -4,         /* a HIP runtime call failed (no device, launch error) */
     PQ_ENOMEM = -5,       /* host or device allocation failed, workspace too small */
@@ -300,7 +300,7 @@ pq_status pq_export_canonical(const pq_ctx *ctx, pq_kind kind, const uint8_t *co
  * == 0; the tile holding the last token must lie inside the pool).  The
  * query attends to all ctx_len[b] cached tokens (its own key/value are
  * appended before the call).  Query head h reads KV head h / (Hq/Hkv);
- * Hq/Hkv must be 1, 2, 4 or 8.  ctx_len[b] == 0 gives a zero output row.
+ * Hq must be a multiple of Hkv and Hq/Hkv at most 16.  ctx_len[b] == 0 gives a zero output row.
  * max_ctx (host) bounds every ctx_len[b]; it sizes the workspace; at most
  * 2^26 tokens, and B * Hkv * ceil(max_ctx / 64) must stay below 2^31 - 4096
  * (PQ_EUNSUPPORTED beyond).  The context lengths themselves are only read on
@@ -393,7 +393,7 @@ pq_status pq_decode_step_polar(const pq_ctx *ctx, const void *xk, const void *xv
  * pq_attn_decode_polar (ctx_len counts the quantised tokens only); workspace:
  * at least pq_attn_hybrid_workspace_bytes(B, Hq, Hkv, max_ctx, win_cap) bytes.
  * A sequence with neither prefix nor window gives a zero output row.
- * Hq/Hkv must be 1, 2, 4 or 8.
+ * Hq/Hkv at most 16.
  * ------------------------------------------------------------------------- */
 pq_status pq_attn_decode_hybrid(const pq_ctx *ctx, const void *q, void *out, pq_dtype out_dtype,
                                 const uint8_t *k_codes, const uint16_t *k_radii,

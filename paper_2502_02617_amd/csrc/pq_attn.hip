@@ -469,10 +469,11 @@ __device__ __forceinline__ float wave_max_f(float x)
  * pairs, and the probability operand has one column per (pair, parity) with zeros in the slots of
  * the other parity.  The result accumulates o' for the even coordinates in the parity-0 columns and
  * for the odd ones in parity 1. */
-template <int G, int NG, bool DEEP>
+template <int NG, bool DEEP>
 __global__ __launch_bounds__(waves_per_block(NG) * 64, 1) void pq_attn_partial_kernel(AttnArgs a)
 {
     constexpr int kWavesPerBlock = waves_per_block(NG), kThreads = kWavesPerBlock * 64;
+    const int G = a.Hq / a.Hkv; /* query heads per kv head: only the set-up and the epilogue of a piece depend on it */
     __shared__ __attribute__((aligned(16))) uint32_t tab[kLdsTabDwords];
     /* probabilities of a tile: sP[wave][group][column = pair slot + 4 parity][token] as dwords; a parity-0 column
        keeps its binary16 value in the low half, a parity-1 column in the high half, and the other halves stay
@@ -1329,19 +1330,18 @@ struct StepWindow {
     int64_t win_cap;
 };
 
-template <int G, bool DEEP>
+template <bool DEEP>
 void launch_partial_depth(int NG, dim3 grid, dim3 blk, hipStream_t s, const AttnArgs &aa)
 {
-    if (NG == 1) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 1, DEEP>), grid, blk, 0, s, aa);
-    else if (NG == 2) hipLaunchKernelGGL((pq_attn_partial_kernel<G, 2, DEEP>), grid, blk, 0, s, aa);
-    else hipLaunchKernelGGL((pq_attn_partial_kernel<G, 4, DEEP>), grid, blk, 0, s, aa);
+    if (NG == 1) hipLaunchKernelGGL((pq_attn_partial_kernel<1, DEEP>), grid, blk, 0, s, aa);
+    else if (NG == 2) hipLaunchKernelGGL((pq_attn_partial_kernel<2, DEEP>), grid, blk, 0, s, aa);
+    else hipLaunchKernelGGL((pq_attn_partial_kernel<4, DEEP>), grid, blk, 0, s, aa);
 }
 
-template <int G>
 void launch_partial(int NG, bool deep, dim3 grid, dim3 blk, hipStream_t s, const AttnArgs &aa)
 {
-    if (deep) launch_partial_depth<G, true>(NG, grid, blk, s, aa);
-    else launch_partial_depth<G, false>(NG, grid, blk, s, aa);
+    if (deep) launch_partial_depth<true>(NG, grid, blk, s, aa);
+    else launch_partial_depth<false>(NG, grid, blk, s, aa);
 }
 
 pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const StepWindow *win, int M, const void *q,
@@ -1361,7 +1361,6 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     if ((int64_t)B * Hkv * ((max_ctx + 63) / 64) >= ((int64_t)1 << 31) - 4096) return PQ_EUNSUPPORTED;
     if (out_dtype != PQ_BF16 && out_dtype != PQ_F32) return PQ_EINVAL;
     const int G = Hq / Hkv;
-    if (G != 1 && G != 2 && G != 4 && G != 8) return PQ_EUNSUPPORTED;
     if (M < 1 || M * G > 16) return PQ_EUNSUPPORTED;   /* at most 16 (query token, head) pairs per kv head */
     if ((app || win) && M != 1) return PQ_EUNSUPPORTED;
     const int NG = M * G <= 4 ? 1 : (M * G <= 8 ? 2 : 4);
@@ -1411,7 +1410,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
                       static_cast<const uint16_t *>(win->win_v), win->win_len, B, Hq, Hkv, (int)win->win_cap,
                       p.n_wchunks, softmax_scale * kLog2e, reinterpret_cast<float *>(ws + p.off_wml),
                       reinterpret_cast<float *>(ws + p.off_wo)};
-        const int per_wave = G >= 4 ? 2 : 1; /* query heads per wavefront */
+        const int per_wave = (G >= 4 && G % 2 == 0) ? 2 : 1; /* query heads per wavefront (of one kv head's group) */
         const int64_t witems = (int64_t)B * (Hq / per_wave) * p.n_wchunks;
         const int64_t wblocks = (witems + kWindowWaves - 1) / kWindowWaves;
         if (wblocks + row_blocks + 1 > 0x7FFFFFFF) return PQ_EINVAL;
@@ -1435,10 +1434,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     aa.up_b5 = ctx->upper_bits[0]; aa.up_b6 = ctx->upper_bits[1]; aa.up_b7 = ctx->upper_bits[2];
     pq_prof_before(0, s);
     const dim3 grid(p.blocks), blk((unsigned)(waves_per_block(NG) * 64));
-    if (G == 8) launch_partial<8>(NG, deep, grid, blk, s, aa);
-    else if (G == 4) launch_partial<4>(NG, deep, grid, blk, s, aa);
-    else if (G == 2) launch_partial<2>(NG, deep, grid, blk, s, aa);
-    else launch_partial<1>(NG, deep, grid, blk, s, aa);
+    launch_partial(NG, deep, grid, blk, s, aa);
     pq_prof_after(0, s);
 
     CombineArgs ca{ws_ml, ws_o, B, Hq, Hkv, M, plan,

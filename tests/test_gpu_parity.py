@@ -378,7 +378,7 @@ def gpu_attention(ctx, q_cpu, caches, starts, lens, max_ctx=None, out_dtype=torc
     return out.float().cpu().numpy()
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (4, 2), (3, 3)])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (4, 2), (3, 3), (6, 2), (5, 1), (12, 2), (14, 2), (16, 1)])
 def test_attention_small_ragged(env, Hq, Hkv):
     ctx, S, cb = env
     lens = [1, 17, 64, 65, 200, 0, 700, 1030]
@@ -648,7 +648,7 @@ def test_decode_step_under_graph_replay(env):
     assert torch.isfinite(out).all()
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (2, 2), (16, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (2, 2), (16, 2), (6, 2), (12, 2), (5, 1), (16, 1)])
 def test_hybrid_attention_prefix_plus_window(env, Hq, Hkv):
     """Quantised prefix + bf16 window against the oracle: every mix of empty / one-tile / ragged prefix and
     empty / partial / several-chunk window."""
@@ -877,7 +877,8 @@ def test_online_codebook_fit(which):
     check_encode(ctx2, S, ref, xs, PQ_KEY, f"fitted ({which})")
 
 
-@pytest.mark.parametrize("M,Hq,Hkv", [(2, 8, 2), (4, 4, 1), (3, 2, 2), (16, 1, 1), (1, 16, 2), (2, 16, 2)])
+@pytest.mark.parametrize("M,Hq,Hkv", [(2, 8, 2), (4, 4, 1), (3, 2, 2), (16, 1, 1), (1, 16, 2), (2, 16, 2), (2, 6, 2), (3, 5, 1),
+                                      (2, 7, 1), (1, 16, 1)])
 def test_multi_query_attention(env, M, Hq, Hkv):
     """M query tokens per sequence (and 8 query heads per kv head): row (b, m) equals single-query attention
     over the first ctx_len - (M-1-m) cached tokens -- the oracle is called once per m with that length."""
@@ -924,3 +925,16 @@ def test_attention_rejects_bad_sequences_gracefully(env):
     bad_starts[1] = pool  # outside the pool: treated as empty, never read
     got = gpu_attention(ctx, q, caches, bad_starts, lens)
     assert np.all(np.isfinite(got)) and np.all(got[1] == 0.0)
+
+
+def test_attention_rejects_more_than_sixteen_heads_per_kv_head(env):
+    """17 query heads per kv head do not fit the 16 (query token, head) pairs of a pass: refused on the host,
+    nothing launched, the output untouched."""
+    ctx, S, cb = env
+    say("attention with Hq/Hkv = 17: refused")
+    lens = [100]
+    caches, starts, pool, k_rec, v_rec = build_cache(ctx, S, cb, lens, 1, seed=701, want_oracle=False)
+    q = synth.queries(1, 17, seed=701)
+    with pytest.raises(Exception) as e:
+        gpu_attention(ctx, q, caches, starts, lens)
+    assert "-2" in str(e.value) or "UNSUPPORTED" in str(e.value).upper()
