@@ -109,8 +109,20 @@ pq_status pq_init_preconditioner(pq_ctx **out, int d, uint64_t seed, const doubl
  * of this kind).  Everything else (codebooks, layout, kernels) is unchanged;
  * because all entries of such an S are +-1/sqrt(d), pq_encode_kv rotates with
  * one exact bf16 term instead of three.  Any S passed to pq_init_preconditioner
- * whose entries all have that magnitude takes the same path. */
+ * whose entries all have that magnitude takes the same path.
+ * The products of single vectors with such an S -- the query rotation, the key
+ * and value of pq_append_kv / pq_decode_step_polar, the un-rotation of the
+ * attention output -- run as a fast Walsh-Hadamard transform (d log2 d additions
+ * in one wavefront, S is not read); so does any S given to pq_init_preconditioner
+ * that is exactly a sign diagonal times the Sylvester matrix over sqrt(d). */
 pq_status pq_init_preconditioner_hadamard(pq_ctx **out, int d, uint64_t seed);
+
+/* How the kernels multiply by this context's S: 0 = general matrix (three bf16
+ * terms in pq_encode_kv, dense products elsewhere), 1 = all entries +-1/sqrt(d)
+ * (one term in pq_encode_kv), 2 = D H / sqrt(d) with the Sylvester H (one term,
+ * and the single-vector products by fast Walsh-Hadamard transform).  -1 if ctx is
+ * NULL. */
+int pq_preconditioner_structure(const pq_ctx *ctx);
 
 /* Replaces the codebooks of a context that has not launched anything yet (PQ_EINVAL
  * afterwards: the tables are already on a device) -- the place where codebooks fitted

@@ -61,6 +61,8 @@ def library():
     L.pq_set_upper_codebooks.argtypes = [vp, vp]
     L.pq_recursion_depth.restype = i32
     L.pq_recursion_depth.argtypes = [vp]
+    L.pq_preconditioner_structure.restype = i32
+    L.pq_preconditioner_structure.argtypes = [vp]
     L.pq_radii_halves_per_tile.restype = i32
     L.pq_radii_halves_per_tile.argtypes = [vp]
     L.pq_record_bytes.restype = i32
@@ -234,6 +236,10 @@ class Context:
 
     def recursion_depth(self):
         return int(library().pq_recursion_depth(self._h))
+
+    def preconditioner_structure(self):
+        """0 general S, 1 all entries +-1/sqrt(d), 2 sign diagonal times the Sylvester Hadamard matrix."""
+        return int(library().pq_preconditioner_structure(self._h))
 
     def radii_halves_per_tile(self):
         return int(library().pq_radii_halves_per_tile(self._h))

@@ -857,6 +857,7 @@ struct RotateArgs {
     const float *S;    /* S[i*128 + j] */
     float scale;       /* softmax_scale * log2(e) */
     const PqDeviceConsts *consts;
+    PqHadamard had;    /* on: q' = q S by a fast Walsh-Hadamard transform, S is not read */
 };
 
 /* Four query rows per workgroup: the workgroup's slice of S (64 KB, what bounds this launch) is
@@ -870,6 +871,19 @@ __device__ __forceinline__ void rotate_query_rows(const RotateArgs &a, int row0,
     __shared__ float sq[kRotateRows][PQ_D];
     __shared__ float spart[kRotateRows][4][PQ_D];
     const int tid = threadIdx.x, r = tid >> 7, j = tid & 127;
+    if (a.had.on) { /* S = D H / sqrt(128): wavefront w transforms row row0 + w, two elements per lane */
+        const int w = tid >> 6, lane = tid & 63, hrow = row0 + w;
+        if (w < kRotateRows && hrow < n_rows) {
+            const uint16_t *qr = a.q + (int64_t)hrow * PQ_D;
+            float lo = __uint_as_float((uint32_t)qr[lane] << 16) * pq_hadamard_sign(a.had, lane);
+            float hi = __uint_as_float((uint32_t)qr[lane + 64] << 16) * pq_hadamard_sign(a.had, lane + 64);
+            pq_fwht128(lo, hi, lane);
+            const float c = a.scale * PQ_INV_SQRT_D;
+            a.qrot[(int64_t)hrow * PQ_D + lane] = __builtin_bit_cast(uint16_t, (_Float16)(lo * c));
+            a.qrot[(int64_t)hrow * PQ_D + lane + 64] = __builtin_bit_cast(uint16_t, (_Float16)(hi * c));
+        }
+        return;
+    }
     MatrixSlice ms;
     matrix_slice_load(ms, a.S, tid);
     const int row = row0 + r;
@@ -999,6 +1013,7 @@ struct CombineArgs {
     const float *win_ml, *win_o;
     const int32_t *win_len;
     int n_wchunks, win_cap;
+    PqHadamard had; /* on: the un-rotation by S^T is a fast Walsh-Hadamard transform, St is not read */
 };
 
 /* HYBRID adds the partial results of the unquantised window.  They live in the original
@@ -1014,7 +1029,7 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
     const int tid = threadIdx.x, cq = tid >> 7, j = tid & 127;
     const int row = blockIdx.x;
     MatrixSlice ms; /* requested first: its latency overlaps the reads of the partial results */
-    matrix_slice_load(ms, a.St, tid);
+    if (!a.had.on) matrix_slice_load(ms, a.St, tid);
     const int b = row / (a.M * a.Hq), mq = (row / a.Hq) % a.M, head = row % a.Hq;
     /* the pieces of this row's stream (sequence b, kv head hk): the wavefronts whose tile ranges
        meet the stream's, in order; their ids are consecutive.  A piece beyond what query token
@@ -1079,7 +1094,19 @@ __global__ __launch_bounds__(512) void pq_attn_combine_kernel(CombineArgs a)
         }
     }
     __syncthreads();
-    float acc = vector_times_slice(so, ms, spart, tid); /* out_j = sum_k o'_k S[j][k] */
+    float acc; /* out_j = sum_k o'_k S[j][k] */
+    if (a.had.on) { /* = D_j / sqrt(128) times the Walsh-Hadamard transform of o' */
+        if (tid < 64) {
+            float lo = so[tid], hi = so[tid + 64];
+            pq_fwht128(lo, hi, tid);
+            spart[0][tid] = lo * PQ_INV_SQRT_D * pq_hadamard_sign(a.had, tid);
+            spart[0][tid + 64] = hi * PQ_INV_SQRT_D * pq_hadamard_sign(a.had, tid + 64);
+        }
+        __syncthreads();
+        acc = spart[0][j];
+    } else {
+        acc = vector_times_slice(so, ms, spart, tid);
+    }
     if (tid < PQ_D) {
         if (HYBRID) acc = lt > 0.f ? (acc + owt) / lt : 0.f;
         if (a.out_f32) {
@@ -1397,10 +1424,10 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
 
     int32_t *plan = reinterpret_cast<int32_t *>(ws + p.off_plan);
     const PlanArgs pa{seq_start, ctx_len, B, Hkv, max_ctx, pool_tokens / 64, p.slots, plan};
-    RotateArgs ra{static_cast<const uint16_t *>(q), qrot, ds->S_f32, softmax_scale * kLog2e, ds->consts};
+    RotateArgs ra{static_cast<const uint16_t *>(q), qrot, ds->S_f32, softmax_scale * kLog2e, ds->consts, ctx->hadamard};
     if (app) {
-        AppendArgs ak{app->xk, k_codes, k_radii, pool_tokens / 64, pool_tokens, app->dst_token, Hkv, ds->S_f32, ds->consts};
-        AppendArgs av{app->xv, v_codes, v_radii, pool_tokens / 64, pool_tokens, app->dst_token, Hkv, ds->S_f32, ds->consts};
+        AppendArgs ak{app->xk, k_codes, k_radii, pool_tokens / 64, pool_tokens, app->dst_token, Hkv, ds->S_f32, ds->consts, ctx->hadamard};
+        AppendArgs av{app->xv, v_codes, v_radii, pool_tokens / 64, pool_tokens, app->dst_token, Hkv, ds->S_f32, ds->consts, ctx->hadamard};
         const int n = B * Hkv;
         const dim3 grid((unsigned)(2 * n + row_blocks + 1)), blk(512);
         if (app->xt == PQ_BF16) hipLaunchKernelGGL((pq_step_prologue_kernel<PQ_BF16>), grid, blk, 0, s, ra, ak, av, n, pa, rows, row_blocks);
@@ -1440,7 +1467,7 @@ pq_status attention_launches(const pq_ctx *ctx, const StepAppend *app, const Ste
     CombineArgs ca{ws_ml, ws_o, B, Hq, Hkv, M, plan,
                    ds->St_f32, out, out_dtype == PQ_F32 ? 1 : 0, ds->consts,
                    reinterpret_cast<const float *>(ws + p.off_wml), reinterpret_cast<const float *>(ws + p.off_wo),
-                   win ? win->win_len : nullptr, p.n_wchunks, win ? (int)win->win_cap : 0};
+                   win ? win->win_len : nullptr, p.n_wchunks, win ? (int)win->win_cap : 0, ctx->hadamard};
     if (win) hipLaunchKernelGGL(pq_attn_combine_kernel<true>, dim3(rows), dim3(512), 0, s, ca);
     else hipLaunchKernelGGL(pq_attn_combine_kernel<false>, dim3(rows), dim3(512), 0, s, ca);
     PQ_HIP_TRY(hipGetLastError());

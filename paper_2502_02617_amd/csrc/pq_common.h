@@ -80,6 +80,16 @@ struct PqDeviceState {
 
 #define PQ_MAX_DEVICES 16
 
+/* S = D H / sqrt(128) with H the Sylvester Hadamard matrix H[i][j] = (-1)^popcount(i & j) and D a diagonal of
+   signs (a randomised Hadamard preconditioner, Section 1): the products of single vectors with S and S^T -- query
+   rotation, the appended key and value, the un-rotation of the output -- then run as a fast Walsh-Hadamard
+   transform inside one wavefront (7 x 64 additions) instead of 128 x 128 products against a matrix read from
+   memory.  Passed to the kernels by value. */
+struct PqHadamard {
+    uint32_t on;     /* 0: S is a general matrix */
+    uint32_t neg[4]; /* bit i set: D_i = -1 */
+};
+
 struct pq_ctx {
     int d;
     uint64_t seed;
@@ -87,6 +97,7 @@ struct pq_ctx {
     /* every entry of S is +-1/sqrt(d) (a sign-flipped Hadamard matrix, say): sqrt(d) * S is then
        exact in bf16 and the encode kernel multiplies by one term instead of three */
     bool unit_entries;
+    PqHadamard hadamard;    /* on: S is D H / sqrt(d) exactly (found by comparing the entries) */
     bool general_codebooks; /* codebooks replaced by pq_set_codebooks */
     double centroids[4][16];
     double boundaries[4][17];
@@ -152,6 +163,29 @@ static __device__ __forceinline__ float vector_times_slice(const float (&sin)[PQ
 }
 
 #if defined(__HIPCC__)
+/* ---- fast Walsh-Hadamard transform of 128 values in one wavefront ----
+ * Lane l holds elements l (lo) and l + 64 (hi); on return it holds elements l and l + 64 of
+ * w_j = sum_i v_i (-1)^popcount(i & j), unscaled: one butterfly stage inside the lane, six across lanes. */
+static __device__ __forceinline__ void pq_fwht128(float &lo, float &hi, int lane)
+{
+    const float a = lo + hi, b = lo - hi;
+    lo = a;
+    hi = b;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const float pl = __shfl_xor(lo, d), ph = __shfl_xor(hi, d);
+        lo = (lane & d) ? pl - lo : lo + pl;
+        hi = (lane & d) ? ph - hi : hi + ph;
+    }
+}
+
+static __device__ __forceinline__ float pq_hadamard_sign(const PqHadamard &h, int i)
+{
+    return ((h.neg[i >> 5] >> (i & 31)) & 1u) ? -1.0f : 1.0f;
+}
+
+#define PQ_INV_SQRT_D 0.08838834764831845f /* 1 / sqrt(128) */
+
 /* ---- depth 7: block radii from a tile's radius-plane word (DeQuant's levels 7, 6, 5) ----
  * cs: the (cos, sin) pairs of the centroids, [3][8] (levels 5, 6, 7), in LDS or global memory.
  * Products in fp32, in the order radius * level 7 * level 6 * level 5. */

@@ -661,7 +661,7 @@ extern "C" pq_status pq_append_kv(const pq_ctx *ctx, const void *x, pq_dtype xt,
     const PqDeviceState *ds = nullptr;
     pq_status st = pq_device_state(ctx, &ds);
     if (st != PQ_OK) return st;
-    AppendArgs a{x, codes, radii, pool_tokens / 64, pool_tokens, dst_token, n_heads, ds->S_f32, ds->consts};
+    AppendArgs a{x, codes, radii, pool_tokens / 64, pool_tokens, dst_token, n_heads, ds->S_f32, ds->consts, ctx->hadamard};
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     dim3 grid((unsigned)(n_seq * n_heads)), block(512);
     if (xt == PQ_BF16) {
@@ -691,8 +691,8 @@ extern "C" pq_status pq_append_kv_pair(const pq_ctx *ctx, const void *xk, const 
     const PqDeviceState *ds = nullptr;
     pq_status st = pq_device_state(ctx, &ds);
     if (st != PQ_OK) return st;
-    AppendArgs ak{xk, k_codes, k_radii, pool_tokens / 64, pool_tokens, dst_token, n_heads, ds->S_f32, ds->consts};
-    AppendArgs av{xv, v_codes, v_radii, pool_tokens / 64, pool_tokens, dst_token, n_heads, ds->S_f32, ds->consts};
+    AppendArgs ak{xk, k_codes, k_radii, pool_tokens / 64, pool_tokens, dst_token, n_heads, ds->S_f32, ds->consts, ctx->hadamard};
+    AppendArgs av{xv, v_codes, v_radii, pool_tokens / 64, pool_tokens, dst_token, n_heads, ds->S_f32, ds->consts, ctx->hadamard};
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const int n = n_seq * n_heads;
     dim3 grid((unsigned)(2 * n)), block(512);

@@ -385,6 +385,21 @@ static pq_status init_context(pq_ctx **out, int d, uint64_t seed, const double *
     ctx->unit_entries = true;
     for (int i = 0; i < d * d; ++i)
         if (fabs(fabs(ctx->S[i]) * sqrt((double)d) - 1.0) > 1e-12) { ctx->unit_entries = false; break; }
+    /* S = D H / sqrt(d) with the Sylvester H: row i is D_i = sign of S[i][0] times (-1)^popcount(i & j) */
+    ctx->hadamard = PqHadamard{};
+    if (ctx->unit_entries) {
+        bool sylvester = true;
+        for (int i = 0; i < d && sylvester; ++i)
+            for (int j = 0; j < d; ++j) {
+                const bool neg = ctx->S[(size_t)i * d + j] < 0.0, neg_row = ctx->S[(size_t)i * d] < 0.0;
+                if (neg != (neg_row != ((__builtin_popcount((unsigned)(i & j)) & 1) != 0))) { sylvester = false; break; }
+            }
+        if (sylvester) {
+            ctx->hadamard.on = 1u;
+            for (int i = 0; i < d; ++i)
+                if (ctx->S[(size_t)i * d] < 0.0) ctx->hadamard.neg[i >> 5] |= 1u << (i & 31);
+        }
+    }
     /* level 1: uniform density on [0, 2 pi): equal cells, centroids at their middles */
     for (int k = 0; k < 16; ++k) ctx->centroids[0][k] = (k + 0.5) * kPi / 8.0;
     for (int k = 0; k <= 16; ++k) ctx->boundaries[0][k] = k * kPi / 8.0;
@@ -392,6 +407,12 @@ static pq_status init_context(pq_ctx **out, int d, uint64_t seed, const double *
     build_tables(ctx);
     *out = ctx;
     return PQ_OK;
+}
+
+extern "C" int pq_preconditioner_structure(const pq_ctx *ctx)
+{
+    if (!ctx) return -1;
+    return ctx->hadamard.on ? 2 : (ctx->unit_entries ? 1 : 0);
 }
 
 extern "C" pq_status pq_set_codebooks(pq_ctx *ctx, const double *cb)

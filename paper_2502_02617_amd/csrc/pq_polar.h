@@ -227,6 +227,7 @@ struct AppendArgs {
     int n_heads;
     const float *S; /* S[i*128 + j] */
     const PqDeviceConsts *consts;
+    PqHadamard had; /* on: y = x S by a fast Walsh-Hadamard transform, S is not read */
 };
 
 /* Sets `width` (<= 32) bits at bit offset `bit` of a layout string inside a tile's code bytes (global memory
@@ -284,7 +285,7 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
     __shared__ float spart[4][PQ_D];
     const int seq = vec / a.n_heads, head = vec % a.n_heads, tid = threadIdx.x, j = tid & 127;
     MatrixSlice ms;
-    matrix_slice_load(ms, a.S, tid);
+    if (!a.had.on) matrix_slice_load(ms, a.S, tid);
     const int64_t dst = a.dst_token[seq];
     if (dst < 0 || dst >= a.pool_tokens) return; /* slot outside the pool: nothing is written */
     const int64_t row = ((int64_t)seq * a.n_heads + head) * PQ_D;
@@ -293,8 +294,21 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
         else sx[j] = static_cast<const float *>(a.x)[row + j];
     }
     __syncthreads();
-    const float acc = vector_times_slice(sx, ms, spart, tid); /* y_j = sum_i x_i S[i][j] */
-    if (tid < PQ_D) sy[j] = acc;
+    /* y_j = sum_i x_i S[i][j].  Hadamard S: the transform of D x, left unscaled -- the angles do not see the
+       common factor 1/sqrt(128), which goes into the radius (as in the encode kernel's one-term product) */
+    float radius_scale = 1.0f;
+    if (a.had.on) {
+        if (tid < 64) {
+            float lo = sx[tid] * pq_hadamard_sign(a.had, tid), hi = sx[tid + 64] * pq_hadamard_sign(a.had, tid + 64);
+            pq_fwht128(lo, hi, tid);
+            sy[tid] = lo;
+            sy[tid + 64] = hi;
+        }
+        radius_scale = PQ_INV_SQRT_D;
+    } else {
+        const float acc = vector_times_slice(sx, ms, spart, tid);
+        if (tid < PQ_D) sy[j] = acc;
+    }
     __syncthreads();
     __shared__ float sq4[8];
     const bool deep = a.consts->depth == 7;
@@ -306,7 +320,7 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
            the sibling's squared radius with a shuffle (the other lanes compute along and are ignored).
            Operations and operand order per node are those of polar_quant_block. */
         const int p = tid, i = p & 7, b = p >> 3;
-        const Thresholds th = load_thresholds(*a.consts);
+        const Thresholds th = load_thresholds(*a.consts, radius_scale);
         const float ya = sy[2 * p], yb = sy[2 * p + 1];
         uint32_t code1;
         if (a.consts->general) { /* the level-1 table is read from the constants in global memory */
@@ -357,7 +371,7 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
             const UpperHalf lo = polar_upper_half(lo4, 0, ut), hi = polar_upper_half(hi4, 1, ut);
             uint32_t *top = reinterpret_cast<uint32_t *>(a.radii) +
                             ((int64_t)head * a.pool_tiles + tile) * (PQ_DEEP_RADII_HALVES / 2);
-            top[tau] = polar_upper_join(lo, hi, 1.0f, ut);
+            top[tau] = polar_upper_join(lo, hi, radius_scale, ut);
         }
     }
 }

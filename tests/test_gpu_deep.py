@@ -243,11 +243,14 @@ def test_deep_online_codebook_fit(bits):
     helpers.check_radii_deep(rg, ro, y.reshape(-1, 128))
 
 
-def test_deep_offsets_and_append():
+@pytest.mark.parametrize("hadamard", [False, True])
+def test_deep_offsets_and_append(hadamard):
+    """hadamard: the appended vector is rotated by a fast Walsh-Hadamard transform, the factor 1/sqrt(128) goes
+    into the vector's one radius."""
     bits = (2, 2, 2)
-    ctx, S, cb, cbt = make(bits)
+    ctx, S, cb, cbt = make(bits, hadamard=True) if hadamard else make(bits)
     H, pool = 2, 256
-    say("deep: encode into the middle of a tile, then append single tokens")
+    say(f"deep: encode into the middle of a tile, then append single tokens (Hadamard S: {hadamard})")
     x = synth.kv_stream(90, H, seed=51).permute(1, 0, 2).contiguous()        # [90, H, 128]
     codes, top = ctx.alloc_cache_for(H, pool, DEV)
     codes.zero_()

@@ -153,7 +153,10 @@ def test_encode_strided_input_and_offsets(env):
 
 
 def test_append_one_token_per_sequence(env):
-    ctx, S, cb = env
+    run_append_case(*env)
+
+
+def run_append_case(ctx, S, cb):
     H, pool = 2, 64 * 6
     lens = [0, 63, 64, 100]           # tokens already cached per sequence
     starts = [0, 64, 128, 256]        # tile-aligned sequence starts
@@ -652,7 +655,10 @@ def test_decode_step_under_graph_replay(env):
 def test_hybrid_attention_prefix_plus_window(env, Hq, Hkv):
     """Quantised prefix + bf16 window against the oracle: every mix of empty / one-tile / ragged prefix and
     empty / partial / several-chunk window."""
-    ctx, S, cb = env
+    run_hybrid_case(*env, Hq, Hkv)
+
+
+def run_hybrid_case(ctx, S, cb, Hq, Hkv):
     lens = [0, 1, 0, 100, 1000, 64, 300, 2000]
     wins = [0, 0, 5, 1, 63, 64, 65, 200]
     cap = 200
@@ -748,6 +754,92 @@ def test_other_preconditioners_encode_and_attend(which):
     err = helpers.rel_l2(got, ref)
     say(f"  {which} S: attention rel L2 {err:.2e}")
     assert err <= 2e-3
+
+
+@pytest.fixture(scope="module", params=["generated", "handed_in"])
+def hadamard_env(request):
+    """A context whose S is a sign diagonal times the Sylvester Hadamard matrix, made by the library or handed in
+    as a plain matrix: either way the single-vector products with S run as fast Walsh-Hadamard transforms.  The
+    oracle gets the library's S as data and multiplies by it as by any other matrix."""
+    ctx = Context(seed=5, hadamard=True)
+    if request.param == "handed_in":
+        ctx = Context(S=ctx.preconditioner())
+    assert ctx.preconditioner_structure() == 2
+    return ctx, ctx.preconditioner(), oracle.default_codebooks()
+
+
+def test_hadamard_append(hadamard_env):
+    """Appended keys and values (transform of D x, the factor 1/sqrt(128) taken into the radius) against the oracle."""
+    run_append_case(*hadamard_env)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (6, 2)])
+def test_hadamard_hybrid_attention(hadamard_env, Hq, Hkv):
+    """Query rotation and un-rotation of the output by the transform, in the launch that also scores the window."""
+    run_hybrid_case(*hadamard_env, Hq, Hkv)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_hadamard_decode_step(hadamard_env, dtype):
+    """One decode step (append + query rotation + attention + un-rotation) against the oracle: the prefix is the
+    oracle's own records, the new token is encoded by both sides (records compared under the tie rule) and the
+    output is compared with the oracle's attention over its records of all tokens."""
+    ctx, S, cb = hadamard_env
+    Hq, Hkv = 8, 2
+    lens = [1, 64, 65, 300, 1000]      # context lengths including the token appended in the step
+    say(f"Hadamard S: decode step, {dtype}, lens={lens}")
+    B = len(lens)
+    starts, pool = [], 0
+    for n in lens:
+        starts.append(pool)
+        pool += ((n + 63) // 64) * 64
+    kc, kr = Context.alloc_cache(Hkv, pool, DEV)
+    vc, vr = Context.alloc_cache(Hkv, pool, DEV)
+    for t in (kc, kr, vc, vr):
+        t.zero_()
+    k_rec = np.zeros((Hkv, pool, 62), dtype=np.uint8)
+    v_rec = np.zeros((Hkv, pool, 62), dtype=np.uint8)
+    nk = synth.kv_stream(B, Hkv, 1830).permute(1, 0, 2).contiguous().to(dtype)     # [B, Hkv, 128]
+    nv = synth.kv_stream(B, Hkv, 1831).permute(1, 0, 2).contiguous().to(dtype)
+    psi_new, y_new = {}, {}
+    for b, n in enumerate(lens):
+        for kind, codes, radii, rec, new, seed in ((PQ_KEY, kc, kr, k_rec, nk, 1810), (PQ_VALUE, vc, vr, v_rec, nv, 1811)):
+            if n > 1:
+                old = synth.kv_stream(n - 1, Hkv, seed + 2 * b).permute(1, 0, 2).contiguous()
+                rec_old = oracle_records(old, S, cb)[0]
+                rec[:, starts[b] : starts[b] + n - 1] = rec_old
+                helpers.upload_records(kind, rec_old, codes, radii, starts[b])
+            rec_new, psi, y = oracle_records(new[b : b + 1], S, cb)
+            rec[:, starts[b] + n - 1] = rec_new[:, 0]
+            psi_new[(kind, b)], y_new[(kind, b)] = psi[:, 0], y[:, 0]
+    q = synth.queries(B, Hq, seed=1832)
+    seq_start = torch.tensor(starts, dtype=torch.int64, device=DEV)
+    ctx_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    dst = seq_start + ctx_len.to(torch.int64) - 1
+    out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(Context.attn_workspace_bytes(B, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
+    ctx.decode_step_polar(nk.to(DEV), nv.to(DEV), dst, q.to(DEV), out, kc, kr, vc, vr, seq_start, ctx_len, max(lens),
+                          helpers.softmax_scale(), ws)
+    torch.cuda.synchronize()
+    # the appended records
+    n_bad = 0
+    for kind, codes, radii, rec in ((PQ_KEY, kc, kr, k_rec), (PQ_VALUE, vc, vr, v_rec)):
+        for b, n in enumerate(lens):
+            slot = starts[b] + n - 1
+            got = canonical_both_ways(ctx, kind, codes, radii, slot - slot % 64, 64)[:, slot % 64]
+            st, rg, ro = helpers.check_codes(got.reshape(-1, 62), rec[:, slot].reshape(-1, 62),
+                                             psi_new[(kind, b)].reshape(-1, 120), enforce_rate=False)
+            helpers.check_radii(rg, ro, y_new[(kind, b)].reshape(-1, 128), enforce_rate=False)
+            n_bad += st["code_mismatches"]
+    assert n_bad <= 1       # 2400 angles: a single proven tie at most
+    got = out.cpu().numpy().astype(np.float64)
+    ref = oracle.attention(q.to(torch.float64).numpy(), k_rec, v_rec, np.array(starts, np.int64), np.array(lens, np.int32),
+                           S, cb, helpers.softmax_scale())
+    err = helpers.rel_l2(got, ref)
+    per_seq = [helpers.rel_l2(got[b], ref[b]) for b in range(B)]
+    say(f"  rel L2 {err:.2e}; per sequence {['%.1e' % e for e in per_seq]}; appended-code ties {n_bad}")
+    assert np.all(np.isfinite(got))
+    assert err <= 2e-3 and max(per_seq) <= 4e-3
 
 
 def lloyd_1d(samples, init, iters=8):
