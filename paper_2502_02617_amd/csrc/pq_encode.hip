@@ -102,10 +102,7 @@ __device__ __forceinline__ void put_pair(uint32_t *img, uint32_t at0, uint32_t a
 template <int KIND, bool CLEAR, bool DEEP>
 __device__ __forceinline__ void emit_block(uint32_t *img, int tau, int b, const BlockCodes &bc)
 {
-    PqBlockFields f;
-    f.l1 = bc.l1; f.g6[0] = bc.g0; f.g6[1] = bc.g1; f.c4 = bc.c4; f.radius = bc.radius;
-    const uint32_t q0 = pql_quarter_index(f, 0), q1 = pql_quarter_index(f, 1), q2 = pql_quarter_index(f, 2),
-                   q3 = pql_quarter_index(f, 3), bi = pql_block_index(f);
+    const uint32_t q0 = bc.q[0], q1 = bc.q[1], q2 = bc.q[2], q3 = bc.q[3], bi = bc.bi;
     uint32_t radius_half;
     if (KIND == PQ_KEY) {
         /* dword d of the token's string: planes of 4, 4, 3 dwords per token, then one half per token */

@@ -74,10 +74,11 @@ __device__ __forceinline__ uint32_t level1_code_general(float ya, float yb, cons
     return c.count + (p > c.thr ? 1u : 0u);
 }
 
+/* What a tile stores of a block (pq_layout.h): the quarter indices Q_j = c1(2j) | c2(j) << 4 | c1(2j+1) << 6 and the
+ * block index B = c4 << 4 | c3(0) << 2 | c3(1), put together as the codes come out of the recursion. */
 struct BlockCodes {
-    uint32_t l1;     /* 8 level-1 codes, pair p at bits [4p, 4p+4) */
-    uint32_t g0, g1; /* [c2(2h) | c3(h) | c2(2h+1)] of half-block 0 / 1 */
-    uint32_t c4;
+    uint32_t q[4];
+    uint32_t bi;
     uint16_t radius; /* binary16 bits */
     float q4;        /* squared radius of the block (before radius_scale): input of the levels above 4 */
 };
@@ -138,7 +139,7 @@ __device__ __forceinline__ uint32_t polar_upper_join(const UpperHalf &lo, const 
  * it between other work. */
 struct PolarState {
     float q1[8], q2[4], q3[2]; /* squared radii */
-    uint32_t mq, l1, c2[4], c3[2];
+    uint32_t mq, c3[2];
     BlockCodes out;
 };
 
@@ -166,7 +167,7 @@ __device__ __forceinline__ void polar_level1_b(PolarState &s, const Y16 &y, int 
         const uint32_t f7 = (uint32_t)((int32_t)(ba ^ bb) >> 31) & 7u;
         code = (s.mq ^ f7) + ((bb >> 28) & 8u);
     }
-    s.l1 = (p == 0) ? code : (s.l1 | (code << (4 * p)));
+    s.out.q[p >> 1] = (p & 1) ? (s.out.q[p >> 1] | (code << 6)) : code;
     s.q1[p] = __builtin_fmaf(ya, ya, yb * yb);
 }
 
@@ -176,8 +177,9 @@ __device__ __forceinline__ void polar_upper(PolarState &s, int p, const Threshol
 {
     if (p & 1) {
         const int n = p >> 1;
-        s.c2[n] = GENERAL ? quant3g(s.q1[2 * n], s.q1[2 * n + 1], th.t2a, th.t2b, th.t2c)
-                          : quant3(s.q1[2 * n], s.q1[2 * n + 1], th.t2a, th.t2c);
+        const uint32_t c2 = GENERAL ? quant3g(s.q1[2 * n], s.q1[2 * n + 1], th.t2a, th.t2b, th.t2c)
+                                    : quant3(s.q1[2 * n], s.q1[2 * n + 1], th.t2a, th.t2c);
+        s.out.q[n] |= c2 << 4;
         s.q2[n] = s.q1[2 * n] + s.q1[2 * n + 1];
     }
     if ((p & 3) == 3) {
@@ -187,15 +189,13 @@ __device__ __forceinline__ void polar_upper(PolarState &s, int p, const Threshol
         s.q3[h] = s.q2[2 * h] + s.q2[2 * h + 1];
     }
     if (p == 7) {
-        s.out.c4 = GENERAL ? quant3g(s.q3[0], s.q3[1], th.t4a, th.t4b, th.t4c)
-                           : quant3(s.q3[0], s.q3[1], th.t4a, th.t4c);
+        const uint32_t c4 = GENERAL ? quant3g(s.q3[0], s.q3[1], th.t4a, th.t4b, th.t4c)
+                                    : quant3(s.q3[0], s.q3[1], th.t4a, th.t4c);
+        s.out.bi = (c4 << 4) | (s.c3[0] << 2) | s.c3[1];
         s.out.q4 = s.q3[0] + s.q3[1];
         const float r4 = pq_saturate_radius(__builtin_amdgcn_sqrtf(s.out.q4) * th.radius_scale);
         const _Float16 rh = (_Float16)r4; /* round to nearest even */
         s.out.radius = __builtin_bit_cast(uint16_t, rh);
-        s.out.l1 = s.l1;
-        s.out.g0 = (s.c2[0] << 4) | (s.c3[0] << 2) | s.c2[1];
-        s.out.g1 = (s.c2[2] << 4) | (s.c3[1] << 2) | s.c2[3];
     }
 }
 
@@ -259,11 +259,9 @@ __device__ __forceinline__ void pql_put_bits(uint32_t *tile_dwords, PqString s, 
 
 /* all code fields of block b of slot tau (not the radius) */
 template <bool CLEAR>
-__device__ __forceinline__ void pql_put_block(uint32_t *tile_dwords, int kind, int tau, int b, const BlockCodes &bc)
+__device__ __forceinline__ void pql_put_block(uint32_t *tile_dwords, int kind, int tau, int b, const PqBlockFields &f)
 {
     const PqBlockPos pos = pql_pos(kind, tau, b);
-    PqBlockFields f;
-    f.l1 = bc.l1; f.g6[0] = bc.g0; f.g6[1] = bc.g1; f.c4 = bc.c4; f.radius = bc.radius;
     const uint32_t q0 = pql_quarter_index(f, 0), q1 = pql_quarter_index(f, 1), q2 = pql_quarter_index(f, 2),
                    q3 = pql_quarter_index(f, 3), bi = pql_block_index(f);
     if (kind == 0) { /* one run of 46 bits: Q_0 | Q_1 << 10 | Q_2 << 20 | Q_3 << 30 | B << 40 */
@@ -339,10 +337,10 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
         const uint32_t c3 = a.consts->general ? quant3g(q2, q2s, th.t3a, th.t3b, th.t3c) : quant3(q2, q2s, th.t3a, th.t3c);
         const float q3 = q2 + q2s;
         const float q3s = __shfl_xor(q3, 4);
-        BlockCodes bc;
+        PqBlockFields bc;
         bc.c4 = a.consts->general ? quant3g(q3, q3s, th.t4a, th.t4b, th.t4c) : quant3(q3, q3s, th.t4a, th.t4c);
-        bc.q4 = q3 + q3s;
-        const _Float16 rh = (_Float16)pq_saturate_radius(__builtin_amdgcn_sqrtf(bc.q4) * th.radius_scale); /* round to nearest even */
+        const float q4 = q3 + q3s;
+        const _Float16 rh = (_Float16)pq_saturate_radius(__builtin_amdgcn_sqrtf(q4) * th.radius_scale); /* round to nearest even */
         bc.radius = __builtin_bit_cast(uint16_t, rh);
         /* the block's fields gathered into its first lane: level-1 codes at their nibbles; the 6-bit
            groups [c2(2h) | c3(h) | c2(2h+1)] of half-block h at bits [8h, 8h+6) of a second word */
@@ -354,12 +352,12 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
             gw |= __shfl_xor(gw, d);
         }
         bc.l1 = l1;
-        bc.g0 = gw & 63u;
-        bc.g1 = (gw >> 8) & 63u;
+        bc.g6[0] = gw & 63u;
+        bc.g6[1] = (gw >> 8) & 63u;
         if (i == 0) {
             uint8_t *gcodes = a.codes + ((int64_t)head * a.pool_tiles + tile) * PQL_CODE_BYTES;
             pql_put_block<true>(reinterpret_cast<uint32_t *>(gcodes), kind, tau, b, bc);
-            if (deep) sq4[b] = bc.q4;
+            if (deep) sq4[b] = q4;
             else a.radii[((int64_t)head * a.pool_tiles + tile) * PQL_RADII + pql_pos(kind, tau, b).radius_half] = bc.radius;
         }
     }
