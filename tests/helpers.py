@@ -25,33 +25,45 @@ RADIUS_MISMATCH_RATE = 2e-3
 _LEVEL_OF = np.concatenate([np.full(64, 1), np.full(32, 2), np.full(16, 3), np.full(8, 4)])
 
 
-def boundary_distance(psi):
-    """psi [n,120] exact oracle angles -> distance to the nearest code boundary."""
+def boundary_distance(psi, cb=None):
+    """psi [n,120] exact oracle angles -> distance to the nearest code boundary.  cb: the 28 centroids in use
+    (16 of level 1, 4 each of levels 2-4) when they are not the analytic ones; a boundary is the middle between two
+    neighbouring centroids (Quant takes the nearest centroid), and at level 1 also the seam 0 = 2 pi of the angle."""
     dist = np.empty_like(psi)
-    step = np.pi / 8
     a = psi[:, :64]
-    dist[:, :64] = np.abs(a - np.round(a / step) * step)
+    if cb is None:
+        step = np.pi / 8
+        dist[:, :64] = np.abs(a - np.round(a / step) * step)
+    else:
+        c1 = np.asarray(cb[:16], dtype=np.float64)
+        marks = np.concatenate([[0.0], 0.5 * (c1[:-1] + c1[1:]), [2.0 * np.pi]])
+        dist[:, :64] = np.min(np.abs(a[..., None] - marks), axis=-1)
     off = 64
     for level, cnt in ((2, 32), (3, 16), (4, 8)):
-        _, bnd = oracle.codebook(level, 4)
-        inner = bnd[1:4]
+        if cb is None:
+            _, bnd = oracle.codebook(level, 4)
+            inner = bnd[1:4]
+        else:
+            c = np.asarray(cb[16 + 4 * (level - 2) : 20 + 4 * (level - 2)], dtype=np.float64)
+            inner = 0.5 * (c[:-1] + c[1:])
         a = psi[:, off : off + cnt]
         dist[:, off : off + cnt] = np.min(np.abs(a[..., None] - inner), axis=-1)
         off += cnt
     return dist
 
 
-def check_codes(rec_gpu, rec_oracle, psi, enforce_rate=True):
+def check_codes(rec_gpu, rec_oracle, psi, enforce_rate=True, cb=None):
     """Returns a dict of statistics; raises AssertionError when the acceptance rule fails.
     enforce_rate=False leaves the rate limit to the caller, who pools the counts of several small calls
-    (on a few hundred angles one legitimate tie already exceeds the rate)."""
+    (on a few hundred angles one legitimate tie already exceeds the rate).  cb: the centroids in use when they are
+    not the analytic ones (the boundaries a mismatch must lie next to are theirs)."""
     Jg, rg = layout_ref.unpack_canonical(rec_gpu)   # the library's records never pass through the oracle package
     Jo, ro = oracle.unpack(rec_oracle)
     bad = Jg != Jo
     n_bad = int(bad.sum())
     stats = {"angles": int(Jo.size), "code_mismatches": n_bad, "code_mismatch_rate": n_bad / Jo.size}
     if n_bad:
-        dist = boundary_distance(psi)
+        dist = boundary_distance(psi, cb)
         worst = float(dist[bad].max())
         stats["worst_mismatch_boundary_distance"] = worst
         assert worst <= ANGLE_TOL, f"code mismatch {worst:.3e} rad away from any boundary"

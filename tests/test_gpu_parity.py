@@ -78,7 +78,7 @@ def check_encode(ctx, S, cb, x_cpu, kind, label):
     codes, radii = gpu_encode(ctx, x_cpu, kind, pool)
     rec_gpu = canonical_both_ways(ctx, kind, codes, radii, 0, T)
     rec_or, psi, y = oracle_records(x_cpu, S, cb)
-    st, rg, ro = helpers.check_codes(rec_gpu.reshape(-1, 62), rec_or.reshape(-1, 62), psi.reshape(-1, 120))
+    st, rg, ro = helpers.check_codes(rec_gpu.reshape(-1, 62), rec_or.reshape(-1, 62), psi.reshape(-1, 120), cb=cb)
     st.update(helpers.check_radii(rg, ro, y.reshape(-1, 128)))
     say(f"  {st}")
     return codes, radii, rec_gpu, rec_or
@@ -902,7 +902,7 @@ def test_general_codebooks_encode_and_attend(which):
         torch.cuda.synchronize()
         rec = canonical_both_ways(ctx, kind, codes, radii, 640, 64)[:, 700 - 640]
         rec_o, psi_o, y_o = oracle_records(new, S, cb)
-        st, rg, ro = helpers.check_codes(rec.reshape(-1, 62), rec_o.reshape(-1, 62), psi_o.reshape(-1, 120))
+        st, rg, ro = helpers.check_codes(rec.reshape(-1, 62), rec_o.reshape(-1, 62), psi_o.reshape(-1, 120), cb=cb)
         helpers.check_radii(rg, ro, y_o.reshape(-1, 128))
     # attention
     lens, Hkv = [70, 900], 2

@@ -782,3 +782,29 @@ def test_stored_radius_saturates_at_the_largest_finite_binary16():
         _, r7 = oracle.unpack_deep(rec7, bits)
         r7 = r7.view(np.float16).astype(np.float64)
         assert r7[2] == 65504.0 and np.isclose(r7[0], np.linalg.norm(g[0]), rtol=2.0 ** -11)
+
+
+def test_tie_rule_boundaries_follow_the_codebooks_in_use():
+    """The GPU tests accept a differing code only next to a cell boundary of Quant (nearest centroid): the helper
+    that measures that distance, given the analytic centroids as data, must place the boundaries where the
+    analytic codebooks' own boundaries are, and with moved centroids at the middles between neighbours."""
+    from tests import helpers
+
+    rng = np.random.default_rng(5)
+    psi = np.concatenate([rng.uniform(0, 2 * np.pi, (50, 64)), rng.uniform(0, np.pi / 2, (50, 56))], axis=1)
+    cb = oracle.default_codebooks()
+    assert np.allclose(helpers.boundary_distance(psi, cb), helpers.boundary_distance(psi), atol=1e-12)
+    moved = cb.copy()
+    moved[3] += 0.05          # level-1 centroid 3: its two boundaries move by 0.025
+    moved[17] -= 0.02         # level-2 centroid 1
+    at = np.zeros((1, 120))
+    at[0, 0] = 0.5 * (moved[3] + moved[4])
+    at[0, 64] = 0.5 * (moved[16] + moved[17])
+    d = helpers.boundary_distance(at, moved)
+    assert d[0, 0] <= 1e-15 and d[0, 64] <= 1e-15
+    assert helpers.boundary_distance(at, cb)[0, 0] > 0.02 and helpers.boundary_distance(at, cb)[0, 64] > 0.005
+    # and the oracle's Quant does switch cells exactly there
+    for col, lvl_slice, mid in ((0, slice(0, 16), at[0, 0]), (64, slice(16, 20), at[0, 64])):
+        c = moved[lvl_slice]
+        lo = int(np.argmin(np.abs(mid - 1e-9 - c))), int(np.argmin(np.abs(mid + 1e-9 - c)))
+        assert lo[1] == lo[0] + 1
