@@ -201,10 +201,29 @@ __device__ __forceinline__ void encode_tiles(const EncodeArgs &a, int block, int
         int tau_lo, tau_hi; /* slots [tau_lo, tau_hi) of the tile are written */
         int64_t src_t0;     /* source token index of slot tau_lo */
     };
-    auto geometry = [&](int64_t item) {
+    /* Item = head * n_tiles + tile.  The 64-bit division happens once per wavefront; from then on the position
+       advances by the (head, tile) parts of the stride between a wavefront's items. */
+    struct Position {
+        int head;
+        int64_t tile_in; /* tile within the range, below n_tiles */
+    };
+    const int64_t item_stride = (int64_t)n_blocks * (EncodeShape<XT>::waves);
+    const int64_t item0 = (int64_t)block * (EncodeShape<XT>::waves) + wave;
+    const int stride_heads = (int)(item_stride / a.n_tiles);
+    const int64_t stride_tiles = item_stride % a.n_tiles;
+    auto advance = [&](Position p) {
+        p.head += stride_heads;
+        p.tile_in += stride_tiles;
+        if (p.tile_in >= a.n_tiles) {
+            p.tile_in -= a.n_tiles;
+            ++p.head;
+        }
+        return p;
+    };
+    auto geometry = [&](const Position &p) {
         Geometry g;
-        g.head = (int)(item / a.n_tiles);
-        g.tile = a.first_tile + item % a.n_tiles;
+        g.head = p.head;
+        g.tile = a.first_tile + p.tile_in;
         const int64_t lo = g.tile * 64 > a.dst0 ? g.tile * 64 : a.dst0;
         const int64_t hi = (g.tile + 1) * 64 < a.dst0 + a.n_tokens ? (g.tile + 1) * 64 : a.dst0 + a.n_tokens;
         g.tau_lo = (int)(lo - g.tile * 64);
@@ -233,9 +252,8 @@ __device__ __forceinline__ void encode_tiles(const EncodeArgs &a, int block, int
             }
         }
     };
-    const int64_t item_stride = (int64_t)n_blocks * (EncodeShape<XT>::waves);
-    const int64_t item0 = (int64_t)block * (EncodeShape<XT>::waves) + wave;
-    if (kPipelined && item0 < a.n_items) load_bf16_rows(geometry(item0));
+    Position pos{(int)(item0 / a.n_tiles), item0 % a.n_tiles};
+    if (kPipelined && item0 < a.n_items) load_bf16_rows(geometry(pos));
 
     {   /* all of a thread's chunks are requested before the first one is stored: one round trip to L2
            instead of one per chunk */
@@ -266,16 +284,17 @@ __device__ __forceinline__ void encode_tiles(const EncodeArgs &a, int block, int
        that the one behind catches up. */
     const int my_items = item0 < a.n_items ? (int)((a.n_items - item0 + item_stride - 1) / item_stride) : 0;
     int items_done = 0;
-    for (int64_t item = item0; item < a.n_items; item += item_stride) {
+    for (int64_t item = item0; item < a.n_items; item += item_stride, pos = advance(pos)) {
         {
-            const int prio = 3 - (4 * items_done) / my_items;
+            const int q4 = 4 * items_done; /* prio = 3 - floor(4 items_done / my_items) */
+            const int prio = 3 - (q4 >= my_items) - (q4 >= 2 * my_items) - (q4 >= 3 * my_items);
             if (prio >= 3) __builtin_amdgcn_s_setprio(3);
             else if (prio == 2) __builtin_amdgcn_s_setprio(2);
             else if (prio == 1) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
             ++items_done;
         }
-        const Geometry geo = geometry(item);
+        const Geometry geo = geometry(pos);
         const int head = geo.head, tau_lo = geo.tau_lo, tau_hi = geo.tau_hi;
         const int64_t tile = geo.tile;
         const bool full = (tau_lo == 0 && tau_hi == 64);
@@ -348,7 +367,7 @@ __device__ __forceinline__ void encode_tiles(const EncodeArgs &a, int block, int
                 f32x16 (&cur)[NVT] = (st & 1) ? acc_odd : acc_even;   /* row tile st: quantised now */
                 f32x16 (&nxt)[NVT] = (st & 1) ? acc_even : acc_odd;   /* row tile st+1: accumulated now */
                 const bool mul = st < 3, quant = st >= 0;
-                if (kPipelined && st == 3 && item + item_stride < a.n_items) load_bf16_rows(geometry(item + item_stride));
+                if (kPipelined && st == 3 && item + item_stride < a.n_items) load_bf16_rows(geometry(advance(pos)));
                 PolarState ps[NVT];
                 BOperand sa_next;
                 if (mul) sa_next.q = sS[(((NTERMS - 1) * 4 + (st + 1)) * 8 + 0) * 64 + lane];

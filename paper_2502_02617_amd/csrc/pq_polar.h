@@ -162,10 +162,10 @@ __device__ __forceinline__ void polar_level1_b(PolarState &s, const Y16 &y, int 
     } else {
         /* cell of atan2(yb, ya) in [0, 2 pi), cells pi/8 wide: quadrant Q = 0..3 from the signs,
            code = 4Q + mq in quadrants 0 and 2, 4Q + 3 - mq in 1 and 3 (angle measured from the
-           other axis), which is (mq xor 7f) + 8 sb with f = sa xor sb */
+           other axis), which is (mq xor 7f) | 8 sb with f = sa xor sb */
         const uint32_t ba = __float_as_uint(ya), bb = __float_as_uint(yb);
         const uint32_t f7 = (uint32_t)((int32_t)(ba ^ bb) >> 31) & 7u;
-        code = (s.mq ^ f7) + ((bb >> 28) & 8u);
+        code = (s.mq ^ f7) | ((bb >> 28) & 8u); /* the first term is below 8 */
     }
     s.out.q[p >> 1] = (p & 1) ? (s.out.q[p >> 1] | (code << 6)) : code;
     s.q1[p] = __builtin_fmaf(ya, ya, yb * yb);
@@ -327,7 +327,7 @@ __device__ __forceinline__ void append_vector(const AppendArgs &a, int kind, int
             const uint32_t mq = quant3(fabsf(ya), fabsf(yb), th.t1a, th.t1c);
             const uint32_t ba = __float_as_uint(ya), bb = __float_as_uint(yb);
             const uint32_t f7 = (uint32_t)((int32_t)(ba ^ bb) >> 31) & 7u;
-            code1 = (mq ^ f7) + ((bb >> 28) & 8u);
+            code1 = (mq ^ f7) | ((bb >> 28) & 8u);
         }
         const float q1 = __builtin_fmaf(ya, ya, yb * yb);
         const float q1s = __shfl_xor(q1, 1);
