@@ -39,6 +39,21 @@ def build_membench():
     return MEMBENCH_PATH
 
 
+ISSUEBENCH_PATH = os.path.join(LIB_DIR, "pq_issuebench")
+
+
+def build_issuebench():
+    """Stand-alone probe of instruction issue costs and matrix / vector overlap (see csrc/pq_issuebench.hip)."""
+    os.makedirs(LIB_DIR, exist_ok=True)
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(CSRC, "pq_issuebench.hip"), "-o", ISSUEBENCH_PATH]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    return ISSUEBENCH_PATH
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
     print(build_membench())
+    print(build_issuebench())
