@@ -541,7 +541,7 @@ def main():
         "general_format": {
             "workload": "the plain path for other bit widths and recursion depths (pq_general_*), depth 5, bits 4/2/2/2/2 "
                         "(55 bytes per vector): encode of 65536 bf16 vectors; attention of 4 sequences x 2048 tokens, "
-                        "8 q / 2 kv heads; generic bit reader, fp32, one wavefront per vector or (sequence, head): not tuned",
+                        "8 q / 2 kv heads; generic bit reader, fp32, one wavefront per vector, sixteen per (sequence, head): not tuned",
             "encode_ms": round(g_enc_ms, 4),
             "encode_m_vectors_per_s": round(g_n / (g_enc_ms * 1e-3) / 1e6, 1),
             "attention_ms": round(g_attn_ms, 4),

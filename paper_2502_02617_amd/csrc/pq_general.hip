@@ -161,25 +161,34 @@ __global__ __launch_bounds__(64) void pq_general_encode_kernel(GenFormat f, cons
     }
 }
 
-/* DeQuant's loops for one record by one wavefront: r^(0) (rotated domain) into buf[returned index][0..127] */
-__device__ __forceinline__ int gen_dequant_rotated(const GenFormat &f, const uint8_t *rec, float (&buf)[2][PQ_D], int tid)
+/* orders the LDS accesses of the lanes of one wavefront (the buffers below belong to a single wavefront) */
+__device__ __forceinline__ void gen_wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+/* DeQuant's loops for one record by one wavefront (lane = 0..63): r^(0) (rotated domain) into
+   buf[returned index][0..127]; buf is the wavefront's own */
+__device__ __forceinline__ int gen_dequant_rotated(const GenFormat &f, const uint8_t *rec, float (&buf)[2][PQ_D], int lane)
 {
     int cur = 0;
-    if (tid < f.n_radii) {
-        const uint16_t h = (uint16_t)(rec[f.code_bytes + 2 * tid] | (rec[f.code_bytes + 2 * tid + 1] << 8));
-        buf[0][tid] = (float)__builtin_bit_cast(_Float16, h);
+    if (lane < f.n_radii) {
+        const uint16_t h = (uint16_t)(rec[f.code_bytes + 2 * lane] | (rec[f.code_bytes + 2 * lane + 1] << 8));
+        buf[0][lane] = (float)__builtin_bit_cast(_Float16, h);
     }
-    __syncthreads();
+    gen_wave_sync();
     for (int l = f.depth - 1; l >= 0; --l) {
         const int n_ang = PQ_D >> (l + 1);
-        if (tid < n_ang) {
-            const uint32_t code = gen_get_bits(rec, gen_bit_pos(f, l, tid), f.bits[l]);
-            const float r = buf[cur][tid];
-            buf[cur ^ 1][2 * tid] = r * f.cosv[l][code];
-            buf[cur ^ 1][2 * tid + 1] = r * f.sinv[l][code];
+        if (lane < n_ang) {
+            const uint32_t code = gen_get_bits(rec, gen_bit_pos(f, l, lane), f.bits[l]);
+            const float r = buf[cur][lane];
+            buf[cur ^ 1][2 * lane] = r * f.cosv[l][code];
+            buf[cur ^ 1][2 * lane + 1] = r * f.sinv[l][code];
         }
         cur ^= 1;
-        __syncthreads();
+        gen_wave_sync();
     }
     return cur;
 }
@@ -215,52 +224,85 @@ __device__ __forceinline__ float gen_wave_sum(float x)
     return x;
 }
 
-/* ---- attention: one wavefront per (sequence, query head), tokens one after another ---- */
-__global__ __launch_bounds__(64) void pq_general_attn_kernel(GenFormat f, const uint16_t *q, float *out, const uint8_t *k_rec,
-                                                             const uint8_t *v_rec, const int64_t *seq_start,
-                                                             const int32_t *ctx_len, int Hq, int Hkv, int64_t pool_tokens,
-                                                             float scale, const float *S, const float *St)
+/* ---- attention: one workgroup of kGenAttnWaves wavefronts per (sequence, query head).  Wavefront w takes tokens
+   w, w + kGenAttnWaves, ... one after another (DeQuant of the key, score, DeQuant of the value, running softmax);
+   the wavefronts' partial results are then merged in wavefront order, so the result does not depend on timing. ---- */
+constexpr int kGenAttnWaves = 16;
+
+__global__ __launch_bounds__(kGenAttnWaves * 64) void pq_general_attn_kernel(GenFormat f, const uint16_t *q, float *out,
+                                                                             const uint8_t *k_rec, const uint8_t *v_rec,
+                                                                             const int64_t *seq_start, const int32_t *ctx_len,
+                                                                             int Hq, int Hkv, int64_t pool_tokens, float scale,
+                                                                             const float *S, const float *St)
 {
     __shared__ float sq[PQ_D];
-    __shared__ float buf[2][PQ_D];
-    const int row = blockIdx.x, b = row / Hq, head = row % Hq, hk = head / (Hq / Hkv), tid = threadIdx.x;
-    for (int c = tid; c < PQ_D; c += 64) sq[c] = __uint_as_float((uint32_t)q[(int64_t)row * PQ_D + c] << 16);
+    __shared__ float sqr[PQ_D];                         /* q' = q S */
+    __shared__ float buf[kGenAttnWaves][2][PQ_D];       /* a wavefront's DeQuant buffers */
+    __shared__ float part_o[kGenAttnWaves][PQ_D];
+    __shared__ float part_ml[kGenAttnWaves][2];
+    const int row = blockIdx.x, b = row / Hq, head = row % Hq, hk = head / (Hq / Hkv);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < PQ_D) sq[tid] = __uint_as_float((uint32_t)q[(int64_t)row * PQ_D + tid] << 16);
     __syncthreads();
-    float q0 = 0.f, q1 = 0.f; /* q' = q S, this thread's two coordinates */
-    for (int i = 0; i < PQ_D; ++i) {
-        const float2 s2 = *reinterpret_cast<const float2 *>(S + i * PQ_D + 2 * tid);
-        q0 = fmaf(sq[i], s2.x, q0);
-        q1 = fmaf(sq[i], s2.y, q1);
+    if (tid < 64) {
+        float a0 = 0.f, a1 = 0.f; /* this thread's two coordinates of q' */
+        for (int i = 0; i < PQ_D; ++i) {
+            const float2 s2 = *reinterpret_cast<const float2 *>(S + i * PQ_D + 2 * tid);
+            a0 = fmaf(sq[i], s2.x, a0);
+            a1 = fmaf(sq[i], s2.y, a1);
+        }
+        sqr[2 * tid] = a0;
+        sqr[2 * tid + 1] = a1;
     }
+    __syncthreads();
+    const float q0 = sqr[2 * lane], q1 = sqr[2 * lane + 1];
     int64_t n = ctx_len[b];
     const int64_t t0 = seq_start[b];
     if (n < 0 || t0 < 0 || t0 + n > pool_tokens) n = 0; /* a sequence outside the pool is treated as empty */
     float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
-    for (int64_t t = 0; t < n; ++t) {
+    for (int64_t t = wave; t < n; t += kGenAttnWaves) {
         const int64_t slot = (int64_t)hk * pool_tokens + t0 + t;
-        int cur = gen_dequant_rotated(f, k_rec + slot * f.rec_bytes, buf, tid);
-        const float s = gen_wave_sum(q0 * buf[cur][2 * tid] + q1 * buf[cur][2 * tid + 1]) * scale;
-        __syncthreads();
-        cur = gen_dequant_rotated(f, v_rec + slot * f.rec_bytes, buf, tid);
+        int cur = gen_dequant_rotated(f, k_rec + slot * f.rec_bytes, buf[wave], lane);
+        const float s = gen_wave_sum(q0 * buf[wave][cur][2 * lane] + q1 * buf[wave][cur][2 * lane + 1]) * scale;
+        gen_wave_sync();
+        cur = gen_dequant_rotated(f, v_rec + slot * f.rec_bytes, buf[wave], lane);
         const float m_new = fmaxf(m, s);
         const float alpha = expf(m - m_new), p = expf(s - m_new); /* exp(-inf) = 0 at the first token */
         l = l * alpha + p;
-        o0 = o0 * alpha + p * buf[cur][2 * tid];
-        o1 = o1 * alpha + p * buf[cur][2 * tid + 1];
+        o0 = o0 * alpha + p * buf[wave][cur][2 * lane];
+        o1 = o1 * alpha + p * buf[wave][cur][2 * lane + 1];
         m = m_new;
-        __syncthreads();
+        gen_wave_sync();
     }
-    buf[0][2 * tid] = l > 0.f ? o0 / l : 0.f;
-    buf[0][2 * tid + 1] = l > 0.f ? o1 / l : 0.f;
+    part_o[wave][2 * lane] = o0;
+    part_o[wave][2 * lane + 1] = o1;
+    if (lane == 0) { part_ml[wave][0] = m; part_ml[wave][1] = l; }
     __syncthreads();
-    float a0 = 0.f, a1 = 0.f;
-    for (int j = 0; j < PQ_D; ++j) {
-        const float2 s2 = *reinterpret_cast<const float2 *>(St + j * PQ_D + 2 * tid);
-        a0 = fmaf(buf[0][j], s2.x, a0);
-        a1 = fmaf(buf[0][j], s2.y, a1);
+    if (tid < 64) {
+        float mm = -INFINITY;
+        for (int w = 0; w < kGenAttnWaves; ++w) mm = fmaxf(mm, part_ml[w][0]);
+        float lt = 0.f, a0 = 0.f, a1 = 0.f;
+        for (int w = 0; w < kGenAttnWaves; ++w) {
+            const float mw = part_ml[w][0];
+            const float wgt = mw == -INFINITY ? 0.f : expf(mw - mm); /* a wavefront without a token */
+            lt = fmaf(part_ml[w][1], wgt, lt);
+            a0 = fmaf(part_o[w][2 * tid], wgt, a0);
+            a1 = fmaf(part_o[w][2 * tid + 1], wgt, a1);
+        }
+        sq[2 * tid] = lt > 0.f ? a0 / lt : 0.f;   /* o' in the rotated domain (sq is free by now) */
+        sq[2 * tid + 1] = lt > 0.f ? a1 / lt : 0.f;
     }
-    out[(int64_t)row * PQ_D + 2 * tid] = a0;
-    out[(int64_t)row * PQ_D + 2 * tid + 1] = a1;
+    __syncthreads();
+    if (tid < 64) {
+        float a0 = 0.f, a1 = 0.f;
+        for (int j = 0; j < PQ_D; ++j) {
+            const float2 s2 = *reinterpret_cast<const float2 *>(St + j * PQ_D + 2 * tid);
+            a0 = fmaf(sq[j], s2.x, a0);
+            a1 = fmaf(sq[j], s2.y, a1);
+        }
+        out[(int64_t)row * PQ_D + 2 * tid] = a0;
+        out[(int64_t)row * PQ_D + 2 * tid + 1] = a1;
+    }
 }
 
 } // namespace
@@ -352,7 +394,7 @@ extern "C" pq_status pq_general_attn_decode(const pq_ctx *ctx, const pq_general_
     const PqDeviceState *ds = nullptr;
     st = pq_device_state(ctx, &ds);
     if (st != PQ_OK) return st;
-    hipLaunchKernelGGL(pq_general_attn_kernel, dim3((unsigned)(B * Hq)), dim3(64), 0, static_cast<hipStream_t>(hip_stream), g,
+    hipLaunchKernelGGL(pq_general_attn_kernel, dim3((unsigned)(B * Hq)), dim3(kGenAttnWaves * 64), 0, static_cast<hipStream_t>(hip_stream), g,
                        static_cast<const uint16_t *>(q), out, k_records, v_records, seq_start, ctx_len, Hq, Hkv, pool_tokens,
                        softmax_scale, ds->S_f32, ds->St_f32);
     PQ_HIP_TRY(hipGetLastError());
