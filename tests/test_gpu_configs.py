@@ -15,7 +15,7 @@ import torch
 
 import oracle
 from paper_2502_02617_amd import Context, PQ_KEY, PQ_VALUE, synth
-from tests import helpers
+from tests import helpers, layout_ref
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -190,3 +190,80 @@ def test_config4_ragged_serving_step(env):
     say(f"config 4: 64 ragged sequences, lengths {min(lens)}..{max(lens)}, decode step (append, then attend); "
         "every sequence with one kv head, every kv head eight times")
     check_case(run_attention_case(ctx, S, cb, lens, lambda b: [(b + b // HKV) % HKV], seed=4000, step=True))
+
+
+# ---------------------------------------------------------------------------
+# a cache whose code planes are larger than 4 GiB: sequences that live beyond the 2^32-byte mark
+# ---------------------------------------------------------------------------
+def test_cache_planes_beyond_four_gib():
+    """8 kv heads x 190000 tiles: 4.47 GB of key codes (and as many of value codes), so the tiles of the last head
+    near the end of the pool start more than 2^32 bytes into the buffer.  Bulk encode, append, export and attention on
+    two short sequences placed there, against the oracle: every address on the way has to be formed in 64 bits."""
+    ctx = Context(seed=0)
+    S, cb = oracle.preconditioner(0), oracle.default_codebooks()
+    tiles = 190000
+    pool = tiles * 64
+    kc, kr = Context.alloc_cache(HKV, pool, DEV)
+    vc, vr = Context.alloc_cache(HKV, pool, DEV)
+    assert kc.numel() > (1 << 32) and (HKV - 1) * tiles * 2944 + (tiles - 1200) * 2944 > (1 << 32)
+    lens = [100, 300]
+    starts = [(tiles - 1000) * 64, (tiles - 500) * 64]
+    say(f"cache planes of {kc.numel() / 1e9:.2f} GB: sequences of {lens} tokens at tiles {[s0 // 64 for s0 in starts]}")
+    k_rec = {}
+    v_rec = {}
+    n_ties = 0
+    for b, (s0, n) in enumerate(zip(starts, lens)):
+        k = synth.kv_stream(n + 1, HKV, 4200 + 2 * b).permute(1, 0, 2).contiguous()   # [n + 1, HKV, 128]; the last one is appended
+        v = synth.kv_stream(n + 1, HKV, 4201 + 2 * b).permute(1, 0, 2).contiguous()
+        for t in (kc, kr, vc, vr):
+            t[:, s0 // 64 : s0 // 64 + (n + 64) // 64 + 1].zero_()
+        ctx.encode_kv_pair(k[:n].to(DEV), v[:n].to(DEV), kc, kr, vc, vr, dst_token0=s0)
+        dst = torch.tensor([s0 + n], dtype=torch.int64, device=DEV)
+        ctx.append_kv_pair(k[n:].to(DEV), v[n:].to(DEV), kc, kr, vc, vr, dst)
+        torch.cuda.synchronize()
+        for kind, x, codes, radii, store in ((PQ_KEY, k, kc, kr, k_rec), (PQ_VALUE, v, vc, vr, v_rec)):
+            rec = torch.empty((HKV, n + 1, 62), dtype=torch.uint8, device=DEV)
+            ctx.export_canonical(kind, codes, radii, s0, n + 1, rec)
+            torch.cuda.synchronize()
+            rec = rec.cpu().numpy()
+            # the same tiles read by the numpy layout reference (only the slices in question leave the device)
+            T = (n + 1 + 63) // 64
+            for h in (0, HKV - 1):
+                c_h = codes[h, s0 // 64 : s0 // 64 + T].cpu().numpy()
+                r_h = radii[h, s0 // 64 : s0 // 64 + T].cpu().numpy().view(np.uint16)
+                assert np.array_equal(rec[h], layout_ref.tiles_to_canonical(kind, c_h, r_h, n + 1))
+            xs = x.permute(1, 0, 2).contiguous().to(torch.float64).numpy().reshape(HKV * (n + 1), 128)
+            rec_or, psi, y = oracle.encode(xs, S, cb, want_psi=True, want_y=True)
+            st, rg, ro = helpers.check_codes(rec.reshape(-1, 62), rec_or, psi, enforce_rate=False)
+            helpers.check_radii(rg, ro, y, enforce_rate=False)
+            n_ties += st["code_mismatches"]
+            store[b] = rec_or.reshape(HKV, n + 1, 62)
+            # attention below runs on the oracle's own records
+            helpers.upload_records(kind, store[b], codes, radii, s0)
+    assert n_ties <= 2
+    B, Hq = len(lens), 32
+    q = synth.queries(B, Hq, seed=4210)
+    ctx_len = [n + 1 for n in lens]
+    out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(Context.attn_workspace_bytes(B, Hq, HKV, max(ctx_len)), dtype=torch.uint8, device=DEV)
+    ctx.attn_decode_polar(q.to(DEV), out, kc, kr, vc, vr, torch.tensor(starts, dtype=torch.int64, device=DEV),
+                          torch.tensor(ctx_len, dtype=torch.int32, device=DEV), max(ctx_len), helpers.softmax_scale(), ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    # the oracle sees a small pool holding just the two sequences
+    small_starts, at = [], 0
+    for n in ctx_len:
+        small_starts.append(at)
+        at += ((n + 63) // 64) * 64
+    kk = np.zeros((HKV, at, 62), dtype=np.uint8)
+    vv = np.zeros((HKV, at, 62), dtype=np.uint8)
+    for b, n in enumerate(ctx_len):
+        kk[:, small_starts[b] : small_starts[b] + n] = k_rec[b]
+        vv[:, small_starts[b] : small_starts[b] + n] = v_rec[b]
+    ref = oracle.attention(q.to(torch.float64).numpy(), kk, vv, np.array(small_starts, np.int64), np.array(ctx_len, np.int32),
+                           S, cb, helpers.softmax_scale())
+    err = helpers.rel_l2(got, ref)
+    say(f"  appended + encoded records: {n_ties} ties; attention rel L2 {err:.2e}")
+    assert np.all(np.isfinite(got)) and err <= ATTN_TOL
+    del kc, kr, vc, vr
+    torch.cuda.empty_cache()
