@@ -192,6 +192,16 @@ def test_config4_ragged_serving_step(env):
     check_case(run_attention_case(ctx, S, cb, lens, lambda b: [(b + b // HKV) % HKV], seed=4000, step=True))
 
 
+def test_one_sequence_of_a_million_tokens(env):
+    """A single sequence of 1000003 tokens (ragged last tile): all wavefronts of the launch work on the eight streams
+    of one sequence, every stream is cut into about 500 pieces that the combine step merges, and the newest token is
+    appended at the end of the longest cache any test builds.  Two of the kv heads against the oracle."""
+    ctx, S, cb = env
+    n = 1000003
+    say(f"one sequence of {n} tokens, decode step (append, then attend); kv heads 0 and 7 against the oracle")
+    check_case(run_attention_case(ctx, S, cb, [n], lambda b: [0, HKV - 1], seed=5000, step=True))
+
+
 # ---------------------------------------------------------------------------
 # a cache whose code planes are larger than 4 GiB: sequences that live beyond the 2^32-byte mark
 # ---------------------------------------------------------------------------
