@@ -436,11 +436,13 @@ def test_attention_medium_against_oracle(env):
     assert err <= 2e-3
 
 
-@pytest.mark.parametrize("B,Hq,Hkv,lo,hi", [(70, 8, 2, 1, 400), (130, 4, 1, 1, 150), (70, 32, 8, 1500, 2500)])
+@pytest.mark.parametrize("B,Hq,Hkv,lo,hi", [(70, 8, 2, 1, 400), (130, 4, 1, 1, 150), (70, 32, 8, 1500, 2500),
+                                            (600, 2, 1, 1, 70)])
 def test_attention_many_sequences(env, B, Hq, Hkv, lo, hi):
     """More than 64 sequences (the per-sequence table of the work plan is then read from global
     memory instead of LDS), empty sequences in between, and wavefront shares that run across
-    the boundaries of several (sequence, kv head) streams."""
+    the boundaries of several (sequence, kv head) streams.  600 sequences: the running sum of the
+    plan takes more than one round of 512."""
     ctx, S, cb = env
     rng = np.random.default_rng(B * 1000 + hi)
     lens = [int(n) for n in rng.integers(lo, hi + 1, size=B)]
