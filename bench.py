@@ -43,8 +43,11 @@ B, HQ, HKV, CTX, D = 16, 32, 8, 32768, 128
 N_CACHES = 3
 BYTES_PER_TOKEN_HEAD = 124  # 62-byte key record + 62-byte value record
 PROFILE_FILE = os.path.join(ROOT, "profiles", "attn_partial_cfg2_counters.txt")
-# Secondary bound of the dominant kernel: vector-ALU issue.  One SIMD issues at most one 64-lane vector instruction
-# per 4 cycles: 256 CUs x 4 SIMDs x 2.4 GHz / 4 = 614.4 G wavefront instructions/s.
+# Secondary bound of the dominant kernel: vector-ALU issue, as a plain instruction count against one 64-lane vector
+# instruction per SIMD every 4 cycles: 256 CUs x 4 SIMDs x 2.4 GHz / 4 = 614.4 G wavefront instructions/s.  That is
+# the measured rate of three-operand integer, packed binary16 and conversion instructions; plain fp32 instructions and
+# shifts issue every 2 cycles and a matrix instruction (counted as one here) holds the SIMD for 8 or 16, so the
+# fraction is an indication, not a bound met instruction by instruction.
 VALU_PEAK_GINSTR = 256 * 4 * 2.4 / 4.0
 
 
@@ -475,6 +478,8 @@ def main():
             "unit": "G wavefront vector instructions/s",
             "frac": round(ginstr / VALU_PEAK_GINSTR, 4),
             "instructions_per_launch": valu,
+            "note": "count-based: the peak is one wavefront instruction per SIMD every 4 cycles (integer three-operand and "
+                    "packed binary16 instructions; fp32 and shifts take 2, matrix instructions 8 or 16)",
             "source": "SQ_INSTS_VALU of a separate rocprofv3 run (" + os.path.relpath(PROFILE_FILE, ROOT) + ", commit "
                       + figures.get("commit", "?") + ") over the launch duration measured here",
         }
