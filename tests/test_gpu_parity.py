@@ -422,6 +422,50 @@ def test_attention_is_deterministic_and_split_invariant(env):
     assert helpers.rel_l2(c, a) <= 2e-3
 
 
+def test_two_streams_with_one_context_do_not_interfere(env):
+    """One context, two HIP streams (default priority), each with its own workspace, cache and output: decode steps
+    issued alternately on both streams give, bit for bit, what each gives alone -- the library keeps no mutable
+    state between calls besides what the caller passes in."""
+    ctx, S, cb = env
+    say("two streams, one context")
+    Hq, Hkv = 8, 2
+    jobs = []
+    for j, lens in enumerate(([3000, 65, 700], [1200, 2500])):
+        caches, starts, pool, _, _ = build_cache(ctx, S, cb, lens, Hkv, seed=360 + 10 * j, want_oracle=False)
+        B = len(lens)
+        q = synth.queries(B, Hq, seed=361 + j).to(DEV)
+        nk = synth.kv_stream(B, Hkv, 362 + j).permute(1, 0, 2).contiguous().to(DEV)
+        nv = synth.kv_stream(B, Hkv, 364 + j).permute(1, 0, 2).contiguous().to(DEV)
+        seq_start = torch.from_numpy(starts).to(DEV)
+        ctx_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
+        dst = seq_start + ctx_len.to(torch.int64) - 1          # the step overwrites the newest slot
+        ws = torch.empty(Context.attn_workspace_bytes(B, Hq, Hkv, max(lens)), dtype=torch.uint8, device=DEV)
+        out = torch.empty((B, Hq, 128), dtype=torch.float32, device=DEV)
+        jobs.append(dict(caches=caches, q=q, nk=nk, nv=nv, seq_start=seq_start, ctx_len=ctx_len, dst=dst, ws=ws, out=out,
+                         max_ctx=max(lens)))
+
+    def step(job):
+        kc, kr, vc, vr = job["caches"]
+        ctx.decode_step_polar(job["nk"], job["nv"], job["dst"], job["q"], job["out"], kc, kr, vc, vr, job["seq_start"],
+                              job["ctx_len"], job["max_ctx"], helpers.softmax_scale(), job["ws"])
+
+    alone = []
+    for job in jobs:
+        step(job)
+        torch.cuda.synchronize()
+        alone.append(job["out"].clone())
+        job["out"].fill_(float("nan"))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for _ in range(20):
+        for job, st in zip(jobs, streams):
+            with torch.cuda.stream(st):
+                step(job)
+    torch.cuda.synchronize()
+    for job, ref in zip(jobs, alone):
+        assert torch.equal(job["out"], ref)
+
+
 def test_attention_medium_against_oracle(env):
     ctx, S, cb = env
     lens = [4096 + 13, 2500]
