@@ -979,7 +979,7 @@ def test_general_codebooks_encode_and_attend(which):
     assert err <= 2e-3
 
 
-@pytest.mark.parametrize("which", ["rotated", "no_rotation"])
+@pytest.mark.parametrize("which", ["rotated", "no_rotation", "hadamard"])
 def test_online_codebook_fit(which):
     """pq_fit_codebooks against the oracle's k-means on the exact angles: the GPU counts the angles into
     fine histograms and clusters the bins, so the centroids agree to a fraction of a bin width; the fitted
@@ -989,6 +989,10 @@ def test_online_codebook_fit(which):
         ctx = Context(seed=2)
         x = synth.kv_stream(5000, 2, seed=60).permute(1, 0, 2).contiguous()          # bf16, outlier channels
         x[4990:] *= 0.0                                                               # some all-zero vectors
+    elif which == "hadamard":
+        # the kernel multiplies by sqrt(128) S (entries +-1, one exact bf16 term): the angles do not see the factor
+        ctx = Context(seed=2, hadamard=True)
+        x = synth.kv_stream(4000, 2, seed=62).permute(1, 0, 2).contiguous()
     else:
         ctx = Context(S=np.eye(128))
         x = synth.gaussian_vectors(2 * 3001, seed=61).reshape(3001, 2, 128).clone()   # fp32, ragged tile tail
