@@ -901,15 +901,16 @@ def lloyd_1d(samples, init, iters=8):
     return c
 
 
-@pytest.mark.parametrize("which", ["jittered", "fitted_no_rotation"])
+@pytest.mark.parametrize("which", ["jittered", "fitted_no_rotation", "jittered_hadamard"])
 def test_general_codebooks_encode_and_attend(which):
     """Codebooks set by the caller (pq_set_codebooks): the analytic ones moved at random, and codebooks fitted
     by Lloyd iterations to the angles of un-rotated data with outlier channels (S = I, the paper's variant
     without preconditioning).  Encode (bulk and append), DeQuant and attention against the oracle, which
     takes the same centroids as data."""
     cb = oracle.default_codebooks().copy()
-    if which == "jittered":
-        ctx = Context(seed=3)
+    if which in ("jittered", "jittered_hadamard"):
+        # with a Hadamard S the encode kernel's one-term product and the transform paths meet the level-1 cell table
+        ctx = Context(seed=3, hadamard=(which == "jittered_hadamard"))
         rng = np.random.default_rng(11)
         cb[:16] += rng.uniform(-0.08, 0.08, 16)
         cb[16:] += rng.uniform(-0.04, 0.04, 12)
