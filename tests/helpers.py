@@ -162,10 +162,9 @@ def upload_records(kind, rec, codes, radii, start, fill=0xFF):
     H, n, _ = rec.shape
     assert start % 64 == 0
     T, t0 = (n + 63) // 64, start // 64
-    for h in range(H):
-        c, r = layout_ref.canonical_to_tiles(kind, rec[h], T, fill)
-        codes[h, t0:t0 + T] = torch.from_numpy(c).to(codes.device)
-        radii[h, t0:t0 + T] = torch.from_numpy(r.view(np.int16)).to(radii.device)
+    c, r = layout_ref.canonical_to_tiles_planes(kind, rec, T, fill)      # all head planes in one pass
+    codes[:, t0:t0 + T] = torch.from_numpy(c).to(codes.device)
+    radii[:, t0:t0 + T] = torch.from_numpy(r.view(np.int16)).to(radii.device)
 
 
 def upload_records_deep(kind, rec, codes, top, start, fill=0xFF):

@@ -112,11 +112,20 @@ def _record_codes(rec):
 def canonical_to_tiles(kind, rec, n_tiles=None, fill=0):
     """rec uint8 [n, 62] (slots 0..n-1 of one head plane) -> (codes uint8 [T, 2944], radii uint16 [T, 512]).
     Slots beyond n keep `fill` in every code byte and radius."""
-    n = rec.shape[0]
-    T = (n + 63) // 64 if n_tiles is None else n_tiles
-    assert T * 64 >= n
-    full = np.zeros((T * 64, 62), dtype=np.uint8)
-    full[:n] = rec
+    codes, radii = canonical_to_tiles_planes(kind, rec[None], n_tiles, fill)
+    return codes[0], radii[0]
+
+
+def canonical_to_tiles_planes(kind, rec, n_tiles=None, fill=0):
+    """The same for several head planes at once: rec uint8 [G, n, 62] -> (codes uint8 [G, T, 2944], radii uint16
+    [G, T, 512]); one pass over the 64 slots of a tile serves the tiles of all planes."""
+    G, n = rec.shape[0], rec.shape[1]
+    Tp = (n + 63) // 64 if n_tiles is None else n_tiles      # tiles per plane
+    assert Tp * 64 >= n
+    T = G * Tp
+    full = np.zeros((G, Tp * 64, 62), dtype=np.uint8)
+    full[:, :n] = rec
+    full = full.reshape(T * 64, 62)
     c1, c2, c3, c4 = _record_codes(full)
     rad = full[:, 46:62].astype(np.uint16)
     rad = (rad[:, 0::2] | (rad[:, 1::2] << 8)).reshape(T, 64, 8)
@@ -125,7 +134,7 @@ def canonical_to_tiles(kind, rec, n_tiles=None, fill=0):
     radii = np.full((T, RADII), (fill & 0xFF) * 0x0101, dtype=np.uint16)
     for tau in range(64):
         # which tiles actually hold slot tau
-        live = (np.arange(T) * 64 + tau) < n
+        live = ((np.arange(T) % Tp) * 64 + tau) < n
         if not live.any():
             continue
         sub = codes[live]
@@ -138,7 +147,7 @@ def canonical_to_tiles(kind, rec, n_tiles=None, fill=0):
             put_bits(sub, *bp, 6, B)
             radii[live, rh] = rad[live, tau, b]
         codes[live] = sub
-    return codes, radii
+    return codes.reshape(G, Tp, CODE_BYTES), radii.reshape(G, Tp, RADII)
 
 
 def tiles_to_canonical_deep(kind, codes, top, n_tokens):

@@ -56,6 +56,19 @@ def test_fields_land_where_the_specification_puts_them():
 
 
 @pytest.mark.parametrize("kind", [0, 1])
+def test_several_planes_in_one_pass_equal_one_plane_at_a_time(kind):
+    n = 64 * 2 + 9
+    planes = np.stack([records_with(n, None, seed=20 + 3 * kind + g) for g in range(3)])
+    codes, radii = layout_ref.canonical_to_tiles_planes(kind, planes, 4, fill=0xC3)
+    assert codes.shape == (3, 4, layout_ref.CODE_BYTES) and radii.shape == (3, 4, layout_ref.RADII)
+    for g in range(3):
+        c1, r1 = layout_ref.canonical_to_tiles(kind, planes[g], 4, fill=0xC3)
+        assert np.array_equal(codes[g], c1) and np.array_equal(radii[g], r1)
+        assert np.array_equal(layout_ref.tiles_to_canonical(kind, codes[g], radii[g], n), planes[g])
+    assert np.all(codes[:, 3] == 0xC3) and np.all(radii[:, 3] == 0xC3C3)   # a tile without records keeps the fill
+
+
+@pytest.mark.parametrize("kind", [0, 1])
 def test_round_trip_and_full_coverage(kind):
     n = 64 * 3 + 17
     rec = records_with(n, None, seed=10 + kind)
