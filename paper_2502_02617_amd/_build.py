@@ -53,7 +53,22 @@ def build_issuebench():
     return ISSUEBENCH_PATH
 
 
+LDSBENCH_PATH = os.path.join(LIB_DIR, "pq_ldsbench")
+
+
+def build_ldsbench():
+    """Stand-alone probe of LDS table-gather costs (see csrc/pq_ldsbench.hip)."""
+    os.makedirs(LIB_DIR, exist_ok=True)
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(CSRC, "pq_ldsbench.hip"), "-o", LDSBENCH_PATH]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    return LDSBENCH_PATH
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
     print(build_membench())
     print(build_issuebench())
+    print(build_ldsbench())
